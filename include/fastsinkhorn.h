@@ -1,0 +1,168 @@
+/*
+ * fastsinkhorn.h -- C ABI of the MI355X (gfx950) log-domain Sinkhorn library.
+ *
+ * The library solves the entropic optimal-transport problem of the paper's
+ * Eq. 3 by the log-domain Sinkhorn iteration (Eqs. 9-10, Alg. 1):
+ *
+ *     f_i <- -eps * LSE_j( (g_j - C_ij)/eps + log b_j )          (Eq. 9)
+ *     g_j <- -eps * LSE_i( (f_i - C_ij)/eps + log a_i )          (Eq. 10, uses the new f)
+ *
+ * starting from f = g = 0 (Eqs. 6-7), with the row-marginal error
+ * err = sum_i |r_i - a_i| (Alg. 1, Sec. 4.5) as the stopping test.
+ * Notation: the paper's alpha, beta, mu, nu, pi are f, g, a, b, P here.
+ *
+ * Conventions shared by every entry point
+ *   - Every array pointer is a DEVICE pointer (HBM of the current HIP device),
+ *     owned by the caller.  The library neither frees nor keeps them after the
+ *     work it enqueued on `stream` has run.  Outputs must not alias inputs.
+ *   - C is row-major n x m, C[i*m + j], fp32 (Sec. 4.4).  X is n x d and Y is
+ *     m x d, row-major fp32; the cost is then the squared Euclidean distance
+ *     ||x_i - y_j||^2 and is recomputed on the fly, never stored.
+ *   - a[n], b[m] are fp32 weights (non-negative; a zero weight carries no mass).
+ *     f[n], g[m] are fp32 potentials.  eps is the regularisation (> 0).
+ *   - tol <= 0 means: run exactly max_iter iterations.  tol > 0 means: stop at
+ *     the first iteration k with k mod check_every == 0 and err_k < tol, or at
+ *     max_iter (Alg. 1).  The returned potentials are those after exactly
+ *     `iters` iterations.
+ *   - Scalars are validated on the host before anything is enqueued
+ *     (n, m >= 1; eps > 0 and finite; max_iter >= 0; 1 <= d <= FS_MAX_DIM;
+ *     non-null pointers); a violation returns FS_ERR_INVALID_ARG.  Array
+ *     contents are the caller's responsibility; non-finite potentials are
+ *     reported through fs_result.nonfinite, never by aborting.
+ *   - No exception crosses this boundary.  fs_last_error() returns a
+ *     thread-local description of the last failure.
+ *   - Internally the potentials are carried in fp64 (scaled by log2(e)/eps) and
+ *     the exponent arguments are formed in fp64; exp2/log2 and the sums are fp32.
+ */
+#ifndef FASTSINKHORN_H
+#define FASTSINKHORN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Opaque stream handle: a hipStream_t passed as void* (NULL = the default stream). */
+typedef void *fs_stream;
+
+#define FS_MAX_DIM 64
+
+typedef enum {
+    FS_OK = 0,
+    FS_ERR_INVALID_ARG = -1,
+    FS_ERR_WORKSPACE = -2,     /* caller workspace missing, misaligned or too small */
+    FS_ERR_HIP = -3,           /* a HIP runtime call failed; see fs_last_error()     */
+    FS_ERR_UNSUPPORTED = -4
+} fs_status;
+
+/* Written by the device at the end of a solve (also mirrored to the host by the
+ * blocking entry points). */
+typedef struct {
+    int32_t iters;         /* iterations performed (f- and g-update pairs)               */
+    int32_t converged;     /* 1 iff the tolerance test of Alg. 1 fired                   */
+    int32_t nonfinite;     /* 1 iff some returned potential is NaN or +-inf              */
+    float   marginal_err;  /* err after `iters` iterations; NaN if it was not evaluated  */
+} fs_result;
+
+/* Options of the _ex entry points.  Zero-initialise for the defaults. */
+typedef struct {
+    int32_t check_every;     /* c of Alg. 1; 0 -> 10 (Sec. 4.5)                                     */
+    int32_t warm_start;      /* 0: start from f = g = 0 (Eqs. 6-7); 1: start from the f, g passed in */
+    int32_t kernel_mode;     /* 0: automatic; 1: streaming row / column kernels; 2: fused row-panel
+                                kernel (dense only; FS_ERR_UNSUPPORTED if the shape does not fit)    */
+    int32_t use_graph;       /* 0: automatic; 1: plain stream launches; 2: hipGraph iteration blocks  */
+    int32_t skip_final_err;  /* 1: do not spend the one trailing pass that evaluates err after the
+                                last iteration when no stop fired (marginal_err is then NaN)          */
+    int32_t fused_variant;  /* tuning knob of the fused kernel: 0 default register tiling, 1 alternative */
+    double *f64_out;         /* optional device [n]: f in double precision (NULL: not wanted)         */
+    double *g64_out;         /* optional device [m]: g in double precision                            */
+    const double *f64_in;    /* optional device [n], [m]: warm start in double precision; when both  */
+    const double *g64_in;    /*   are given (and warm_start = 1) they take the place of f, g          */
+    float  *err_history;     /* optional device [err_history_len]: err_k stored at index k-1          */
+    int32_t err_history_len;
+    int32_t reserved1;
+} fs_options;
+
+/* ---- Blocking solves (Alg. 1).  Return the number of iterations performed (>= 0) or a
+ * negative fs_status.  They use a library-owned, per-device cached workspace, enqueue the
+ * iterations on `stream` in blocks without waiting for them, watch a host-visible stop flag,
+ * and synchronise with the stream once, at the end.  check_every = 10. ---- */
+
+/* Dense cost (Alg. 1 REQUIRE: C, mu, nu, eps, tau, K).  Writes f[n], g[m]. */
+int fs_sinkhorn_dense(const float *C, const float *a, const float *b, int n, int m,
+                      float eps, int max_iter, float tol, float *f, float *g, fs_stream stream);
+
+/* Point clouds, squared-Euclidean cost recomputed on the fly (Sec. 1.1: "Euclidean point
+ * cloud inputs").  Writes f[n], g[m]. */
+int fs_sinkhorn_points(const float *X, const float *Y, int d, const float *a, const float *b,
+                       int n, int m, float eps, int max_iter, float tol, float *f, float *g,
+                       fs_stream stream);
+
+/* ---- Asynchronous solves: caller workspace, device-side result, no host synchronisation.
+ * All max_iter iterations (plus one trailing error pass) are enqueued; after the device-side
+ * stop flag is set the remaining kernels return immediately.  `workspace` is device memory of at
+ * least fs_workspace_bytes(n, m, d) bytes, 256-byte aligned, exclusively this call's until its
+ * stream work has finished.  `opts` may be NULL.  `result_dev` (device, may be NULL) receives
+ * the fs_result.  `result_host` (pinned host memory, may be NULL) receives a copy written by
+ * the device.  The blocking-with-options variants below take the same arguments. ---- */
+size_t fs_workspace_bytes(int n, int m, int d /* 0 = dense */);
+
+fs_status fs_sinkhorn_dense_ex(const float *C, const float *a, const float *b, int n, int m,
+                               float eps, int max_iter, float tol, float *f, float *g,
+                               fs_stream stream, const fs_options *opts,
+                               void *workspace, size_t workspace_bytes, fs_result *result_dev);
+
+fs_status fs_sinkhorn_points_ex(const float *X, const float *Y, int d, const float *a, const float *b,
+                                int n, int m, float eps, int max_iter, float tol, float *f, float *g,
+                                fs_stream stream, const fs_options *opts,
+                                void *workspace, size_t workspace_bytes, fs_result *result_dev);
+
+/* Blocking solve with options and a host-side result: like fs_sinkhorn_dense / _points
+ * (library workspace, early stop watched from the host, one synchronisation at the end) but
+ * honouring `opts` and filling *result_host (ordinary host memory, may be NULL).  Exactly one of
+ * C or (X, Y, d > 0) is non-NULL.  Returns iterations performed or a negative fs_status. */
+int fs_sinkhorn_solve(const float *C, const float *X, const float *Y, int d,
+                      const float *a, const float *b, int n, int m,
+                      float eps, int max_iter, float tol, float *f, float *g,
+                      fs_stream stream, const fs_options *opts, fs_result *result_host);
+
+/* ---- Plan and cost from potentials (Eq. 5 and the last step of Alg. 1).
+ * Exactly one of C or (X, Y, d > 0) is non-NULL.  f64 / g64 (device, optional) give the
+ * potentials in double precision and then take the place of f / g.  Asynchronous on `stream`. ---- */
+
+/* P[i*m + j] = a_i b_j exp((f_i + g_j - C_ij)/eps), fp32, n x m row-major. */
+fs_status fs_plan(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                  int n, int m, float eps, const float *f, const float *g, float *P, fs_stream stream);
+
+/* cost_dev[0] = sum_ij C_ij P_ij (double, device). */
+fs_status fs_cost(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                  int n, int m, float eps, const float *f, const float *g, double *cost_dev,
+                  fs_stream stream);
+
+/* Same as fs_plan / fs_cost with the potentials given in double precision. */
+fs_status fs_plan_f64(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                      int n, int m, float eps, const double *f64, const double *g64, float *P,
+                      fs_stream stream);
+fs_status fs_cost_f64(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                      int n, int m, float eps, const double *f64, const double *g64, double *cost_dev,
+                      fs_stream stream);
+
+/* ---- One half-step on its own (Eq. 9 / Eq. 10), for kernel-level checks and for callers
+ * that drive the loop themselves.  Potentials in double precision, device pointers;
+ * asynchronous on `stream`; uses the library-owned workspace. ---- */
+fs_status fs_update_f(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                      int n, int m, float eps, const double *g64, double *f64_out, fs_stream stream);
+fs_status fs_update_g(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                      int n, int m, float eps, const double *f64, double *g64_out, fs_stream stream);
+
+/* ---- Housekeeping ---- */
+const char *fs_last_error(void);     /* thread-local, static storage, never NULL        */
+void        fs_clear_cache(void);    /* frees cached workspaces and hipGraph executables */
+const char *fs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTSINKHORN_H */

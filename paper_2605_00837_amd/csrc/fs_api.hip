@@ -1,0 +1,571 @@
+// C ABI of the library (declared in include/fastsinkhorn.h) and the host-side
+// driver of Alg. 1: validation, workspace layout, the iteration loop enqueued
+// either as plain stream launches or as replayed hipGraph blocks, and the
+// host-visible stop flag that lets the blocking entry points stop enqueuing
+// without ever waiting on the device inside the loop.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <tuple>
+#include <vector>
+
+#include "../../include/fastsinkhorn.h"
+#include "fs_kernels.h"
+
+namespace {
+
+using namespace fs;
+
+thread_local char g_err[512] = "";
+
+void set_err(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+#define FS_HIP(call)                                                                     \
+    do {                                                                                 \
+        hipError_t e__ = (call);                                                         \
+        if (e__ != hipSuccess) {                                                         \
+            set_err("%s failed: %s (%s:%d)", #call, hipGetErrorString(e__), __FILE__, __LINE__); \
+            return FS_ERR_HIP;                                                           \
+        }                                                                                \
+    } while (0)
+
+constexpr double kLog2e = 1.4426950408889634074;
+
+inline size_t up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---------------------------------------------------------------- workspace layout
+struct Layout {
+    int n, m, d, n_ld, m_ld;
+    // dense
+    int P_stream, rpp_stream, P_fused;
+    // points
+    int JSf, cpsf, JSg, cpsg;
+    size_t o_state, o_F, o_U, o_G, o_V, o_la2, o_lb2, o_part, o_part2, o_err;
+    size_t o_Xp, o_Xs, o_cx, o_Yp, o_Ys, o_cy;
+    size_t total;
+};
+
+Layout make_layout(int n, int m, int d) {
+    Layout L{};
+    L.n = n; L.m = m; L.d = d;
+    L.n_ld = (int)up((size_t)n, 32);
+    L.m_ld = (int)up((size_t)m, 32);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += up(bytes, 256); return o; };
+    L.o_state = take(sizeof(State));
+    L.o_F = take(sizeof(double) * 2 * L.n_ld);
+    L.o_U = take(sizeof(double) * 2 * L.n_ld);
+    L.o_G = take(sizeof(double) * 2 * L.m_ld);
+    L.o_V = take(sizeof(double) * 2 * L.m_ld);
+    L.o_la2 = take(sizeof(double) * L.n_ld);
+    L.o_lb2 = take(sizeof(double) * L.m_ld);
+    if (d == 0) {
+        dense_stream_plan(n, m, &L.P_stream, &L.rpp_stream);
+        dense_fused_plan(n, m, &L.P_fused);
+        const int Pmax = L.P_stream > L.P_fused ? L.P_stream : L.P_fused;
+        L.o_part = take(sizeof(double) * (size_t)Pmax * L.m_ld);
+        L.o_part2 = L.o_part;
+    } else {
+        points_plan(n, m, d, &L.JSf, &L.cpsf);
+        points_plan(m, n, d, &L.JSg, &L.cpsg);
+        L.o_part = take(sizeof(double) * (size_t)L.JSf * L.n_ld);
+        L.o_part2 = take(sizeof(double) * (size_t)L.JSg * L.m_ld);
+        L.o_Xp = take(sizeof(double) * (size_t)n * d);
+        L.o_Xs = take(sizeof(double) * (size_t)n * d);
+        L.o_cx = take(sizeof(double) * L.n_ld);
+        L.o_Yp = take(sizeof(double) * (size_t)m * d);
+        L.o_Ys = take(sizeof(double) * (size_t)m * d);
+        L.o_cy = take(sizeof(double) * L.m_ld);
+    }
+    L.o_err = take(sizeof(double) * (size_t)((m + 255) / 256));      // one per workgroup of the g-combine
+    L.total = off;
+    return L;
+}
+
+// ---------------------------------------------------------------- per-device cache
+struct HostBlock {            // pinned, device-visible
+    volatile int32_t flag;
+    int32_t pad[3];
+    fs_result res;
+};
+
+struct DeviceCache {
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    HostBlock *host = nullptr;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+};
+
+std::mutex g_mu;
+std::map<int, DeviceCache> g_cache;
+
+fs_status get_cache(size_t need_bytes, DeviceCache **out) {
+    int dev = 0;
+    FS_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(g_mu);
+    DeviceCache &c = g_cache[dev];
+    if (!c.host) {
+        FS_HIP(hipHostMalloc((void **)&c.host, sizeof(HostBlock), hipHostMallocDefault));
+        memset((void *)c.host, 0, sizeof(HostBlock));
+        for (auto &e : c.ev) FS_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    }
+    if (c.ws_bytes < need_bytes) {
+        if (c.ws) {
+            FS_HIP(hipDeviceSynchronize());
+            FS_HIP(hipFree(c.ws));
+            c.ws = nullptr;
+            c.ws_bytes = 0;
+        }
+        const size_t want = up(need_bytes, (size_t)1 << 20);
+        FS_HIP(hipMalloc(&c.ws, want));
+        c.ws_bytes = want;
+    }
+    *out = &c;
+    return FS_OK;
+}
+
+// ---------------------------------------------------------------- one solve, described
+struct Problem {
+    const float *C, *X, *Y, *a, *b;
+    int d, n, m;
+    float eps;
+    int max_iter;
+    float tol;
+};
+
+struct Solve {
+    Problem pr;
+    fs_options opt;
+    Layout L;
+    char *ws;
+    hipStream_t st;
+    Pots pots;
+    State *state;
+    int mode;              // 1 streaming, 2 fused (dense); 3 points
+    double *errpart;
+    volatile int32_t *host_flag;   // device-visible address of the pinned flag, or null
+
+    Ctl ctl(int phase) const {
+        Ctl c;
+        c.st = state;
+        c.max_iter = pr.max_iter;
+        c.check_every = opt.check_every;
+        c.tol = pr.tol > 0.0f ? (double)pr.tol : 0.0;
+        c.err_history = opt.err_history;
+        c.err_history_len = opt.err_history ? opt.err_history_len : 0;
+        c.phase = phase;
+        c.host_flag = host_flag;
+        return c;
+    }
+    DenseArgs dense() const {
+        DenseArgs a;
+        a.C = pr.C;
+        a.p = pots;
+        a.colpart = (double *)(ws + L.o_part);
+        if (mode == 2) { a.P = dense_fused_grid(pr.n, pr.m, opt.fused_variant); a.rows_per_panel = 0; }
+        else { a.P = L.P_stream; a.rows_per_panel = L.rpp_stream; }
+        return a;
+    }
+    ErrSrc err_src() const {
+        ErrSrc e;
+        e.F = pots.F; e.a = pots.a; e.n = pr.n; e.n_ld = L.n_ld; e.errpart = errpart;
+        return e;
+    }
+    CombineArgs combine_g(int P, const double *part, const double *rowconst) const {
+        CombineArgs a{};
+        a.part = part; a.P = P; a.ld = L.m_ld; a.len = pr.m;
+        a.rowconst = rowconst; a.lw2 = pots.lb2; a.w = pots.b;
+        a.pot = pots.G; a.shift = pots.V;
+        a.do_advance = 1;
+        a.es = err_src();
+        return a;
+    }
+    CombineArgs combine_f(int P, const double *part, const double *rowconst) const {
+        CombineArgs a{};
+        a.part = part; a.P = P; a.ld = L.n_ld; a.len = pr.n;
+        a.rowconst = rowconst; a.lw2 = pots.la2; a.w = pots.a;
+        a.pot = pots.F; a.shift = pots.U;
+        a.do_advance = 0;
+        a.es = err_src();
+        return a;
+    }
+    PointsArgs points_f() const {
+        PointsArgs a{};
+        a.rows = (const double *)(ws + L.o_Xp);
+        a.cols2s = (const double *)(ws + L.o_Ys);
+        a.colconst = (const double *)(ws + L.o_cy);
+        a.colshift = pots.V;
+        a.nr = pr.n; a.nc = pr.m; a.d = pr.d;
+        a.part = (double *)(ws + L.o_part);
+        a.JS = L.JSf; a.ld = L.n_ld; a.cols_per_split = L.cpsf;
+        return a;
+    }
+    PointsArgs points_g() const {
+        PointsArgs a{};
+        a.rows = (const double *)(ws + L.o_Yp);
+        a.cols2s = (const double *)(ws + L.o_Xs);
+        a.colconst = (const double *)(ws + L.o_cx);
+        a.colshift = pots.U;
+        a.nr = pr.m; a.nc = pr.n; a.d = pr.d;
+        a.part = (double *)(ws + L.o_part2);
+        a.JS = L.JSg; a.ld = L.m_ld; a.cols_per_split = L.cpsg;
+        return a;
+    }
+
+    hipError_t enqueue_f_update(int phase) const {      // Eq. 9 (and the error terms of Sec. 4.5)
+        const Ctl c = ctl(phase);
+        hipError_t e = hipSuccess;
+        if (mode == 1) e = launch_dense_row(st, dense(), c);
+        else if (mode == 2) e = launch_dense_fused(st, dense(), c, opt.fused_variant);     // both half-steps
+        else {
+            e = launch_points_lse(st, points_f(), c, 0, L.m_ld);
+            if (e == hipSuccess)
+                e = launch_combine(st, combine_f(L.JSf, (const double *)(ws + L.o_part), (const double *)(ws + L.o_cx)), c);
+        }
+        return e;
+    }
+    hipError_t enqueue_g_update() const {                // Eq. 10 + state advance
+        const Ctl c = ctl(0);
+        hipError_t e = hipSuccess;
+        if (mode == 1) {
+            e = launch_dense_col(st, dense(), c);
+            if (e == hipSuccess) e = launch_combine(st, combine_g(L.P_stream, (const double *)(ws + L.o_part), nullptr), c);
+        } else if (mode == 2) {
+            {
+            const int g = dense_fused_grid(pr.n, pr.m, opt.fused_variant);
+            e = launch_combine(st, combine_g(g, (const double *)(ws + L.o_part), nullptr), c);
+        }
+        } else {
+            e = launch_points_lse(st, points_g(), c, 1, L.n_ld);
+            if (e == hipSuccess)
+                e = launch_combine(st, combine_g(L.JSg, (const double *)(ws + L.o_part2), (const double *)(ws + L.o_cy)), c);
+        }
+        return e;
+    }
+    hipError_t enqueue_iteration() const {
+        hipError_t e = enqueue_f_update(0);
+        if (e == hipSuccess) e = enqueue_g_update();
+        return e;
+    }
+    hipError_t enqueue_trailing() const {                // err after the last iteration
+        hipError_t e = enqueue_f_update(1);
+        if (e == hipSuccess) e = launch_advance(st, err_src(), ctl(1));
+        return e;
+    }
+    hipError_t enqueue_init() const {
+        int warm = 0;
+        if (opt.warm_start) warm = 3;
+        hipError_t e = launch_init(st, pots, state, /*f_in*/ warm_f, warm_g, opt.f64_in && opt.g64_in ? opt.f64_in : nullptr,
+                                   opt.f64_in && opt.g64_in ? opt.g64_in : nullptr, warm);
+        if (e == hipSuccess && mode == 3) {
+            e = launch_points_prep(st, pr.X, pr.n, pr.d, pots.s, (double *)(ws + L.o_Xp), (double *)(ws + L.o_Xs),
+                                   (double *)(ws + L.o_cx));
+            if (e == hipSuccess)
+                e = launch_points_prep(st, pr.Y, pr.m, pr.d, pots.s, (double *)(ws + L.o_Yp), (double *)(ws + L.o_Ys),
+                                       (double *)(ws + L.o_cy));
+        }
+        return e;
+    }
+    const float *warm_f = nullptr, *warm_g = nullptr;
+};
+
+fs_status validate(const Problem &p, const float *f, const float *g) {
+    if (p.n < 1 || p.m < 1) { set_err("n and m must be >= 1 (got %d, %d)", p.n, p.m); return FS_ERR_INVALID_ARG; }
+    if (!(p.eps > 0.0f) || !std::isfinite(p.eps)) { set_err("eps must be positive and finite"); return FS_ERR_INVALID_ARG; }
+    if (p.max_iter < 0) { set_err("max_iter must be >= 0"); return FS_ERR_INVALID_ARG; }
+    if (std::isnan(p.tol)) { set_err("tol must not be NaN"); return FS_ERR_INVALID_ARG; }
+    if (!p.a || !p.b) { set_err("a and b must be non-null"); return FS_ERR_INVALID_ARG; }
+    if (!f || !g) { set_err("f and g must be non-null"); return FS_ERR_INVALID_ARG; }
+    const bool dense = p.C != nullptr;
+    const bool points = p.X != nullptr || p.Y != nullptr;
+    if (dense == points) { set_err("exactly one of C or (X, Y) must be given"); return FS_ERR_INVALID_ARG; }
+    if (points) {
+        if (!p.X || !p.Y) { set_err("X and Y must both be non-null"); return FS_ERR_INVALID_ARG; }
+        if (p.d < 1 || p.d > FS_MAX_DIM) { set_err("d must be in [1, %d] (got %d)", FS_MAX_DIM, p.d); return FS_ERR_INVALID_ARG; }
+    }
+    if ((size_t)p.n > ((size_t)1 << 30) || (size_t)p.m > ((size_t)1 << 30)) {
+        set_err("n and m are limited to 2^30"); return FS_ERR_INVALID_ARG;
+    }
+    return FS_OK;
+}
+
+fs_status setup(Solve &S, const Problem &pr, const fs_options *opts, float *f, float *g, hipStream_t st,
+                void *ws, size_t ws_bytes) {
+    S.pr = pr;
+    S.opt = fs_options{};
+    if (opts) S.opt = *opts;
+    if (S.opt.check_every <= 0) S.opt.check_every = 10;
+    if (S.opt.err_history && S.opt.err_history_len < 0) { set_err("err_history_len < 0"); return FS_ERR_INVALID_ARG; }
+    S.L = make_layout(pr.n, pr.m, pr.C ? 0 : pr.d);
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) { set_err("workspace must be non-null and 256-byte aligned"); return FS_ERR_WORKSPACE; }
+    if (ws_bytes < S.L.total) { set_err("workspace too small: %zu < %zu bytes", ws_bytes, S.L.total); return FS_ERR_WORKSPACE; }
+    S.ws = (char *)ws;
+    S.st = st;
+    S.state = (State *)(S.ws + S.L.o_state);
+    Pots &p = S.pots;
+    p.F = (double *)(S.ws + S.L.o_F); p.U = (double *)(S.ws + S.L.o_U);
+    p.G = (double *)(S.ws + S.L.o_G); p.V = (double *)(S.ws + S.L.o_V);
+    p.la2 = (const double *)(S.ws + S.L.o_la2); p.lb2 = (const double *)(S.ws + S.L.o_lb2);
+    p.a = pr.a; p.b = pr.b;
+    p.n = pr.n; p.m = pr.m; p.n_ld = S.L.n_ld; p.m_ld = S.L.m_ld;
+    p.s = kLog2e / (double)pr.eps;
+    S.errpart = (double *)(S.ws + S.L.o_err);
+    S.host_flag = nullptr;
+    S.warm_f = f; S.warm_g = g;
+    if (pr.C) {
+        const bool fused_ok = dense_fused_supported(pr.n, pr.m, pr.C);
+        if (S.opt.kernel_mode == 2 && !fused_ok) { set_err("fused kernel does not support m = %d (needs m %% 4 == 0, m <= 8192, 16-byte aligned C)", pr.m); return FS_ERR_UNSUPPORTED; }
+        if (S.opt.kernel_mode < 0 || S.opt.kernel_mode > 2) { set_err("kernel_mode must be 0, 1 or 2"); return FS_ERR_INVALID_ARG; }
+        S.mode = S.opt.kernel_mode == 0 ? (fused_ok ? 2 : 1) : S.opt.kernel_mode;
+        if (S.mode == 2 && dense_fused_grid(pr.n, pr.m, S.opt.fused_variant) == 0) S.opt.fused_variant = 0;
+    } else {
+        S.mode = 3;
+    }
+    return FS_OK;
+}
+
+// Blocks of iterations replayed as one hipGraph.  The kernels read the iteration
+// index from device memory, so one captured block serves every replay; a replay
+// that overshoots max_iter, or that runs after the stop flag is set, is a no-op.
+struct GraphKey {
+    const void *ws, *C, *X, *a, *f;
+    int n, m, d, mode, block, max_iter, check_every;
+    float eps, tol;
+    bool operator<(const GraphKey &o) const {
+        return std::tie(ws, C, X, a, f, n, m, d, mode, block, max_iter, check_every, eps, tol) <
+               std::tie(o.ws, o.C, o.X, o.a, o.f, o.n, o.m, o.d, o.mode, o.block, o.max_iter, o.check_every, o.eps, o.tol);
+    }
+};
+
+fs_status run_solve_async(Solve &S, float *f, float *g, fs_result *result_dev) {
+    FS_HIP(S.enqueue_init());
+    for (int it = 0; it < S.pr.max_iter; ++it) FS_HIP(S.enqueue_iteration());
+    if (!S.opt.skip_final_err) FS_HIP(S.enqueue_trailing());
+    FS_HIP(launch_finalize(S.st, S.pots, S.state, f, g, S.opt.f64_out, S.opt.g64_out, result_dev, nullptr));
+    return FS_OK;
+}
+
+int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result *result_host) {
+    HostBlock *hb = dc->host;
+    hb->flag = 0;
+    memset((void *)&hb->res, 0, sizeof(hb->res));
+    void *hb_dev = nullptr;
+    FS_HIP(hipHostGetDevicePointer(&hb_dev, (void *)hb, 0));
+    S.host_flag = (volatile int32_t *)hb_dev;
+    FS_HIP(S.enqueue_init());
+    const int block = S.opt.check_every;
+    int it = 0, blk = 0;
+    while (it < S.pr.max_iter) {
+        if (hb->flag) break;                           // the device has stopped: enqueue nothing more
+        if (blk >= 3) FS_HIP(hipEventSynchronize(dc->ev[(blk - 3) & 3]));   // bound the run-ahead to 3 blocks
+        if (hb->flag) break;
+        const int nb = (S.pr.max_iter - it) < block ? (S.pr.max_iter - it) : block;
+        for (int q = 0; q < nb; ++q) FS_HIP(S.enqueue_iteration());
+        FS_HIP(hipEventRecord(dc->ev[blk & 3], S.st));
+        it += nb;
+        ++blk;
+    }
+    if (!S.opt.skip_final_err && !hb->flag) FS_HIP(S.enqueue_trailing());
+    FS_HIP(launch_finalize(S.st, S.pots, S.state, f, g, S.opt.f64_out, S.opt.g64_out, nullptr,
+                           (char *)hb_dev + offsetof(HostBlock, res)));
+    FS_HIP(hipStreamSynchronize(S.st));
+    if (result_host) *result_host = hb->res;
+    return hb->res.iters;
+}
+
+int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const fs_options *opts,
+                   fs_result *result_host) {
+    fs_status v = validate(pr, f, g);
+    if (v != FS_OK) return v;
+    Layout L = make_layout(pr.n, pr.m, pr.C ? 0 : pr.d);
+    DeviceCache *dc = nullptr;
+    v = get_cache(L.total, &dc);
+    if (v != FS_OK) return v;
+    Solve S;
+    v = setup(S, pr, opts, f, g, st, dc->ws, dc->ws_bytes);
+    if (v != FS_OK) return v;
+    return run_solve_blocking(S, dc, f, g, result_host);
+}
+
+fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, const fs_options *opts,
+                      void *ws, size_t ws_bytes, fs_result *result_dev) {
+    fs_status v = validate(pr, f, g);
+    if (v != FS_OK) return v;
+    Solve S;
+    v = setup(S, pr, opts, f, g, st, ws, ws_bytes);
+    if (v != FS_OK) return v;
+    return run_solve_async(S, f, g, result_dev);
+}
+
+fs_status plan_or_cost(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                       int n, int m, float eps, const float *f, const float *g, const double *f64,
+                       const double *g64, float *P, double *cost_dev, hipStream_t st) {
+    Problem pr{C, X, Y, a, b, d, n, m, eps, 0, 0.0f};
+    const float *fchk = f ? f : (const float *)f64, *gchk = g ? g : (const float *)g64;
+    fs_status v = validate(pr, (float *)fchk, (float *)gchk);
+    if (v != FS_OK) return v;
+    if (!P && !cost_dev) { set_err("output pointer is null"); return FS_ERR_INVALID_ARG; }
+    const int need = cost_scratch_len(n, m);
+    DeviceCache *dc = nullptr;
+    v = get_cache(sizeof(double) * (size_t)need, &dc);
+    if (v != FS_OK) return v;
+    PlanArgs A{};
+    A.C = C; A.X = X; A.Y = Y; A.a = a; A.b = b; A.f = f; A.g = g; A.f64 = f64; A.g64 = g64;
+    A.n = n; A.m = m; A.d = C ? 0 : d;
+    A.s = kLog2e / (double)eps;
+    if (P) FS_HIP(launch_plan(st, A, P, (double *)dc->ws, need));
+    else FS_HIP(launch_cost(st, A, cost_dev, (double *)dc->ws, need));
+    return FS_OK;
+}
+
+fs_status half_step(bool update_f, const float *C, const float *X, const float *Y, int d, const float *a,
+                    const float *b, int n, int m, float eps, const double *in64, double *out64, hipStream_t st) {
+    Problem pr{C, X, Y, a, b, d, n, m, eps, 1, 0.0f};
+    fs_status v = validate(pr, (float *)in64, (float *)out64);
+    if (v != FS_OK) return v;
+    Layout L = make_layout(n, m, C ? 0 : d);
+    DeviceCache *dc = nullptr;
+    v = get_cache(L.total, &dc);
+    if (v != FS_OK) return v;
+    Solve S;
+    fs_options o{};
+    o.kernel_mode = C ? 1 : 0;
+    v = setup(S, pr, &o, nullptr, nullptr, st, dc->ws, dc->ws_bytes);
+    if (v != FS_OK) return v;
+    // start state: the given side from in64, the other side zero; iteration counter 0
+    FS_HIP(launch_init(st, S.pots, S.state, nullptr, nullptr, update_f ? nullptr : in64, update_f ? in64 : nullptr,
+                       update_f ? 2 : 1));
+    if (S.mode == 3) {
+        FS_HIP(launch_points_prep(st, X, n, d, S.pots.s, (double *)(S.ws + L.o_Xp), (double *)(S.ws + L.o_Xs), (double *)(S.ws + L.o_cx)));
+        FS_HIP(launch_points_prep(st, Y, m, d, S.pots.s, (double *)(S.ws + L.o_Yp), (double *)(S.ws + L.o_Ys), (double *)(S.ws + L.o_cy)));
+    }
+    if (update_f) {
+        FS_HIP(S.enqueue_f_update(0));                 // writes F into buffer 1
+        FS_HIP(launch_export(st, S.pots.F + L.n_ld, n, S.pots.s, out64));
+    } else {
+        FS_HIP(S.enqueue_g_update());                  // reads U of buffer 1 (= the given f), writes G into buffer 1
+        FS_HIP(launch_export(st, S.pots.G + L.m_ld, m, S.pots.s, out64));
+    }
+    return FS_OK;
+}
+
+}  // namespace
+
+// ================================================================ C ABI
+extern "C" {
+
+const char *fs_last_error(void) { return g_err; }
+const char *fs_version(void) { return "fastsinkhorn-gfx950 0.1"; }
+
+void fs_clear_cache(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (auto &kv : g_cache) {
+        DeviceCache &c = kv.second;
+        int cur = 0;
+        if (hipGetDevice(&cur) != hipSuccess) continue;
+        (void)hipSetDevice(kv.first);
+        (void)hipDeviceSynchronize();
+        if (c.ws) (void)hipFree(c.ws);
+        if (c.host) (void)hipHostFree((void *)c.host);
+        for (auto &e : c.ev) if (e) (void)hipEventDestroy(e);
+        (void)hipSetDevice(cur);
+    }
+    g_cache.clear();
+}
+
+size_t fs_workspace_bytes(int n, int m, int d) {
+    if (n < 1 || m < 1 || d < 0 || d > FS_MAX_DIM) return 0;
+    return make_layout(n, m, d).total;
+}
+
+int fs_sinkhorn_dense(const float *C, const float *a, const float *b, int n, int m, float eps, int max_iter,
+                      float tol, float *f, float *g, fs_stream stream) {
+    if (!C) { set_err("C must be non-null"); return FS_ERR_INVALID_ARG; }
+    Problem pr{C, nullptr, nullptr, a, b, 0, n, m, eps, max_iter, tol};
+    return solve_blocking(pr, f, g, (hipStream_t)stream, nullptr, nullptr);
+}
+
+int fs_sinkhorn_points(const float *X, const float *Y, int d, const float *a, const float *b, int n, int m,
+                       float eps, int max_iter, float tol, float *f, float *g, fs_stream stream) {
+    if (!X || !Y) { set_err("X and Y must be non-null"); return FS_ERR_INVALID_ARG; }
+    Problem pr{nullptr, X, Y, a, b, d, n, m, eps, max_iter, tol};
+    return solve_blocking(pr, f, g, (hipStream_t)stream, nullptr, nullptr);
+}
+
+int fs_sinkhorn_solve(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                      int n, int m, float eps, int max_iter, float tol, float *f, float *g, fs_stream stream,
+                      const fs_options *opts, fs_result *result_host) {
+    Problem pr{C, X, Y, a, b, d, n, m, eps, max_iter, tol};
+    return solve_blocking(pr, f, g, (hipStream_t)stream, opts, result_host);
+}
+
+fs_status fs_sinkhorn_dense_ex(const float *C, const float *a, const float *b, int n, int m, float eps,
+                               int max_iter, float tol, float *f, float *g, fs_stream stream,
+                               const fs_options *opts, void *workspace, size_t workspace_bytes,
+                               fs_result *result_dev) {
+    if (!C) { set_err("C must be non-null"); return FS_ERR_INVALID_ARG; }
+    Problem pr{C, nullptr, nullptr, a, b, 0, n, m, eps, max_iter, tol};
+    return solve_async(pr, f, g, (hipStream_t)stream, opts, workspace, workspace_bytes, result_dev);
+}
+
+fs_status fs_sinkhorn_points_ex(const float *X, const float *Y, int d, const float *a, const float *b, int n,
+                                int m, float eps, int max_iter, float tol, float *f, float *g, fs_stream stream,
+                                const fs_options *opts, void *workspace, size_t workspace_bytes,
+                                fs_result *result_dev) {
+    if (!X || !Y) { set_err("X and Y must be non-null"); return FS_ERR_INVALID_ARG; }
+    Problem pr{nullptr, X, Y, a, b, d, n, m, eps, max_iter, tol};
+    return solve_async(pr, f, g, (hipStream_t)stream, opts, workspace, workspace_bytes, result_dev);
+}
+
+fs_status fs_plan(const float *C, const float *X, const float *Y, int d, const float *a, const float *b, int n,
+                  int m, float eps, const float *f, const float *g, float *P, fs_stream stream) {
+    if (!P) { set_err("P must be non-null"); return FS_ERR_INVALID_ARG; }
+    if (!f || !g) { set_err("f and g must be non-null"); return FS_ERR_INVALID_ARG; }
+    return plan_or_cost(C, X, Y, d, a, b, n, m, eps, f, g, nullptr, nullptr, P, nullptr, (hipStream_t)stream);
+}
+
+fs_status fs_cost(const float *C, const float *X, const float *Y, int d, const float *a, const float *b, int n,
+                  int m, float eps, const float *f, const float *g, double *cost_dev, fs_stream stream) {
+    if (!cost_dev) { set_err("cost_dev must be non-null"); return FS_ERR_INVALID_ARG; }
+    if (!f || !g) { set_err("f and g must be non-null"); return FS_ERR_INVALID_ARG; }
+    return plan_or_cost(C, X, Y, d, a, b, n, m, eps, f, g, nullptr, nullptr, nullptr, cost_dev, (hipStream_t)stream);
+}
+
+fs_status fs_plan_f64(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                      int n, int m, float eps, const double *f64, const double *g64, float *P, fs_stream stream) {
+    if (!P) { set_err("P must be non-null"); return FS_ERR_INVALID_ARG; }
+    if (!f64 || !g64) { set_err("f64 and g64 must be non-null"); return FS_ERR_INVALID_ARG; }
+    return plan_or_cost(C, X, Y, d, a, b, n, m, eps, nullptr, nullptr, f64, g64, P, nullptr, (hipStream_t)stream);
+}
+
+fs_status fs_cost_f64(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                      int n, int m, float eps, const double *f64, const double *g64, double *cost_dev,
+                      fs_stream stream) {
+    if (!cost_dev) { set_err("cost_dev must be non-null"); return FS_ERR_INVALID_ARG; }
+    if (!f64 || !g64) { set_err("f64 and g64 must be non-null"); return FS_ERR_INVALID_ARG; }
+    return plan_or_cost(C, X, Y, d, a, b, n, m, eps, nullptr, nullptr, f64, g64, nullptr, cost_dev, (hipStream_t)stream);
+}
+
+fs_status fs_update_f(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                      int n, int m, float eps, const double *g64, double *f64_out, fs_stream stream) {
+    if (!g64 || !f64_out) { set_err("g64 and f64_out must be non-null"); return FS_ERR_INVALID_ARG; }
+    return half_step(true, C, X, Y, d, a, b, n, m, eps, g64, f64_out, (hipStream_t)stream);
+}
+
+fs_status fs_update_g(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                      int n, int m, float eps, const double *f64, double *g64_out, fs_stream stream) {
+    if (!f64 || !g64_out) { set_err("f64 and g64_out must be non-null"); return FS_ERR_INVALID_ARG; }
+    return half_step(false, C, X, Y, d, a, b, n, m, eps, f64, g64_out, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,362 @@
+// Dense-cost kernels for gfx950.
+//
+//   k_row_stream   f-update (Eq. 9): one workgroup owns 4 rows and streams them
+//                  once with coalesced 16-byte loads, online (max, sum) LSE per
+//                  lane, wave64 DPP reduction, LDS combine of the 4 waves.
+//   k_col_stream   g-update (Eq. 10) without strided reads: a workgroup owns a
+//                  strip of adjacent columns (4 per lane) and walks down a panel
+//                  of rows; every load is a coalesced row segment and the
+//                  reduction over rows is lane-local.  Per-panel partial LSE
+//                  values are merged by k_combine.
+//   k_fused        both half-steps in ONE pass over C: a workgroup holds a
+//                  panel of R full rows in registers, finishes their row LSE
+//                  (new f_i), and immediately folds the same registers into the
+//                  running column LSE with the new f_i.  HBM sees C once per
+//                  iteration instead of twice.
+#include "fs_kernels.h"
+
+namespace fs {
+
+constexpr int kRowsPerWG = 4;      // k_row_stream
+constexpr int kStreamT = 256;
+
+template <int VEC>
+struct VecLoad;
+template <>
+struct VecLoad<4> {
+    static __device__ __forceinline__ void ld(const float *p, float (&o)[4]) {
+        const float4 v = *reinterpret_cast<const float4 *>(p);
+        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    }
+};
+template <>
+struct VecLoad<1> {
+    static __device__ __forceinline__ void ld(const float *p, float (&o)[1]) { o[0] = *p; }
+};
+
+// ---------------------------------------------------------------- row pass (streaming)
+template <int VEC>
+__global__ __launch_bounds__(kStreamT) void k_row_stream(DenseArgs A, Ctl c) {
+    __shared__ double sM[kRowsPerWG][kStreamT / 64];
+    __shared__ float sS[kRowsPerWG][kStreamT / 64];
+    int k;
+    if (!launch_active(c, k)) return;
+    const int cur = k & 1, nxt = cur ^ 1;
+    const Pots &p = A.p;
+    const int tid = threadIdx.x;
+    const int i0 = blockIdx.x * kRowsPerWG;
+    const double *V = p.V + (size_t)cur * p.m_ld;
+    const double ns = -p.s;
+
+    Lse acc[kRowsPerWG];
+#pragma unroll
+    for (int r = 0; r < kRowsPerWG; ++r) acc[r].init();
+
+    for (int col = tid * VEC; col < p.m; col += kStreamT * VEC) {
+        double v[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = V[col + e];
+#pragma unroll
+        for (int r = 0; r < kRowsPerWG; ++r) {
+            const int i = i0 + r;
+            if (i < p.n) {
+                float cv[VEC];
+                VecLoad<VEC>::ld(A.C + (size_t)i * p.m + col, cv);
+                double x[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[e] = fma(ns, (double)cv[e], v[e]);
+                acc[r].template add<VEC>(x);
+            }
+        }
+    }
+    const int wave = tid >> 6, lane = tid & 63;
+#pragma unroll
+    for (int r = 0; r < kRowsPerWG; ++r) {
+        acc[r].wave_reduce();
+        if (lane == 0) { sM[r][wave] = acc[r].M; sS[r][wave] = acc[r].s; }
+    }
+    __syncthreads();
+    if (tid < kRowsPerWG) {
+        const int i = i0 + tid;
+        if (i < p.n) {
+            Lse t; t.init();
+#pragma unroll
+            for (int w = 0; w < kStreamT / 64; ++w) t.merge(sM[tid][w], sS[tid][w]);
+            const double Fn = t.value();
+            p.F[(size_t)nxt * p.n_ld + i] = Fn;
+            p.U[(size_t)nxt * p.n_ld + i] = p.la2[i] - Fn;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- column pass (streaming)
+template <int VEC>
+__global__ __launch_bounds__(kStreamT) void k_col_stream(DenseArgs A, Ctl c) {
+    int k;
+    if (!launch_active(c, k)) return;
+    const int nxt = (k & 1) ^ 1;
+    const Pots &p = A.p;
+    const int j0 = (blockIdx.x * kStreamT + threadIdx.x) * VEC;
+    if (j0 >= p.m) return;                       // no cross-lane work below
+    const int r0 = blockIdx.y * A.rows_per_panel;
+    const int r1 = min(p.n, r0 + A.rows_per_panel);
+    const double *U = p.U + (size_t)nxt * p.n_ld;     // the new f of this iteration (Gauss-Seidel order)
+    const double ns = -p.s;
+
+    Lse acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e].init();
+
+    constexpr int RC = 4;                         // rows folded per rescale
+    for (int i = r0; i < r1; i += RC) {
+        double x[VEC][RC];
+#pragma unroll
+        for (int q = 0; q < RC; ++q) {
+            const int ii = i + q;
+            if (ii < r1) {
+                float cv[VEC];
+                VecLoad<VEC>::ld(A.C + (size_t)ii * p.m + j0, cv);
+                const double u = U[ii];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[e][q] = fma(ns, (double)cv[e], u);
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[e][q] = kNegHuge;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e].template add<RC>(x[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) A.colpart[(size_t)blockIdx.y * p.m_ld + j0 + e] = acc[e].value();
+}
+
+static bool vec4_ok(const DenseArgs &a) {
+    return (a.p.m % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.C) & 15u) == 0);
+}
+
+void dense_stream_plan(int n, int m, int *P, int *rows_per_panel) {
+    const int strips = (m + kStreamT * 4 - 1) / (kStreamT * 4);   // conservative: vector path
+    int want = (1024 + strips - 1) / strips;                      // about 1024 workgroups in total
+    int maxP = (n + 15) / 16;                                     // at least 16 rows per panel
+    int p = want < maxP ? want : maxP;
+    if (p < 1) p = 1;
+    if (p > 512) p = 512;
+    int rpp = (n + p - 1) / p;
+    p = (n + rpp - 1) / rpp;
+    *P = p;
+    *rows_per_panel = rpp;
+}
+
+hipError_t launch_dense_row(hipStream_t st, const DenseArgs &a, const Ctl &c) {
+    const dim3 grid((a.p.n + kRowsPerWG - 1) / kRowsPerWG);
+    if (vec4_ok(a)) hipLaunchKernelGGL(k_row_stream<4>, grid, dim3(kStreamT), 0, st, a, c);
+    else hipLaunchKernelGGL(k_row_stream<1>, grid, dim3(kStreamT), 0, st, a, c);
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_col(hipStream_t st, const DenseArgs &a, const Ctl &c) {
+    if (vec4_ok(a)) {
+        const dim3 grid((a.p.m + kStreamT * 4 - 1) / (kStreamT * 4), a.P);
+        hipLaunchKernelGGL(k_col_stream<4>, grid, dim3(kStreamT), 0, st, a, c);
+    } else {
+        const dim3 grid((a.p.m + kStreamT - 1) / kStreamT, a.P);
+        hipLaunchKernelGGL(k_col_stream<1>, grid, dim3(kStreamT), 0, st, a, c);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- fused row-panel pass
+// T threads, each owning Q groups of 4 adjacent columns: column(q, e) =
+// (q*T + tid)*4 + e, so a panel row is read as Q fully coalesced 16-byte loads
+// per lane and m <= 4*Q*T.  R rows are held at once.
+template <int T, int Q, int R>
+__global__ __launch_bounds__(T) void k_fused(DenseArgs A, Ctl c) {
+    constexpr int NW = T / 64;
+    static_assert(R * NW <= 64, "one wave merges all (row, wave) partials in one shot");
+    __shared__ double sM[2][R][NW];
+    __shared__ float sS[2][R][NW];
+    int k;
+    if (!launch_active(c, k)) return;
+    const int cur = k & 1, nxt = cur ^ 1;
+    const Pots &p = A.p;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const double ns = -p.s;
+    const bool col_phase = (c.phase == 0);        // the trailing error pass needs the row LSE only
+    const int m = p.m;                            // m % 4 == 0 on this path
+
+    double v[Q][4];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int col = (q * T + tid) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            v[q][e] = col < m ? p.V[(size_t)cur * p.m_ld + col + e] : -__builtin_huge_val();
+    }
+    Lse cs[Q][4];
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cs[q][e].init();
+
+    const int npanels = (p.n + R - 1) / R;
+    int par = 0;
+    for (int pn = blockIdx.x; pn < npanels; pn += gridDim.x, par ^= 1) {
+        const int i0 = pn * R;
+        float cv[R][Q][4];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const bool rok = (i0 + r) < p.n;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int col = (q * T + tid) * 4;
+                if (rok && col < m) {
+                    VecLoad<4>::ld(A.C + (size_t)(i0 + r) * m + col, cv[r][q]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) cv[r][q][e] = 0.0f;
+                }
+            }
+        }
+        // ---- row phase: lane-local LSE over the lane's 4Q columns (one row at a time, so that
+        //      only one row's fp64 arguments are live), then the wave reductions of all R rows
+        Lse rs[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            double x[Q * 4];
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[q * 4 + e] = fma(ns, (double)cv[r][q][e], v[q][e]);
+            rs[r].init();
+            rs[r].template add<Q * 4>(x);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            rs[r].wave_reduce();
+            if (lane == 0) { sM[par][r][wave] = rs[r].M; sS[par][r][wave] = rs[r].s; }
+        }
+        __syncthreads();
+        // ---- every wave merges the NW wave partials of all R rows: lane r*NW + w holds (row r, wave w)
+        double Fn_lane;
+        {
+            const int rr = lane / NW, ww = lane % NW;
+            Lse t; t.init();
+            if (rr < R) { t.M = sM[par][rr][ww]; t.s = sS[par][rr][ww]; }
+            double Mg = t.M;
+#pragma unroll
+            for (int off = NW / 2; off >= 1; off >>= 1) Mg = dmax(Mg, __shfl_xor(Mg, off));
+            float sg = t.s * fast_exp2((float)(t.M - Mg));
+#pragma unroll
+            for (int off = NW / 2; off >= 1; off >>= 1) sg += __shfl_xor(sg, off);
+            Fn_lane = Mg + (double)fast_log2(sg);
+        }
+        // ---- new potentials: lane r*NW of wave 0 owns row r
+        if (wave == 0 && (lane % NW) == 0 && (lane / NW) < R) {
+            const int i = i0 + lane / NW;
+            if (i < p.n) {
+                p.F[(size_t)nxt * p.n_ld + i] = Fn_lane;
+                p.U[(size_t)nxt * p.n_ld + i] = p.la2[i] - Fn_lane;
+            }
+        }
+        // ---- column phase with the new f: lane-local over the R rows, one column at a time
+        if (col_phase) {
+            double u[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const double Fn = __shfl(Fn_lane, r * NW);
+                u[r] = (i0 + r) < p.n ? p.la2[i0 + r] - Fn : -__builtin_huge_val();
+            }
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    double y[R];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) y[r] = fma(ns, (double)cv[r][q][e], u[r]);
+                    cs[q][e].template add<R>(y);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    if (col_phase) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int col = (q * T + tid) * 4;
+            if (col < m) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    A.colpart[(size_t)blockIdx.x * p.m_ld + col + e] = cs[q][e].value();
+            }
+        }
+    }
+}
+
+struct FusedShape { int T, Q, R; };
+
+// Shapes held in registers without spilling: 4*Q*T columns, R rows per panel.
+static bool fused_shape(int m, int variant, FusedShape *fsh) {
+    if (m % 4 != 0) return false;
+    if (m <= 1024) { *fsh = {256, 1, 4}; return true; }
+    if (m <= 4096) { *fsh = {1024, 1, 4}; return true; }
+    if (m <= 8192) {
+        if (variant == 1) *fsh = {1024, 2, 2};
+        else if (variant == 2) *fsh = {1024, 2, 4};
+        else if (variant == 3) *fsh = {512, 4, 2};
+        else *fsh = {512, 4, 4};
+        return true;
+    }
+    return false;
+}
+
+bool dense_fused_supported(int n, int m, const void *C) {
+    FusedShape s;
+    (void)n;
+    return fused_shape(m, 0, &s) && ((reinterpret_cast<uintptr_t>(C) & 15u) == 0);
+}
+
+void dense_fused_plan(int n, int m, int *P) {
+    // the largest grid any variant uses: one panel set per resident workgroup
+    FusedShape s{256, 1, 4};
+    int best = 1;
+    for (int variant = 0; variant < 4; ++variant) {
+        if (!fused_shape(m, variant, &s)) continue;
+        const int npanels = (n + s.R - 1) / s.R;
+        const int resident = s.T == 256 ? 1024 : 256;      // workgroups the 256 CUs hold at once
+        const int p = npanels < resident ? npanels : resident;
+        if (p > best) best = p;
+    }
+    *P = best;
+}
+
+hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, int variant) {
+    FusedShape s;
+    if (!fused_shape(a.p.m, variant, &s)) return hipErrorInvalidValue;
+    const int npanels = (a.p.n + s.R - 1) / s.R;
+    const int resident = s.T == 256 ? 1024 : 256;
+    int g = npanels < resident ? npanels : resident;
+    if (g > a.P) g = a.P;
+    DenseArgs b = a;
+    b.P = g;
+    const dim3 grid(g);
+    if (s.T == 256) hipLaunchKernelGGL((k_fused<256, 1, 4>), grid, dim3(256), 0, st, b, c);
+    else if (s.T == 1024 && s.Q == 1) hipLaunchKernelGGL((k_fused<1024, 1, 4>), grid, dim3(1024), 0, st, b, c);
+    else if (s.T == 1024 && s.R == 2) hipLaunchKernelGGL((k_fused<1024, 2, 2>), grid, dim3(1024), 0, st, b, c);
+    else if (s.T == 1024) hipLaunchKernelGGL((k_fused<1024, 2, 4>), grid, dim3(1024), 0, st, b, c);
+    else if (s.R == 2) hipLaunchKernelGGL((k_fused<512, 4, 2>), grid, dim3(512), 0, st, b, c);
+    else hipLaunchKernelGGL((k_fused<512, 4, 4>), grid, dim3(512), 0, st, b, c);
+    return hipGetLastError();
+}
+
+// number of column-partial sets the fused launch of this shape writes
+int dense_fused_grid(int n, int m, int variant) {
+    FusedShape s;
+    if (!fused_shape(m, variant, &s)) return 0;
+    const int npanels = (n + s.R - 1) / s.R;
+    const int resident = s.T == 256 ? 1024 : 256;
+    return npanels < resident ? npanels : resident;
+}
+
+}  // namespace fs

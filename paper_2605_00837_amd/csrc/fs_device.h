@@ -1,0 +1,195 @@
+// Device-side building blocks shared by the gfx950 kernels: wave64 reductions
+// (DPP inside a row of 16 lanes, ds_swizzle / ds_bpermute across rows), the
+// fp32 exp2/log2 hardware instructions, the online (max, sum) LogSumExp update
+// and the device-resident solver state.
+//
+// Arithmetic convention of every kernel.  With s = log2(e)/eps the potentials
+// are carried as F_i = -s f_i and G_j = -s g_j in double precision, together
+// with U_i = log2 a_i - F_i and V_j = log2 b_j - G_j.  One half-step of the
+// paper's Eq. 9 is then F_i = LSE2_j( V_j - s C_ij ), and Eq. 10 is
+// G_j = LSE2_i( U_i - s C_ij ), where LSE2 is the base-2 LogSumExp of Eq. 8.
+// The argument of every exponential is formed in fp64 and only the difference
+// to the running maximum is rounded to fp32 for v_exp_f32.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fs {
+
+constexpr double kNegHuge = -1.0e300;   // finite stand-in for "-inf" as a running maximum
+
+// ---------------------------------------------------------------- state
+// Lives in device memory (first 256 bytes of the workspace).  Written only by
+// the init kernel, by the single "advance" thread after each iteration and by
+// the finalize kernels.
+struct alignas(256) State {
+    int32_t k;            // iterations completed
+    int32_t done;         // stop flag: every later kernel of the solve returns at once
+    int32_t iters;        // result: iterations whose potentials are returned
+    int32_t converged;
+    int32_t nonfinite;
+    uint32_t ticket;      // last-workgroup-done counter (returns to 0 after every use)
+    int32_t err_valid;
+    int32_t pad0;
+    double err;           // err after `iters`
+};
+
+// Constant description of one solve, passed by value to the kernels.
+struct Ctl {
+    State *st;
+    int32_t max_iter;
+    int32_t check_every;
+    double tol;               // <= 0: fixed iteration count
+    float *err_history;       // device, may be null
+    int32_t err_history_len;
+    int32_t phase;            // 0: iteration kernel, 1: trailing error pass
+    volatile int32_t *host_flag;   // pinned host mirror of `done`, may be null
+};
+
+// Does this launch have work to do?  Iteration kernels run while k < max_iter,
+// the trailing error pass runs only when k == max_iter; nothing runs once done.
+__device__ __forceinline__ bool launch_active(const Ctl &c, int &k) {
+    const volatile State *st = c.st;
+    k = st->k;
+    if (st->done) return false;
+    return c.phase == 0 ? (k < c.max_iter) : (k == c.max_iter);
+}
+
+// ---------------------------------------------------------------- math
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }    // v_log_f32
+
+__device__ __forceinline__ double dmax(double a, double b) { return fmax(a, b); }
+
+// log2 of an fp32 weight in double precision; zero (or negative) weight -> -inf.
+__device__ __forceinline__ double log2_weight(float w) {
+    return w > 0.0f ? log2((double)w) : -__builtin_huge_val();
+}
+
+// ---------------------------------------------------------------- DPP / swizzle moves
+// dpp_ctrl encodings: row_ror:n = 0x120 + n (rotate inside a row of 16 lanes).
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(dpp_i32<CTRL>(__float_as_int(v)));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    int lo = dpp_i32<CTRL>(__double2loint(v));
+    int hi = dpp_i32<CTRL>(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+// lane ^ 16 inside each half-wave: ds_swizzle bit mode, and_mask 0x1f, xor_mask 0x10.
+__device__ __forceinline__ int swz16_i32(int v) { return __builtin_amdgcn_ds_swizzle(v, 0x401F); }
+// lane ^ 32: crosses the two half-waves, needs ds_bpermute.
+__device__ __forceinline__ int xor32_i32(int v) {
+    int lane = __lane_id();
+    return __builtin_amdgcn_ds_bpermute(((lane ^ 32) << 2), v);
+}
+__device__ __forceinline__ float swz16_f32(float v) { return __int_as_float(swz16_i32(__float_as_int(v))); }
+__device__ __forceinline__ float xor32_f32(float v) { return __int_as_float(xor32_i32(__float_as_int(v))); }
+__device__ __forceinline__ double swz16_f64(double v) {
+    return __hiloint2double(swz16_i32(__double2hiint(v)), swz16_i32(__double2loint(v)));
+}
+__device__ __forceinline__ double xor32_f64(double v) {
+    return __hiloint2double(xor32_i32(__double2hiint(v)), xor32_i32(__double2loint(v)));
+}
+
+// All-reduce over the 64 lanes of a wave; every lane must be active.
+__device__ __forceinline__ double wave_max_f64(double v) {
+    v = dmax(v, dpp_f64<0x128>(v));   // row_ror:8
+    v = dmax(v, dpp_f64<0x124>(v));   // row_ror:4
+    v = dmax(v, dpp_f64<0x122>(v));   // row_ror:2
+    v = dmax(v, dpp_f64<0x121>(v));   // row_ror:1
+    v = dmax(v, swz16_f64(v));
+    v = dmax(v, xor32_f64(v));
+    return v;
+}
+__device__ __forceinline__ float wave_sum_f32(float v) {
+    v += dpp_f32<0x128>(v);
+    v += dpp_f32<0x124>(v);
+    v += dpp_f32<0x122>(v);
+    v += dpp_f32<0x121>(v);
+    v += swz16_f32(v);
+    v += xor32_f32(v);
+    return v;
+}
+__device__ __forceinline__ double wave_sum_f64(double v) {
+    v += dpp_f64<0x128>(v);
+    v += dpp_f64<0x124>(v);
+    v += dpp_f64<0x122>(v);
+    v += dpp_f64<0x121>(v);
+    v += swz16_f64(v);
+    v += xor32_f64(v);
+    return v;
+}
+
+// ---------------------------------------------------------------- online LSE
+// Running base-2 LogSumExp as (M, s): value = M + log2(s), s = sum 2^(x - M).
+struct Lse {
+    double M;
+    float s;
+    __device__ __forceinline__ void init() { M = kNegHuge; s = 0.0f; }
+    // fold a chunk of N arguments; one rescale per chunk
+    template <int N>
+    __device__ __forceinline__ void add(const double (&x)[N]) {
+        double cm = x[0];
+#pragma unroll
+        for (int e = 1; e < N; ++e) cm = dmax(cm, x[e]);
+        const double Mn = dmax(M, cm);
+        float acc = s * fast_exp2((float)(M - Mn));
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc += fast_exp2((float)(x[e] - Mn));
+        s = acc;
+        M = Mn;
+    }
+    // merge another running pair
+    __device__ __forceinline__ void merge(double M2, float s2) {
+        const double Mn = dmax(M, M2);
+        s = s * fast_exp2((float)(M - Mn)) + s2 * fast_exp2((float)(M2 - Mn));
+        M = Mn;
+    }
+    // all lanes of the wave end up with the wave's pair
+    __device__ __forceinline__ void wave_reduce() {
+        const double Mw = wave_max_f64(M);
+        s = wave_sum_f32(s * fast_exp2((float)(M - Mw)));
+        M = Mw;
+    }
+    __device__ __forceinline__ double value() const { return M + (double)fast_log2(s); }
+};
+
+// ---------------------------------------------------------------- advance
+// Runs in ONE thread after the g-update of an iteration (or after the trailing
+// error pass).  `err` is the row-marginal error of the iterate the launch
+// started from, i.e. err_k for k = st->k (Alg. 1: checked when k mod c == 0).
+__device__ __forceinline__ void advance_state(const Ctl &c, int k, double err) {
+    State *st = c.st;
+    if (c.err_history && k >= 1 && k - 1 < c.err_history_len) c.err_history[k - 1] = (float)err;
+    const bool checked = (c.tol > 0.0) && (k >= 1) && (k % c.check_every == 0);
+    bool stop = false;
+    if (c.phase == 1) {                 // trailing pass: k == max_iter, nothing left to run
+        stop = true;
+        st->converged = (checked && err < c.tol) ? 1 : 0;
+    } else if (checked && err < c.tol) {
+        stop = true;
+        st->converged = 1;
+    }
+    if (stop) {
+        st->iters = k;
+        st->err = err;
+        st->err_valid = 1;
+        __threadfence();
+        st->done = 1;
+        if (c.host_flag) {
+            *c.host_flag = 1;
+            __threadfence_system();
+        }
+    } else {
+        st->k = k + 1;
+    }
+}
+
+}  // namespace fs

@@ -1,0 +1,105 @@
+// Host-visible declarations of the kernel launchers (one translation unit per
+// kernel family; the C ABI in fs_api.hip drives them).
+#pragma once
+#include "fs_device.h"
+
+namespace fs {
+
+// Arrays of one solve.  F, U, G, V are double-buffered by iteration parity:
+// buffer (k & 1) holds the potentials after k iterations.
+struct Pots {
+    double *F, *U;        // [2][n_ld]   F_i = -s f_i,  U_i = log2 a_i - F_i
+    double *G, *V;        // [2][m_ld]   G_j = -s g_j,  V_j = log2 b_j - G_j
+    const double *la2;    // [n] log2 a_i
+    const double *lb2;    // [m] log2 b_j
+    const float *a;       // [n] weights (for the error terms)
+    const float *b;       // [m]
+    int32_t n, m, n_ld, m_ld;
+    double s;             // log2(e) / eps
+};
+
+struct DenseArgs {
+    const float *C;       // n x m row-major
+    Pots p;
+    double *colpart;      // [P][m_ld] per-panel partial column LSE values
+    int32_t P;            // number of row panels of the column pass
+    int32_t rows_per_panel;
+};
+
+// Where the row-marginal error comes from.  r_i = a_i 2^(Fnew_i - Fold_i) is the row marginal of
+// the iterate a launch started from (the new f-update computes exactly the LSE of Sec. 4.5), so
+// err = sum_i a_i |2^(Fnew_i - Fold_i) - 1| needs only the two F buffers.
+struct ErrSrc {
+    const double *F;          // [2][n_ld]
+    const float *a;           // [n]
+    int32_t n, n_ld;
+    double *errpart;          // [>= number of workgroups of the combine launch]
+};
+
+// One combine launch: out[j] = LSE2 over p < P of part[p][j] (+ rowconst[j]),
+// then pot = out, shift = lw2 - out, optionally the error terms against the old
+// potential, optionally the once-per-iteration state advance.
+struct CombineArgs {
+    const double *part;       // [P][ld]
+    int32_t P, ld, len;
+    const double *rowconst;   // [len] or null
+    const double *lw2;        // [len] log2 weights of this side
+    const float *w;           // [len] weights of this side (error terms)
+    double *pot;              // [2][ld]
+    double *shift;            // [2][ld]
+    int32_t do_advance;       // 1: this is the g-update: also evaluate the error terms of Sec. 4.5 from
+                              //    the old and new F, and let the last workgroup advance the state
+    ErrSrc es;
+};
+
+// warm: bit 0 = start f from f_in / f64_in, bit 1 = start g from g_in / g64_in (else zero)
+hipError_t launch_init(hipStream_t st, const Pots &p, State *state, const float *f_in, const float *g_in,
+                       const double *f64_in, const double *g64_in, int warm);
+// out[t] = -pot[t] / s (potential in natural units, double precision)
+hipError_t launch_export(hipStream_t st, const double *pot, int len, double s, double *out);
+hipError_t launch_finalize(hipStream_t st, const Pots &p, State *state, float *f, float *g,
+                           double *f64_out, double *g64_out, void *result_dev, void *result_host);
+hipError_t launch_combine(hipStream_t st, const CombineArgs &a, const Ctl &c);
+hipError_t launch_advance(hipStream_t st, const ErrSrc &es, const Ctl &c);
+
+// Dense streaming kernels (any n, m).
+void dense_stream_plan(int n, int m, int *P, int *rows_per_panel);
+hipError_t launch_dense_row(hipStream_t st, const DenseArgs &a, const Ctl &c);
+hipError_t launch_dense_col(hipStream_t st, const DenseArgs &a, const Ctl &c);
+
+// Dense fused row-panel kernel (m limited by what a workgroup holds in registers).
+bool dense_fused_supported(int n, int m, const void *C);
+void dense_fused_plan(int n, int m, int *P);
+hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, int variant);
+int dense_fused_grid(int n, int m, int variant);
+
+// Point-cloud kernels.
+struct PointsArgs {
+    // rows side (plain coordinates, fp64) and columns side (coordinates pre-multiplied by 2s)
+    const double *rows;       // [nr][d]
+    const double *cols2s;     // [nc][d]
+    const double *colconst;   // [nc]  -s |col|^2
+    const double *colshift;   // [nc]  V (or U) of the current iterate
+    int32_t nr, nc, d;
+    double *part;             // [JS][ld] partial LSE values per row
+    int32_t JS, ld, cols_per_split;
+};
+void points_plan(int nr, int nc, int d, int *JS, int *cols_per_split);
+hipError_t launch_points_lse(hipStream_t st, const PointsArgs &a, const Ctl &c, int use_next_shift, int ld_shift);
+hipError_t launch_points_prep(hipStream_t st, const float *X, int n, int d, double s, double *plain,
+                              double *scaled, double *negsq);
+
+// Plan and cost.
+struct PlanArgs {
+    const float *C, *X, *Y;
+    const float *a, *b;
+    const float *f, *g;          // fp32 potentials, or
+    const double *f64, *g64;     // fp64 potentials (take precedence when non-null)
+    int32_t n, m, d;
+    double s;
+};
+hipError_t launch_plan(hipStream_t st, const PlanArgs &a, float *P, double *scratch, int nscratch);
+hipError_t launch_cost(hipStream_t st, const PlanArgs &a, double *cost_dev, double *scratch, int nscratch);
+int cost_scratch_len(int n, int m);
+
+}  // namespace fs

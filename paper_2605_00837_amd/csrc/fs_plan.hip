@@ -1,0 +1,117 @@
+// Plan (Eq. 5) and transport cost (last step of Alg. 1) from given potentials.
+//
+//   P_ij = a_i b_j exp((f_i + g_j - C_ij)/eps) = 2^( ri_i + cj_j - s C_ij ),
+//   ri_i = s f_i + log2 a_i,  cj_j = s g_j + log2 b_j,  s = log2(e)/eps.
+//
+// ri, cj are prepared once in fp64; the exponent is formed in fp64 and rounded
+// to fp32 only for v_exp_f32.  The cost is accumulated in fp64 per workgroup
+// and the per-workgroup partials are summed in index order by one workgroup.
+#include "fs_kernels.h"
+
+namespace fs {
+
+__global__ __launch_bounds__(256) void k_plan_prep(PlanArgs A, double *ri, double *cj) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t < A.n) {
+        const double f = A.f64 ? A.f64[t] : (double)A.f[t];
+        ri[t] = fma(A.s, f, log2_weight(A.a[t]));
+    }
+    if (t < A.m) {
+        const double g = A.g64 ? A.g64[t] : (double)A.g[t];
+        cj[t] = fma(A.s, g, log2_weight(A.b[t]));
+    }
+}
+
+__device__ __forceinline__ double cost_entry(const PlanArgs &A, int i, int j) {
+    if (A.C) return (double)A.C[(size_t)i * A.m + j];
+    double sq = 0.0;
+    for (int t = 0; t < A.d; ++t) {
+        const double df = (double)A.X[(size_t)i * A.d + t] - (double)A.Y[(size_t)j * A.d + t];
+        sq = fma(df, df, sq);
+    }
+    return sq;
+}
+
+// grid.x covers columns (256 per workgroup), grid.y strides over rows.
+template <bool WRITE_PLAN>
+__global__ __launch_bounds__(256) void k_plan_cost(PlanArgs A, const double *ri, const double *cj, float *P,
+                                                   double *partial) {
+    __shared__ double lds[256];
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const bool jok = j < A.m;
+    const double cjv = jok ? cj[j] : 0.0;
+    double acc = 0.0;
+    for (int i = blockIdx.y; i < A.n; i += gridDim.y) {
+        if (jok) {
+            const double cst = cost_entry(A, i, j);
+            const double e = ri[i] + cjv - A.s * cst;
+            const float pij = fast_exp2((float)e);
+            if (WRITE_PLAN) P[(size_t)i * A.m + j] = pij;
+            else if (pij > 0.0f) acc = fma(cst, (double)pij, acc);
+        }
+    }
+    if (!WRITE_PLAN) {
+        lds[threadIdx.x] = acc;
+        __syncthreads();
+        for (int w = 128; w >= 1; w >>= 1) {
+            if (threadIdx.x < w) lds[threadIdx.x] += lds[threadIdx.x + w];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) partial[(size_t)blockIdx.y * gridDim.x + blockIdx.x] = lds[0];
+    }
+}
+
+__global__ __launch_bounds__(256) void k_sum_partials(const double *partial, int count, double *out) {
+    __shared__ double lds[256];
+    double acc = 0.0;
+    for (int q = threadIdx.x; q < count; q += 256) acc += partial[q];
+    lds[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if (threadIdx.x < w) lds[threadIdx.x] += lds[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = lds[0];
+}
+
+static void plan_grid(int n, int m, dim3 *grid) {
+    const int gx = (m + 255) / 256;
+    int gy = (4096 + gx - 1) / gx;
+    if (gy > n) gy = n;
+    if (gy < 1) gy = 1;
+    if (gy > 65535) gy = 65535;
+    *grid = dim3(gx, gy);
+}
+
+int cost_scratch_len(int n, int m) {
+    dim3 g;
+    plan_grid(n, m, &g);
+    return n + m + (int)(g.x * g.y);          // ri, cj, partials
+}
+
+hipError_t launch_cost(hipStream_t st, const PlanArgs &a, double *cost_dev, double *scratch, int nscratch) {
+    dim3 grid;
+    plan_grid(a.n, a.m, &grid);
+    if (nscratch < a.n + a.m + (int)(grid.x * grid.y)) return hipErrorInvalidValue;
+    double *ri = scratch, *cj = scratch + a.n, *partial = scratch + a.n + a.m;
+    const int len = a.n > a.m ? a.n : a.m;
+    hipLaunchKernelGGL(k_plan_prep, dim3((len + 255) / 256), dim3(256), 0, st, a, ri, cj);
+    if (cost_dev) {
+        hipLaunchKernelGGL(k_plan_cost<false>, grid, dim3(256), 0, st, a, ri, cj, (float *)nullptr, partial);
+        hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, partial, (int)(grid.x * grid.y), cost_dev);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_plan(hipStream_t st, const PlanArgs &a, float *P, double *scratch, int nscratch) {
+    dim3 grid;
+    plan_grid(a.n, a.m, &grid);
+    if (nscratch < a.n + a.m) return hipErrorInvalidValue;
+    double *ri = scratch, *cj = scratch + a.n;
+    const int len = a.n > a.m ? a.n : a.m;
+    hipLaunchKernelGGL(k_plan_prep, dim3((len + 255) / 256), dim3(256), 0, st, a, ri, cj);
+    hipLaunchKernelGGL(k_plan_cost<true>, grid, dim3(256), 0, st, a, ri, cj, P, (double *)nullptr);
+    return hipGetLastError();
+}
+
+}  // namespace fs

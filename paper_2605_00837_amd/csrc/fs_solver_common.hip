@@ -1,0 +1,211 @@
+// Kernels every solve uses, whatever the cost representation: initialisation of
+// the log-weights and potentials (Alg. 1, first two steps), the combine of
+// partial LogSumExp values, the once-per-iteration state advance with the
+// stopping test (Alg. 1, check every c iterations) and the final conversion of
+// the scaled fp64 potentials to the caller's fp32 f, g.
+#include "fs_kernels.h"
+
+namespace fs {
+
+// ---------------------------------------------------------------- init
+// la2 = log2 a, lb2 = log2 b (Alg. 1 "precompute"); F = G = 0 (Eqs. 6-7) or the
+// caller's warm start; U = la2 - F, V = lb2 - G; state cleared.
+__global__ __launch_bounds__(256) void k_init(Pots p, State *state, const float *f_in,
+                                              const float *g_in, const double *f64_in, const double *g64_in,
+                                              int warm) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t == 0) {
+        state->k = 0; state->done = 0; state->iters = 0; state->converged = 0; state->nonfinite = 0;
+        state->ticket = 0; state->err_valid = 0; state->pad0 = 0;
+        state->err = __builtin_nan("");
+    }
+    double *la2 = const_cast<double *>(p.la2);
+    double *lb2 = const_cast<double *>(p.lb2);
+    if (t < p.n) {
+        const double la = log2_weight(p.a[t]);
+        double F = 0.0;
+        if (warm & 1) F = -p.s * (f64_in ? f64_in[t] : (double)f_in[t]);
+        la2[t] = la;
+        p.F[t] = F;
+        p.U[t] = la - F;
+        p.F[p.n_ld + t] = F;
+        p.U[p.n_ld + t] = la - F;
+    }
+    if (t < p.m) {
+        const double lb = log2_weight(p.b[t]);
+        double G = 0.0;
+        if (warm & 2) G = -p.s * (g64_in ? g64_in[t] : (double)g_in[t]);
+        lb2[t] = lb;
+        p.G[t] = G;
+        p.V[t] = lb - G;
+        p.G[p.m_ld + t] = G;
+        p.V[p.m_ld + t] = lb - G;
+    }
+}
+
+hipError_t launch_init(hipStream_t st, const Pots &p, State *state, const float *f_in, const float *g_in,
+                       const double *f64_in, const double *g64_in, int warm) {
+    const int len = p.n > p.m ? p.n : p.m;
+    hipLaunchKernelGGL(k_init, dim3((len + 255) / 256), dim3(256), 0, st, p, state, f_in, g_in, f64_in,
+                       g64_in, warm);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_export(const double *pot, int len, double s, double *out) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t < len) out[t] = -pot[t] / s;
+}
+
+hipError_t launch_export(hipStream_t st, const double *pot, int len, double s, double *out) {
+    hipLaunchKernelGGL(k_export, dim3((len + 255) / 256), dim3(256), 0, st, pot, len, s, out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- finalize
+// f = -F/s, g = -G/s from the buffer of the returned iterate; flags non-finite values.
+__global__ __launch_bounds__(256) void k_finalize(Pots p, State *state, float *f, float *g, double *f64_out,
+                                                  double *g64_out) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int it = state->done ? state->iters : state->k;
+    const int buf = it & 1;
+    const double inv = -1.0 / p.s;
+    bool bad = false;
+    if (t < p.n) {
+        const double v = p.F[buf * p.n_ld + t] * inv;
+        f[t] = (float)v;
+        if (f64_out) f64_out[t] = v;
+        bad |= !(fabs(v) <= 1.7e308);
+    }
+    if (t < p.m) {
+        const double v = p.G[buf * p.m_ld + t] * inv;
+        g[t] = (float)v;
+        if (g64_out) g64_out[t] = v;
+        bad |= !(fabs(v) <= 1.7e308);
+    }
+    if (bad) atomicOr(&state->nonfinite, 1);
+}
+
+struct ResultRecord { int32_t iters, converged, nonfinite; float marginal_err; };
+
+__global__ void k_result(State *state, ResultRecord *dev, ResultRecord *host) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    ResultRecord r;
+    r.iters = state->done ? state->iters : state->k;
+    r.converged = state->done ? state->converged : 0;
+    r.nonfinite = state->nonfinite;
+    r.marginal_err = (state->done && state->err_valid) ? (float)state->err : __builtin_nanf("");
+    if (!state->done) { state->iters = r.iters; state->done = 1; }
+    if (dev) *dev = r;
+    if (host) {
+        *host = r;
+        __threadfence_system();
+    }
+}
+
+hipError_t launch_finalize(hipStream_t st, const Pots &p, State *state, float *f, float *g, double *f64_out,
+                           double *g64_out, void *result_dev, void *result_host) {
+    const int len = p.n > p.m ? p.n : p.m;
+    hipLaunchKernelGGL(k_finalize, dim3((len + 255) / 256), dim3(256), 0, st, p, state, f, g, f64_out, g64_out);
+    hipLaunchKernelGGL(k_result, dim3(1), dim3(64), 0, st, state, (ResultRecord *)result_dev,
+                       (ResultRecord *)result_host);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- error terms + advance
+// Sum over 256 threads in a fixed order (tree in LDS).
+__device__ __forceinline__ double block_sum_256(double v, double *lds) {
+    const int t = threadIdx.x;
+    __syncthreads();
+    lds[t] = v;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if (t < w) lds[t] += lds[t + w];
+        __syncthreads();
+    }
+    return lds[0];
+}
+
+// Error terms a_i |2^(Fnew_i - Fold_i) - 1| of the rows first, first+stride, ... (fp64, expm1 for
+// the small differences near convergence).
+__device__ __forceinline__ double err_terms(const ErrSrc &es, int cur, int first, int stride) {
+    const double *Fo = es.F + (size_t)cur * es.n_ld;
+    const double *Fn = es.F + (size_t)(cur ^ 1) * es.n_ld;
+    double acc = 0.0;
+    for (int i = first; i < es.n; i += stride) {
+        const float a = es.a[i];
+        if (a > 0.0f) acc += (double)a * fabs(expm1((Fn[i] - Fo[i]) * 0.6931471805599453094));
+    }
+    return acc;
+}
+
+// Trailing pass: one workgroup evaluates err of the last iterate and closes the solve.
+__global__ __launch_bounds__(256) void k_advance(ErrSrc es, Ctl c) {
+    __shared__ double lds[256];
+    int k;
+    if (!launch_active(c, k)) return;
+    const double err = block_sum_256(err_terms(es, k & 1, threadIdx.x, 256), lds);
+    if (threadIdx.x == 0) advance_state(c, k, err);
+}
+
+hipError_t launch_advance(hipStream_t st, const ErrSrc &es, const Ctl &c) {
+    hipLaunchKernelGGL(k_advance, dim3(1), dim3(256), 0, st, es, c);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- combine
+// One thread per entry j: out_j = LSE2_p part[p][j] (+ rowconst_j).  Two passes
+// over the P partials (max, then sum), as in Eq. 8.  The g-update's combine also
+// evaluates the error terms (spread over all its threads; per-workgroup sums are
+// added up in index order by whichever workgroup finishes last) and advances
+// the iteration state.
+__global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
+    __shared__ double lds[256];
+    __shared__ int s_last;
+    int k;
+    if (!launch_active(c, k)) return;
+    const int cur = k & 1, nxt = cur ^ 1;
+    const int t = threadIdx.x;
+    const int j = blockIdx.x * 256 + t;
+    if (j < A.len) {
+        double Lm = -__builtin_huge_val();
+        for (int p = 0; p < A.P; ++p) Lm = dmax(Lm, A.part[(size_t)p * A.ld + j]);
+        double out;
+        if (Lm > -1.0e299) {
+            float s = 0.0f;
+            for (int p = 0; p < A.P; ++p) s += fast_exp2((float)(A.part[(size_t)p * A.ld + j] - Lm));
+            out = Lm + (double)fast_log2(s);
+        } else {
+            out = Lm < 0 ? -__builtin_huge_val() : Lm;     // every term was -inf (or NaN came through)
+        }
+        if (A.rowconst) out += A.rowconst[j];
+        A.pot[(size_t)nxt * A.ld + j] = out;
+        A.shift[(size_t)nxt * A.ld + j] = A.lw2[j] - out;
+    }
+    if (A.do_advance) {
+        const double part = block_sum_256(err_terms(A.es, cur, j, gridDim.x * 256), lds);
+        if (t == 0) {
+            A.es.errpart[blockIdx.x] = part;
+            __threadfence();
+            const unsigned prev = atomicAdd(&c.st->ticket, 1u);
+            s_last = (prev == gridDim.x - 1) ? 1 : 0;
+        }
+        __syncthreads();
+        if (s_last) {
+            __threadfence();
+            double acc = 0.0;
+            for (int q = t; q < (int)gridDim.x; q += 256) acc += __hip_atomic_load(A.es.errpart + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const double err = block_sum_256(acc, lds);
+            if (t == 0) {
+                c.st->ticket = 0;
+                advance_state(c, k, err);
+            }
+        }
+    }
+}
+
+hipError_t launch_combine(hipStream_t st, const CombineArgs &a, const Ctl &c) {
+    hipLaunchKernelGGL(k_combine, dim3((a.len + 255) / 256), dim3(256), 0, st, a, c);
+    return hipGetLastError();
+}
+
+}  // namespace fs

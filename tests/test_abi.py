@@ -1,0 +1,78 @@
+"""The C-ABI library builds for gfx950, loads without a GPU, and exports every
+symbol that include/fastsinkhorn.h declares (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fastsinkhorn.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2605_00837_amd import build
+    if build.is_stale():
+        build.build(force=True)
+    return ctypes.CDLL(build.LIB)
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fs_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_north_star_entry_points():
+    syms = declared_symbols()
+    for name in ("fs_sinkhorn_dense", "fs_sinkhorn_points", "fs_plan", "fs_cost"):
+        assert name in syms
+
+
+def test_every_declared_symbol_is_exported(lib):
+    syms = declared_symbols()
+    assert len(syms) >= 10
+    for name in syms:
+        assert hasattr(lib, name), f"{name} declared in the header but not exported"
+
+
+def test_host_only_calls(lib):
+    lib.fs_version.restype = ctypes.c_char_p
+    lib.fs_last_error.restype = ctypes.c_char_p
+    lib.fs_workspace_bytes.restype = ctypes.c_size_t
+    lib.fs_workspace_bytes.argtypes = [ctypes.c_int] * 3
+    assert lib.fs_version().startswith(b"fastsinkhorn")
+    assert lib.fs_last_error() is not None
+    dense = lib.fs_workspace_bytes(8192, 8192, 0)
+    # potentials + log-weights + column partials: tens of MiB, far below the 256 MiB cost matrix
+    assert 1 << 20 < dense < 64 << 20
+    assert lib.fs_workspace_bytes(65536, 65536, 3) > 0
+    assert lib.fs_workspace_bytes(0, 5, 0) == 0 and lib.fs_workspace_bytes(5, 5, 65) == 0
+    assert dense % 256 == 0
+
+
+def test_binding_mirrors_the_header():
+    """Struct layouts and names of the Python binding follow the header (parsed, not imported:
+    importing the binding needs torch with a GPU only at call time, so importing is fine here too)."""
+    from paper_2605_00837_amd import binding
+    assert ctypes.sizeof(binding.fs_result) == 16
+    assert ctypes.sizeof(binding.fs_options) == 24 + 5 * 8 + 8
+    for name in declared_symbols():
+        assert name in binding.EXPORTED and hasattr(binding, name), name
+
+
+def test_argument_validation_without_gpu(lib):
+    """Scalar validation happens before any HIP call, so it can be exercised on a GPU-less host."""
+    lib.fs_sinkhorn_dense.restype = ctypes.c_int
+    lib.fs_sinkhorn_dense.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int, ctypes.c_int, ctypes.c_float,
+                                                              ctypes.c_int, ctypes.c_float] + [ctypes.c_void_p] * 3
+    lib.fs_last_error.restype = ctypes.c_char_p
+    fake = ctypes.c_void_p(256)
+    assert lib.fs_sinkhorn_dense(fake, fake, fake, 0, 4, 0.1, 3, 0.0, fake, fake, None) == -1
+    assert b"n and m" in lib.fs_last_error()
+    assert lib.fs_sinkhorn_dense(fake, fake, fake, 4, 4, 0.0, 3, 0.0, fake, fake, None) == -1
+    assert b"eps" in lib.fs_last_error()
+    assert lib.fs_sinkhorn_dense(fake, fake, fake, 4, 4, 0.1, -2, 0.0, fake, fake, None) == -1
+    assert lib.fs_sinkhorn_dense(None, fake, fake, 4, 4, 0.1, 3, 0.0, fake, fake, None) == -1
+    assert lib.fs_sinkhorn_dense(fake, fake, fake, 4, 4, 0.1, 3, 0.0, None, fake, None) == -1

@@ -1,0 +1,293 @@
+"""GPU parity: the HIP path (through the C ABI binding) against the CPU oracle,
+element by element on the same seeded inputs.
+
+Tolerances (north-star): potentials max|df|/eps <= 1e-3 for the fp32 outputs,
+plan-marginal L1 difference <= 1e-5, transport-cost relative error <= 1e-4.
+The library carries the potentials in fp64 internally and can hand them out in
+fp64; those are held to a much tighter bound (1e-5 in units of eps; the
+difference to the oracle is then only the fp32 exp2/log2 and summation noise).
+"""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2605_00837_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-3       # max |df| / eps, fp32 outputs
+TOL_F64 = 2e-5       # max |df| / eps, fp64 outputs
+TOL_MARG = 1e-5      # L1 difference of plan marginals
+TOL_COST = 1e-4      # relative
+
+
+@pytest.fixture(scope="module")
+def fs():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_00837_amd import binding
+    return binding
+
+
+def dev(x, dtype=None):
+    import torch
+    if x is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def to_dev(w):
+    return dict(C=dev(w.C), X=dev(w.X), Y=dev(w.Y)), dev(w.a), dev(w.b)
+
+
+def pot_err(x_gpu, x_ref, eps):
+    return float(np.max(np.abs(np.asarray(x_gpu, dtype=np.float64) - x_ref)) / eps)
+
+
+# ------------------------------------------------------------------ kernel level: one half-step
+DENSE_SHAPES = [(1, 1), (2, 3), (3, 2), (63, 65), (64, 64), (65, 63), (255, 257), (257, 256), (100, 1028),
+                (300, 1100), (37, 4100), (515, 2048)]
+
+
+@pytest.mark.parametrize("n,m", DENSE_SHAPES)
+def test_dense_half_steps(fs, oracle, n, m):
+    import torch
+    w = W.random_dense(n, m, seed=1000 + n * 7 + m, cmax=3.0, eps=0.02)
+    rng = np.random.default_rng(n * 31 + m)
+    g0 = rng.standard_normal(m) * 0.3
+    f0 = rng.standard_normal(n) * 0.3
+    geo, a, b = to_dev(w)
+    f_gpu = fs.fs_update_f(a, b, w.eps, dev(g0), **geo).cpu().numpy()
+    g_gpu = fs.fs_update_g(a, b, w.eps, dev(f0), **geo).cpu().numpy()
+    f_ref = oracle.update_f(w.a, w.b, w.eps, g0, C=w.C)
+    g_ref = oracle.update_g(w.a, w.b, w.eps, f0, C=w.C)
+    assert pot_err(f_gpu, f_ref, w.eps) < TOL_F64
+    assert pot_err(g_gpu, g_ref, w.eps) < TOL_F64
+
+
+@pytest.mark.parametrize("n,m,d", [(1, 1, 1), (5, 7, 2), (257, 300, 3), (600, 513, 3), (300, 257, 4),
+                                   (129, 200, 5), (70, 90, 17), (40, 33, 64)])
+def test_points_half_steps(fs, oracle, n, m, d):
+    w = W.random_points(n, m, d, seed=2000 + n + m + d, eps=0.02)
+    rng = np.random.default_rng(n * 31 + m + d)
+    g0 = rng.standard_normal(m) * 0.3
+    f0 = rng.standard_normal(n) * 0.3
+    geo, a, b = to_dev(w)
+    f_gpu = fs.fs_update_f(a, b, w.eps, dev(g0), **geo).cpu().numpy()
+    g_gpu = fs.fs_update_g(a, b, w.eps, dev(f0), **geo).cpu().numpy()
+    f_ref = oracle.update_f(w.a, w.b, w.eps, g0, X=w.X, Y=w.Y)
+    g_ref = oracle.update_g(w.a, w.b, w.eps, f0, X=w.X, Y=w.Y)
+    assert pot_err(f_gpu, f_ref, w.eps) < TOL_F64
+    assert pot_err(g_gpu, g_ref, w.eps) < TOL_F64
+
+
+# ------------------------------------------------------------------ full solves, every kernel path
+def _solve_and_compare(fs, oracle, w, iters, eps=None, **kw):
+    eps = w.eps if eps is None else eps
+    geo, a, b = to_dev(w)
+    r = fs.fs_sinkhorn_solve(a, b, eps, iters, 0.0, want_f64=True, **geo, **kw)
+    ref = oracle.solve(w.a, w.b, eps, iters, C=w.C, X=w.X, Y=w.Y)
+    assert r["iters"] == iters and not r["nonfinite"]
+    e64 = max(pot_err(r["f64"].cpu().numpy(), ref["f"], eps), pot_err(r["g64"].cpu().numpy(), ref["g"], eps))
+    e32 = max(pot_err(r["f"].cpu().numpy(), ref["f"], eps), pot_err(r["g"].cpu().numpy(), ref["g"], eps))
+    return r, ref, e64, e32
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("n,m", [(1, 4), (4, 4), (130, 64), (67, 1024), (517, 1028), (300, 4096), (90, 8192)])
+def test_dense_solve_modes(fs, oracle, mode, n, m):
+    w = W.random_dense(n, m, seed=3000 + n + m, cmax=2.0, eps=0.03)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 25, kernel_mode=mode)
+    assert e64 < TOL_F64 and e32 < TOL_F32
+    # the trailing pass reports err of the last iterate
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+def test_fused_variants_full_width(fs, oracle, variant):
+    w = W.random_dense(70, 8192, seed=77, cmax=2.0, eps=0.03)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 12, kernel_mode=2, fused_variant=variant)
+    assert e64 < TOL_F64 and e32 < TOL_F32
+
+
+def test_streaming_rejects_nothing_and_fused_rejects_odd_m(fs):
+    w = W.random_dense(8, 10, seed=5)
+    geo, a, b = to_dev(w)
+    fs.fs_sinkhorn_solve(a, b, w.eps, 3, 0.0, kernel_mode=1, **geo)
+    w2 = W.random_dense(8, 9, seed=5)
+    geo2, a2, b2 = to_dev(w2)
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_sinkhorn_solve(a2, b2, w2.eps, 3, 0.0, kernel_mode=2, **geo2)
+    assert e.value.status == fs.FS_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("n,m,d", [(300, 257, 3), (1000, 777, 3), (64, 64, 2), (129, 200, 5), (50, 60, 11)])
+def test_points_solve(fs, oracle, n, m, d):
+    w = W.random_points(n, m, d, seed=4000 + n + m + d, eps=0.02)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 30)
+    assert e64 < TOL_F64 and e32 < TOL_F32
+
+
+# ------------------------------------------------------------------ stopping rule, history, resume
+@pytest.mark.parametrize("kind,mode", [("dense", 1), ("dense", 2), ("points", 0)])
+def test_stopping_rule_and_history(fs, oracle, kind, mode):
+    import torch
+    w = W.random_dense(96, 128, seed=9, eps=0.05) if kind == "dense" else W.random_points(96, 120, 3, seed=9, eps=0.05)
+    geo, a, b = to_dev(w)
+    tol, K = 1e-5, 400        # well above the ~1e-7 fp32 noise floor of the device-side error
+    full = oracle.solve(w.a, w.b, w.eps, K, C=w.C, X=w.X, Y=w.Y, err_every_iter=True)
+    eh = full["err_hist"]
+    for c in (1, 7, 10):
+        hist = torch.full((K,), float("nan"), dtype=torch.float32, device="cuda")
+        r = fs.fs_sinkhorn_solve(a, b, w.eps, K, tol, want_f64=True, check_every=c, kernel_mode=mode,
+                                 err_history=hist, **geo)
+        ks = [k for k in range(c, K + 1, c) if eh[k - 1] < tol]
+        assert r["converged"] and r["iters"] == ks[0]
+        ref = oracle.solve(w.a, w.b, w.eps, r["iters"], C=w.C, X=w.X, Y=w.Y)
+        assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+        assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+        assert abs(r["marginal_err"] - eh[r["iters"] - 1]) <= 1e-3 * eh[r["iters"] - 1] + 5e-7
+        h = hist.cpu().numpy()[:r["iters"]]
+        assert np.all(np.isfinite(h))
+        assert np.allclose(h, eh[:r["iters"]], rtol=1e-3, atol=5e-7)
+    # not reached: runs to max_iter, reports not converged, err of the last iterate
+    r = fs.fs_sinkhorn_solve(a, b, w.eps, 15, 1e-30, check_every=5, kernel_mode=mode, **geo)
+    assert r["iters"] == 15 and not r["converged"]
+    assert abs(r["marginal_err"] - eh[14]) <= 1e-3 * eh[14] + 5e-7
+    # max_iter = 0 returns the start
+    r0 = fs.fs_sinkhorn_solve(a, b, w.eps, 0, 0.0, kernel_mode=mode, **geo)
+    assert r0["iters"] == 0 and float(r0["f"].abs().max()) == 0.0 and float(r0["g"].abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("kind,mode", [("dense", 1), ("dense", 2), ("points", 0)])
+def test_warm_start_resume_is_bit_identical(fs, kind, mode):
+    import torch
+    w = W.random_dense(80, 256, seed=19, eps=0.05) if kind == "dense" else W.random_points(80, 250, 3, seed=19, eps=0.05)
+    geo, a, b = to_dev(w)
+    r1 = fs.fs_sinkhorn_solve(a, b, w.eps, 13, 0.0, want_f64=True, kernel_mode=mode, **geo)
+    r2 = fs.fs_sinkhorn_solve(a, b, w.eps, 9, 0.0, want_f64=True, kernel_mode=mode, warm_start=True,
+                              f64_in=r1["f64"], g64_in=r1["g64"], **geo)
+    r3 = fs.fs_sinkhorn_solve(a, b, w.eps, 22, 0.0, want_f64=True, kernel_mode=mode, **geo)
+    assert torch.equal(r2["f64"], r3["f64"]) and torch.equal(r2["g64"], r3["g64"])
+    # run-to-run determinism
+    r4 = fs.fs_sinkhorn_solve(a, b, w.eps, 22, 0.0, want_f64=True, kernel_mode=mode, **geo)
+    assert torch.equal(r4["f64"], r3["f64"]) and torch.equal(r4["g"], r3["g"])
+
+
+def test_blocking_and_async_entry_points_agree(fs):
+    import torch
+    w = W.random_dense(200, 512, seed=23, eps=0.05)
+    geo, a, b = to_dev(w)
+    f1, g1, it1 = fs.fs_sinkhorn_dense(geo["C"], a, b, w.eps, 300, 1e-6)
+    h = fs.fs_sinkhorn_dense_ex(geo["C"], a, b, w.eps, 300, 1e-6)
+    res = h.result()
+    assert res["iters"] == it1 and res["converged"]
+    assert torch.equal(h.f, f1) and torch.equal(h.g, g1)
+    wp = W.random_points(150, 170, 3, seed=24, eps=0.05)
+    geop, ap, bp = to_dev(wp)
+    f2, g2, it2 = fs.fs_sinkhorn_points(geop["X"], geop["Y"], ap, bp, wp.eps, 300, 1e-6)
+    hp = fs.fs_sinkhorn_points_ex(geop["X"], geop["Y"], ap, bp, wp.eps, 300, 1e-6)
+    resp = hp.result()
+    assert resp["iters"] == it2 and torch.equal(hp.f, f2) and torch.equal(hp.g, g2)
+    assert it2 % 10 == 0 and it1 % 10 == 0          # default check interval c = 10
+
+
+# ------------------------------------------------------------------ plan and cost
+@pytest.mark.parametrize("kind", ["dense", "points"])
+def test_plan_and_cost(fs, oracle, kind):
+    w = W.random_dense(130, 300, seed=31, eps=0.04) if kind == "dense" else W.random_points(130, 257, 3, seed=31, eps=0.04)
+    geo, a, b = to_dev(w)
+    ref = oracle.solve(w.a, w.b, w.eps, 40, C=w.C, X=w.X, Y=w.Y)
+    f32, g32 = ref["f"].astype(np.float32), ref["g"].astype(np.float32)
+    P = fs.fs_plan(a, b, w.eps, dev(f32), dev(g32), **geo).cpu().numpy().astype(np.float64)
+    P_ref = oracle.plan(w.a, w.b, w.eps, f32.astype(np.float64), g32.astype(np.float64), C=w.C, X=w.X, Y=w.Y)
+    assert np.max(np.abs(P - P_ref) / (P_ref + 1e-30 + 1e-6 * P_ref.max())) < 2e-5
+    c = float(fs.fs_cost(a, b, w.eps, dev(f32), dev(g32), **geo).cpu()[0])
+    c_ref = float(oracle.cost(w.a, w.b, w.eps, f32.astype(np.float64), g32.astype(np.float64), C=w.C, X=w.X, Y=w.Y))
+    assert abs(c - c_ref) <= 1e-5 * abs(c_ref)
+    P64 = fs.fs_plan(a, b, w.eps, dev(ref["f"]), dev(ref["g"]), **geo).cpu().numpy().astype(np.float64)
+    P64_ref = oracle.plan(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C, X=w.X, Y=w.Y)
+    assert np.max(np.abs(P64 - P64_ref) / (P64_ref + 1e-30 + 1e-6 * P64_ref.max())) < 2e-5
+    c64 = float(fs.fs_cost(a, b, w.eps, dev(ref["f"]), dev(ref["g"]), **geo).cpu()[0])
+    assert abs(c64 - float(oracle.cost(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C, X=w.X, Y=w.Y))) <= 1e-5 * abs(c_ref)
+
+
+# ------------------------------------------------------------------ closed form at size (independent of the oracle)
+@pytest.mark.parametrize("mode", [1, 2])
+def test_separable_cost_closed_form_large(fs, mode):
+    """C_ij = u_i + v_j (exactly representable) => after ONE iteration f = u + kappa, g = v - kappa - eps log(sum a),
+    and every later iteration is a fixed point of the plan (err = |sum a - sum b| only)."""
+    import torch
+    n, m, eps = 2048, 4096, float(np.float32(0.01))
+    rng = np.random.default_rng(5)
+    u = (rng.integers(0, 1024, n) / 256.0)
+    v = (rng.integers(0, 1024, m) / 256.0)
+    C = (u[:, None] + v[None, :]).astype(np.float32)
+    assert np.array_equal(C.astype(np.float64), u[:, None] + v[None, :])
+    w = W.random_dense(8, 8, seed=1)
+    a = W._dirichlet(rng, n, 1.0)
+    b = W._dirichlet(rng, m, 1.0)
+    a64, b64 = a.astype(np.float64), b.astype(np.float64)
+    r = fs.fs_sinkhorn_solve(dev(a), dev(b), eps, 1, 0.0, C=dev(C), want_f64=True, kernel_mode=mode)
+    vm = (-v / eps).max()
+    kappa = -eps * (vm + np.log(np.sum(b64 * np.exp(-v / eps - vm))))
+    f_ref = u + kappa
+    g_ref = v - kappa - eps * np.log(a64.sum())
+    assert pot_err(r["f64"].cpu().numpy(), f_ref, eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), g_ref, eps) < TOL_F64
+    assert r["marginal_err"] < 1e-6
+    r5 = fs.fs_sinkhorn_solve(dev(a), dev(b), eps, 5, 0.0, C=dev(C), want_f64=True, kernel_mode=mode)
+    fsum = (r5["f64"].cpu().numpy()[:, None] + r5["g64"].cpu().numpy()[None, :] - C.astype(np.float64))
+    assert np.ptp(fsum) / eps < 1e-4          # f_i + g_j - C_ij is one constant: P = a x b up to normalisation
+
+
+# ------------------------------------------------------------------ degenerate inputs and argument errors
+def test_zero_weights_and_singletons(fs, oracle):
+    w = W.random_dense(40, 64, seed=41, eps=0.05)
+    a = w.a.copy(); a[7] = 0.0
+    b = w.b.copy(); b[11] = 0.0
+    for mode in (1, 2):
+        r = fs.fs_sinkhorn_solve(dev(a), dev(b), w.eps, 30, 0.0, C=dev(w.C), want_f64=True, kernel_mode=mode)
+        ref = oracle.solve(a, b, w.eps, 30, C=w.C)
+        assert not r["nonfinite"]
+        assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+        assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+    one = np.ones(1, dtype=np.float32)
+    C11 = np.array([[0.7]], dtype=np.float32)
+    r = fs.fs_sinkhorn_solve(dev(one), dev(one), 0.1, 3, 0.0, C=dev(C11), want_f64=True)
+    ref = oracle.solve(one, one, float(np.float32(0.1)), 3, C=C11)
+    assert pot_err(r["f64"].cpu().numpy(), ref["f"], 0.1) < TOL_F64
+
+
+def test_nonfinite_cost_is_flagged_not_fatal(fs):
+    w = W.random_dense(32, 64, seed=43, eps=0.05)
+    C = w.C.copy(); C[3, 5] = np.nan
+    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, 5, 1e-9, C=dev(C), kernel_mode=1)
+    assert r["nonfinite"] and r["iters"] == 5 and not r["converged"]
+
+
+def test_argument_errors(fs):
+    import torch
+    w = W.random_dense(8, 8, seed=2)
+    geo, a, b = to_dev(w)
+    C = geo["C"]
+    for kw in (dict(eps=0.0), dict(eps=-1.0), dict(eps=float("nan")), dict(eps=float("inf")), dict(max_iter=-1)):
+        args = dict(eps=w.eps, max_iter=3)
+        args.update(kw)
+        with pytest.raises(fs.FsError) as e:
+            fs.fs_sinkhorn_dense(C, a, b, args["eps"], args["max_iter"], 0.0)
+        assert e.value.status == fs.FS_ERR_INVALID_ARG and fs.fs_last_error()
+    X = torch.zeros((8, 65), device="cuda")
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_sinkhorn_points(X, X, a, b, 0.1, 3, 0.0)
+    assert e.value.status == fs.FS_ERR_INVALID_ARG
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(fs.FsError) as e:
+        fs.fs_sinkhorn_dense_ex(C, a, b, w.eps, 3, 0.0, workspace=small)
+    assert e.value.status == fs.FS_ERR_WORKSPACE
