@@ -70,10 +70,14 @@ def _load():
     lib.fs_sinkhorn_points_ex.restype = ci
     lib.fs_sinkhorn_points_ex.argtypes = [vp, vp, ci, vp, vp, ci, ci, cf, ci, cf, vp, vp, vp,
                                           ctypes.POINTER(fs_options), vp, ctypes.c_size_t, vp]
-    for name in ("fs_plan", "fs_cost", "fs_plan_f64", "fs_cost_f64", "fs_update_f", "fs_update_g"):
+    for name in ("fs_plan", "fs_cost", "fs_plan_f64", "fs_cost_f64"):
         fn = getattr(lib, name)
         fn.restype = ci
         fn.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, vp, vp, vp, vp]
+    for name in ("fs_update_f", "fs_update_g"):
+        fn = getattr(lib, name)
+        fn.restype = ci
+        fn.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, vp, vp, vp]
     return lib
 
 

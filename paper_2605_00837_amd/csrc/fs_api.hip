@@ -87,7 +87,7 @@ Layout make_layout(int n, int m, int d) {
         L.o_Ys = take(sizeof(double) * (size_t)m * d);
         L.o_cy = take(sizeof(double) * L.m_ld);
     }
-    L.o_err = take(sizeof(double) * (size_t)((m + 255) / 256));      // one per workgroup of the g-combine
+    L.o_err = take(sizeof(double) * (size_t)((m + 63) / 64));        // one per workgroup of the g-combine
     L.total = off;
     return L;
 }

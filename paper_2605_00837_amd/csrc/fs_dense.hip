@@ -98,7 +98,10 @@ __global__ __launch_bounds__(kStreamT) void k_col_stream(DenseArgs A, Ctl c) {
     const Pots &p = A.p;
     const int j0 = (blockIdx.x * kStreamT + threadIdx.x) * VEC;
     if (j0 >= p.m) return;                       // no cross-lane work below
-    const int r0 = blockIdx.y * A.rows_per_panel;
+    // panels are walked from the bottom of C upwards: the row pass that ran just before streamed C
+    // top to bottom, so the rows still resident in the last-level cache are visited first
+    const int panel = (int)gridDim.y - 1 - (int)blockIdx.y;
+    const int r0 = panel * A.rows_per_panel;
     const int r1 = min(p.n, r0 + A.rows_per_panel);
     const double *U = p.U + (size_t)nxt * p.n_ld;     // the new f of this iteration (Gauss-Seidel order)
     const double ns = -p.s;
@@ -128,7 +131,7 @@ __global__ __launch_bounds__(kStreamT) void k_col_stream(DenseArgs A, Ctl c) {
         for (int e = 0; e < VEC; ++e) acc[e].template add<RC>(x[e]);
     }
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) A.colpart[(size_t)blockIdx.y * p.m_ld + j0 + e] = acc[e].value();
+    for (int e = 0; e < VEC; ++e) A.colpart[(size_t)panel * p.m_ld + j0 + e] = acc[e].value();
 }
 
 static bool vec4_ok(const DenseArgs &a) {
@@ -201,7 +204,11 @@ __global__ __launch_bounds__(T) void k_fused(DenseArgs A, Ctl c) {
 
     const int npanels = (p.n + R - 1) / R;
     int par = 0;
-    for (int pn = blockIdx.x; pn < npanels; pn += gridDim.x, par ^= 1) {
+    // odd iterations walk the panels from the bottom up: what the previous iteration read last is
+    // still in the last-level cache and is read first
+    const bool rev = (k & 1) != 0;
+    for (int pq = blockIdx.x; pq < npanels; pq += gridDim.x, par ^= 1) {
+        const int pn = rev ? npanels - 1 - pq : pq;
         const int i0 = pn * R;
         float cv[R][Q][4];
 #pragma unroll

@@ -153,36 +153,51 @@ hipError_t launch_advance(hipStream_t st, const ErrSrc &es, const Ctl &c) {
 }
 
 // ---------------------------------------------------------------- combine
-// One thread per entry j: out_j = LSE2_p part[p][j] (+ rowconst_j).  Two passes
-// over the P partials (max, then sum), as in Eq. 8.  The g-update's combine also
-// evaluates the error terms (spread over all its threads; per-workgroup sums are
-// added up in index order by whichever workgroup finishes last) and advances
-// the iteration state.
+// out_j = LSE2_p part[p][j] (+ rowconst_j).  A workgroup of 4 waves owns 64
+// adjacent entries; wave w folds the partial sets p = w, w+4, ... online (each
+// read is one coalesced 512-byte row segment, 8 independent loads in flight),
+// the four wave results meet in LDS.  The g-update's combine also evaluates
+// the error terms (spread over all its threads; per-workgroup sums are added
+// up in index order by whichever workgroup finishes last) and advances the
+// iteration state.
 __global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
     __shared__ double lds[256];
+    __shared__ double sM[4][64];
+    __shared__ float sS[4][64];
     __shared__ int s_last;
     int k;
     if (!launch_active(c, k)) return;
     const int cur = k & 1, nxt = cur ^ 1;
-    const int t = threadIdx.x;
-    const int j = blockIdx.x * 256 + t;
-    if (j < A.len) {
-        double Lm = -__builtin_huge_val();
-        for (int p = 0; p < A.P; ++p) Lm = dmax(Lm, A.part[(size_t)p * A.ld + j]);
-        double out;
-        if (Lm > -1.0e299) {
-            float s = 0.0f;
-            for (int p = 0; p < A.P; ++p) s += fast_exp2((float)(A.part[(size_t)p * A.ld + j] - Lm));
-            out = Lm + (double)fast_log2(s);
-        } else {
-            out = Lm < 0 ? -__builtin_huge_val() : Lm;     // every term was -inf (or NaN came through)
+    const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+    const int j = blockIdx.x * 64 + lane;
+    const bool jok = j < A.len;
+    Lse acc; acc.init();
+    if (jok) {
+        int p = wave;
+        for (; p + 28 < A.P; p += 32) {
+            double x[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) x[q] = A.part[(size_t)(p + 4 * q) * A.ld + j];
+            acc.add<8>(x);
         }
+        for (; p < A.P; p += 4) {
+            double x[1] = {A.part[(size_t)p * A.ld + j]};
+            acc.add<1>(x);
+        }
+    }
+    sM[wave][lane] = acc.M;
+    sS[wave][lane] = acc.s;
+    __syncthreads();
+    if (wave == 0 && jok) {
+#pragma unroll
+        for (int w = 1; w < 4; ++w) acc.merge(sM[w][lane], sS[w][lane]);
+        double out = acc.value();                  // -inf when every term was -inf
         if (A.rowconst) out += A.rowconst[j];
         A.pot[(size_t)nxt * A.ld + j] = out;
         A.shift[(size_t)nxt * A.ld + j] = A.lw2[j] - out;
     }
     if (A.do_advance) {
-        const double part = block_sum_256(err_terms(A.es, cur, j, gridDim.x * 256), lds);
+        const double part = block_sum_256(err_terms(A.es, cur, blockIdx.x * 256 + t, gridDim.x * 256), lds);
         if (t == 0) {
             A.es.errpart[blockIdx.x] = part;
             __threadfence();
@@ -192,9 +207,10 @@ __global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
         __syncthreads();
         if (s_last) {
             __threadfence();
-            double acc = 0.0;
-            for (int q = t; q < (int)gridDim.x; q += 256) acc += __hip_atomic_load(A.es.errpart + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const double err = block_sum_256(acc, lds);
+            double acc2 = 0.0;
+            for (int q = t; q < (int)gridDim.x; q += 256)
+                acc2 += __hip_atomic_load(A.es.errpart + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const double err = block_sum_256(acc2, lds);
             if (t == 0) {
                 c.st->ticket = 0;
                 advance_state(c, k, err);
@@ -204,7 +220,7 @@ __global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
 }
 
 hipError_t launch_combine(hipStream_t st, const CombineArgs &a, const Ctl &c) {
-    hipLaunchKernelGGL(k_combine, dim3((a.len + 255) / 256), dim3(256), 0, st, a, c);
+    hipLaunchKernelGGL(k_combine, dim3((a.len + 63) / 64), dim3(256), 0, st, a, c);
     return hipGetLastError();
 }
 
