@@ -82,7 +82,9 @@ typedef struct {
     const double *g64_in;    /*   are given (and warm_start = 1) they take the place of f, g          */
     float  *err_history;     /* optional device [err_history_len]: err_k stored at index k-1          */
     int32_t err_history_len;
-    int32_t reserved1;
+    int32_t time_kernel_every; /* blocking solves only: > 0 brackets the dominant kernel (row pass, fused
+                                  pass or point-cloud LSE pass of the f-update) of every N-th iteration
+                                  with HIP events on `stream`; read back with fs_last_kernel_timing()   */
 } fs_options;
 
 /* ---- Blocking solves (Alg. 1).  Return the number of iterations performed (>= 0) or a
@@ -161,6 +163,12 @@ fs_status fs_update_g(const float *C, const float *X, const float *Y, int d, con
 const char *fs_last_error(void);     /* thread-local, static storage, never NULL        */
 void        fs_clear_cache(void);    /* frees cached workspaces and hipGraph executables */
 const char *fs_version(void);
+
+/* Average duration (ms) of the dominant kernel over the launches sampled by the most recent
+ * blocking solve on this thread that had time_kernel_every > 0, the number of samples, and the
+ * kernel's name (static storage).  Any output pointer may be NULL.  FS_ERR_INVALID_ARG when
+ * there is no such solve.  For benchmarks; no effect on results. */
+fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name);
 
 #ifdef __cplusplus
 }

@@ -42,7 +42,7 @@ class fs_options(ctypes.Structure):
                 ("f64_out", ctypes.c_void_p), ("g64_out", ctypes.c_void_p),
                 ("f64_in", ctypes.c_void_p), ("g64_in", ctypes.c_void_p),
                 ("err_history", ctypes.c_void_p), ("err_history_len", ctypes.c_int32),
-                ("reserved1", ctypes.c_int32)]
+                ("time_kernel_every", ctypes.c_int32)]
 
 
 def _load():
@@ -55,6 +55,9 @@ def _load():
     lib.fs_last_error.restype = ctypes.c_char_p
     lib.fs_version.restype = ctypes.c_char_p
     lib.fs_clear_cache.restype = None
+    lib.fs_last_kernel_timing.restype = ci
+    lib.fs_last_kernel_timing.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32),
+                                          ctypes.POINTER(ctypes.c_char_p)]
     lib.fs_workspace_bytes.restype = ctypes.c_size_t
     lib.fs_workspace_bytes.argtypes = [ci, ci, ci]
     lib.fs_sinkhorn_dense.restype = ci
@@ -85,7 +88,8 @@ _lib = _load()
 
 EXPORTED = ("fs_sinkhorn_dense", "fs_sinkhorn_points", "fs_sinkhorn_solve", "fs_workspace_bytes",
             "fs_sinkhorn_dense_ex", "fs_sinkhorn_points_ex", "fs_plan", "fs_cost", "fs_plan_f64",
-            "fs_cost_f64", "fs_update_f", "fs_update_g", "fs_last_error", "fs_clear_cache", "fs_version")
+            "fs_cost_f64", "fs_update_f", "fs_update_g", "fs_last_error", "fs_clear_cache", "fs_version",
+            "fs_last_kernel_timing")
 
 
 def _check(status: int):
@@ -125,7 +129,8 @@ def _shape(C, X, Y, a, b):
 
 
 def make_options(check_every=0, warm_start=False, kernel_mode=0, use_graph=0, skip_final_err=False,
-                 fused_variant=0, f64_out=None, g64_out=None, f64_in=None, g64_in=None, err_history=None):
+                 fused_variant=0, f64_out=None, g64_out=None, f64_in=None, g64_in=None, err_history=None,
+                 time_kernel_every=0):
     o = fs_options()
     o.check_every = int(check_every)
     o.warm_start = int(bool(warm_start))
@@ -139,6 +144,7 @@ def make_options(check_every=0, warm_start=False, kernel_mode=0, use_graph=0, sk
     o.g64_in = _p(g64_in, torch.float64)
     o.err_history = _p(err_history, torch.float32)
     o.err_history_len = 0 if err_history is None else int(err_history.numel())
+    o.time_kernel_every = int(time_kernel_every)
     return o
 
 
@@ -153,6 +159,13 @@ def fs_last_error() -> str:
 
 def fs_clear_cache() -> None:
     _lib.fs_clear_cache()
+
+
+def fs_last_kernel_timing():
+    """(avg_ms, samples, kernel_name) of the dominant kernel sampled by the last timed blocking solve."""
+    ms, cnt, name = ctypes.c_float(0), ctypes.c_int32(0), ctypes.c_char_p()
+    _check(_lib.fs_last_kernel_timing(ctypes.byref(ms), ctypes.byref(cnt), ctypes.byref(name)))
+    return float(ms.value), int(cnt.value), name.value.decode()
 
 
 def fs_workspace_bytes(n: int, m: int, d: int = 0) -> int:

@@ -104,7 +104,11 @@ struct DeviceCache {
     size_t ws_bytes = 0;
     HostBlock *host = nullptr;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    std::vector<hipEvent_t> timing;     // start/stop pairs for sampled kernel timing
 };
+
+struct KernelTiming { float avg_ms = 0.0f; int samples = 0; const char *name = ""; };
+thread_local KernelTiming g_timing;
 
 std::mutex g_mu;
 std::map<int, DeviceCache> g_cache;
@@ -222,13 +226,21 @@ struct Solve {
         return a;
     }
 
-    hipError_t enqueue_f_update(int phase) const {      // Eq. 9 (and the error terms of Sec. 4.5)
+    const char *dominant_kernel() const {
+        return mode == 1 ? "k_row_stream" : mode == 2 ? "k_fused" : "k_points_lse";
+    }
+    // Eq. 9.  t0/t1 (optional) are recorded right before and after the dominant kernel of the
+    // iteration: the row pass, the fused pass, or the point-cloud LSE pass of the f-update.
+    hipError_t enqueue_f_update(int phase, hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr) const {
         const Ctl c = ctl(phase);
         hipError_t e = hipSuccess;
+        if (t0) e = hipEventRecord(t0, st);
+        if (e != hipSuccess) return e;
         if (mode == 1) e = launch_dense_row(st, dense(), c);
         else if (mode == 2) e = launch_dense_fused(st, dense(), c, opt.fused_variant);     // both half-steps
-        else {
-            e = launch_points_lse(st, points_f(), c, 0, L.m_ld);
+        else e = launch_points_lse(st, points_f(), c, 0, L.m_ld);
+        if (e == hipSuccess && t1) e = hipEventRecord(t1, st);
+        if (mode == 3) {
             if (e == hipSuccess)
                 e = launch_combine(st, combine_f(L.JSf, (const double *)(ws + L.o_part), (const double *)(ws + L.o_cx)), c);
         }
@@ -252,8 +264,8 @@ struct Solve {
         }
         return e;
     }
-    hipError_t enqueue_iteration() const {
-        hipError_t e = enqueue_f_update(0);
+    hipError_t enqueue_iteration(hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr) const {
+        hipError_t e = enqueue_f_update(0, t0, t1);
         if (e == hipSuccess) e = enqueue_g_update();
         return e;
     }
@@ -364,13 +376,28 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     S.host_flag = (volatile int32_t *)hb_dev;
     FS_HIP(S.enqueue_init());
     const int block = S.opt.check_every;
+    const int tevery = S.opt.time_kernel_every > 0 ? S.opt.time_kernel_every : 0;
+    int nsamples = 0;
+    g_timing = KernelTiming{};
     int it = 0, blk = 0;
     while (it < S.pr.max_iter) {
         if (hb->flag) break;                           // the device has stopped: enqueue nothing more
         if (blk >= 3) FS_HIP(hipEventSynchronize(dc->ev[(blk - 3) & 3]));   // bound the run-ahead to 3 blocks
         if (hb->flag) break;
         const int nb = (S.pr.max_iter - it) < block ? (S.pr.max_iter - it) : block;
-        for (int q = 0; q < nb; ++q) FS_HIP(S.enqueue_iteration());
+        for (int q = 0; q < nb; ++q) {
+            if (tevery && ((it + q) % tevery == 0) && nsamples < 4096) {
+                while ((int)dc->timing.size() < 2 * (nsamples + 1)) {
+                    hipEvent_t e;
+                    FS_HIP(hipEventCreate(&e));
+                    dc->timing.push_back(e);
+                }
+                FS_HIP(S.enqueue_iteration(dc->timing[2 * nsamples], dc->timing[2 * nsamples + 1]));
+                ++nsamples;
+            } else {
+                FS_HIP(S.enqueue_iteration());
+            }
+        }
         FS_HIP(hipEventRecord(dc->ev[blk & 3], S.st));
         it += nb;
         ++blk;
@@ -379,6 +406,21 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     FS_HIP(launch_finalize(S.st, S.pots, S.state, f, g, S.opt.f64_out, S.opt.g64_out, nullptr,
                            (char *)hb_dev + offsetof(HostBlock, res)));
     FS_HIP(hipStreamSynchronize(S.st));
+    if (nsamples > 0) {
+        // only launches that did work count: those of iterations the solve actually performed
+        double tot = 0.0;
+        int used = 0;
+        for (int q = 0; q < nsamples; ++q) {
+            if (q * tevery >= hb->res.iters) break;
+            float ms = 0.0f;
+            FS_HIP(hipEventElapsedTime(&ms, dc->timing[2 * q], dc->timing[2 * q + 1]));
+            tot += ms;
+            ++used;
+        }
+        g_timing.avg_ms = used ? (float)(tot / used) : 0.0f;
+        g_timing.samples = used;
+        g_timing.name = S.dominant_kernel();
+    }
     if (result_host) *result_host = hb->res;
     return hb->res.iters;
 }
@@ -478,9 +520,18 @@ void fs_clear_cache(void) {
         if (c.ws) (void)hipFree(c.ws);
         if (c.host) (void)hipHostFree((void *)c.host);
         for (auto &e : c.ev) if (e) (void)hipEventDestroy(e);
+        for (auto &e : c.timing) (void)hipEventDestroy(e);
         (void)hipSetDevice(cur);
     }
     g_cache.clear();
+}
+
+fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name) {
+    if (g_timing.samples <= 0) { set_err("no timed solve has run on this thread"); return FS_ERR_INVALID_ARG; }
+    if (avg_ms) *avg_ms = g_timing.avg_ms;
+    if (samples) *samples = g_timing.samples;
+    if (kernel_name) *kernel_name = g_timing.name;
+    return FS_OK;
 }
 
 size_t fs_workspace_bytes(int n, int m, int d) {

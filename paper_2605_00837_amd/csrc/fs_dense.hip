@@ -309,10 +309,10 @@ static bool fused_shape(int m, int variant, FusedShape *fsh) {
     if (m <= 1024) { *fsh = {256, 1, 4}; return true; }
     if (m <= 4096) { *fsh = {1024, 1, 4}; return true; }
     if (m <= 8192) {
-        if (variant == 1) *fsh = {1024, 2, 2};
+        if (variant == 1) *fsh = {512, 4, 4};
         else if (variant == 2) *fsh = {1024, 2, 4};
         else if (variant == 3) *fsh = {512, 4, 2};
-        else *fsh = {512, 4, 4};
+        else *fsh = {1024, 2, 2};
         return true;
     }
     return false;
