@@ -301,6 +301,271 @@ __global__ __launch_bounds__(T) void k_fused(DenseArgs A, Ctl c) {
     }
 }
 
+// ---------------------------------------------------------------- fused pass, asynchronous LDS prefetch
+// The production form of the fused pass for m in (4096, 8192].
+//
+// Arithmetic: the common case does no max pass at all.
+//   row phase    the reference of row i is its previous LSE value F_old_i.  Every lane sums
+//                2^(x - F_old_i) directly; if the workgroup-wide sum S_i lands in [2^-60, 2^100]
+//                (always, once the potentials move by less than ~60 eps per iteration) then
+//                F_new_i = F_old_i + log2 S_i.  Otherwise the panel is redone with the exact
+//                running-max form.
+//   column phase each column keeps a reference r_j that is a true maximum of some earlier chunk and
+//                is only raised when a sum would exceed 2^100: terms are summed as 2^(y - r_j)
+//                with no rescaling; a wave falls back to the exact update for a panel when a sum
+//                leaves the safe range (or the reference is not set yet).
+// Both references satisfy  ref <= running max <= ref + 100 (base 2), so nothing overflows and no
+// term that matters in fp32 underflows.
+//
+// Data movement:
+//   * every wave owns two private LDS staging buffers of R*Q KiB.  Panel p+1 is fetched into one of
+//     them with buffer_load_dwordx4 ... lds (HBM -> LDS, no registers, no wait) while panel p is
+//     consumed from the other with ds_read_b128, so the HBM stream runs under all of the arithmetic;
+//   * the panel is never held in registers: row phase and column phase both read it from LDS;
+//   * the only barrier per panel is the one that exchanges the R*16 wave sums.  It is a bare
+//     s_barrier after lgkmcnt(0): a fence would also wait for the prefetch in flight;
+//   * the per-row scalars of the next panel (old F, log2 a) are loaded one panel ahead, before the
+//     prefetch is issued, because vmcnt retires in order.
+__device__ __forceinline__ void lds_only_barrier() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): this wave's LDS writes are done
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#endif
+}
+
+template <int Q, int R>
+__global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
+    constexpr int T = 1024, NW = 16;
+    static_assert(R * NW <= 64, "one wave merges all (row, wave) partials in one shot");
+    constexpr float kHi = 1.2676506e30f;      // 2^100
+    constexpr float kLo = 8.6736174e-19f;     // 2^-60
+    __shared__ float4 stage[2][NW][R][Q][64];
+    __shared__ float sSum[2][R][NW];
+    __shared__ double sM[2][R][NW];
+    __shared__ float sS[2][R][NW];
+    int k;
+    if (!launch_active(c, k)) return;
+#if defined(__HIP_DEVICE_COMPILE__)
+    const int cur = k & 1, nxt = cur ^ 1;
+    const Pots &p = A.p;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform, and the compiler knows it
+    const double ns = -p.s;
+    const bool col_phase = (c.phase == 0);
+    const int m = p.m, n = p.n;
+    const int rr = lane / NW;                  // the panel row this lane serves in the merge
+    bool colok[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) colok[q] = ((q * T + tid) * 4) < m;
+
+    // Lanes whose columns lie past m never receive data (their loads are masked off); their staging
+    // slots are cleared once so that they read as a finite cost and V = -inf removes them.
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int q = 0; q < Q; ++q) stage[b][wave][r][q][lane] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    double v[Q][4];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int col = (q * T + tid) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            v[q][e] = col < m ? p.V[(size_t)cur * p.m_ld + col + e] : -__builtin_huge_val();
+    }
+    Lse cs[Q][4];                              // (r_j, s_j)
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cs[q][e].init();
+
+    const int npanels = (n + R - 1) / R;
+    const bool rev = (k & 1) != 0;
+    auto first_row = [&](int pq) { return (rev ? npanels - 1 - pq : pq) * R; };
+    // HBM -> LDS prefetch of one panel into staging buffer `buf`.  The buffer descriptor covers exactly
+    // the valid rows of the panel, so rows past n read as zero.
+    auto issue = [&](int pq, int buf) {
+        const int i0 = first_row(pq);
+        const int rows = (n - i0) < R ? (n - i0) : R;
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(A.C + (size_t)i0 * m), 0, rows * m * 4, 0x00020000);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+                if (colok[q])
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, &stage[buf][wave][r][q][0], 16,
+                                                             (r * m + (q * T + tid) * 4) * 4, 0, 0, 0);
+    };
+    auto row_scalars = [&](int pq, double &rho, double &la2) {
+        const int irow = first_row(pq) + rr;
+        const bool ok = rr < R && irow < n;
+        rho = ok ? p.F[(size_t)cur * p.n_ld + irow] : 0.0;
+        la2 = ok ? p.la2[irow] : -__builtin_huge_val();
+    };
+
+    int pq = blockIdx.x;
+    double rho_next = 0.0, la2_next = 0.0;
+    if (pq < npanels) {
+        row_scalars(pq, rho_next, la2_next);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xc07f);        // the clearing stores above are done
+        issue(pq, 0);
+        asm volatile("" ::: "memory");
+    }
+    int buf = 0;
+    bool refs_set = false;                         // column references hold a true maximum
+    for (; pq < npanels; pq += gridDim.x, buf ^= 1) {
+        const int i0 = first_row(pq);
+        const int irow = i0 + rr;
+        const bool rowok = rr < R && irow < n;
+        __builtin_amdgcn_s_waitcnt(0x0f70);        // vmcnt(0): panel `pq` has landed in stage[buf], scalars too
+        asm volatile("" ::: "memory");             // no LDS read of the stage may move above the wait
+        const double rho_lane = rho_next, la2_lane = la2_next;
+        const int pq2 = pq + gridDim.x;
+        if (pq2 < npanels) {
+            row_scalars(pq2, rho_next, la2_next);  // older than the prefetch below: retires first
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(0xc07f);    // every earlier read of stage[buf^1] has returned
+            issue(pq2, buf ^ 1);
+            asm volatile("" ::: "memory");
+        }
+        // ---- row phase, optimistic: sum 2^(x - rho_r)
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const double rho = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(rho_lane), r * NW),
+                                                __builtin_amdgcn_readlane(__double2loint(rho_lane), r * NW));
+            float acc = 0.0f;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const float4 c4 = stage[buf][wave][r][q][lane];
+                const float cvv[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    acc += fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - rho));
+            }
+            acc = wave_sum_f32(acc);
+            if (lane == 0) sSum[buf][r][wave] = acc;
+        }
+        lds_only_barrier();
+        float S = rr < R ? sSum[buf][rr < R ? rr : 0][lane % NW] : 1.0f;
+        S += dpp_f32<0x128>(S);
+        S += dpp_f32<0x124>(S);
+        S += dpp_f32<0x122>(S);
+        S += dpp_f32<0x121>(S);
+        const bool fine = (S >= kLo) && (S <= kHi);          // false for NaN / inf / 0
+        double Fn_lane = rho_lane + (double)fast_log2(S);
+        if (__builtin_expect(!__all(fine || !rowok), 0)) {
+            // ---- exact redo of the row phase of this panel (uniform over the workgroup: every wave
+            //      sees the same sums)
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                Lse rs; rs.init();
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    const float4 c4 = stage[buf][wave][r][q][lane];
+                    const float cvv[4] = {c4.x, c4.y, c4.z, c4.w};
+                    double x[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) x[e] = fma(ns, (double)cvv[e], v[q][e]);
+                    rs.template add<4>(x);
+                }
+                rs.wave_reduce();
+                if (lane == 0) { sM[buf][r][wave] = rs.M; sS[buf][r][wave] = rs.s; }
+            }
+            lds_only_barrier();
+            Lse t; t.init();
+            if (rr < R) { t.M = sM[buf][rr][lane % NW]; t.s = sS[buf][rr][lane % NW]; }
+            double Mg = t.M;
+            Mg = dmax(Mg, dpp_f64<0x128>(Mg));
+            Mg = dmax(Mg, dpp_f64<0x124>(Mg));
+            Mg = dmax(Mg, dpp_f64<0x122>(Mg));
+            Mg = dmax(Mg, dpp_f64<0x121>(Mg));
+            float sg = t.s * fast_exp2((float)(t.M - Mg));
+            sg += dpp_f32<0x128>(sg);
+            sg += dpp_f32<0x124>(sg);
+            sg += dpp_f32<0x122>(sg);
+            sg += dpp_f32<0x121>(sg);
+            Fn_lane = Mg + (double)fast_log2(sg);
+        }
+        if (wave == 0 && (lane % NW) == 0 && rowok) {
+            p.F[(size_t)nxt * p.n_ld + irow] = Fn_lane;
+            p.U[(size_t)nxt * p.n_ld + irow] = la2_lane - Fn_lane;
+        }
+        // ---- column phase with the new f
+        if (col_phase) {
+            const double u_lane = la2_lane - Fn_lane;          // -inf for rows past n
+            double u[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                u[r] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(u_lane), r * NW),
+                                        __builtin_amdgcn_readlane(__double2loint(u_lane), r * NW));
+            float tnew[Q][4];
+            float tall = 0.0f;                                 // sum of the (non-negative) candidate sums
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                float cvv[R][4];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const float4 c4 = stage[buf][wave][r][q][lane];
+                    cvv[r][0] = c4.x; cvv[r][1] = c4.y; cvv[r][2] = c4.z; cvv[r][3] = c4.w;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float t = cs[q][e].s;
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+                        t += fast_exp2((float)(fma(ns, (double)cvv[r][e], u[r]) - cs[q][e].M));
+                    tnew[q][e] = t;
+                    tall += t;
+                }
+            }
+            // every candidate is >= 0, so tall <= 2^100 bounds each of them; inf and NaN fail the test
+            const bool cfine = refs_set && (tall <= kHi);
+            if (__builtin_expect(__all(cfine), 1)) {
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) cs[q][e].s = tnew[q][e];
+            } else {
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    float cvv[R][4];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const float4 c4 = stage[buf][wave][r][q][lane];
+                        cvv[r][0] = c4.x; cvv[r][1] = c4.y; cvv[r][2] = c4.z; cvv[r][3] = c4.w;
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        double y[R];
+#pragma unroll
+                        for (int r = 0; r < R; ++r) y[r] = fma(ns, (double)cvv[r][e], u[r]);
+                        cs[q][e].template add<R>(y);
+                    }
+                }
+                refs_set = true;
+            }
+        }
+    }
+    if (col_phase) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int col = (q * T + tid) * 4;
+            if (col < m) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    A.colpart[(size_t)blockIdx.x * p.m_ld + col + e] = cs[q][e].value();
+            }
+        }
+    }
+#endif
+}
+
 struct FusedShape { int T, Q, R; };
 
 // Shapes held in registers without spilling: 4*Q*T columns, R rows per panel.
@@ -312,7 +577,8 @@ static bool fused_shape(int m, int variant, FusedShape *fsh) {
         if (variant == 1) *fsh = {512, 4, 4};
         else if (variant == 2) *fsh = {1024, 2, 4};
         else if (variant == 3) *fsh = {512, 4, 2};
-        else *fsh = {1024, 2, 2};
+        else if (variant == 4) *fsh = {1024, 2, 2};
+        else *fsh = {1024, 2, 302};                          // asynchronous LDS prefetch, R = 2
         return true;
     }
     return false;
@@ -328,9 +594,9 @@ void dense_fused_plan(int n, int m, int *P) {
     // the largest grid any variant uses: one panel set per resident workgroup
     FusedShape s{256, 1, 4};
     int best = 1;
-    for (int variant = 0; variant < 4; ++variant) {
+    for (int variant = 0; variant < 5; ++variant) {
         if (!fused_shape(m, variant, &s)) continue;
-        const int npanels = (n + s.R - 1) / s.R;
+        const int npanels = (n + (s.R % 100) - 1) / (s.R % 100);
         const int resident = s.T == 256 ? 1024 : 256;      // workgroups the 256 CUs hold at once
         const int p = npanels < resident ? npanels : resident;
         if (p > best) best = p;
@@ -341,14 +607,15 @@ void dense_fused_plan(int n, int m, int *P) {
 hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, int variant) {
     FusedShape s;
     if (!fused_shape(a.p.m, variant, &s)) return hipErrorInvalidValue;
-    const int npanels = (a.p.n + s.R - 1) / s.R;
+    const int npanels = (a.p.n + (s.R % 100) - 1) / (s.R % 100);
     const int resident = s.T == 256 ? 1024 : 256;
     int g = npanels < resident ? npanels : resident;
     if (g > a.P) g = a.P;
     DenseArgs b = a;
     b.P = g;
     const dim3 grid(g);
-    if (s.T == 256) hipLaunchKernelGGL((k_fused<256, 1, 4>), grid, dim3(256), 0, st, b, c);
+    if (s.R == 302) hipLaunchKernelGGL((k_fused_pf<2, 2>), grid, dim3(1024), 0, st, b, c);
+    else if (s.T == 256) hipLaunchKernelGGL((k_fused<256, 1, 4>), grid, dim3(256), 0, st, b, c);
     else if (s.T == 1024 && s.Q == 1) hipLaunchKernelGGL((k_fused<1024, 1, 4>), grid, dim3(1024), 0, st, b, c);
     else if (s.T == 1024 && s.R == 2) hipLaunchKernelGGL((k_fused<1024, 2, 2>), grid, dim3(1024), 0, st, b, c);
     else if (s.T == 1024) hipLaunchKernelGGL((k_fused<1024, 2, 4>), grid, dim3(1024), 0, st, b, c);
@@ -361,7 +628,7 @@ hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, 
 int dense_fused_grid(int n, int m, int variant) {
     FusedShape s;
     if (!fused_shape(m, variant, &s)) return 0;
-    const int npanels = (n + s.R - 1) / s.R;
+    const int npanels = (n + (s.R % 100) - 1) / (s.R % 100);
     const int resident = s.T == 256 ? 1024 : 256;
     return npanels < resident ? npanels : resident;
 }

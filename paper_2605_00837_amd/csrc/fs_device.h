@@ -50,8 +50,10 @@ struct Ctl {
 // the trailing error pass runs only when k == max_iter; nothing runs once done.
 __device__ __forceinline__ bool launch_active(const Ctl &c, int &k) {
     const volatile State *st = c.st;
-    k = st->k;
-    if (st->done) return false;
+    // the same value in every lane; readfirstlane tells the compiler so (scalar control flow and
+    // scalar addressing everywhere downstream)
+    k = __builtin_amdgcn_readfirstlane(st->k);
+    if (__builtin_amdgcn_readfirstlane(st->done)) return false;
     return c.phase == 0 ? (k < c.max_iter) : (k == c.max_iter);
 }
 

@@ -109,7 +109,7 @@ def test_dense_solve_modes(fs, oracle, mode, n, m):
     assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
 def test_fused_variants_full_width(fs, oracle, variant):
     w = W.random_dense(70, 8192, seed=77, cmax=2.0, eps=0.03)
     r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 12, kernel_mode=2, fused_variant=variant)
