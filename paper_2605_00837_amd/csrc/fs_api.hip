@@ -255,7 +255,12 @@ struct Solve {
         } else if (mode == 2) {
             {
             const int g = dense_fused_grid(pr.n, pr.m, opt.fused_variant);
-            e = launch_combine(st, combine_g(g, (const double *)(ws + L.o_part), nullptr), c);
+            CombineArgs ca = combine_g(g, (const double *)(ws + L.o_part), nullptr);
+            if (dense_fused_predicts(pr.m, opt.fused_variant)) {
+                ca.repair_C = pr.C; ca.repair_U = pots.U; ca.repair_n = pr.n; ca.repair_ld = L.n_ld;
+                ca.repair_s = pots.s;
+            }
+            e = launch_combine(st, ca, c);
         }
         } else {
             e = launch_points_lse(st, points_g(), c, 1, L.n_ld);

@@ -61,6 +61,15 @@ __device__ __forceinline__ bool launch_active(const Ctl &c, int &k) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }    // v_log_f32
 
+// log2 of a positive fp32 sum as a double, accurate to ~1e-7 absolute whatever the magnitude of
+// the sum: the exponent is taken exactly (v_frexp_exp), v_log_f32 only sees the mantissa in
+// [0.5, 1).  log2(0) = -inf, log2(inf) = +inf, NaN stays NaN.
+__device__ __forceinline__ double log2_sum(float s) {
+    const int e = __builtin_amdgcn_frexp_expf(s);
+    const float mant = __builtin_amdgcn_frexp_mantf(s);
+    return (double)e + (double)__builtin_amdgcn_logf(mant);
+}
+
 __device__ __forceinline__ double dmax(double a, double b) { return fmax(a, b); }
 
 // log2 of an fp32 weight in double precision; zero (or negative) weight -> -inf.
@@ -160,7 +169,7 @@ struct Lse {
         s = wave_sum_f32(s * fast_exp2((float)(M - Mw)));
         M = Mw;
     }
-    __device__ __forceinline__ double value() const { return M + (double)fast_log2(s); }
+    __device__ __forceinline__ double value() const { return M + log2_sum(s); }
 };
 
 // ---------------------------------------------------------------- advance

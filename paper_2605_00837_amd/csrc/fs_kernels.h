@@ -24,7 +24,17 @@ struct DenseArgs {
     double *colpart;      // [P][m_ld] per-panel partial column LSE values
     int32_t P;            // number of row panels of the column pass
     int32_t rows_per_panel;
+    double col_ref_bias;  // 0 in production; a test knob that shifts the predicted column references
 };
+
+// Margins of the predicted column references of the fused pass (base-2 units): the reference of
+// column j is Ghat_j - kColRefBelow with Ghat_j = 2 G_j^(k) - G_j^(k-1).  Terms overflow the 2^100
+// guard only if the new G_j exceeds the prediction by more than ~70 (handled in the kernel by the
+// exact update); a term 2^-40 below the new G_j is flushed by fp32 only if the new G_j is more than
+// ~100 below the prediction, so a combined result lower than Ghat_j - kColRepairBelow is treated
+// as possibly incomplete and recomputed exactly.
+constexpr double kColRefBelow = 16.0;
+constexpr double kColRepairBelow = 60.0;
 
 // Where the row-marginal error comes from.  r_i = a_i 2^(Fnew_i - Fold_i) is the row marginal of
 // the iterate a launch started from (the new f-update computes exactly the LSE of Sec. 4.5), so
@@ -50,6 +60,13 @@ struct CombineArgs {
     int32_t do_advance;       // 1: this is the g-update: also evaluate the error terms of Sec. 4.5 from
                               //    the old and new F, and let the last workgroup advance the state
     ErrSrc es;
+    // Repair of columns whose partials were formed against a predicted reference (fused dense pass,
+    // iterations k >= 2): when repair_C is non-null, a combined value below the prediction by more
+    // than kColRepairBelow is recomputed exactly from column j of C and the new U.
+    const float *repair_C;    // n x len row-major, or null
+    const double *repair_U;   // [2][repair_ld]
+    int32_t repair_n, repair_ld;
+    double repair_s;
 };
 
 // warm: bit 0 = start f from f_in / f64_in, bit 1 = start g from g_in / g64_in (else zero)
@@ -72,6 +89,7 @@ bool dense_fused_supported(int n, int m, const void *C);
 void dense_fused_plan(int n, int m, int *P);
 hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, int variant);
 int dense_fused_grid(int n, int m, int variant);
+bool dense_fused_predicts(int m, int variant);   // this shape / variant uses predicted column references
 
 // Point-cloud kernels.
 struct PointsArgs {

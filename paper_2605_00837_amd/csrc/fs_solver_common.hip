@@ -18,6 +18,9 @@ __global__ __launch_bounds__(256) void k_init(Pots p, State *state, const float 
         state->k = 0; state->done = 0; state->iters = 0; state->converged = 0; state->nonfinite = 0;
         state->ticket = 0; state->err_valid = 0; state->pad0 = 0;
         state->err = __builtin_nan("");
+#ifdef FS_COUNT_SLOW
+        reinterpret_cast<int32_t *>(state)[22] = 0;
+#endif
     }
     double *la2 = const_cast<double *>(p.la2);
     double *lb2 = const_cast<double *>(p.lb2);
@@ -164,6 +167,7 @@ __global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
     __shared__ double lds[256];
     __shared__ double sM[4][64];
     __shared__ float sS[4][64];
+    __shared__ unsigned long long s_mask;
     __shared__ int s_last;
     int k;
     if (!launch_active(c, k)) return;
@@ -188,13 +192,53 @@ __global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
     sM[wave][lane] = acc.M;
     sS[wave][lane] = acc.s;
     __syncthreads();
-    if (wave == 0 && jok) {
+    unsigned long long repair_mask = 0;
+    if (wave == 0) {
+        bool suspect = false;
+        if (jok) {
 #pragma unroll
-        for (int w = 1; w < 4; ++w) acc.merge(sM[w][lane], sS[w][lane]);
-        double out = acc.value();                  // -inf when every term was -inf
-        if (A.rowconst) out += A.rowconst[j];
-        A.pot[(size_t)nxt * A.ld + j] = out;
-        A.shift[(size_t)nxt * A.ld + j] = A.lw2[j] - out;
+            for (int w = 1; w < 4; ++w) acc.merge(sM[w][lane], sS[w][lane]);
+            double out = acc.value();                  // -inf when every term was -inf
+            if (A.rowconst) out += A.rowconst[j];
+            if (A.repair_C && k >= 2) {
+                // the partials were formed against the predicted reference Ghat - kColRefBelow
+                const double ghat = 2.0 * A.pot[(size_t)cur * A.ld + j] - A.pot[(size_t)nxt * A.ld + j];
+                suspect = !(out >= ghat - kColRepairBelow);      // also true for NaN / -inf
+            }
+            A.pot[(size_t)nxt * A.ld + j] = out;
+            A.shift[(size_t)nxt * A.ld + j] = A.lw2[j] - out;
+        }
+        repair_mask = __ballot(suspect);
+        if (lane == 0) s_mask = repair_mask;
+    }
+    if (A.repair_C && k >= 2) {
+        // ---- exact recomputation of the suspect columns of this workgroup (rare): all 256 threads
+        //      walk down column j of C with the new U, online LSE per thread, then wave + LDS merge
+        __syncthreads();
+        unsigned long long todo = s_mask;
+        const double *U = A.repair_U + (size_t)nxt * A.repair_ld;
+        while (todo) {
+            const int bit = __ffsll((long long)todo) - 1;
+            todo &= todo - 1;
+            const int jj = blockIdx.x * 64 + bit;
+            Lse ex; ex.init();
+            for (int i = t; i < A.repair_n; i += 256) {
+                double y[1] = {fma(-A.repair_s, (double)A.repair_C[(size_t)i * A.len + jj], U[i])};
+                ex.add<1>(y);
+            }
+            ex.wave_reduce();
+            __syncthreads();                           // previous round's LDS reads are done
+            if (lane == 0) { sM[wave][0] = ex.M; sS[wave][0] = ex.s; }
+            __syncthreads();
+            if (t == 0) {
+                Lse tot; tot.init();
+#pragma unroll
+                for (int w = 0; w < 4; ++w) tot.merge(sM[w][0], sS[w][0]);
+                const double out = tot.value();
+                A.pot[(size_t)nxt * A.ld + jj] = out;
+                A.shift[(size_t)nxt * A.ld + jj] = A.lw2[jj] - out;
+            }
+        }
     }
     if (A.do_advance) {
         const double part = block_sum_256(err_terms(A.es, cur, blockIdx.x * 256 + t, gridDim.x * 256), lds);

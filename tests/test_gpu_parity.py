@@ -116,6 +116,18 @@ def test_fused_variants_full_width(fs, oracle, variant):
     assert e64 < TOL_F64 and e32 < TOL_F32
 
 
+def test_fused_column_repair_path(fs, oracle):
+    """fused_variant >= 100 is a test knob: it shifts the predicted column references of the fused
+    pass far too high, so that every column's partial sums underflow and the combine kernel has to
+    recompute every column exactly from C.  The results must not change."""
+    w = W.random_dense(70, 8192, seed=78, cmax=2.0, eps=0.03)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 9, kernel_mode=2, fused_variant=100)
+    assert e64 < TOL_F64 and e32 < TOL_F32
+    w = W.random_dense(300, 4100, seed=79, cmax=2.0, eps=0.03)       # odd tail columns on the same path
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 9, kernel_mode=2, fused_variant=100)
+    assert e64 < TOL_F64 and e32 < TOL_F32
+
+
 def test_streaming_rejects_nothing_and_fused_rejects_odd_m(fs):
     w = W.random_dense(8, 10, seed=5)
     geo, a, b = to_dev(w)
