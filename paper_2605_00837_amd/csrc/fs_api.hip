@@ -87,7 +87,7 @@ Layout make_layout(int n, int m, int d) {
         L.o_Ys = take(sizeof(double) * (size_t)m * d);
         L.o_cy = take(sizeof(double) * L.m_ld);
     }
-    L.o_err = take(sizeof(double) * (size_t)((m + 63) / 64));        // one per workgroup of the g-combine
+    L.o_err = take(sizeof(double) * 2 * (size_t)((m + 63) / 64));    // error sum and largest move, one each per workgroup of the g-combine
     L.total = off;
     return L;
 }
@@ -259,6 +259,7 @@ struct Solve {
             if (dense_fused_predicts(pr.m, opt.fused_variant)) {
                 ca.repair_C = pr.C; ca.repair_U = pots.U; ca.repair_n = pr.n; ca.repair_ld = L.n_ld;
                 ca.repair_s = pots.s;
+                ca.force_fast = opt.fused_variant >= 100 ? 1 : 0;
             }
             e = launch_combine(st, ca, c);
         }

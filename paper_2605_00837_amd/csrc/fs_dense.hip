@@ -304,28 +304,33 @@ __global__ __launch_bounds__(T) void k_fused(DenseArgs A, Ctl c) {
 // ---------------------------------------------------------------- fused pass, asynchronous LDS prefetch
 // The production form of the fused pass for m in (4096, 8192].
 //
-// Arithmetic: the common case does no max pass at all.
-//   row phase    the reference of row i is its previous LSE value F_old_i.  Every lane sums
-//                2^(x - F_old_i) directly; if the workgroup-wide sum S_i lands in [2^-60, 2^100]
-//                (always, once the potentials move by less than ~60 eps per iteration) then
-//                F_new_i = F_old_i + log2 S_i.  Otherwise the panel is redone with the exact
-//                running-max form.
-//   column phase each column keeps a reference r_j that is a true maximum of some earlier chunk and
-//                is only raised when a sum would exceed 2^100: terms are summed as 2^(y - r_j)
-//                with no rescaling; a wave falls back to the exact update for a panel when a sum
-//                leaves the safe range (or the reference is not set yet).
-// Both references satisfy  ref <= running max <= ref + 100 (base 2), so nothing overflows and no
-// term that matters in fp32 underflows.
-//
-// Data movement:
+// Data movement
 //   * every wave owns two private LDS staging buffers of R*Q KiB.  Panel p+1 is fetched into one of
 //     them with buffer_load_dwordx4 ... lds (HBM -> LDS, no registers, no wait) while panel p is
 //     consumed from the other with ds_read_b128, so the HBM stream runs under all of the arithmetic;
-//   * the panel is never held in registers: row phase and column phase both read it from LDS;
 //   * the only barrier per panel is the one that exchanges the R*16 wave sums.  It is a bare
 //     s_barrier after lgkmcnt(0): a fence would also wait for the prefetch in flight;
-//   * the per-row scalars of the next panel (old F, log2 a) are loaded one panel ahead, before the
-//     prefetch is issued, because vmcnt retires in order.
+//   * the per-row scalars of the next panel (old F, log2 a, a) are loaded one panel ahead, before
+//     the prefetch is issued, because vmcnt retires in order.
+//
+// Arithmetic
+//   row phase    The reference of row i is its previous LSE value rho_i = F_old_i.  Every lane forms
+//                e_ij = 2^(x_ij - rho_i) and sums it; if the workgroup-wide sum S_i lands in
+//                [2^-60, 2^60] (always, once the potentials move by less than ~40 eps per
+//                iteration) then F_new_i = rho_i + log2 S_i with no max pass at all.  Otherwise
+//                the panel is redone with the exact running-max form of Eq. 8.
+//   column phase, FAST mode.  With the new f the plan entry is pi_ij = e_ij * a_i / S_i, all of
+//                them in [0, 1].  The column pass is therefore one fused multiply-add per entry:
+//                T_j += e_ij * alpha_i, alpha_i = a_i / S_i, and the partial column LSE is
+//                log2 T_j - V_j.  This is the classical scaling form of Sinkhorn, usable here
+//                because e_ij is already stabilised by the row reference.  It cannot overflow.  It
+//                loses a column only if that column's mass collapses by more than 2^60 in one
+//                iteration; the combine kernel detects exactly that (new G_j more than 60 below
+//                the old one, or not a number) and recomputes such columns from C.
+//   column phase, ROBUST mode.  Each column keeps a reference r_j that is a true running maximum,
+//                raised lazily when a sum would exceed 2^100; used while the potentials still move
+//                fast (the device switches modes by itself: FAST after an iteration in which at
+//                most 128 columns moved by more than 40, ROBUST otherwise).
 __device__ __forceinline__ void lds_only_barrier() {
 #if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("" ::: "memory");
@@ -335,12 +340,21 @@ __device__ __forceinline__ void lds_only_barrier() {
 #endif
 }
 
+__device__ __forceinline__ double bcast_f64(double x, int src_lane) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), src_lane),
+                            __builtin_amdgcn_readlane(__double2loint(x), src_lane));
+}
+__device__ __forceinline__ float bcast_f32(float x, int src_lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src_lane));
+}
+
 template <int Q, int R>
 __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     constexpr int T = 1024, NW = 16;
     static_assert(R * NW <= 64, "one wave merges all (row, wave) partials in one shot");
     constexpr float kHi = 1.2676506e30f;      // 2^100
-    constexpr float kLo = 8.6736174e-19f;     // 2^-60
+    constexpr float kRowHi = 1.1529215e18f;   // 2^60
+    constexpr float kRowLo = 8.6736174e-19f;  // 2^-60
     __shared__ float4 stage[2][NW][R][Q][64];
     __shared__ float sSum[2][R][NW];
     __shared__ double sM[2][R][NW];
@@ -354,6 +368,7 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform, and the compiler knows it
     const double ns = -p.s;
     const bool col_phase = (c.phase == 0);
+    const bool fast_cols = A.force_fast || (__builtin_amdgcn_readfirstlane(c.st->mode) == kModeFast);
     const int m = p.m, n = p.n;
     const int rr = lane / NW;                  // the panel row this lane serves in the merge
     bool colok[Q];
@@ -377,27 +392,12 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
         for (int e = 0; e < 4; ++e)
             v[q][e] = col < m ? p.V[(size_t)cur * p.m_ld + col + e] : -__builtin_huge_val();
     }
-    // Column references (r_j, s_j).  From the third iteration on the reference is predicted from the
-    // last two iterates, r_j = (2 G_j^(k) - G_j^(k-1)) - 16: every term of the column is then at most
-    // about 2^16 and every term that matters for the new G_j is far above the fp32 flush threshold,
-    // so no maximum has to be tracked.  A prediction that is too low shows up as a sum above 2^100
-    // and is handled here by the exact update; one that is too high is caught and repaired by the
-    // combine kernel.  The first two iterations (no history yet) track a true running maximum.
-    const bool predicted = (k >= 2);
-    Lse cs[Q][4];
+    float Tc[Q][4];                            // FAST: column sums of the plan entries
+    Lse cs[Q][4];                              // ROBUST: (r_j, s_j)
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        const int col = (q * T + tid) * 4;
+    for (int q = 0; q < Q; ++q)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            cs[q][e].init();
-            if (predicted && col < m) {
-                const double ghat = 2.0 * p.G[(size_t)cur * p.m_ld + col + e] - p.G[(size_t)nxt * p.m_ld + col + e];
-                const double ref = ghat - kColRefBelow + A.col_ref_bias;
-                if (fabs(ref) < 1.0e300) cs[q][e].M = ref;      // else: unset, the exact update sets it
-            }
-        }
-    }
+        for (int e = 0; e < 4; ++e) { Tc[q][e] = 0.0f; cs[q][e].init(); }
 
     const int npanels = (n + R - 1) / R;
     const bool rev = (k & 1) != 0;
@@ -417,24 +417,26 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, &stage[buf][wave][r][q][0], 16,
                                                              (r * m + (q * T + tid) * 4) * 4, 0, 0, 0);
     };
-    auto row_scalars = [&](int pq, double &rho, double &la2) {
+    auto row_scalars = [&](int pq, double &rho, double &la2, float &aw) {
         const int irow = first_row(pq) + rr;
         const bool ok = rr < R && irow < n;
         rho = ok ? p.F[(size_t)cur * p.n_ld + irow] : 0.0;
         la2 = ok ? p.la2[irow] : -__builtin_huge_val();
+        aw = ok ? p.a[irow] : 0.0f;
     };
 
     int pq = blockIdx.x;
     double rho_next = 0.0, la2_next = 0.0;
+    float a_next = 0.0f;
     if (pq < npanels) {
-        row_scalars(pq, rho_next, la2_next);
+        row_scalars(pq, rho_next, la2_next, a_next);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(0xc07f);        // the clearing stores above are done
         issue(pq, 0);
         asm volatile("" ::: "memory");
     }
     int buf = 0;
-    bool refs_set = predicted;                     // every column reference is set
+    bool refs_set = false;                         // ROBUST: every column reference holds a true maximum
     for (; pq < npanels; pq += gridDim.x, buf ^= 1) {
         const int i0 = first_row(pq);
         const int irow = i0 + rr;
@@ -442,27 +444,30 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
         __builtin_amdgcn_s_waitcnt(0x0f70);        // vmcnt(0): panel `pq` has landed in stage[buf], scalars too
         asm volatile("" ::: "memory");             // no LDS read of the stage may move above the wait
         const double rho_lane = rho_next, la2_lane = la2_next;
+        const float a_lane = a_next;
         const int pq2 = pq + gridDim.x;
         if (pq2 < npanels) {
-            row_scalars(pq2, rho_next, la2_next);  // older than the prefetch below: retires first
+            row_scalars(pq2, rho_next, la2_next, a_next);  // older than the prefetch below: retires first
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_waitcnt(0xc07f);    // every earlier read of stage[buf^1] has returned
             issue(pq2, buf ^ 1);
             asm volatile("" ::: "memory");
         }
-        // ---- row phase, optimistic: sum 2^(x - rho_r)
+        // ---- row phase, optimistic: e = 2^(x - rho_r), summed
+        float ev[R][Q][4];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const double rho = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(rho_lane), r * NW),
-                                                __builtin_amdgcn_readlane(__double2loint(rho_lane), r * NW));
+            const double rho = bcast_f64(rho_lane, r * NW);
             float acc = 0.0f;
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
                 const float4 c4 = stage[buf][wave][r][q][lane];
                 const float cvv[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    acc += fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - rho));
+                for (int e = 0; e < 4; ++e) {
+                    ev[r][q][e] = fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - rho));
+                    acc += ev[r][q][e];
+                }
             }
             acc = wave_sum_f32(acc);
             if (lane == 0) sSum[buf][r][wave] = acc;
@@ -473,14 +478,12 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
         S += dpp_f32<0x124>(S);
         S += dpp_f32<0x122>(S);
         S += dpp_f32<0x121>(S);
-        const bool fine = (S >= kLo) && (S <= kHi);          // false for NaN / inf / 0
+        const bool fine = (S >= kRowLo) && (S <= kRowHi);    // false for NaN / inf / 0
         double Fn_lane = rho_lane + log2_sum(S);
+        float alpha_lane = a_lane / S;                        // pi_ij = e_ij * a_i / S_i
         if (__builtin_expect(!__all(fine || !rowok), 0)) {
             // ---- exact redo of the row phase of this panel (uniform over the workgroup: every wave
             //      sees the same sums)
-#ifdef FS_COUNT_SLOW
-            if (tid == 0) atomicAdd((unsigned *)&c.st->pad0, 1u);
-#endif
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 Lse rs; rs.init();
@@ -510,6 +513,21 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
             sg += dpp_f32<0x122>(sg);
             sg += dpp_f32<0x121>(sg);
             Fn_lane = Mg + log2_sum(sg);
+            alpha_lane = a_lane;                               // e is re-based on the new F below
+            if (col_phase && fast_cols) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const double Fn = bcast_f64(Fn_lane, r * NW);
+#pragma unroll
+                    for (int q = 0; q < Q; ++q) {
+                        const float4 c4 = stage[buf][wave][r][q][lane];
+                        const float cvv[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            ev[r][q][e] = fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - Fn));
+                    }
+                }
+            }
         }
         if (wave == 0 && (lane % NW) == 0 && rowok) {
             p.F[(size_t)nxt * p.n_ld + irow] = Fn_lane;
@@ -517,40 +535,23 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
         }
         // ---- column phase with the new f
         if (col_phase) {
-            const double u_lane = la2_lane - Fn_lane;          // -inf for rows past n
-            double u[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                u[r] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(u_lane), r * NW),
-                                        __builtin_amdgcn_readlane(__double2loint(u_lane), r * NW));
-            float tnew[Q][4];
-            float tall = 0.0f;                                 // sum of the (non-negative) candidate sums
-#pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                float cvv[R][4];
+            if (fast_cols) {
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    const float4 c4 = stage[buf][wave][r][q][lane];
-                    cvv[r][0] = c4.x; cvv[r][1] = c4.y; cvv[r][2] = c4.z; cvv[r][3] = c4.w;
+                    float alpha = bcast_f32(alpha_lane, r * NW);
+                    if (!(alpha == alpha) || (i0 + r) >= n) alpha = 0.0f;   // rows past n, or a row whose F is not finite
+#pragma unroll
+                    for (int q = 0; q < Q; ++q)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) Tc[q][e] = fmaf(ev[r][q][e], alpha, Tc[q][e]);
                 }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float t = cs[q][e].s;
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-                        t += fast_exp2((float)(fma(ns, (double)cvv[r][e], u[r]) - cs[q][e].M));
-                    tnew[q][e] = t;
-                    tall += t;
-                }
-            }
-            // every candidate is >= 0, so tall <= 2^100 bounds each of them; inf and NaN fail the test
-            const bool cfine = refs_set && (tall <= kHi);
-            if (__builtin_expect(__all(cfine), 1)) {
-#pragma unroll
-                for (int q = 0; q < Q; ++q)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) cs[q][e].s = tnew[q][e];
             } else {
+                const double u_lane = la2_lane - Fn_lane;          // -inf for rows past n
+                double u[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) u[r] = bcast_f64(u_lane, r * NW);
+                float tnew[Q][4];
+                float tall = 0.0f;                                 // sum of the (non-negative) candidate sums
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
                     float cvv[R][4];
@@ -561,16 +562,40 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
                     }
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        double y[R];
+                        float t = cs[q][e].s;
 #pragma unroll
-                        for (int r = 0; r < R; ++r) y[r] = fma(ns, (double)cvv[r][e], u[r]);
-                        cs[q][e].template add<R>(y);
+                        for (int r = 0; r < R; ++r)
+                            t += fast_exp2((float)(fma(ns, (double)cvv[r][e], u[r]) - cs[q][e].M));
+                        tnew[q][e] = t;
+                        tall += t;
                     }
                 }
-                refs_set = true;
-#ifdef FS_COUNT_SLOW
-                if (lane == 0) atomicAdd((unsigned *)&c.st->err_valid + 16, 1u);
-#endif
+                // every candidate is >= 0, so tall <= 2^100 bounds each of them; inf and NaN fail the test
+                const bool cfine = refs_set && (tall <= kHi);
+                if (__builtin_expect(__all(cfine), 1)) {
+#pragma unroll
+                    for (int q = 0; q < Q; ++q)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) cs[q][e].s = tnew[q][e];
+                } else {
+#pragma unroll
+                    for (int q = 0; q < Q; ++q) {
+                        float cvv[R][4];
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+                            const float4 c4 = stage[buf][wave][r][q][lane];
+                            cvv[r][0] = c4.x; cvv[r][1] = c4.y; cvv[r][2] = c4.z; cvv[r][3] = c4.w;
+                        }
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            double y[R];
+#pragma unroll
+                            for (int r = 0; r < R; ++r) y[r] = fma(ns, (double)cvv[r][e], u[r]);
+                            cs[q][e].template add<R>(y);
+                        }
+                    }
+                    refs_set = true;
+                }
             }
         }
     }
@@ -580,8 +605,12 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
             const int col = (q * T + tid) * 4;
             if (col < m) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    A.colpart[(size_t)blockIdx.x * p.m_ld + col + e] = cs[q][e].value();
+                for (int e = 0; e < 4; ++e) {
+                    // FAST: sum_i 2^(U_i - s C_ij) = T_j 2^(-V_j); a column of zero weight (V = -inf)
+                    // comes out as NaN here and is recomputed by the combine kernel
+                    const double part = fast_cols ? log2_sum(Tc[q][e]) - v[q][e] : cs[q][e].value();
+                    A.colpart[(size_t)blockIdx.x * p.m_ld + col + e] = part;
+                }
             }
         }
     }
@@ -636,7 +665,7 @@ hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, 
     if (g > a.P) g = a.P;
     DenseArgs b = a;
     b.P = g;
-    b.col_ref_bias = variant >= 100 ? 400.0 : 0.0;       // test knob: forces the combine-side repair
+    b.force_fast = variant >= 100 ? 1 : 0;                // test knob: FAST column mode from iteration 1
     const dim3 grid(g);
     if (s.R == 302) hipLaunchKernelGGL((k_fused_pf<2, 2>), grid, dim3(1024), 0, st, b, c);
     else if (s.T == 256) hipLaunchKernelGGL((k_fused<256, 1, 4>), grid, dim3(256), 0, st, b, c);

@@ -30,7 +30,7 @@ struct alignas(256) State {
     int32_t nonfinite;
     uint32_t ticket;      // last-workgroup-done counter (returns to 0 after every use)
     int32_t err_valid;
-    int32_t pad0;
+    int32_t mode;         // column mode of the fused dense pass for the next iteration (0 robust, 1 fast)
     double err;           // err after `iters`
 };
 
@@ -176,8 +176,11 @@ struct Lse {
 // Runs in ONE thread after the g-update of an iteration (or after the trailing
 // error pass).  `err` is the row-marginal error of the iterate the launch
 // started from, i.e. err_k for k = st->k (Alg. 1: checked when k mod c == 0).
-__device__ __forceinline__ void advance_state(const Ctl &c, int k, double err) {
+__device__ __forceinline__ void advance_state(const Ctl &c, int k, double err, double big_cols) {
     State *st = c.st;
+    // fused dense pass: FAST column mode next time iff at most 128 columns moved by more than 40
+    // (base 2) this time; the few that still do are caught and recomputed by the combine kernel
+    st->mode = (big_cols <= 128.0) ? 1 : 0;
     if (c.err_history && k >= 1 && k - 1 < c.err_history_len) c.err_history[k - 1] = (float)err;
     const bool checked = (c.tol > 0.0) && (k >= 1) && (k % c.check_every == 0);
     bool stop = false;

@@ -24,16 +24,16 @@ struct DenseArgs {
     double *colpart;      // [P][m_ld] per-panel partial column LSE values
     int32_t P;            // number of row panels of the column pass
     int32_t rows_per_panel;
-    double col_ref_bias;  // 0 in production; a test knob that shifts the predicted column references
+    int32_t force_fast;   // 0 in production; test knob: FAST column mode whatever the device-side mode says
 };
 
-// Margins of the predicted column references of the fused pass (base-2 units): the reference of
-// column j is Ghat_j - kColRefBelow with Ghat_j = 2 G_j^(k) - G_j^(k-1).  Terms overflow the 2^100
-// guard only if the new G_j exceeds the prediction by more than ~70 (handled in the kernel by the
-// exact update); a term 2^-40 below the new G_j is flushed by fp32 only if the new G_j is more than
-// ~100 below the prediction, so a combined result lower than Ghat_j - kColRepairBelow is treated
-// as possibly incomplete and recomputed exactly.
-constexpr double kColRefBelow = 16.0;
+// Column modes of the fused pass, chosen on the device after every iteration (State::mode):
+// FAST after an iteration in which at most 128 columns moved by more than kFastBelow (base-2 units),
+// ROBUST otherwise.  In FAST mode a combined G_j that fell by more than kColRepairBelow (or is not a
+// number) may have lost terms to fp32 underflow and is recomputed exactly by the combine kernel.
+constexpr int kModeRobust = 0;
+constexpr int kModeFast = 1;
+constexpr double kFastBelow = 40.0;
 constexpr double kColRepairBelow = 60.0;
 
 // Where the row-marginal error comes from.  r_i = a_i 2^(Fnew_i - Fold_i) is the row marginal of
@@ -60,12 +60,13 @@ struct CombineArgs {
     int32_t do_advance;       // 1: this is the g-update: also evaluate the error terms of Sec. 4.5 from
                               //    the old and new F, and let the last workgroup advance the state
     ErrSrc es;
-    // Repair of columns whose partials were formed against a predicted reference (fused dense pass,
-    // iterations k >= 2): when repair_C is non-null, a combined value below the prediction by more
-    // than kColRepairBelow is recomputed exactly from column j of C and the new U.
+    // Repair of columns whose partials were formed in FAST column mode (fused dense pass): when
+    // repair_C is non-null and the iteration ran in FAST mode, a combined value more than
+    // kColRepairBelow under the old G_j (or NaN) is recomputed exactly from column j of C and the new U.
     const float *repair_C;    // n x len row-major, or null
     const double *repair_U;   // [2][repair_ld]
     int32_t repair_n, repair_ld;
+    int32_t force_fast;       // mirrors DenseArgs::force_fast
     double repair_s;
 };
 

@@ -16,11 +16,8 @@ __global__ __launch_bounds__(256) void k_init(Pots p, State *state, const float 
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t == 0) {
         state->k = 0; state->done = 0; state->iters = 0; state->converged = 0; state->nonfinite = 0;
-        state->ticket = 0; state->err_valid = 0; state->pad0 = 0;
+        state->ticket = 0; state->err_valid = 0; state->mode = kModeRobust;
         state->err = __builtin_nan("");
-#ifdef FS_COUNT_SLOW
-        reinterpret_cast<int32_t *>(state)[22] = 0;
-#endif
     }
     double *la2 = const_cast<double *>(p.la2);
     double *lb2 = const_cast<double *>(p.lb2);
@@ -130,13 +127,16 @@ __device__ __forceinline__ double block_sum_256(double v, double *lds) {
 
 // Error terms a_i |2^(Fnew_i - Fold_i) - 1| of the rows first, first+stride, ... (fp64, expm1 for
 // the small differences near convergence).
+// 1 if a potential moved by more than kFastBelow (or by a non-finite amount), else 0
+__device__ __forceinline__ double big_move(double diff) { return (fabs(diff) <= kFastBelow) ? 0.0 : 1.0; }
 __device__ __forceinline__ double err_terms(const ErrSrc &es, int cur, int first, int stride) {
     const double *Fo = es.F + (size_t)cur * es.n_ld;
     const double *Fn = es.F + (size_t)(cur ^ 1) * es.n_ld;
     double acc = 0.0;
     for (int i = first; i < es.n; i += stride) {
         const float a = es.a[i];
-        if (a > 0.0f) acc += (double)a * fabs(expm1((Fn[i] - Fo[i]) * 0.6931471805599453094));
+        const double diff = Fn[i] - Fo[i];
+        if (a > 0.0f) acc += (double)a * fabs(expm1(diff * 0.6931471805599453094));
     }
     return acc;
 }
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(256) void k_advance(ErrSrc es, Ctl c) {
     int k;
     if (!launch_active(c, k)) return;
     const double err = block_sum_256(err_terms(es, k & 1, threadIdx.x, 256), lds);
-    if (threadIdx.x == 0) advance_state(c, k, err);
+    if (threadIdx.x == 0) advance_state(c, k, err, 1.0e300);
 }
 
 hipError_t launch_advance(hipStream_t st, const ErrSrc &es, const Ctl &c) {
@@ -156,17 +156,30 @@ hipError_t launch_advance(hipStream_t st, const ErrSrc &es, const Ctl &c) {
 }
 
 // ---------------------------------------------------------------- combine
-// out_j = LSE2_p part[p][j] (+ rowconst_j).  A workgroup of 4 waves owns 64
-// adjacent entries; wave w folds the partial sets p = w, w+4, ... online (each
-// read is one coalesced 512-byte row segment, 8 independent loads in flight),
-// the four wave results meet in LDS.  The g-update's combine also evaluates
-// the error terms (spread over all its threads; per-workgroup sums are added
-// up in index order by whichever workgroup finishes last) and advances the
-// iteration state.
-__global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
-    __shared__ double lds[256];
-    __shared__ double sM[4][64];
-    __shared__ float sS[4][64];
+// out_j = LSE2_p part[p][j] (+ rowconst_j).  A workgroup of kCombW waves owns 64 adjacent entries;
+// wave w folds the partial sets p = w, w + kCombW, ... online (each read is one coalesced 512-byte
+// row segment, 8 independent loads in flight), the wave results meet in LDS.  The g-update's combine
+// also evaluates the error terms (spread over all its threads; per-workgroup sums are added up in
+// index order by whichever workgroup finishes last) and advances the iteration state.
+constexpr int kCombW = 16;
+constexpr int kCombT = kCombW * 64;
+
+__device__ __forceinline__ double block_sum_comb(double v, double *lds) {
+    const int t = threadIdx.x;
+    __syncthreads();
+    lds[t] = v;
+    __syncthreads();
+    for (int w = kCombT / 2; w >= 1; w >>= 1) {
+        if (t < w) lds[t] += lds[t + w];
+        __syncthreads();
+    }
+    return lds[0];
+}
+
+__global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
+    __shared__ double lds[kCombT];
+    __shared__ double sM[kCombW][64];
+    __shared__ float sS[kCombW][64];
     __shared__ unsigned long long s_mask;
     __shared__ int s_last;
     int k;
@@ -175,16 +188,18 @@ __global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
     const int j = blockIdx.x * 64 + lane;
     const bool jok = j < A.len;
+    const bool fast_mode = A.repair_C && (A.force_fast || __builtin_amdgcn_readfirstlane(c.st->mode) == kModeFast);
+    double nbig = 0.0;                             // columns of this thread that moved by more than kFastBelow
     Lse acc; acc.init();
     if (jok) {
         int p = wave;
-        for (; p + 28 < A.P; p += 32) {
+        for (; p + 7 * kCombW < A.P; p += 8 * kCombW) {
             double x[8];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) x[q] = A.part[(size_t)(p + 4 * q) * A.ld + j];
+            for (int q = 0; q < 8; ++q) x[q] = A.part[(size_t)(p + kCombW * q) * A.ld + j];
             acc.add<8>(x);
         }
-        for (; p < A.P; p += 4) {
+        for (; p < A.P; p += kCombW) {
             double x[1] = {A.part[(size_t)p * A.ld + j]};
             acc.add<1>(x);
         }
@@ -192,28 +207,27 @@ __global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
     sM[wave][lane] = acc.M;
     sS[wave][lane] = acc.s;
     __syncthreads();
-    unsigned long long repair_mask = 0;
     if (wave == 0) {
         bool suspect = false;
         if (jok) {
 #pragma unroll
-            for (int w = 1; w < 4; ++w) acc.merge(sM[w][lane], sS[w][lane]);
+            for (int w = 1; w < kCombW; ++w) acc.merge(sM[w][lane], sS[w][lane]);
             double out = acc.value();                  // -inf when every term was -inf
             if (A.rowconst) out += A.rowconst[j];
-            if (A.repair_C && k >= 2) {
-                // the partials were formed against the predicted reference Ghat - kColRefBelow
-                const double ghat = 2.0 * A.pot[(size_t)cur * A.ld + j] - A.pot[(size_t)nxt * A.ld + j];
-                suspect = !(out >= ghat - kColRepairBelow);      // also true for NaN / -inf
-            }
+            const double old = A.pot[(size_t)cur * A.ld + j];
+            // FAST column mode sums plan entries in fp32: a column whose G fell by more than 2^60
+            // in one iteration (or is not a number) may have lost terms to underflow
+            if (fast_mode) suspect = !(out >= old - kColRepairBelow);
+            nbig = suspect ? 1.0 : big_move(out - old);
             A.pot[(size_t)nxt * A.ld + j] = out;
             A.shift[(size_t)nxt * A.ld + j] = A.lw2[j] - out;
         }
-        repair_mask = __ballot(suspect);
-        if (lane == 0) s_mask = repair_mask;
+        const unsigned long long mask = __ballot(suspect);
+        if (lane == 0) s_mask = mask;
     }
-    if (A.repair_C && k >= 2) {
-        // ---- exact recomputation of the suspect columns of this workgroup (rare): all 256 threads
-        //      walk down column j of C with the new U, online LSE per thread, then wave + LDS merge
+    if (fast_mode) {
+        // ---- exact recomputation of the suspect columns of this workgroup (rare): all threads walk
+        //      down column j of C with the new U, online LSE per thread, then wave + LDS merge
         __syncthreads();
         unsigned long long todo = s_mask;
         const double *U = A.repair_U + (size_t)nxt * A.repair_ld;
@@ -222,7 +236,7 @@ __global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
             todo &= todo - 1;
             const int jj = blockIdx.x * 64 + bit;
             Lse ex; ex.init();
-            for (int i = t; i < A.repair_n; i += 256) {
+            for (int i = t; i < A.repair_n; i += kCombT) {
                 double y[1] = {fma(-A.repair_s, (double)A.repair_C[(size_t)i * A.len + jj], U[i])};
                 ex.add<1>(y);
             }
@@ -233,7 +247,7 @@ __global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
             if (t == 0) {
                 Lse tot; tot.init();
 #pragma unroll
-                for (int w = 0; w < 4; ++w) tot.merge(sM[w][0], sS[w][0]);
+                for (int w = 0; w < kCombW; ++w) tot.merge(sM[w][0], sS[w][0]);
                 const double out = tot.value();
                 A.pot[(size_t)nxt * A.ld + jj] = out;
                 A.shift[(size_t)nxt * A.ld + jj] = A.lw2[jj] - out;
@@ -241,9 +255,11 @@ __global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
         }
     }
     if (A.do_advance) {
-        const double part = block_sum_256(err_terms(A.es, cur, blockIdx.x * 256 + t, gridDim.x * 256), lds);
+        const double part = block_sum_comb(err_terms(A.es, cur, blockIdx.x * kCombT + t, gridDim.x * kCombT), lds);
+        const double bbig = block_sum_comb(nbig, lds);
         if (t == 0) {
             A.es.errpart[blockIdx.x] = part;
+            A.es.errpart[gridDim.x + blockIdx.x] = bbig;
             __threadfence();
             const unsigned prev = atomicAdd(&c.st->ticket, 1u);
             s_last = (prev == gridDim.x - 1) ? 1 : 0;
@@ -251,20 +267,23 @@ __global__ __launch_bounds__(256) void k_combine(CombineArgs A, Ctl c) {
         __syncthreads();
         if (s_last) {
             __threadfence();
-            double acc2 = 0.0;
-            for (int q = t; q < (int)gridDim.x; q += 256)
+            double acc2 = 0.0, mv = 0.0;
+            for (int q = t; q < (int)gridDim.x; q += kCombT) {
                 acc2 += __hip_atomic_load(A.es.errpart + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const double err = block_sum_256(acc2, lds);
+                mv += __hip_atomic_load(A.es.errpart + gridDim.x + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            const double err = block_sum_comb(acc2, lds);
+            const double big_cols = block_sum_comb(mv, lds);
             if (t == 0) {
                 c.st->ticket = 0;
-                advance_state(c, k, err);
+                advance_state(c, k, err, big_cols);
             }
         }
     }
 }
 
 hipError_t launch_combine(hipStream_t st, const CombineArgs &a, const Ctl &c) {
-    hipLaunchKernelGGL(k_combine, dim3((a.len + 63) / 64), dim3(256), 0, st, a, c);
+    hipLaunchKernelGGL(k_combine, dim3((a.len + 63) / 64), dim3(kCombT), 0, st, a, c);
     return hipGetLastError();
 }
 

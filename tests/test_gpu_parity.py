@@ -281,6 +281,19 @@ def test_zero_weights_and_singletons(fs, oracle):
     assert pot_err(r["f64"].cpu().numpy(), ref["f"], 0.1) < TOL_F64
 
 
+def test_zero_weights_on_the_prefetch_fused_path(fs, oracle):
+    """m in (4096, 8192] runs the LDS-prefetch fused kernel; a zero column weight makes that column's
+    FAST-mode partial undefined, which the combine kernel must notice and recompute."""
+    w = W.random_dense(48, 8192, seed=45, eps=0.05)
+    a = w.a.copy(); a[7] = 0.0
+    b = w.b.copy(); b[11] = 0.0; b[5000] = 0.0
+    r = fs.fs_sinkhorn_solve(dev(a), dev(b), w.eps, 30, 0.0, C=dev(w.C), want_f64=True, kernel_mode=2)
+    ref = oracle.solve(a, b, w.eps, 30, C=w.C)
+    assert not r["nonfinite"]
+    assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+
+
 def test_nonfinite_cost_is_flagged_not_fatal(fs):
     w = W.random_dense(32, 64, seed=43, eps=0.05)
     C = w.C.copy(); C[3, 5] = np.nan
