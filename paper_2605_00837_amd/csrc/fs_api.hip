@@ -94,8 +94,10 @@ Layout make_layout(int n, int m, int d) {
 
 // ---------------------------------------------------------------- per-device cache
 struct HostBlock {            // pinned, device-visible
-    volatile int32_t flag;
-    int32_t pad[3];
+    volatile int32_t flag;    // done
+    volatile int32_t hint;    // latest pace hint (1 = potentials move slowly)
+    volatile int32_t hints[64];   // pace hint after iteration k, at index k % 64
+    int32_t pad[2];
     fs_result res;
 };
 
@@ -171,12 +173,15 @@ struct Solve {
         c.host_flag = host_flag;
         return c;
     }
-    DenseArgs dense() const {
+    // kind of an iteration of the dense solver: the exact streaming kernels, or a fused kernel
+    enum Kind { STREAM = 1, FUSED = 2 };
+    bool fused_is_fp32_cols() const { return mode == 2 && dense_fused_predicts(pr.m, opt.fused_variant); }
+    DenseArgs dense(Kind kind) const {
         DenseArgs a;
         a.C = pr.C;
         a.p = pots;
         a.colpart = (double *)(ws + L.o_part);
-        if (mode == 2) { a.P = dense_fused_grid(pr.n, pr.m, opt.fused_variant); a.rows_per_panel = 0; }
+        if (kind == FUSED) { a.P = dense_fused_grid(pr.n, pr.m, opt.fused_variant); a.rows_per_panel = 0; }
         else { a.P = L.P_stream; a.rows_per_panel = L.rpp_stream; }
         return a;
     }
@@ -227,18 +232,18 @@ struct Solve {
     }
 
     const char *dominant_kernel() const {
-        return mode == 1 ? "k_row_stream" : mode == 2 ? "k_fused" : "k_points_lse";
+        return mode == 1 ? "k_row_stream" : mode == 2 ? (fused_is_fp32_cols() ? "k_fused_pf" : "k_fused") : "k_points_lse";
     }
     // Eq. 9.  t0/t1 (optional) are recorded right before and after the dominant kernel of the
     // iteration: the row pass, the fused pass, or the point-cloud LSE pass of the f-update.
-    hipError_t enqueue_f_update(int phase, hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr) const {
+    hipError_t enqueue_f_update(int phase, Kind kind, hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr) const {
         const Ctl c = ctl(phase);
         hipError_t e = hipSuccess;
         if (t0) e = hipEventRecord(t0, st);
         if (e != hipSuccess) return e;
-        if (mode == 1) e = launch_dense_row(st, dense(), c);
-        else if (mode == 2) e = launch_dense_fused(st, dense(), c, opt.fused_variant);     // both half-steps
-        else e = launch_points_lse(st, points_f(), c, 0, L.m_ld);
+        if (mode == 3) e = launch_points_lse(st, points_f(), c, 0, L.m_ld);
+        else if (kind == STREAM) e = launch_dense_row(st, dense(STREAM), c);
+        else e = launch_dense_fused(st, dense(FUSED), c, opt.fused_variant);     // both half-steps
         if (e == hipSuccess && t1) e = hipEventRecord(t1, st);
         if (mode == 3) {
             if (e == hipSuccess)
@@ -246,11 +251,11 @@ struct Solve {
         }
         return e;
     }
-    hipError_t enqueue_g_update() const {                // Eq. 10 + state advance
+    hipError_t enqueue_g_update(Kind kind) const {       // Eq. 10 + state advance
         const Ctl c = ctl(0);
         hipError_t e = hipSuccess;
-        if (mode == 1) {
-            e = launch_dense_col(st, dense(), c);
+        if (mode != 3 && kind == STREAM) {
+            e = launch_dense_col(st, dense(STREAM), c);
             if (e == hipSuccess) e = launch_combine(st, combine_g(L.P_stream, (const double *)(ws + L.o_part), nullptr), c);
         } else if (mode == 2) {
             {
@@ -259,7 +264,6 @@ struct Solve {
             if (dense_fused_predicts(pr.m, opt.fused_variant)) {
                 ca.repair_C = pr.C; ca.repair_U = pots.U; ca.repair_n = pr.n; ca.repair_ld = L.n_ld;
                 ca.repair_s = pots.s;
-                ca.force_fast = opt.fused_variant >= 100 ? 1 : 0;
             }
             e = launch_combine(st, ca, c);
         }
@@ -270,13 +274,14 @@ struct Solve {
         }
         return e;
     }
-    hipError_t enqueue_iteration(hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr) const {
-        hipError_t e = enqueue_f_update(0, t0, t1);
-        if (e == hipSuccess) e = enqueue_g_update();
+    Kind default_kind() const { return mode == 2 ? FUSED : STREAM; }
+    hipError_t enqueue_iteration(Kind kind, hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr) const {
+        hipError_t e = enqueue_f_update(0, kind, t0, t1);
+        if (e == hipSuccess) e = enqueue_g_update(kind);
         return e;
     }
     hipError_t enqueue_trailing() const {                // err after the last iteration
-        hipError_t e = enqueue_f_update(1);
+        hipError_t e = enqueue_f_update(1, default_kind());
         if (e == hipSuccess) e = launch_advance(st, err_src(), ctl(1));
         return e;
     }
@@ -365,9 +370,17 @@ struct GraphKey {
     }
 };
 
+constexpr int kAsyncExactFirst = 4;     // asynchronous solves: exact streaming iterations before the fused kernel
+constexpr int kFirstBlock = 2;          // blocking solves: iterations before the first look at the pace hint
+
 fs_status run_solve_async(Solve &S, float *f, float *g, fs_result *result_dev) {
     FS_HIP(S.enqueue_init());
-    for (int it = 0; it < S.pr.max_iter; ++it) FS_HIP(S.enqueue_iteration());
+    // Without a host in the loop the pace hint cannot be followed: the fp32-column fused kernel takes
+    // over after a fixed number of exact streaming iterations (its repair keeps it correct anyway).
+    const bool two_kinds = S.fused_is_fp32_cols();
+    const int exact_first = S.opt.fused_variant >= 100 ? 0 : kAsyncExactFirst;
+    for (int it = 0; it < S.pr.max_iter; ++it)
+        FS_HIP(S.enqueue_iteration(two_kinds && it < exact_first ? Solve::STREAM : S.default_kind()));
     if (!S.opt.skip_final_err) FS_HIP(S.enqueue_trailing());
     FS_HIP(launch_finalize(S.st, S.pots, S.state, f, g, S.opt.f64_out, S.opt.g64_out, result_dev, nullptr));
     return FS_OK;
@@ -376,7 +389,10 @@ fs_status run_solve_async(Solve &S, float *f, float *g, fs_result *result_dev) {
 int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result *result_host) {
     HostBlock *hb = dc->host;
     hb->flag = 0;
+    hb->hint = 0;
+    for (auto &h : hb->hints) h = 0;
     memset((void *)&hb->res, 0, sizeof(hb->res));
+    std::vector<int> sample_iter;
     void *hb_dev = nullptr;
     FS_HIP(hipHostGetDevicePointer(&hb_dev, (void *)hb, 0));
     S.host_flag = (volatile int32_t *)hb_dev;
@@ -385,27 +401,47 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     const int tevery = S.opt.time_kernel_every > 0 ? S.opt.time_kernel_every : 0;
     int nsamples = 0;
     g_timing = KernelTiming{};
+    // Dense solves whose fused kernel sums its column phase in fp32 run the exact streaming kernels
+    // while the device reports fast-moving potentials.  The hint used for block b is the one the
+    // device published at the end of the block whose completion the host has just waited for, so the
+    // sequence of kernels, and with it every bit of the result, does not depend on host timing.
+    const bool two_kinds = S.fused_is_fp32_cols();
+    const bool force_fused = S.opt.fused_variant >= 100;
+    int block_end[4] = {0, 0, 0, 0};
     int it = 0, blk = 0;
     while (it < S.pr.max_iter) {
         if (hb->flag) break;                           // the device has stopped: enqueue nothing more
-        if (blk >= 3) FS_HIP(hipEventSynchronize(dc->ev[(blk - 3) & 3]));   // bound the run-ahead to 3 blocks
+        Solve::Kind kind = S.default_kind();
+        int hint_block = -1;
+        if (blk >= 3) hint_block = blk - 3;            // bound the run-ahead to 3 blocks
+        else if (blk >= 1 && two_kinds && !force_fused) hint_block = 0;
+        if (hint_block >= 0) FS_HIP(hipEventSynchronize(dc->ev[hint_block & 3]));
         if (hb->flag) break;
-        const int nb = (S.pr.max_iter - it) < block ? (S.pr.max_iter - it) : block;
+        if (two_kinds && !force_fused) {
+            if (blk == 0) kind = Solve::STREAM;
+            else kind = hb->hints[block_end[hint_block & 3] & 63] ? Solve::FUSED : Solve::STREAM;
+        }
+        int nb = (blk == 0 && two_kinds && !force_fused) ? kFirstBlock : block;
+        if (nb > S.pr.max_iter - it) nb = S.pr.max_iter - it;
         for (int q = 0; q < nb; ++q) {
-            if (tevery && ((it + q) % tevery == 0) && nsamples < 4096) {
+            const bool sample = tevery && ((it + q) % tevery == 0) && nsamples < 4096 &&
+                                kind == S.default_kind();       // only the dominant kernel is timed
+            if (sample) {
                 while ((int)dc->timing.size() < 2 * (nsamples + 1)) {
                     hipEvent_t e;
                     FS_HIP(hipEventCreate(&e));
                     dc->timing.push_back(e);
                 }
-                FS_HIP(S.enqueue_iteration(dc->timing[2 * nsamples], dc->timing[2 * nsamples + 1]));
+                FS_HIP(S.enqueue_iteration(kind, dc->timing[2 * nsamples], dc->timing[2 * nsamples + 1]));
+                sample_iter.push_back(it + q);
                 ++nsamples;
             } else {
-                FS_HIP(S.enqueue_iteration());
+                FS_HIP(S.enqueue_iteration(kind));
             }
         }
         FS_HIP(hipEventRecord(dc->ev[blk & 3], S.st));
         it += nb;
+        block_end[blk & 3] = it;
         ++blk;
     }
     if (!S.opt.skip_final_err && !hb->flag) FS_HIP(S.enqueue_trailing());
@@ -417,7 +453,7 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
         double tot = 0.0;
         int used = 0;
         for (int q = 0; q < nsamples; ++q) {
-            if (q * tevery >= hb->res.iters) break;
+            if (sample_iter[q] >= hb->res.iters) break;
             float ms = 0.0f;
             FS_HIP(hipEventElapsedTime(&ms, dc->timing[2 * q], dc->timing[2 * q + 1]));
             tot += ms;
@@ -498,10 +534,10 @@ fs_status half_step(bool update_f, const float *C, const float *X, const float *
         FS_HIP(launch_points_prep(st, Y, m, d, S.pots.s, (double *)(S.ws + L.o_Yp), (double *)(S.ws + L.o_Ys), (double *)(S.ws + L.o_cy)));
     }
     if (update_f) {
-        FS_HIP(S.enqueue_f_update(0));                 // writes F into buffer 1
+        FS_HIP(S.enqueue_f_update(0, Solve::STREAM));  // writes F into buffer 1
         FS_HIP(launch_export(st, S.pots.F + L.n_ld, n, S.pots.s, out64));
     } else {
-        FS_HIP(S.enqueue_g_update());                  // reads U of buffer 1 (= the given f), writes G into buffer 1
+        FS_HIP(S.enqueue_g_update(Solve::STREAM));     // reads U of buffer 1 (= the given f), writes G into buffer 1
         FS_HIP(launch_export(st, S.pots.G + L.m_ld, m, S.pots.s, out64));
     }
     return FS_OK;

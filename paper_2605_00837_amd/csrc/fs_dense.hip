@@ -319,7 +319,7 @@ __global__ __launch_bounds__(T) void k_fused(DenseArgs A, Ctl c) {
 //                [2^-60, 2^60] (always, once the potentials move by less than ~40 eps per
 //                iteration) then F_new_i = rho_i + log2 S_i with no max pass at all.  Otherwise
 //                the panel is redone with the exact running-max form of Eq. 8.
-//   column phase, FAST mode.  With the new f the plan entry is pi_ij = e_ij * a_i / S_i, all of
+//   column phase With the new f the plan entry is pi_ij = e_ij * a_i / S_i, all of
 //                them in [0, 1].  The column pass is therefore one fused multiply-add per entry:
 //                T_j += e_ij * alpha_i, alpha_i = a_i / S_i, and the partial column LSE is
 //                log2 T_j - V_j.  This is the classical scaling form of Sinkhorn, usable here
@@ -327,10 +327,10 @@ __global__ __launch_bounds__(T) void k_fused(DenseArgs A, Ctl c) {
 //                loses a column only if that column's mass collapses by more than 2^60 in one
 //                iteration; the combine kernel detects exactly that (new G_j more than 60 below
 //                the old one, or not a number) and recomputes such columns from C.
-//   column phase, ROBUST mode.  Each column keeps a reference r_j that is a true running maximum,
-//                raised lazily when a sum would exceed 2^100; used while the potentials still move
-//                fast (the device switches modes by itself: FAST after an iteration in which at
-//                most 128 columns moved by more than 40, ROBUST otherwise).
+//   While the potentials still move fast (early iterations) the driver runs the exact streaming
+//   row and column kernels instead of this one; the device reports after every iteration whether
+//   at most 128 columns moved by more than 40 (base 2), and the driver follows that hint.  The hint
+//   only steers performance: this kernel plus the repair is correct in either regime.
 __device__ __forceinline__ void lds_only_barrier() {
 #if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("" ::: "memory");
@@ -348,14 +348,26 @@ __device__ __forceinline__ float bcast_f32(float x, int src_lane) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src_lane));
 }
 
-template <int Q, int R>
+constexpr int waitcnt_vm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }   // s_waitcnt vmcnt(n) only
+
+// FULLW: m == 4*Q*T, every lane owns valid columns.  Then every wave issues exactly R*Q + 5
+// prefetch loads per panel, which lets the kernel keep TWO panels in flight and wait with an
+// exact vmcnt (vmcnt retires in order: "at most R*Q + 5 outstanding" means "everything but the
+// youngest panel has landed").  Otherwise one panel is in flight and the wait is vmcnt(0).
+//
+// The per-row scalars of a panel (old F, log2 a, a) travel the same way as the panel itself:
+// lanes 0..R-1 of every wave fetch them with dword-sized HBM -> LDS loads next to the panel's
+// loads, so nothing that is prefetched occupies a register while it is in flight.
+template <int Q, int R, bool FULLW>
 __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     constexpr int T = 1024, NW = 16;
     static_assert(R * NW <= 64, "one wave merges all (row, wave) partials in one shot");
-    constexpr float kHi = 1.2676506e30f;      // 2^100
+    static_assert(5 * R <= 16, "scalar staging holds 16 dwords per wave");
+    constexpr int NDMA = R * Q + 5;            // loads per panel and wave (FULLW)
     constexpr float kRowHi = 1.1529215e18f;   // 2^60
     constexpr float kRowLo = 8.6736174e-19f;  // 2^-60
     __shared__ float4 stage[2][NW][R][Q][64];
+    __shared__ int scal[2][NW][16];            // [0,R) F lo  [R,2R) F hi  [2R,3R) la2 lo  [3R,4R) la2 hi  [4R,5R) a
     __shared__ float sSum[2][R][NW];
     __shared__ double sM[2][R][NW];
     __shared__ float sS[2][R][NW];
@@ -368,21 +380,21 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform, and the compiler knows it
     const double ns = -p.s;
     const bool col_phase = (c.phase == 0);
-    const bool fast_cols = A.force_fast || (__builtin_amdgcn_readfirstlane(c.st->mode) == kModeFast);
     const int m = p.m, n = p.n;
     const int rr = lane / NW;                  // the panel row this lane serves in the merge
-    bool colok[Q];
-#pragma unroll
-    for (int q = 0; q < Q; ++q) colok[q] = ((q * T + tid) * 4) < m;
+    const int rc = rr < R ? rr : R - 1;
+    auto colok = [&](int q) { return FULLW || ((q * T + tid) * 4) < m; };
 
     // Lanes whose columns lie past m never receive data (their loads are masked off); their staging
     // slots are cleared once so that they read as a finite cost and V = -inf removes them.
+    if (!FULLW) {
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int r = 0; r < R; ++r)
+            for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int q = 0; q < Q; ++q) stage[b][wave][r][q][lane] = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int q = 0; q < Q; ++q) stage[b][wave][r][q][lane] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
 
     double v[Q][4];
 #pragma unroll
@@ -390,74 +402,93 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
         const int col = (q * T + tid) * 4;
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            v[q][e] = col < m ? p.V[(size_t)cur * p.m_ld + col + e] : -__builtin_huge_val();
+            v[q][e] = colok(q) ? p.V[(size_t)cur * p.m_ld + col + e] : -__builtin_huge_val();
     }
-    float Tc[Q][4];                            // FAST: column sums of the plan entries
-    Lse cs[Q][4];                              // ROBUST: (r_j, s_j)
+    float cS[Q][4];                            // column sums of the plan entries
 #pragma unroll
     for (int q = 0; q < Q; ++q)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { Tc[q][e] = 0.0f; cs[q][e].init(); }
+        for (int e = 0; e < 4; ++e) cS[q][e] = 0.0f;
 
     const int npanels = (n + R - 1) / R;
     const bool rev = (k & 1) != 0;
     auto first_row = [&](int pq) { return (rev ? npanels - 1 - pq : pq) * R; };
-    // HBM -> LDS prefetch of one panel into staging buffer `buf`.  The buffer descriptor covers exactly
-    // the valid rows of the panel, so rows past n read as zero.
+    const __amdgpu_buffer_rsrc_t rsF = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(p.F + (size_t)cur * p.n_ld), 0, n * 8, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsL = __builtin_amdgcn_make_buffer_rsrc((void *)p.la2, 0, n * 8, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void *)p.a, 0, n * 4, 0x00020000);
+    // HBM -> LDS prefetch of one panel and of its row scalars into staging buffer `buf`.  The buffer
+    // descriptors cover exactly the valid rows, so rows past n read as zero.
     auto issue = [&](int pq, int buf) {
         const int i0 = first_row(pq);
         const int rows = (n - i0) < R ? (n - i0) : R;
+        // per-lane offsets stay loop-invariant (lane * 8, tid * 16); everything that changes from
+        // load to load goes through the scalar offset operand.  (The instruction's immediate offset
+        // is not used: it would shift the LDS destination as well as the memory address.)
+        if (lane < R) {
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsF, &scal[buf][wave][0], 4, lane * 8, i0 * 8, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsF, &scal[buf][wave][R], 4, lane * 8, i0 * 8 + 4, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsL, &scal[buf][wave][2 * R], 4, lane * 8, i0 * 8, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsL, &scal[buf][wave][3 * R], 4, lane * 8, i0 * 8 + 4, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, &scal[buf][wave][4 * R], 4, lane * 4, i0 * 4, 0, 0);
+        }
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             (void *)(A.C + (size_t)i0 * m), 0, rows * m * 4, 0x00020000);
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int q = 0; q < Q; ++q)
-                if (colok[q])
+                if (colok(q))
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, &stage[buf][wave][r][q][0], 16,
-                                                             (r * m + (q * T + tid) * 4) * 4, 0, 0, 0);
-    };
-    auto row_scalars = [&](int pq, double &rho, double &la2, float &aw) {
-        const int irow = first_row(pq) + rr;
-        const bool ok = rr < R && irow < n;
-        rho = ok ? p.F[(size_t)cur * p.n_ld + irow] : 0.0;
-        la2 = ok ? p.la2[irow] : -__builtin_huge_val();
-        aw = ok ? p.a[irow] : 0.0f;
+                                                             tid * 16, (r * m + q * T * 4) * 4, 0, 0);
     };
 
     int pq = blockIdx.x;
-    double rho_next = 0.0, la2_next = 0.0;
-    float a_next = 0.0f;
+    const int pstep = gridDim.x;
     if (pq < npanels) {
-        row_scalars(pq, rho_next, la2_next, a_next);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(0xc07f);        // the clearing stores above are done
         issue(pq, 0);
+        if (FULLW && pq + pstep < npanels) issue(pq + pstep, 1);
         asm volatile("" ::: "memory");
     }
     int buf = 0;
-    bool refs_set = false;                         // ROBUST: every column reference holds a true maximum
-    for (; pq < npanels; pq += gridDim.x, buf ^= 1) {
+    for (; pq < npanels; pq += pstep, buf ^= 1) {
         const int i0 = first_row(pq);
-        const int irow = i0 + rr;
-        const bool rowok = rr < R && irow < n;
-        __builtin_amdgcn_s_waitcnt(0x0f70);        // vmcnt(0): panel `pq` has landed in stage[buf], scalars too
-        asm volatile("" ::: "memory");             // no LDS read of the stage may move above the wait
-        const double rho_lane = rho_next, la2_lane = la2_next;
-        const float a_lane = a_next;
-        const int pq2 = pq + gridDim.x;
-        if (pq2 < npanels) {
-            row_scalars(pq2, rho_next, la2_next, a_next);  // older than the prefetch below: retires first
+        const int pq1 = pq + pstep, pq2 = pq + 2 * pstep;
+        // Panel `pq` and its row scalars must have landed.  FULLW: the only younger VMEM operations are
+        // the NDMA prefetch loads of the next panel (if there is one), which may stay in flight.
+        if (FULLW && pq1 < npanels) __builtin_amdgcn_s_waitcnt(waitcnt_vm(NDMA));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        asm volatile("" ::: "memory");             // no LDS read of the staging buffers may move above the wait
+        const int *sc = scal[buf][wave];
+        const bool rowok = rr < R && (i0 + rr) < n;
+        const double rho_lane = __hiloint2double(sc[R + rc], sc[rc]);
+        const double la2_lane = rowok ? __hiloint2double(sc[3 * R + rc], sc[2 * R + rc]) : -__builtin_huge_val();
+        const float a_lane = rowok ? __int_as_float(sc[4 * R + rc]) : 0.0f;
+        double rho[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) rho[r] = __hiloint2double(sc[R + r], sc[r]);
+        if (!FULLW && pq1 < npanels) {
             asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_waitcnt(0xc07f);    // every earlier read of stage[buf^1] has returned
-            issue(pq2, buf ^ 1);
+            __builtin_amdgcn_s_waitcnt(0xc07f);    // every earlier read of the other staging buffer has returned
+            issue(pq1, buf ^ 1);
             asm volatile("" ::: "memory");
         }
+        // FULLW: prefetch of the panel after next into the buffer this panel occupies, as soon as the
+        // last read of that buffer has returned
+        auto issue_ahead = [&]() {
+            if (FULLW && pq2 < npanels) {
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0xc07f);
+                issue(pq2, buf);
+                asm volatile("" ::: "memory");
+            }
+        };
         // ---- row phase, optimistic: e = 2^(x - rho_r), summed
         float ev[R][Q][4];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const double rho = bcast_f64(rho_lane, r * NW);
             float acc = 0.0f;
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
@@ -465,7 +496,7 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
                 const float cvv[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    ev[r][q][e] = fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - rho));
+                    ev[r][q][e] = fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - rho[r]));
                     acc += ev[r][q][e];
                 }
             }
@@ -473,7 +504,7 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
             if (lane == 0) sSum[buf][r][wave] = acc;
         }
         lds_only_barrier();
-        float S = rr < R ? sSum[buf][rr < R ? rr : 0][lane % NW] : 1.0f;
+        float S = rr < R ? sSum[buf][rc][lane % NW] : 1.0f;
         S += dpp_f32<0x128>(S);
         S += dpp_f32<0x124>(S);
         S += dpp_f32<0x122>(S);
@@ -484,6 +515,9 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
         if (__builtin_expect(!__all(fine || !rowok), 0)) {
             // ---- exact redo of the row phase of this panel (uniform over the workgroup: every wave
             //      sees the same sums)
+#ifdef FS_COUNT_SLOW
+            if (tid == 0) atomicAdd((unsigned *)c.st + 40, 1u);
+#endif
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 Lse rs; rs.init();
@@ -501,7 +535,7 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
             }
             lds_only_barrier();
             Lse t; t.init();
-            if (rr < R) { t.M = sM[buf][rr][lane % NW]; t.s = sS[buf][rr][lane % NW]; }
+            if (rr < R) { t.M = sM[buf][rc][lane % NW]; t.s = sS[buf][rc][lane % NW]; }
             double Mg = t.M;
             Mg = dmax(Mg, dpp_f64<0x128>(Mg));
             Mg = dmax(Mg, dpp_f64<0x124>(Mg));
@@ -514,7 +548,7 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
             sg += dpp_f32<0x121>(sg);
             Fn_lane = Mg + log2_sum(sg);
             alpha_lane = a_lane;                               // e is re-based on the new F below
-            if (col_phase && fast_cols) {
+            if (col_phase) {
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
                     const double Fn = bcast_f64(Fn_lane, r * NW);
@@ -530,72 +564,20 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
             }
         }
         if (wave == 0 && (lane % NW) == 0 && rowok) {
-            p.F[(size_t)nxt * p.n_ld + irow] = Fn_lane;
-            p.U[(size_t)nxt * p.n_ld + irow] = la2_lane - Fn_lane;
+            p.F[(size_t)nxt * p.n_ld + i0 + rr] = Fn_lane;
+            p.U[(size_t)nxt * p.n_ld + i0 + rr] = la2_lane - Fn_lane;
         }
-        // ---- column phase with the new f
+        // ---- column phase with the new f: nothing below reads the stage any more
+        issue_ahead();
         if (col_phase) {
-            if (fast_cols) {
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    float alpha = bcast_f32(alpha_lane, r * NW);
-                    if (!(alpha == alpha) || (i0 + r) >= n) alpha = 0.0f;   // rows past n, or a row whose F is not finite
+            for (int r = 0; r < R; ++r) {
+                float alpha = bcast_f32(alpha_lane, r * NW);
+                if (!(alpha == alpha) || (i0 + r) >= n) alpha = 0.0f;   // rows past n, or a row whose F is not finite
 #pragma unroll
-                    for (int q = 0; q < Q; ++q)
+                for (int q = 0; q < Q; ++q)
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) Tc[q][e] = fmaf(ev[r][q][e], alpha, Tc[q][e]);
-                }
-            } else {
-                const double u_lane = la2_lane - Fn_lane;          // -inf for rows past n
-                double u[R];
-#pragma unroll
-                for (int r = 0; r < R; ++r) u[r] = bcast_f64(u_lane, r * NW);
-                float tnew[Q][4];
-                float tall = 0.0f;                                 // sum of the (non-negative) candidate sums
-#pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    float cvv[R][4];
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        const float4 c4 = stage[buf][wave][r][q][lane];
-                        cvv[r][0] = c4.x; cvv[r][1] = c4.y; cvv[r][2] = c4.z; cvv[r][3] = c4.w;
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float t = cs[q][e].s;
-#pragma unroll
-                        for (int r = 0; r < R; ++r)
-                            t += fast_exp2((float)(fma(ns, (double)cvv[r][e], u[r]) - cs[q][e].M));
-                        tnew[q][e] = t;
-                        tall += t;
-                    }
-                }
-                // every candidate is >= 0, so tall <= 2^100 bounds each of them; inf and NaN fail the test
-                const bool cfine = refs_set && (tall <= kHi);
-                if (__builtin_expect(__all(cfine), 1)) {
-#pragma unroll
-                    for (int q = 0; q < Q; ++q)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) cs[q][e].s = tnew[q][e];
-                } else {
-#pragma unroll
-                    for (int q = 0; q < Q; ++q) {
-                        float cvv[R][4];
-#pragma unroll
-                        for (int r = 0; r < R; ++r) {
-                            const float4 c4 = stage[buf][wave][r][q][lane];
-                            cvv[r][0] = c4.x; cvv[r][1] = c4.y; cvv[r][2] = c4.z; cvv[r][3] = c4.w;
-                        }
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            double y[R];
-#pragma unroll
-                            for (int r = 0; r < R; ++r) y[r] = fma(ns, (double)cvv[r][e], u[r]);
-                            cs[q][e].template add<R>(y);
-                        }
-                    }
-                    refs_set = true;
-                }
+                    for (int e = 0; e < 4; ++e) cS[q][e] = fmaf(ev[r][q][e], alpha, cS[q][e]);
             }
         }
     }
@@ -603,12 +585,12 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             const int col = (q * T + tid) * 4;
-            if (col < m) {
+            if (colok(q)) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    // FAST: sum_i 2^(U_i - s C_ij) = T_j 2^(-V_j); a column of zero weight (V = -inf)
-                    // comes out as NaN here and is recomputed by the combine kernel
-                    const double part = fast_cols ? log2_sum(Tc[q][e]) - v[q][e] : cs[q][e].value();
+                    // sum_i 2^(U_i - s C_ij) = T_j 2^(-V_j); a column of zero weight (V = -inf) comes out
+                    // as NaN here and is recomputed by the combine kernel
+                    const double part = log2_sum(cS[q][e]) - v[q][e];
                     A.colpart[(size_t)blockIdx.x * p.m_ld + col + e] = part;
                 }
             }
@@ -630,6 +612,7 @@ static bool fused_shape(int m, int variant, FusedShape *fsh) {
         else if (variant == 2) *fsh = {1024, 2, 4};
         else if (variant == 3) *fsh = {512, 4, 2};
         else if (variant == 4) *fsh = {1024, 2, 2};
+        else if (variant == 5) *fsh = {1024, 2, 302};        // LDS prefetch, one panel in flight even at full width
         else *fsh = {1024, 2, 302};                          // asynchronous LDS prefetch, R = 2
         return true;
     }
@@ -646,7 +629,7 @@ void dense_fused_plan(int n, int m, int *P) {
     // the largest grid any variant uses: one panel set per resident workgroup
     FusedShape s{256, 1, 4};
     int best = 1;
-    for (int variant = 0; variant < 5; ++variant) {
+    for (int variant = 0; variant < 6; ++variant) {
         if (!fused_shape(m, variant, &s)) continue;
         const int npanels = (n + (s.R % 100) - 1) / (s.R % 100);
         const int resident = s.T == 256 ? 1024 : 256;      // workgroups the 256 CUs hold at once
@@ -665,9 +648,9 @@ hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, 
     if (g > a.P) g = a.P;
     DenseArgs b = a;
     b.P = g;
-    b.force_fast = variant >= 100 ? 1 : 0;                // test knob: FAST column mode from iteration 1
     const dim3 grid(g);
-    if (s.R == 302) hipLaunchKernelGGL((k_fused_pf<2, 2>), grid, dim3(1024), 0, st, b, c);
+    if (s.R == 302 && a.p.m == 8192 && variant % 100 != 5) hipLaunchKernelGGL((k_fused_pf<2, 2, true>), grid, dim3(1024), 0, st, b, c);
+    else if (s.R == 302) hipLaunchKernelGGL((k_fused_pf<2, 2, false>), grid, dim3(1024), 0, st, b, c);
     else if (s.T == 256) hipLaunchKernelGGL((k_fused<256, 1, 4>), grid, dim3(256), 0, st, b, c);
     else if (s.T == 1024 && s.Q == 1) hipLaunchKernelGGL((k_fused<1024, 1, 4>), grid, dim3(1024), 0, st, b, c);
     else if (s.T == 1024 && s.R == 2) hipLaunchKernelGGL((k_fused<1024, 2, 2>), grid, dim3(1024), 0, st, b, c);

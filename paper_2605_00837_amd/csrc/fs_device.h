@@ -30,8 +30,11 @@ struct alignas(256) State {
     int32_t nonfinite;
     uint32_t ticket;      // last-workgroup-done counter (returns to 0 after every use)
     int32_t err_valid;
-    int32_t mode;         // column mode of the fused dense pass for the next iteration (0 robust, 1 fast)
+    int32_t mode;         // hint for the driver after each iteration: 1 = the potentials move slowly (FAST)
     double err;           // err after `iters`
+    unsigned long long err_acc;   // fixed-point sum of the error terms of the iteration in progress
+    uint32_t bad_acc;     // workgroups whose error share was not a number
+    uint32_t big_acc;     // columns that moved by more than the FAST-mode threshold
 };
 
 // Constant description of one solve, passed by value to the kernels.
@@ -43,7 +46,7 @@ struct Ctl {
     float *err_history;       // device, may be null
     int32_t err_history_len;
     int32_t phase;            // 0: iteration kernel, 1: trailing error pass
-    volatile int32_t *host_flag;   // pinned host mirror of `done`, may be null
+    volatile int32_t *host_flag;   // pinned host mirror of {done, mode hint}, may be null
 };
 
 // Does this launch have work to do?  Iteration kernels run while k < max_iter,
@@ -178,9 +181,13 @@ struct Lse {
 // started from, i.e. err_k for k = st->k (Alg. 1: checked when k mod c == 0).
 __device__ __forceinline__ void advance_state(const Ctl &c, int k, double err, double big_cols) {
     State *st = c.st;
-    // fused dense pass: FAST column mode next time iff at most 128 columns moved by more than 40
-    // (base 2) this time; the few that still do are caught and recomputed by the combine kernel
-    st->mode = (big_cols <= 128.0) ? 1 : 0;
+    // hint for the driver: at most 128 columns moved by more than 40 (base 2) this time
+    const int hint = (big_cols <= 128.0) ? 1 : 0;
+    st->mode = hint;
+    if (c.host_flag) {                            // made visible by the completion of this kernel
+        c.host_flag[1] = hint;
+        c.host_flag[2 + ((k + 1) & 63)] = hint;
+    }
     if (c.err_history && k >= 1 && k - 1 < c.err_history_len) c.err_history[k - 1] = (float)err;
     const bool checked = (c.tol > 0.0) && (k >= 1) && (k % c.check_every == 0);
     bool stop = false;

@@ -24,13 +24,13 @@ struct DenseArgs {
     double *colpart;      // [P][m_ld] per-panel partial column LSE values
     int32_t P;            // number of row panels of the column pass
     int32_t rows_per_panel;
-    int32_t force_fast;   // 0 in production; test knob: FAST column mode whatever the device-side mode says
 };
 
-// Column modes of the fused pass, chosen on the device after every iteration (State::mode):
-// FAST after an iteration in which at most 128 columns moved by more than kFastBelow (base-2 units),
-// ROBUST otherwise.  In FAST mode a combined G_j that fell by more than kColRepairBelow (or is not a
-// number) may have lost terms to fp32 underflow and is recomputed exactly by the combine kernel.
+// The LDS-prefetch fused pass sums plan entries in fp32 (its column phase): a combined G_j that fell
+// by more than kColRepairBelow in one iteration (or is not a number) may have lost terms to fp32
+// underflow and is recomputed exactly by the combine kernel.  After every iteration the device
+// publishes a hint (State::mode): FAST if at most 128 columns moved by more than kFastBelow (base-2
+// units), ROBUST otherwise; the driver runs the exact streaming kernels while the hint says ROBUST.
 constexpr int kModeRobust = 0;
 constexpr int kModeFast = 1;
 constexpr double kFastBelow = 40.0;
@@ -60,13 +60,12 @@ struct CombineArgs {
     int32_t do_advance;       // 1: this is the g-update: also evaluate the error terms of Sec. 4.5 from
                               //    the old and new F, and let the last workgroup advance the state
     ErrSrc es;
-    // Repair of columns whose partials were formed in FAST column mode (fused dense pass): when
-    // repair_C is non-null and the iteration ran in FAST mode, a combined value more than
-    // kColRepairBelow under the old G_j (or NaN) is recomputed exactly from column j of C and the new U.
+    // Repair of columns whose partials come from the LDS-prefetch fused pass: when repair_C is
+    // non-null, a combined value more than kColRepairBelow under the old G_j (or NaN) is recomputed
+    // exactly from column j of C and the new U.
     const float *repair_C;    // n x len row-major, or null
     const double *repair_U;   // [2][repair_ld]
     int32_t repair_n, repair_ld;
-    int32_t force_fast;       // mirrors DenseArgs::force_fast
     double repair_s;
 };
 

@@ -17,6 +17,10 @@ __global__ __launch_bounds__(256) void k_init(Pots p, State *state, const float 
     if (t == 0) {
         state->k = 0; state->done = 0; state->iters = 0; state->converged = 0; state->nonfinite = 0;
         state->ticket = 0; state->err_valid = 0; state->mode = kModeRobust;
+        state->err_acc = 0; state->bad_acc = 0; state->big_acc = 0;
+#ifdef FS_COUNT_SLOW
+        reinterpret_cast<unsigned *>(state)[40] = 0;
+#endif
         state->err = __builtin_nan("");
     }
     double *la2 = const_cast<double *>(p.la2);
@@ -158,46 +162,61 @@ hipError_t launch_advance(hipStream_t st, const ErrSrc &es, const Ctl &c) {
 // ---------------------------------------------------------------- combine
 // out_j = LSE2_p part[p][j] (+ rowconst_j).  A workgroup of kCombW waves owns 64 adjacent entries;
 // wave w folds the partial sets p = w, w + kCombW, ... online (each read is one coalesced 512-byte
-// row segment, 8 independent loads in flight), the wave results meet in LDS.  The g-update's combine
-// also evaluates the error terms (spread over all its threads; per-workgroup sums are added up in
-// index order by whichever workgroup finishes last) and advances the iteration state.
+// row segment, up to 16 independent loads in flight per lane), the wave results meet in LDS.
+//
+// The g-update's combine also closes the iteration.  Its threads evaluate the error terms of
+// Sec. 4.5 (one row each); every workgroup adds its share to a 64-bit fixed-point accumulator in the
+// solver state (integer addition: the total does not depend on the order of arrival), counts its
+// fast-moving columns the same way, and takes a ticket; the workgroup that draws the last ticket
+// reads the totals, applies the stopping rule of Alg. 1 and resets the accumulators.
 constexpr int kCombW = 16;
 constexpr int kCombT = kCombW * 64;
-
-__device__ __forceinline__ double block_sum_comb(double v, double *lds) {
-    const int t = threadIdx.x;
-    __syncthreads();
-    lds[t] = v;
-    __syncthreads();
-    for (int w = kCombT / 2; w >= 1; w >>= 1) {
-        if (t < w) lds[t] += lds[t + w];
-        __syncthreads();
-    }
-    return lds[0];
-}
+constexpr double kErrScale = 288230376151711744.0;     // 2^58: err <= 16 fits, resolution 3.5e-18
 
 __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
-    __shared__ double lds[kCombT];
     __shared__ double sM[kCombW][64];
     __shared__ float sS[kCombW][64];
+    __shared__ double sErr[kCombW];
+    __shared__ double sBig[kCombW];
     __shared__ unsigned long long s_mask;
-    __shared__ int s_last;
     int k;
     if (!launch_active(c, k)) return;
     const int cur = k & 1, nxt = cur ^ 1;
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
     const int j = blockIdx.x * 64 + lane;
     const bool jok = j < A.len;
-    const bool fast_mode = A.repair_C && (A.force_fast || __builtin_amdgcn_readfirstlane(c.st->mode) == kModeFast);
+    const bool fast_mode = A.repair_C != nullptr;      // the partials come from the fp32 plan-unit column phase
+    // error term of one row per thread (the loads go out first, the partials follow)
+    double term = 0.0;
+    if (A.do_advance) {
+        double diff[2] = {0.0, 0.0};
+        float aw[2] = {0.0f, 0.0f};
+        const int stride = gridDim.x * kCombT;
+        const int i0 = blockIdx.x * kCombT + t;
+        const double *Fo = A.es.F + (size_t)cur * A.es.n_ld;
+        const double *Fn = A.es.F + (size_t)nxt * A.es.n_ld;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int i = i0 + q * stride;
+            if (i < A.es.n) { diff[q] = Fn[i] - Fo[i]; aw[q] = A.es.a[i]; }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+            if (aw[q] > 0.0f) term += (double)aw[q] * fabs(expm1(diff[q] * 0.6931471805599453094));
+        for (int i = i0 + 2 * stride; i < A.es.n; i += stride) {      // only when n > 2 * (threads of the grid)
+            const float a = A.es.a[i];
+            if (a > 0.0f) term += (double)a * fabs(expm1((Fn[i] - Fo[i]) * 0.6931471805599453094));
+        }
+    }
     double nbig = 0.0;                             // columns of this thread that moved by more than kFastBelow
     Lse acc; acc.init();
     if (jok) {
         int p = wave;
-        for (; p + 7 * kCombW < A.P; p += 8 * kCombW) {
-            double x[8];
+        for (; p + 15 * kCombW < A.P; p += 16 * kCombW) {
+            double x[16];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) x[q] = A.part[(size_t)(p + kCombW * q) * A.ld + j];
-            acc.add<8>(x);
+            for (int q = 0; q < 16; ++q) x[q] = A.part[(size_t)(p + kCombW * q) * A.ld + j];
+            acc.add<16>(x);
         }
         for (; p < A.P; p += kCombW) {
             double x[1] = {A.part[(size_t)p * A.ld + j]};
@@ -255,28 +274,28 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
         }
     }
     if (A.do_advance) {
-        const double part = block_sum_comb(err_terms(A.es, cur, blockIdx.x * kCombT + t, gridDim.x * kCombT), lds);
-        const double bbig = block_sum_comb(nbig, lds);
-        if (t == 0) {
-            A.es.errpart[blockIdx.x] = part;
-            A.es.errpart[gridDim.x + blockIdx.x] = bbig;
-            __threadfence();
-            const unsigned prev = atomicAdd(&c.st->ticket, 1u);
-            s_last = (prev == gridDim.x - 1) ? 1 : 0;
-        }
+        const double wsum = wave_sum_f64(term);
+        const double wbig = wave_sum_f64(nbig);
+        if (lane == 0) { sErr[wave] = wsum; sBig[wave] = wbig; }
         __syncthreads();
-        if (s_last) {
+        if (t == 0) {
+            double part = 0.0, big = 0.0;
+#pragma unroll
+            for (int w = 0; w < kCombW; ++w) { part += sErr[w]; big += sBig[w]; }
+            State *st = c.st;
+            if (part >= 0.0 && part <= 16.0) atomicAdd(&st->err_acc, (unsigned long long)(part * kErrScale));
+            else atomicAdd(&st->bad_acc, 1u);          // NaN or absurd: the error is reported as NaN
+            if (big > 0.0) atomicAdd(&st->big_acc, (unsigned)big);
             __threadfence();
-            double acc2 = 0.0, mv = 0.0;
-            for (int q = t; q < (int)gridDim.x; q += kCombT) {
-                acc2 += __hip_atomic_load(A.es.errpart + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                mv += __hip_atomic_load(A.es.errpart + gridDim.x + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            const double err = block_sum_comb(acc2, lds);
-            const double big_cols = block_sum_comb(mv, lds);
-            if (t == 0) {
-                c.st->ticket = 0;
-                advance_state(c, k, err, big_cols);
+            const unsigned prev = atomicAdd(&st->ticket, 1u);
+            if (prev == gridDim.x - 1) {
+                __threadfence();
+                const unsigned long long tot = __hip_atomic_load(&st->err_acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned bad = __hip_atomic_load(&st->bad_acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned bigc = __hip_atomic_load(&st->big_acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                st->err_acc = 0; st->bad_acc = 0; st->big_acc = 0; st->ticket = 0;
+                const double err = bad ? __builtin_nan("") : (double)tot / kErrScale;
+                advance_state(c, k, err, (double)bigc);
             }
         }
     }
