@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0
 
 def _traffic_from_profiles(n, m):
     """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary."""
-    path = os.path.join(ROOT, "profiles", "k_fused_c2_dense8192_pmc.json")
+    path = os.path.join(ROOT, "profiles", "k_fused_pf_c2_dense8192_pmc.json")
     try:
         with open(path) as fh:
             rec = json.load(fh)
