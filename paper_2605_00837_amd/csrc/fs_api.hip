@@ -107,6 +107,7 @@ struct DeviceCache {
     HostBlock *host = nullptr;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
     std::vector<hipEvent_t> timing;     // start/stop pairs for sampled kernel timing
+    hipStream_t cap_stream = nullptr;   // library-owned stream on which iteration blocks are captured
 };
 
 struct KernelTiming { float avg_ms = 0.0f; int samples = 0; const char *name = ""; };
@@ -124,6 +125,7 @@ fs_status get_cache(size_t need_bytes, DeviceCache **out) {
         FS_HIP(hipHostMalloc((void **)&c.host, sizeof(HostBlock), hipHostMallocDefault));
         memset((void *)c.host, 0, sizeof(HostBlock));
         for (auto &e : c.ev) FS_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        FS_HIP(hipStreamCreateWithFlags(&c.cap_stream, hipStreamNonBlocking));
     }
     if (c.ws_bytes < need_bytes) {
         if (c.ws) {
@@ -370,6 +372,35 @@ struct GraphKey {
     }
 };
 
+// A block of `nb` iterations captured once as a hipGraph and replayed.  The kernels take the
+// iteration index from device memory, so the same executable graph serves every block of the solve;
+// a replay that overshoots max_iter, or that runs after the stop flag is set, does nothing.  The block
+// is captured on a library-owned stream (the caller's may be the legacy default stream, which cannot
+// be captured) and launched on the caller's stream.  No memset node is ever recorded.
+struct BlockGraph {
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    ~BlockGraph() {
+        if (exec) (void)hipGraphExecDestroy(exec);
+        if (graph) (void)hipGraphDestroy(graph);
+    }
+};
+
+fs_status build_block_graph(const Solve &S, hipStream_t cap, Solve::Kind kind, int nb, BlockGraph *out) {
+    Solve T = S;
+    T.st = cap;
+    FS_HIP(hipStreamBeginCapture(cap, hipStreamCaptureModeThreadLocal));
+    hipError_t e = hipSuccess;
+    for (int q = 0; q < nb && e == hipSuccess; ++q) e = T.enqueue_iteration(kind);
+    hipGraph_t g = nullptr;
+    const hipError_t e2 = hipStreamEndCapture(cap, &g);
+    out->graph = g;
+    if (e != hipSuccess) { set_err("kernel launch failed during graph capture: %s", hipGetErrorString(e)); return FS_ERR_HIP; }
+    FS_HIP(e2);
+    FS_HIP(hipGraphInstantiate(&out->exec, out->graph, nullptr, nullptr, 0));
+    return FS_OK;
+}
+
 constexpr int kAsyncExactFirst = 4;     // asynchronous solves: exact streaming iterations before the fused kernel
 constexpr int kFirstBlock = 2;          // blocking solves: iterations before the first look at the pace hint
 
@@ -407,6 +438,12 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     // sequence of kernels, and with it every bit of the result, does not depend on host timing.
     const bool two_kinds = S.fused_is_fp32_cols();
     const bool force_fused = S.opt.fused_variant >= 100;
+    // Launch-bound sizes replay each block as one hipGraph (never while kernels are being timed).
+    const size_t cells = (size_t)S.pr.n * (size_t)S.pr.m;
+    const bool small = S.mode == 3 ? cells <= ((size_t)1 << 24) : cells <= ((size_t)1 << 22);
+    const bool use_graph = !tevery && S.pr.max_iter >= block &&
+                           (S.opt.use_graph == 2 || (S.opt.use_graph == 0 && small));
+    BlockGraph graphs[3];                              // indexed by kind
     int block_end[4] = {0, 0, 0, 0};
     int it = 0, blk = 0;
     while (it < S.pr.max_iter) {
@@ -423,6 +460,14 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
         }
         int nb = (blk == 0 && two_kinds && !force_fused) ? kFirstBlock : block;
         if (nb > S.pr.max_iter - it) nb = S.pr.max_iter - it;
+        if (use_graph && nb == block) {
+            BlockGraph &bg = graphs[(int)kind];
+            if (!bg.exec) {
+                const fs_status gs = build_block_graph(S, dc->cap_stream, kind, block, &bg);
+                if (gs != FS_OK) return gs;
+            }
+            FS_HIP(hipGraphLaunch(bg.exec, S.st));
+        } else
         for (int q = 0; q < nb; ++q) {
             const bool sample = tevery && ((it + q) % tevery == 0) && nsamples < 4096 &&
                                 kind == S.default_kind();       // only the dominant kernel is timed
@@ -563,6 +608,7 @@ void fs_clear_cache(void) {
         if (c.host) (void)hipHostFree((void *)c.host);
         for (auto &e : c.ev) if (e) (void)hipEventDestroy(e);
         for (auto &e : c.timing) (void)hipEventDestroy(e);
+        if (c.cap_stream) (void)hipStreamDestroy(c.cap_stream);
         (void)hipSetDevice(cur);
     }
     g_cache.clear();

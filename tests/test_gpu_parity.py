@@ -196,6 +196,26 @@ def test_warm_start_resume_and_determinism(fs, kind, mode):
     assert torch.equal(r4["f64"], r3["f64"]) and torch.equal(r4["g"], r3["g"])
 
 
+@pytest.mark.parametrize("kind,mode", [("dense", 1), ("dense", 2), ("points", 0)])
+def test_graph_replayed_blocks_match_plain_launches(fs, kind, mode):
+    """Blocks of check_every iterations replayed as one hipGraph: several solves in a row, eager work and
+    synchronisations between them, fixed-count and stop-by-tolerance; every one must equal the
+    plain-launch result bit for bit."""
+    import torch
+    w = W.random_dense(96, 256, seed=29, eps=0.05) if kind == "dense" else W.random_points(96, 250, 3, seed=29, eps=0.05)
+    geo, a, b = to_dev(w)
+    for max_iter, tol in ((37, 0.0), (400, 1e-5), (60, 0.0)):
+        ref = fs.fs_sinkhorn_solve(a, b, w.eps, max_iter, tol, want_f64=True, kernel_mode=mode, use_graph=1, **geo)
+        for rep in range(3):
+            junk = (torch.rand(1000, device="cuda") * 2).sum()       # unrelated eager work between replays
+            r = fs.fs_sinkhorn_solve(a, b, w.eps, max_iter, tol, want_f64=True, kernel_mode=mode, use_graph=2, **geo)
+            torch.cuda.synchronize()
+            assert r["iters"] == ref["iters"] and r["converged"] == ref["converged"]
+            assert torch.equal(r["f64"], ref["f64"]) and torch.equal(r["g64"], ref["g64"])
+            assert r["marginal_err"] == ref["marginal_err"] or (math.isnan(r["marginal_err"]) and math.isnan(ref["marginal_err"]))
+            assert float(junk) > 0
+
+
 def test_blocking_and_async_entry_points_agree(fs):
     import torch
     w = W.random_dense(200, 512, seed=23, eps=0.05)
