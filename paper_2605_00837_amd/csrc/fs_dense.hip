@@ -586,13 +586,11 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
         for (int q = 0; q < Q; ++q) {
             const int col = (q * T + tid) * 4;
             if (colok(q)) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    // sum_i 2^(U_i - s C_ij) = T_j 2^(-V_j); a column of zero weight (V = -inf) comes out
-                    // as NaN here and is recomputed by the combine kernel
-                    const double part = log2_sum(cS[q][e]) - v[q][e];
-                    A.colpart[(size_t)blockIdx.x * p.m_ld + col + e] = part;
-                }
+                // The partial of this workgroup is the plain fp32 sum T_j of its plan entries: all
+                // workgroups share the reference V_j, so the combine kernel only has to add them up
+                // (G_j = log2 sum_p T_j - V_j).
+                float *row = reinterpret_cast<float *>(A.colpart) + (size_t)blockIdx.x * p.m_ld + col;
+                *reinterpret_cast<float4 *>(row) = make_float4(cS[q][0], cS[q][1], cS[q][2], cS[q][3]);
             }
         }
     }

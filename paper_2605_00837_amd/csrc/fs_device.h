@@ -73,6 +73,13 @@ __device__ __forceinline__ double log2_sum(float s) {
     return (double)e + (double)__builtin_amdgcn_logf(mant);
 }
 
+// same for a sum held in double precision (it may lie below the fp32 range)
+__device__ __forceinline__ double log2_sum(double s) {
+    const int e = __builtin_amdgcn_frexp_exp(s);
+    const float mant = (float)__builtin_amdgcn_frexp_mant(s);
+    return (double)e + (double)__builtin_amdgcn_logf(mant);
+}
+
 __device__ __forceinline__ double dmax(double a, double b) { return fmax(a, b); }
 
 // log2 of an fp32 weight in double precision; zero (or negative) weight -> -inf.

@@ -210,7 +210,20 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
     }
     double nbig = 0.0;                             // columns of this thread that moved by more than kFastBelow
     Lse acc; acc.init();
-    if (jok) {
+    double tsum = 0.0;                             // fp32-sum partials: plain total
+    if (jok && fast_mode) {
+        // partials are fp32 sums against a common reference: add them up (in double)
+        const float *pf = reinterpret_cast<const float *>(A.part);
+        int p = wave;
+        for (; p + 15 * kCombW < A.P; p += 16 * kCombW) {
+            float x[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) x[q] = pf[(size_t)(p + kCombW * q) * A.ld + j];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) tsum += (double)x[q];
+        }
+        for (; p < A.P; p += kCombW) tsum += (double)pf[(size_t)p * A.ld + j];
+    } else if (jok) {
         int p = wave;
         for (; p + 15 * kCombW < A.P; p += 16 * kCombW) {
             double x[16];
@@ -223,15 +236,22 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
             acc.add<1>(x);
         }
     }
-    sM[wave][lane] = acc.M;
+    sM[wave][lane] = fast_mode ? tsum : acc.M;
     sS[wave][lane] = acc.s;
     __syncthreads();
     if (wave == 0) {
         bool suspect = false;
         if (jok) {
+            double out;
+            if (fast_mode) {
 #pragma unroll
-            for (int w = 1; w < kCombW; ++w) acc.merge(sM[w][lane], sS[w][lane]);
-            double out = acc.value();                  // -inf when every term was -inf
+                for (int w = 1; w < kCombW; ++w) tsum += sM[w][lane];
+                out = log2_sum(tsum) - A.shift[(size_t)cur * A.ld + j];     // log2 T_j - V_j (NaN if V_j = -inf)
+            } else {
+#pragma unroll
+                for (int w = 1; w < kCombW; ++w) acc.merge(sM[w][lane], sS[w][lane]);
+                out = acc.value();                     // -inf when every term was -inf
+            }
             if (A.rowconst) out += A.rowconst[j];
             const double old = A.pot[(size_t)cur * A.ld + j];
             // FAST column mode sums plan entries in fp32: a column whose G fell by more than 2^60
