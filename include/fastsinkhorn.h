@@ -19,14 +19,16 @@
  *     m x d, row-major fp32; the cost is then the squared Euclidean distance
  *     ||x_i - y_j||^2 and is recomputed on the fly, never stored.
  *   - a[n], b[m] are fp32 weights (non-negative; a zero weight carries no mass).
+ *     They are meant to sum to 1 each: the marginal error is accumulated in fixed
+ *     point and reported as NaN once it reaches 16.
  *     f[n], g[m] are fp32 potentials.  eps is the regularisation (> 0).
  *   - tol <= 0 means: run exactly max_iter iterations.  tol > 0 means: stop at
  *     the first iteration k with k mod check_every == 0 and err_k < tol, or at
  *     max_iter (Alg. 1).  The returned potentials are those after exactly
  *     `iters` iterations.
  *   - Scalars are validated on the host before anything is enqueued
- *     (n, m >= 1; eps > 0 and finite; max_iter >= 0; 1 <= d <= FS_MAX_DIM;
- *     non-null pointers); a violation returns FS_ERR_INVALID_ARG.  Array
+ *     (1 <= n, m <= FS_MAX_POINTS; eps > 0 and finite; max_iter >= 0;
+ *     1 <= d <= FS_MAX_DIM; non-null pointers); a violation returns FS_ERR_INVALID_ARG.  Array
  *     contents are the caller's responsibility; non-finite potentials are
  *     reported through fs_result.nonfinite, never by aborting.
  *   - No exception crosses this boundary.  fs_last_error() returns a
@@ -48,6 +50,7 @@ extern "C" {
 typedef void *fs_stream;
 
 #define FS_MAX_DIM 64
+#define FS_MAX_POINTS 1048512   /* 16383 * 64 */
 
 typedef enum {
     FS_OK = 0,

@@ -318,8 +318,8 @@ fs_status validate(const Problem &p, const float *f, const float *g) {
         if (!p.X || !p.Y) { set_err("X and Y must both be non-null"); return FS_ERR_INVALID_ARG; }
         if (p.d < 1 || p.d > FS_MAX_DIM) { set_err("d must be in [1, %d] (got %d)", FS_MAX_DIM, p.d); return FS_ERR_INVALID_ARG; }
     }
-    if ((size_t)p.n > ((size_t)1 << 30) || (size_t)p.m > ((size_t)1 << 30)) {
-        set_err("n and m are limited to 2^30"); return FS_ERR_INVALID_ARG;
+    if (p.n > FS_MAX_POINTS || p.m > FS_MAX_POINTS) {
+        set_err("n and m are limited to %d", FS_MAX_POINTS); return FS_ERR_INVALID_ARG;
     }
     return FS_OK;
 }

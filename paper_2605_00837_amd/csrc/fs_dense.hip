@@ -515,9 +515,6 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
         if (__builtin_expect(!__all(fine || !rowok), 0)) {
             // ---- exact redo of the row phase of this panel (uniform over the workgroup: every wave
             //      sees the same sums)
-#ifdef FS_COUNT_SLOW
-            if (tid == 0) atomicAdd((unsigned *)c.st + 40, 1u);
-#endif
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 Lse rs; rs.init();

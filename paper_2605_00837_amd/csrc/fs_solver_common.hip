@@ -16,11 +16,9 @@ __global__ __launch_bounds__(256) void k_init(Pots p, State *state, const float 
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t == 0) {
         state->k = 0; state->done = 0; state->iters = 0; state->converged = 0; state->nonfinite = 0;
-        state->ticket = 0; state->err_valid = 0; state->mode = kModeRobust;
-        state->err_acc = 0; state->bad_acc = 0; state->big_acc = 0;
-#ifdef FS_COUNT_SLOW
-        reinterpret_cast<unsigned *>(state)[40] = 0;
-#endif
+        state->reserved0 = 0; state->err_valid = 0; state->mode = kModeRobust;
+        state->err_acc = 0; state->reserved1 = 0;
+        state->big_acc[0] = 0; state->big_acc[1] = 0x7fffffffu;   // no count yet: the first hint says ROBUST
         state->err = __builtin_nan("");
     }
     double *la2 = const_cast<double *>(p.la2);
@@ -161,113 +159,212 @@ hipError_t launch_advance(hipStream_t st, const ErrSrc &es, const Ctl &c) {
 
 // ---------------------------------------------------------------- combine
 // out_j = LSE2_p part[p][j] (+ rowconst_j).  A workgroup of kCombW waves owns 64 adjacent entries;
-// wave w folds the partial sets p = w, w + kCombW, ... online (each read is one coalesced 512-byte
-// row segment, up to 16 independent loads in flight per lane), the wave results meet in LDS.
+// wave w folds the partial sets p = w, w + kCombW, ... (each read is one coalesced row segment, 16
+// independent loads in flight per lane), the wave results meet in LDS and wave 0 finishes the columns.
+// Partials of the LDS-prefetch fused pass are plain fp32 sums against a common reference and are
+// simply added up.
 //
-// The g-update's combine also closes the iteration.  Its threads evaluate the error terms of
-// Sec. 4.5 (one row each); every workgroup adds its share to a 64-bit fixed-point accumulator in the
-// solver state (integer addition: the total does not depend on the order of arrival), counts its
-// fast-moving columns the same way, and takes a ticket; the workgroup that draws the last ticket
-// reads the totals, applies the stopping rule of Alg. 1 and resets the accumulators.
+// The g-update's combine also closes the iteration, on a second track that runs beside the column
+// work: wave 1 of every workgroup evaluates the error terms of Sec. 4.5 for 64 rows and reports their
+// sum with one atomic addition to the closing word of the solver state, which carries a fixed-point
+// sum (integer addition: the total does not depend on the order of arrival) above a count of the
+// workgroups that have reported.  The workgroup whose addition completes the count holds the total
+// in the value the atomic returned; it applies the stopping rule of Alg. 1 and resets the word.  The count of fast-moving
+// columns that steers the driver's choice of kernels is collected per parity of the iteration and
+// read one iteration late, so that it never waits for the column work either.
+//
+// The kernel is a chain of memory latencies, so every load whose address does not depend on the
+// iteration counter is issued before the counter itself has arrived.
 constexpr int kCombW = 16;
 constexpr int kCombT = kCombW * 64;
-constexpr double kErrScale = 288230376151711744.0;     // 2^58: err <= 16 fits, resolution 3.5e-18
+constexpr int kErrWave = 1;
+constexpr int kTicketBits = 14;                        // up to 16383 workgroups
+constexpr double kErrScale = 35184372088832.0;         // 2^45: sums below 16 fit in bits 14..62, resolution 2.8e-14
+constexpr unsigned long long kErrBad = 1ull << 63;
+constexpr double kLn2 = 0.6931471805599453094;
+
+#ifdef FS_TS
+__device__ unsigned long long g_ts[256 * 8];
+#define TS(w, i) do { if (threadIdx.x == (w) * 64) g_ts[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define TS(w, i)
+#endif
 
 __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
     __shared__ double sM[kCombW][64];
     __shared__ float sS[kCombW][64];
-    __shared__ double sErr[kCombW];
-    __shared__ double sBig[kCombW];
     __shared__ unsigned long long s_mask;
-    int k;
-    if (!launch_active(c, k)) return;
-    const int cur = k & 1, nxt = cur ^ 1;
+    TS(0, 0);
+    const volatile State *vst = c.st;
+    const int k_ld = vst->k, done_ld = vst->done;
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
     const int j = blockIdx.x * 64 + lane;
     const bool jok = j < A.len;
     const bool fast_mode = A.repair_C != nullptr;      // the partials come from the fp32 plan-unit column phase
-    // error term of one row per thread (the loads go out first, the partials follow)
-    double term = 0.0;
-    if (A.do_advance) {
-        double diff[2] = {0.0, 0.0};
-        float aw[2] = {0.0f, 0.0f};
-        const int stride = gridDim.x * kCombT;
-        const int i0 = blockIdx.x * kCombT + t;
-        const double *Fo = A.es.F + (size_t)cur * A.es.n_ld;
-        const double *Fn = A.es.F + (size_t)nxt * A.es.n_ld;
+    const bool err_wave = A.do_advance && wave == kErrWave;
+    const float *pf = reinterpret_cast<const float *>(A.part);
+    // first batch of partial sets p = wave, wave + kCombW, ...
+    const bool batch = jok && (wave + 15 * kCombW < A.P);
+    float xf[16];
+    double xd[16];
+    if (batch) {
+        if (fast_mode) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int i = i0 + q * stride;
-            if (i < A.es.n) { diff[q] = Fn[i] - Fo[i]; aw[q] = A.es.a[i]; }
-        }
+            for (int q = 0; q < 16; ++q) xf[q] = pf[(size_t)(wave + kCombW * q) * A.ld + j];
+        } else {
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
-            if (aw[q] > 0.0f) term += (double)aw[q] * fabs(expm1(diff[q] * 0.6931471805599453094));
-        for (int i = i0 + 2 * stride; i < A.es.n; i += stride) {      // only when n > 2 * (threads of the grid)
-            const float a = A.es.a[i];
-            if (a > 0.0f) term += (double)a * fabs(expm1((Fn[i] - Fo[i]) * 0.6931471805599453094));
+            for (int q = 0; q < 16; ++q) xd[q] = A.part[(size_t)(wave + kCombW * q) * A.ld + j];
         }
     }
-    double nbig = 0.0;                             // columns of this thread that moved by more than kFastBelow
+    // rows of the error sum: 64 per workgroup and round (both copies of F; the counter says which is new)
+    const int estride = gridDim.x * 64;
+    const int ei0 = blockIdx.x * 64 + lane;
+    double F0[2] = {0.0, 0.0}, F1[2] = {0.0, 0.0};
+    float aw[2] = {0.0f, 0.0f};
+    if (err_wave) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int i = ei0 + q * estride;
+            if (i < A.es.n) { F0[q] = A.es.F[i]; F1[q] = A.es.F[(size_t)A.es.n_ld + i]; aw[q] = A.es.a[i]; }
+        }
+    }
+    unsigned big_ld[2] = {0u, 0u};
+    if (err_wave && lane == 0) {
+        big_ld[0] = __hip_atomic_load(&c.st->big_acc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        big_ld[1] = __hip_atomic_load(&c.st->big_acc[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    double lw2_j = 0.0, rowconst_j = 0.0, pot_j[2] = {0.0, 0.0}, shift_b[2] = {0.0, 0.0};
+    if (wave == 0 && jok) {
+        lw2_j = A.lw2[j];
+        if (A.rowconst) rowconst_j = A.rowconst[j];
+        pot_j[0] = A.pot[j];
+        pot_j[1] = A.pot[(size_t)A.ld + j];
+        if (fast_mode) { shift_b[0] = A.shift[j]; shift_b[1] = A.shift[(size_t)A.ld + j]; }
+    }
+
+    // ---- everything that needs no counter
     Lse acc; acc.init();
-    double tsum = 0.0;                             // fp32-sum partials: plain total
-    if (jok && fast_mode) {
-        // partials are fp32 sums against a common reference: add them up (in double)
-        const float *pf = reinterpret_cast<const float *>(A.part);
+    double tsum = 0.0;                             // fp32-sum partials: plain total (in double)
+    if (jok) {
         int p = wave;
-        for (; p + 15 * kCombW < A.P; p += 16 * kCombW) {
-            float x[16];
+        if (fast_mode) {
+            if (batch) {
 #pragma unroll
-            for (int q = 0; q < 16; ++q) x[q] = pf[(size_t)(p + kCombW * q) * A.ld + j];
+                for (int q = 0; q < 16; ++q) tsum += (double)xf[q];
+                p += 16 * kCombW;
+            }
+            for (; p + 15 * kCombW < A.P; p += 16 * kCombW) {
 #pragma unroll
-            for (int q = 0; q < 16; ++q) tsum += (double)x[q];
-        }
-        for (; p < A.P; p += kCombW) tsum += (double)pf[(size_t)p * A.ld + j];
-    } else if (jok) {
-        int p = wave;
-        for (; p + 15 * kCombW < A.P; p += 16 * kCombW) {
-            double x[16];
+                for (int q = 0; q < 16; ++q) xf[q] = pf[(size_t)(p + kCombW * q) * A.ld + j];
 #pragma unroll
-            for (int q = 0; q < 16; ++q) x[q] = A.part[(size_t)(p + kCombW * q) * A.ld + j];
-            acc.add<16>(x);
+                for (int q = 0; q < 16; ++q) tsum += (double)xf[q];
+            }
+            for (; p < A.P; p += kCombW) tsum += (double)pf[(size_t)p * A.ld + j];
+        } else {
+            if (batch) {
+                acc.add<16>(xd);
+                p += 16 * kCombW;
+            }
+            for (; p + 15 * kCombW < A.P; p += 16 * kCombW) {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) xd[q] = A.part[(size_t)(p + kCombW * q) * A.ld + j];
+                acc.add<16>(xd);
+            }
+            for (; p < A.P; p += kCombW) {
+                double x[1] = {A.part[(size_t)p * A.ld + j]};
+                acc.add<1>(x);
+            }
         }
-        for (; p < A.P; p += kCombW) {
-            double x[1] = {A.part[(size_t)p * A.ld + j]};
-            acc.add<1>(x);
+    }
+    // error terms a_i |2^(Fnew_i - Fold_i) - 1| in fp64 (expm1 for the small differences near
+    // convergence), for either role of the two copies of F
+    double term_if[2] = {0.0, 0.0};                // [0]: copy 1 is the new one, [1]: copy 0 is
+    if (err_wave) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            if (aw[q] > 0.0f) {
+                const double x = (F1[q] - F0[q]) * kLn2;
+                term_if[0] += (double)aw[q] * fabs(expm1(x));
+                term_if[1] += (double)aw[q] * fabs(expm1(-x));
+            }
         }
+    }
+
+    const int k = __builtin_amdgcn_readfirstlane(k_ld);
+    if (__builtin_amdgcn_readfirstlane(done_ld)) return;
+    if (c.phase == 0 ? !(k < c.max_iter) : !(k == c.max_iter)) return;
+    const int cur = k & 1, nxt = cur ^ 1;
+    TS(1, 1); TS(0, 5);
+    State *st = c.st;
+
+    double err_part = 0.0;
+    if (err_wave) {
+        double term = term_if[cur];
+        const double *Fo = A.es.F + (size_t)cur * A.es.n_ld;
+        const double *Fn = A.es.F + (size_t)nxt * A.es.n_ld;
+        for (int i = ei0 + 2 * estride; i < A.es.n; i += estride) {   // only when n > 128 * (workgroups of the grid)
+            const float a = A.es.a[i];
+            if (a > 0.0f) term += (double)a * fabs(expm1((Fn[i] - Fo[i]) * kLn2));
+        }
+        err_part = wave_sum_f64(term);
     }
     sM[wave][lane] = fast_mode ? tsum : acc.M;
     sS[wave][lane] = acc.s;
-    __syncthreads();
+    __syncthreads();                                   // also: every wave of the workgroup has read the counter
+
+    if (err_wave && lane == 0) {
+        // close the iteration.  A share that is not a number (or absurd) sets the flag bit first; the two
+        // atomics go to the same address, so they are performed in this order.
+        unsigned long long add = 1;
+        if (err_part >= 0.0 && err_part <= 4.0) add += (unsigned long long)(err_part * kErrScale) << kTicketBits;
+        else atomicOr(&st->err_acc, kErrBad);
+        const unsigned long long word = atomicAdd(&st->err_acc, add) + add;
+        TS(1, 2);
+        if ((word & ((1ull << kTicketBits) - 1)) == gridDim.x) {
+            // fast-moving columns of the previous iteration (complete since the previous launch, read above)
+            const unsigned bigc = cur ? big_ld[0] : big_ld[1];
+            st->err_acc = 0; st->big_acc[nxt] = 0;
+            const double err = (word & kErrBad) ? __builtin_nan("")
+                                                : (double)((word & ~kErrBad) >> kTicketBits) / kErrScale;
+            advance_state(c, k, err, (double)bigc);
+            TS(1, 3);
+        }
+    }
     if (wave == 0) {
         bool suspect = false;
+        double nbig = 0.0;                             // 1 if this column moved by more than kFastBelow
         if (jok) {
+            const double old_j = cur ? pot_j[1] : pot_j[0];
             double out;
             if (fast_mode) {
 #pragma unroll
                 for (int w = 1; w < kCombW; ++w) tsum += sM[w][lane];
-                out = log2_sum(tsum) - A.shift[(size_t)cur * A.ld + j];     // log2 T_j - V_j (NaN if V_j = -inf)
+                out = log2_sum(tsum) - (cur ? shift_b[1] : shift_b[0]);      // log2 T_j - V_j (NaN if V_j = -inf)
             } else {
 #pragma unroll
                 for (int w = 1; w < kCombW; ++w) acc.merge(sM[w][lane], sS[w][lane]);
                 out = acc.value();                     // -inf when every term was -inf
             }
-            if (A.rowconst) out += A.rowconst[j];
-            const double old = A.pot[(size_t)cur * A.ld + j];
+            out += rowconst_j;
             // FAST column mode sums plan entries in fp32: a column whose G fell by more than 2^60
             // in one iteration (or is not a number) may have lost terms to underflow
-            if (fast_mode) suspect = !(out >= old - kColRepairBelow);
-            nbig = suspect ? 1.0 : big_move(out - old);
+            if (fast_mode) suspect = !(out >= old_j - kColRepairBelow);
+            nbig = suspect ? 1.0 : big_move(out - old_j);
             A.pot[(size_t)nxt * A.ld + j] = out;
-            A.shift[(size_t)nxt * A.ld + j] = A.lw2[j] - out;
+            A.shift[(size_t)nxt * A.ld + j] = lw2_j - out;
         }
         const unsigned long long mask = __ballot(suspect);
         if (lane == 0) s_mask = mask;
+        if (A.do_advance) {
+            const double wbig = wave_sum_f64(nbig);
+            if (lane == 0 && wbig > 0.0) atomicAdd(&st->big_acc[cur], (unsigned)wbig);
+        }
+        TS(0, 4);
     }
     if (fast_mode) {
         // ---- exact recomputation of the suspect columns of this workgroup (rare): all threads walk
         //      down column j of C with the new U, online LSE per thread, then wave + LDS merge
-        __syncthreads();
+        __syncthreads();                               // s_mask is visible
         unsigned long long todo = s_mask;
         const double *U = A.repair_U + (size_t)nxt * A.repair_ld;
         while (todo) {
@@ -287,41 +384,19 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
                 Lse tot; tot.init();
 #pragma unroll
                 for (int w = 0; w < kCombW; ++w) tot.merge(sM[w][0], sS[w][0]);
-                const double out = tot.value();
+                const double out = tot.value() + (A.rowconst ? A.rowconst[jj] : 0.0);
                 A.pot[(size_t)nxt * A.ld + jj] = out;
                 A.shift[(size_t)nxt * A.ld + jj] = A.lw2[jj] - out;
             }
         }
     }
-    if (A.do_advance) {
-        const double wsum = wave_sum_f64(term);
-        const double wbig = wave_sum_f64(nbig);
-        if (lane == 0) { sErr[wave] = wsum; sBig[wave] = wbig; }
-        __syncthreads();
-        if (t == 0) {
-            double part = 0.0, big = 0.0;
-#pragma unroll
-            for (int w = 0; w < kCombW; ++w) { part += sErr[w]; big += sBig[w]; }
-            State *st = c.st;
-            if (part >= 0.0 && part <= 16.0) atomicAdd(&st->err_acc, (unsigned long long)(part * kErrScale));
-            else atomicAdd(&st->bad_acc, 1u);          // NaN or absurd: the error is reported as NaN
-            if (big > 0.0) atomicAdd(&st->big_acc, (unsigned)big);
-            __threadfence();
-            const unsigned prev = atomicAdd(&st->ticket, 1u);
-            if (prev == gridDim.x - 1) {
-                __threadfence();
-                const unsigned long long tot = __hip_atomic_load(&st->err_acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const unsigned bad = __hip_atomic_load(&st->bad_acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const unsigned bigc = __hip_atomic_load(&st->big_acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                st->err_acc = 0; st->bad_acc = 0; st->big_acc = 0; st->ticket = 0;
-                const double err = bad ? __builtin_nan("") : (double)tot / kErrScale;
-                advance_state(c, k, err, (double)bigc);
-            }
-        }
-    }
 }
 
+#ifdef FS_TS
+extern "C" int fs_debug_ts(unsigned long long *out) { return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_ts), sizeof(g_ts)); }
+#endif
 hipError_t launch_combine(hipStream_t st, const CombineArgs &a, const Ctl &c) {
+    if ((a.len + 63) / 64 >= (1 << kTicketBits)) return hipErrorInvalidValue;     // the ticket field would overflow
     hipLaunchKernelGGL(k_combine, dim3((a.len + 63) / 64), dim3(kCombT), 0, st, a, c);
     return hipGetLastError();
 }
