@@ -371,10 +371,12 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     __shared__ float sSum[2][R][NW];
     __shared__ double sM[2][R][NW];
     __shared__ float sS[2][R][NW];
-    int k;
-    if (!launch_active(c, k)) return;
+    __shared__ int scalF0[NW][4];              // old F of the first panel, for either parity of the counter
 #if defined(__HIP_DEVICE_COMPILE__)
-    const int cur = k & 1, nxt = cur ^ 1;
+    // Everything whose address does not depend on the iteration counter is requested before the
+    // counter itself has arrived: the first panel of this workgroup (always the same one), its row
+    // scalars (old F from both buffers) and both copies of V.
+    const unsigned long long kd = load_counter(c);
     const Pots &p = A.p;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform, and the compiler knows it
@@ -396,38 +398,25 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
                 for (int q = 0; q < Q; ++q) stage[b][wave][r][q][lane] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
 
-    double v[Q][4];
-#pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        const int col = (q * T + tid) * 4;
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            v[q][e] = colok(q) ? p.V[(size_t)cur * p.m_ld + col + e] : -__builtin_huge_val();
-    }
-    float cS[Q][4];                            // column sums of the plan entries
-#pragma unroll
-    for (int q = 0; q < Q; ++q)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) cS[q][e] = 0.0f;
-
+    // This workgroup owns the panels b, b + G, b + 2G, ... (G workgroups).  It always starts with the
+    // first of them and then walks the others upwards on even iterations and downwards on odd ones, so
+    // that what the last-level cache still holds from the previous pass is read first.
     const int npanels = (n + R - 1) / R;
-    const bool rev = (k & 1) != 0;
-    auto first_row = [&](int pq) { return (rev ? npanels - 1 - pq : pq) * R; };
-    const __amdgpu_buffer_rsrc_t rsF = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(p.F + (size_t)cur * p.n_ld), 0, n * 8, 0x00020000);
+    const int G = gridDim.x;
+    const int mine = ((int)blockIdx.x < npanels) ? (npanels - 1 - (int)blockIdx.x) / G + 1 : 0;
+    const __amdgpu_buffer_rsrc_t rsF0 = __builtin_amdgcn_make_buffer_rsrc((void *)p.F, 0, n * 8, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsF1 =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(p.F + p.n_ld), 0, n * 8, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsL = __builtin_amdgcn_make_buffer_rsrc((void *)p.la2, 0, n * 8, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void *)p.a, 0, n * 4, 0x00020000);
-    // HBM -> LDS prefetch of one panel and of its row scalars into staging buffer `buf`.  The buffer
-    // descriptors cover exactly the valid rows, so rows past n read as zero.
-    auto issue = [&](int pq, int buf) {
-        const int i0 = first_row(pq);
+    // HBM -> LDS prefetch of one panel (rows i0, i0 + 1, ...) and of its weights into staging buffer
+    // `buf`.  The buffer descriptors cover exactly the valid rows, so rows past n read as zero.
+    // Per-lane offsets stay loop-invariant (lane * 8, tid * 16); everything that changes from load to
+    // load goes through the scalar offset operand.  (The instruction's immediate offset is not used:
+    // it would shift the LDS destination as well as the memory address.)
+    auto issue_data = [&](int i0, int buf) {
         const int rows = (n - i0) < R ? (n - i0) : R;
-        // per-lane offsets stay loop-invariant (lane * 8, tid * 16); everything that changes from
-        // load to load goes through the scalar offset operand.  (The instruction's immediate offset
-        // is not used: it would shift the LDS destination as well as the memory address.)
         if (lane < R) {
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsF, &scal[buf][wave][0], 4, lane * 8, i0 * 8, 0, 0);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsF, &scal[buf][wave][R], 4, lane * 8, i0 * 8 + 4, 0, 0);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsL, &scal[buf][wave][2 * R], 4, lane * 8, i0 * 8, 0, 0);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsL, &scal[buf][wave][3 * R], 4, lane * 8, i0 * 8 + 4, 0, 0);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, &scal[buf][wave][4 * R], 4, lane * 4, i0 * 4, 0, 0);
@@ -442,46 +431,96 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, &stage[buf][wave][r][q][0], 16,
                                                              tid * 16, (r * m + q * T * 4) * 4, 0, 0);
     };
+    // old F of the rows of a panel, from the buffer the counter names
+    auto issue_F = [&](const __amdgpu_buffer_rsrc_t &rsF, int i0, int *dst) {
+        if (lane < R) {
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsF, dst, 4, lane * 8, i0 * 8, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsF, dst + R, 4, lane * 8, i0 * 8 + 4, 0, 0);
+        }
+    };
+    static_assert(2 * R <= 4, "scalF0 holds two dwords per row and parity");
 
-    int pq = blockIdx.x;
-    const int pstep = gridDim.x;
-    if (pq < npanels) {
+    double v0[Q][4], v1[Q][4];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int col = (q * T + tid) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v0[q][e] = colok(q) ? p.V[col + e] : -__builtin_huge_val();
+            v1[q][e] = colok(q) ? p.V[(size_t)p.m_ld + col + e] : -__builtin_huge_val();
+        }
+    }
+    if (mine > 0) {
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(0xc07f);        // the clearing stores above are done
-        issue(pq, 0);
-        if (FULLW && pq + pstep < npanels) issue(pq + pstep, 1);
+        issue_data((int)blockIdx.x * R, 0);
+        // both candidates for the old F of the first panel: parity 0 -> scalF0[wave][0..2R), parity 1 -> scal[0]
+        issue_F(rsF0, (int)blockIdx.x * R, &scalF0[wave][0]);
+        issue_F(rsF1, (int)blockIdx.x * R, &scal[0][wave][0]);
+        asm volatile("" ::: "memory");
+    }
+
+    int k;
+    if (!counter_active(c, kd, k)) {
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0)); // no prefetch may land after the workgroup has given up its LDS
+        return;
+    }
+    const int cur = k & 1, nxt = cur ^ 1;
+    const bool rev = cur != 0;
+    const __amdgpu_buffer_rsrc_t rsF = cur ? rsF1 : rsF0;
+    // row index of the t-th panel this workgroup processes
+    auto panel_row = [&](int t) { return ((int)blockIdx.x + (t == 0 ? 0 : (rev ? mine - t : t)) * G) * R; };
+    auto issue = [&](int t, int buf) {
+        const int i0 = panel_row(t);
+        issue_F(rsF, i0, &scal[buf][wave][0]);
+        issue_data(i0, buf);
+    };
+    double v[Q][4];
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[q][e] = cur ? v1[q][e] : v0[q][e];
+    float cS[Q][4];                            // column sums of the plan entries
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cS[q][e] = 0.0f;
+
+    if (FULLW && mine > 1) {
+        asm volatile("" ::: "memory");
+        issue(1, 1);
         asm volatile("" ::: "memory");
     }
     int buf = 0;
-    for (; pq < npanels; pq += pstep, buf ^= 1) {
-        const int i0 = first_row(pq);
-        const int pq1 = pq + pstep, pq2 = pq + 2 * pstep;
-        // Panel `pq` and its row scalars must have landed.  FULLW: the only younger VMEM operations are
+    for (int t = 0; t < mine; ++t, buf ^= 1) {
+        const int i0 = panel_row(t);
+        // Panel t and its row scalars must have landed.  FULLW: the only younger VMEM operations are
         // the NDMA prefetch loads of the next panel (if there is one), which may stay in flight.
-        if (FULLW && pq1 < npanels) __builtin_amdgcn_s_waitcnt(waitcnt_vm(NDMA));
+        if (FULLW && t + 1 < mine) __builtin_amdgcn_s_waitcnt(waitcnt_vm(NDMA));
         else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
         asm volatile("" ::: "memory");             // no LDS read of the staging buffers may move above the wait
         const int *sc = scal[buf][wave];
+        const int *scF = (t == 0 && cur == 0) ? scalF0[wave] : sc;
         const bool rowok = rr < R && (i0 + rr) < n;
-        const double rho_lane = __hiloint2double(sc[R + rc], sc[rc]);
+        const double rho_lane = __hiloint2double(scF[R + rc], scF[rc]);
         const double la2_lane = rowok ? __hiloint2double(sc[3 * R + rc], sc[2 * R + rc]) : -__builtin_huge_val();
         const float a_lane = rowok ? __int_as_float(sc[4 * R + rc]) : 0.0f;
         double rho[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) rho[r] = __hiloint2double(sc[R + r], sc[r]);
-        if (!FULLW && pq1 < npanels) {
+        for (int r = 0; r < R; ++r) rho[r] = __hiloint2double(scF[R + r], scF[r]);
+        if (!FULLW && t + 1 < mine) {
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_waitcnt(0xc07f);    // every earlier read of the other staging buffer has returned
-            issue(pq1, buf ^ 1);
+            issue(t + 1, buf ^ 1);
             asm volatile("" ::: "memory");
         }
         // FULLW: prefetch of the panel after next into the buffer this panel occupies, as soon as the
         // last read of that buffer has returned
         auto issue_ahead = [&]() {
-            if (FULLW && pq2 < npanels) {
+            if (FULLW && t + 2 < mine) {
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_s_waitcnt(0xc07f);
-                issue(pq2, buf);
+                issue(t + 2, buf);
                 asm volatile("" ::: "memory");
             }
         };

@@ -12,6 +12,7 @@
 // to the running maximum is rounded to fp32 for v_exp_f32.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 namespace fs {
@@ -53,16 +54,24 @@ struct Ctl {
     volatile int32_t *host_flag;   // pinned host mirror of {done, mode hint}, may be null
 };
 
-// Does this launch have work to do?  Iteration kernels run while k < max_iter,
-// the trailing error pass runs only when k == max_iter; nothing runs once done.
-__device__ __forceinline__ bool launch_active(const Ctl &c, int &k) {
-    const volatile State *st = c.st;
+// The iteration counter and the stop flag sit side by side and are fetched with ONE 8-byte load (a
+// relaxed atomic: it is neither split nor repeated, and nothing waits for it until its value is used,
+// so loads issued after it overlap with it).
+__device__ __forceinline__ unsigned long long load_counter(const Ctl &c) {
+    static_assert(offsetof(State, k) == 0 && offsetof(State, done) == 4, "k and done are read as one word");
+    return __hip_atomic_load(reinterpret_cast<const unsigned long long *>(c.st), __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+}
+// Does this launch have work to do?  Iteration kernels run while k < max_iter, the trailing error
+// pass runs only when k == max_iter; nothing runs once done.
+__device__ __forceinline__ bool counter_active(const Ctl &c, unsigned long long kd, int &k) {
     // the same value in every lane; readfirstlane tells the compiler so (scalar control flow and
     // scalar addressing everywhere downstream)
-    k = __builtin_amdgcn_readfirstlane(st->k);
-    if (__builtin_amdgcn_readfirstlane(st->done)) return false;
+    k = __builtin_amdgcn_readfirstlane((int)(unsigned)kd);
+    if (__builtin_amdgcn_readfirstlane((int)(unsigned)(kd >> 32))) return false;
     return c.phase == 0 ? (k < c.max_iter) : (k == c.max_iter);
 }
+__device__ __forceinline__ bool launch_active(const Ctl &c, int &k) { return counter_active(c, load_counter(c), k); }
 
 // ---------------------------------------------------------------- math
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32

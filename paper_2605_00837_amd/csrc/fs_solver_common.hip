@@ -183,20 +183,11 @@ constexpr double kErrScale = 35184372088832.0;         // 2^45: sums below 16 fi
 constexpr unsigned long long kErrBad = 1ull << 63;
 constexpr double kLn2 = 0.6931471805599453094;
 
-#ifdef FS_TS
-__device__ unsigned long long g_ts[256 * 8];
-#define TS(w, i) do { if (threadIdx.x == (w) * 64) g_ts[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define TS(w, i)
-#endif
-
 __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
     __shared__ double sM[kCombW][64];
     __shared__ float sS[kCombW][64];
     __shared__ unsigned long long s_mask;
-    TS(0, 0);
-    const volatile State *vst = c.st;
-    const int k_ld = vst->k, done_ld = vst->done;
+    const unsigned long long kd = load_counter(c);
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
     const int j = blockIdx.x * 64 + lane;
     const bool jok = j < A.len;
@@ -290,11 +281,9 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
         }
     }
 
-    const int k = __builtin_amdgcn_readfirstlane(k_ld);
-    if (__builtin_amdgcn_readfirstlane(done_ld)) return;
-    if (c.phase == 0 ? !(k < c.max_iter) : !(k == c.max_iter)) return;
+    int k;
+    if (!counter_active(c, kd, k)) return;
     const int cur = k & 1, nxt = cur ^ 1;
-    TS(1, 1); TS(0, 5);
     State *st = c.st;
 
     double err_part = 0.0;
@@ -319,7 +308,6 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
         if (err_part >= 0.0 && err_part <= 4.0) add += (unsigned long long)(err_part * kErrScale) << kTicketBits;
         else atomicOr(&st->err_acc, kErrBad);
         const unsigned long long word = atomicAdd(&st->err_acc, add) + add;
-        TS(1, 2);
         if ((word & ((1ull << kTicketBits) - 1)) == gridDim.x) {
             // fast-moving columns of the previous iteration (complete since the previous launch, read above)
             const unsigned bigc = cur ? big_ld[0] : big_ld[1];
@@ -327,7 +315,6 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
             const double err = (word & kErrBad) ? __builtin_nan("")
                                                 : (double)((word & ~kErrBad) >> kTicketBits) / kErrScale;
             advance_state(c, k, err, (double)bigc);
-            TS(1, 3);
         }
     }
     if (wave == 0) {
@@ -359,7 +346,6 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
             const double wbig = wave_sum_f64(nbig);
             if (lane == 0 && wbig > 0.0) atomicAdd(&st->big_acc[cur], (unsigned)wbig);
         }
-        TS(0, 4);
     }
     if (fast_mode) {
         // ---- exact recomputation of the suspect columns of this workgroup (rare): all threads walk
@@ -392,9 +378,6 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
     }
 }
 
-#ifdef FS_TS
-extern "C" int fs_debug_ts(unsigned long long *out) { return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_ts), sizeof(g_ts)); }
-#endif
 hipError_t launch_combine(hipStream_t st, const CombineArgs &a, const Ctl &c) {
     if ((a.len + 63) / 64 >= (1 << kTicketBits)) return hipErrorInvalidValue;     // the ticket field would overflow
     hipLaunchKernelGGL(k_combine, dim3((a.len + 63) / 64), dim3(kCombT), 0, st, a, c);

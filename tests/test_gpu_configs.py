@@ -44,10 +44,16 @@ def check(fs, oracle, w, eps, r, g, marginals=True, tol64=TOL_F64):
     f64, g64 = r["f64"].cpu().numpy(), r["g64"].cpu().numpy()
     f32, g32 = r["f"].cpu().numpy().astype(np.float64), r["g"].cpu().numpy().astype(np.float64)
     assert np.all(np.isfinite(f32)) and np.all(np.isfinite(g32)) and not r["nonfinite"]
-    e64 = max(np.abs(f64 - g["f"]).max(), np.abs(g64 - g["g"]).max()) / eps
     e32 = max(np.abs(f32 - g["f"]).max(), np.abs(g32 - g["g"]).max()) / eps
+    assert e32 < TOL_F32, e32                     # the spec bar, on the raw fp32 potentials
+    # The tighter bar on the fp64 outputs is taken after removing the shift (f + c, g - c), which leaves
+    # the plan unchanged: nothing in the iteration damps that direction, so the rounding bias of the
+    # fp32 sums (about 1e-8 eps per iteration) adds up along it over thousands of iterations.
+    df, dg = f64 - g["f"], g64 - g["g"]
+    c = 0.5 * (df.mean() - dg.mean())
+    assert abs(c) / eps < TOL_F32, c / eps
+    e64 = max(np.abs(df - c).max(), np.abs(dg + c).max()) / eps
     assert e64 < tol64, e64
-    assert e32 < TOL_F32, e32
     geo = dict(C=dev(w.C), X=dev(w.X), Y=dev(w.Y))
     cost = float(fs.fs_cost(dev(w.a), dev(w.b), eps, r["f"], r["g"], **geo).cpu()[0])
     assert abs(cost - float(g["cost"])) <= TOL_COST * abs(float(g["cost"])), (cost, float(g["cost"]))
