@@ -78,7 +78,9 @@ typedef struct {
     int32_t use_graph;       /* 0: automatic; 1: plain stream launches; 2: hipGraph iteration blocks  */
     int32_t skip_final_err;  /* 1: do not spend the one trailing pass that evaluates err after the
                                 last iteration when no stop fired (marginal_err is then NaN)          */
-    int32_t fused_variant;  /* tuning knob of the fused kernel: 0 default register tiling, 1 alternative */
+    int32_t fused_variant;   /* tuning knob: 0 default; 1..5 alternative tilings of the dense fused kernel;
+                                +100: take the optimistic (fp32-sum) kernels from the first iteration on,
+                                whatever the pace of the potentials (exercises the exact repair paths) */
     double *f64_out;         /* optional device [n]: f in double precision (NULL: not wanted)         */
     double *g64_out;         /* optional device [m]: g in double precision                            */
     const double *f64_in;    /* optional device [n], [m]: warm start in double precision; when both  */

@@ -173,6 +173,7 @@ struct Solve {
         c.err_history_len = opt.err_history ? opt.err_history_len : 0;
         c.phase = phase;
         c.host_flag = host_flag;
+        c.force_fast = opt.fused_variant >= 100 ? 1 : 0;
         return c;
     }
     // kind of an iteration of the dense solver: the exact streaming kernels, or a fused kernel
@@ -219,6 +220,7 @@ struct Solve {
         a.nr = pr.n; a.nc = pr.m; a.d = pr.d;
         a.part = (double *)(ws + L.o_part);
         a.JS = L.JSf; a.ld = L.n_ld; a.cols_per_split = L.cpsf;
+        a.rowpot = pots.F; a.rowconst = (const double *)(ws + L.o_cx);
         return a;
     }
     PointsArgs points_g() const {
@@ -230,6 +232,7 @@ struct Solve {
         a.nr = pr.m; a.nc = pr.n; a.d = pr.d;
         a.part = (double *)(ws + L.o_part2);
         a.JS = L.JSg; a.ld = L.m_ld; a.cols_per_split = L.cpsg;
+        a.rowpot = pots.G; a.rowconst = (const double *)(ws + L.o_cy);
         return a;
     }
 
@@ -247,9 +250,14 @@ struct Solve {
         else if (kind == STREAM) e = launch_dense_row(st, dense(STREAM), c);
         else e = launch_dense_fused(st, dense(FUSED), c, opt.fused_variant);     // both half-steps
         if (e == hipSuccess && t1) e = hipEventRecord(t1, st);
-        if (mode == 3) {
-            if (e == hipSuccess)
-                e = launch_combine(st, combine_f(L.JSf, (const double *)(ws + L.o_part), (const double *)(ws + L.o_cx)), c);
+        if (mode == 3 && e == hipSuccess) {
+            CombineArgs ca = combine_f(L.JSf, (const double *)(ws + L.o_part), (const double *)(ws + L.o_cx));
+            if (points_optimistic(pr.d)) {      // the pass may have run optimistically: let the combine check it
+                const PointsArgs pa = points_f();
+                ca.pr_rows = pa.rows; ca.pr_cols2s = pa.cols2s; ca.pr_colconst = pa.colconst;
+                ca.pr_colshift = pa.colshift; ca.pr_nc = pa.nc; ca.pr_d = pa.d; ca.pr_shift_next = 0; ca.pr_ld = L.m_ld;
+            }
+            e = launch_combine(st, ca, c);
         }
         return e;
     }
@@ -271,8 +279,15 @@ struct Solve {
         }
         } else {
             e = launch_points_lse(st, points_g(), c, 1, L.n_ld);
-            if (e == hipSuccess)
-                e = launch_combine(st, combine_g(L.JSg, (const double *)(ws + L.o_part2), (const double *)(ws + L.o_cy)), c);
+            if (e == hipSuccess) {
+                CombineArgs ca = combine_g(L.JSg, (const double *)(ws + L.o_part2), (const double *)(ws + L.o_cy));
+                if (points_optimistic(pr.d)) {
+                    const PointsArgs pa = points_g();
+                    ca.pr_rows = pa.rows; ca.pr_cols2s = pa.cols2s; ca.pr_colconst = pa.colconst;
+                    ca.pr_colshift = pa.colshift; ca.pr_nc = pa.nc; ca.pr_d = pa.d; ca.pr_shift_next = 1; ca.pr_ld = L.n_ld;
+                }
+                e = launch_combine(st, ca, c);
+            }
         }
         return e;
     }

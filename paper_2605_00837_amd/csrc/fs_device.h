@@ -25,13 +25,14 @@ constexpr double kNegHuge = -1.0e300;   // finite stand-in for "-inf" as a runni
 // the finalize kernels.
 struct alignas(256) State {
     int32_t k;            // iterations completed
-    int32_t done;         // stop flag: every later kernel of the solve returns at once
+    int32_t flags;        // bit 0: stop flag (every later kernel of the solve returns at once);
+                          // bit 1: pace hint for the next iteration, 1 = the potentials move slowly (FAST)
     int32_t iters;        // result: iterations whose potentials are returned
     int32_t converged;
     int32_t nonfinite;
     uint32_t reserved0;
     int32_t err_valid;
-    int32_t mode;         // hint for the driver after each iteration: 1 = the potentials move slowly (FAST)
+    int32_t reserved2;
     double err;           // err after `iters`
     // Closing word of the iteration in progress, updated with ONE atomic per workgroup: bits 0..13
     // count the workgroups that have reported (the ticket), bits 14..62 hold the fixed-point sum of
@@ -52,23 +53,27 @@ struct Ctl {
     int32_t err_history_len;
     int32_t phase;            // 0: iteration kernel, 1: trailing error pass
     volatile int32_t *host_flag;   // pinned host mirror of {done, mode hint}, may be null
+    int32_t force_fast;       // 1: kernels that follow the device's pace hint take the FAST variant regardless
 };
 
 // The iteration counter and the stop flag sit side by side and are fetched with ONE 8-byte load (a
 // relaxed atomic: it is neither split nor repeated, and nothing waits for it until its value is used,
 // so loads issued after it overlap with it).
 __device__ __forceinline__ unsigned long long load_counter(const Ctl &c) {
-    static_assert(offsetof(State, k) == 0 && offsetof(State, done) == 4, "k and done are read as one word");
+    static_assert(offsetof(State, k) == 0 && offsetof(State, flags) == 4, "k and the flags are read as one word");
     return __hip_atomic_load(reinterpret_cast<const unsigned long long *>(c.st), __ATOMIC_RELAXED,
                              __HIP_MEMORY_SCOPE_AGENT);
 }
 // Does this launch have work to do?  Iteration kernels run while k < max_iter, the trailing error
 // pass runs only when k == max_iter; nothing runs once done.
-__device__ __forceinline__ bool counter_active(const Ctl &c, unsigned long long kd, int &k) {
+constexpr int kFlagDone = 1, kFlagFast = 2;
+__device__ __forceinline__ bool counter_active(const Ctl &c, unsigned long long kd, int &k, bool *fast_hint = nullptr) {
     // the same value in every lane; readfirstlane tells the compiler so (scalar control flow and
     // scalar addressing everywhere downstream)
     k = __builtin_amdgcn_readfirstlane((int)(unsigned)kd);
-    if (__builtin_amdgcn_readfirstlane((int)(unsigned)(kd >> 32))) return false;
+    const int flags = __builtin_amdgcn_readfirstlane((int)(unsigned)(kd >> 32));
+    if (fast_hint) *fast_hint = (flags & kFlagFast) != 0 || c.force_fast != 0;
+    if (flags & kFlagDone) return false;
     return c.phase == 0 ? (k < c.max_iter) : (k == c.max_iter);
 }
 __device__ __forceinline__ bool launch_active(const Ctl &c, int &k) { return counter_active(c, load_counter(c), k); }
@@ -203,7 +208,6 @@ __device__ __forceinline__ void advance_state(const Ctl &c, int k, double err, d
     State *st = c.st;
     // hint for the driver: at most 128 columns moved by more than 40 (base 2) this time
     const int hint = (big_cols <= 128.0) ? 1 : 0;
-    st->mode = hint;
     if (c.host_flag) {                            // made visible by the completion of this kernel
         c.host_flag[1] = hint;
         c.host_flag[2 + ((k + 1) & 63)] = hint;
@@ -223,12 +227,13 @@ __device__ __forceinline__ void advance_state(const Ctl &c, int k, double err, d
         st->err = err;
         st->err_valid = 1;
         __threadfence();
-        st->done = 1;
+        st->flags = kFlagDone | (hint ? kFlagFast : 0);
         if (c.host_flag) {
             *c.host_flag = 1;
             __threadfence_system();
         }
     } else {
+        st->flags = hint ? kFlagFast : 0;
         st->k = k + 1;
     }
 }

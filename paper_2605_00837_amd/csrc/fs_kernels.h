@@ -29,12 +29,13 @@ struct DenseArgs {
 // The LDS-prefetch fused pass sums plan entries in fp32 (its column phase): a combined G_j that fell
 // by more than kColRepairBelow in one iteration (or is not a number) may have lost terms to fp32
 // underflow and is recomputed exactly by the combine kernel.  After every iteration the device
-// publishes a hint (State::mode): FAST if at most 128 columns moved by more than kFastBelow (base-2
+// publishes a hint (bit 1 of State::flags): FAST if at most 128 columns moved by more than kFastBelow (base-2
 // units), ROBUST otherwise; the driver runs the exact streaming kernels while the hint says ROBUST.
 constexpr int kModeRobust = 0;
 constexpr int kModeFast = 1;
 constexpr double kFastBelow = 40.0;
 constexpr double kColRepairBelow = 60.0;
+constexpr double kRepairAbove = 100.0;    // optimistic point-cloud pass: fp32 sums stay finite up to 2^127
 
 // Where the row-marginal error comes from.  r_i = a_i 2^(Fnew_i - Fold_i) is the row marginal of
 // the iterate a launch started from (the new f-update computes exactly the LSE of Sec. 4.5), so
@@ -67,6 +68,16 @@ struct CombineArgs {
     const double *repair_U;   // [2][repair_ld]
     int32_t repair_n, repair_ld;
     double repair_s;
+    // Repair of entries whose partials come from the optimistic point-cloud pass (only looked at while
+    // the pace hint says FAST): when pr_rows is non-null, a combined value outside
+    // [old - kColRepairBelow, old + kRepairAbove] (or NaN) is recomputed exactly over all columns.
+    const double *pr_rows;      // [len][d] coordinates of this side
+    const double *pr_cols2s;    // [pr_nc][d] other side, times 2s
+    const double *pr_colconst;  // [pr_nc]
+    const double *pr_colshift;  // [pr_nc] V or U the pass ran with (buffer already selected)
+    int32_t pr_nc, pr_d;
+    int32_t pr_shift_next;      // 1: pr_colshift is [2][pr_ld] and the pass used the NEXT buffer
+    int32_t pr_ld;
 };
 
 // warm: bit 0 = start f from f_in / f64_in, bit 1 = start g from g_in / g64_in (else zero)
@@ -101,8 +112,13 @@ struct PointsArgs {
     int32_t nr, nc, d;
     double *part;             // [JS][ld] partial LSE values per row
     int32_t JS, ld, cols_per_split;
+    // reference for the optimistic pass: the rows' own potential ([2][ld], buffer of the current
+    // iterate) and the row constant -s |row|^2 that the combine kernel adds to the LSE
+    const double *rowpot;
+    const double *rowconst;
 };
 void points_plan(int nr, int nc, int d, int *JS, int *cols_per_split);
+bool points_optimistic(int d);      // does the LSE pass for this dimension have the optimistic (FAST) variant?
 hipError_t launch_points_lse(hipStream_t st, const PointsArgs &a, const Ctl &c, int use_next_shift, int ld_shift);
 hipError_t launch_points_prep(hipStream_t st, const float *X, int n, int d, double s, double *plain,
                               double *scaled, double *negsq);

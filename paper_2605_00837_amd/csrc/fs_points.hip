@@ -18,7 +18,7 @@ namespace fs {
 
 constexpr int kPT = 256;       // threads per workgroup
 constexpr int kTile = 256;     // columns staged per tile
-constexpr int kIB = 2;         // rows per lane
+constexpr int kIB = 4;         // rows per lane
 constexpr int kChunk = 8;      // pairs folded per rescale
 
 __global__ __launch_bounds__(256) void k_points_prep(const float *X, int n, int d, double s, double *plain,
@@ -41,53 +41,101 @@ hipError_t launch_points_prep(hipStream_t st, const float *X, int n, int d, doub
     return hipGetLastError();
 }
 
-template <int D>
+// Two ways through the column slice, chosen by the pace hint the device keeps next to the
+// iteration counter (the same for every workgroup of a launch, and for the combine kernel that
+// follows):
+//   ROBUST  exact online LogSumExp, one fp64 running maximum per row and chunk of kChunk pairs;
+//   FAST    optimistic: the previous value of the row's own LSE is the reference, every pair costs
+//           d fp64 FMAs, one fp64 subtraction, one conversion, v_exp_f32 and one fp32 addition.
+//           Nothing is checked here: the combine kernel compares the merged result with the
+//           reference and recomputes exactly whatever moved too far for the fp32 sums to be trusted.
+template <int D, int IB>
 __global__ __launch_bounds__(kPT) void k_points_lse(PointsArgs A, Ctl c, int use_next, int ld_shift) {
     __shared__ __align__(16) double tile[kTile][D + 1];
-    int k;
-    if (!launch_active(c, k)) return;
-    const int buf = use_next ? ((k & 1) ^ 1) : (k & 1);
-    const double *shift = A.colshift + (size_t)buf * ld_shift;
+    const unsigned long long kd = load_counter(c);
     const int tid = threadIdx.x;
 
-    double x[kIB][D];
-    int row[kIB];
+    double x[IB][D];
+    double rconst[IB];
+    int row[IB];
 #pragma unroll
-    for (int b = 0; b < kIB; ++b) {
-        row[b] = (blockIdx.x * kIB + b) * kPT + tid;
+    for (int b = 0; b < IB; ++b) {
+        row[b] = (blockIdx.x * IB + b) * kPT + tid;
+        const bool ok = row[b] < A.nr;
 #pragma unroll
-        for (int t = 0; t < D; ++t) x[b][t] = row[b] < A.nr ? A.rows[(size_t)row[b] * D + t] : 0.0;
+        for (int t = 0; t < D; ++t) x[b][t] = ok ? A.rows[(size_t)row[b] * D + t] : 0.0;
+        rconst[b] = ok ? A.rowconst[row[b]] : 0.0;
     }
-    Lse acc[kIB];
-#pragma unroll
-    for (int b = 0; b < kIB; ++b) acc[b].init();
-
+    int k;
+    bool fast;
+    if (!counter_active(c, kd, k, &fast)) return;
+    const int cur = k & 1;
+    const int buf = use_next ? (cur ^ 1) : cur;
+    const double *shift = A.colshift + (size_t)buf * ld_shift;
     const int j0 = blockIdx.y * A.cols_per_split;
     const int j1 = min(A.nc, j0 + A.cols_per_split);
-    for (int jt = j0; jt < j1; jt += kTile) {
+
+    auto stage = [&](int jt) {
         __syncthreads();                                   // previous tile fully consumed
-        {
-            const int j = jt + tid;
-            if (j < j1) {
-                tile[tid][0] = shift[j] + A.colconst[j];
+        const int j = jt + tid;
+        if (j < j1) {
+            tile[tid][0] = shift[j] + A.colconst[j];
 #pragma unroll
-                for (int t = 0; t < D; ++t) tile[tid][1 + t] = A.cols2s[(size_t)j * D + t];
-            } else {
-                tile[tid][0] = -__builtin_huge_val();      // contributes 2^-inf = 0
+            for (int t = 0; t < D; ++t) tile[tid][1 + t] = A.cols2s[(size_t)j * D + t];
+        } else {
+            tile[tid][0] = -__builtin_huge_val();          // contributes 2^-inf = 0
 #pragma unroll
-                for (int t = 0; t < D; ++t) tile[tid][1 + t] = 0.0;
-            }
+            for (int t = 0; t < D; ++t) tile[tid][1 + t] = 0.0;
         }
         __syncthreads();
-        for (int jj = 0; jj < kTile; jj += kChunk) {
-            double val[kIB][kChunk];
+    };
+
+    if (fast) {
+        double ref[IB];
+        float sum[IB];
 #pragma unroll
-            for (int q = 0; q < kChunk; ++q) {
+        for (int b = 0; b < IB; ++b) {
+            // LSE of the bracket = potential - row constant
+            ref[b] = row[b] < A.nr ? A.rowpot[(size_t)cur * A.ld + row[b]] - rconst[b] : 0.0;
+            sum[b] = 0.0f;
+        }
+        for (int jt = j0; jt < j1; jt += kTile) {
+            stage(jt);
+#pragma unroll 4
+            for (int jj = 0; jj < kTile; ++jj) {
+                double w[D + 1];
+#pragma unroll
+                for (int t = 0; t <= D; ++t) w[t] = tile[jj][t];
+#pragma unroll
+                for (int b = 0; b < IB; ++b) {
+                    double acc2 = w[0];
+#pragma unroll
+                    for (int t = 0; t < D; ++t) acc2 = fma(x[b][t], w[1 + t], acc2);
+                    sum[b] += fast_exp2((float)(acc2 - ref[b]));
+                }
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < IB; ++b)
+            if (row[b] < A.nr) A.part[(size_t)blockIdx.y * A.ld + row[b]] = ref[b] + log2_sum(sum[b]);
+        return;
+    }
+
+    Lse acc[IB];
+#pragma unroll
+    for (int b = 0; b < IB; ++b) acc[b].init();
+    constexpr int CH = IB <= 2 ? kChunk : 4;               // pairs folded per rescale
+    for (int jt = j0; jt < j1; jt += kTile) {
+        stage(jt);
+        for (int jj = 0; jj < kTile; jj += CH) {
+            double val[IB][CH];
+#pragma unroll
+            for (int q = 0; q < CH; ++q) {
                 double w[D + 1];
 #pragma unroll
                 for (int t = 0; t <= D; ++t) w[t] = tile[jj + q][t];
 #pragma unroll
-                for (int b = 0; b < kIB; ++b) {
+                for (int b = 0; b < IB; ++b) {
                     double acc2 = w[0];
 #pragma unroll
                     for (int t = 0; t < D; ++t) acc2 = fma(x[b][t], w[1 + t], acc2);
@@ -95,11 +143,11 @@ __global__ __launch_bounds__(kPT) void k_points_lse(PointsArgs A, Ctl c, int use
                 }
             }
 #pragma unroll
-            for (int b = 0; b < kIB; ++b) acc[b].add<kChunk>(val[b]);
+            for (int b = 0; b < IB; ++b) acc[b].template add<CH>(val[b]);
         }
     }
 #pragma unroll
-    for (int b = 0; b < kIB; ++b)
+    for (int b = 0; b < IB; ++b)
         if (row[b] < A.nr) A.part[(size_t)blockIdx.y * A.ld + row[b]] = acc[b].value();
 }
 
@@ -144,6 +192,8 @@ __global__ __launch_bounds__(kPT) void k_points_lse_anyd(PointsArgs A, Ctl c, in
     if (rok) A.part[(size_t)blockIdx.y * A.ld + row] = acc.value();
 }
 
+bool points_optimistic(int d) { return d <= 4; }
+
 void points_plan(int nr, int nc, int d, int *JS, int *cols_per_split) {
     const int rows_per_wg = (d <= 4) ? kPT * kIB : kPT;
     const int rowblocks = (nr + rows_per_wg - 1) / rows_per_wg;
@@ -163,10 +213,10 @@ hipError_t launch_points_lse(hipStream_t st, const PointsArgs &a, const Ctl &c, 
     if (a.d <= 4) {
         const dim3 grid((a.nr + kPT * kIB - 1) / (kPT * kIB), a.JS);
         switch (a.d) {
-            case 1: hipLaunchKernelGGL(k_points_lse<1>, grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
-            case 2: hipLaunchKernelGGL(k_points_lse<2>, grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
-            case 3: hipLaunchKernelGGL(k_points_lse<3>, grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
-            default: hipLaunchKernelGGL(k_points_lse<4>, grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
+            case 1: hipLaunchKernelGGL((k_points_lse<1, kIB>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
+            case 2: hipLaunchKernelGGL((k_points_lse<2, kIB>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
+            case 3: hipLaunchKernelGGL((k_points_lse<3, kIB>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
+            default: hipLaunchKernelGGL((k_points_lse<4, kIB>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
         }
     } else {
         const dim3 grid((a.nr + kPT - 1) / kPT, a.JS);

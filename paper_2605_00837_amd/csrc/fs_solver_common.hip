@@ -15,8 +15,8 @@ __global__ __launch_bounds__(256) void k_init(Pots p, State *state, const float 
                                               int warm) {
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t == 0) {
-        state->k = 0; state->done = 0; state->iters = 0; state->converged = 0; state->nonfinite = 0;
-        state->reserved0 = 0; state->err_valid = 0; state->mode = kModeRobust;
+        state->k = 0; state->flags = 0; state->iters = 0; state->converged = 0; state->nonfinite = 0;
+        state->reserved0 = 0; state->err_valid = 0; state->reserved2 = 0;
         state->err_acc = 0; state->reserved1 = 0;
         state->big_acc[0] = 0; state->big_acc[1] = 0x7fffffffu;   // no count yet: the first hint says ROBUST
         state->err = __builtin_nan("");
@@ -68,7 +68,7 @@ hipError_t launch_export(hipStream_t st, const double *pot, int len, double s, d
 __global__ __launch_bounds__(256) void k_finalize(Pots p, State *state, float *f, float *g, double *f64_out,
                                                   double *g64_out) {
     const int t = blockIdx.x * 256 + threadIdx.x;
-    const int it = state->done ? state->iters : state->k;
+    const int it = (state->flags & kFlagDone) ? state->iters : state->k;
     const int buf = it & 1;
     const double inv = -1.0 / p.s;
     bool bad = false;
@@ -92,11 +92,12 @@ struct ResultRecord { int32_t iters, converged, nonfinite; float marginal_err; }
 __global__ void k_result(State *state, ResultRecord *dev, ResultRecord *host) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     ResultRecord r;
-    r.iters = state->done ? state->iters : state->k;
-    r.converged = state->done ? state->converged : 0;
+    const bool done = (state->flags & kFlagDone) != 0;
+    r.iters = done ? state->iters : state->k;
+    r.converged = done ? state->converged : 0;
     r.nonfinite = state->nonfinite;
-    r.marginal_err = (state->done && state->err_valid) ? (float)state->err : __builtin_nanf("");
-    if (!state->done) { state->iters = r.iters; state->done = 1; }
+    r.marginal_err = (done && state->err_valid) ? (float)state->err : __builtin_nanf("");
+    if (!done) { state->iters = r.iters; state->flags |= kFlagDone; }
     if (dev) *dev = r;
     if (host) {
         *host = r;
@@ -282,9 +283,12 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
     }
 
     int k;
-    if (!counter_active(c, kd, k)) return;
+    bool fast_hint;
+    if (!counter_active(c, kd, k, &fast_hint)) return;
     const int cur = k & 1, nxt = cur ^ 1;
     State *st = c.st;
+    // the partials come from the optimistic point-cloud pass (it ran because of the same hint)
+    const bool pts_check = A.pr_rows != nullptr && fast_hint;
 
     double err_part = 0.0;
     if (err_wave) {
@@ -336,6 +340,7 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
             // FAST column mode sums plan entries in fp32: a column whose G fell by more than 2^60
             // in one iteration (or is not a number) may have lost terms to underflow
             if (fast_mode) suspect = !(out >= old_j - kColRepairBelow);
+            else if (pts_check) suspect = !(out >= old_j - kColRepairBelow && out <= old_j + kRepairAbove);
             nbig = suspect ? 1.0 : big_move(out - old_j);
             A.pot[(size_t)nxt * A.ld + j] = out;
             A.shift[(size_t)nxt * A.ld + j] = lw2_j - out;
@@ -347,20 +352,31 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
             if (lane == 0 && wbig > 0.0) atomicAdd(&st->big_acc[cur], (unsigned)wbig);
         }
     }
-    if (fast_mode) {
-        // ---- exact recomputation of the suspect columns of this workgroup (rare): all threads walk
-        //      down column j of C with the new U, online LSE per thread, then wave + LDS merge
+    if (fast_mode || pts_check) {
+        // ---- exact recomputation of the suspect entries of this workgroup (rare): all threads walk
+        //      over the other side (down column j of C with the new U, or over all points of the other
+        //      cloud), online LSE per thread, then wave + LDS merge
         __syncthreads();                               // s_mask is visible
         unsigned long long todo = s_mask;
-        const double *U = A.repair_U + (size_t)nxt * A.repair_ld;
+        const double *U = fast_mode ? A.repair_U + (size_t)nxt * A.repair_ld : nullptr;
+        const double *cshift = pts_check ? A.pr_colshift + (size_t)(A.pr_shift_next ? nxt : cur) * A.pr_ld : nullptr;
         while (todo) {
             const int bit = __ffsll((long long)todo) - 1;
             todo &= todo - 1;
             const int jj = blockIdx.x * 64 + bit;
             Lse ex; ex.init();
-            for (int i = t; i < A.repair_n; i += kCombT) {
-                double y[1] = {fma(-A.repair_s, (double)A.repair_C[(size_t)i * A.len + jj], U[i])};
-                ex.add<1>(y);
+            if (fast_mode) {
+                for (int i = t; i < A.repair_n; i += kCombT) {
+                    double y[1] = {fma(-A.repair_s, (double)A.repair_C[(size_t)i * A.len + jj], U[i])};
+                    ex.add<1>(y);
+                }
+            } else {
+                const double *xr = A.pr_rows + (size_t)jj * A.pr_d;
+                for (int i = t; i < A.pr_nc; i += kCombT) {
+                    double y[1] = {cshift[i] + A.pr_colconst[i]};
+                    for (int q = 0; q < A.pr_d; ++q) y[0] = fma(xr[q], A.pr_cols2s[(size_t)i * A.pr_d + q], y[0]);
+                    ex.add<1>(y);
+                }
             }
             ex.wave_reduce();
             __syncthreads();                           // previous round's LDS reads are done

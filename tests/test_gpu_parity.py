@@ -146,6 +146,26 @@ def test_points_solve(fs, oracle, n, m, d):
     assert e64 < TOL_F64 and e32 < TOL_F32
 
 
+@pytest.mark.parametrize("n,m,d,zero", [(300, 257, 3, False), (2100, 1500, 2, False), (700, 3000, 4, True),
+                                        (1030, 1030, 1, False)])
+def test_points_optimistic_pass_and_repair(fs, oracle, n, m, d, zero):
+    """fused_variant = 100 makes the point-cloud LSE pass optimistic (previous potential as the
+    reference, plain fp32 sums) from the first iteration on, while the potentials still move by
+    hundreds of units: the combine kernel then has to find and recompute the rows whose sums
+    under- or overflowed.  The results must not change."""
+    w = W.random_points(n, m, d, seed=4100 + n + m + d, eps=0.004)
+    if zero:
+        w.a[::7] = 0.0
+        w.b[3::5] = 0.0
+        w.a[:] = w.a / w.a.sum(dtype=np.float64)
+        w.b[:] = w.b / w.b.sum(dtype=np.float64)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 40, fused_variant=100)
+    assert e64 < TOL_F64 and e32 < TOL_F32
+    # the same solve on the device's own schedule (exact passes while the potentials move fast)
+    r2, _, e64b, e32b = _solve_and_compare(fs, oracle, w, 40)
+    assert e64b < TOL_F64 and e32b < TOL_F32
+
+
 # ------------------------------------------------------------------ stopping rule, history, resume
 @pytest.mark.parametrize("kind,mode", [("dense", 1), ("dense", 2), ("points", 0)])
 def test_stopping_rule_and_history(fs, oracle, kind, mode):
