@@ -156,6 +156,32 @@ fs_status fs_cost_f64(const float *C, const float *X, const float *Y, int d, con
                       int n, int m, float eps, const double *f64, const double *g64, double *cost_dev,
                       fs_stream stream);
 
+/* ---- Diagnostics of a pair of potentials in ONE pass over C (or, for point clouds, one pass over all
+ * pairs per side): everything Alg. 1 reports after the loop and everything Secs. 3 and 4.5 define on
+ * the plan P of Eq. 5.  Potentials: either f, g (fp32) or f64, g64 (fp64), the other pair NULL.
+ * out_dev: device, FS_DIAG_LEN doubles:
+ *   [FS_DIAG_COST]    <C, P>                                   (last step of Alg. 1)
+ *   [FS_DIAG_MASS]    sum_ij P_ij
+ *   [FS_DIAG_KL]      KL(P | a x b) = sum P log(P/(a b)) - sum P + 1              (Eq. 4)
+ *   [FS_DIAG_PRIMAL]  <C, P> + eps KL(P | a x b)                                  (Eq. 3)
+ *   [FS_DIAG_DUAL]    <a, f> + <b, g> - eps sum P + eps                           (App. A.1)
+ *   [FS_DIAG_ROW_ERR] sum_i |sum_j P_ij - a_i|                                    (Sec. 4.5)
+ *   [FS_DIAG_COL_ERR] sum_j |sum_i P_ij - b_j|
+ * row_marginal_dev[n], col_marginal_dev[m]: optional device outputs (double), NULL = not wanted.
+ * Asynchronous on `stream`; uses the library-owned workspace; results are independent of timing. ---- */
+#define FS_DIAG_COST 0
+#define FS_DIAG_MASS 1
+#define FS_DIAG_KL 2
+#define FS_DIAG_PRIMAL 3
+#define FS_DIAG_DUAL 4
+#define FS_DIAG_ROW_ERR 5
+#define FS_DIAG_COL_ERR 6
+#define FS_DIAG_LEN 8
+fs_status fs_diagnostics(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                         int n, int m, float eps, const float *f, const float *g, const double *f64,
+                         const double *g64, double *out_dev, double *row_marginal_dev,
+                         double *col_marginal_dev, fs_stream stream);
+
 /* ---- One half-step on its own (Eq. 9 / Eq. 10), for kernel-level checks and for callers
  * that drive the loop themselves.  Potentials in double precision, device pointers;
  * asynchronous on `stream`; uses the library-owned workspace. ---- */

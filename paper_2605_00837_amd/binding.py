@@ -77,6 +77,8 @@ def _load():
         fn = getattr(lib, name)
         fn.restype = ci
         fn.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, vp, vp, vp, vp]
+    lib.fs_diagnostics.restype = ci
+    lib.fs_diagnostics.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, vp, vp, vp, vp, vp, vp, vp, vp]
     for name in ("fs_update_f", "fs_update_g"):
         fn = getattr(lib, name)
         fn.restype = ci
@@ -88,7 +90,7 @@ _lib = _load()
 
 EXPORTED = ("fs_sinkhorn_dense", "fs_sinkhorn_points", "fs_sinkhorn_solve", "fs_workspace_bytes",
             "fs_sinkhorn_dense_ex", "fs_sinkhorn_points_ex", "fs_plan", "fs_cost", "fs_plan_f64",
-            "fs_cost_f64", "fs_update_f", "fs_update_g", "fs_last_error", "fs_clear_cache", "fs_version",
+            "fs_cost_f64", "fs_diagnostics", "fs_update_f", "fs_update_g", "fs_last_error", "fs_clear_cache", "fs_version",
             "fs_last_kernel_timing")
 
 
@@ -294,6 +296,24 @@ def fs_cost(a, b, eps, f, g, C=None, X=None, Y=None):
 
 fs_plan_f64 = fs_plan
 fs_cost_f64 = fs_cost
+
+DIAG_FIELDS = ("cost", "mass", "kl", "primal", "dual", "row_err", "col_err")
+
+
+def fs_diagnostics(a, b, eps, f, g, C=None, X=None, Y=None, want_marginals=False):
+    """Cost, mass, KL, primal and dual objectives and both marginal L1 errors of the plan of (f, g), in
+    one pass.  Returns dict(out=fp64 device tensor of 8 values in the order of DIAG_FIELDS (FS_DIAG_* in
+    the header), row_marginal, col_marginal = fp64 device tensors, or None when not asked for)."""
+    n, m, d = _shape(C, X, Y, a, b)
+    dt = _pots(f, g)
+    out = torch.empty(8, dtype=torch.float64, device=a.device)
+    r = torch.empty(n, dtype=torch.float64, device=a.device) if want_marginals else None
+    c = torch.empty(m, dtype=torch.float64, device=a.device) if want_marginals else None
+    f32 = (_p(f), _p(g)) if dt == torch.float32 else (None, None)
+    f64 = (_p(f, dt), _p(g, dt)) if dt == torch.float64 else (None, None)
+    _check(_lib.fs_diagnostics(_p(C), _p(X), _p(Y), d, _p(a), _p(b), n, m, float(eps), f32[0], f32[1], f64[0], f64[1],
+                               _p(out, torch.float64), _p(r, torch.float64), _p(c, torch.float64), _stream()))
+    return dict(out=out, row_marginal=r, col_marginal=c)
 
 
 def fs_update_f(a, b, eps, g64, C=None, X=None, Y=None):

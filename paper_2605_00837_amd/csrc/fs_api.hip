@@ -559,16 +559,41 @@ fs_status plan_or_cost(const float *C, const float *X, const float *Y, int d, co
     fs_status v = validate(pr, (float *)fchk, (float *)gchk);
     if (v != FS_OK) return v;
     if (!P && !cost_dev) { set_err("output pointer is null"); return FS_ERR_INVALID_ARG; }
+    const int dd = C ? 0 : d;
     const int need = cost_scratch_len(n, m);
+    const size_t bytes = P ? sizeof(double) * (size_t)need : diag_scratch_bytes(n, m, dd);
     DeviceCache *dc = nullptr;
-    v = get_cache(sizeof(double) * (size_t)need, &dc);
+    v = get_cache(bytes, &dc);
     if (v != FS_OK) return v;
     PlanArgs A{};
     A.C = C; A.X = X; A.Y = Y; A.a = a; A.b = b; A.f = f; A.g = g; A.f64 = f64; A.g64 = g64;
-    A.n = n; A.m = m; A.d = C ? 0 : d;
+    A.n = n; A.m = m; A.d = dd;
     A.s = kLog2e / (double)eps;
     if (P) FS_HIP(launch_plan(st, A, P, (double *)dc->ws, need));
-    else FS_HIP(launch_cost(st, A, cost_dev, (double *)dc->ws, need));
+    else FS_HIP(launch_diag(st, A, nullptr, nullptr, nullptr, dc->ws, dc->ws_bytes, cost_dev));   // one pass
+    return FS_OK;
+}
+
+fs_status diagnostics(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                      int n, int m, float eps, const float *f, const float *g, const double *f64,
+                      const double *g64, double *out8, double *row_marg, double *col_marg, hipStream_t st) {
+    Problem pr{C, X, Y, a, b, d, n, m, eps, 0, 0.0f};
+    if ((f == nullptr) != (g == nullptr) || (f64 == nullptr) != (g64 == nullptr) || (!f && !f64)) {
+        set_err("potentials: give f and g, or f64 and g64"); return FS_ERR_INVALID_ARG;
+    }
+    const float *fchk = f ? f : (const float *)f64, *gchk = g ? g : (const float *)g64;
+    fs_status v = validate(pr, (float *)fchk, (float *)gchk);
+    if (v != FS_OK) return v;
+    if (!out8) { set_err("out must be non-null"); return FS_ERR_INVALID_ARG; }
+    const int dd = C ? 0 : d;
+    DeviceCache *dc = nullptr;
+    v = get_cache(diag_scratch_bytes(n, m, dd), &dc);
+    if (v != FS_OK) return v;
+    PlanArgs A{};
+    A.C = C; A.X = X; A.Y = Y; A.a = a; A.b = b; A.f = f64 ? nullptr : f; A.g = g64 ? nullptr : g; A.f64 = f64; A.g64 = g64;
+    A.n = n; A.m = m; A.d = dd;
+    A.s = kLog2e / (double)eps;
+    FS_HIP(launch_diag(st, A, out8, row_marg, col_marg, dc->ws, dc->ws_bytes));
     return FS_OK;
 }
 
@@ -708,6 +733,14 @@ fs_status fs_cost_f64(const float *C, const float *X, const float *Y, int d, con
     if (!cost_dev) { set_err("cost_dev must be non-null"); return FS_ERR_INVALID_ARG; }
     if (!f64 || !g64) { set_err("f64 and g64 must be non-null"); return FS_ERR_INVALID_ARG; }
     return plan_or_cost(C, X, Y, d, a, b, n, m, eps, nullptr, nullptr, f64, g64, nullptr, cost_dev, (hipStream_t)stream);
+}
+
+fs_status fs_diagnostics(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                         int n, int m, float eps, const float *f, const float *g, const double *f64,
+                         const double *g64, double *out_dev, double *row_marginal_dev, double *col_marginal_dev,
+                         fs_stream stream) {
+    return diagnostics(C, X, Y, d, a, b, n, m, eps, f, g, f64, g64, out_dev, row_marginal_dev, col_marginal_dev,
+                       (hipStream_t)stream);
 }
 
 fs_status fs_update_f(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,

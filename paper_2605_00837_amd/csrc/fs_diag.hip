@@ -1,0 +1,579 @@
+// Diagnostics of a pair of potentials in one pass over C (dense) or over all point pairs:
+// transport cost (last step of Alg. 1), total mass, KL term and primal objective (Eq. 3), dual
+// objective (Eq. 4 and App. A.1), both marginals of the plan of Eq. 5 and their L1 errors (Sec. 4.5).
+//
+//   P_ij = 2^(e_ij),  e_ij = ri_i + cj_j - s C_ij,  ri_i = s f_i + log2 a_i,  cj_j = s g_j + log2 b_j.
+//
+// The exponent is formed in fp64 and rounded to fp32 for v_exp_f32; sums over at most a few dozen
+// entries are kept in fp32, everything longer in fp64.  log(P_ij/(a_i b_j)) = (e_ij - log2 a_i -
+// log2 b_j) ln 2, so  sum P log(P/(a b)) = ln 2 (sum P e - sum_i r_i log2 a_i - sum_j c_j log2 b_j)
+// and only sum P e has to be collected per entry.
+//
+// Dense: a workgroup of 1024 lanes owns a strip of 1024*VEC columns and a panel of rows; lanes keep
+// their column sums, row sums go wave -> LDS -> one value per (strip, row).  Points: the layout of
+// the LSE pass (rows in registers, column tiles in LDS), run once per side so that every marginal
+// is a lane-local sum; the cost uses s C_ij = s|x_i|^2 + s|y_j|^2 - x_i . (2 s y_j).
+// All partial results are combined in fixed order: the outputs do not depend on timing.
+#include "fs_kernels.h"
+
+namespace fs {
+
+namespace {
+
+constexpr int kDT = 1024;           // threads of the dense kernel
+constexpr int kDRows = 16;          // rows per LDS exchange
+constexpr int kPT2 = 256;           // threads of the point-cloud kernel
+constexpr int kTile2 = 256;
+constexpr int kIB2 = 4;
+constexpr double kLn2d = 0.6931471805599453094;
+
+struct DiagLayout {
+    // dense
+    int vec, strip_cols, nstrips, P, rpp;
+    // points
+    int JSx, cpsx, JSy, cpsy;
+    // scratch offsets (bytes)
+    size_t o_ri, o_cj, o_rowpart, o_colpart, o_scal, o_red, o_out, total;
+    // points extras
+    size_t o_xp, o_xs, o_xq, o_yp, o_ys, o_yq;
+    int nred, nscal;
+};
+
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+DiagLayout diag_layout(int n, int m, int d) {
+    DiagLayout L{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
+    L.o_ri = take(sizeof(double) * n);
+    L.o_cj = take(sizeof(double) * m);
+    const int len = n > m ? n : m;
+    L.nred = (len + 63) / 64;
+    L.o_red = take(sizeof(double) * 8 * L.nred);
+    L.o_out = take(sizeof(double) * 8);
+    if (d == 0) {
+        L.vec = (m % 4 == 0) ? 4 : 1;
+        L.strip_cols = kDT * L.vec;
+        L.nstrips = (m + L.strip_cols - 1) / L.strip_cols;
+        int P = (512 + L.nstrips - 1) / L.nstrips;
+        const int maxP = (n + kDRows - 1) / kDRows;
+        if (P > maxP) P = maxP;
+        if (P < 1) P = 1;
+        int rpp = (n + P - 1) / P;
+        rpp = ((rpp + kDRows - 1) / kDRows) * kDRows;
+        L.rpp = rpp;
+        L.P = (n + rpp - 1) / rpp;
+        L.o_rowpart = take(sizeof(double) * (size_t)L.nstrips * n);
+        L.o_colpart = take(sizeof(float) * (size_t)L.P * m);
+        L.nscal = L.nstrips * L.P;
+        L.o_scal = take(sizeof(double) * 2 * L.nscal);
+    } else {
+        points_plan(n, m, d, &L.JSx, &L.cpsx);
+        points_plan(m, n, d, &L.JSy, &L.cpsy);
+        L.o_rowpart = take(sizeof(double) * (size_t)L.JSx * n);      // row sums per column slice
+        L.o_colpart = take(sizeof(double) * (size_t)L.JSy * m);      // column sums per row slice
+        const int rows_per_wg = d <= 4 ? kPT2 * kIB2 : kPT2;
+        const int gx = (n + rows_per_wg - 1) / rows_per_wg;
+        L.nscal = gx * L.JSx;
+        L.o_scal = take(sizeof(double) * 2 * L.nscal);
+        L.o_xp = take(sizeof(double) * (size_t)n * d);
+        L.o_xs = take(sizeof(double) * (size_t)n * d);
+        L.o_xq = take(sizeof(double) * n);
+        L.o_yp = take(sizeof(double) * (size_t)m * d);
+        L.o_ys = take(sizeof(double) * (size_t)m * d);
+        L.o_yq = take(sizeof(double) * m);
+    }
+    L.total = o;
+    return L;
+}
+
+// ri, cj; for points also the repacked clouds: plain, times 2s, and s|.|^2.
+__global__ __launch_bounds__(256) void k_diag_prep(PlanArgs A, double *ri, double *cj, double *xp, double *xs,
+                                                   double *xq, double *yp, double *ys, double *yq) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t < A.n) {
+        const double f = A.f64 ? A.f64[t] : (double)A.f[t];
+        ri[t] = fma(A.s, f, log2_weight(A.a[t]));
+        if (A.d > 0) {
+            double sq = 0.0;
+            for (int q = 0; q < A.d; ++q) {
+                const double x = (double)A.X[(size_t)t * A.d + q];
+                xp[(size_t)t * A.d + q] = x;
+                xs[(size_t)t * A.d + q] = 2.0 * A.s * x;
+                sq = fma(x, x, sq);
+            }
+            xq[t] = A.s * sq;
+        }
+    }
+    if (t < A.m) {
+        const double g = A.g64 ? A.g64[t] : (double)A.g[t];
+        cj[t] = fma(A.s, g, log2_weight(A.b[t]));
+        if (A.d > 0) {
+            double sq = 0.0;
+            for (int q = 0; q < A.d; ++q) {
+                const double y = (double)A.Y[(size_t)t * A.d + q];
+                yp[(size_t)t * A.d + q] = y;
+                ys[(size_t)t * A.d + q] = 2.0 * A.s * y;
+                sq = fma(y, y, sq);
+            }
+            yq[t] = A.s * sq;
+        }
+    }
+}
+
+// Sum of v over the workgroup in a fixed order (tree in LDS); result in thread 0.
+template <int T>
+__device__ __forceinline__ double block_sum(double v, double *lds) {
+    const int t = threadIdx.x;
+    __syncthreads();
+    lds[t] = v;
+    __syncthreads();
+#pragma unroll
+    for (int w = T / 2; w >= 1; w >>= 1) {
+        if (t < w) lds[t] += lds[t + w];
+        __syncthreads();
+    }
+    return lds[0];
+}
+
+// ---------------------------------------------------------------- dense
+struct DenseDiag {
+    const float *C;
+    const double *ri, *cj;
+    int32_t n, m;
+    double s;
+    double *rowpart;     // [nstrips][n]
+    float *colpart;      // [P][m]
+    double *scal;        // [nstrips * P][2]: sum P (s C), sum P e
+    int32_t rpp;
+};
+
+template <int VEC>
+__global__ __launch_bounds__(kDT) void k_diag_dense(DenseDiag A) {
+    __shared__ float sRow[kDRows][kDT / 64];
+    __shared__ double lds[kDT];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int strip = blockIdx.x, panel = blockIdx.y;
+    const int j0 = (strip * kDT + tid) * VEC;
+    double cjv[VEC];
+    bool jok[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        jok[e] = j0 + e < A.m;
+        cjv[e] = jok[e] ? A.cj[j0 + e] : -__builtin_huge_val();
+    }
+    float cs[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) cs[e] = 0.0f;
+    double cost_acc = 0.0, ent_acc = 0.0;
+    const int i0 = panel * A.rpp;
+    const int i1 = min(A.n, i0 + A.rpp);
+    for (int ib = i0; ib < i1; ib += kDRows) {
+        float cf = 0.0f, ef = 0.0f;            // this chunk's share of sum P (s C) and sum P e
+#pragma unroll 4
+        for (int r = 0; r < kDRows; ++r) {
+            const int i = ib + r;
+            float rs = 0.0f;
+            if (i < i1) {
+                float cv[VEC];
+                if constexpr (VEC == 4) {
+                    const float4 c4 = jok[0] ? *reinterpret_cast<const float4 *>(A.C + (size_t)i * A.m + j0)
+                                             : make_float4(0.f, 0.f, 0.f, 0.f);
+                    cv[0] = c4.x; cv[1] = c4.y; cv[2] = c4.z; cv[3] = c4.w;
+                } else {
+                    cv[0] = jok[0] ? A.C[(size_t)i * A.m + j0] : 0.0f;
+                }
+                const double rv = A.ri[i];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const double sc = A.s * (double)cv[e];
+                    const double arg = (rv + cjv[e]) - sc;
+                    const float p = fast_exp2((float)arg);
+                    if (p > 0.0f) {                                  // also skips NaN
+                        rs += p;
+                        cs[e] += p;
+                        cf = fmaf(p, (float)sc, cf);
+                        ef = fmaf(p, (float)arg, ef);
+                    }
+                }
+            }
+            rs = wave_sum_f32(rs);
+            if (lane == 0) sRow[r][wave] = rs;
+        }
+        cost_acc += (double)cf;
+        ent_acc += (double)ef;
+        __syncthreads();
+        if (tid < kDRows && ib + tid < i1) {
+            double tot = 0.0;
+#pragma unroll
+            for (int w = 0; w < kDT / 64; ++w) tot += (double)sRow[tid][w];
+            A.rowpart[(size_t)strip * A.n + ib + tid] = tot;
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e)
+        if (jok[e]) A.colpart[(size_t)panel * A.m + j0 + e] = cs[e];
+    const double c_tot = block_sum<kDT>(cost_acc, lds);
+    const double e_tot = block_sum<kDT>(ent_acc, lds);
+    if (tid == 0) {
+        const size_t w = (size_t)panel * gridDim.x + strip;
+        A.scal[2 * w] = c_tot;
+        A.scal[2 * w + 1] = e_tot;
+    }
+}
+
+// ---------------------------------------------------------------- points
+struct PointsDiag {
+    const double *rows;      // [nr][d] plain coordinates of the row side
+    const double *rowq;      // [nr] s |row|^2
+    const double *rowlog;    // [nr] ri (or cj): s pot + log2 weight
+    const double *cols2s;    // [nc][d] other side times 2s
+    const double *colq;      // [nc] s |col|^2
+    const double *collog;    // [nc]
+    int32_t nr, nc;
+    double *part;            // [JS][nr] row sums of this column slice
+    double *scal;            // [gridDim.x * JS][2] or null: sum P (s C), sum P e
+    int32_t cols_per_split;
+};
+
+template <int D, bool WITH_COST>
+__global__ __launch_bounds__(kPT2) void k_diag_points(PointsDiag A) {
+    __shared__ __align__(16) double tile[kTile2][D + 2];     // [0] collog - colq, [1..D] 2s y, [D+1] collog
+    __shared__ double lds[kPT2];
+    const int tid = threadIdx.x;
+    double x[kIB2][D], rc[kIB2], rq[kIB2];
+    int row[kIB2];
+    double rs[kIB2];
+#pragma unroll
+    for (int b = 0; b < kIB2; ++b) {
+        row[b] = (blockIdx.x * kIB2 + b) * kPT2 + tid;
+        const bool ok = row[b] < A.nr;
+#pragma unroll
+        for (int t = 0; t < D; ++t) x[b][t] = ok ? A.rows[(size_t)row[b] * D + t] : 0.0;
+        rq[b] = ok ? A.rowq[row[b]] : 0.0;
+        rc[b] = ok ? A.rowlog[row[b]] - rq[b] : -__builtin_huge_val();
+        rs[b] = 0.0;
+    }
+    double cost_acc = 0.0, ent_acc = 0.0;
+    const int j0 = blockIdx.y * A.cols_per_split;
+    const int j1 = min(A.nc, j0 + A.cols_per_split);
+    for (int jt = j0; jt < j1; jt += kTile2) {
+        __syncthreads();
+        {
+            const int j = jt + tid;
+            if (j < j1) {
+                const double lg = A.collog[j];
+                tile[tid][0] = lg - A.colq[j];
+#pragma unroll
+                for (int t = 0; t < D; ++t) tile[tid][1 + t] = A.cols2s[(size_t)j * D + t];
+                tile[tid][D + 1] = lg;
+            } else {
+                tile[tid][0] = -__builtin_huge_val();
+#pragma unroll
+                for (int t = 0; t < D; ++t) tile[tid][1 + t] = 0.0;
+                tile[tid][D + 1] = 0.0;
+            }
+        }
+        __syncthreads();
+        float rf[kIB2], cf = 0.0f, ef = 0.0f;
+#pragma unroll
+        for (int b = 0; b < kIB2; ++b) rf[b] = 0.0f;
+#pragma unroll 2
+        for (int jj = 0; jj < kTile2; ++jj) {
+            double w[D + 2];
+#pragma unroll
+            for (int t = 0; t < D + 2; ++t) w[t] = tile[jj][t];
+#pragma unroll
+            for (int b = 0; b < kIB2; ++b) {
+                double tq = w[0];                                                  // collog - colq + 2 s x.y
+#pragma unroll
+                for (int t = 0; t < D; ++t) tq = fma(x[b][t], w[1 + t], tq);
+                const double arg = tq + rc[b];
+                const float argf = (float)arg;
+                float p = fast_exp2(argf);
+                p = p > 0.0f ? p : 0.0f;                                           // drops NaN
+                rf[b] += p;
+                if (WITH_COST) {
+                    const double sc = (rq[b] + w[D + 1]) - tq;                     // s |x - y|^2, w[D+1] = collog
+                    cf = fmaf(p, fminf((float)sc, 1.0e30f), cf);                   // 0 * inf (or NaN) must stay 0:
+                    ef = fmaf(p, fmaxf(argf, -1.0e30f), ef);                       // zero-weight entries
+                }
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < kIB2; ++b) rs[b] += (double)rf[b];
+        cost_acc += (double)cf;
+        ent_acc += (double)ef;
+    }
+#pragma unroll
+    for (int b = 0; b < kIB2; ++b)
+        if (row[b] < A.nr) A.part[(size_t)blockIdx.y * A.nr + row[b]] = rs[b];
+    if (WITH_COST) {
+        const double c_tot = block_sum<kPT2>(cost_acc, lds);
+        const double e_tot = block_sum<kPT2>(ent_acc, lds);
+        if (tid == 0) {
+            const size_t w = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+            A.scal[2 * w] = c_tot;
+            A.scal[2 * w + 1] = e_tot;
+        }
+    }
+}
+
+// Any dimension: one row per lane, coordinates of the row re-read through the cache.
+template <bool WITH_COST>
+__global__ __launch_bounds__(kPT2) void k_diag_points_anyd(PointsDiag A, int d) {
+    extern __shared__ double dyn[];                         // [64][d + 2]
+    __shared__ double lds[kPT2];
+    constexpr int TJ = 64;
+    const int tid = threadIdx.x, ldt = d + 2;
+    const int row = blockIdx.x * kPT2 + tid;
+    const bool rok = row < A.nr;
+    const double *xr = A.rows + (size_t)(rok ? row : 0) * d;
+    const double rq = rok ? A.rowq[row] : 0.0;
+    const double rc = rok ? A.rowlog[row] - rq : -__builtin_huge_val();
+    double rs = 0.0, cost_acc = 0.0, ent_acc = 0.0;
+    const int j0 = blockIdx.y * A.cols_per_split;
+    const int j1 = min(A.nc, j0 + A.cols_per_split);
+    for (int jt = j0; jt < j1; jt += TJ) {
+        __syncthreads();
+        for (int e = tid; e < TJ * ldt; e += kPT2) {
+            const int jj = e / ldt, t = e % ldt;
+            const int j = jt + jj;
+            double v;
+            if (j < j1) v = (t == 0) ? A.collog[j] - A.colq[j] : (t == d + 1) ? A.colq[j] : A.cols2s[(size_t)j * d + (t - 1)];
+            else v = (t == 0) ? -__builtin_huge_val() : 0.0;
+            dyn[e] = v;
+        }
+        __syncthreads();
+        float rf = 0.0f, cf = 0.0f, ef = 0.0f;
+        for (int jj = 0; jj < TJ; ++jj) {
+            double dot = 0.0;
+            for (int t = 0; t < d; ++t) dot = fma(xr[t], dyn[jj * ldt + 1 + t], dot);
+            const double arg = (dyn[jj * ldt] + rc) + dot;
+            const float p = fast_exp2((float)arg);
+            if (p > 0.0f) {
+                rf += p;
+                if (WITH_COST) {
+                    const double sc = (rq + dyn[jj * ldt + d + 1]) - dot;
+                    cf = fmaf(p, (float)sc, cf);
+                    ef = fmaf(p, (float)arg, ef);
+                }
+            }
+        }
+        rs += (double)rf;
+        cost_acc += (double)cf;
+        ent_acc += (double)ef;
+    }
+    if (rok) A.part[(size_t)blockIdx.y * A.nr + row] = rs;
+    if (WITH_COST) {
+        const double c_tot = block_sum<kPT2>(cost_acc, lds);
+        const double e_tot = block_sum<kPT2>(ent_acc, lds);
+        if (tid == 0) {
+            const size_t w = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+            A.scal[2 * w] = c_tot;
+            A.scal[2 * w + 1] = e_tot;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- reduction of the partials
+// Entry t = row t and column t: marginals, their L1 errors, <a,f>, <b,g>, and the sums
+// r_i log2 a_i, c_j log2 b_j.  One record of 8 doubles per workgroup.
+struct ReduceArgs {
+    PlanArgs P;
+    const double *rowpart; int32_t nrowpart;      // [nrowpart][n]
+    const void *colpart; int32_t ncolpart;        // [ncolpart][m], float (dense) or double (points)
+    int32_t colpart_is_float;
+    double *row_marg, *col_marg;                  // optional outputs
+    double *red;                                  // [gridDim.x][8]
+};
+
+// A workgroup of 256 threads finishes 64 rows and 64 columns: lane = entry, the 4 waves split the
+// partial sets (8 loads in flight each) and meet in LDS.
+__global__ __launch_bounds__(256) void k_diag_reduce(ReduceArgs A) {
+    __shared__ double sR[4][64], sC[4][64];
+    const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int t = blockIdx.x * 64 + lane;
+    double r = 0.0, c = 0.0;
+    if (t < A.P.n) {
+        int q = grp;
+        for (; q + 28 < A.nrowpart; q += 32) {
+            double x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = A.rowpart[(size_t)(q + 4 * u) * A.P.n + t];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) r += x[u];
+        }
+        for (; q < A.nrowpart; q += 4) r += A.rowpart[(size_t)q * A.P.n + t];
+    }
+    if (t < A.P.m) {
+        int q = grp;
+        if (A.colpart_is_float) {
+            const float *cp = (const float *)A.colpart;
+            for (; q + 28 < A.ncolpart; q += 32) {
+                float x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = cp[(size_t)(q + 4 * u) * A.P.m + t];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) c += (double)x[u];
+            }
+            for (; q < A.ncolpart; q += 4) c += (double)cp[(size_t)q * A.P.m + t];
+        } else {
+            const double *cp = (const double *)A.colpart;
+            for (; q + 28 < A.ncolpart; q += 32) {
+                double x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = cp[(size_t)(q + 4 * u) * A.P.m + t];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) c += x[u];
+            }
+            for (; q < A.ncolpart; q += 4) c += cp[(size_t)q * A.P.m + t];
+        }
+    }
+    sR[grp][lane] = r;
+    sC[grp][lane] = c;
+    __syncthreads();
+    double v[7] = {0, 0, 0, 0, 0, 0, 0};          // mass, row err, col err, <a,f>, <b,g>, r.log2 a, c.log2 b
+    if (grp == 0) {
+        r = (sR[0][lane] + sR[1][lane]) + (sR[2][lane] + sR[3][lane]);
+        c = (sC[0][lane] + sC[1][lane]) + (sC[2][lane] + sC[3][lane]);
+        if (t < A.P.n) {
+            const float a = A.P.a[t];
+            if (A.row_marg) A.row_marg[t] = r;
+            v[0] = r;
+            v[1] = fabs(r - (double)a);
+            if (a > 0.0f) {
+                const double f = A.P.f64 ? A.P.f64[t] : (double)A.P.f[t];
+                v[3] = (double)a * f;
+                v[5] = r * log2((double)a);
+            }
+        }
+        if (t < A.P.m) {
+            const float b = A.P.b[t];
+            if (A.col_marg) A.col_marg[t] = c;
+            v[2] = fabs(c - (double)b);
+            if (b > 0.0f) {
+                const double g = A.P.g64 ? A.P.g64[t] : (double)A.P.g[t];
+                v[4] = (double)b * g;
+                v[6] = c * log2((double)b);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 7; ++q) {
+            const double tot = wave_sum_f64(v[q]);
+            if (lane == 0) A.red[(size_t)blockIdx.x * 8 + q] = tot;
+        }
+    }
+}
+
+// out[0] cost, [1] mass, [2] KL(P | a x b), [3] primal, [4] dual, [5] row-marginal L1 error,
+// [6] column-marginal L1 error, [7] 0.
+__global__ __launch_bounds__(256) void k_diag_final(const double *red, int nred, const double *scal, int nscal,
+                                                    double s, double *out, double *cost_out) {
+    __shared__ double lds[256];
+    double v[7];
+    for (int q = 0; q < 7; ++q) {
+        double acc = 0.0;
+        for (int w = threadIdx.x; w < nred; w += 256) acc += red[(size_t)w * 8 + q];
+        v[q] = block_sum<256>(acc, lds);
+    }
+    double sc[2];
+    for (int q = 0; q < 2; ++q) {
+        double acc = 0.0;
+        for (int w = threadIdx.x; w < nscal; w += 256) acc += scal[(size_t)w * 2 + q];
+        sc[q] = block_sum<256>(acc, lds);
+    }
+    if (threadIdx.x == 0) {
+        const double eps = 1.4426950408889634074 / s;
+        const double mass = v[0];
+        const double cost = sc[0] / s;
+        const double plogp = kLn2d * (sc[1] - v[5] - v[6]);      // sum P log(P/(a b))
+        const double kl = plogp - mass + 1.0;
+        out[0] = cost;
+        out[1] = mass;
+        out[2] = kl;
+        out[3] = cost + eps * kl;
+        out[4] = v[3] + v[4] - eps * mass + eps;
+        out[5] = v[1];
+        out[6] = v[2];
+        out[7] = 0.0;
+        if (cost_out) cost_out[0] = cost;
+    }
+}
+
+}  // namespace
+
+size_t diag_scratch_bytes(int n, int m, int d) { return diag_layout(n, m, d).total; }
+
+// cost_only_out non-null: only the cost is wanted (out8 may be null; the pass that exists only for the
+// column marginals of a point-cloud problem is skipped).
+hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *row_marg, double *col_marg,
+                       void *scratch, size_t scratch_bytes, double *cost_only_out) {
+    const DiagLayout L = diag_layout(a.n, a.m, a.d);
+    if (scratch_bytes < L.total) return hipErrorInvalidValue;
+    unsigned char *ws = (unsigned char *)scratch;
+    if (!out8) out8 = (double *)(ws + L.o_out);
+    const bool cost_only = cost_only_out != nullptr;
+    double *ri = (double *)(ws + L.o_ri), *cj = (double *)(ws + L.o_cj);
+    const int len = a.n > a.m ? a.n : a.m;
+    double *xp = nullptr, *xs = nullptr, *xq = nullptr, *yp = nullptr, *ys = nullptr, *yq = nullptr;
+    if (a.d > 0) {
+        xp = (double *)(ws + L.o_xp); xs = (double *)(ws + L.o_xs); xq = (double *)(ws + L.o_xq);
+        yp = (double *)(ws + L.o_yp); ys = (double *)(ws + L.o_ys); yq = (double *)(ws + L.o_yq);
+    }
+    hipLaunchKernelGGL(k_diag_prep, dim3((len + 255) / 256), dim3(256), 0, st, a, ri, cj, xp, xs, xq, yp, ys, yq);
+    ReduceArgs R{};
+    R.P = a;
+    R.row_marg = row_marg; R.col_marg = col_marg;
+    R.red = (double *)(ws + L.o_red);
+    double *scal = (double *)(ws + L.o_scal);
+    if (a.d == 0) {
+        DenseDiag D{};
+        D.C = a.C; D.ri = ri; D.cj = cj; D.n = a.n; D.m = a.m; D.s = a.s;
+        D.rowpart = (double *)(ws + L.o_rowpart);
+        D.colpart = (float *)(ws + L.o_colpart);
+        D.scal = scal; D.rpp = L.rpp;
+        const dim3 grid(L.nstrips, L.P);
+        if (L.vec == 4) hipLaunchKernelGGL(k_diag_dense<4>, grid, dim3(kDT), 0, st, D);
+        else hipLaunchKernelGGL(k_diag_dense<1>, grid, dim3(kDT), 0, st, D);
+        R.rowpart = D.rowpart; R.nrowpart = L.nstrips;
+        R.colpart = D.colpart; R.ncolpart = L.P; R.colpart_is_float = 1;
+    } else {
+        PointsDiag X{};                         // rows = x side: row marginals, cost, entropy
+        X.rows = xp; X.rowq = xq; X.rowlog = ri; X.cols2s = ys; X.colq = yq; X.collog = cj;
+        X.nr = a.n; X.nc = a.m; X.part = (double *)(ws + L.o_rowpart); X.scal = scal; X.cols_per_split = L.cpsx;
+        PointsDiag Y{};                         // rows = y side: column marginals only
+        Y.rows = yp; Y.rowq = yq; Y.rowlog = cj; Y.cols2s = xs; Y.colq = xq; Y.collog = ri;
+        Y.nr = a.m; Y.nc = a.n; Y.part = (double *)(ws + L.o_colpart); Y.scal = nullptr; Y.cols_per_split = L.cpsy;
+        if (a.d <= 4) {
+            const dim3 gx((a.n + kPT2 * kIB2 - 1) / (kPT2 * kIB2), L.JSx), gy((a.m + kPT2 * kIB2 - 1) / (kPT2 * kIB2), L.JSy);
+            switch (a.d) {
+                case 1: hipLaunchKernelGGL((k_diag_points<1, true>), gx, dim3(kPT2), 0, st, X);
+                        if (!cost_only) hipLaunchKernelGGL((k_diag_points<1, false>), gy, dim3(kPT2), 0, st, Y);
+                        break;
+                case 2: hipLaunchKernelGGL((k_diag_points<2, true>), gx, dim3(kPT2), 0, st, X);
+                        if (!cost_only) hipLaunchKernelGGL((k_diag_points<2, false>), gy, dim3(kPT2), 0, st, Y);
+                        break;
+                case 3: hipLaunchKernelGGL((k_diag_points<3, true>), gx, dim3(kPT2), 0, st, X);
+                        if (!cost_only) hipLaunchKernelGGL((k_diag_points<3, false>), gy, dim3(kPT2), 0, st, Y);
+                        break;
+                default: hipLaunchKernelGGL((k_diag_points<4, true>), gx, dim3(kPT2), 0, st, X);
+                         if (!cost_only) hipLaunchKernelGGL((k_diag_points<4, false>), gy, dim3(kPT2), 0, st, Y);
+                        break;
+            }
+        } else {
+            const dim3 gx((a.n + kPT2 - 1) / kPT2, L.JSx), gy((a.m + kPT2 - 1) / kPT2, L.JSy);
+            const size_t lds = (size_t)64 * (a.d + 2) * sizeof(double);
+            hipLaunchKernelGGL(k_diag_points_anyd<true>, gx, dim3(kPT2), lds, st, X, a.d);
+            if (!cost_only) hipLaunchKernelGGL(k_diag_points_anyd<false>, gy, dim3(kPT2), lds, st, Y, a.d);
+        }
+        R.rowpart = X.part; R.nrowpart = L.JSx;
+        R.colpart = Y.part; R.ncolpart = cost_only ? 0 : L.JSy; R.colpart_is_float = 0;
+    }
+    hipLaunchKernelGGL(k_diag_reduce, dim3(L.nred), dim3(256), 0, st, R);
+    hipLaunchKernelGGL(k_diag_final, dim3(1), dim3(256), 0, st, R.red, L.nred, scal, L.nscal, a.s, out8, cost_only_out);
+    return hipGetLastError();
+}
+
+}  // namespace fs

@@ -136,4 +136,9 @@ hipError_t launch_plan(hipStream_t st, const PlanArgs &a, float *P, double *scra
 hipError_t launch_cost(hipStream_t st, const PlanArgs &a, double *cost_dev, double *scratch, int nscratch);
 int cost_scratch_len(int n, int m);
 
+// Diagnostics in one pass (cost, mass, KL, primal, dual, marginal errors; optional marginals).
+size_t diag_scratch_bytes(int n, int m, int d);
+hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *row_marg, double *col_marg,
+                       void *scratch, size_t scratch_bytes, double *cost_only_out = nullptr);
+
 }  // namespace fs

@@ -275,6 +275,42 @@ def test_plan_and_cost(fs, oracle, kind):
 
 
 # ------------------------------------------------------------------ closed form at size (independent of the oracle)
+@pytest.mark.parametrize("kind,n,m,d", [("dense", 300, 257, 0), ("dense", 130, 4100, 0), ("dense", 1000, 8192, 0),
+                                         ("dense", 33, 1, 0), ("points", 700, 1300, 3), ("points", 1030, 500, 2),
+                                         ("points", 90, 200, 7)])
+@pytest.mark.parametrize("precision", ["f32", "f64"])
+def test_diagnostics_one_pass(fs, oracle, kind, n, m, d, precision):
+    """fs_diagnostics against the oracle's direct definitions (explicit plan, own sums): cost, mass, KL,
+    primal, dual, both marginals and their L1 errors, from potentials that are NOT converged (so that
+    no term vanishes) and with some zero weights."""
+    w = W.random_dense(n, m, seed=6000 + n + m, cmax=2.0, eps=0.05) if kind == "dense" else \
+        W.random_points(n, m, d, seed=6000 + n + m + d, eps=0.05)
+    if n > 40:
+        w.a[5::11] = 0.0
+        w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    ref = oracle.solve(w.a, w.b, w.eps, 3, C=w.C, X=w.X, Y=w.Y)
+    f_h, g_h = ref["f"], ref["g"]
+    if precision == "f32":
+        f_h, g_h = f_h.astype(np.float32).astype(np.float64), g_h.astype(np.float32).astype(np.float64)
+    import torch
+    geo, a, b = to_dev(w)
+    dt = torch.float32 if precision == "f32" else torch.float64
+    r = fs.fs_diagnostics(a, b, w.eps, dev(f_h, dt), dev(g_h, dt), want_marginals=True, **geo)
+    out = r["out"].cpu().numpy()
+    o = oracle.objectives(w.a, w.b, w.eps, f_h, g_h, C=w.C, X=w.X, Y=w.Y)
+    ro, co = oracle.marginals(w.a, w.b, w.eps, f_h, g_h, C=w.C, X=w.X, Y=w.Y)
+    got = dict(zip(fs.DIAG_FIELDS, out))
+    for key in ("cost", "mass", "kl", "primal", "dual"):
+        assert abs(got[key] - float(o[key])) <= 2e-6 * max(1.0, abs(float(o[key]))), (key, got[key], float(o[key]))
+    assert np.abs(r["row_marginal"].cpu().numpy() - ro).sum() <= 2e-6
+    assert np.abs(r["col_marginal"].cpu().numpy() - co).sum() <= 2e-6
+    assert abs(got["row_err"] - np.abs(ro - w.a).sum()) <= 2e-6
+    assert abs(got["col_err"] - np.abs(co - w.b).sum()) <= 2e-6
+    # the stand-alone cost entry point agrees
+    cost2 = float(fs.fs_cost(a, b, w.eps, dev(f_h, dt), dev(g_h, dt), **geo).cpu()[0])
+    assert abs(cost2 - got["cost"]) <= 2e-6 * max(1.0, abs(got["cost"]))
+
+
 @pytest.mark.parametrize("mode", [1, 2])
 def test_separable_cost_closed_form_large(fs, mode):
     """C_ij = u_i + v_j (exactly representable) => after ONE iteration f = u + kappa, g = v - kappa - eps log(sum a),
