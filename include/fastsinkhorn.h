@@ -51,6 +51,7 @@ typedef void *fs_stream;
 
 #define FS_MAX_DIM 64
 #define FS_MAX_POINTS 1048512   /* 16383 * 64 */
+#define FS_SMALL_MAX 256        /* largest n, m of the single-workgroup / batched kernel */
 
 typedef enum {
     FS_OK = 0,
@@ -74,7 +75,9 @@ typedef struct {
     int32_t check_every;     /* c of Alg. 1; 0 -> 10 (Sec. 4.5)                                     */
     int32_t warm_start;      /* 0: start from f = g = 0 (Eqs. 6-7); 1: start from the f, g passed in */
     int32_t kernel_mode;     /* 0: automatic; 1: streaming row / column kernels; 2: fused row-panel
-                                kernel (dense only; FS_ERR_UNSUPPORTED if the shape does not fit)    */
+                                kernel (dense only; FS_ERR_UNSUPPORTED if the shape does not fit);
+                                3: the whole solve in one single-workgroup kernel (dense, n, m <=
+                                FS_SMALL_MAX, else FS_ERR_UNSUPPORTED; what 0 picks up to about 128 x 128) */
     int32_t use_graph;       /* 0: automatic; 1: plain stream launches; 2: hipGraph iteration blocks  */
     int32_t skip_final_err;  /* 1: do not spend the one trailing pass that evaluates err after the
                                 last iteration when no stop fired (marginal_err is then NaN)          */
@@ -155,6 +158,16 @@ fs_status fs_plan_f64(const float *C, const float *X, const float *Y, int d, con
 fs_status fs_cost_f64(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
                       int n, int m, float eps, const double *f64, const double *g64, double *cost_dev,
                       fs_stream stream);
+
+/* ---- Many small dense problems of one shape in ONE launch (Alg. 1 entirely on the device, one
+ * workgroup per problem, C held in registers; the paper's latency-sensitive regime, n >= 64 in its
+ * Table 3).  n, m <= FS_SMALL_MAX.  Problem p reads C + p*n*m, a + p*n, b + p*m and writes f + p*n,
+ * g + p*m and result_dev[p] (optional, device).  Options used: check_every, warm_start (f, g or f64_in,
+ * g64_in hold `batch` starting points), skip_final_err, f64_out / g64_out ([batch][n], [batch][m]),
+ * err_history ([batch][err_history_len]).  Asynchronous on `stream`; needs no workspace. ---- */
+fs_status fs_sinkhorn_dense_batched(const float *C, const float *a, const float *b, int batch, int n, int m,
+                                    float eps, int max_iter, float tol, float *f, float *g, fs_stream stream,
+                                    const fs_options *opts, fs_result *result_dev);
 
 /* ---- Diagnostics of a pair of potentials in ONE pass over C (or, for point clouds, one pass over all
  * pairs per side): everything Alg. 1 reports after the loop and everything Secs. 3 and 4.5 define on

@@ -77,6 +77,9 @@ def _load():
         fn = getattr(lib, name)
         fn.restype = ci
         fn.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, vp, vp, vp, vp]
+    lib.fs_sinkhorn_dense_batched.restype = ci
+    lib.fs_sinkhorn_dense_batched.argtypes = [vp, vp, vp, ci, ci, ci, cf, ci, cf, vp, vp, vp,
+                                              ctypes.POINTER(fs_options), vp]
     lib.fs_diagnostics.restype = ci
     lib.fs_diagnostics.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, vp, vp, vp, vp, vp, vp, vp, vp]
     for name in ("fs_update_f", "fs_update_g"):
@@ -89,7 +92,7 @@ def _load():
 _lib = _load()
 
 EXPORTED = ("fs_sinkhorn_dense", "fs_sinkhorn_points", "fs_sinkhorn_solve", "fs_workspace_bytes",
-            "fs_sinkhorn_dense_ex", "fs_sinkhorn_points_ex", "fs_plan", "fs_cost", "fs_plan_f64",
+            "fs_sinkhorn_dense_ex", "fs_sinkhorn_points_ex", "fs_sinkhorn_dense_batched", "fs_plan", "fs_cost", "fs_plan_f64",
             "fs_cost_f64", "fs_diagnostics", "fs_update_f", "fs_update_g", "fs_last_error", "fs_clear_cache", "fs_version",
             "fs_last_kernel_timing")
 
@@ -265,6 +268,37 @@ def fs_sinkhorn_dense_ex(C, a, b, eps, max_iter, tol, f=None, g=None, workspace=
 def fs_sinkhorn_points_ex(X, Y, a, b, eps, max_iter, tol, f=None, g=None, workspace=None, **opt_kw) -> AsyncSolve:
     """Asynchronous point-cloud solve on the current stream (no host synchronisation)."""
     return _ex(False, None, X, Y, a, b, eps, max_iter, tol, f, g, workspace, opt_kw)
+
+
+def fs_sinkhorn_dense_batched(C, a, b, eps, max_iter, tol, f=None, g=None, want_f64=False, **opt_kw):
+    """`batch` small dense problems of one shape in one launch (C [B, n, m], a [B, n], b [B, m]; n, m <= 256).
+    Asynchronous.  Returns dict(f [B, n], g [B, m], result = uint8 tensor [B, 16] of fs_result records
+    (decode with results_from_device)[, f64, g64])."""
+    if C.dim() != 3 or a.dim() != 2 or b.dim() != 2:
+        raise ValueError("expected C [B, n, m], a [B, n], b [B, m]")
+    B, n, m = (int(x) for x in C.shape)
+    if tuple(a.shape) != (B, n) or tuple(b.shape) != (B, m):
+        raise ValueError("a, b must have shapes (B, n), (B, m)")
+    dev = C.device
+    f = torch.empty((B, n), dtype=torch.float32, device=dev) if f is None else f
+    g = torch.empty((B, m), dtype=torch.float32, device=dev) if g is None else g
+    out = dict(f=f, g=g)
+    if want_f64:
+        out["f64"] = torch.empty((B, n), dtype=torch.float64, device=dev)
+        out["g64"] = torch.empty((B, m), dtype=torch.float64, device=dev)
+        opt_kw.update(f64_out=out["f64"], g64_out=out["g64"])
+    o = make_options(**opt_kw)
+    res = torch.zeros((B, 16), dtype=torch.uint8, device=dev)
+    _check(_lib.fs_sinkhorn_dense_batched(_p(C), _p(a), _p(b), B, n, m, float(eps), int(max_iter), float(tol),
+                                          _p(f), _p(g), _stream(), ctypes.byref(o), _p(res, torch.uint8)))
+    out["result"] = res
+    return out
+
+
+def results_from_device(t: torch.Tensor):
+    """Decode a [B, 16] uint8 tensor of fs_result records (synchronises)."""
+    raw = t.cpu().numpy()
+    return [_result_from_device(torch.from_numpy(raw[q].copy())) for q in range(raw.shape[0])]
 
 
 def _pots(f, g):

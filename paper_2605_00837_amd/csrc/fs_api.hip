@@ -365,7 +365,7 @@ fs_status setup(Solve &S, const Problem &pr, const fs_options *opts, float *f, f
     if (pr.C) {
         const bool fused_ok = dense_fused_supported(pr.n, pr.m, pr.C);
         if (S.opt.kernel_mode == 2 && !fused_ok) { set_err("fused kernel does not support m = %d (needs m %% 4 == 0, m <= 8192, 16-byte aligned C)", pr.m); return FS_ERR_UNSUPPORTED; }
-        if (S.opt.kernel_mode < 0 || S.opt.kernel_mode > 2) { set_err("kernel_mode must be 0, 1 or 2"); return FS_ERR_INVALID_ARG; }
+        if (S.opt.kernel_mode < 0 || S.opt.kernel_mode > 2) { set_err("kernel_mode must be 0, 1, 2 or 3"); return FS_ERR_INVALID_ARG; }
         S.mode = S.opt.kernel_mode == 0 ? (fused_ok ? 2 : 1) : S.opt.kernel_mode;
         if (S.mode == 2 && dense_fused_grid(pr.n, pr.m, S.opt.fused_variant) == 0) S.opt.fused_variant = 0;
     } else {
@@ -527,10 +527,69 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     return hb->res.iters;
 }
 
+// Small dense problems run whole inside one single-workgroup kernel (fs_small.hip).
+bool small_path(const Problem &pr, const fs_options *opts, fs_status *err) {
+    const int km = opts ? opts->kernel_mode : 0;
+    const bool fits = pr.C && pr.n <= kSmallMax && pr.m <= kSmallMax;
+    if (km == 3 && !fits) {
+        set_err("kernel_mode 3 needs a dense problem with n, m <= %d", kSmallMax);
+        *err = FS_ERR_UNSUPPORTED;
+        return false;
+    }
+    if (!fits || (opts && opts->time_kernel_every > 0)) return false;
+    if (km == 3) return true;
+    // automatic: up to 16 entries per lane (e.g. 128 x 128, 256 x 64) one workgroup beats the multi-kernel
+    // path (2.5 - 5 us against 10 us per iteration); beyond that a single compute unit is the limit
+    auto slots = [](int x) { const int q = (x + 31) / 32; return q <= 2 ? 2 : q <= 4 ? 4 : 8; };
+    return km == 0 && slots(pr.n) * slots(pr.m) <= 16;
+}
+
+fs_status small_args(const Problem &pr, int batch, const fs_options *opts, float *f, float *g, SmallArgs *out) {
+    fs_options o{};
+    if (opts) o = *opts;
+    if (o.check_every <= 0) o.check_every = 10;
+    if (o.err_history && o.err_history_len < 0) { set_err("err_history_len < 0"); return FS_ERR_INVALID_ARG; }
+    SmallArgs A{};
+    A.C = pr.C; A.a = pr.a; A.b = pr.b;
+    A.n = pr.n; A.m = pr.m; A.batch = batch;
+    A.s = kLog2e / (double)pr.eps;
+    A.max_iter = pr.max_iter; A.check_every = o.check_every;
+    A.tol = pr.tol > 0.0f ? (double)pr.tol : 0.0;
+    A.warm = o.warm_start ? 1 : 0;
+    A.f_in = f; A.g_in = g;
+    A.f64_in = (o.f64_in && o.g64_in) ? o.f64_in : nullptr;
+    A.g64_in = (o.f64_in && o.g64_in) ? o.g64_in : nullptr;
+    A.f = f; A.g = g;
+    A.f64_out = o.f64_out; A.g64_out = o.g64_out;
+    A.err_history = o.err_history; A.err_history_len = o.err_history ? o.err_history_len : 0;
+    A.want_final_err = o.skip_final_err ? 0 : 1;
+    *out = A;
+    return FS_OK;
+}
+
 int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const fs_options *opts,
                    fs_result *result_host) {
     fs_status v = validate(pr, f, g);
     if (v != FS_OK) return v;
+    fs_status serr = FS_OK;
+    if (small_path(pr, opts, &serr)) {
+        DeviceCache *dc = nullptr;
+        v = get_cache(256, &dc);
+        if (v != FS_OK) return v;
+        HostBlock *hb = dc->host;
+        memset((void *)&hb->res, 0, sizeof(hb->res));
+        void *hb_dev = nullptr;
+        FS_HIP(hipHostGetDevicePointer(&hb_dev, (void *)hb, 0));
+        SmallArgs A;
+        v = small_args(pr, 1, opts, f, g, &A);
+        if (v != FS_OK) return v;
+        A.result = (ResultRecord *)((char *)hb_dev + offsetof(HostBlock, res));
+        FS_HIP(launch_small(st, A));
+        FS_HIP(hipStreamSynchronize(st));
+        if (result_host) *result_host = hb->res;
+        return hb->res.iters;
+    }
+    if (serr != FS_OK) return serr;
     Layout L = make_layout(pr.n, pr.m, pr.C ? 0 : pr.d);
     DeviceCache *dc = nullptr;
     v = get_cache(L.total, &dc);
@@ -545,6 +604,20 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
                       void *ws, size_t ws_bytes, fs_result *result_dev) {
     fs_status v = validate(pr, f, g);
     if (v != FS_OK) return v;
+    fs_status serr = FS_OK;
+    if (small_path(pr, opts, &serr)) {
+        // the workspace contract is the same whichever kernel ends up running
+        if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) { set_err("workspace must be non-null and 256-byte aligned"); return FS_ERR_WORKSPACE; }
+        const size_t need = make_layout(pr.n, pr.m, 0).total;
+        if (ws_bytes < need) { set_err("workspace too small: %zu < %zu bytes", ws_bytes, need); return FS_ERR_WORKSPACE; }
+        SmallArgs A;
+        v = small_args(pr, 1, opts, f, g, &A);
+        if (v != FS_OK) return v;
+        A.result = (ResultRecord *)result_dev;
+        FS_HIP(launch_small(st, A));
+        return FS_OK;
+    }
+    if (serr != FS_OK) return serr;
     Solve S;
     v = setup(S, pr, opts, f, g, st, ws, ws_bytes);
     if (v != FS_OK) return v;
@@ -704,6 +777,27 @@ fs_status fs_sinkhorn_points_ex(const float *X, const float *Y, int d, const flo
     if (!X || !Y) { set_err("X and Y must be non-null"); return FS_ERR_INVALID_ARG; }
     Problem pr{nullptr, X, Y, a, b, d, n, m, eps, max_iter, tol};
     return solve_async(pr, f, g, (hipStream_t)stream, opts, workspace, workspace_bytes, result_dev);
+}
+
+fs_status fs_sinkhorn_dense_batched(const float *C, const float *a, const float *b, int batch, int n, int m,
+                                    float eps, int max_iter, float tol, float *f, float *g, fs_stream stream,
+                                    const fs_options *opts, fs_result *result_dev) {
+    if (!C) { set_err("C must be non-null"); return FS_ERR_INVALID_ARG; }
+    if (batch < 1) { set_err("batch must be >= 1 (got %d)", batch); return FS_ERR_INVALID_ARG; }
+    Problem pr{C, nullptr, nullptr, a, b, 0, n, m, eps, max_iter, tol};
+    fs_status v = validate(pr, f, g);
+    if (v != FS_OK) return v;
+    if (n > FS_SMALL_MAX || m > FS_SMALL_MAX) {
+        set_err("batched solves need n, m <= %d (got %d, %d)", FS_SMALL_MAX, n, m);
+        return FS_ERR_UNSUPPORTED;
+    }
+    if (opts && opts->kernel_mode != 0 && opts->kernel_mode != 3) { set_err("batched solves have one kernel (kernel_mode 0 or 3)"); return FS_ERR_INVALID_ARG; }
+    SmallArgs A;
+    v = small_args(pr, batch, opts, f, g, &A);
+    if (v != FS_OK) return v;
+    A.result = (ResultRecord *)result_dev;
+    FS_HIP(launch_small((hipStream_t)stream, A));
+    return FS_OK;
 }
 
 fs_status fs_plan(const float *C, const float *X, const float *Y, int d, const float *a, const float *b, int n,

@@ -141,4 +141,25 @@ size_t diag_scratch_bytes(int n, int m, int d);
 hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *row_marg, double *col_marg,
                        void *scratch, size_t scratch_bytes, double *cost_only_out = nullptr);
 
+// Whole solve of small dense problems in one launch (one workgroup per problem).
+constexpr int kSmallMax = 256;
+struct ResultRecord { int32_t iters, converged, nonfinite; float marginal_err; };    // = fs_result
+struct SmallArgs {
+    const float *C, *a, *b;          // [batch][n][m], [batch][n], [batch][m]
+    int32_t n, m, batch;
+    double s;
+    int32_t max_iter, check_every;
+    double tol;                      // <= 0: fixed iteration count
+    int32_t warm;                    // 1: start from f_in, g_in (or f64_in, g64_in when non-null)
+    const float *f_in, *g_in;
+    const double *f64_in, *g64_in;
+    float *f, *g;                    // [batch][n], [batch][m]
+    double *f64_out, *g64_out;       // optional
+    float *err_history;              // optional [batch][err_history_len]
+    int32_t err_history_len;
+    int32_t want_final_err;          // evaluate err of the last iterate when no stop fired
+    ResultRecord *result;            // optional [batch], device or pinned host memory
+};
+hipError_t launch_small(hipStream_t st, const SmallArgs &a);
+
 }  // namespace fs

@@ -87,8 +87,6 @@ __global__ __launch_bounds__(256) void k_finalize(Pots p, State *state, float *f
     if (bad) atomicOr(&state->nonfinite, 1);
 }
 
-struct ResultRecord { int32_t iters, converged, nonfinite; float marginal_err; };
-
 __global__ void k_result(State *state, ResultRecord *dev, ResultRecord *host) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     ResultRecord r;

@@ -166,6 +166,85 @@ def test_points_optimistic_pass_and_repair(fs, oracle, n, m, d, zero):
     assert e64b < TOL_F64 and e32b < TOL_F32
 
 
+# ------------------------------------------------------------------ single-workgroup kernel, batched solves
+SMALL_SHAPES = [(1, 1), (1, 7), (5, 1), (31, 33), (64, 64), (100, 37), (128, 256), (256, 129), (256, 256), (200, 255)]
+
+
+@pytest.mark.parametrize("n,m", SMALL_SHAPES)
+def test_small_kernel_matches_oracle(fs, oracle, n, m):
+    """kernel_mode = 3: the whole solve inside one workgroup (also what the automatic mode picks here)."""
+    w = W.random_dense(n, m, seed=7000 + n + m, cmax=2.0, eps=0.02)
+    if n > 8:
+        w.a[2::9] = 0.0
+        w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 40, kernel_mode=3)
+    assert e64 < TOL_F64 and e32 < TOL_F32
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+    # the multi-kernel path gives the same potentials (to rounding)
+    r1, _, _, _ = _solve_and_compare(fs, oracle, w, 40, kernel_mode=1)
+    assert float((r1["f64"] - r["f64"]).abs().max()) / w.eps < TOL_F64
+
+
+def test_small_kernel_stop_rule_history_and_resume(fs, oracle):
+    import torch
+    w = W.random_dense(150, 190, seed=7100, cmax=1.0, eps=0.05)
+    geo, a, b = to_dev(w)
+    ref = oracle.solve(w.a, w.b, w.eps, 400, tol=1e-5, check_every=7, C=w.C, err_every_iter=True)
+    hist = torch.full((400,), float("nan"), dtype=torch.float32, device="cuda")
+    r = fs.fs_sinkhorn_solve(a, b, w.eps, 400, 1e-5, C=geo["C"], want_f64=True, check_every=7, kernel_mode=3,
+                             err_history=hist)
+    assert r["converged"] and ref["converged"]
+    assert abs(r["iters"] - int(ref["iters"])) <= 7 and r["iters"] % 7 == 0
+    k = r["iters"]
+    refk = oracle.solve(w.a, w.b, w.eps, k, C=w.C)
+    assert pot_err(r["f64"].cpu().numpy(), refk["f"], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), refk["g"], w.eps) < TOL_F64
+    h = hist.cpu().numpy()
+    eh = np.asarray(ref["err_hist"], dtype=np.float64)
+    upto = min(k, int(ref["iters"]))
+    assert np.all(np.isfinite(h[:upto]))
+    assert np.allclose(h[:upto], eh[:upto], rtol=2e-3, atol=5e-7)
+    assert np.all(np.isnan(h[k:]))
+    # fixed count without the trailing error pass; resume from fp64 potentials = one longer run
+    r1 = fs.fs_sinkhorn_solve(a, b, w.eps, 11, 0.0, C=geo["C"], want_f64=True, kernel_mode=3, skip_final_err=True)
+    assert math.isnan(r1["marginal_err"]) and r1["iters"] == 11
+    r2 = fs.fs_sinkhorn_solve(a, b, w.eps, 9, 0.0, C=geo["C"], want_f64=True, kernel_mode=3, warm_start=True,
+                              f64_in=r1["f64"], g64_in=r1["g64"])
+    r3 = fs.fs_sinkhorn_solve(a, b, w.eps, 20, 0.0, C=geo["C"], want_f64=True, kernel_mode=3)
+    assert float((r2["f64"] - r3["f64"]).abs().max()) / w.eps < 1e-9
+    assert float((r2["g64"] - r3["g64"]).abs().max()) / w.eps < 1e-9
+    # max_iter = 0 returns the start
+    r0 = fs.fs_sinkhorn_solve(a, b, w.eps, 0, 0.0, C=geo["C"], kernel_mode=3)
+    assert r0["iters"] == 0 and float(r0["f"].abs().max()) == 0.0 and float(r0["g"].abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("B,n,m", [(1, 64, 64), (7, 100, 90), (300, 64, 64), (33, 256, 256)])
+def test_batched_small_solves(fs, oracle, B, n, m):
+    import torch
+    ws = [W.random_dense(n, m, seed=7200 + 13 * q + n, cmax=1.5, eps=0.03) for q in range(B)]
+    C = torch.from_numpy(np.stack([w.C for w in ws])).cuda()
+    a = torch.from_numpy(np.stack([w.a for w in ws])).cuda()
+    b = torch.from_numpy(np.stack([w.b for w in ws])).cuda()
+    out = fs.fs_sinkhorn_dense_batched(C, a, b, ws[0].eps, 30, 0.0, want_f64=True)
+    res = fs.results_from_device(out["result"])
+    f64, g64 = out["f64"].cpu().numpy(), out["g64"].cpu().numpy()
+    for q in sorted(set([0, B // 2, B - 1] + list(range(0, B, max(1, B // 6))))):
+        ref = oracle.solve(ws[q].a, ws[q].b, ws[q].eps, 30, C=ws[q].C)
+        assert res[q]["iters"] == 30 and not res[q]["nonfinite"]
+        assert pot_err(f64[q], ref["f"], ws[q].eps) < TOL_F64 and pot_err(g64[q], ref["g"], ws[q].eps) < TOL_F64
+        err_ref = float(oracle.marginal_err(ws[q].a, ws[q].b, ws[q].eps, ref["f"], ref["g"], C=ws[q].C))
+        assert abs(res[q]["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+    # problems stop independently: a tolerance only the easy ones reach
+    out2 = fs.fs_sinkhorn_dense_batched(C, a, b, ws[0].eps, 500, 1e-4, check_every=5)
+    res2 = fs.results_from_device(out2["result"])
+    ref0 = oracle.solve(ws[0].a, ws[0].b, ws[0].eps, 500, tol=1e-4, check_every=5, C=ws[0].C)
+    assert res2[0]["converged"] == bool(ref0["converged"]) and abs(res2[0]["iters"] - int(ref0["iters"])) <= 5
+    with pytest.raises(fs.FsError):
+        fs.fs_sinkhorn_dense_batched(torch.zeros((2, 300, 8), device="cuda"), torch.ones((2, 300), device="cuda"),
+                                     torch.ones((2, 8), device="cuda"), 0.1, 3, 0.0)
+
+
 # ------------------------------------------------------------------ stopping rule, history, resume
 @pytest.mark.parametrize("kind,mode", [("dense", 1), ("dense", 2), ("points", 0)])
 def test_stopping_rule_and_history(fs, oracle, kind, mode):
