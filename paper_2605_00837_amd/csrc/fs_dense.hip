@@ -640,7 +640,11 @@ static bool fused_shape(int m, int variant, FusedShape *fsh) {
     if (m % 4 != 0) return false;
     if (variant >= 100) variant -= 100;
     if (m <= 1024) { *fsh = {256, 1, 4}; return true; }
-    if (m <= 4096) { *fsh = {1024, 1, 4}; return true; }
+    if (m <= 4096) {
+        if (variant == 1) *fsh = {1024, 1, 4};               // register panel, exact running-max arithmetic
+        else *fsh = {1024, 1, 302};                          // asynchronous LDS prefetch, one 16-byte load per lane and row
+        return true;
+    }
     if (m <= 8192) {
         if (variant == 1) *fsh = {512, 4, 4};
         else if (variant == 2) *fsh = {1024, 2, 4};
@@ -683,7 +687,9 @@ hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, 
     DenseArgs b = a;
     b.P = g;
     const dim3 grid(g);
-    if (s.R == 302 && a.p.m == 8192 && variant % 100 != 5) hipLaunchKernelGGL((k_fused_pf<2, 2, true>), grid, dim3(1024), 0, st, b, c);
+    if (s.R == 302 && s.Q == 1 && a.p.m == 4096) hipLaunchKernelGGL((k_fused_pf<1, 2, true>), grid, dim3(1024), 0, st, b, c);
+    else if (s.R == 302 && s.Q == 1) hipLaunchKernelGGL((k_fused_pf<1, 2, false>), grid, dim3(1024), 0, st, b, c);
+    else if (s.R == 302 && a.p.m == 8192 && variant % 100 != 5) hipLaunchKernelGGL((k_fused_pf<2, 2, true>), grid, dim3(1024), 0, st, b, c);
     else if (s.R == 302) hipLaunchKernelGGL((k_fused_pf<2, 2, false>), grid, dim3(1024), 0, st, b, c);
     else if (s.T == 256) hipLaunchKernelGGL((k_fused<256, 1, 4>), grid, dim3(256), 0, st, b, c);
     else if (s.T == 1024 && s.Q == 1) hipLaunchKernelGGL((k_fused<1024, 1, 4>), grid, dim3(1024), 0, st, b, c);
