@@ -440,14 +440,19 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     };
     static_assert(2 * R <= 4, "scalF0 holds two dwords per row and parity");
 
-    double v0[Q][4], v1[Q][4];
+    // both copies of V while the counter is on its way (narrow shapes only: 16 Q registers each)
+    constexpr bool kBothV = Q <= 2;
+    constexpr int QV = kBothV ? Q : 1;
+    double v0[QV][4], v1[QV][4];
+    if constexpr (kBothV) {
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        const int col = (q * T + tid) * 4;
+        for (int q = 0; q < Q; ++q) {
+            const int col = (q * T + tid) * 4;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            v0[q][e] = colok(q) ? p.V[col + e] : -__builtin_huge_val();
-            v1[q][e] = colok(q) ? p.V[(size_t)p.m_ld + col + e] : -__builtin_huge_val();
+            for (int e = 0; e < 4; ++e) {
+                v0[q][e] = colok(q) ? p.V[col + e] : -__builtin_huge_val();
+                v1[q][e] = colok(q) ? p.V[(size_t)p.m_ld + col + e] : -__builtin_huge_val();
+            }
         }
     }
     if (mine > 0) {
@@ -477,9 +482,14 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     };
     double v[Q][4];
 #pragma unroll
-    for (int q = 0; q < Q; ++q)
+    for (int q = 0; q < Q; ++q) {
+        const int col = (q * T + tid) * 4;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[q][e] = cur ? v1[q][e] : v0[q][e];
+        for (int e = 0; e < 4; ++e) {
+            if constexpr (kBothV) v[q][e] = cur ? v1[q][e] : v0[q][e];
+            else v[q][e] = colok(q) ? p.V[(size_t)cur * p.m_ld + col + e] : -__builtin_huge_val();
+        }
+    }
     float cS[Q][4];                            // column sums of the plan entries
 #pragma unroll
     for (int q = 0; q < Q; ++q)
@@ -645,6 +655,10 @@ static bool fused_shape(int m, int variant, FusedShape *fsh) {
         else *fsh = {1024, 1, 302};                          // asynchronous LDS prefetch, one 16-byte load per lane and row
         return true;
     }
+    if (m > 8192 && m <= 16384) {
+        *fsh = {1024, m <= 12288 ? 3 : 4, 301};              // asynchronous LDS prefetch, one row per panel
+        return true;
+    }
     if (m <= 8192) {
         if (variant == 1) *fsh = {512, 4, 4};
         else if (variant == 2) *fsh = {1024, 2, 4};
@@ -687,7 +701,11 @@ hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, 
     DenseArgs b = a;
     b.P = g;
     const dim3 grid(g);
-    if (s.R == 302 && s.Q == 1 && a.p.m == 4096) hipLaunchKernelGGL((k_fused_pf<1, 2, true>), grid, dim3(1024), 0, st, b, c);
+    if (s.R == 301 && s.Q == 3 && a.p.m == 12288) hipLaunchKernelGGL((k_fused_pf<3, 1, true>), grid, dim3(1024), 0, st, b, c);
+    else if (s.R == 301 && s.Q == 3) hipLaunchKernelGGL((k_fused_pf<3, 1, false>), grid, dim3(1024), 0, st, b, c);
+    else if (s.R == 301 && a.p.m == 16384) hipLaunchKernelGGL((k_fused_pf<4, 1, true>), grid, dim3(1024), 0, st, b, c);
+    else if (s.R == 301) hipLaunchKernelGGL((k_fused_pf<4, 1, false>), grid, dim3(1024), 0, st, b, c);
+    else if (s.R == 302 && s.Q == 1 && a.p.m == 4096) hipLaunchKernelGGL((k_fused_pf<1, 2, true>), grid, dim3(1024), 0, st, b, c);
     else if (s.R == 302 && s.Q == 1) hipLaunchKernelGGL((k_fused_pf<1, 2, false>), grid, dim3(1024), 0, st, b, c);
     else if (s.R == 302 && a.p.m == 8192 && variant % 100 != 5) hipLaunchKernelGGL((k_fused_pf<2, 2, true>), grid, dim3(1024), 0, st, b, c);
     else if (s.R == 302) hipLaunchKernelGGL((k_fused_pf<2, 2, false>), grid, dim3(1024), 0, st, b, c);
@@ -702,7 +720,7 @@ hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, 
 
 bool dense_fused_predicts(int m, int variant) {
     FusedShape s;
-    return fused_shape(m, variant, &s) && s.R == 302;
+    return fused_shape(m, variant, &s) && s.R > 300;
 }
 
 // number of column-partial sets the fused launch of this shape writes
