@@ -126,6 +126,20 @@ def plan(a, b, eps, f, g, C=None, X=None, Y=None, long_double=False):
     return P
 
 
+def barycentric(a, b, eps, f, g, Z, C=None, X=None, Y=None, long_double=False):
+    """T[i] = sum_j P_ij Z[j] / sum_j P_ij (barycentric mapping, Sec. 5.6); Z is m x dz."""
+    head, n, m = _head(C, X, Y, a, b, eps)
+    dt = _rdt(long_double)
+    f = np.ascontiguousarray(f, dtype=dt)
+    g = np.ascontiguousarray(g, dtype=dt)
+    Z = np.ascontiguousarray(Z, dtype=dt)
+    if Z.ndim != 2 or Z.shape[0] != m:
+        raise ValueError("Z must be m x dz")
+    T = np.empty((n, Z.shape[1]), dtype=dt)
+    _lib(long_double).fso_barycentric(*head, _rp(f), _rp(g), _rp(Z), ctypes.c_int(Z.shape[1]), _rp(T))
+    return T
+
+
 def objectives(a, b, eps, f, g, C=None, X=None, Y=None, long_double=False):
     """dict(cost=<C,P>, mass=sum P, kl=KL(P|a x b), primal=Eq. 3 objective, dual=D(f,g))."""
     head, n, m = _head(C, X, Y, a, b, eps)

@@ -236,6 +236,26 @@ void fso_plan(const float *C, const float *X, const float *Y, int d, const float
         for (int64_t j = 0; j < m; ++j) P_out[i * m + j] = plan_ij(&p, f, g, i, j);
 }
 
+/* Barycentric projection of the plan (the "barycentric mapping" of Sec. 5.6):
+ * T[i][t] = sum_j P_ij Z[j][t] / sum_j P_ij; a row without mass gives 0.
+ * Z: m x dz, T_out: n x dz, both row-major. */
+void fso_barycentric(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                     int n, int m, double eps, const real *f, const real *g, const real *Z, int dz,
+                     real *T_out) {
+    fso_problem p; fill_problem(&p, C, X, Y, d, a, b, n, m, eps);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        real den = 0;
+        for (int t = 0; t < dz; ++t) T_out[i * dz + t] = 0;
+        for (int64_t j = 0; j < m; ++j) {
+            real pij = plan_ij(&p, f, g, i, j);
+            den += pij;
+            for (int t = 0; t < dz; ++t) T_out[i * dz + t] += pij * Z[j * dz + t];
+        }
+        for (int t = 0; t < dz; ++t) T_out[i * dz + t] = den > 0 ? T_out[i * dz + t] / den : 0;
+    }
+}
+
 /* out[0] = <C,P>, out[1] = sum P, out[2] = KL(P | a x b) of Eq. 4,
  * out[3] = primal objective of Eq. 3, out[4] = dual objective D(f,g). */
 void fso_objectives(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,

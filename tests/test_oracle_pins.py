@@ -295,3 +295,47 @@ def test_thread_count_independence(oracle):
     finally:
         oracle.set_threads(nt)
     assert np.array_equal(r1["f"], r2["f"]) and np.array_equal(r1["g"], r2["g"])
+
+
+# ---- barycentric mapping (Sec. 5.6): pinned by what the projection must do in the cases where the
+# ---- plan is known, not by re-typing its formula
+def test_barycentric_projection_pins(oracle):
+    rng = np.random.default_rng(12)
+    # (a) huge eps: the plan is a (x) b, every row is mapped to the b-weighted mean of Z
+    w = W.random_dense(13, 19, seed=31)
+    Z = rng.standard_normal((19, 3))
+    r = oracle.solve(w.a, w.b, 1e6, 50, C=w.C)
+    T = oracle.barycentric(w.a, w.b, 1e6, r["f"], r["g"], Z, C=w.C)
+    mean = (w.b.astype(np.float64)[:, None] * Z).sum(0) / w.b.astype(np.float64).sum()
+    assert np.abs(T - mean[None, :]).max() < 1e-5
+    # (b) constant Z is reproduced exactly whatever the potentials
+    Zc = np.tile(np.array([[0.25, -3.0]]), (19, 1))
+    f = rng.standard_normal(13)
+    g = rng.standard_normal(19)
+    T = oracle.barycentric(w.a, w.b, 0.3, f, g, Zc, C=w.C)
+    assert np.abs(T - Zc[:13]).max() < 1e-13
+    # (c) eps -> 0 on a uniform n x n problem: the plan concentrates on the optimal permutation found by
+    #     brute force, so row i is mapped to Z[sigma(i)]
+    n = 6
+    wq = W.random_dense(n, n, seed=105, uniform=True)
+    C = wq.C.astype(np.float64)
+    best = min(itertools.permutations(range(n)), key=lambda s: sum(C[i, s[i]] for i in range(n)))
+    Zq = rng.standard_normal((n, 2))
+    nt = oracle.max_threads()
+    oracle.set_threads(1)
+    try:
+        rq = _solve_converged(oracle, wq, 1e-3, iters=300000, tol=1e-11)
+    finally:
+        oracle.set_threads(nt)
+    Tq = oracle.barycentric(wq.a, wq.b, 1e-3, rq["f"], rq["g"], Zq, C=wq.C)
+    assert np.abs(Tq - Zq[list(best)]).max() < 1e-3
+    # (d) the explicit plan and a library matrix product say the same (zero-weight row -> 0)
+    w2 = W.random_points(11, 9, 3, seed=5)
+    w2.a[3] = 0.0
+    r2 = oracle.solve(w2.a, w2.b, 0.05, 5, X=w2.X, Y=w2.Y)
+    Z2 = rng.standard_normal((9, 4))
+    P = oracle.plan(w2.a, w2.b, 0.05, r2["f"], r2["g"], X=w2.X, Y=w2.Y)
+    T2 = oracle.barycentric(w2.a, w2.b, 0.05, r2["f"], r2["g"], Z2, X=w2.X, Y=w2.Y)
+    den = P.sum(1)
+    ref = np.where(den[:, None] > 0, (P @ Z2) / np.where(den > 0, den, 1.0)[:, None], 0.0)
+    assert np.abs(T2 - ref).max() < 1e-13 and np.all(T2[3] == 0.0)
