@@ -195,6 +195,17 @@ fs_status fs_diagnostics(const float *C, const float *X, const float *Y, int d, 
                          const double *g64, double *out_dev, double *row_marginal_dev,
                          double *col_marginal_dev, fs_stream stream);
 
+/* ---- Barycentric mapping of the plan (Sec. 5.6: colour transfer, point-cloud correspondences), in one
+ * pass and without storing the plan:  T[i][t] = sum_j P_ij Z[j][t] / sum_j P_ij,  t < dz.
+ * Z: device [m][dz] fp32 row-major (e.g. the target points themselves); T: device [n][dz] fp32;
+ * 1 <= dz <= FS_MAX_BARY_DIM (wider Z: one call per group of columns).  Rows without mass give 0.
+ * Potentials: either f, g (fp32) or f64, g64 (fp64), the other pair NULL.  Asynchronous on `stream`;
+ * uses the library-owned workspace. ---- */
+#define FS_MAX_BARY_DIM 4
+fs_status fs_barycentric(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                         int n, int m, float eps, const float *f, const float *g, const double *f64,
+                         const double *g64, const float *Z, int dz, float *T, fs_stream stream);
+
 /* ---- One half-step on its own (Eq. 9 / Eq. 10), for kernel-level checks and for callers
  * that drive the loop themselves.  Potentials in double precision, device pointers;
  * asynchronous on `stream`; uses the library-owned workspace. ---- */

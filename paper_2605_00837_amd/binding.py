@@ -80,6 +80,8 @@ def _load():
     lib.fs_sinkhorn_dense_batched.restype = ci
     lib.fs_sinkhorn_dense_batched.argtypes = [vp, vp, vp, ci, ci, ci, cf, ci, cf, vp, vp, vp,
                                               ctypes.POINTER(fs_options), vp]
+    lib.fs_barycentric.restype = ci
+    lib.fs_barycentric.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, vp, vp, vp, vp, vp, ci, vp, vp]
     lib.fs_diagnostics.restype = ci
     lib.fs_diagnostics.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, vp, vp, vp, vp, vp, vp, vp, vp]
     for name in ("fs_update_f", "fs_update_g"):
@@ -93,7 +95,7 @@ _lib = _load()
 
 EXPORTED = ("fs_sinkhorn_dense", "fs_sinkhorn_points", "fs_sinkhorn_solve", "fs_workspace_bytes",
             "fs_sinkhorn_dense_ex", "fs_sinkhorn_points_ex", "fs_sinkhorn_dense_batched", "fs_plan", "fs_cost", "fs_plan_f64",
-            "fs_cost_f64", "fs_diagnostics", "fs_update_f", "fs_update_g", "fs_last_error", "fs_clear_cache", "fs_version",
+            "fs_cost_f64", "fs_diagnostics", "fs_barycentric", "fs_update_f", "fs_update_g", "fs_last_error", "fs_clear_cache", "fs_version",
             "fs_last_kernel_timing")
 
 
@@ -330,6 +332,21 @@ def fs_cost(a, b, eps, f, g, C=None, X=None, Y=None):
 
 fs_plan_f64 = fs_plan
 fs_cost_f64 = fs_cost
+
+def fs_barycentric(a, b, eps, f, g, Z, C=None, X=None, Y=None):
+    """T[i] = sum_j P_ij Z[j] / sum_j P_ij for the plan of (f, g); Z is [m, dz] fp32, dz <= 4.  Returns [n, dz]."""
+    n, m, d = _shape(C, X, Y, a, b)
+    if Z.dim() != 2 or Z.shape[0] != m:
+        raise ValueError("Z must be [m, dz]")
+    dz = int(Z.shape[1])
+    dt = _pots(f, g)
+    T = torch.empty((n, dz), dtype=torch.float32, device=a.device)
+    f32 = (_p(f), _p(g)) if dt == torch.float32 else (None, None)
+    f64 = (_p(f, dt), _p(g, dt)) if dt == torch.float64 else (None, None)
+    _check(_lib.fs_barycentric(_p(C), _p(X), _p(Y), d, _p(a), _p(b), n, m, float(eps), f32[0], f32[1], f64[0], f64[1],
+                               _p(Z), dz, _p(T), _stream()))
+    return T
+
 
 DIAG_FIELDS = ("cost", "mass", "kl", "primal", "dual", "row_err", "col_err")
 

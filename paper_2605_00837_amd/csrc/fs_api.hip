@@ -670,6 +670,30 @@ fs_status diagnostics(const float *C, const float *X, const float *Y, int d, con
     return FS_OK;
 }
 
+fs_status barycentric(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                      int n, int m, float eps, const float *f, const float *g, const double *f64,
+                      const double *g64, const float *Z, int dz, float *T, hipStream_t st) {
+    Problem pr{C, X, Y, a, b, d, n, m, eps, 0, 0.0f};
+    if ((f == nullptr) != (g == nullptr) || (f64 == nullptr) != (g64 == nullptr) || (!f && !f64)) {
+        set_err("potentials: give f and g, or f64 and g64"); return FS_ERR_INVALID_ARG;
+    }
+    const float *fchk = f ? f : (const float *)f64, *gchk = g ? g : (const float *)g64;
+    fs_status v = validate(pr, (float *)fchk, (float *)gchk);
+    if (v != FS_OK) return v;
+    if (!Z || !T) { set_err("Z and T must be non-null"); return FS_ERR_INVALID_ARG; }
+    if (dz < 1 || dz > FS_MAX_BARY_DIM) { set_err("dz must be in [1, %d] (got %d)", FS_MAX_BARY_DIM, dz); return FS_ERR_INVALID_ARG; }
+    const int dd = C ? 0 : d;
+    DeviceCache *dc = nullptr;
+    v = get_cache(bary_scratch_bytes(n, m, dd), &dc);
+    if (v != FS_OK) return v;
+    PlanArgs A{};
+    A.C = C; A.X = X; A.Y = Y; A.a = a; A.b = b; A.f = f64 ? nullptr : f; A.g = g64 ? nullptr : g; A.f64 = f64; A.g64 = g64;
+    A.n = n; A.m = m; A.d = dd;
+    A.s = kLog2e / (double)eps;
+    FS_HIP(launch_bary(st, A, Z, dz, T, dc->ws, dc->ws_bytes));
+    return FS_OK;
+}
+
 fs_status half_step(bool update_f, const float *C, const float *X, const float *Y, int d, const float *a,
                     const float *b, int n, int m, float eps, const double *in64, double *out64, hipStream_t st) {
     Problem pr{C, X, Y, a, b, d, n, m, eps, 1, 0.0f};
@@ -835,6 +859,12 @@ fs_status fs_diagnostics(const float *C, const float *X, const float *Y, int d, 
                          fs_stream stream) {
     return diagnostics(C, X, Y, d, a, b, n, m, eps, f, g, f64, g64, out_dev, row_marginal_dev, col_marginal_dev,
                        (hipStream_t)stream);
+}
+
+fs_status fs_barycentric(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                         int n, int m, float eps, const float *f, const float *g, const double *f64,
+                         const double *g64, const float *Z, int dz, float *T, fs_stream stream) {
+    return barycentric(C, X, Y, d, a, b, n, m, eps, f, g, f64, g64, Z, dz, T, (hipStream_t)stream);
 }
 
 fs_status fs_update_f(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,

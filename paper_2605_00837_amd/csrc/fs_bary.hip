@@ -1,0 +1,324 @@
+// Barycentric mapping of the plan of Eq. 5 (the "barycentric mapping" of Sec. 5.6):
+//   T[i][t] = sum_j P_ij Z[j][t] / sum_j P_ij,   t < dz <= 4,
+// computed in one pass over C (or over all point pairs) without ever storing P.  Rows without mass
+// give 0.  Layouts as in the diagnostics pass: dense = 1024 lanes own a strip of columns and walk
+// down a panel of rows (row sums wave -> LDS); points = rows in registers, column tiles in LDS, every
+// sum lane-local.  Partial numerators / denominators per (strip or slice, row) are added in fixed
+// order by a finishing kernel.
+#include "fs_kernels.h"
+
+namespace fs {
+
+namespace {
+
+constexpr int kBT = 1024;           // threads of the dense kernel
+constexpr int kBRows = 16;          // rows per LDS exchange
+constexpr int kBP = 256;            // threads of the point-cloud kernel
+constexpr int kBTile = 256;
+constexpr int kBIB = 4;
+constexpr int kZ = kBaryMaxDim;
+
+struct BaryLayout {
+    int vec, nstrips, P, rpp;       // dense
+    int JS, cps;                    // points
+    int nparts;                     // partial sets per row (nstrips or JS)
+    size_t o_ri, o_cj, o_part, o_xp, o_xs, o_xq, o_yp, o_ys, o_yq, total;
+};
+
+size_t up256b(size_t x) { return (x + 255) & ~(size_t)255; }
+
+BaryLayout bary_layout(int n, int m, int d) {
+    BaryLayout L{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += up256b(bytes); return at; };
+    L.o_ri = take(sizeof(double) * n);
+    L.o_cj = take(sizeof(double) * m);
+    if (d == 0) {
+        L.vec = (m % 4 == 0) ? 4 : 1;
+        const int strip_cols = kBT * L.vec;
+        L.nstrips = (m + strip_cols - 1) / strip_cols;
+        int P = (512 + L.nstrips - 1) / L.nstrips;
+        const int maxP = (n + kBRows - 1) / kBRows;
+        if (P > maxP) P = maxP;
+        if (P < 1) P = 1;
+        int rpp = (n + P - 1) / P;
+        rpp = ((rpp + kBRows - 1) / kBRows) * kBRows;
+        L.rpp = rpp;
+        L.P = (n + rpp - 1) / rpp;
+        L.nparts = L.nstrips;
+    } else {
+        points_plan(n, m, d, &L.JS, &L.cps);
+        L.nparts = L.JS;
+        L.o_xp = take(sizeof(double) * (size_t)n * d);
+        L.o_xs = take(sizeof(double) * (size_t)n * d);
+        L.o_xq = take(sizeof(double) * n);
+        L.o_yp = take(sizeof(double) * (size_t)m * d);
+        L.o_ys = take(sizeof(double) * (size_t)m * d);
+        L.o_yq = take(sizeof(double) * m);
+    }
+    L.o_part = take(sizeof(float) * (size_t)L.nparts * n * (kZ + 1));     // [part][row][num0..3, den]
+    L.total = o;
+    return L;
+}
+
+struct BaryDense {
+    const float *C;
+    const double *ri, *cj;
+    const float *Z;
+    int32_t n, m, dz;
+    double s;
+    float *part;         // [nstrips][n][kZ + 1]
+    int32_t rpp;
+};
+
+template <int VEC>
+__global__ __launch_bounds__(kBT) void k_bary_dense(BaryDense A) {
+    __shared__ float sRow[kBRows][kBT / 64][kZ + 1];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int strip = blockIdx.x, panel = blockIdx.y;
+    const int j0 = (strip * kBT + tid) * VEC;
+    double cjv[VEC];
+    float zv[VEC][kZ];
+    bool jok[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        jok[e] = j0 + e < A.m;
+        cjv[e] = jok[e] ? A.cj[j0 + e] : -__builtin_huge_val();
+#pragma unroll
+        for (int t = 0; t < kZ; ++t) zv[e][t] = (jok[e] && t < A.dz) ? A.Z[(size_t)(j0 + e) * A.dz + t] : 0.0f;
+    }
+    const int i0 = panel * A.rpp;
+    const int i1 = min(A.n, i0 + A.rpp);
+    for (int ib = i0; ib < i1; ib += kBRows) {
+#pragma unroll 4
+        for (int r = 0; r < kBRows; ++r) {
+            const int i = ib + r;
+            float acc[kZ + 1];
+#pragma unroll
+            for (int t = 0; t <= kZ; ++t) acc[t] = 0.0f;
+            if (i < i1) {
+                float cv[VEC];
+                if constexpr (VEC == 4) {
+                    const float4 c4 = jok[0] ? *reinterpret_cast<const float4 *>(A.C + (size_t)i * A.m + j0)
+                                             : make_float4(0.f, 0.f, 0.f, 0.f);
+                    cv[0] = c4.x; cv[1] = c4.y; cv[2] = c4.z; cv[3] = c4.w;
+                } else {
+                    cv[0] = jok[0] ? A.C[(size_t)i * A.m + j0] : 0.0f;
+                }
+                const double rv = A.ri[i];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    float p = fast_exp2((float)((rv + cjv[e]) - A.s * (double)cv[e]));
+                    p = p > 0.0f ? p : 0.0f;                      // drops NaN
+#pragma unroll
+                    for (int t = 0; t < kZ; ++t) acc[t] = fmaf(p, zv[e][t], acc[t]);
+                    acc[kZ] += p;
+                }
+            }
+#pragma unroll
+            for (int t = 0; t <= kZ; ++t) {
+                const float w = wave_sum_f32(acc[t]);
+                if (lane == 0) sRow[r][wave][t] = w;
+            }
+        }
+        __syncthreads();
+        if (tid < kBRows * (kZ + 1)) {
+            const int r = tid / (kZ + 1), t = tid % (kZ + 1);
+            if (ib + r < i1) {
+                float tot = 0.0f;
+#pragma unroll
+                for (int w = 0; w < kBT / 64; ++w) tot += sRow[r][w][t];
+                A.part[((size_t)strip * A.n + ib + r) * (kZ + 1) + t] = tot;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+struct BaryPoints {
+    const double *rows, *rowq, *rowlog;     // x side: plain coordinates, s|x|^2, ri
+    const double *cols2s, *colq, *collog;   // y side: 2 s y, s|y|^2, cj
+    const float *Z;
+    int32_t nr, nc, dz;
+    float *part;                            // [JS][nr][kZ + 1]
+    int32_t cols_per_split;
+};
+
+template <int D>
+__global__ __launch_bounds__(kBP) void k_bary_points(BaryPoints A) {
+    __shared__ __align__(16) double tile[kBTile][D + 1];      // [0] collog - colq, [1..D] 2 s y
+    __shared__ float tileZ[kBTile][kZ];
+    const int tid = threadIdx.x;
+    double x[kBIB][D], rc[kBIB];
+    int row[kBIB];
+    float acc[kBIB][kZ + 1];
+#pragma unroll
+    for (int b = 0; b < kBIB; ++b) {
+        row[b] = (blockIdx.x * kBIB + b) * kBP + tid;
+        const bool ok = row[b] < A.nr;
+#pragma unroll
+        for (int t = 0; t < D; ++t) x[b][t] = ok ? A.rows[(size_t)row[b] * D + t] : 0.0;
+        rc[b] = ok ? A.rowlog[row[b]] - A.rowq[row[b]] : -__builtin_huge_val();
+#pragma unroll
+        for (int t = 0; t <= kZ; ++t) acc[b][t] = 0.0f;
+    }
+    const int j0 = blockIdx.y * A.cols_per_split;
+    const int j1 = min(A.nc, j0 + A.cols_per_split);
+    for (int jt = j0; jt < j1; jt += kBTile) {
+        __syncthreads();
+        {
+            const int j = jt + tid;
+            if (j < j1) {
+                tile[tid][0] = A.collog[j] - A.colq[j];
+#pragma unroll
+                for (int t = 0; t < D; ++t) tile[tid][1 + t] = A.cols2s[(size_t)j * D + t];
+#pragma unroll
+                for (int t = 0; t < kZ; ++t) tileZ[tid][t] = t < A.dz ? A.Z[(size_t)j * A.dz + t] : 0.0f;
+            } else {
+                tile[tid][0] = -__builtin_huge_val();
+#pragma unroll
+                for (int t = 0; t < D; ++t) tile[tid][1 + t] = 0.0;
+#pragma unroll
+                for (int t = 0; t < kZ; ++t) tileZ[tid][t] = 0.0f;
+            }
+        }
+        __syncthreads();
+#pragma unroll 2
+        for (int jj = 0; jj < kBTile; ++jj) {
+            double w[D + 1];
+#pragma unroll
+            for (int t = 0; t <= D; ++t) w[t] = tile[jj][t];
+            float z[kZ];
+#pragma unroll
+            for (int t = 0; t < kZ; ++t) z[t] = tileZ[jj][t];
+#pragma unroll
+            for (int b = 0; b < kBIB; ++b) {
+                double tq = w[0];
+#pragma unroll
+                for (int t = 0; t < D; ++t) tq = fma(x[b][t], w[1 + t], tq);
+                float p = fast_exp2((float)(tq + rc[b]));
+                p = p > 0.0f ? p : 0.0f;
+#pragma unroll
+                for (int t = 0; t < kZ; ++t) acc[b][t] = fmaf(p, z[t], acc[b][t]);
+                acc[b][kZ] += p;
+            }
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < kBIB; ++b)
+        if (row[b] < A.nr) {
+#pragma unroll
+            for (int t = 0; t <= kZ; ++t) A.part[((size_t)blockIdx.y * A.nr + row[b]) * (kZ + 1) + t] = acc[b][t];
+        }
+}
+
+// Any dimension: one row per lane, its coordinates re-read through the cache.
+__global__ __launch_bounds__(kBP) void k_bary_points_anyd(BaryPoints A, int d) {
+    extern __shared__ double dyn[];                          // [64][d + 1], then 64 x kZ floats
+    constexpr int TJ = 64;
+    const int tid = threadIdx.x, ldt = d + 1;
+    float *dz_tile = reinterpret_cast<float *>(dyn + TJ * ldt);
+    const int row = blockIdx.x * kBP + tid;
+    const bool rok = row < A.nr;
+    const double *xr = A.rows + (size_t)(rok ? row : 0) * d;
+    const double rc = rok ? A.rowlog[row] - A.rowq[row] : -__builtin_huge_val();
+    float acc[kZ + 1];
+#pragma unroll
+    for (int t = 0; t <= kZ; ++t) acc[t] = 0.0f;
+    const int j0 = blockIdx.y * A.cols_per_split;
+    const int j1 = min(A.nc, j0 + A.cols_per_split);
+    for (int jt = j0; jt < j1; jt += TJ) {
+        __syncthreads();
+        for (int e = tid; e < TJ * ldt; e += kBP) {
+            const int jj = e / ldt, t = e % ldt;
+            const int j = jt + jj;
+            double v;
+            if (j < j1) v = (t == 0) ? A.collog[j] - A.colq[j] : A.cols2s[(size_t)j * d + (t - 1)];
+            else v = (t == 0) ? -__builtin_huge_val() : 0.0;
+            dyn[e] = v;
+        }
+        for (int e = tid; e < TJ * kZ; e += kBP) {
+            const int jj = e / kZ, t = e % kZ;
+            const int j = jt + jj;
+            dz_tile[e] = (j < j1 && t < A.dz) ? A.Z[(size_t)j * A.dz + t] : 0.0f;
+        }
+        __syncthreads();
+        for (int jj = 0; jj < TJ; ++jj) {
+            double tq = dyn[jj * ldt];
+            for (int t = 0; t < d; ++t) tq = fma(xr[t], dyn[jj * ldt + 1 + t], tq);
+            float p = fast_exp2((float)(tq + rc));
+            p = p > 0.0f ? p : 0.0f;
+#pragma unroll
+            for (int t = 0; t < kZ; ++t) acc[t] = fmaf(p, dz_tile[jj * kZ + t], acc[t]);
+            acc[kZ] += p;
+        }
+    }
+    if (rok) {
+#pragma unroll
+        for (int t = 0; t <= kZ; ++t) A.part[((size_t)blockIdx.y * A.nr + row) * (kZ + 1) + t] = acc[t];
+    }
+}
+
+// T[i][t] = (sum over partial sets of the numerators) / (sum of the denominators), in double.
+__global__ __launch_bounds__(256) void k_bary_finish(const float *part, int nparts, int n, int dz, float *T) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    double num[kZ] = {0, 0, 0, 0}, den = 0.0;
+    for (int q = 0; q < nparts; ++q) {
+        const float *src = part + ((size_t)q * n + i) * (kZ + 1);
+#pragma unroll
+        for (int t = 0; t < kZ; ++t) num[t] += (double)src[t];
+        den += (double)src[kZ];
+    }
+    for (int t = 0; t < dz; ++t) T[(size_t)i * dz + t] = den > 0.0 ? (float)(num[t] / den) : 0.0f;
+}
+
+}  // namespace
+
+size_t bary_scratch_bytes(int n, int m, int d) { return bary_layout(n, m, d).total; }
+
+hipError_t launch_bary(hipStream_t st, const PlanArgs &a, const float *Z, int dz, float *T, void *scratch,
+                       size_t scratch_bytes) {
+    if (dz < 1 || dz > kZ) return hipErrorInvalidValue;
+    const BaryLayout L = bary_layout(a.n, a.m, a.d);
+    if (scratch_bytes < L.total) return hipErrorInvalidValue;
+    unsigned char *ws = (unsigned char *)scratch;
+    double *ri = (double *)(ws + L.o_ri), *cj = (double *)(ws + L.o_cj);
+    double *xp = nullptr, *xs = nullptr, *xq = nullptr, *yp = nullptr, *ys = nullptr, *yq = nullptr;
+    if (a.d > 0) {
+        xp = (double *)(ws + L.o_xp); xs = (double *)(ws + L.o_xs); xq = (double *)(ws + L.o_xq);
+        yp = (double *)(ws + L.o_yp); ys = (double *)(ws + L.o_ys); yq = (double *)(ws + L.o_yq);
+    }
+    hipError_t e = launch_plan_prep_all(st, a, ri, cj, xp, xs, xq, yp, ys, yq);
+    if (e != hipSuccess) return e;
+    float *part = (float *)(ws + L.o_part);
+    if (a.d == 0) {
+        BaryDense D{};
+        D.C = a.C; D.ri = ri; D.cj = cj; D.Z = Z; D.n = a.n; D.m = a.m; D.dz = dz; D.s = a.s;
+        D.part = part; D.rpp = L.rpp;
+        const dim3 grid(L.nstrips, L.P);
+        if (L.vec == 4) hipLaunchKernelGGL(k_bary_dense<4>, grid, dim3(kBT), 0, st, D);
+        else hipLaunchKernelGGL(k_bary_dense<1>, grid, dim3(kBT), 0, st, D);
+    } else {
+        BaryPoints X{};
+        X.rows = xp; X.rowq = xq; X.rowlog = ri; X.cols2s = ys; X.colq = yq; X.collog = cj;
+        X.Z = Z; X.nr = a.n; X.nc = a.m; X.dz = dz; X.part = part; X.cols_per_split = L.cps;
+        if (a.d <= 4) {
+            const dim3 grid((a.n + kBP * kBIB - 1) / (kBP * kBIB), L.JS);
+            switch (a.d) {
+                case 1: hipLaunchKernelGGL(k_bary_points<1>, grid, dim3(kBP), 0, st, X); break;
+                case 2: hipLaunchKernelGGL(k_bary_points<2>, grid, dim3(kBP), 0, st, X); break;
+                case 3: hipLaunchKernelGGL(k_bary_points<3>, grid, dim3(kBP), 0, st, X); break;
+                default: hipLaunchKernelGGL(k_bary_points<4>, grid, dim3(kBP), 0, st, X); break;
+            }
+        } else {
+            const dim3 grid((a.n + kBP - 1) / kBP, L.JS);
+            const size_t lds = (size_t)64 * (a.d + 1) * sizeof(double) + (size_t)64 * kZ * sizeof(float);
+            hipLaunchKernelGGL(k_bary_points_anyd, grid, dim3(kBP), lds, st, X, a.d);
+        }
+    }
+    hipLaunchKernelGGL(k_bary_finish, dim3((a.n + 255) / 256), dim3(256), 0, st, part, L.nparts, a.n, dz, T);
+    return hipGetLastError();
+}
+
+}  // namespace fs

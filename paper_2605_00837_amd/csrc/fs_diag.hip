@@ -508,6 +508,13 @@ size_t diag_scratch_bytes(int n, int m, int d) { return diag_layout(n, m, d).tot
 
 // cost_only_out non-null: only the cost is wanted (out8 may be null; the pass that exists only for the
 // column marginals of a point-cloud problem is skipped).
+hipError_t launch_plan_prep_all(hipStream_t st, const PlanArgs &a, double *ri, double *cj, double *xp, double *xs,
+                                double *xq, double *yp, double *ys, double *yq) {
+    const int len = a.n > a.m ? a.n : a.m;
+    hipLaunchKernelGGL(k_diag_prep, dim3((len + 255) / 256), dim3(256), 0, st, a, ri, cj, xp, xs, xq, yp, ys, yq);
+    return hipGetLastError();
+}
+
 hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *row_marg, double *col_marg,
                        void *scratch, size_t scratch_bytes, double *cost_only_out) {
     const DiagLayout L = diag_layout(a.n, a.m, a.d);

@@ -141,6 +141,16 @@ size_t diag_scratch_bytes(int n, int m, int d);
 hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *row_marg, double *col_marg,
                        void *scratch, size_t scratch_bytes, double *cost_only_out = nullptr);
 
+// ri = s f + log2 a, cj = s g + log2 b; for point clouds also the repacked clouds (plain, times 2s, s|.|^2).
+hipError_t launch_plan_prep_all(hipStream_t st, const PlanArgs &a, double *ri, double *cj, double *xp, double *xs,
+                                double *xq, double *yp, double *ys, double *yq);
+
+// Barycentric mapping of the plan: T[i][t] = sum_j P_ij Z[j][t] / sum_j P_ij, t < dz <= kBaryMaxDim.
+constexpr int kBaryMaxDim = 4;
+size_t bary_scratch_bytes(int n, int m, int d);
+hipError_t launch_bary(hipStream_t st, const PlanArgs &a, const float *Z, int dz, float *T, void *scratch,
+                       size_t scratch_bytes);
+
 // Whole solve of small dense problems in one launch (one workgroup per problem).
 constexpr int kSmallMax = 256;
 struct ResultRecord { int32_t iters, converged, nonfinite; float marginal_err; };    // = fs_result

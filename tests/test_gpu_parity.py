@@ -395,6 +395,36 @@ def test_diagnostics_one_pass(fs, oracle, kind, n, m, d, precision):
     assert abs(cost2 - got["cost"]) <= 2e-6 * max(1.0, abs(got["cost"]))
 
 
+@pytest.mark.parametrize("kind,n,m,d,dz", [("dense", 300, 257, 0, 3), ("dense", 130, 4100, 0, 1), ("dense", 700, 8192, 0, 4),
+                                            ("dense", 17, 3, 0, 2), ("points", 700, 1300, 3, 3), ("points", 1030, 500, 2, 4),
+                                            ("points", 90, 200, 7, 2)])
+def test_barycentric_mapping(fs, oracle, kind, n, m, d, dz):
+    """fs_barycentric against the oracle's explicit-plan definition; a zero-weight row maps to 0."""
+    import torch
+    w = W.random_dense(n, m, seed=6500 + n + m, cmax=2.0, eps=0.05) if kind == "dense" else \
+        W.random_points(n, m, d, seed=6500 + n + m + d, eps=0.05)
+    w.a[1] = 0.0
+    w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    ref = oracle.solve(w.a, w.b, w.eps, 4, C=w.C, X=w.X, Y=w.Y)
+    rng = np.random.default_rng(n + m)
+    Z = rng.standard_normal((m, dz)).astype(np.float32) if kind == "dense" or dz != d else w.Y.copy()
+    geo, a, b = to_dev(w)
+    To = oracle.barycentric(w.a, w.b, w.eps, ref["f"], ref["g"], Z.astype(np.float64), C=w.C, X=w.X, Y=w.Y)
+    scale = 1.0 + float(np.abs(Z).max())
+    for dt in (torch.float64, torch.float32):
+        f_h = ref["f"] if dt == torch.float64 else ref["f"].astype(np.float32).astype(np.float64)
+        g_h = ref["g"] if dt == torch.float64 else ref["g"].astype(np.float32).astype(np.float64)
+        To_dt = To if dt == torch.float64 else oracle.barycentric(w.a, w.b, w.eps, f_h, g_h, Z.astype(np.float64),
+                                                                   C=w.C, X=w.X, Y=w.Y)
+        T = fs.fs_barycentric(a, b, w.eps, dev(f_h, dt), dev(g_h, dt), dev(Z), **geo).cpu().numpy()
+        assert T.shape == (n, dz)
+        assert np.abs(T - To_dt).max() <= 5e-6 * scale, float(np.abs(T - To_dt).max())
+        assert np.all(T[1] == 0.0)
+    with pytest.raises(fs.FsError):
+        fs.fs_barycentric(a, b, w.eps, dev(ref["f"], torch.float64), dev(ref["g"], torch.float64),
+                          torch.zeros((m, 5), device="cuda"), **geo)
+
+
 @pytest.mark.parametrize("mode", [1, 2])
 def test_separable_cost_closed_form_large(fs, mode):
     """C_ij = u_i + v_j (exactly representable) => after ONE iteration f = u + kappa, g = v - kappa - eps log(sum a),
