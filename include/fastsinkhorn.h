@@ -159,6 +159,17 @@ fs_status fs_cost_f64(const float *C, const float *X, const float *Y, int d, con
                       int n, int m, float eps, const double *f64, const double *g64, double *cost_dev,
                       fs_stream stream);
 
+/* ---- Annealed regularisation (eps-scaling; named as future work in the paper's conclusion): stages at
+ * eps_k = eps_start * decay^k while eps_k > eps, `stage_iters` iterations each, every stage started
+ * from the potentials of the one before (handed on in f, g), then the final stage at `eps` with
+ * max_iter / tol exactly as fs_sinkhorn_solve.  Blocking.  Returns the iterations of the final stage
+ * (>= 0) or an fs_status error; *total_iters (optional, host) counts all stages; *result_host
+ * describes the final stage.  eps_start >= eps, 0 < decay < 1, stage_iters >= 1. ---- */
+int fs_sinkhorn_annealed(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                         int n, int m, float eps, float eps_start, float decay, int stage_iters, int max_iter,
+                         float tol, float *f, float *g, fs_stream stream, const fs_options *opts,
+                         fs_result *result_host, int32_t *total_iters);
+
 /* ---- Many small dense problems of one shape in ONE launch (Alg. 1 entirely on the device, one
  * workgroup per problem, C held in registers; the paper's latency-sensitive regime, n >= 64 in its
  * Table 3).  n, m <= FS_SMALL_MAX.  Problem p reads C + p*n*m, a + p*n, b + p*m and writes f + p*n,

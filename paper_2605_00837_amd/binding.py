@@ -80,6 +80,10 @@ def _load():
     lib.fs_sinkhorn_dense_batched.restype = ci
     lib.fs_sinkhorn_dense_batched.argtypes = [vp, vp, vp, ci, ci, ci, cf, ci, cf, vp, vp, vp,
                                               ctypes.POINTER(fs_options), vp]
+    lib.fs_sinkhorn_annealed.restype = ci
+    lib.fs_sinkhorn_annealed.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, cf, cf, ci, ci, cf, vp, vp, vp,
+                                         ctypes.POINTER(fs_options), ctypes.POINTER(fs_result),
+                                         ctypes.POINTER(ctypes.c_int32)]
     lib.fs_barycentric.restype = ci
     lib.fs_barycentric.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, vp, vp, vp, vp, vp, ci, vp, vp]
     lib.fs_diagnostics.restype = ci
@@ -94,7 +98,7 @@ def _load():
 _lib = _load()
 
 EXPORTED = ("fs_sinkhorn_dense", "fs_sinkhorn_points", "fs_sinkhorn_solve", "fs_workspace_bytes",
-            "fs_sinkhorn_dense_ex", "fs_sinkhorn_points_ex", "fs_sinkhorn_dense_batched", "fs_plan", "fs_cost", "fs_plan_f64",
+            "fs_sinkhorn_dense_ex", "fs_sinkhorn_points_ex", "fs_sinkhorn_dense_batched", "fs_sinkhorn_annealed", "fs_plan", "fs_cost", "fs_plan_f64",
             "fs_cost_f64", "fs_diagnostics", "fs_barycentric", "fs_update_f", "fs_update_g", "fs_last_error", "fs_clear_cache", "fs_version",
             "fs_last_kernel_timing")
 
@@ -217,6 +221,32 @@ def fs_sinkhorn_solve(a, b, eps, max_iter, tol, C=None, X=None, Y=None, f=None, 
                                        float(tol), _p(f), _p(g), _stream(), ctypes.byref(o), ctypes.byref(res)))
     out = dict(f=f, g=g, iters=it, converged=bool(res.converged), nonfinite=bool(res.nonfinite),
                marginal_err=float(res.marginal_err))
+    if want_f64:
+        out.update(f64=f64, g64=g64)
+    return out
+
+
+def fs_sinkhorn_annealed(a, b, eps, eps_start, decay, stage_iters, max_iter, tol, C=None, X=None, Y=None,
+                         f=None, g=None, want_f64=False, **opt_kw):
+    """eps-scaling: stages at eps_start * decay^k > eps (stage_iters iterations each, warm-started), then
+    the final stage at eps.  Returns the dict of fs_sinkhorn_solve plus total_iters."""
+    n, m, d = _shape(C, X, Y, a, b)
+    dev = a.device
+    f = torch.zeros(n, dtype=torch.float32, device=dev) if f is None else f
+    g = torch.zeros(m, dtype=torch.float32, device=dev) if g is None else g
+    f64 = g64 = None
+    if want_f64:
+        f64 = torch.empty(n, dtype=torch.float64, device=dev)
+        g64 = torch.empty(m, dtype=torch.float64, device=dev)
+        opt_kw.update(f64_out=f64, g64_out=g64)
+    o = make_options(**opt_kw)
+    res = fs_result()
+    total = ctypes.c_int32(0)
+    it = _check(_lib.fs_sinkhorn_annealed(_p(C), _p(X), _p(Y), d, _p(a), _p(b), n, m, float(eps), float(eps_start),
+                                          float(decay), int(stage_iters), int(max_iter), float(tol), _p(f), _p(g),
+                                          _stream(), ctypes.byref(o), ctypes.byref(res), ctypes.byref(total)))
+    out = dict(f=f, g=g, iters=it, total_iters=int(total.value), converged=bool(res.converged),
+               nonfinite=bool(res.nonfinite), marginal_err=float(res.marginal_err))
     if want_f64:
         out.update(f64=f64, g64=g64)
     return out

@@ -785,6 +785,40 @@ int fs_sinkhorn_solve(const float *C, const float *X, const float *Y, int d, con
     return solve_blocking(pr, f, g, (hipStream_t)stream, opts, result_host);
 }
 
+int fs_sinkhorn_annealed(const float *C, const float *X, const float *Y, int d, const float *a, const float *b,
+                         int n, int m, float eps, float eps_start, float decay, int stage_iters, int max_iter,
+                         float tol, float *f, float *g, fs_stream stream, const fs_options *opts,
+                         fs_result *result_host, int32_t *total_iters) {
+    if (!(eps_start >= eps) || !std::isfinite(eps_start)) { set_err("eps_start must be finite and >= eps"); return FS_ERR_INVALID_ARG; }
+    if (!(decay > 0.0f && decay < 1.0f)) { set_err("decay must be in (0, 1)"); return FS_ERR_INVALID_ARG; }
+    if (stage_iters < 1) { set_err("stage_iters must be >= 1"); return FS_ERR_INVALID_ARG; }
+    fs_options o{};
+    if (opts) o = *opts;
+    const int user_warm = o.warm_start;
+    int total = 0, stage = 0;
+    // intermediate stages: fixed iteration count, no trailing error pass, potentials handed on in f, g
+    for (float e = eps_start; e > eps; e *= decay, ++stage) {
+        fs_options so = o;
+        so.warm_start = (stage > 0) ? 1 : user_warm;
+        so.skip_final_err = 1;
+        so.err_history = nullptr; so.err_history_len = 0;
+        so.f64_out = nullptr; so.g64_out = nullptr;
+        if (stage > 0) { so.f64_in = nullptr; so.g64_in = nullptr; }
+        so.time_kernel_every = 0;
+        Problem pr{C, X, Y, a, b, d, n, m, e, stage_iters, 0.0f};
+        const int it = solve_blocking(pr, f, g, (hipStream_t)stream, &so, nullptr);
+        if (it < 0) return it;
+        total += it;
+    }
+    fs_options fo = o;
+    if (stage > 0) { fo.warm_start = 1; fo.f64_in = nullptr; fo.g64_in = nullptr; }
+    Problem pr{C, X, Y, a, b, d, n, m, eps, max_iter, tol};
+    const int it = solve_blocking(pr, f, g, (hipStream_t)stream, &fo, result_host);
+    if (it < 0) return it;
+    if (total_iters) *total_iters = total + it;
+    return it;
+}
+
 fs_status fs_sinkhorn_dense_ex(const float *C, const float *a, const float *b, int n, int m, float eps,
                                int max_iter, float tol, float *f, float *g, fs_stream stream,
                                const fs_options *opts, void *workspace, size_t workspace_bytes,

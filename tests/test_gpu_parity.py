@@ -171,6 +171,43 @@ def test_points_optimistic_pass_and_repair(fs, oracle, n, m, d, zero):
     assert e64b < TOL_F64 and e32b < TOL_F32
 
 
+# ------------------------------------------------------------------ eps-scaling
+@pytest.mark.parametrize("kind", ["dense", "points", "small"])
+def test_annealed_regularisation(fs, oracle, kind):
+    """fs_sinkhorn_annealed = the same chain of warm-started solves composed from the oracle (potentials
+    handed from stage to stage as fp32, as the library does)."""
+    if kind == "dense":
+        w = W.random_dense(300, 520, seed=8100, cmax=1.0, eps=0.002)
+    elif kind == "small":
+        w = W.random_dense(90, 70, seed=8101, cmax=1.0, eps=0.002)
+    else:
+        w = W.random_points(400, 350, 3, seed=8102, eps=0.002)
+    geo, a, b = to_dev(w)
+    eps, eps0, decay, stage = w.eps, 0.25, 0.5, 8
+    r = fs.fs_sinkhorn_annealed(a, b, eps, eps0, decay, stage, 30, 0.0, want_f64=True, **geo)
+    f0 = g0 = None
+    e = np.float32(eps0)
+    nst = 0
+    while e > np.float32(eps):
+        o = oracle.solve(w.a, w.b, float(e), stage, C=w.C, X=w.X, Y=w.Y, f0=f0, g0=g0)
+        f0 = o["f"].astype(np.float32).astype(np.float64)
+        g0 = o["g"].astype(np.float32).astype(np.float64)
+        e = np.float32(e * np.float32(decay))
+        nst += 1
+    o = oracle.solve(w.a, w.b, eps, 30, C=w.C, X=w.X, Y=w.Y, f0=f0, g0=g0)
+    assert r["iters"] == 30 and r["total_iters"] == 30 + nst * stage
+    # fp32 hand-over of potentials of size ~1 moves the start by ~1e-7/eps of the unit: allow for it
+    assert pot_err(r["f64"].cpu().numpy(), o["f"], eps) < 2e-4 and pot_err(r["g64"].cpu().numpy(), o["g"], eps) < 2e-4
+    assert pot_err(r["f"].cpu().numpy(), o["f"], eps) < TOL_F32
+    err_ref = float(oracle.marginal_err(w.a, w.b, eps, o["f"], o["g"], C=w.C, X=w.X, Y=w.Y))
+    assert abs(r["marginal_err"] - err_ref) <= 2e-3 * err_ref + 5e-7
+    for bad in (dict(eps_start=eps / 2), dict(decay=1.0), dict(stage_iters=0)):
+        kw = dict(eps_start=eps0, decay=decay, stage_iters=stage)
+        kw.update(bad)
+        with pytest.raises(fs.FsError):
+            fs.fs_sinkhorn_annealed(a, b, eps, kw["eps_start"], kw["decay"], kw["stage_iters"], 5, 0.0, **geo)
+
+
 # ------------------------------------------------------------------ single-workgroup kernel, batched solves
 SMALL_SHAPES = [(1, 1), (1, 7), (5, 1), (31, 33), (64, 64), (100, 37), (128, 256), (256, 129), (256, 256), (200, 255)]
 
