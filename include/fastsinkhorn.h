@@ -33,6 +33,11 @@
  *     reported through fs_result.nonfinite, never by aborting.
  *   - No exception crosses this boundary.  fs_last_error() returns a
  *     thread-local description of the last failure.
+ *   - Concurrency: every entry point that says it uses the library-owned workspace shares ONE
+ *     cached workspace (and one pinned host block) per device; such calls on one device must not
+ *     overlap, neither from two host threads nor by asynchronous work of two of them still running
+ *     on different streams.  The *_ex entry points with a caller workspace and
+ *     fs_sinkhorn_dense_batched have no such shared state and may overlap freely.
  *   - Internally the potentials are carried in fp64 (scaled by log2(e)/eps) and
  *     the exponent arguments are formed in fp64; exp2/log2 and the sums are fp32.
  */
