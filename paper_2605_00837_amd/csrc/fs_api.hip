@@ -50,7 +50,7 @@ struct Layout {
     int P_stream, rpp_stream, P_fused;
     // points
     int JSf, cpsf, JSg, cpsg;
-    size_t o_state, o_F, o_U, o_G, o_V, o_la2, o_lb2, o_part, o_part2, o_err;
+    size_t o_state, o_F, o_U, o_G, o_V, o_la2, o_lb2, o_part, o_part2;
     size_t o_Xp, o_Xs, o_cx, o_Yp, o_Ys, o_cy;
     size_t total;
 };
@@ -87,7 +87,6 @@ Layout make_layout(int n, int m, int d) {
         L.o_Ys = take(sizeof(double) * (size_t)m * d);
         L.o_cy = take(sizeof(double) * L.m_ld);
     }
-    L.o_err = take(sizeof(double) * 2 * (size_t)((m + 63) / 64));    // error sum and largest move, one each per workgroup of the g-combine
     L.total = off;
     return L;
 }
@@ -160,7 +159,6 @@ struct Solve {
     Pots pots;
     State *state;
     int mode;              // 1 streaming, 2 fused (dense); 3 points
-    double *errpart;
     volatile int32_t *host_flag;   // device-visible address of the pinned flag, or null
 
     Ctl ctl(int phase) const {
@@ -190,7 +188,7 @@ struct Solve {
     }
     ErrSrc err_src() const {
         ErrSrc e;
-        e.F = pots.F; e.a = pots.a; e.n = pr.n; e.n_ld = L.n_ld; e.errpart = errpart;
+        e.F = pots.F; e.a = pots.a; e.n = pr.n; e.n_ld = L.n_ld;
         return e;
     }
     CombineArgs combine_g(int P, const double *part, const double *rowconst) const {
@@ -359,7 +357,6 @@ fs_status setup(Solve &S, const Problem &pr, const fs_options *opts, float *f, f
     p.a = pr.a; p.b = pr.b;
     p.n = pr.n; p.m = pr.m; p.n_ld = S.L.n_ld; p.m_ld = S.L.m_ld;
     p.s = kLog2e / (double)pr.eps;
-    S.errpart = (double *)(S.ws + S.L.o_err);
     S.host_flag = nullptr;
     S.warm_f = f; S.warm_g = g;
     if (pr.C) {

@@ -30,16 +30,13 @@ struct alignas(256) State {
     int32_t iters;        // result: iterations whose potentials are returned
     int32_t converged;
     int32_t nonfinite;
-    uint32_t reserved0;
     int32_t err_valid;
-    int32_t reserved2;
     double err;           // err after `iters`
     // Closing word of the iteration in progress, updated with ONE atomic per workgroup: bits 0..13
     // count the workgroups that have reported (the ticket), bits 14..62 hold the fixed-point sum of
     // their error terms, bit 63 says that some share was not a number (or that the sum left its range).
     // Returns to 0 after every use.
     unsigned long long err_acc;
-    uint32_t reserved1;
     uint32_t big_acc[2];  // columns that moved by more than the FAST-mode threshold, by parity of the iteration
 };
 

@@ -31,8 +31,6 @@ struct DenseArgs {
 // underflow and is recomputed exactly by the combine kernel.  After every iteration the device
 // publishes a hint (bit 1 of State::flags): FAST if at most 128 columns moved by more than kFastBelow (base-2
 // units), ROBUST otherwise; the driver runs the exact streaming kernels while the hint says ROBUST.
-constexpr int kModeRobust = 0;
-constexpr int kModeFast = 1;
 constexpr double kFastBelow = 40.0;
 constexpr double kColRepairBelow = 60.0;
 constexpr double kRepairAbove = 100.0;    // optimistic point-cloud pass: fp32 sums stay finite up to 2^127
@@ -44,7 +42,6 @@ struct ErrSrc {
     const double *F;          // [2][n_ld]
     const float *a;           // [n]
     int32_t n, n_ld;
-    double *errpart;          // [>= number of workgroups of the combine launch]
 };
 
 // One combine launch: out[j] = LSE2 over p < P of part[p][j] (+ rowconst[j]),

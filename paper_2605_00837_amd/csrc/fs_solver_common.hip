@@ -16,8 +16,8 @@ __global__ __launch_bounds__(256) void k_init(Pots p, State *state, const float 
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t == 0) {
         state->k = 0; state->flags = 0; state->iters = 0; state->converged = 0; state->nonfinite = 0;
-        state->reserved0 = 0; state->err_valid = 0; state->reserved2 = 0;
-        state->err_acc = 0; state->reserved1 = 0;
+        state->err_valid = 0;
+        state->err_acc = 0;
         state->big_acc[0] = 0; state->big_acc[1] = 0x7fffffffu;   // no count yet: the first hint says ROBUST
         state->err = __builtin_nan("");
     }
