@@ -113,23 +113,22 @@ hipError_t launch_finalize(hipStream_t st, const Pots &p, State *state, float *f
 }
 
 // ---------------------------------------------------------------- error terms + advance
-// Sum over 256 threads in a fixed order (tree in LDS).
-__device__ __forceinline__ double block_sum_256(double v, double *lds) {
-    const int t = threadIdx.x;
+// Sum over the 1024 threads of a workgroup in a fixed order (wave sums by DPP, 16 wave sums in LDS).
+__device__ __forceinline__ double block_sum_1024(double v, double *lds16) {
+    const double w = wave_sum_f64(v);
     __syncthreads();
-    lds[t] = v;
+    if ((threadIdx.x & 63) == 0) lds16[threadIdx.x >> 6] = w;
     __syncthreads();
-    for (int w = 128; w >= 1; w >>= 1) {
-        if (t < w) lds[t] += lds[t + w];
-        __syncthreads();
-    }
-    return lds[0];
+    double tot = 0.0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) tot += lds16[q];
+    return tot;
 }
 
-// Error terms a_i |2^(Fnew_i - Fold_i) - 1| of the rows first, first+stride, ... (fp64, expm1 for
-// the small differences near convergence).
 // 1 if a potential moved by more than kFastBelow (or by a non-finite amount), else 0
 __device__ __forceinline__ double big_move(double diff) { return (fabs(diff) <= kFastBelow) ? 0.0 : 1.0; }
+// Error terms a_i |2^(Fnew_i - Fold_i) - 1| of the rows first, first+stride, ... (fp64, expm1 for
+// the small differences near convergence).
 __device__ __forceinline__ double err_terms(const ErrSrc &es, int cur, int first, int stride) {
     const double *Fo = es.F + (size_t)cur * es.n_ld;
     const double *Fn = es.F + (size_t)(cur ^ 1) * es.n_ld;
@@ -143,16 +142,16 @@ __device__ __forceinline__ double err_terms(const ErrSrc &es, int cur, int first
 }
 
 // Trailing pass: one workgroup evaluates err of the last iterate and closes the solve.
-__global__ __launch_bounds__(256) void k_advance(ErrSrc es, Ctl c) {
-    __shared__ double lds[256];
+__global__ __launch_bounds__(1024) void k_advance(ErrSrc es, Ctl c) {
+    __shared__ double lds[16];
     int k;
     if (!launch_active(c, k)) return;
-    const double err = block_sum_256(err_terms(es, k & 1, threadIdx.x, 256), lds);
+    const double err = block_sum_1024(err_terms(es, k & 1, threadIdx.x, 1024), lds);
     if (threadIdx.x == 0) advance_state(c, k, err, 1.0e300);
 }
 
 hipError_t launch_advance(hipStream_t st, const ErrSrc &es, const Ctl &c) {
-    hipLaunchKernelGGL(k_advance, dim3(1), dim3(256), 0, st, es, c);
+    hipLaunchKernelGGL(k_advance, dim3(1), dim3(1024), 0, st, es, c);
     return hipGetLastError();
 }
 
