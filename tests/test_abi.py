@@ -76,3 +76,32 @@ def test_argument_validation_without_gpu(lib):
     assert lib.fs_sinkhorn_dense(fake, fake, fake, 4, 4, 0.1, -2, 0.0, fake, fake, None) == -1
     assert lib.fs_sinkhorn_dense(None, fake, fake, 4, 4, 0.1, 3, 0.0, fake, fake, None) == -1
     assert lib.fs_sinkhorn_dense(fake, fake, fake, 4, 4, 0.1, 3, 0.0, None, fake, None) == -1
+
+
+def test_size_limits_and_new_entry_points_validate_on_the_host(lib):
+    """n, m <= FS_MAX_POINTS; batched solves need n, m <= FS_SMALL_MAX and batch >= 1; the barycentric
+    mapping takes 1..FS_MAX_BARY_DIM columns: all refused before any HIP call."""
+    fake = ctypes.c_void_p(256)
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    lib.fs_last_error.restype = ctypes.c_char_p
+    lib.fs_sinkhorn_points.restype = ci
+    lib.fs_sinkhorn_points.argtypes = [vp, vp, ci, vp, vp, ci, ci, cf, ci, cf, vp, vp, vp]
+    assert lib.fs_sinkhorn_points(fake, fake, 3, fake, fake, 1048513, 8, 0.1, 3, 0.0, fake, fake, None) == -1
+    assert b"limited" in lib.fs_last_error()
+    assert lib.fs_sinkhorn_points(fake, fake, 65, fake, fake, 8, 8, 0.1, 3, 0.0, fake, fake, None) == -1
+    lib.fs_sinkhorn_dense_batched.restype = ci
+    lib.fs_sinkhorn_dense_batched.argtypes = [vp, vp, vp, ci, ci, ci, cf, ci, cf, vp, vp, vp, vp, vp]
+    assert lib.fs_sinkhorn_dense_batched(fake, fake, fake, 0, 8, 8, 0.1, 3, 0.0, fake, fake, None, None, None) == -1
+    assert lib.fs_sinkhorn_dense_batched(fake, fake, fake, 2, 257, 8, 0.1, 3, 0.0, fake, fake, None, None, None) == -4
+    assert b"256" in lib.fs_last_error()
+    lib.fs_barycentric.restype = ci
+    lib.fs_barycentric.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, vp, vp, vp, vp, vp, ci, vp, vp]
+    assert lib.fs_barycentric(fake, None, None, 0, fake, fake, 4, 4, 0.1, fake, fake, None, None, fake, 5, fake, None) == -1
+    assert b"dz" in lib.fs_last_error()
+    assert lib.fs_barycentric(fake, None, None, 0, fake, fake, 4, 4, 0.1, fake, None, None, None, fake, 2, fake, None) == -1
+    lib.fs_sinkhorn_annealed.restype = ci
+    lib.fs_sinkhorn_annealed.argtypes = [vp, vp, vp, ci, vp, vp, ci, ci, cf, cf, cf, ci, ci, cf, vp, vp, vp, vp, vp, vp]
+    assert lib.fs_sinkhorn_annealed(fake, None, None, 0, fake, fake, 4, 4, 0.1, 0.05, 0.5, 3, 3, 0.0, fake, fake,
+                                    None, None, None, None) == -1
+    assert lib.fs_sinkhorn_annealed(fake, None, None, 0, fake, fake, 4, 4, 0.1, 1.0, 1.5, 3, 3, 0.0, fake, fake,
+                                    None, None, None, None) == -1

@@ -133,6 +133,24 @@ def test_fused_column_repair_path(fs, oracle):
         assert e64 < TOL_F64 and e32 < TOL_F32, (n, m, e64, e32)
 
 
+@pytest.mark.parametrize("n,m,mode", [(5000, 64, 0), (3000, 12, 1), (40, 20000, 0), (9, 16388, 0), (2, 70001, 1)])
+def test_dense_extreme_aspect_ratios(fs, oracle, n, m, mode):
+    """Very tall (many rows of the error sum per workgroup of the combine) and very wide (beyond the
+    widths the fused kernels cover: streaming kernels, many column strips) problems."""
+    w = W.random_dense(n, m, seed=3500 + n + m, cmax=2.0, eps=0.03)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 15, kernel_mode=mode)
+    assert e64 < TOL_F64 and e32 < TOL_F32
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+
+
+@pytest.mark.parametrize("n,m,d", [(1, 1, 3), (1, 700, 2), (900, 1, 4), (130, 140, 64), (2500, 40, 1)])
+def test_points_extreme_shapes(fs, oracle, n, m, d):
+    w = W.random_points(n, m, d, seed=4300 + n + m + d, eps=0.05)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 25)
+    assert e64 < TOL_F64 and e32 < TOL_F32
+
+
 def test_streaming_rejects_nothing_and_fused_rejects_odd_m(fs):
     w = W.random_dense(8, 10, seed=5)
     geo, a, b = to_dev(w)
