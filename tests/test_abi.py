@@ -105,3 +105,18 @@ def test_size_limits_and_new_entry_points_validate_on_the_host(lib):
                                     None, None, None, None) == -1
     assert lib.fs_sinkhorn_annealed(fake, None, None, 0, fake, fake, 4, 4, 0.1, 1.0, 1.5, 3, 3, 0.0, fake, fake,
                                     None, None, None, None) == -1
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C (gcc, C11, pedantic) on its own."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "fastsinkhorn.h"\n'
+                   "int main(void) { fs_options o; fs_result r; (void)o; (void)r;\n"
+                   "  return (int)(sizeof(fs_options) + sizeof(fs_result)) * 0 + FS_DIAG_LEN * 0; }\n")
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run([gcc, "-std=c11", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
