@@ -80,7 +80,8 @@ typedef struct {
     int32_t check_every;     /* c of Alg. 1; 0 -> 10 (Sec. 4.5)                                     */
     int32_t warm_start;      /* 0: start from f = g = 0 (Eqs. 6-7); 1: start from the f, g passed in */
     int32_t kernel_mode;     /* 0: automatic; 1: streaming row / column kernels; 2: fused row-panel
-                                kernel (dense only; FS_ERR_UNSUPPORTED if the shape does not fit);
+                                kernel (dense, m <= 16384, and m % 4 == 0 when m <= 1024; else
+                                FS_ERR_UNSUPPORTED);
                                 3: the whole solve in one single-workgroup kernel (dense, n, m <=
                                 FS_SMALL_MAX, else FS_ERR_UNSUPPORTED; what 0 picks up to about 128 x 128) */
     int32_t use_graph;       /* 0: automatic; 1: plain stream launches; 2: hipGraph iteration blocks  */

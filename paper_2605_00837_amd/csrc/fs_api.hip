@@ -361,7 +361,7 @@ fs_status setup(Solve &S, const Problem &pr, const fs_options *opts, float *f, f
     S.warm_f = f; S.warm_g = g;
     if (pr.C) {
         const bool fused_ok = dense_fused_supported(pr.n, pr.m, pr.C);
-        if (S.opt.kernel_mode == 2 && !fused_ok) { set_err("fused kernel does not support m = %d (needs m %% 4 == 0, m <= 16384, 16-byte aligned C)", pr.m); return FS_ERR_UNSUPPORTED; }
+        if (S.opt.kernel_mode == 2 && !fused_ok) { set_err("fused kernel does not support m = %d (needs m <= 16384, and m %% 4 == 0 when m <= 1024)", pr.m); return FS_ERR_UNSUPPORTED; }
         if (S.opt.kernel_mode < 0 || S.opt.kernel_mode > 2) { set_err("kernel_mode must be 0, 1, 2 or 3"); return FS_ERR_INVALID_ARG; }
         S.mode = S.opt.kernel_mode == 0 ? (fused_ok ? 2 : 1) : S.opt.kernel_mode;
         if (S.mode == 2 && dense_fused_grid(pr.n, pr.m, S.opt.fused_variant) == 0) S.opt.fused_variant = 0;

@@ -22,16 +22,25 @@ constexpr int kStreamT = 256;
 
 template <int VEC>
 struct VecLoad;
+// Four adjacent costs with one 16-byte load.  Rows of C start at multiples of m floats, i.e. at any
+// 4-byte boundary: the vector type says so, and the hardware's unaligned access mode does the rest.
+// `valid` < 4 (the last columns of a row whose length is not a multiple of 4) falls back to single loads.
+typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 template <>
 struct VecLoad<4> {
-    static __device__ __forceinline__ void ld(const float *p, float (&o)[4]) {
-        const float4 v = *reinterpret_cast<const float4 *>(p);
-        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    static __device__ __forceinline__ void ld(const float *p, float (&o)[4], int valid) {
+        if (valid >= 4) {
+            const float4_a4 v = *reinterpret_cast<const float4_a4 *>(p);
+            o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = e < valid ? p[e] : 0.0f;
+        }
     }
 };
 template <>
 struct VecLoad<1> {
-    static __device__ __forceinline__ void ld(const float *p, float (&o)[1]) { o[0] = *p; }
+    static __device__ __forceinline__ void ld(const float *p, float (&o)[1], int) { o[0] = *p; }
 };
 
 // ---------------------------------------------------------------- row pass (streaming)
@@ -53,15 +62,16 @@ __global__ __launch_bounds__(kStreamT) void k_row_stream(DenseArgs A, Ctl c) {
     for (int r = 0; r < kRowsPerWG; ++r) acc[r].init();
 
     for (int col = tid * VEC; col < p.m; col += kStreamT * VEC) {
+        const int valid = p.m - col;                   // >= VEC except in the last columns of the row
         double v[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) v[e] = V[col + e];
+        for (int e = 0; e < VEC; ++e) v[e] = e < valid ? V[col + e] : -__builtin_huge_val();
 #pragma unroll
         for (int r = 0; r < kRowsPerWG; ++r) {
             const int i = i0 + r;
             if (i < p.n) {
                 float cv[VEC];
-                VecLoad<VEC>::ld(A.C + (size_t)i * p.m + col, cv);
+                VecLoad<VEC>::ld(A.C + (size_t)i * p.m + col, cv, valid);
                 double x[VEC];
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) x[e] = fma(ns, (double)cv[e], v[e]);
@@ -98,6 +108,7 @@ __global__ __launch_bounds__(kStreamT) void k_col_stream(DenseArgs A, Ctl c) {
     const Pots &p = A.p;
     const int j0 = (blockIdx.x * kStreamT + threadIdx.x) * VEC;
     if (j0 >= p.m) return;                       // no cross-lane work below
+    const int valid = p.m - j0;                  // >= VEC except for the lane that owns the last columns
     // panels are walked from the bottom of C upwards: the row pass that ran just before streamed C
     // top to bottom, so the rows still resident in the last-level cache are visited first
     const int panel = (int)gridDim.y - 1 - (int)blockIdx.y;
@@ -118,7 +129,7 @@ __global__ __launch_bounds__(kStreamT) void k_col_stream(DenseArgs A, Ctl c) {
             const int ii = i + q;
             if (ii < r1) {
                 float cv[VEC];
-                VecLoad<VEC>::ld(A.C + (size_t)ii * p.m + j0, cv);
+                VecLoad<VEC>::ld(A.C + (size_t)ii * p.m + j0, cv, valid);
                 const double u = U[ii];
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) x[e][q] = fma(ns, (double)cv[e], u);
@@ -131,11 +142,12 @@ __global__ __launch_bounds__(kStreamT) void k_col_stream(DenseArgs A, Ctl c) {
         for (int e = 0; e < VEC; ++e) acc[e].template add<RC>(x[e]);
     }
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) A.colpart[(size_t)panel * p.m_ld + j0 + e] = acc[e].value();
+    for (int e = 0; e < VEC; ++e)
+        if (e < valid) A.colpart[(size_t)panel * p.m_ld + j0 + e] = acc[e].value();
 }
 
 static bool vec4_ok(const DenseArgs &a) {
-    return (a.p.m % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.C) & 15u) == 0);
+    return a.p.m >= 4 && ((reinterpret_cast<uintptr_t>(a.C) & 3u) == 0);
 }
 
 void dense_stream_plan(int n, int m, int *P, int *rows_per_panel) {
@@ -218,7 +230,7 @@ __global__ __launch_bounds__(T) void k_fused(DenseArgs A, Ctl c) {
             for (int q = 0; q < Q; ++q) {
                 const int col = (q * T + tid) * 4;
                 if (rok && col < m) {
-                    VecLoad<4>::ld(A.C + (size_t)(i0 + r) * m + col, cv[r][q]);
+                    VecLoad<4>::ld(A.C + (size_t)(i0 + r) * m + col, cv[r][q], 4);
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) cv[r][q][e] = 0.0f;
@@ -386,6 +398,18 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     const int rr = lane / NW;                  // the panel row this lane serves in the merge
     const int rc = rr < R ? rr : R - 1;
     auto colok = [&](int q) { return FULLW || ((q * T + tid) * 4) < m; };
+    // Staged costs of group q: the 16 bytes of a lane that owns the last columns of a row run on into the
+    // next row (or past the panel, where the load returns 0); those entries are zeroed here and removed
+    // by V = -inf, so that nothing foreign (a NaN of the next row, say) enters this row's sum.
+    auto unpack = [&](const float4 &c4, int q, float (&o)[4]) {
+        o[0] = c4.x; o[1] = c4.y; o[2] = c4.z; o[3] = c4.w;
+        if (!FULLW) {
+            const int col = (q * T + tid) * 4;
+#pragma unroll
+            for (int e = 1; e < 4; ++e)
+                if (col + e >= m) o[e] = 0.0f;
+        }
+    };
 
     // Lanes whose columns lie past m never receive data (their loads are masked off); their staging
     // slots are cleared once so that they read as a finite cost and V = -inf removes them.
@@ -450,8 +474,9 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
             const int col = (q * T + tid) * 4;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                v0[q][e] = colok(q) ? p.V[col + e] : -__builtin_huge_val();
-                v1[q][e] = colok(q) ? p.V[(size_t)p.m_ld + col + e] : -__builtin_huge_val();
+                const bool ok = FULLW || col + e < m;          // m need not be a multiple of 4
+                v0[q][e] = ok ? p.V[col + e] : -__builtin_huge_val();
+                v1[q][e] = ok ? p.V[(size_t)p.m_ld + col + e] : -__builtin_huge_val();
             }
         }
     }
@@ -487,7 +512,7 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             if constexpr (kBothV) v[q][e] = cur ? v1[q][e] : v0[q][e];
-            else v[q][e] = colok(q) ? p.V[(size_t)cur * p.m_ld + col + e] : -__builtin_huge_val();
+            else v[q][e] = (FULLW || col + e < m) ? p.V[(size_t)cur * p.m_ld + col + e] : -__builtin_huge_val();
         }
     }
     float cS[Q][4];                            // column sums of the plan entries
@@ -542,7 +567,8 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
                 const float4 c4 = stage[buf][wave][r][q][lane];
-                const float cvv[4] = {c4.x, c4.y, c4.z, c4.w};
+                float cvv[4];
+                unpack(c4, q, cvv);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     ev[r][q][e] = fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - rho[r]));
@@ -570,7 +596,8 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
                     const float4 c4 = stage[buf][wave][r][q][lane];
-                    const float cvv[4] = {c4.x, c4.y, c4.z, c4.w};
+                    float cvv[4];
+                unpack(c4, q, cvv);
                     double x[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) x[e] = fma(ns, (double)cvv[e], v[q][e]);
@@ -601,7 +628,8 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
 #pragma unroll
                     for (int q = 0; q < Q; ++q) {
                         const float4 c4 = stage[buf][wave][r][q][lane];
-                        const float cvv[4] = {c4.x, c4.y, c4.z, c4.w};
+                        float cvv[4];
+                unpack(c4, q, cvv);
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
                             ev[r][q][e] = fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - Fn));
@@ -647,8 +675,13 @@ struct FusedShape { int T, Q, R; };
 
 // Shapes held in registers without spilling: 4*Q*T columns, R rows per panel.
 static bool fused_shape(int m, int variant, FusedShape *fsh) {
-    if (m % 4 != 0) return false;
     if (variant >= 100) variant -= 100;
+    // The LDS-prefetch kernels take any m (a row may start at any 4-byte boundary; columns past m are
+    // masked by V = -inf); the register-panel kernels need whole groups of 4 columns.
+    if (m % 4 != 0) {
+        if (m <= 1024) return false;
+        if (m <= 8192) variant = 0;
+    }
     if (m <= 1024) { *fsh = {256, 1, 4}; return true; }
     if (m <= 4096) {
         if (variant == 1) *fsh = {1024, 1, 4};               // register panel, exact running-max arithmetic
@@ -674,7 +707,7 @@ static bool fused_shape(int m, int variant, FusedShape *fsh) {
 bool dense_fused_supported(int n, int m, const void *C) {
     FusedShape s;
     (void)n;
-    return fused_shape(m, 0, &s) && ((reinterpret_cast<uintptr_t>(C) & 15u) == 0);
+    return fused_shape(m, 0, &s) && ((reinterpret_cast<uintptr_t>(C) & 3u) == 0);
 }
 
 void dense_fused_plan(int n, int m, int *P) {
