@@ -12,9 +12,10 @@ LIB = os.path.join(HERE, "libfastsinkhorn.so")
 OBJDIR = os.path.join(HERE, "_build")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-# packed fp32 VALU forms are switched off for every device compile
+# packed fp32 VALU forms are switched off for every device compile; matrix-core accumulators stay in
+# ordinary vector registers (no copies to and from the accumulation registers around every tile)
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 
 def sources():

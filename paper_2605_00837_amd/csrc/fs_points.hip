@@ -11,7 +11,7 @@
 // Work split: a workgroup of 256 lanes owns 256*IB rows (IB per lane, kept in
 // registers) and one slice of the columns; column tiles are staged in LDS and
 // read back as wave-wide broadcasts.  Per-slice partial LSE values are merged
-// by k_combine.
+// by k_combine.  More than 4 coordinates: the matrix-core kernel further down.
 #include "fs_kernels.h"
 
 namespace fs {
@@ -151,48 +151,153 @@ __global__ __launch_bounds__(kPT) void k_points_lse(PointsArgs A, Ctl c, int use
         if (row[b] < A.nr) A.part[(size_t)blockIdx.y * A.ld + row[b]] = acc[b].value();
 }
 
-// Any dimension: one row per lane, coordinates re-read through the cache.
-__global__ __launch_bounds__(kPT) void k_points_lse_anyd(PointsArgs A, Ctl c, int use_next, int ld_shift) {
-    extern __shared__ double dyn[];                        // [64][d + 1]
-    constexpr int TJ = 64;
-    int k;
-    if (!launch_active(c, k)) return;
-    const int buf = use_next ? ((k & 1) ^ 1) : (k & 1);
-    const double *shift = A.colshift + (size_t)buf * ld_shift;
-    const int tid = threadIdx.x, d = A.d, ldt = d + 1;
-    const int row = blockIdx.x * kPT + tid;
-    const bool rok = row < A.nr;
-    const double *xr = A.rows + (size_t)(rok ? row : 0) * d;
-    Lse acc; acc.init();
-    const int j0 = blockIdx.y * A.cols_per_split;
-    const int j1 = min(A.nc, j0 + A.cols_per_split);
-    for (int jt = j0; jt < j1; jt += TJ) {
-        __syncthreads();
-        for (int e = tid; e < TJ * ldt; e += kPT) {
-            const int jj = e / ldt, t = e % ldt;
-            const int j = jt + jj;
-            double v;
-            if (j < j1) v = (t == 0) ? shift[j] + A.colconst[j] : A.cols2s[(size_t)j * d + (t - 1)];
-            else v = (t == 0) ? -__builtin_huge_val() : 0.0;
-            dyn[e] = v;
-        }
-        __syncthreads();
-        for (int jj = 0; jj < TJ; jj += 4) {
-            double val[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) val[q] = dyn[(jj + q) * ldt];
-            for (int t = 0; t < d; ++t) {
-                const double xv = xr[t];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) val[q] = fma(xv, dyn[(jj + q) * ldt + 1 + t], val[q]);
-            }
-            acc.add<4>(val);
-        }
-    }
-    if (rok) A.part[(size_t)blockIdx.y * A.ld + row] = acc.value();
+// ---------------------------------------------------------------- d > 4: the dot products are a contraction
+// For more than a handful of coordinates the bracket's x_i . (2 s y_j) is a dense n x m x d contraction,
+// and it runs on the fp64 matrix cores: v_mfma_f64_16x16x4f64 computes a 16 x 16 tile of dot products
+// over 4 coordinates per instruction (A: lane l holds x[row l % 16][k = l / 16]; B: lane l holds
+// y'[col l % 16][k = l / 16]; D register r of lane l is entry (row l / 16 + 4 r, col l % 16)).  Products
+// of fp32 coordinates are exact in fp64 and the accumulation is fp64, so nothing is lost against the
+// d <= 4 kernels.  A wave keeps a few row tiles (16 rows each) of x in registers for the whole launch
+// and streams column tiles of y' from LDS; the accumulator starts at the column constant
+// (V_j - s|y_j|^2, minus the row's reference in the optimistic variant), so what comes out of the
+// matrix core is the exponent itself.  (kRT = 4 row tiles up to d = 16, 2 beyond.)  Row sums live in the 16 lanes that share a row quad and meet by
+// DPP at the end.  Both variants of the pass (see above k_points_lse) are here: FAST adds 2^(arg - ref);
+// ROBUST is the exact online LSE with one running maximum per row, updated per tile of 16 columns.
+constexpr int kMfmaTJ = 64;          // columns staged per LDS tile
+// row tiles per wave: more of them reuse every B operand more often, as long as the A operands fit
+constexpr int mfma_rt(int d4) { return d4 <= 4 ? 4 : 2; }
+constexpr int mfma_rows(int d4) { return 4 * mfma_rt(d4) * 16; }      // rows per workgroup of 4 waves
+
+typedef double double4_v __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ double row16_max_f64(double v) {      // all-reduce over a DPP row of 16 lanes
+    v = dmax(v, dpp_f64<0x128>(v));
+    v = dmax(v, dpp_f64<0x124>(v));
+    v = dmax(v, dpp_f64<0x122>(v));
+    v = dmax(v, dpp_f64<0x121>(v));
+    return v;
+}
+__device__ __forceinline__ float row16_sum_f32(float v) {
+    v += dpp_f32<0x128>(v);
+    v += dpp_f32<0x124>(v);
+    v += dpp_f32<0x122>(v);
+    v += dpp_f32<0x121>(v);
+    return v;
 }
 
-bool points_optimistic(int d) { return d <= 4; }
+template <int D4>
+__global__ __launch_bounds__(256) void k_points_mfma(PointsArgs A, Ctl c, int use_next, int ld_shift) {
+    constexpr int kRT = mfma_rt(D4), kMfmaRows = mfma_rows(D4);
+    constexpr int LDT = 4 * D4 + 1;                       // padded row of the LDS tile (doubles)
+    __shared__ double tile[kMfmaTJ][LDT];
+    __shared__ double tilew[kMfmaTJ];
+#if defined(__HIP_DEVICE_COMPILE__)
+    const unsigned long long kd = load_counter(c);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lj = lane & 15, lk = lane >> 4;
+    const int d = A.d;
+    const int row0 = blockIdx.x * kMfmaRows + wave * (kRT * 16);
+
+    // A operands: x[row0 + rt*16 + lj][4 ks + lk], zero beyond nr and beyond d
+    double a[kRT][D4];
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt) {
+        const int row = row0 + rt * 16 + lj;
+#pragma unroll
+        for (int ks = 0; ks < D4; ++ks) {
+            const int t = 4 * ks + lk;
+            a[rt][ks] = (row < A.nr && t < d) ? A.rows[(size_t)row * d + t] : 0.0;
+        }
+    }
+    // the rows this lane sees in the results: row0 + rt*16 + lk + 4 r
+    double rconst[kRT][4];
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + rt * 16 + lk + 4 * r;
+            rconst[rt][r] = row < A.nr ? A.rowconst[row] : 0.0;
+        }
+    int k;
+    bool fast;
+    if (!counter_active(c, kd, k, &fast)) return;
+    const int cur = k & 1;
+    const int buf = use_next ? (cur ^ 1) : cur;
+    const double *shift = A.colshift + (size_t)buf * ld_shift;
+    const int j0 = blockIdx.y * A.cols_per_split;
+    const int j1 = min(A.nc, j0 + A.cols_per_split);
+
+    // FAST: ref = previous LSE of the bracket; ROBUST: M = running maximum
+    double ref[kRT][4];
+    float sum[kRT][4];
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + rt * 16 + lk + 4 * r;
+            ref[rt][r] = fast ? (row < A.nr ? A.rowpot[(size_t)cur * A.ld + row] - rconst[rt][r] : 0.0) : kNegHuge;
+            sum[rt][r] = 0.0f;
+        }
+
+    for (int jt = j0; jt < j1; jt += kMfmaTJ) {
+        __syncthreads();                                   // previous tile fully consumed
+        for (int e = tid; e < kMfmaTJ * 4 * D4; e += 256) {
+            const int jj = e / (4 * D4), t = e % (4 * D4);
+            const int j = jt + jj;
+            tile[jj][t] = (j < j1 && t < d) ? A.cols2s[(size_t)j * d + t] : 0.0;
+        }
+        if (tid < kMfmaTJ) {
+            const int j = jt + tid;
+            tilew[tid] = j < j1 ? shift[j] + A.colconst[j] : -__builtin_huge_val();
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ct = 0; ct < kMfmaTJ / 16; ++ct) {
+            double b[D4];
+#pragma unroll
+            for (int ks = 0; ks < D4; ++ks) b[ks] = tile[ct * 16 + lj][4 * ks + lk];
+            const double w = tilew[ct * 16 + lj];
+            // kRT independent accumulator chains, interleaved, so that a wave always has a matrix
+            // instruction to issue while the previous ones are still in the pipeline
+            double4_v acc[kRT];
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[rt][r] = fast ? w - ref[rt][r] : w;
+            }
+#pragma unroll
+            for (int ks = 0; ks < D4; ++ks)
+#pragma unroll
+                for (int rt = 0; rt < kRT; ++rt)
+                    acc[rt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[rt][ks], b[ks], acc[rt], 0, 0, 0);
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+                if (fast) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) sum[rt][r] += fast_exp2((float)acc[rt][r]);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const double Mn = dmax(ref[rt][r], row16_max_f64(acc[rt][r]));    // the same in all 16 lanes of the row
+                        sum[rt][r] = sum[rt][r] * fast_exp2((float)(ref[rt][r] - Mn)) + fast_exp2((float)(acc[rt][r] - Mn));
+                        ref[rt][r] = Mn;
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float S = row16_sum_f32(sum[rt][r]);
+            const int row = row0 + rt * 16 + lk + 4 * r;
+            if (lj == 0 && row < A.nr) A.part[(size_t)blockIdx.y * A.ld + row] = ref[rt][r] + log2_sum(S);
+        }
+#endif
+}
+
+bool points_optimistic(int d) { (void)d; return true; }
 
 void points_plan(int nr, int nc, int d, int *JS, int *cols_per_split) {
     const int rows_per_wg = (d <= 4) ? kPT * kIB : kPT;
@@ -219,9 +324,12 @@ hipError_t launch_points_lse(hipStream_t st, const PointsArgs &a, const Ctl &c, 
             default: hipLaunchKernelGGL((k_points_lse<4, kIB>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
         }
     } else {
-        const dim3 grid((a.nr + kPT - 1) / kPT, a.JS);
-        const size_t lds = (size_t)64 * (a.d + 1) * sizeof(double);
-        hipLaunchKernelGGL(k_points_lse_anyd, grid, dim3(kPT), lds, st, a, c, use_next_shift, ld_shift);
+        const int d4 = a.d <= 8 ? 2 : a.d <= 16 ? 4 : a.d <= 32 ? 8 : 16;
+        const dim3 grid((a.nr + mfma_rows(d4) - 1) / mfma_rows(d4), a.JS);
+        if (a.d <= 8) hipLaunchKernelGGL(k_points_mfma<2>, grid, dim3(256), 0, st, a, c, use_next_shift, ld_shift);
+        else if (a.d <= 16) hipLaunchKernelGGL(k_points_mfma<4>, grid, dim3(256), 0, st, a, c, use_next_shift, ld_shift);
+        else if (a.d <= 32) hipLaunchKernelGGL(k_points_mfma<8>, grid, dim3(256), 0, st, a, c, use_next_shift, ld_shift);
+        else hipLaunchKernelGGL(k_points_mfma<16>, grid, dim3(256), 0, st, a, c, use_next_shift, ld_shift);
     }
     return hipGetLastError();
 }

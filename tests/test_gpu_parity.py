@@ -163,7 +163,8 @@ def test_streaming_rejects_nothing_and_fused_rejects_odd_m(fs):
     assert e.value.status == fs.FS_ERR_UNSUPPORTED
 
 
-@pytest.mark.parametrize("n,m,d", [(300, 257, 3), (1000, 777, 3), (64, 64, 2), (129, 200, 5), (50, 60, 11)])
+@pytest.mark.parametrize("n,m,d", [(300, 257, 3), (1000, 777, 3), (64, 64, 2), (129, 200, 5), (50, 60, 11),
+                                   (700, 900, 8), (1500, 400, 16), (300, 2000, 17), (520, 515, 32), (400, 300, 50)])
 def test_points_solve(fs, oracle, n, m, d):
     w = W.random_points(n, m, d, seed=4000 + n + m + d, eps=0.02)
     r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 30)
@@ -171,7 +172,8 @@ def test_points_solve(fs, oracle, n, m, d):
 
 
 @pytest.mark.parametrize("n,m,d,zero", [(300, 257, 3, False), (2100, 1500, 2, False), (700, 3000, 4, True),
-                                        (1030, 1030, 1, False)])
+                                        (1030, 1030, 1, False), (900, 1100, 6, True), (333, 1500, 20, False),
+                                        (260, 130, 64, False), (1000, 70, 33, False)])
 def test_points_optimistic_pass_and_repair(fs, oracle, n, m, d, zero):
     """fused_variant = 100 makes the point-cloud LSE pass optimistic (previous potential as the
     reference, plain fp32 sums) from the first iteration on, while the potentials still move by
