@@ -630,7 +630,7 @@ fs_status plan_or_cost(const float *C, const float *X, const float *Y, int d, co
     if (v != FS_OK) return v;
     if (!P && !cost_dev) { set_err("output pointer is null"); return FS_ERR_INVALID_ARG; }
     const int dd = C ? 0 : d;
-    const int need = cost_scratch_len(n, m);
+    const int need = plan_scratch_len(n, m, dd);
     const size_t bytes = P ? sizeof(double) * (size_t)need : diag_scratch_bytes(n, m, dd);
     DeviceCache *dc = nullptr;
     v = get_cache(bytes, &dc);

@@ -6,6 +6,7 @@
 // sum lane-local.  Partial numerators / denominators per (strip or slice, row) are added in fixed
 // order by a finishing kernel.
 #include "fs_kernels.h"
+#include "fs_mfma.h"
 
 namespace fs {
 
@@ -212,51 +213,64 @@ __global__ __launch_bounds__(kBP) void k_bary_points(BaryPoints A) {
         }
 }
 
-// Any dimension: one row per lane, its coordinates re-read through the cache.
-__global__ __launch_bounds__(kBP) void k_bary_points_anyd(BaryPoints A, int d) {
-    extern __shared__ double dyn[];                          // [64][d + 1], then 64 x kZ floats
-    constexpr int TJ = 64;
-    const int tid = threadIdx.x, ldt = d + 1;
-    float *dz_tile = reinterpret_cast<float *>(dyn + TJ * ldt);
-    const int row = blockIdx.x * kBP + tid;
-    const bool rok = row < A.nr;
-    const double *xr = A.rows + (size_t)(rok ? row : 0) * d;
-    const double rc = rok ? A.rowlog[row] - A.rowq[row] : -__builtin_huge_val();
-    float acc[kZ + 1];
+// More than 4 coordinates: the dot products run on the fp64 matrix cores (fs_mfma.h); the accumulator
+// starts at (cj_j - s|y_j|^2) + (ri_i - s|x_i|^2), so the matrix core delivers log2 P_ij itself.
+template <int D4>
+__global__ __launch_bounds__(256) void k_bary_points_mfma(BaryPoints A, int d) {
+    __shared__ double tile[kTileJ][4 * D4 + 1];
+    __shared__ double tw[kTileJ];
+    __shared__ float tz[kTileJ][kZ];
+    const int tid = threadIdx.x, lj = tid & 15;
+    RowTiles<D4> R;
+    R.load(A.rows, A.nr, d);
+    double rc[kTileRT][4];
+    float acc5[kTileRT][4][kZ + 1];
 #pragma unroll
-    for (int t = 0; t <= kZ; ++t) acc[t] = 0.0f;
+    for (int rt = 0; rt < kTileRT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = R.result_row(rt, r);
+            rc[rt][r] = row < A.nr ? A.rowlog[row] - A.rowq[row] : -__builtin_huge_val();
+#pragma unroll
+            for (int t = 0; t <= kZ; ++t) acc5[rt][r][t] = 0.0f;
+        }
     const int j0 = blockIdx.y * A.cols_per_split;
     const int j1 = min(A.nc, j0 + A.cols_per_split);
-    for (int jt = j0; jt < j1; jt += TJ) {
-        __syncthreads();
-        for (int e = tid; e < TJ * ldt; e += kBP) {
-            const int jj = e / ldt, t = e % ldt;
-            const int j = jt + jj;
-            double v;
-            if (j < j1) v = (t == 0) ? A.collog[j] - A.colq[j] : A.cols2s[(size_t)j * d + (t - 1)];
-            else v = (t == 0) ? -__builtin_huge_val() : 0.0;
-            dyn[e] = v;
-        }
-        for (int e = tid; e < TJ * kZ; e += kBP) {
-            const int jj = e / kZ, t = e % kZ;
-            const int j = jt + jj;
-            dz_tile[e] = (j < j1 && t < A.dz) ? A.Z[(size_t)j * A.dz + t] : 0.0f;
-        }
-        __syncthreads();
-        for (int jj = 0; jj < TJ; ++jj) {
-            double tq = dyn[jj * ldt];
-            for (int t = 0; t < d; ++t) tq = fma(xr[t], dyn[jj * ldt + 1 + t], tq);
-            float p = fast_exp2((float)(tq + rc));
-            p = p > 0.0f ? p : 0.0f;
+    mfma_walk<D4>(
+        R, tile, A.cols2s, d, j0, j1,
+        [&](int jt) {
+            if (tid < kTileJ) {
+                const int j = jt + tid;
+                tw[tid] = j < j1 ? A.collog[j] - A.colq[j] : -__builtin_huge_val();
 #pragma unroll
-            for (int t = 0; t < kZ; ++t) acc[t] = fmaf(p, dz_tile[jj * kZ + t], acc[t]);
-            acc[kZ] += p;
-        }
-    }
-    if (rok) {
+                for (int t = 0; t < kZ; ++t) tz[tid][t] = (j < j1 && t < A.dz) ? A.Z[(size_t)j * A.dz + t] : 0.0f;
+            }
+        },
+        [&](int ct, int rt, int r) { return tw[ct * 16 + lj] + rc[rt][r]; },
+        [&](int, int ct, int rt, const double4_m &acc) {
+            float z[kZ];
 #pragma unroll
-        for (int t = 0; t <= kZ; ++t) A.part[((size_t)blockIdx.y * A.nr + row) * (kZ + 1) + t] = acc[t];
-    }
+            for (int t = 0; t < kZ; ++t) z[t] = tz[ct * 16 + lj][t];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float p = fast_exp2((float)acc[r]);
+                p = p > 0.0f ? p : 0.0f;
+#pragma unroll
+                for (int t = 0; t < kZ; ++t) acc5[rt][r][t] = fmaf(p, z[t], acc5[rt][r][t]);
+                acc5[rt][r][kZ] += p;
+            }
+        });
+#pragma unroll
+    for (int rt = 0; rt < kTileRT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = R.result_row(rt, r);
+#pragma unroll
+            for (int t = 0; t <= kZ; ++t) {
+                const float tot = row16_sum(acc5[rt][r][t]);
+                if (lj == 0 && row < A.nr) A.part[((size_t)blockIdx.y * A.nr + row) * (kZ + 1) + t] = tot;
+            }
+        }
 }
 
 // T[i][t] = (sum over partial sets of the numerators) / (sum of the denominators), in double.
@@ -312,9 +326,13 @@ hipError_t launch_bary(hipStream_t st, const PlanArgs &a, const float *Z, int dz
                 default: hipLaunchKernelGGL(k_bary_points<4>, grid, dim3(kBP), 0, st, X); break;
             }
         } else {
-            const dim3 grid((a.n + kBP - 1) / kBP, L.JS);
-            const size_t lds = (size_t)64 * (a.d + 1) * sizeof(double) + (size_t)64 * kZ * sizeof(float);
-            hipLaunchKernelGGL(k_bary_points_anyd, grid, dim3(kBP), lds, st, X, a.d);
+            const dim3 grid((a.n + kTileRows - 1) / kTileRows, L.JS);
+            switch (mfma_d4(a.d)) {
+                case 2: hipLaunchKernelGGL(k_bary_points_mfma<2>, grid, dim3(256), 0, st, X, a.d); break;
+                case 4: hipLaunchKernelGGL(k_bary_points_mfma<4>, grid, dim3(256), 0, st, X, a.d); break;
+                case 8: hipLaunchKernelGGL(k_bary_points_mfma<8>, grid, dim3(256), 0, st, X, a.d); break;
+                default: hipLaunchKernelGGL(k_bary_points_mfma<16>, grid, dim3(256), 0, st, X, a.d); break;
+            }
         }
     }
     hipLaunchKernelGGL(k_bary_finish, dim3((a.n + 255) / 256), dim3(256), 0, st, part, L.nparts, a.n, dz, T);

@@ -15,6 +15,7 @@
 // is a lane-local sum; the cost uses s C_ij = s|x_i|^2 + s|y_j|^2 - x_i . (2 s y_j).
 // All partial results are combined in fixed order: the outputs do not depend on timing.
 #include "fs_kernels.h"
+#include "fs_mfma.h"
 
 namespace fs {
 
@@ -72,7 +73,7 @@ DiagLayout diag_layout(int n, int m, int d) {
         points_plan(m, n, d, &L.JSy, &L.cpsy);
         L.o_rowpart = take(sizeof(double) * (size_t)L.JSx * n);      // row sums per column slice
         L.o_colpart = take(sizeof(double) * (size_t)L.JSy * m);      // column sums per row slice
-        const int rows_per_wg = d <= 4 ? kPT2 * kIB2 : kPT2;
+        const int rows_per_wg = d <= 4 ? kPT2 * kIB2 : kTileRows;
         const int gx = (n + rows_per_wg - 1) / rows_per_wg;
         L.nscal = gx * L.JSx;
         L.o_scal = take(sizeof(double) * 2 * L.nscal);
@@ -320,55 +321,76 @@ __global__ __launch_bounds__(kPT2) void k_diag_points(PointsDiag A) {
     }
 }
 
-// Any dimension: one row per lane, coordinates of the row re-read through the cache.
-template <bool WITH_COST>
-__global__ __launch_bounds__(kPT2) void k_diag_points_anyd(PointsDiag A, int d) {
-    extern __shared__ double dyn[];                         // [64][d + 2]
-    __shared__ double lds[kPT2];
-    constexpr int TJ = 64;
-    const int tid = threadIdx.x, ldt = d + 2;
-    const int row = blockIdx.x * kPT2 + tid;
-    const bool rok = row < A.nr;
-    const double *xr = A.rows + (size_t)(rok ? row : 0) * d;
-    const double rq = rok ? A.rowq[row] : 0.0;
-    const double rc = rok ? A.rowlog[row] - rq : -__builtin_huge_val();
-    double rs = 0.0, cost_acc = 0.0, ent_acc = 0.0;
+// More than 4 coordinates: the dot products run on the fp64 matrix cores (fs_mfma.h).  The accumulator
+// starts at (cj_j - s|y_j|^2) + (ri_i - s|x_i|^2), so the matrix core delivers log2 P_ij itself.
+template <int D4, bool WITH_COST>
+__global__ __launch_bounds__(256) void k_diag_points_mfma(PointsDiag A, int d) {
+    __shared__ double tile[kTileJ][4 * D4 + 1];
+    __shared__ double tw[kTileJ], tcl[kTileJ];
+    __shared__ double lds[256];
+    const int tid = threadIdx.x, lj = tid & 15;
+    RowTiles<D4> R;
+    R.load(A.rows, A.nr, d);
+    double rc[kTileRT][4], rlog[kTileRT][4], rs[kTileRT][4];
+    float rf[kTileRT][4];
+#pragma unroll
+    for (int rt = 0; rt < kTileRT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = R.result_row(rt, r);
+            const bool ok = row < A.nr;
+            rlog[rt][r] = ok ? A.rowlog[row] : -__builtin_huge_val();
+            rc[rt][r] = ok ? rlog[rt][r] - A.rowq[row] : -__builtin_huge_val();
+            rs[rt][r] = 0.0;
+            rf[rt][r] = 0.0f;
+        }
+    double cost_acc = 0.0, ent_acc = 0.0;
+    float cf = 0.0f, ef = 0.0f;
     const int j0 = blockIdx.y * A.cols_per_split;
     const int j1 = min(A.nc, j0 + A.cols_per_split);
-    for (int jt = j0; jt < j1; jt += TJ) {
-        __syncthreads();
-        for (int e = tid; e < TJ * ldt; e += kPT2) {
-            const int jj = e / ldt, t = e % ldt;
-            const int j = jt + jj;
-            double v;
-            if (j < j1) v = (t == 0) ? A.collog[j] - A.colq[j] : (t == d + 1) ? A.colq[j] : A.cols2s[(size_t)j * d + (t - 1)];
-            else v = (t == 0) ? -__builtin_huge_val() : 0.0;
-            dyn[e] = v;
-        }
-        __syncthreads();
-        float rf = 0.0f, cf = 0.0f, ef = 0.0f;
-        for (int jj = 0; jj < TJ; ++jj) {
-            double dot = 0.0;
-            for (int t = 0; t < d; ++t) dot = fma(xr[t], dyn[jj * ldt + 1 + t], dot);
-            const double arg = (dyn[jj * ldt] + rc) + dot;
-            const float p = fast_exp2((float)arg);
-            if (p > 0.0f) {
-                rf += p;
+    mfma_walk<D4>(
+        R, tile, A.cols2s, d, j0, j1,
+        [&](int jt) {
+            if (tid < kTileJ) {
+                const int j = jt + tid;
+                const double lg = j < j1 ? A.collog[j] : -__builtin_huge_val();
+                tw[tid] = j < j1 ? lg - A.colq[j] : -__builtin_huge_val();
+                tcl[tid] = lg;
+            }
+        },
+        [&](int ct, int rt, int r) { return tw[ct * 16 + lj] + rc[rt][r]; },
+        [&](int, int ct, int rt, const double4_m &acc) {
+            const double cl = tcl[ct * 16 + lj];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const double arg = acc[r];
+                const float argf = (float)arg;
+                float p = fast_exp2(argf);
+                p = p > 0.0f ? p : 0.0f;                                   // drops NaN
+                rf[rt][r] += p;
                 if (WITH_COST) {
-                    const double sc = (rq + dyn[jj * ldt + d + 1]) - dot;
-                    cf = fmaf(p, (float)sc, cf);
-                    ef = fmaf(p, (float)arg, ef);
+                    const double sc = (rlog[rt][r] + cl) - arg;              // s |x - y|^2
+                    cf = fmaf(p, fminf((float)sc, 1.0e30f), cf);             // 0 * inf (or NaN) must stay 0
+                    ef = fmaf(p, fmaxf(argf, -1.0e30f), ef);
                 }
             }
+            if (ct == kTileJ / 16 - 1) {                                    // fp32 sums span one LDS tile
+#pragma unroll
+                for (int r = 0; r < 4; ++r) { rs[rt][r] += (double)rf[rt][r]; rf[rt][r] = 0.0f; }
+                if (rt == kTileRT - 1) { cost_acc += (double)cf; ent_acc += (double)ef; cf = 0.0f; ef = 0.0f; }
+            }
+        });
+#pragma unroll
+    for (int rt = 0; rt < kTileRT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const double tot = row16_sum(rs[rt][r]);
+            const int row = R.result_row(rt, r);
+            if (lj == 0 && row < A.nr) A.part[(size_t)blockIdx.y * A.nr + row] = tot;
         }
-        rs += (double)rf;
-        cost_acc += (double)cf;
-        ent_acc += (double)ef;
-    }
-    if (rok) A.part[(size_t)blockIdx.y * A.nr + row] = rs;
     if (WITH_COST) {
-        const double c_tot = block_sum<kPT2>(cost_acc, lds);
-        const double e_tot = block_sum<kPT2>(ent_acc, lds);
+        const double c_tot = block_sum<256>(cost_acc, lds);
+        const double e_tot = block_sum<256>(ent_acc, lds);
         if (tid == 0) {
             const size_t w = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
             A.scal[2 * w] = c_tot;
@@ -570,10 +592,19 @@ hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *
                         break;
             }
         } else {
-            const dim3 gx((a.n + kPT2 - 1) / kPT2, L.JSx), gy((a.m + kPT2 - 1) / kPT2, L.JSy);
-            const size_t lds = (size_t)64 * (a.d + 2) * sizeof(double);
-            hipLaunchKernelGGL(k_diag_points_anyd<true>, gx, dim3(kPT2), lds, st, X, a.d);
-            if (!cost_only) hipLaunchKernelGGL(k_diag_points_anyd<false>, gy, dim3(kPT2), lds, st, Y, a.d);
+            const dim3 gx((a.n + kTileRows - 1) / kTileRows, L.JSx), gy((a.m + kTileRows - 1) / kTileRows, L.JSy);
+#define FS_DIAG_MFMA(D4)                                                                                   \
+    do {                                                                                                    \
+        hipLaunchKernelGGL((k_diag_points_mfma<D4, true>), gx, dim3(256), 0, st, X, a.d);                  \
+        if (!cost_only) hipLaunchKernelGGL((k_diag_points_mfma<D4, false>), gy, dim3(256), 0, st, Y, a.d); \
+    } while (0)
+            switch (mfma_d4(a.d)) {
+                case 2: FS_DIAG_MFMA(2); break;
+                case 4: FS_DIAG_MFMA(4); break;
+                case 8: FS_DIAG_MFMA(8); break;
+                default: FS_DIAG_MFMA(16); break;
+            }
+#undef FS_DIAG_MFMA
         }
         R.rowpart = X.part; R.nrowpart = L.JSx;
         R.colpart = Y.part; R.ncolpart = cost_only ? 0 : L.JSy; R.colpart_is_float = 0;

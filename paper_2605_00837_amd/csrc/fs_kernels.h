@@ -132,6 +132,7 @@ struct PlanArgs {
 hipError_t launch_plan(hipStream_t st, const PlanArgs &a, float *P, double *scratch, int nscratch);
 hipError_t launch_cost(hipStream_t st, const PlanArgs &a, double *cost_dev, double *scratch, int nscratch);
 int cost_scratch_len(int n, int m);
+int plan_scratch_len(int n, int m, int d);
 
 // Diagnostics in one pass (cost, mass, KL, primal, dual, marginal errors; optional marginals).
 size_t diag_scratch_bytes(int n, int m, int d);

@@ -7,6 +7,7 @@
 // to fp32 only for v_exp_f32.  The cost is accumulated in fp64 per workgroup
 // and the per-workgroup partials are summed in index order by one workgroup.
 #include "fs_kernels.h"
+#include "fs_mfma.h"
 
 namespace fs {
 
@@ -94,6 +95,53 @@ __global__ __launch_bounds__(256) void k_plan_dense4(PlanArgs A, const double *r
     }
 }
 
+// Plan of a point-cloud problem: 16 x 16 tiles of exponents from the fp64 matrix cores (fs_mfma.h; d <= 4
+// is padded to one instruction), written as they come: result register r of lane l is entry
+// (row l / 16 + 4 r, col l % 16), so every store instruction writes four 64-byte row segments.
+struct PlanPoints {
+    const double *rows, *rowq, *rowlog;     // x side: plain coordinates, s|x|^2, ri
+    const double *cols2s, *colq, *collog;   // y side: 2 s y, s|y|^2, cj
+    int32_t nr, nc;
+    float *P;
+    int32_t cols_per_split;
+};
+
+template <int D4>
+__global__ __launch_bounds__(256) void k_plan_points_mfma(PlanPoints A, int d) {
+    __shared__ double tile[kTileJ][4 * D4 + 1];
+    __shared__ double tw[kTileJ];
+    const int tid = threadIdx.x, lj = tid & 15;
+    RowTiles<D4> R;
+    R.load(A.rows, A.nr, d);
+    double rc[kTileRT][4];
+#pragma unroll
+    for (int rt = 0; rt < kTileRT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = R.result_row(rt, r);
+            rc[rt][r] = row < A.nr ? A.rowlog[row] - A.rowq[row] : -__builtin_huge_val();
+        }
+    const int j0 = blockIdx.y * A.cols_per_split;
+    const int j1 = min(A.nc, j0 + A.cols_per_split);
+    mfma_walk<D4>(
+        R, tile, A.cols2s, d, j0, j1,
+        [&](int jt) {
+            if (tid < kTileJ) {
+                const int j = jt + tid;
+                tw[tid] = j < j1 ? A.collog[j] - A.colq[j] : -__builtin_huge_val();
+            }
+        },
+        [&](int ct, int rt, int r) { return tw[ct * 16 + lj] + rc[rt][r]; },
+        [&](int jt, int ct, int rt, const double4_m &acc) {
+            const int j = jt + ct * 16 + lj;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = R.result_row(rt, r);
+                if (row < A.nr && j < j1) A.P[(size_t)row * A.nc + j] = fast_exp2((float)acc[r]);
+            }
+        });
+}
+
 __global__ __launch_bounds__(256) void k_sum_partials(const double *partial, int count, double *out) {
     __shared__ double lds[256];
     double acc = 0.0;
@@ -136,12 +184,35 @@ hipError_t launch_cost(hipStream_t st, const PlanArgs &a, double *cost_dev, doub
     return hipGetLastError();
 }
 
+int plan_scratch_len(int n, int m, int d) {
+    return d > 0 ? n + m + (n + m) * (2 * d + 1) : cost_scratch_len(n, m);
+}
+
 hipError_t launch_plan(hipStream_t st, const PlanArgs &a, float *P, double *scratch, int nscratch) {
     dim3 grid;
     plan_grid(a.n, a.m, &grid);
-    if (nscratch < a.n + a.m) return hipErrorInvalidValue;
+    if (nscratch < plan_scratch_len(a.n, a.m, a.d)) return hipErrorInvalidValue;
     double *ri = scratch, *cj = scratch + a.n;
     const int len = a.n > a.m ? a.n : a.m;
+    if (a.d > 0) {
+        // point clouds: repacked clouds after ri, cj; tiles of the plan from the matrix cores
+        double *xp = cj + a.m, *xs = xp + (size_t)a.n * a.d, *xq = xs + (size_t)a.n * a.d;
+        double *yp = xq + a.n, *ys = yp + (size_t)a.m * a.d, *yq = ys + (size_t)a.m * a.d;
+        hipError_t e = launch_plan_prep_all(st, a, ri, cj, xp, xs, xq, yp, ys, yq);
+        if (e != hipSuccess) return e;
+        PlanPoints pp{};
+        pp.rows = xp; pp.rowq = xq; pp.rowlog = ri; pp.cols2s = ys; pp.colq = yq; pp.collog = cj;
+        pp.nr = a.n; pp.nc = a.m; pp.P = P; pp.cols_per_split = 2048;
+        const dim3 g2((a.n + kTileRows - 1) / kTileRows, (a.m + 2047) / 2048);
+        switch (mfma_d4(a.d)) {
+            case 1: hipLaunchKernelGGL(k_plan_points_mfma<1>, g2, dim3(256), 0, st, pp, a.d); break;
+            case 2: hipLaunchKernelGGL(k_plan_points_mfma<2>, g2, dim3(256), 0, st, pp, a.d); break;
+            case 4: hipLaunchKernelGGL(k_plan_points_mfma<4>, g2, dim3(256), 0, st, pp, a.d); break;
+            case 8: hipLaunchKernelGGL(k_plan_points_mfma<8>, g2, dim3(256), 0, st, pp, a.d); break;
+            default: hipLaunchKernelGGL(k_plan_points_mfma<16>, g2, dim3(256), 0, st, pp, a.d); break;
+        }
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(k_plan_prep, dim3((len + 255) / 256), dim3(256), 0, st, a, ri, cj);
     if (a.C && a.m % 4 == 0) {
         const int gx = (a.m / 4 + 255) / 256;
