@@ -35,7 +35,7 @@ BaryLayout bary_layout(int n, int m, int d) {
     L.o_ri = take(sizeof(double) * n);
     L.o_cj = take(sizeof(double) * m);
     if (d == 0) {
-        L.vec = (m % 4 == 0) ? 4 : 1;
+        L.vec = m >= 4 ? 4 : 1;
         const int strip_cols = kBT * L.vec;
         L.nstrips = (m + strip_cols - 1) / strip_cols;
         int P = (512 + L.nstrips - 1) / L.nstrips;
@@ -100,9 +100,13 @@ __global__ __launch_bounds__(kBT) void k_bary_dense(BaryDense A) {
             if (i < i1) {
                 float cv[VEC];
                 if constexpr (VEC == 4) {
-                    const float4 c4 = jok[0] ? *reinterpret_cast<const float4 *>(A.C + (size_t)i * A.m + j0)
-                                             : make_float4(0.f, 0.f, 0.f, 0.f);
-                    cv[0] = c4.x; cv[1] = c4.y; cv[2] = c4.z; cv[3] = c4.w;
+                    if (jok[3]) {
+                        const float4_a4 c4 = *reinterpret_cast<const float4_a4 *>(A.C + (size_t)i * A.m + j0);
+                        cv[0] = c4.x; cv[1] = c4.y; cv[2] = c4.z; cv[3] = c4.w;
+                    } else {                                        // past m, or the last columns of an odd width
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) cv[e] = jok[e] ? A.C[(size_t)i * A.m + j0 + e] : 0.0f;
+                    }
                 } else {
                     cv[0] = jok[0] ? A.C[(size_t)i * A.m + j0] : 0.0f;
                 }

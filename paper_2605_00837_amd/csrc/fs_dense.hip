@@ -23,9 +23,8 @@ constexpr int kStreamT = 256;
 template <int VEC>
 struct VecLoad;
 // Four adjacent costs with one 16-byte load.  Rows of C start at multiples of m floats, i.e. at any
-// 4-byte boundary: the vector type says so, and the hardware's unaligned access mode does the rest.
-// `valid` < 4 (the last columns of a row whose length is not a multiple of 4) falls back to single loads.
-typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+// 4-byte boundary (float4_a4).  `valid` < 4 (the last columns of a row whose length is not a multiple
+// of 4) falls back to single loads.
 template <>
 struct VecLoad<4> {
     static __device__ __forceinline__ void ld(const float *p, float (&o)[4], int valid) {

@@ -102,6 +102,10 @@ __device__ __forceinline__ double log2_weight(float w) {
     return w > 0.0f ? log2((double)w) : -__builtin_huge_val();
 }
 
+// Four adjacent fp32 values at any 4-byte boundary (rows of a matrix whose width is not a multiple of
+// 4 start anywhere): one 16-byte access, the hardware's unaligned access mode does the rest.
+typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+
 // ---------------------------------------------------------------- DPP / swizzle moves
 // dpp_ctrl encodings: row_ror:n = 0x120 + n (rotate inside a row of 16 lanes).
 template <int CTRL>

@@ -53,7 +53,7 @@ DiagLayout diag_layout(int n, int m, int d) {
     L.o_red = take(sizeof(double) * 8 * L.nred);
     L.o_out = take(sizeof(double) * 8);
     if (d == 0) {
-        L.vec = (m % 4 == 0) ? 4 : 1;
+        L.vec = m >= 4 ? 4 : 1;
         L.strip_cols = kDT * L.vec;
         L.nstrips = (m + L.strip_cols - 1) / L.strip_cols;
         int P = (512 + L.nstrips - 1) / L.nstrips;
@@ -178,9 +178,13 @@ __global__ __launch_bounds__(kDT) void k_diag_dense(DenseDiag A) {
             if (i < i1) {
                 float cv[VEC];
                 if constexpr (VEC == 4) {
-                    const float4 c4 = jok[0] ? *reinterpret_cast<const float4 *>(A.C + (size_t)i * A.m + j0)
-                                             : make_float4(0.f, 0.f, 0.f, 0.f);
-                    cv[0] = c4.x; cv[1] = c4.y; cv[2] = c4.z; cv[3] = c4.w;
+                    if (jok[3]) {
+                        const float4_a4 c4 = *reinterpret_cast<const float4_a4 *>(A.C + (size_t)i * A.m + j0);
+                        cv[0] = c4.x; cv[1] = c4.y; cv[2] = c4.z; cv[3] = c4.w;
+                    } else {                                        // past m, or the last columns of an odd width
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) cv[e] = jok[e] ? A.C[(size_t)i * A.m + j0 + e] : 0.0f;
+                    }
                 } else {
                     cv[0] = jok[0] ? A.C[(size_t)i * A.m + j0] : 0.0f;
                 }

@@ -62,34 +62,49 @@ __global__ __launch_bounds__(256) void k_plan_cost(PlanArgs A, const double *ri,
     }
 }
 
-// Dense plan with m a multiple of 4: every lane owns 4 adjacent columns (16-byte loads of C, 16-byte
-// streaming stores of P), four rows in flight.
+// Dense plan: every lane owns 4 adjacent columns (16-byte loads of C, 16-byte streaming stores of P, at
+// whatever 4-byte boundary the row starts), four rows in flight; the lane that owns the last columns
+// of a width that is not a multiple of 4 works element by element.
 __global__ __launch_bounds__(256) void k_plan_dense4(PlanArgs A, const double *ri, const double *cj, float *P) {
     const int j = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (j >= A.m) return;
+    const int valid = A.m - j < 4 ? A.m - j : 4;
     double cjv[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) cjv[e] = cj[j + e];
+    for (int e = 0; e < 4; ++e) cjv[e] = e < valid ? cj[j + e] : 0.0;
     const double ns = -A.s;
     for (int i0 = blockIdx.y * 4; i0 < A.n; i0 += gridDim.y * 4) {
-        float4 c[4];
+        float c[4][4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            if (i0 + r < A.n) c[r] = *reinterpret_cast<const float4 *>(A.C + (size_t)(i0 + r) * A.m + j);
+        for (int r = 0; r < 4; ++r) {
+            if (i0 + r < A.n) {
+                const float *src = A.C + (size_t)(i0 + r) * A.m + j;
+                if (valid == 4) {
+                    const float4_a4 v = *reinterpret_cast<const float4_a4 *>(src);
+                    c[r][0] = v.x; c[r][1] = v.y; c[r][2] = v.z; c[r][3] = v.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) c[r][e] = e < valid ? src[e] : 0.0f;
+                }
+            }
+        }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             if (i0 + r < A.n) {
                 const double rv = ri[i0 + r];
-                float4 p;
-                p.x = fast_exp2((float)(fma(ns, (double)c[r].x, rv + cjv[0])));
-                p.y = fast_exp2((float)(fma(ns, (double)c[r].y, rv + cjv[1])));
-                p.z = fast_exp2((float)(fma(ns, (double)c[r].z, rv + cjv[2])));
-                p.w = fast_exp2((float)(fma(ns, (double)c[r].w, rv + cjv[3])));
+                float p[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) p[e] = fast_exp2((float)(fma(ns, (double)c[r][e], rv + cjv[e])));
                 float *dst = P + (size_t)(i0 + r) * A.m + j;
-                __builtin_nontemporal_store(p.x, dst);
-                __builtin_nontemporal_store(p.y, dst + 1);
-                __builtin_nontemporal_store(p.z, dst + 2);
-                __builtin_nontemporal_store(p.w, dst + 3);
+                if (valid == 4) {
+                    float4_a4 v;
+                    v.x = p[0]; v.y = p[1]; v.z = p[2]; v.w = p[3];
+                    __builtin_nontemporal_store(v, reinterpret_cast<float4_a4 *>(dst));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (e < valid) dst[e] = p[e];
+                }
             }
         }
     }
@@ -214,8 +229,8 @@ hipError_t launch_plan(hipStream_t st, const PlanArgs &a, float *P, double *scra
         return hipGetLastError();
     }
     hipLaunchKernelGGL(k_plan_prep, dim3((len + 255) / 256), dim3(256), 0, st, a, ri, cj);
-    if (a.C && a.m % 4 == 0) {
-        const int gx = (a.m / 4 + 255) / 256;
+    if (a.C && a.m >= 4) {
+        const int gx = ((a.m + 3) / 4 + 255) / 256;
         int gy = (2048 + gx - 1) / gx;
         if (gy > (a.n + 3) / 4) gy = (a.n + 3) / 4;
         hipLaunchKernelGGL(k_plan_dense4, dim3(gx, gy), dim3(256), 0, st, a, ri, cj, P);

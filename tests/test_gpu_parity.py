@@ -397,10 +397,12 @@ def test_blocking_and_async_entry_points_agree(fs):
 
 
 # ------------------------------------------------------------------ plan and cost
-@pytest.mark.parametrize("kind", ["dense", "points", "points1", "points6", "points20", "points64"])
+@pytest.mark.parametrize("kind", ["dense", "dense_odd", "points", "points1", "points6", "points20", "points64"])
 def test_plan_and_cost(fs, oracle, kind):
     if kind == "dense":
         w = W.random_dense(130, 300, seed=31, eps=0.04)
+    elif kind == "dense_odd":
+        w = W.random_dense(77, 4099, seed=33, eps=0.04)
     else:
         d = int(kind[6:] or 3)
         w = W.random_points(130 + 7 * d, 257 + d, d, seed=31 + d, eps=0.04)
@@ -424,7 +426,8 @@ def test_plan_and_cost(fs, oracle, kind):
 
 # ------------------------------------------------------------------ closed form at size (independent of the oracle)
 @pytest.mark.parametrize("kind,n,m,d", [("dense", 300, 257, 0), ("dense", 130, 4100, 0), ("dense", 1000, 8192, 0),
-                                         ("dense", 33, 1, 0), ("points", 700, 1300, 3), ("points", 1030, 500, 2),
+                                         ("dense", 33, 1, 0), ("dense", 90, 4101, 0), ("dense", 50, 6, 0),
+                                         ("points", 700, 1300, 3), ("points", 1030, 500, 2),
                                          ("points", 90, 200, 7), ("points", 300, 1000, 16), ("points", 520, 130, 33),
                                          ("points", 129, 257, 64)])
 @pytest.mark.parametrize("precision", ["f32", "f64"])
@@ -461,7 +464,7 @@ def test_diagnostics_one_pass(fs, oracle, kind, n, m, d, precision):
 
 
 @pytest.mark.parametrize("kind,n,m,d,dz", [("dense", 300, 257, 0, 3), ("dense", 130, 4100, 0, 1), ("dense", 700, 8192, 0, 4),
-                                            ("dense", 17, 3, 0, 2), ("points", 700, 1300, 3, 3), ("points", 1030, 500, 2, 4),
+                                            ("dense", 17, 3, 0, 2), ("dense", 61, 4102, 0, 3), ("points", 700, 1300, 3, 3), ("points", 1030, 500, 2, 4),
                                             ("points", 90, 200, 7, 2), ("points", 400, 300, 12, 4), ("points", 131, 1025, 40, 1),
                                             ("points", 260, 64, 64, 3)])
 def test_barycentric_mapping(fs, oracle, kind, n, m, d, dz):
