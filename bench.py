@@ -50,9 +50,18 @@ def cpu_baseline(w, budget_s=12.0):
     t0 = time.perf_counter()
     oracle.solve(w.a, w.b, w.eps, iters, tol=1e-30, check_every=10, C=w.C)
     dt = time.perf_counter() - t0
+    # the same oracle on one thread, two iterations
+    oracle.set_threads(1)
+    try:
+        t0 = time.perf_counter()
+        oracle.solve(w.a, w.b, w.eps, 2, tol=1e-30, check_every=10, C=w.C)
+        dt1 = time.perf_counter() - t0
+    finally:
+        oracle.set_threads(threads)
     return {"value": iters / dt, "unit": "iter/s", "cores": threads, "kind": "oracle",
             "sample": f"{iters} iterations of Alg. 1 (check every 10) on the same n=m={w.n} dense inputs, "
-                      f"fp64, OpenMP over rows/columns, {dt:.1f} s"}
+                      f"fp64, OpenMP over rows/columns, {dt:.1f} s",
+            "one_thread_value": 2 / dt1}
 
 
 # Point-cloud LSE pass, optimistic variant, per point pair: d fp64 FMAs, one fp64 subtraction, one
