@@ -56,6 +56,9 @@ typedef void *fs_stream;
 
 #define FS_MAX_DIM 64
 #define FS_MAX_POINTS 1048512   /* 16383 * 64 */
+#define FS_COST_F32 0
+#define FS_COST_F16 1
+#define FS_COST_BF16 2
 #define FS_SMALL_MAX 256        /* largest n, m of the single-workgroup / batched kernel */
 
 typedef enum {
@@ -96,6 +99,15 @@ typedef struct {
     const double *g64_in;    /*   are given (and warm_start = 1) they take the place of f, g          */
     float  *err_history;     /* optional device [err_history_len]: err_k stored at index k-1          */
     int32_t err_history_len;
+    int32_t cost_dtype;      /* storage of the dense cost matrix behind the `const float *C` argument:
+                                FS_COST_F32 (0, default), FS_COST_F16 (IEEE half precision) or FS_COST_BF16,
+                                n x m row-major entries of 2 bytes; the iteration then moves half the bytes.
+                                Every entry is widened exactly to fp32 and the arithmetic is unchanged, so the
+                                result is that of the solve on the rounded matrix.  Needs m % 8 == 0 and a
+                                16-byte aligned C (else FS_ERR_UNSUPPORTED); honoured by fs_sinkhorn_dense_ex,
+                                fs_sinkhorn_solve and fs_sinkhorn_annealed (dense); the batched solver and
+                                kernel_mode 3 take fp32 only; kernel_mode 2 then needs 2048 < m <= 16384 */
+    int32_t reserved0;       /* must be 0                                                              */
     int32_t time_kernel_every; /* blocking solves only: > 0 brackets the dominant kernel (row pass, fused
                                   pass or point-cloud LSE pass of the f-update) of every N-th iteration
                                   with HIP events on `stream`; read back with fs_last_kernel_timing()   */

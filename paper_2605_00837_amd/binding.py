@@ -42,6 +42,7 @@ class fs_options(ctypes.Structure):
                 ("f64_out", ctypes.c_void_p), ("g64_out", ctypes.c_void_p),
                 ("f64_in", ctypes.c_void_p), ("g64_in", ctypes.c_void_p),
                 ("err_history", ctypes.c_void_p), ("err_history_len", ctypes.c_int32),
+                ("cost_dtype", ctypes.c_int32), ("reserved0", ctypes.c_int32),
                 ("time_kernel_every", ctypes.c_int32)]
 
 
@@ -121,6 +122,21 @@ def _p(t: Optional[torch.Tensor], dtype=torch.float32):
     return ctypes.c_void_p(t.data_ptr())
 
 
+_COST_DTYPES = {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}     # FS_COST_F32 / _F16 / _BF16
+
+
+def _cost(C: Optional[torch.Tensor], opt_kw: dict):
+    """Pointer to a dense cost matrix; a 2-byte storage type is recorded in the options (cost_dtype)."""
+    if C is None:
+        return None
+    code = _COST_DTYPES.get(C.dtype)
+    if code is None:
+        raise TypeError(f"cost matrix must be float32, float16 or bfloat16, got {C.dtype}")
+    if code:
+        opt_kw["cost_dtype"] = code
+    return _p(C, C.dtype)
+
+
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -141,8 +157,9 @@ def _shape(C, X, Y, a, b):
 
 def make_options(check_every=0, warm_start=False, kernel_mode=0, use_graph=0, skip_final_err=False,
                  fused_variant=0, f64_out=None, g64_out=None, f64_in=None, g64_in=None, err_history=None,
-                 time_kernel_every=0):
+                 time_kernel_every=0, cost_dtype=0):
     o = fs_options()
+    o.cost_dtype = int(cost_dtype)
     o.check_every = int(check_every)
     o.warm_start = int(bool(warm_start))
     o.kernel_mode = int(kernel_mode)
@@ -215,9 +232,10 @@ def fs_sinkhorn_solve(a, b, eps, max_iter, tol, C=None, X=None, Y=None, f=None, 
         f64 = torch.empty(n, dtype=torch.float64, device=dev)
         g64 = torch.empty(m, dtype=torch.float64, device=dev)
         opt_kw.update(f64_out=f64, g64_out=g64)
+    Cp = _cost(C, opt_kw)
     o = make_options(**opt_kw)
     res = fs_result()
-    it = _check(_lib.fs_sinkhorn_solve(_p(C), _p(X), _p(Y), d, _p(a), _p(b), n, m, float(eps), int(max_iter),
+    it = _check(_lib.fs_sinkhorn_solve(Cp, _p(X), _p(Y), d, _p(a), _p(b), n, m, float(eps), int(max_iter),
                                        float(tol), _p(f), _p(g), _stream(), ctypes.byref(o), ctypes.byref(res)))
     out = dict(f=f, g=g, iters=it, converged=bool(res.converged), nonfinite=bool(res.nonfinite),
                marginal_err=float(res.marginal_err))
@@ -239,10 +257,11 @@ def fs_sinkhorn_annealed(a, b, eps, eps_start, decay, stage_iters, max_iter, tol
         f64 = torch.empty(n, dtype=torch.float64, device=dev)
         g64 = torch.empty(m, dtype=torch.float64, device=dev)
         opt_kw.update(f64_out=f64, g64_out=g64)
+    Cp = _cost(C, opt_kw)
     o = make_options(**opt_kw)
     res = fs_result()
     total = ctypes.c_int32(0)
-    it = _check(_lib.fs_sinkhorn_annealed(_p(C), _p(X), _p(Y), d, _p(a), _p(b), n, m, float(eps), float(eps_start),
+    it = _check(_lib.fs_sinkhorn_annealed(Cp, _p(X), _p(Y), d, _p(a), _p(b), n, m, float(eps), float(eps_start),
                                           float(decay), int(stage_iters), int(max_iter), float(tol), _p(f), _p(g),
                                           _stream(), ctypes.byref(o), ctypes.byref(res), ctypes.byref(total)))
     out = dict(f=f, g=g, iters=it, total_iters=int(total.value), converged=bool(res.converged),
@@ -279,9 +298,10 @@ def _ex(fn_dense: bool, C, X, Y, a, b, eps, max_iter, tol, f, g, workspace, opt_
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     res = torch.zeros(16, dtype=torch.uint8, device=dev)
+    Cp = _cost(C, opt_kw)
     o = make_options(**opt_kw)
     if fn_dense:
-        st = _lib.fs_sinkhorn_dense_ex(_p(C), _p(a), _p(b), n, m, float(eps), int(max_iter), float(tol), _p(f),
+        st = _lib.fs_sinkhorn_dense_ex(Cp, _p(a), _p(b), n, m, float(eps), int(max_iter), float(tol), _p(f),
                                        _p(g), _stream(), ctypes.byref(o), _p(workspace, torch.uint8),
                                        workspace.numel(), _p(res, torch.uint8))
     else:

@@ -176,13 +176,14 @@ struct Solve {
     }
     // kind of an iteration of the dense solver: the exact streaming kernels, or a fused kernel
     enum Kind { STREAM = 1, FUSED = 2 };
-    bool fused_is_fp32_cols() const { return mode == 2 && dense_fused_predicts(pr.m, opt.fused_variant); }
+    bool fused_is_fp32_cols() const { return mode == 2 && dense_fused_predicts(pr.m, opt.fused_variant, opt.cost_dtype); }
     DenseArgs dense(Kind kind) const {
         DenseArgs a;
         a.C = pr.C;
+        a.c_dtype = opt.cost_dtype;
         a.p = pots;
         a.colpart = (double *)(ws + L.o_part);
-        if (kind == FUSED) { a.P = dense_fused_grid(pr.n, pr.m, opt.fused_variant); a.rows_per_panel = 0; }
+        if (kind == FUSED) { a.P = dense_fused_grid(pr.n, pr.m, opt.fused_variant, opt.cost_dtype); a.rows_per_panel = 0; }
         else { a.P = L.P_stream; a.rows_per_panel = L.rpp_stream; }
         return a;
     }
@@ -267,10 +268,11 @@ struct Solve {
             if (e == hipSuccess) e = launch_combine(st, combine_g(L.P_stream, (const double *)(ws + L.o_part), nullptr), c);
         } else if (mode == 2) {
             {
-            const int g = dense_fused_grid(pr.n, pr.m, opt.fused_variant);
+            const int g = dense_fused_grid(pr.n, pr.m, opt.fused_variant, opt.cost_dtype);
             CombineArgs ca = combine_g(g, (const double *)(ws + L.o_part), nullptr);
-            if (dense_fused_predicts(pr.m, opt.fused_variant)) {
+            if (dense_fused_predicts(pr.m, opt.fused_variant, opt.cost_dtype)) {
                 ca.repair_C = pr.C; ca.repair_U = pots.U; ca.repair_n = pr.n; ca.repair_ld = L.n_ld;
+                ca.repair_dtype = opt.cost_dtype;
                 ca.repair_s = pots.s;
             }
             e = launch_combine(st, ca, c);
@@ -359,12 +361,24 @@ fs_status setup(Solve &S, const Problem &pr, const fs_options *opts, float *f, f
     p.s = kLog2e / (double)pr.eps;
     S.host_flag = nullptr;
     S.warm_f = f; S.warm_g = g;
+    if (S.opt.cost_dtype < 0 || S.opt.cost_dtype > 2) { set_err("cost_dtype must be FS_COST_F32, FS_COST_F16 or FS_COST_BF16"); return FS_ERR_INVALID_ARG; }
+    if (S.opt.cost_dtype != 0) {
+        if (!pr.C) { set_err("cost_dtype applies to a dense cost matrix only"); return FS_ERR_INVALID_ARG; }
+        if (pr.m % 8 != 0 || (reinterpret_cast<uintptr_t>(pr.C) & 15u)) {
+            set_err("2-byte costs need m %% 8 == 0 (got %d) and a 16-byte aligned C", pr.m);
+            return FS_ERR_UNSUPPORTED;
+        }
+    }
     if (pr.C) {
-        const bool fused_ok = dense_fused_supported(pr.n, pr.m, pr.C);
-        if (S.opt.kernel_mode == 2 && !fused_ok) { set_err("fused kernel does not support m = %d (needs m <= 16384, and m %% 4 == 0 when m <= 1024)", pr.m); return FS_ERR_UNSUPPORTED; }
+        const bool fused_ok = dense_fused_supported(pr.n, pr.m, pr.C, S.opt.cost_dtype);
+        if (S.opt.kernel_mode == 2 && !fused_ok) {
+            if (S.opt.cost_dtype != 0) set_err("fused kernel for 2-byte costs does not support m = %d (needs 2048 < m <= 16384)", pr.m);
+            else set_err("fused kernel does not support m = %d (needs m <= 16384, and m %% 4 == 0 when m <= 1024)", pr.m);
+            return FS_ERR_UNSUPPORTED;
+        }
         if (S.opt.kernel_mode < 0 || S.opt.kernel_mode > 2) { set_err("kernel_mode must be 0, 1, 2 or 3"); return FS_ERR_INVALID_ARG; }
         S.mode = S.opt.kernel_mode == 0 ? (fused_ok ? 2 : 1) : S.opt.kernel_mode;
-        if (S.mode == 2 && dense_fused_grid(pr.n, pr.m, S.opt.fused_variant) == 0) S.opt.fused_variant = 0;
+        if (S.mode == 2 && dense_fused_grid(pr.n, pr.m, S.opt.fused_variant, S.opt.cost_dtype) == 0) S.opt.fused_variant = 0;
     } else {
         S.mode = 3;
     }
@@ -527,9 +541,9 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
 // Small dense problems run whole inside one single-workgroup kernel (fs_small.hip).
 bool small_path(const Problem &pr, const fs_options *opts, fs_status *err) {
     const int km = opts ? opts->kernel_mode : 0;
-    const bool fits = pr.C && pr.n <= kSmallMax && pr.m <= kSmallMax;
+    const bool fits = pr.C && pr.n <= kSmallMax && pr.m <= kSmallMax && !(opts && opts->cost_dtype != 0);
     if (km == 3 && !fits) {
-        set_err("kernel_mode 3 needs a dense problem with n, m <= %d", kSmallMax);
+        set_err("kernel_mode 3 needs a dense fp32 cost matrix with n, m <= %d", kSmallMax);
         *err = FS_ERR_UNSUPPORTED;
         return false;
     }
@@ -847,6 +861,7 @@ fs_status fs_sinkhorn_dense_batched(const float *C, const float *a, const float 
         return FS_ERR_UNSUPPORTED;
     }
     if (opts && opts->kernel_mode != 0 && opts->kernel_mode != 3) { set_err("batched solves have one kernel (kernel_mode 0 or 3)"); return FS_ERR_INVALID_ARG; }
+    if (opts && opts->cost_dtype != 0) { set_err("batched solves take an fp32 cost matrix"); return FS_ERR_UNSUPPORTED; }
     SmallArgs A;
     v = small_args(pr, batch, opts, f, g, &A);
     if (v != FS_OK) return v;

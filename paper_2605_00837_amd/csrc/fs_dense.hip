@@ -42,8 +42,26 @@ struct VecLoad<1> {
     static __device__ __forceinline__ void ld(const float *p, float (&o)[1], int) { o[0] = *p; }
 };
 
+// VEC adjacent costs starting at entry `idx` of C, as fp32: 4 fp32 entries, or 8 entries stored in
+// 2 bytes each (16-byte aligned: such matrices have m % 8 == 0).
+template <int VEC, int DT>
+__device__ __forceinline__ void load_costs(const float *C, size_t idx, float (&o)[VEC], int valid) {
+    if constexpr (DT == 0) {
+        VecLoad<VEC>::ld(C + idx, o, valid);
+    } else {
+        static_assert(VEC == 8, "2-byte costs are read 8 at a time");
+        const uint4 raw = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned short *>(C) + idx);
+        const unsigned w4[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            o[2 * h] = cost_from_bits<DT>(w4[h] & 0xffffu);
+            o[2 * h + 1] = cost_from_bits<DT>(w4[h] >> 16);
+        }
+    }
+}
+
 // ---------------------------------------------------------------- row pass (streaming)
-template <int VEC>
+template <int VEC, int DT = 0>
 __global__ __launch_bounds__(kStreamT) void k_row_stream(DenseArgs A, Ctl c) {
     __shared__ double sM[kRowsPerWG][kStreamT / 64];
     __shared__ float sS[kRowsPerWG][kStreamT / 64];
@@ -70,7 +88,7 @@ __global__ __launch_bounds__(kStreamT) void k_row_stream(DenseArgs A, Ctl c) {
             const int i = i0 + r;
             if (i < p.n) {
                 float cv[VEC];
-                VecLoad<VEC>::ld(A.C + (size_t)i * p.m + col, cv, valid);
+                load_costs<VEC, DT>(A.C, (size_t)i * p.m + col, cv, valid);
                 double x[VEC];
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) x[e] = fma(ns, (double)cv[e], v[e]);
@@ -99,7 +117,7 @@ __global__ __launch_bounds__(kStreamT) void k_row_stream(DenseArgs A, Ctl c) {
 }
 
 // ---------------------------------------------------------------- column pass (streaming)
-template <int VEC>
+template <int VEC, int DT = 0>
 __global__ __launch_bounds__(kStreamT) void k_col_stream(DenseArgs A, Ctl c) {
     int k;
     if (!launch_active(c, k)) return;
@@ -120,7 +138,7 @@ __global__ __launch_bounds__(kStreamT) void k_col_stream(DenseArgs A, Ctl c) {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e].init();
 
-    constexpr int RC = 4;                         // rows folded per rescale
+    constexpr int RC = VEC == 8 ? 2 : 4;          // rows folded per rescale
     for (int i = r0; i < r1; i += RC) {
         double x[VEC][RC];
 #pragma unroll
@@ -128,7 +146,7 @@ __global__ __launch_bounds__(kStreamT) void k_col_stream(DenseArgs A, Ctl c) {
             const int ii = i + q;
             if (ii < r1) {
                 float cv[VEC];
-                VecLoad<VEC>::ld(A.C + (size_t)ii * p.m + j0, cv, valid);
+                load_costs<VEC, DT>(A.C, (size_t)ii * p.m + j0, cv, valid);
                 const double u = U[ii];
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) x[e][q] = fma(ns, (double)cv[e], u);
@@ -164,13 +182,19 @@ void dense_stream_plan(int n, int m, int *P, int *rows_per_panel) {
 
 hipError_t launch_dense_row(hipStream_t st, const DenseArgs &a, const Ctl &c) {
     const dim3 grid((a.p.n + kRowsPerWG - 1) / kRowsPerWG);
-    if (vec4_ok(a)) hipLaunchKernelGGL(k_row_stream<4>, grid, dim3(kStreamT), 0, st, a, c);
+    if (a.c_dtype == 1) hipLaunchKernelGGL((k_row_stream<8, 1>), grid, dim3(kStreamT), 0, st, a, c);
+    else if (a.c_dtype == 2) hipLaunchKernelGGL((k_row_stream<8, 2>), grid, dim3(kStreamT), 0, st, a, c);
+    else if (vec4_ok(a)) hipLaunchKernelGGL(k_row_stream<4>, grid, dim3(kStreamT), 0, st, a, c);
     else hipLaunchKernelGGL(k_row_stream<1>, grid, dim3(kStreamT), 0, st, a, c);
     return hipGetLastError();
 }
 
 hipError_t launch_dense_col(hipStream_t st, const DenseArgs &a, const Ctl &c) {
-    if (vec4_ok(a)) {
+    if (a.c_dtype != 0) {
+        const dim3 grid((a.p.m + kStreamT * 8 - 1) / (kStreamT * 8), a.P);
+        if (a.c_dtype == 1) hipLaunchKernelGGL((k_col_stream<8, 1>), grid, dim3(kStreamT), 0, st, a, c);
+        else hipLaunchKernelGGL((k_col_stream<8, 2>), grid, dim3(kStreamT), 0, st, a, c);
+    } else if (vec4_ok(a)) {
         const dim3 grid((a.p.m + kStreamT * 4 - 1) / (kStreamT * 4), a.P);
         hipLaunchKernelGGL(k_col_stream<4>, grid, dim3(kStreamT), 0, st, a, c);
     } else {
@@ -369,9 +393,11 @@ constexpr int waitcnt_vm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }
 // The per-row scalars of a panel (old F, log2 a, a) travel the same way as the panel itself:
 // lanes 0..R-1 of every wave fetch them with dword-sized HBM -> LDS loads next to the panel's
 // loads, so nothing that is prefetched occupies a register while it is in flight.
-template <int Q, int R, bool FULLW>
+template <int Q, int R, bool FULLW, int DT = 0>
 __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     constexpr int T = 1024, NW = 16;
+    constexpr int EPL = DT == 0 ? 4 : 8;       // cost entries per 16-byte chunk: fp32, or fp16 / bf16 storage
+    constexpr int ES = 16 / EPL;               // bytes per stored cost entry
     static_assert(R * NW <= 64, "one wave merges all (row, wave) partials in one shot");
     static_assert(5 * R <= 16, "scalar staging holds 16 dwords per wave");
     constexpr int NDMA = R * Q + 5;            // loads per panel and wave (FULLW)
@@ -396,16 +422,25 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     const int m = p.m, n = p.n;
     const int rr = lane / NW;                  // the panel row this lane serves in the merge
     const int rc = rr < R ? rr : R - 1;
-    auto colok = [&](int q) { return FULLW || ((q * T + tid) * 4) < m; };
+    auto colok = [&](int q) { return FULLW || ((q * T + tid) * EPL) < m; };
     // Staged costs of group q: the 16 bytes of a lane that owns the last columns of a row run on into the
     // next row (or past the panel, where the load returns 0); those entries are zeroed here and removed
     // by V = -inf, so that nothing foreign (a NaN of the next row, say) enters this row's sum.
-    auto unpack = [&](const float4 &c4, int q, float (&o)[4]) {
-        o[0] = c4.x; o[1] = c4.y; o[2] = c4.z; o[3] = c4.w;
-        if (!FULLW) {
-            const int col = (q * T + tid) * 4;
+    auto unpack = [&](const float4 &c4, int q, float (&o)[EPL]) {
+        if constexpr (DT == 0) {
+            o[0] = c4.x; o[1] = c4.y; o[2] = c4.z; o[3] = c4.w;
+        } else {
+            const unsigned w4[4] = {__float_as_uint(c4.x), __float_as_uint(c4.y), __float_as_uint(c4.z), __float_as_uint(c4.w)};
 #pragma unroll
-            for (int e = 1; e < 4; ++e)
+            for (int h = 0; h < 4; ++h) {
+                o[2 * h] = cost_from_bits<DT>(w4[h] & 0xffffu);
+                o[2 * h + 1] = cost_from_bits<DT>(w4[h] >> 16);
+            }
+        }
+        if (!FULLW) {
+            const int col = (q * T + tid) * EPL;
+#pragma unroll
+            for (int e = 1; e < EPL; ++e)
                 if (col + e >= m) o[e] = 0.0f;
         }
     };
@@ -445,14 +480,14 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, &scal[buf][wave][4 * R], 4, lane * 4, i0 * 4, 0, 0);
         }
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(A.C + (size_t)i0 * m), 0, rows * m * 4, 0x00020000);
+            (void *)((const char *)A.C + (size_t)i0 * m * ES), 0, rows * m * ES, 0x00020000);
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int q = 0; q < Q; ++q)
                 if (colok(q))
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, &stage[buf][wave][r][q][0], 16,
-                                                             tid * 16, (r * m + q * T * 4) * 4, 0, 0);
+                                                             tid * 16, (r * m + q * T * EPL) * ES, 0, 0);
     };
     // old F of the rows of a panel, from the buffer the counter names
     auto issue_F = [&](const __amdgpu_buffer_rsrc_t &rsF, int i0, int *dst) {
@@ -464,15 +499,15 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     static_assert(2 * R <= 4, "scalF0 holds two dwords per row and parity");
 
     // both copies of V while the counter is on its way (narrow shapes only: 16 Q registers each)
-    constexpr bool kBothV = Q <= 2;
+    constexpr bool kBothV = Q * EPL <= 8;
     constexpr int QV = kBothV ? Q : 1;
-    double v0[QV][4], v1[QV][4];
+    double v0[QV][EPL], v1[QV][EPL];
     if constexpr (kBothV) {
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            const int col = (q * T + tid) * 4;
+            const int col = (q * T + tid) * EPL;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < EPL; ++e) {
                 const bool ok = FULLW || col + e < m;          // m need not be a multiple of 4
                 v0[q][e] = ok ? p.V[col + e] : -__builtin_huge_val();
                 v1[q][e] = ok ? p.V[(size_t)p.m_ld + col + e] : -__builtin_huge_val();
@@ -504,21 +539,21 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
         issue_F(rsF, i0, &scal[buf][wave][0]);
         issue_data(i0, buf);
     };
-    double v[Q][4];
+    double v[Q][EPL];
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
-        const int col = (q * T + tid) * 4;
+        const int col = (q * T + tid) * EPL;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
+        for (int e = 0; e < EPL; ++e) {
             if constexpr (kBothV) v[q][e] = cur ? v1[q][e] : v0[q][e];
             else v[q][e] = (FULLW || col + e < m) ? p.V[(size_t)cur * p.m_ld + col + e] : -__builtin_huge_val();
         }
     }
-    float cS[Q][4];                            // column sums of the plan entries
+    float cS[Q][EPL];                            // column sums of the plan entries
 #pragma unroll
     for (int q = 0; q < Q; ++q)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) cS[q][e] = 0.0f;
+        for (int e = 0; e < EPL; ++e) cS[q][e] = 0.0f;
 
     if (FULLW && mine > 1) {
         asm volatile("" ::: "memory");
@@ -559,17 +594,17 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
             }
         };
         // ---- row phase, optimistic: e = 2^(x - rho_r), summed
-        float ev[R][Q][4];
+        float ev[R][Q][EPL];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             float acc = 0.0f;
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
                 const float4 c4 = stage[buf][wave][r][q][lane];
-                float cvv[4];
+                float cvv[EPL];
                 unpack(c4, q, cvv);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
+                for (int e = 0; e < EPL; ++e) {
                     ev[r][q][e] = fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - rho[r]));
                     acc += ev[r][q][e];
                 }
@@ -595,12 +630,12 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
                     const float4 c4 = stage[buf][wave][r][q][lane];
-                    float cvv[4];
+                    float cvv[EPL];
                 unpack(c4, q, cvv);
-                    double x[4];
+                    double x[EPL];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) x[e] = fma(ns, (double)cvv[e], v[q][e]);
-                    rs.template add<4>(x);
+                    for (int e = 0; e < EPL; ++e) x[e] = fma(ns, (double)cvv[e], v[q][e]);
+                    rs.template add<EPL>(x);
                 }
                 rs.wave_reduce();
                 if (lane == 0) { sM[buf][r][wave] = rs.M; sS[buf][r][wave] = rs.s; }
@@ -627,10 +662,10 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
 #pragma unroll
                     for (int q = 0; q < Q; ++q) {
                         const float4 c4 = stage[buf][wave][r][q][lane];
-                        float cvv[4];
+                        float cvv[EPL];
                 unpack(c4, q, cvv);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
+                        for (int e = 0; e < EPL; ++e)
                             ev[r][q][e] = fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - Fn));
                     }
                 }
@@ -650,20 +685,23 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
 #pragma unroll
                 for (int q = 0; q < Q; ++q)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) cS[q][e] = fmaf(ev[r][q][e], alpha, cS[q][e]);
+                    for (int e = 0; e < EPL; ++e) cS[q][e] = fmaf(ev[r][q][e], alpha, cS[q][e]);
             }
         }
     }
     if (col_phase) {
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            const int col = (q * T + tid) * 4;
+            const int col = (q * T + tid) * EPL;
             if (colok(q)) {
                 // The partial of this workgroup is the plain fp32 sum T_j of its plan entries: all
                 // workgroups share the reference V_j, so the combine kernel only has to add them up
                 // (G_j = log2 sum_p T_j - V_j).
                 float *row = reinterpret_cast<float *>(A.colpart) + (size_t)blockIdx.x * p.m_ld + col;
-                *reinterpret_cast<float4 *>(row) = make_float4(cS[q][0], cS[q][1], cS[q][2], cS[q][3]);
+#pragma unroll
+                for (int h = 0; h < EPL / 4; ++h)
+                    reinterpret_cast<float4 *>(row)[h] =
+                        make_float4(cS[q][4 * h], cS[q][4 * h + 1], cS[q][4 * h + 2], cS[q][4 * h + 3]);
             }
         }
     }
@@ -673,8 +711,14 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
 struct FusedShape { int T, Q, R; };
 
 // Shapes held in registers without spilling: 4*Q*T columns, R rows per panel.
-static bool fused_shape(int m, int variant, FusedShape *fsh) {
+static bool fused_shape(int m, int variant, int c_dtype, FusedShape *fsh) {
     if (variant >= 100) variant -= 100;
+    if (c_dtype != 0) {
+        // 2-byte costs: LDS-prefetch kernels only, 8 columns per lane and group, rows of whole 16-byte chunks
+        if (m % 8 != 0 || m <= 2048 || m > 16384) return false;
+        *fsh = {1024, m <= 8192 ? 1 : 2, m <= 8192 ? 302 : 301};
+        return true;
+    }
     // The LDS-prefetch kernels take any m (a row may start at any 4-byte boundary; columns past m are
     // masked by V = -inf); the register-panel kernels need whole groups of 4 columns.
     if (m % 4 != 0) {
@@ -703,18 +747,19 @@ static bool fused_shape(int m, int variant, FusedShape *fsh) {
     return false;
 }
 
-bool dense_fused_supported(int n, int m, const void *C) {
+bool dense_fused_supported(int n, int m, const void *C, int c_dtype) {
     FusedShape s;
     (void)n;
-    return fused_shape(m, 0, &s) && ((reinterpret_cast<uintptr_t>(C) & 3u) == 0);
+    const uintptr_t mask = c_dtype != 0 ? 15u : 3u;
+    return fused_shape(m, 0, c_dtype, &s) && ((reinterpret_cast<uintptr_t>(C) & mask) == 0);
 }
 
 void dense_fused_plan(int n, int m, int *P) {
     // the largest grid any variant uses: one panel set per resident workgroup
     FusedShape s{256, 1, 4};
     int best = 1;
-    for (int variant = 0; variant < 6; ++variant) {
-        if (!fused_shape(m, variant, &s)) continue;
+    for (int variant = 0; variant < 8; ++variant) {        // 6, 7: the shapes for 2-byte costs
+        if (!fused_shape(m, variant < 6 ? variant : 0, variant < 6 ? 0 : variant - 5, &s)) continue;
         const int npanels = (n + (s.R % 100) - 1) / (s.R % 100);
         const int resident = s.T == 256 ? 1024 : 256;      // workgroups the 256 CUs hold at once
         const int p = npanels < resident ? npanels : resident;
@@ -725,7 +770,7 @@ void dense_fused_plan(int n, int m, int *P) {
 
 hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, int variant) {
     FusedShape s;
-    if (!fused_shape(a.p.m, variant, &s)) return hipErrorInvalidValue;
+    if (!fused_shape(a.p.m, variant, a.c_dtype, &s)) return hipErrorInvalidValue;
     const int npanels = (a.p.n + (s.R % 100) - 1) / (s.R % 100);
     const int resident = s.T == 256 ? 1024 : 256;
     int g = npanels < resident ? npanels : resident;
@@ -733,6 +778,21 @@ hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, 
     DenseArgs b = a;
     b.P = g;
     const dim3 grid(g);
+    if (a.c_dtype != 0) {
+        const bool full = a.p.m == s.Q * 8192;
+        const int key = (a.c_dtype == 1 ? 0 : 4) + (s.Q == 1 ? 0 : 2) + (full ? 0 : 1);
+        switch (key) {
+        case 0: hipLaunchKernelGGL((k_fused_pf<1, 2, true, 1>), grid, dim3(1024), 0, st, b, c); break;
+        case 1: hipLaunchKernelGGL((k_fused_pf<1, 2, false, 1>), grid, dim3(1024), 0, st, b, c); break;
+        case 2: hipLaunchKernelGGL((k_fused_pf<2, 1, true, 1>), grid, dim3(1024), 0, st, b, c); break;
+        case 3: hipLaunchKernelGGL((k_fused_pf<2, 1, false, 1>), grid, dim3(1024), 0, st, b, c); break;
+        case 4: hipLaunchKernelGGL((k_fused_pf<1, 2, true, 2>), grid, dim3(1024), 0, st, b, c); break;
+        case 5: hipLaunchKernelGGL((k_fused_pf<1, 2, false, 2>), grid, dim3(1024), 0, st, b, c); break;
+        case 6: hipLaunchKernelGGL((k_fused_pf<2, 1, true, 2>), grid, dim3(1024), 0, st, b, c); break;
+        default: hipLaunchKernelGGL((k_fused_pf<2, 1, false, 2>), grid, dim3(1024), 0, st, b, c); break;
+        }
+        return hipGetLastError();
+    }
     if (s.R == 301 && s.Q == 3 && a.p.m == 12288) hipLaunchKernelGGL((k_fused_pf<3, 1, true>), grid, dim3(1024), 0, st, b, c);
     else if (s.R == 301 && s.Q == 3) hipLaunchKernelGGL((k_fused_pf<3, 1, false>), grid, dim3(1024), 0, st, b, c);
     else if (s.R == 301 && a.p.m == 16384) hipLaunchKernelGGL((k_fused_pf<4, 1, true>), grid, dim3(1024), 0, st, b, c);
@@ -750,15 +810,15 @@ hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, 
     return hipGetLastError();
 }
 
-bool dense_fused_predicts(int m, int variant) {
+bool dense_fused_predicts(int m, int variant, int c_dtype) {
     FusedShape s;
-    return fused_shape(m, variant, &s) && s.R > 300;
+    return fused_shape(m, variant, c_dtype, &s) && s.R > 300;
 }
 
 // number of column-partial sets the fused launch of this shape writes
-int dense_fused_grid(int n, int m, int variant) {
+int dense_fused_grid(int n, int m, int variant, int c_dtype) {
     FusedShape s;
-    if (!fused_shape(m, variant, &s)) return 0;
+    if (!fused_shape(m, variant, c_dtype, &s)) return 0;
     const int npanels = (n + (s.R % 100) - 1) / (s.R % 100);
     const int resident = s.T == 256 ? 1024 : 256;
     return npanels < resident ? npanels : resident;

@@ -104,6 +104,23 @@ __device__ __forceinline__ double log2_weight(float w) {
 
 // Four adjacent fp32 values at any 4-byte boundary (rows of a matrix whose width is not a multiple of
 // 4 start anywhere): one 16-byte access, the hardware's unaligned access mode does the rest.
+// A cost entry stored in 2 bytes, from its bits: DT = 1 IEEE half precision, DT = 2 bfloat16.
+template <int DT>
+__device__ __forceinline__ float cost_from_bits(unsigned bits16) {
+    if constexpr (DT == 1) {
+        return (float)__builtin_bit_cast(_Float16, (unsigned short)bits16);
+    } else {
+        return __uint_as_float(bits16 << 16);
+    }
+}
+
+// Entry `idx` of a cost matrix stored as fp32 (dtype 0), fp16 (1) or bfloat16 (2).
+__device__ __forceinline__ float cost_entry(const float *C, int dtype, size_t idx) {
+    if (dtype == 0) return C[idx];
+    const unsigned bits = reinterpret_cast<const unsigned short *>(C)[idx];
+    return dtype == 1 ? cost_from_bits<1>(bits) : cost_from_bits<2>(bits);
+}
+
 typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
 // ---------------------------------------------------------------- DPP / swizzle moves

@@ -19,7 +19,8 @@ struct Pots {
 };
 
 struct DenseArgs {
-    const float *C;       // n x m row-major
+    const float *C;       // n x m row-major; fp32, or (c_dtype 1, 2) entries of 2 bytes: fp16, bfloat16
+    int32_t c_dtype;
     Pots p;
     double *colpart;      // [P][m_ld] per-panel partial column LSE values
     int32_t P;            // number of row panels of the column pass
@@ -63,7 +64,7 @@ struct CombineArgs {
     // exactly from column j of C and the new U.
     const float *repair_C;    // n x len row-major, or null
     const double *repair_U;   // [2][repair_ld]
-    int32_t repair_n, repair_ld;
+    int32_t repair_n, repair_ld, repair_dtype;   // repair_dtype: storage of repair_C as in DenseArgs::c_dtype
     double repair_s;
     // Repair of entries whose partials come from the optimistic point-cloud pass (only looked at while
     // the pace hint says FAST): when pr_rows is non-null, a combined value outside
@@ -93,11 +94,11 @@ hipError_t launch_dense_row(hipStream_t st, const DenseArgs &a, const Ctl &c);
 hipError_t launch_dense_col(hipStream_t st, const DenseArgs &a, const Ctl &c);
 
 // Dense fused row-panel kernel (m limited by what a workgroup holds in registers).
-bool dense_fused_supported(int n, int m, const void *C);
+bool dense_fused_supported(int n, int m, const void *C, int c_dtype);
 void dense_fused_plan(int n, int m, int *P);
 hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, int variant);
-int dense_fused_grid(int n, int m, int variant);
-bool dense_fused_predicts(int m, int variant);   // this shape / variant uses predicted column references
+int dense_fused_grid(int n, int m, int variant, int c_dtype);
+bool dense_fused_predicts(int m, int variant, int c_dtype);   // this shape / variant uses predicted column references
 
 // Point-cloud kernels.
 struct PointsArgs {

@@ -364,7 +364,7 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
             Lse ex; ex.init();
             if (fast_mode) {
                 for (int i = t; i < A.repair_n; i += kCombT) {
-                    double y[1] = {fma(-A.repair_s, (double)A.repair_C[(size_t)i * A.len + jj], U[i])};
+                    double y[1] = {fma(-A.repair_s, (double)cost_entry(A.repair_C, A.repair_dtype, (size_t)i * A.len + jj), U[i])};
                     ex.add<1>(y);
                 }
             } else {

@@ -14,7 +14,7 @@ import time
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--reps", type=int, default=5)
-    ap.add_argument("--only", default="c1,c2,c2_fixed,c2_check1,c3,c4,c5")
+    ap.add_argument("--only", default="c1,c2,c2_fixed,c2_check1,c2_half,c3,c4,c5")
     args = ap.parse_args()
     import torch
     from . import binding as fs, workloads as W
@@ -22,8 +22,10 @@ def main():
     def dev(x):
         return None if x is None else torch.from_numpy(x).cuda()
 
-    def timed(label, w, eps, max_iter, tol, dense=True, **kw):
+    def timed(label, w, eps, max_iter, tol, dense=True, cost_dtype=None, **kw):
         geo = dict(C=dev(w.C)) if dense else dict(X=dev(w.X), Y=dev(w.Y))
+        if cost_dtype is not None:                   # the same matrix stored in 2 bytes per entry
+            geo["C"] = geo["C"].to(cost_dtype)
         a, b = dev(w.a), dev(w.b)
         fs.fs_sinkhorn_solve(a, b, eps, min(max_iter, 20), 0.0, **geo, **kw)
         torch.cuda.synchronize()
@@ -45,7 +47,7 @@ def main():
         w = W.c1_small_dense()
         timed("c1 dense 256x256 eps 0.05, 200 fixed", w, w.eps, 200, 0.0)
         timed("c1, single-workgroup kernel", w, w.eps, 200, 0.0, kernel_mode=3)
-    if only & {"c2", "c2_fixed", "c2_check1"}:
+    if only & {"c2", "c2_fixed", "c2_check1", "c2_half"}:
         w = W.c2_dense_gauss()
         if "c2" in only:
             timed("c2 dense 8192x8192 eps 1e-2, tol 1e-6, check every 10", w, w.eps, w.max_iter, w.tol, check_every=10)
@@ -53,6 +55,9 @@ def main():
             timed("c2, check every iteration", w, w.eps, w.max_iter, w.tol, check_every=1)
         if "c2_fixed" in only:
             timed("c2, 1000 fixed iterations", w, w.eps, 1000, 0.0)
+        if "c2_half" in only:
+            timed("c2 with C stored as fp16, 1000 fixed iterations", w, w.eps, 1000, 0.0, cost_dtype=torch.float16)
+            timed("c2 with C stored as bfloat16, 1000 fixed iterations", w, w.eps, 1000, 0.0, cost_dtype=torch.bfloat16)
     if "c3" in only:
         w = W.c3_small_eps()
         for eps in w.eps_list:

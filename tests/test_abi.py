@@ -57,7 +57,7 @@ def test_binding_mirrors_the_header():
     importing the binding needs torch with a GPU only at call time, so importing is fine here too)."""
     from paper_2605_00837_amd import binding
     assert ctypes.sizeof(binding.fs_result) == 16
-    assert ctypes.sizeof(binding.fs_options) == 24 + 5 * 8 + 8
+    assert ctypes.sizeof(binding.fs_options) == 24 + 5 * 8 + 16
     for name in declared_symbols():
         assert name in binding.EXPORTED and hasattr(binding, name), name
 
@@ -120,3 +120,16 @@ def test_header_is_plain_c(tmp_path):
                    "  return (int)(sizeof(fs_options) + sizeof(fs_result)) * 0 + FS_DIAG_LEN * 0; }\n")
     inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
     subprocess.run([gcc, "-std=c11", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    # the ctypes mirror of fs_options has the C compiler's layout, field by field
+    from paper_2605_00837_amd import binding
+    names = [f[0] for f in binding.fs_options._fields_]
+    lay = tmp_path / "layout.c"
+    lay.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "fastsinkhorn.h"\n'
+                   'int main(void) { printf("%zu", sizeof(fs_options));\n' +
+                   "".join(f'  printf(" %zu", offsetof(fs_options, {nm}));\n' for nm in names) +
+                   "  return 0; }\n")
+    exe = tmp_path / "layout"
+    subprocess.run([gcc, "-std=c11", "-I", inc, str(lay), "-o", str(exe)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got[0] == ctypes.sizeof(binding.fs_options)
+    assert got[1:] == [getattr(binding.fs_options, nm).offset for nm in names]

@@ -134,6 +134,71 @@ def test_fused_column_repair_path(fs, oracle):
         assert e64 < TOL_F64 and e32 < TOL_F32, (n, m, e64, e32)
 
 
+# ------------------------------------------------------------------ cost matrix stored in 2 bytes per entry
+def _rounded_cost(C, dtype_name):
+    """The fp32 values of C after rounding to fp16 / bfloat16 (what the oracle is given), and the device
+    tensor in that storage type.  The rounding is torch's conversion, on the CPU."""
+    import torch
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16}[dtype_name]
+    t16 = torch.from_numpy(np.ascontiguousarray(C)).to(tdt)
+    return t16.to(torch.float32).numpy(), t16.cuda()
+
+
+@pytest.mark.parametrize("dtype_name", ["f16", "bf16"])
+@pytest.mark.parametrize("n,m,mode,variant", [
+    (300, 520, 1, 0), (70, 8, 1, 0), (3, 2040, 0, 0),          # streaming kernels (automatic up to m = 2048)
+    (130, 4096, 2, 0), (90, 8192, 2, 0), (45, 6008, 2, 0),     # prefetch kernel, 8 columns per lane
+    (33, 10000, 2, 0), (21, 16384, 2, 0),                      # two groups of 8 columns per lane
+    (70, 8192, 2, 100), (35, 10000, 2, 100), (64, 3000, 2, 100),   # optimistic from the start: repair from 2-byte C
+    (40, 20000, 0, 0)])                                        # wider than the fused kernels: streaming
+def test_dense_solve_half_precision_cost(fs, oracle, dtype_name, n, m, mode, variant):
+    """C stored as fp16 / bfloat16: the solve must be the fp32 solve on the rounded matrix (the oracle gets
+    the rounded values), to the same tolerances as every other dense path."""
+    w = W.random_dense(n, m, seed=3300 + n + m, cmax=2.0, eps=0.03)
+    C32, C16 = _rounded_cost(w.C, dtype_name)
+    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, 25, 0.0, C=C16, want_f64=True, kernel_mode=mode,
+                             fused_variant=variant)
+    ref = oracle.solve(w.a, w.b, w.eps, 25, C=C32)
+    assert r["iters"] == 25 and not r["nonfinite"]
+    e64 = max(pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps), pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps))
+    e32 = max(pot_err(r["f"].cpu().numpy(), ref["f"], w.eps), pot_err(r["g"].cpu().numpy(), ref["g"], w.eps))
+    assert e64 < TOL_F64 and e32 < TOL_F32, (e64, e32)
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=C32))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+    # and it is NOT the solve on the unrounded matrix: the result is closer to the oracle on the rounded one
+    ref_full = oracle.solve(w.a, w.b, w.eps, 25, C=w.C)
+    assert pot_err(r["f64"].cpu().numpy(), ref_full["f"], w.eps) > 2 * e64
+
+
+def test_half_precision_cost_async_and_rejections(fs, oracle):
+    import torch
+    w = W.random_dense(60, 4096, seed=3401, cmax=2.0, eps=0.03)
+    C32, C16 = _rounded_cost(w.C, "f16")
+    h = fs.fs_sinkhorn_dense_ex(C16, dev(w.a), dev(w.b), w.eps, 15, 0.0)
+    res = h.result()
+    ref = oracle.solve(w.a, w.b, w.eps, 15, C=C32)
+    assert res["iters"] == 15
+    assert pot_err(h.f.cpu().numpy(), ref["f"], w.eps) < TOL_F32
+    # rows that are not whole 16-byte chunks, the single-workgroup and batched kernels, point clouds
+    a, b = dev(w.a), dev(np.full(4100, 1.0 / 4100, dtype=np.float32))
+    with pytest.raises(fs.FsError, match="m % 8"):
+        fs.fs_sinkhorn_solve(a, b, 0.1, 3, 0.0, C=torch.zeros(60, 4100, dtype=torch.float16, device="cuda"))
+    sm = torch.zeros(64, 64, dtype=torch.float16, device="cuda")
+    u = torch.full((64,), 1 / 64, device="cuda")
+    with pytest.raises(fs.FsError, match="fp32"):
+        fs.fs_sinkhorn_solve(u, u, 0.1, 3, 0.0, C=sm, kernel_mode=3)
+    r = fs.fs_sinkhorn_solve(u, u, 0.1, 3, 0.0, C=sm)                 # automatic: the multi-kernel path takes it
+    assert r["iters"] == 3 and not r["nonfinite"]
+    with pytest.raises(fs.FsError, match="dense cost matrix only"):
+        fs.fs_sinkhorn_solve(u, u, 0.1, 3, 0.0, X=torch.zeros(64, 2, device="cuda"),
+                             Y=torch.zeros(64, 2, device="cuda"), cost_dtype=1)
+    with pytest.raises(fs.FsError, match="fp32 cost"):
+        fs.fs_sinkhorn_dense_batched(sm.float()[None], u[None], u[None], 0.1, 3, 0.0, cost_dtype=1)
+    with pytest.raises(fs.FsError, match="2048 < m"):
+        fs.fs_sinkhorn_solve(u, torch.full((1024,), 1 / 1024, device="cuda"), 0.1, 3, 0.0,
+                             C=torch.zeros(64, 1024, dtype=torch.bfloat16, device="cuda"), kernel_mode=2)
+
+
 @pytest.mark.parametrize("n,m,mode", [(5000, 64, 0), (3000, 12, 1), (40, 20000, 0), (9, 16388, 0), (2, 70001, 1)])
 def test_dense_extreme_aspect_ratios(fs, oracle, n, m, mode):
     """Very tall (many rows of the error sum per workgroup of the combine) and very wide (beyond the
