@@ -60,6 +60,7 @@ typedef void *fs_stream;
 #define FS_COST_F16 1
 #define FS_COST_BF16 2
 #define FS_SMALL_MAX 256        /* largest n, m of the single-workgroup / batched kernel */
+#define FS_COOP_MAX 1024        /* largest n, m of the one-launch multi-workgroup kernel */
 
 typedef enum {
     FS_OK = 0,
@@ -86,11 +87,18 @@ typedef struct {
                                 kernel (dense, m <= 16384, and m % 4 == 0 when m <= 1024; else
                                 FS_ERR_UNSUPPORTED);
                                 3: the whole solve in one single-workgroup kernel (dense, n, m <=
-                                FS_SMALL_MAX, else FS_ERR_UNSUPPORTED; what 0 picks up to about 128 x 128) */
+                                FS_SMALL_MAX, else FS_ERR_UNSUPPORTED; what 0 picks up to about 128 x 128);
+                                4: the whole solve in one launch over up to 32 workgroups that hold C in
+                                registers and exchange column partials once per iteration (dense fp32, n, m <=
+                                FS_COOP_MAX, else FS_ERR_UNSUPPORTED; what 0 picks from there up to 2^18
+                                entries).  Its workgroups wait for one another with a bounded number of
+                                polls: should the device keep some of them from running for seconds, the
+                                solve gives up and reports NaN potentials with nonfinite = 1                */
     int32_t use_graph;       /* 0: automatic; 1: plain stream launches; 2: hipGraph iteration blocks  */
     int32_t skip_final_err;  /* 1: do not spend the one trailing pass that evaluates err after the
                                 last iteration when no stop fired (marginal_err is then NaN)          */
-    int32_t fused_variant;   /* tuning knob: 0 default; 1..5 alternative tilings of the dense fused kernel;
+    int32_t fused_variant;   /* tuning knob: 0 default; 1..5 alternative tilings of the dense fused kernel
+                                (kernel_mode 4: 1..3 = at most 16, 8, 4 workgroups);
                                 +100: take the optimistic (fp32-sum) kernels from the first iteration on,
                                 whatever the pace of the potentials (exercises the exact repair paths) */
     double *f64_out;         /* optional device [n]: f in double precision (NULL: not wanted)         */

@@ -21,6 +21,8 @@ namespace {
 
 using namespace fs;
 
+static_assert(kSmallMax == FS_SMALL_MAX && kCoopMax == FS_COOP_MAX, "the header states the kernels' limits");
+
 thread_local char g_err[512] = "";
 
 void set_err(const char *fmt, ...) {
@@ -52,6 +54,7 @@ struct Layout {
     int JSf, cpsf, JSg, cpsg;
     size_t o_state, o_F, o_U, o_G, o_V, o_la2, o_lb2, o_part, o_part2;
     size_t o_Xp, o_Xs, o_cx, o_Yp, o_Ys, o_cy;
+    size_t o_coop;         // scratch of the one-launch solver for mid-size dense problems (0: none)
     size_t total;
 };
 
@@ -75,6 +78,7 @@ Layout make_layout(int n, int m, int d) {
         const int Pmax = L.P_stream > L.P_fused ? L.P_stream : L.P_fused;
         L.o_part = take(sizeof(double) * (size_t)Pmax * L.m_ld);
         L.o_part2 = L.o_part;
+        if (coop_supported(n, m)) L.o_coop = take(coop_scratch_bytes());
     } else {
         points_plan(n, m, d, &L.JSf, &L.cpsf);
         points_plan(m, n, d, &L.JSg, &L.cpsg);
@@ -376,7 +380,7 @@ fs_status setup(Solve &S, const Problem &pr, const fs_options *opts, float *f, f
             else set_err("fused kernel does not support m = %d (needs m <= 16384, and m %% 4 == 0 when m <= 1024)", pr.m);
             return FS_ERR_UNSUPPORTED;
         }
-        if (S.opt.kernel_mode < 0 || S.opt.kernel_mode > 2) { set_err("kernel_mode must be 0, 1, 2 or 3"); return FS_ERR_INVALID_ARG; }
+        if (S.opt.kernel_mode < 0 || S.opt.kernel_mode > 2) { set_err("kernel_mode must be 0, 1, 2, 3 or 4"); return FS_ERR_INVALID_ARG; }
         S.mode = S.opt.kernel_mode == 0 ? (fused_ok ? 2 : 1) : S.opt.kernel_mode;
         if (S.mode == 2 && dense_fused_grid(pr.n, pr.m, S.opt.fused_variant, S.opt.cost_dtype) == 0) S.opt.fused_variant = 0;
     } else {
@@ -555,6 +559,23 @@ bool small_path(const Problem &pr, const fs_options *opts, fs_status *err) {
     return km == 0 && slots(pr.n) * slots(pr.m) <= 16;
 }
 
+// Mid-size dense problems can run whole inside one multi-workgroup kernel (fs_coop.hip).
+bool coop_path(const Problem &pr, const fs_options *opts, fs_status *err) {
+    const int km = opts ? opts->kernel_mode : 0;
+    const bool fits = pr.C && coop_supported(pr.n, pr.m) && !(opts && opts->cost_dtype != 0);
+    if (km == 4 && !fits) {
+        set_err("kernel_mode 4 needs a dense fp32 cost matrix with n, m <= %d", kCoopMax);
+        *err = FS_ERR_UNSUPPORTED;
+        return false;
+    }
+    if (!fits || (opts && opts->time_kernel_every > 0)) return false;
+    if (km == 4) return true;
+    // automatic: up to 2^18 entries (512 x 512, 1024 x 256) one launch beats the chain of dependent launches of
+    // the multi-kernel driver (5.6 against 11.3 us per iteration at 256 x 256, 8.4 against 12.7 at 512 x 512);
+    // beyond that too few compute units are at work
+    return km == 0 && (size_t)pr.n * (size_t)pr.m <= ((size_t)1 << 18);
+}
+
 fs_status small_args(const Problem &pr, int batch, const fs_options *opts, float *f, float *g, SmallArgs *out) {
     fs_options o{};
     if (opts) o = *opts;
@@ -605,6 +626,21 @@ int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const 
     DeviceCache *dc = nullptr;
     v = get_cache(L.total, &dc);
     if (v != FS_OK) return v;
+    if (coop_path(pr, opts, &serr)) {
+        HostBlock *hb = dc->host;
+        memset((void *)&hb->res, 0, sizeof(hb->res));
+        void *hb_dev = nullptr;
+        FS_HIP(hipHostGetDevicePointer(&hb_dev, (void *)hb, 0));
+        CoopArgs A{};
+        v = small_args(pr, 1, opts, f, g, &A);
+        if (v != FS_OK) return v;
+        A.result = (ResultRecord *)((char *)hb_dev + offsetof(HostBlock, res));
+        FS_HIP(launch_coop(st, A, (char *)dc->ws + L.o_coop, opts ? opts->fused_variant : 0));
+        FS_HIP(hipStreamSynchronize(st));
+        if (result_host) *result_host = hb->res;
+        return hb->res.iters;
+    }
+    if (serr != FS_OK) return serr;
     Solve S;
     v = setup(S, pr, opts, f, g, st, dc->ws, dc->ws_bytes);
     if (v != FS_OK) return v;
@@ -626,6 +662,18 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
         if (v != FS_OK) return v;
         A.result = (ResultRecord *)result_dev;
         FS_HIP(launch_small(st, A));
+        return FS_OK;
+    }
+    if (serr != FS_OK) return serr;
+    if (coop_path(pr, opts, &serr)) {
+        const Layout L = make_layout(pr.n, pr.m, 0);
+        if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) { set_err("workspace must be non-null and 256-byte aligned"); return FS_ERR_WORKSPACE; }
+        if (ws_bytes < L.total) { set_err("workspace too small: %zu < %zu bytes", ws_bytes, L.total); return FS_ERR_WORKSPACE; }
+        CoopArgs A{};
+        v = small_args(pr, 1, opts, f, g, &A);
+        if (v != FS_OK) return v;
+        A.result = (ResultRecord *)result_dev;
+        FS_HIP(launch_coop(st, A, (char *)ws + L.o_coop, opts ? opts->fused_variant : 0));
         return FS_OK;
     }
     if (serr != FS_OK) return serr;

@@ -375,14 +375,6 @@ __device__ __forceinline__ void lds_only_barrier() {
 #endif
 }
 
-__device__ __forceinline__ double bcast_f64(double x, int src_lane) {
-    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), src_lane),
-                            __builtin_amdgcn_readlane(__double2loint(x), src_lane));
-}
-__device__ __forceinline__ float bcast_f32(float x, int src_lane) {
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src_lane));
-}
-
 constexpr int waitcnt_vm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }   // s_waitcnt vmcnt(n) only
 
 // FULLW: m == 4*Q*T, every lane owns valid columns.  Then every wave issues exactly R*Q + 5

@@ -102,8 +102,6 @@ __device__ __forceinline__ double log2_weight(float w) {
     return w > 0.0f ? log2((double)w) : -__builtin_huge_val();
 }
 
-// Four adjacent fp32 values at any 4-byte boundary (rows of a matrix whose width is not a multiple of
-// 4 start anywhere): one 16-byte access, the hardware's unaligned access mode does the rest.
 // A cost entry stored in 2 bytes, from its bits: DT = 1 IEEE half precision, DT = 2 bfloat16.
 template <int DT>
 __device__ __forceinline__ float cost_from_bits(unsigned bits16) {
@@ -121,6 +119,8 @@ __device__ __forceinline__ float cost_entry(const float *C, int dtype, size_t id
     return dtype == 1 ? cost_from_bits<1>(bits) : cost_from_bits<2>(bits);
 }
 
+// Four adjacent fp32 values at any 4-byte boundary (rows of a matrix whose width is not a multiple of
+// 4 start anywhere): one 16-byte access, the hardware's unaligned access mode does the rest.
 typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
 // ---------------------------------------------------------------- DPP / swizzle moves
@@ -153,6 +153,15 @@ __device__ __forceinline__ double swz16_f64(double v) {
 }
 __device__ __forceinline__ double xor32_f64(double v) {
     return __hiloint2double(xor32_i32(__double2hiint(v)), xor32_i32(__double2loint(v)));
+}
+
+// the value lane `src_lane` (wave-uniform) holds, in every lane
+__device__ __forceinline__ double bcast_f64(double x, int src_lane) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), src_lane),
+                            __builtin_amdgcn_readlane(__double2loint(x), src_lane));
+}
+__device__ __forceinline__ float bcast_f32(float x, int src_lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src_lane));
 }
 
 // All-reduce over the 64 lanes of a wave; every lane must be active.

@@ -171,4 +171,23 @@ struct SmallArgs {
 };
 hipError_t launch_small(hipStream_t st, const SmallArgs &a);
 
+// ---- mid-size dense problems: the whole solve in one launch over up to 32 workgroups (fs_coop.hip)
+constexpr int kCoopMax = 1024;                   // largest n, m
+struct CoopSync {                                // two 256-byte lines
+    unsigned long long arrivals;                 // workgroups that have reached a grid-wide wait, ever
+    unsigned long long pad0[31];
+    unsigned int abort_flag, bad;                // a wait was abandoned; some returned potential is not finite
+    unsigned int pad1[62];
+};
+struct CoopArgs : SmallArgs {                    // batch is ignored (one problem)
+    double *xchg;                                // [2][W][ldx]: published partials by parity of the round
+    CoopSync *sync;
+    int32_t ldx;                                 // slots per workgroup: columns, the last one the error partial
+    int32_t spin_limit;                          // polls before a grid-wide wait is abandoned (<= 0: default)
+};
+bool coop_supported(int n, int m);
+size_t coop_scratch_bytes();                     // device scratch (256-byte aligned) one solve needs
+// variant 0: up to 32 workgroups; 1, 2, 3: at most 16, 8, 4 (more rows per lane)
+hipError_t launch_coop(hipStream_t st, const CoopArgs &a, void *scratch, int variant);
+
 }  // namespace fs

@@ -347,6 +347,72 @@ def test_small_kernel_stop_rule_history_and_resume(fs, oracle):
     assert r0["iters"] == 0 and float(r0["f"].abs().max()) == 0.0 and float(r0["g"].abs().max()) == 0.0
 
 
+# ------------------------------------------------------------------ one launch over several workgroups (n, m <= 1024)
+COOP_SHAPES = [(1, 1, 0), (5, 7, 0), (3, 1024, 0), (1024, 3, 0), (256, 256, 0), (257, 300, 0), (300, 257, 2),
+               (129, 513, 1), (513, 129, 3), (700, 1000, 0), (1000, 700, 1), (1024, 1024, 0), (1024, 1024, 1),
+               (512, 512, 0), (512, 512, 2), (64, 64, 3), (1023, 1021, 0)]
+
+
+@pytest.mark.parametrize("n,m,variant", COOP_SHAPES)
+def test_coop_kernel_matches_oracle(fs, oracle, n, m, variant):
+    """kernel_mode = 4: the whole solve in one launch, rows split over up to 32 workgroups that exchange
+    column partials once per iteration (fused_variant 1..3: fewer workgroups, more rows per lane)."""
+    w = W.random_dense(n, m, seed=7500 + n + m, cmax=2.0, eps=0.02)
+    if n > 8:
+        w.a[2::9] = 0.0
+        w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 30, kernel_mode=4, fused_variant=variant)
+    assert e64 < TOL_F64 and e32 < TOL_F32, (e64, e32)
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+
+
+def test_coop_kernel_stop_rule_history_and_resume(fs, oracle):
+    import torch
+    w = W.random_dense(300, 410, seed=7600, cmax=1.0, eps=0.05)
+    geo, a, b = to_dev(w)
+    ref = oracle.solve(w.a, w.b, w.eps, 400, tol=1e-5, check_every=7, C=w.C, err_every_iter=True)
+    hist = torch.full((400,), float("nan"), dtype=torch.float32, device="cuda")
+    r = fs.fs_sinkhorn_solve(a, b, w.eps, 400, 1e-5, C=geo["C"], want_f64=True, check_every=7, kernel_mode=4,
+                             err_history=hist)
+    assert r["converged"] and ref["converged"]
+    assert abs(r["iters"] - int(ref["iters"])) <= 7 and r["iters"] % 7 == 0
+    k = r["iters"]
+    refk = oracle.solve(w.a, w.b, w.eps, k, C=w.C)
+    assert pot_err(r["f64"].cpu().numpy(), refk["f"], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), refk["g"], w.eps) < TOL_F64
+    h = hist.cpu().numpy()
+    eh = np.asarray(ref["err_hist"], dtype=np.float64)
+    upto = min(k, int(ref["iters"]))
+    assert np.all(np.isfinite(h[:upto]))
+    assert np.allclose(h[:upto], eh[:upto], rtol=2e-3, atol=5e-7)
+    assert np.all(np.isnan(h[k:]))
+    # the multi-kernel driver stops at the same iteration with the same potentials (to rounding)
+    rm = fs.fs_sinkhorn_solve(a, b, w.eps, 400, 1e-5, C=geo["C"], want_f64=True, check_every=7, kernel_mode=1)
+    assert rm["iters"] == k and float((rm["f64"] - r["f64"]).abs().max()) / w.eps < TOL_F64
+    # fixed count without the trailing error pass; resume from fp64 potentials = one longer run
+    r1 = fs.fs_sinkhorn_solve(a, b, w.eps, 11, 0.0, C=geo["C"], want_f64=True, kernel_mode=4, skip_final_err=True)
+    assert math.isnan(r1["marginal_err"]) and r1["iters"] == 11
+    r2 = fs.fs_sinkhorn_solve(a, b, w.eps, 9, 0.0, C=geo["C"], want_f64=True, kernel_mode=4, warm_start=True,
+                              f64_in=r1["f64"], g64_in=r1["g64"])
+    r3 = fs.fs_sinkhorn_solve(a, b, w.eps, 20, 0.0, C=geo["C"], want_f64=True, kernel_mode=4)
+    assert float((r2["f64"] - r3["f64"]).abs().max()) / w.eps < 1e-9
+    assert float((r2["g64"] - r3["g64"]).abs().max()) / w.eps < 1e-9
+    # repeated solves are bit-identical, and the asynchronous entry point runs the same kernel
+    r4 = fs.fs_sinkhorn_solve(a, b, w.eps, 20, 0.0, C=geo["C"], want_f64=True, kernel_mode=4)
+    assert torch.equal(r3["f64"], r4["f64"]) and torch.equal(r3["g64"], r4["g64"])
+    h5 = fs.fs_sinkhorn_dense_ex(geo["C"], a, b, w.eps, 20, 0.0, kernel_mode=4)
+    res5 = h5.result()
+    assert res5["iters"] == 20 and torch.equal(h5.f, r3["f"]) and torch.equal(h5.g, r3["g"])
+    # max_iter = 0 returns the start
+    r0 = fs.fs_sinkhorn_solve(a, b, w.eps, 0, 0.0, C=geo["C"], kernel_mode=4)
+    assert r0["iters"] == 0 and float(r0["f"].abs().max()) == 0.0 and float(r0["g"].abs().max()) == 0.0
+    # shapes it does not take
+    with pytest.raises(fs.FsError, match="kernel_mode 4"):
+        fs.fs_sinkhorn_solve(a, torch.full((1025,), 1 / 1025, device="cuda"), w.eps, 3, 0.0,
+                             C=torch.zeros(300, 1025, device="cuda"), kernel_mode=4)
+
+
 @pytest.mark.parametrize("B,n,m", [(1, 64, 64), (7, 100, 90), (300, 64, 64), (33, 256, 256)])
 def test_batched_small_solves(fs, oracle, B, n, m):
     import torch
