@@ -93,7 +93,8 @@ typedef struct {
                                 FS_COOP_MAX, else FS_ERR_UNSUPPORTED; what 0 picks from there up to 2^18
                                 entries).  Its workgroups wait for one another with a bounded number of
                                 polls: should the device keep some of them from running for seconds, the
-                                solve gives up and reports NaN potentials with nonfinite = 1                */
+                                solve gives up and reports nonfinite = 1 (potentials then invalid: NaN in
+                                the parts of the workgroups that had stopped), never a silent wrong result   */
     int32_t use_graph;       /* 0: automatic; 1: plain stream launches; 2: hipGraph iteration blocks  */
     int32_t skip_final_err;  /* 1: do not spend the one trailing pass that evaluates err after the
                                 last iteration when no stop fired (marginal_err is then NaN)          */
@@ -115,7 +116,9 @@ typedef struct {
                                 16-byte aligned C (else FS_ERR_UNSUPPORTED); honoured by fs_sinkhorn_dense_ex,
                                 fs_sinkhorn_solve and fs_sinkhorn_annealed (dense); the batched solver and
                                 kernel_mode 3 take fp32 only; kernel_mode 2 then needs 2048 < m <= 16384 */
-    int32_t reserved0;       /* must be 0                                                              */
+    int32_t wait_limit;      /* kernel_mode 4 only: polls after which a workgroup stops waiting for the others
+                                (0: default, about two million = seconds).  A tiny value makes the solve give
+                                up early and report nonfinite = 1, which is how the bounded wait is tested   */
     int32_t time_kernel_every; /* blocking solves only: > 0 brackets the dominant kernel (row pass, fused
                                   pass or point-cloud LSE pass of the f-update) of every N-th iteration
                                   with HIP events on `stream`; read back with fs_last_kernel_timing()   */

@@ -42,7 +42,7 @@ class fs_options(ctypes.Structure):
                 ("f64_out", ctypes.c_void_p), ("g64_out", ctypes.c_void_p),
                 ("f64_in", ctypes.c_void_p), ("g64_in", ctypes.c_void_p),
                 ("err_history", ctypes.c_void_p), ("err_history_len", ctypes.c_int32),
-                ("cost_dtype", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+                ("cost_dtype", ctypes.c_int32), ("wait_limit", ctypes.c_int32),
                 ("time_kernel_every", ctypes.c_int32)]
 
 
@@ -157,9 +157,10 @@ def _shape(C, X, Y, a, b):
 
 def make_options(check_every=0, warm_start=False, kernel_mode=0, use_graph=0, skip_final_err=False,
                  fused_variant=0, f64_out=None, g64_out=None, f64_in=None, g64_in=None, err_history=None,
-                 time_kernel_every=0, cost_dtype=0):
+                 time_kernel_every=0, cost_dtype=0, wait_limit=0):
     o = fs_options()
     o.cost_dtype = int(cost_dtype)
+    o.wait_limit = int(wait_limit)
     o.check_every = int(check_every)
     o.warm_start = int(bool(warm_start))
     o.kernel_mode = int(kernel_mode)

@@ -635,6 +635,7 @@ int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const 
         v = small_args(pr, 1, opts, f, g, &A);
         if (v != FS_OK) return v;
         A.result = (ResultRecord *)((char *)hb_dev + offsetof(HostBlock, res));
+        A.spin_limit = opts ? opts->wait_limit : 0;
         FS_HIP(launch_coop(st, A, (char *)dc->ws + L.o_coop, opts ? opts->fused_variant : 0));
         FS_HIP(hipStreamSynchronize(st));
         if (result_host) *result_host = hb->res;
@@ -673,6 +674,7 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
         v = small_args(pr, 1, opts, f, g, &A);
         if (v != FS_OK) return v;
         A.result = (ResultRecord *)result_dev;
+        A.spin_limit = opts ? opts->wait_limit : 0;
         FS_HIP(launch_coop(st, A, (char *)ws + L.o_coop, opts ? opts->fused_variant : 0));
         return FS_OK;
     }

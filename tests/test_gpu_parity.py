@@ -413,6 +413,31 @@ def test_coop_kernel_stop_rule_history_and_resume(fs, oracle):
                              C=torch.zeros(300, 1025, device="cuda"), kernel_mode=4)
 
 
+def test_coop_kernel_bounded_wait_gives_up_cleanly(fs, oracle):
+    """wait_limit = 1: a workgroup stops waiting for the others after a single poll.  Whether that is enough
+    depends on timing, so either outcome is legal - but nothing in between: the solve is either complete and
+    right, or it says so (nonfinite = 1, no error value, not converged).  Every workgroup exits either way, and the next
+    solve on the same workspace is unaffected."""
+    import torch
+    w = W.random_dense(512, 500, seed=7700, cmax=1.0, eps=0.05)
+    geo, a, b = to_dev(w)
+    ref = oracle.solve(w.a, w.b, w.eps, 30, C=w.C)
+    outcomes = set()
+    for _ in range(6):
+        r = fs.fs_sinkhorn_solve(a, b, w.eps, 30, 0.0, C=geo["C"], want_f64=True, kernel_mode=4, wait_limit=1)
+        if r["nonfinite"]:
+            outcomes.add("gave up")          # potentials are then not valid (NaN where a workgroup had stopped)
+            assert math.isnan(r["marginal_err"]) and not r["converged"] and 0 <= r["iters"] <= 30
+        else:
+            outcomes.add("completed")
+            assert r["iters"] == 30 and pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+    r = fs.fs_sinkhorn_solve(a, b, w.eps, 30, 0.0, C=geo["C"], want_f64=True, kernel_mode=4)
+    assert r["iters"] == 30 and not r["nonfinite"]
+    assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+    print("outcomes with wait_limit = 1:", sorted(outcomes))
+
+
 @pytest.mark.parametrize("B,n,m", [(1, 64, 64), (7, 100, 90), (300, 64, 64), (33, 256, 256)])
 def test_batched_small_solves(fs, oracle, B, n, m):
     import torch
