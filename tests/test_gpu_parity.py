@@ -101,7 +101,8 @@ def _solve_and_compare(fs, oracle, w, iters, eps=None, **kw):
 @pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("n,m", [(1, 4), (4, 4), (130, 64), (67, 1024), (517, 1028), (300, 4096), (90, 8192),
                                  (130, 2052), (40, 9000), (33, 12288), (30, 13004), (21, 16384),
-                                 (70, 1027), (64, 4097), (45, 8190), (37, 8189), (20, 16383), (50, 3001)])
+                                 (70, 1027), (64, 4097), (45, 8190), (37, 8189), (20, 16383), (50, 3001),
+                                 (2049, 4096), (2300, 1500), (2051, 1026)])     # many panels per workgroup
 def test_dense_solve_modes(fs, oracle, mode, n, m):
     w = W.random_dense(n, m, seed=3000 + n + m, cmax=2.0, eps=0.03)
     r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 25, kernel_mode=mode)
@@ -128,7 +129,7 @@ def test_fused_column_repair_path(fs, oracle):
     w = W.random_dense(300, 4100, seed=79, cmax=2.0, eps=0.03)       # odd tail columns on the same path
     r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 9, kernel_mode=2, fused_variant=100)
     assert e64 < TOL_F64 and e32 < TOL_F32
-    for n, m in ((64, 3000), (50, 4096), (35, 10000), (25, 16384), (40, 8191), (33, 2050)):  # other widths
+    for n, m in ((64, 3000), (50, 4096), (35, 10000), (25, 16384), (40, 8191), (33, 2050), (2100, 4096), (2064, 3001)):  # other widths
         w = W.random_dense(n, m, seed=80 + m, cmax=2.0, eps=0.03)
         r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 9, kernel_mode=2, fused_variant=100)
         assert e64 < TOL_F64 and e32 < TOL_F32, (n, m, e64, e32)
