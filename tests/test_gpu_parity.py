@@ -200,6 +200,56 @@ def test_half_precision_cost_async_and_rejections(fs, oracle):
                              C=torch.zeros(64, 1024, dtype=torch.bfloat16, device="cuda"), kernel_mode=2)
 
 
+def _sweep_cases():
+    """Seeded sweep over the widths where the dense driver changes kernels (and their neighbours), every kernel
+    mode that takes the shape, all three storage types of C, occasional zero weights."""
+    rng = np.random.default_rng(20240607)
+    edges = [128, 256, 512, 1024, 2048, 4096, 8192, 12288, 16384]
+    cases = []
+    for t in range(48):
+        if t % 3 == 0:
+            m = int(rng.choice(edges)) + int(rng.choice([-8, -1, 0, 1, 8]))
+        else:
+            m = int(rng.integers(1, 17000))
+        n = int(rng.integers(1, 400)) if m > 2048 else int(rng.integers(1, 1200))
+        dt = ["f32", "f32", "f16", "bf16"][int(rng.integers(0, 4))] if m % 8 == 0 else "f32"
+        modes = [0, 1]
+        if dt == "f32" and (m <= 16384 and (m > 1024 or m % 4 == 0)):
+            modes.append(2)
+        if dt != "f32" and 2048 < m <= 16384:
+            modes.append(2)
+        if dt == "f32" and n <= 1024 and m <= 1024:
+            modes.append(4)
+        if dt == "f32" and n <= 256 and m <= 256:
+            modes.append(3)
+        mode = int(rng.choice(modes))
+        eps = float(rng.choice([0.02, 0.05, 0.3]))
+        cases.append((t, n, m, dt, mode, eps, bool(rng.integers(0, 3) == 0)))
+    return cases
+
+
+@pytest.mark.parametrize("t,n,m,dt,mode,eps,zeros", _sweep_cases())
+def test_dense_shape_sweep(fs, oracle, t, n, m, dt, mode, eps, zeros):
+    w = W.random_dense(n, m, seed=9100 + t, cmax=2.0, eps=eps)
+    if zeros and n > 4 and m > 4:
+        w.a[1::5] = 0.0
+        w.a[:] = w.a / w.a.sum(dtype=np.float64)
+        w.b[3::7] = 0.0
+        w.b[:] = w.b / w.b.sum(dtype=np.float64)
+    if dt == "f32":
+        C32, Cd = w.C, dev(w.C)
+    else:
+        C32, Cd = _rounded_cost(w.C, dt)
+    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), eps, 12, 0.0, C=Cd, want_f64=True, kernel_mode=mode)
+    ref = oracle.solve(w.a, w.b, eps, 12, C=C32)
+    assert r["iters"] == 12 and not r["nonfinite"]
+    fin_f, fin_g = np.isfinite(ref["f"]), np.isfinite(ref["g"])
+    f64, g64 = r["f64"].cpu().numpy(), r["g64"].cpu().numpy()
+    assert np.array_equal(np.isfinite(f64), fin_f) and np.array_equal(np.isfinite(g64), fin_g)
+    assert pot_err(f64[fin_f], ref["f"][fin_f], eps) < TOL_F64
+    assert pot_err(g64[fin_g], ref["g"][fin_g], eps) < TOL_F64
+
+
 @pytest.mark.parametrize("n,m,mode", [(5000, 64, 0), (3000, 12, 1), (40, 20000, 0), (9, 16388, 0), (2, 70001, 1)])
 def test_dense_extreme_aspect_ratios(fs, oracle, n, m, mode):
     """Very tall (many rows of the error sum per workgroup of the combine) and very wide (beyond the
