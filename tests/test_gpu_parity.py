@@ -250,6 +250,33 @@ def test_dense_shape_sweep(fs, oracle, t, n, m, dt, mode, eps, zeros):
     assert pot_err(g64[fin_g], ref["g"][fin_g], eps) < TOL_F64
 
 
+def _points_sweep_cases():
+    rng = np.random.default_rng(20240608)
+    dims = [1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64]
+    cases = []
+    for t in range(32):
+        d = dims[t % len(dims)]
+        n, m = int(rng.integers(1, 2500)), int(rng.integers(1, 2500))
+        cases.append((t, n, m, d, float(rng.choice([0.02, 0.05, 0.3])), bool(rng.integers(0, 3) == 0)))
+    return cases
+
+
+@pytest.mark.parametrize("t,n,m,d,eps,zeros", _points_sweep_cases())
+def test_points_shape_sweep(fs, oracle, t, n, m, d, eps, zeros):
+    """Seeded sweep over every coordinate count the point-cloud kernels specialise on (vector kernels up to 4,
+    matrix-core tiles of 8, 16, 32, 64 and their neighbours), ragged sizes, occasional zero weights."""
+    w = W.random_points(n, m, d, seed=9300 + t, eps=eps)
+    if zeros and n > 4 and m > 4:
+        w.a[1::5] = 0.0
+        w.a[:] = w.a / w.a.sum(dtype=np.float64)
+        w.b[3::7] = 0.0
+        w.b[:] = w.b / w.b.sum(dtype=np.float64)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 10)
+    assert e64 < TOL_F64 and e32 < TOL_F32, (e64, e32)
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], X=w.X, Y=w.Y))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+
+
 @pytest.mark.parametrize("n,m,mode", [(5000, 64, 0), (3000, 12, 1), (40, 20000, 0), (9, 16388, 0), (2, 70001, 1)])
 def test_dense_extreme_aspect_ratios(fs, oracle, n, m, mode):
     """Very tall (many rows of the error sum per workgroup of the combine) and very wide (beyond the
