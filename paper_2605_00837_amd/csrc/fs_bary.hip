@@ -48,7 +48,7 @@ BaryLayout bary_layout(int n, int m, int d) {
         L.P = (n + rpp - 1) / rpp;
         L.nparts = L.nstrips;
     } else {
-        points_plan(n, m, d, &L.JS, &L.cps);
+        points_plan_tiles(n, m, d, &L.JS, &L.cps);
         L.nparts = L.JS;
         L.o_xp = take(sizeof(double) * (size_t)n * d);
         L.o_xs = take(sizeof(double) * (size_t)n * d);

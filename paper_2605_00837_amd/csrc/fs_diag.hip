@@ -69,8 +69,8 @@ DiagLayout diag_layout(int n, int m, int d) {
         L.nscal = L.nstrips * L.P;
         L.o_scal = take(sizeof(double) * 2 * L.nscal);
     } else {
-        points_plan(n, m, d, &L.JSx, &L.cpsx);
-        points_plan(m, n, d, &L.JSy, &L.cpsy);
+        points_plan_tiles(n, m, d, &L.JSx, &L.cpsx);
+        points_plan_tiles(m, n, d, &L.JSy, &L.cpsy);
         L.o_rowpart = take(sizeof(double) * (size_t)L.JSx * n);      // row sums per column slice
         L.o_colpart = take(sizeof(double) * (size_t)L.JSy * m);      // column sums per row slice
         const int rows_per_wg = d <= 4 ? kPT2 * kIB2 : kTileRows;

@@ -116,6 +116,7 @@ struct PointsArgs {
     const double *rowconst;
 };
 void points_plan(int nr, int nc, int d, int *JS, int *cols_per_split);
+void points_plan_tiles(int nr, int nc, int d, int *JS, int *cols_per_split);   // same for the after-the-loop kernels
 bool points_optimistic(int d);      // does the LSE pass for this dimension have the optimistic (FAST) variant?
 hipError_t launch_points_lse(hipStream_t st, const PointsArgs &a, const Ctl &c, int use_next_shift, int ld_shift);
 hipError_t launch_points_prep(hipStream_t st, const float *X, int n, int d, double s, double *plain,

@@ -101,8 +101,9 @@ __global__ __launch_bounds__(kPT) void k_points_lse(PointsArgs A, Ctl c, int use
         }
         for (int jt = j0; jt < j1; jt += kTile) {
             stage(jt);
+            const int cnt = min(kTile, (j1 - jt + 3) & ~3);      // staged columns (the tile is padded with -inf)
 #pragma unroll 4
-            for (int jj = 0; jj < kTile; ++jj) {
+            for (int jj = 0; jj < cnt; ++jj) {
                 double w[D + 1];
 #pragma unroll
                 for (int t = 0; t <= D; ++t) w[t] = tile[jj][t];
@@ -127,7 +128,8 @@ __global__ __launch_bounds__(kPT) void k_points_lse(PointsArgs A, Ctl c, int use
     constexpr int CH = IB <= 2 ? kChunk : 4;               // pairs folded per rescale
     for (int jt = j0; jt < j1; jt += kTile) {
         stage(jt);
-        for (int jj = 0; jj < kTile; jj += CH) {
+        const int cnt = min(kTile, (j1 - jt + CH - 1) / CH * CH);
+        for (int jj = 0; jj < cnt; jj += CH) {
             double val[IB][CH];
 #pragma unroll
             for (int q = 0; q < CH; ++q) {
@@ -299,7 +301,29 @@ __global__ __launch_bounds__(256) void k_points_mfma(PointsArgs A, Ctl c, int us
 
 bool points_optimistic(int d) { (void)d; return true; }
 
+// Rows per lane of the vector kernels: 4 (every staged column is reused four times) once there are enough
+// rows to fill the chip that way, 1 below.
+static int points_ib(int nr) { return nr < 4096 ? 1 : kIB; }
+
 void points_plan(int nr, int nc, int d, int *JS, int *cols_per_split) {
+    // About 2048 workgroups per launch: row blocks x column slices, a slice being a whole number of
+    // 64-column groups (the matrix-core kernel's tile; the vector kernels stage up to kTile at a time).
+    const int rows_per_wg = (d <= 4) ? kPT * points_ib(nr) : mfma_rows(d <= 8 ? 2 : d <= 16 ? 4 : d <= 32 ? 8 : 16);
+    const int rowblocks = (nr + rows_per_wg - 1) / rows_per_wg;
+    int want = (2048 + rowblocks - 1) / rowblocks;
+    if (want > 256) want = 256;
+    int cps = (nc + want - 1) / want;
+    cps = ((cps + kMfmaTJ - 1) / kMfmaTJ) * kMfmaTJ;
+    // whole tiles of kTile columns as soon as that still gives every compute unit two workgroups: fewer
+    // partials for the combine kernel, fewer stage-and-wait rounds per column
+    if (cps < kTile && (long long)rowblocks * ((nc + kTile - 1) / kTile) >= 512) cps = kTile;
+    *JS = (nc + cps - 1) / cps;
+    *cols_per_split = cps;
+}
+
+// The after-the-loop kernels (diagnostics, barycentric mapping; one pass each, 4 rows per lane, tiles of
+// kTile columns walked in full): slices of whole tiles.
+void points_plan_tiles(int nr, int nc, int d, int *JS, int *cols_per_split) {
     const int rows_per_wg = (d <= 4) ? kPT * kIB : kPT;
     const int rowblocks = (nr + rows_per_wg - 1) / rows_per_wg;
     int js = (2048 + rowblocks - 1) / rowblocks;
@@ -308,14 +332,21 @@ void points_plan(int nr, int nc, int d, int *JS, int *cols_per_split) {
     if (js > 256) js = 256;
     if (js < 1) js = 1;
     int cps = (nc + js - 1) / js;
-    cps = ((cps + kTile - 1) / kTile) * kTile;             // whole tiles per slice
-    js = (nc + cps - 1) / cps;
-    *JS = js;
+    cps = ((cps + kTile - 1) / kTile) * kTile;
+    *JS = (nc + cps - 1) / cps;
     *cols_per_split = cps;
 }
 
 hipError_t launch_points_lse(hipStream_t st, const PointsArgs &a, const Ctl &c, int use_next_shift, int ld_shift) {
-    if (a.d <= 4) {
+    if (a.d <= 4 && points_ib(a.nr) == 1) {
+        const dim3 grid((a.nr + kPT - 1) / kPT, a.JS);
+        switch (a.d) {
+            case 1: hipLaunchKernelGGL((k_points_lse<1, 1>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
+            case 2: hipLaunchKernelGGL((k_points_lse<2, 1>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
+            case 3: hipLaunchKernelGGL((k_points_lse<3, 1>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
+            default: hipLaunchKernelGGL((k_points_lse<4, 1>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
+        }
+    } else if (a.d <= 4) {
         const dim3 grid((a.nr + kPT * kIB - 1) / (kPT * kIB), a.JS);
         switch (a.d) {
             case 1: hipLaunchKernelGGL((k_points_lse<1, kIB>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
