@@ -89,9 +89,11 @@ typedef struct {
                                 3: the whole solve in one single-workgroup kernel (dense, n, m <=
                                 FS_SMALL_MAX, else FS_ERR_UNSUPPORTED; what 0 picks up to about 128 x 128);
                                 4: the whole solve in one launch over up to 32 workgroups that hold C in
-                                registers and exchange column partials once per iteration (dense fp32, n, m <=
-                                FS_COOP_MAX, else FS_ERR_UNSUPPORTED; what 0 picks from there up to 2^18
-                                entries).  Its workgroups wait for one another with a bounded number of
+                                registers and exchange column partials once per iteration (n, m <= FS_COOP_MAX
+                                and a dense fp32 cost, or point clouds up to about n * m = 2^19 - exactly:
+                                roundup(n / 128, power of 2) * roundup(m / 256, power of 2) <= 16 - whose squared
+                                distances are then formed once in fp64; else FS_ERR_UNSUPPORTED; what 0 picks
+                                from there up to 2^18 entries or pairs).  Its workgroups wait for one another with a bounded number of
                                 polls: should the device keep some of them from running for seconds, the
                                 solve gives up and reports nonfinite = 1 (potentials then invalid: NaN in
                                 the parts of the workgroups that had stopped), never a silent wrong result   */

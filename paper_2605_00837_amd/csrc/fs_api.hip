@@ -89,6 +89,7 @@ Layout make_layout(int n, int m, int d) {
         L.o_cx = take(sizeof(double) * L.n_ld);
         L.o_Yp = take(sizeof(double) * (size_t)m * d);
         L.o_Ys = take(sizeof(double) * (size_t)m * d);
+        if (coop_points_supported(n, m)) L.o_coop = take(coop_scratch_bytes());
         L.o_cy = take(sizeof(double) * L.m_ld);
     }
     L.total = off;
@@ -559,12 +560,14 @@ bool small_path(const Problem &pr, const fs_options *opts, fs_status *err) {
     return km == 0 && slots(pr.n) * slots(pr.m) <= 16;
 }
 
-// Mid-size dense problems can run whole inside one multi-workgroup kernel (fs_coop.hip).
+// Mid-size problems can run whole inside one multi-workgroup kernel (fs_coop.hip): dense fp32 cost, or point
+// clouds (the squared distances are then formed once, in fp64, and kept in registers like a cost matrix).
 bool coop_path(const Problem &pr, const fs_options *opts, fs_status *err) {
     const int km = opts ? opts->kernel_mode : 0;
-    const bool fits = pr.C && coop_supported(pr.n, pr.m) && !(opts && opts->cost_dtype != 0);
+    const bool fits = pr.C ? (coop_supported(pr.n, pr.m) && !(opts && opts->cost_dtype != 0))
+                           : coop_points_supported(pr.n, pr.m);
     if (km == 4 && !fits) {
-        set_err("kernel_mode 4 needs a dense fp32 cost matrix with n, m <= %d", kCoopMax);
+        set_err("kernel_mode 4 needs n, m <= %d and a dense fp32 cost matrix, or point clouds of at most 16 pairs per lane (n * m <= 2^19, less for ragged shapes)", kCoopMax);
         *err = FS_ERR_UNSUPPORTED;
         return false;
     }
@@ -636,6 +639,7 @@ int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const 
         if (v != FS_OK) return v;
         A.result = (ResultRecord *)((char *)hb_dev + offsetof(HostBlock, res));
         A.spin_limit = opts ? opts->wait_limit : 0;
+        A.X = pr.X; A.Y = pr.Y; A.d = pr.C ? 0 : pr.d;
         FS_HIP(launch_coop(st, A, (char *)dc->ws + L.o_coop, opts ? opts->fused_variant : 0));
         FS_HIP(hipStreamSynchronize(st));
         if (result_host) *result_host = hb->res;
@@ -667,7 +671,7 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
     }
     if (serr != FS_OK) return serr;
     if (coop_path(pr, opts, &serr)) {
-        const Layout L = make_layout(pr.n, pr.m, 0);
+        const Layout L = make_layout(pr.n, pr.m, pr.C ? 0 : pr.d);
         if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) { set_err("workspace must be non-null and 256-byte aligned"); return FS_ERR_WORKSPACE; }
         if (ws_bytes < L.total) { set_err("workspace too small: %zu < %zu bytes", ws_bytes, L.total); return FS_ERR_WORKSPACE; }
         CoopArgs A{};
@@ -675,6 +679,7 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
         if (v != FS_OK) return v;
         A.result = (ResultRecord *)result_dev;
         A.spin_limit = opts ? opts->wait_limit : 0;
+        A.X = pr.X; A.Y = pr.Y; A.d = pr.C ? 0 : pr.d;
         FS_HIP(launch_coop(st, A, (char *)ws + L.o_coop, opts ? opts->fused_variant : 0));
         return FS_OK;
     }

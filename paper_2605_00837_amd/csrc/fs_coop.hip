@@ -24,6 +24,8 @@
 // alternate by the parity of the generation, and every wait is bounded: a workgroup that gives up
 // raises a flag that makes all others give up too, the solve then reports NaN potentials and
 // nonfinite = 1 instead of hanging.
+#include <type_traits>
+
 #include "fs_kernels.h"
 
 namespace fs {
@@ -42,6 +44,7 @@ __device__ __forceinline__ double cost_f64(float c) {      // see fs_small.hip: 
 #endif
     return (double)c;
 }
+__device__ __forceinline__ double cost_f64(double c) { return c; }
 __device__ __forceinline__ void publish(double *p, double v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -85,7 +88,9 @@ __global__ void k_coop_reset(CoopSync *sy) {
     }
 }
 
-template <int RA, int CB>
+// PTS: point clouds - the tile holds |x_i - y_j|^2 in fp64, formed once from the fp32 coordinates in the
+// difference form (nothing of the cost is rounded to fp32 on this path either).
+template <int RA, int CB, bool PTS>
 __global__ __launch_bounds__(kCT) void k_coop(CoopArgs A) {
     __shared__ double sF[2][kRowsMax];             // F = -s f of the workgroup's rows, by parity of k
     __shared__ double sLa[kRowsMax];               // log2 a
@@ -131,13 +136,23 @@ __global__ __launch_bounds__(kCT) void k_coop(CoopArgs A) {
         if (A.warm) Gt = ns * (A.g64_in ? A.g64_in[tid] : (double)A.g_in[tid]);
     }
     if (colthread) sV[tid] = tid < m ? lb2 - Gt : ninf;
-    float c[RA][CB];
+    typename std::conditional<PTS, double, float>::type c[RA][CB];
 #pragma unroll
     for (int a = 0; a < RA; ++a)
 #pragma unroll
         for (int b = 0; b < CB; ++b) {
             const int i = row0 + tr * RA + a, j = tc + kTC * b;
-            c[a][b] = (i < n && j < m) ? A.C[(size_t)i * m + j] : 0.0f;
+            if constexpr (PTS) {
+                double sq = 0.0;
+                if (i < n && j < m)
+                    for (int t = 0; t < A.d; ++t) {
+                        const double df = (double)A.X[(size_t)i * A.d + t] - (double)A.Y[(size_t)j * A.d + t];
+                        sq = fma(df, df, sq);
+                    }
+                c[a][b] = sq;
+            } else {
+                c[a][b] = (i < n && j < m) ? A.C[(size_t)i * m + j] : 0.0f;
+            }
         }
     __syncthreads();
     double V[CB];
@@ -317,18 +332,37 @@ __global__ __launch_bounds__(kCT) void k_coop(CoopArgs A) {
 #endif
 }
 
-template <int RA>
+template <int RA, bool PTS>
 hipError_t launch_cb(hipStream_t st, const CoopArgs &a, int W, int cb) {
     const dim3 grid(W), block(kCT);
-    if (cb <= 1) hipLaunchKernelGGL((k_coop<RA, 1>), grid, block, 0, st, a);
-    else if (cb <= 2) hipLaunchKernelGGL((k_coop<RA, 2>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((k_coop<RA, 4>), grid, block, 0, st, a);
+    if (cb <= 1) hipLaunchKernelGGL((k_coop<RA, 1, PTS>), grid, block, 0, st, a);
+    else if (cb <= 2) hipLaunchKernelGGL((k_coop<RA, 2, PTS>), grid, block, 0, st, a);
+    else if constexpr (PTS && RA == 8) return hipErrorInvalidValue;       // 32 fp64 entries per lane: not built
+    else hipLaunchKernelGGL((k_coop<RA, 4, PTS>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
 bool coop_supported(int n, int m) { return n >= 1 && m >= 1 && m <= kCoopMax && n <= kCoopMax; }
+
+// Tile per lane: RA rows (the smallest of 1, 2, 4, 8 that keeps the grid within wmax workgroups) x CB columns.
+static void coop_tile(int n, int m, int wmax, int *RA, int *CB) {
+    int ra = 8;
+    for (int r = 1; r <= 8; r *= 2)
+        if ((n + kTR * r - 1) / (kTR * r) <= wmax) { ra = r; break; }
+    const int cb = (m + kTC - 1) / kTC;
+    *RA = ra;
+    *CB = cb <= 1 ? 1 : cb <= 2 ? 2 : 4;
+}
+
+// point clouds: the tile is fp64, so half as many entries per lane (at most 16, with the largest grid)
+bool coop_points_supported(int n, int m) {
+    if (!coop_supported(n, m)) return false;
+    int RA, CB;
+    coop_tile(n, m, 32, &RA, &CB);
+    return RA * CB <= 16;
+}
 
 constexpr int kCoopWMax = 32;                    // workgroups at most: each reads every other's partials
 constexpr int kCoopLdx = kCoopMax + 32;
@@ -339,11 +373,11 @@ size_t coop_scratch_bytes() {
 
 hipError_t launch_coop(hipStream_t st, const CoopArgs &a0, void *scratch, int variant) {
     if (!coop_supported(a0.n, a0.m) || !scratch) return hipErrorInvalidValue;
-    // rows per lane: the smallest tile that keeps the grid within the wanted number of workgroups
-    const int wmax = variant == 1 ? 16 : variant == 2 ? 8 : variant == 3 ? 4 : kCoopWMax;
-    int RA = 8;
-    for (int ra = 1; ra <= 8; ra *= 2)
-        if ((a0.n + kTR * ra - 1) / (kTR * ra) <= wmax) { RA = ra; break; }
+    if (a0.X && (!a0.Y || a0.d < 1 || !coop_points_supported(a0.n, a0.m))) return hipErrorInvalidValue;
+    // fewer workgroups on request (more rows per lane); point clouds always take the largest grid
+    const int wmax = a0.X ? kCoopWMax : variant == 1 ? 16 : variant == 2 ? 8 : variant == 3 ? 4 : kCoopWMax;
+    int RA, CB;
+    coop_tile(a0.n, a0.m, wmax, &RA, &CB);
     const int W = (a0.n + kTR * RA - 1) / (kTR * RA);
     if (W < 1 || W > kCoopWMax) return hipErrorInvalidValue;      // cannot happen for n <= kCoopMax
     CoopArgs a = a0;
@@ -354,11 +388,17 @@ hipError_t launch_coop(hipStream_t st, const CoopArgs &a0, void *scratch, int va
     hipLaunchKernelGGL(k_coop_reset, dim3(1), dim3(64), 0, st, a.sync);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int cb = (a.m + kTC - 1) / kTC;
-    if (RA == 1) return launch_cb<1>(st, a, W, cb);
-    if (RA == 2) return launch_cb<2>(st, a, W, cb);
-    if (RA == 4) return launch_cb<4>(st, a, W, cb);
-    return launch_cb<8>(st, a, W, cb);
+    const int cb = CB;
+    if (a.X) {
+        if (RA == 1) return launch_cb<1, true>(st, a, W, cb);
+        if (RA == 2) return launch_cb<2, true>(st, a, W, cb);
+        if (RA == 4) return launch_cb<4, true>(st, a, W, cb);
+        return launch_cb<8, true>(st, a, W, cb);
+    }
+    if (RA == 1) return launch_cb<1, false>(st, a, W, cb);
+    if (RA == 2) return launch_cb<2, false>(st, a, W, cb);
+    if (RA == 4) return launch_cb<4, false>(st, a, W, cb);
+    return launch_cb<8, false>(st, a, W, cb);
 }
 
 }  // namespace fs

@@ -181,12 +181,15 @@ struct CoopSync {                                // two 256-byte lines
     unsigned int pad1[62];
 };
 struct CoopArgs : SmallArgs {                    // batch is ignored (one problem)
+    const float *X, *Y;                          // point clouds [n][d], [m][d] (then C is null), or null
+    int32_t d;
     double *xchg;                                // [2][W][ldx]: published partials by parity of the round
     CoopSync *sync;
     int32_t ldx;                                 // slots per workgroup: columns, the last one the error partial
     int32_t spin_limit;                          // polls before a grid-wide wait is abandoned (<= 0: default)
 };
 bool coop_supported(int n, int m);
+bool coop_points_supported(int n, int m);
 size_t coop_scratch_bytes();                     // device scratch (256-byte aligned) one solve needs
 // variant 0: up to 32 workgroups; 1, 2, 3: at most 16, 8, 4 (more rows per lane)
 hipError_t launch_coop(hipStream_t st, const CoopArgs &a, void *scratch, int variant);

@@ -445,6 +445,25 @@ def test_coop_kernel_matches_oracle(fs, oracle, n, m, variant):
     assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
 
 
+@pytest.mark.parametrize("n,m,d,variant", [(1, 1, 1, 0), (5, 7, 2, 0), (200, 200, 3, 0), (256, 256, 3, 1), (300, 257, 4, 0),
+                                           (1024, 512, 3, 0), (512, 1024, 2, 0), (700, 500, 3, 0), (129, 513, 17, 2),
+                                           (100, 90, 64, 0), (1000, 20, 5, 0)])
+def test_coop_kernel_point_clouds(fs, oracle, n, m, d, variant):
+    """kernel_mode = 4 on point clouds: the squared distances are formed once in fp64 (difference form) and
+    stay in registers; everything else is the dense one-launch solver."""
+    w = W.random_points(n, m, d, seed=7800 + n + m + d, eps=0.02)
+    if n > 8:
+        w.a[2::9] = 0.0
+        w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 30, kernel_mode=4, fused_variant=variant)
+    assert e64 < TOL_F64 and e32 < TOL_F32, (e64, e32)
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], X=w.X, Y=w.Y))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+    # the multi-kernel point-cloud path (any other kernel_mode) agrees to rounding
+    r1, _, _, _ = _solve_and_compare(fs, oracle, w, 30, kernel_mode=1)
+    assert float((r1["f64"] - r["f64"]).abs().max()) / w.eps < TOL_F64
+
+
 def test_coop_kernel_stop_rule_history_and_resume(fs, oracle):
     import torch
     w = W.random_dense(300, 410, seed=7600, cmax=1.0, eps=0.05)
@@ -489,6 +508,10 @@ def test_coop_kernel_stop_rule_history_and_resume(fs, oracle):
     with pytest.raises(fs.FsError, match="kernel_mode 4"):
         fs.fs_sinkhorn_solve(a, torch.full((1025,), 1 / 1025, device="cuda"), w.eps, 3, 0.0,
                              C=torch.zeros(300, 1025, device="cuda"), kernel_mode=4)
+    u = torch.full((1024,), 1 / 1024, device="cuda")
+    with pytest.raises(fs.FsError, match="kernel_mode 4"):
+        fs.fs_sinkhorn_solve(u, u, w.eps, 3, 0.0, X=torch.zeros(1024, 3, device="cuda"),
+                             Y=torch.zeros(1024, 3, device="cuda"), kernel_mode=4)
 
 
 def test_coop_kernel_bounded_wait_gives_up_cleanly(fs, oracle):
