@@ -543,6 +543,15 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     return hb->res.iters;
 }
 
+// Option values that make no sense for the problem at hand, whichever kernel would run it.
+fs_status check_options(const Problem &pr, const fs_options *opts) {
+    if (!opts) return FS_OK;
+    if (opts->cost_dtype < 0 || opts->cost_dtype > 2) { set_err("cost_dtype must be FS_COST_F32, FS_COST_F16 or FS_COST_BF16"); return FS_ERR_INVALID_ARG; }
+    if (opts->cost_dtype != 0 && !pr.C) { set_err("cost_dtype applies to a dense cost matrix only"); return FS_ERR_INVALID_ARG; }
+    if (opts->kernel_mode < 0 || opts->kernel_mode > 4) { set_err("kernel_mode must be 0, 1, 2, 3 or 4"); return FS_ERR_INVALID_ARG; }
+    return FS_OK;
+}
+
 // Small dense problems run whole inside one single-workgroup kernel (fs_small.hip).
 bool small_path(const Problem &pr, const fs_options *opts, fs_status *err) {
     const int km = opts ? opts->kernel_mode : 0;
@@ -605,6 +614,7 @@ fs_status small_args(const Problem &pr, int batch, const fs_options *opts, float
 int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const fs_options *opts,
                    fs_result *result_host) {
     fs_status v = validate(pr, f, g);
+    if (v == FS_OK) v = check_options(pr, opts);
     if (v != FS_OK) return v;
     fs_status serr = FS_OK;
     if (small_path(pr, opts, &serr)) {
@@ -655,6 +665,7 @@ int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const 
 fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, const fs_options *opts,
                       void *ws, size_t ws_bytes, fs_result *result_dev) {
     fs_status v = validate(pr, f, g);
+    if (v == FS_OK) v = check_options(pr, opts);
     if (v != FS_OK) return v;
     fs_status serr = FS_OK;
     if (small_path(pr, opts, &serr)) {
