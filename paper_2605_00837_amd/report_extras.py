@@ -1,5 +1,6 @@
 """Time what runs around the iteration loop, on the GPU: plan, cost, one-pass diagnostics and barycentric
-mapping at the headline size and at the point-cloud size, the single-workgroup kernel and batched solves.
+mapping at the headline size and at the point-cloud size; the single-workgroup kernel, the one-launch
+multi-workgroup kernel (dense and point clouds) against the multi-kernel path, and batched solves.
 
     python -m paper_2605_00837_amd.report_extras
 """
@@ -60,6 +61,28 @@ def main():
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
             print(f"| {n} x {n}, {name} | 2000 | {dt * 1e3:.2f} | {dt / 2000 * 1e6:.2f} us |", flush=True)
+    for n in (256, 384, 512, 1024):
+        w = W.random_dense(n, n, seed=1, cmax=1.0, eps=0.05)
+        C, a, b = (torch.from_numpy(t).cuda() for t in (w.C, w.a, w.b))
+        for mode, name in ((4, "one launch over several workgroups"), (2, "multi-kernel path")):
+            fs.fs_sinkhorn_solve(a, b, w.eps, 10, 0.0, C=C, kernel_mode=mode)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fs.fs_sinkhorn_solve(a, b, w.eps, 2000, 0.0, C=C, kernel_mode=mode)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            print(f"| {n} x {n}, {name} | 2000 | {dt * 1e3:.2f} | {dt / 2000 * 1e6:.2f} us |", flush=True)
+    for n, d in ((200, 3), (512, 3), (200, 16), (2048, 3)):
+        w = W.random_points(n, n, d, seed=1, eps=0.05)
+        X, Y, a, b = (torch.from_numpy(t).cuda() for t in (w.X, w.Y, w.a, w.b))
+        for mode, name in ((0, "automatic"), (1, "multi-kernel path")):
+            fs.fs_sinkhorn_solve(a, b, w.eps, 10, 0.0, X=X, Y=Y, kernel_mode=mode)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fs.fs_sinkhorn_solve(a, b, w.eps, 1000, 0.0, X=X, Y=Y, kernel_mode=mode)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            print(f"| points {n} x {n}, d = {d}, {name} | 1000 | {dt * 1e3:.2f} | {dt / 1000 * 1e6:.2f} us |", flush=True)
     for B, n in ((256, 64), (256, 128), (256, 256), (1024, 256)):
         Cb = torch.rand((B, n, n), device="cuda")
         ab = torch.full((B, n), 1.0 / n, device="cuda")
