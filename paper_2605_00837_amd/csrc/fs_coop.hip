@@ -38,13 +38,6 @@ constexpr int kTR = kCT / kTC;         // row groups
 constexpr int kNWR = kTC / 64;         // waves per row group
 constexpr int kRowsMax = kTR * 8;      // rows per workgroup at RA = 8
 
-__device__ __forceinline__ double cost_f64(float c) {      // see fs_small.hip: keeps the compiler from
-#if defined(__HIP_DEVICE_COMPILE__)                         // holding all converted entries in registers
-    asm volatile("" : "+v"(c));
-#endif
-    return (double)c;
-}
-__device__ __forceinline__ double cost_f64(double c) { return c; }
 __device__ __forceinline__ void publish(double *p, double v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

@@ -119,6 +119,18 @@ __device__ __forceinline__ float cost_entry(const float *C, int dtype, size_t id
     return dtype == 1 ? cost_from_bits<1>(bits) : cost_from_bits<2>(bits);
 }
 
+// A cost entry held in a register for a whole solve, as an fp64 value, through a compiler barrier: every
+// use converts its 4-byte register afresh.  Without it the compiler keeps all converted values of a lane's
+// tile alive (twice the registers) across the two half-steps, or hoists them out of the iteration loop,
+// and spills.
+__device__ __forceinline__ double cost_f64(float c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("" : "+v"(c));
+#endif
+    return (double)c;
+}
+__device__ __forceinline__ double cost_f64(double c) { return c; }
+
 // Four adjacent fp32 values at any 4-byte boundary (rows of a matrix whose width is not a multiple of
 // 4 start anywhere): one 16-byte access, the hardware's unaligned access mode does the rest.
 typedef float float4_a4 __attribute__((ext_vector_type(4), aligned(4)));

@@ -30,15 +30,6 @@ __device__ __forceinline__ double half_max_f64(double v) {      // all-reduce ov
     v = dmax(v, swz16_f64(v));
     return v;
 }
-// The cost entry as an fp64 value, through a compiler barrier: every use converts its 4-byte register
-// afresh.  Without it the compiler keeps all RA*CB converted values alive (twice the registers) across
-// the two half-steps, or hoists them out of the iteration loop, and spills.
-__device__ __forceinline__ double cost_f64(float c) {
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("" : "+v"(c));
-#endif
-    return (double)c;
-}
 __device__ __forceinline__ float half_sum_f32(float v) {
     v += dpp_f32<0x128>(v);
     v += dpp_f32<0x124>(v);
