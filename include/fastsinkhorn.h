@@ -15,9 +15,10 @@
  *   - Every array pointer is a DEVICE pointer (HBM of the current HIP device),
  *     owned by the caller.  The library neither frees nor keeps them after the
  *     work it enqueued on `stream` has run.  Outputs must not alias inputs.
- *   - C is row-major n x m, C[i*m + j], fp32 (Sec. 4.4).  X is n x d and Y is
+ *   - C is row-major n x m, C[i*m + j], fp32 (Sec. 4.4; the solvers with options also
+ *     take fp16 / bfloat16 storage, fs_options.cost_dtype).  X is n x d and Y is
  *     m x d, row-major fp32; the cost is then the squared Euclidean distance
- *     ||x_i - y_j||^2 and is recomputed on the fly, never stored.
+ *     ||x_i - y_j||^2 and is recomputed on the fly, never written to memory.
  *   - a[n], b[m] are fp32 weights (non-negative; a zero weight carries no mass).
  *     They are meant to sum to 1 each: the marginal error is accumulated in fixed
  *     point and reported as NaN once it reaches 16.
