@@ -635,6 +635,54 @@ def test_graph_replayed_blocks_match_plain_launches(fs, kind, mode):
             assert float(junk) > 0
 
 
+@pytest.mark.parametrize("kind,mode", [("dense", 2), ("dense", 4), ("dense_small", 3), ("points", 0), ("points_small", 4)])
+def test_async_entry_points_replay_from_a_captured_graph(fs, kind, mode):
+    """The asynchronous entry points only enqueue kernels (no host synchronisation, no memset nodes), so a caller
+    may capture them into a graph of its own.  Each replay - with eager solves and synchronisations in between -
+    must reproduce the eager result bit for bit."""
+    import torch
+    if kind == "dense":
+        w = W.random_dense(300, 1100 if mode == 2 else 700, seed=8800 + mode, cmax=2.0, eps=0.03)
+    elif kind == "dense_small":
+        w = W.random_dense(100, 120, seed=8810, cmax=2.0, eps=0.03)
+    elif kind == "points":
+        w = W.random_points(900, 1300, 3, seed=8820, eps=0.03)
+    else:
+        w = W.random_points(200, 260, 3, seed=8830, eps=0.03)
+    geo, a, b = to_dev(w)
+    dense = w.C is not None
+    d = 0 if dense else 3
+    f = torch.empty(w.n, dtype=torch.float32, device="cuda")
+    g = torch.empty(w.m, dtype=torch.float32, device="cuda")
+    ws = torch.empty(fs.fs_workspace_bytes(w.n, w.m, d), dtype=torch.uint8, device="cuda")
+
+    def enqueue():
+        if dense:
+            return fs.fs_sinkhorn_dense_ex(geo["C"], a, b, w.eps, 30, 0.0, f=f, g=g, workspace=ws, kernel_mode=mode)
+        return fs.fs_sinkhorn_points_ex(geo["X"], geo["Y"], a, b, w.eps, 30, 0.0, f=f, g=g, workspace=ws, kernel_mode=mode)
+
+    h = enqueue()
+    assert h.result()["iters"] == 30
+    f_ref, g_ref = f.clone(), g.clone()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        hg = enqueue()
+    other = W.random_dense(130, 90, seed=8899, cmax=1.0, eps=0.05)
+    for rep in range(3):
+        f.fill_(float("nan"))
+        g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(f, f_ref) and torch.equal(g, g_ref), rep
+        assert hg.result()["iters"] == 30
+        # eager work of the library between the replays
+        fs.fs_sinkhorn_solve(dev(other.a), dev(other.b), other.eps, 7, 0.0, C=dev(other.C))
+        torch.cuda.synchronize()
+
+
 def test_blocking_and_async_entry_points_agree(fs):
     import torch
     w = W.random_dense(200, 512, seed=23, eps=0.05)
