@@ -122,9 +122,11 @@ typedef struct {
     int32_t wait_limit;      /* kernel_mode 4 only: polls after which a workgroup stops waiting for the others
                                 (0: default, about two million = seconds).  A tiny value makes the solve give
                                 up early and report nonfinite = 1, which is how the bounded wait is tested   */
-    int32_t time_kernel_every; /* blocking solves only: > 0 brackets the dominant kernel (row pass, fused
-                                  pass or point-cloud LSE pass of the f-update) of every N-th iteration
-                                  with HIP events on `stream`; read back with fs_last_kernel_timing()   */
+    int32_t time_kernel_every; /* blocking solves only: > 0 times the dominant kernel (row pass, fused pass
+                                  or point-cloud LSE pass of the f-update) of every N-th iteration with a pair
+                                  of HIP events that the runtime stamps with the start and the stop of that
+                                  dispatch on `stream` (hipExtLaunchKernel); read back with
+                                  fs_last_kernel_timing()                                                */
 } fs_options;
 
 /* ---- Blocking solves (Alg. 1).  Return the number of iterations performed (>= 0) or a

@@ -243,17 +243,17 @@ struct Solve {
     const char *dominant_kernel() const {
         return mode == 1 ? "k_row_stream" : mode == 2 ? (fused_is_fp32_cols() ? "k_fused_pf" : "k_fused") : "k_points_lse";
     }
-    // Eq. 9.  t0/t1 (optional) are recorded right before and after the dominant kernel of the
-    // iteration: the row pass, the fused pass, or the point-cloud LSE pass of the f-update.
+    // Eq. 9.  t0/t1 (optional) are stamped by the runtime with the start and stop of the dominant kernel
+    // of the iteration: the row pass, the fused pass, or the point-cloud LSE pass of the f-update.
     hipError_t enqueue_f_update(int phase, Kind kind, hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr) const {
         const Ctl c = ctl(phase);
         hipError_t e = hipSuccess;
-        if (t0) e = hipEventRecord(t0, st);
-        if (e != hipSuccess) return e;
-        if (mode == 3) e = launch_points_lse(st, points_f(), c, 0, L.m_ld);
-        else if (kind == STREAM) e = launch_dense_row(st, dense(STREAM), c);
-        else e = launch_dense_fused(st, dense(FUSED), c, opt.fused_variant);     // both half-steps
-        if (e == hipSuccess && t1) e = hipEventRecord(t1, st);
+        Stamp tm;
+        tm.t0 = t0;
+        tm.t1 = t1;
+        if (mode == 3) e = launch_points_lse(st, points_f(), c, 0, L.m_ld, tm);
+        else if (kind == STREAM) e = launch_dense_row(st, dense(STREAM), c, tm);
+        else e = launch_dense_fused(st, dense(FUSED), c, opt.fused_variant, tm);     // both half-steps
         if (mode == 3 && e == hipSuccess) {
             CombineArgs ca = combine_f(L.JSf, (const double *)(ws + L.o_part), (const double *)(ws + L.o_cx));
             if (points_optimistic(pr.d)) {      // the pass may have run optimistically: let the combine check it

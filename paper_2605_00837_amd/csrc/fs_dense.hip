@@ -180,12 +180,12 @@ void dense_stream_plan(int n, int m, int *P, int *rows_per_panel) {
     *rows_per_panel = rpp;
 }
 
-hipError_t launch_dense_row(hipStream_t st, const DenseArgs &a, const Ctl &c) {
+hipError_t launch_dense_row(hipStream_t st, const DenseArgs &a, const Ctl &c, const Stamp &tm) {
     const dim3 grid((a.p.n + kRowsPerWG - 1) / kRowsPerWG);
-    if (a.c_dtype == 1) hipLaunchKernelGGL((k_row_stream<8, 1>), grid, dim3(kStreamT), 0, st, a, c);
-    else if (a.c_dtype == 2) hipLaunchKernelGGL((k_row_stream<8, 2>), grid, dim3(kStreamT), 0, st, a, c);
-    else if (vec4_ok(a)) hipLaunchKernelGGL(k_row_stream<4>, grid, dim3(kStreamT), 0, st, a, c);
-    else hipLaunchKernelGGL(k_row_stream<1>, grid, dim3(kStreamT), 0, st, a, c);
+    if (a.c_dtype == 1) launch_stamped((k_row_stream<8, 1>), grid, dim3(kStreamT), st, tm, a, c);
+    else if (a.c_dtype == 2) launch_stamped((k_row_stream<8, 2>), grid, dim3(kStreamT), st, tm, a, c);
+    else if (vec4_ok(a)) launch_stamped(k_row_stream<4>, grid, dim3(kStreamT), st, tm, a, c);
+    else launch_stamped(k_row_stream<1>, grid, dim3(kStreamT), st, tm, a, c);
     return hipGetLastError();
 }
 
@@ -760,7 +760,7 @@ void dense_fused_plan(int n, int m, int *P) {
     *P = best;
 }
 
-hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, int variant) {
+hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, int variant, const Stamp &tm) {
     FusedShape s;
     if (!fused_shape(a.p.m, variant, a.c_dtype, &s)) return hipErrorInvalidValue;
     const int npanels = (a.p.n + (s.R % 100) - 1) / (s.R % 100);
@@ -774,31 +774,31 @@ hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, 
         const bool full = a.p.m == s.Q * 8192;
         const int key = (a.c_dtype == 1 ? 0 : 4) + (s.Q == 1 ? 0 : 2) + (full ? 0 : 1);
         switch (key) {
-        case 0: hipLaunchKernelGGL((k_fused_pf<1, 2, true, 1>), grid, dim3(1024), 0, st, b, c); break;
-        case 1: hipLaunchKernelGGL((k_fused_pf<1, 2, false, 1>), grid, dim3(1024), 0, st, b, c); break;
-        case 2: hipLaunchKernelGGL((k_fused_pf<2, 1, true, 1>), grid, dim3(1024), 0, st, b, c); break;
-        case 3: hipLaunchKernelGGL((k_fused_pf<2, 1, false, 1>), grid, dim3(1024), 0, st, b, c); break;
-        case 4: hipLaunchKernelGGL((k_fused_pf<1, 2, true, 2>), grid, dim3(1024), 0, st, b, c); break;
-        case 5: hipLaunchKernelGGL((k_fused_pf<1, 2, false, 2>), grid, dim3(1024), 0, st, b, c); break;
-        case 6: hipLaunchKernelGGL((k_fused_pf<2, 1, true, 2>), grid, dim3(1024), 0, st, b, c); break;
-        default: hipLaunchKernelGGL((k_fused_pf<2, 1, false, 2>), grid, dim3(1024), 0, st, b, c); break;
+        case 0: launch_stamped((k_fused_pf<1, 2, true, 1>), grid, dim3(1024), st, tm, b, c); break;
+        case 1: launch_stamped((k_fused_pf<1, 2, false, 1>), grid, dim3(1024), st, tm, b, c); break;
+        case 2: launch_stamped((k_fused_pf<2, 1, true, 1>), grid, dim3(1024), st, tm, b, c); break;
+        case 3: launch_stamped((k_fused_pf<2, 1, false, 1>), grid, dim3(1024), st, tm, b, c); break;
+        case 4: launch_stamped((k_fused_pf<1, 2, true, 2>), grid, dim3(1024), st, tm, b, c); break;
+        case 5: launch_stamped((k_fused_pf<1, 2, false, 2>), grid, dim3(1024), st, tm, b, c); break;
+        case 6: launch_stamped((k_fused_pf<2, 1, true, 2>), grid, dim3(1024), st, tm, b, c); break;
+        default: launch_stamped((k_fused_pf<2, 1, false, 2>), grid, dim3(1024), st, tm, b, c); break;
         }
         return hipGetLastError();
     }
-    if (s.R == 301 && s.Q == 3 && a.p.m == 12288) hipLaunchKernelGGL((k_fused_pf<3, 1, true>), grid, dim3(1024), 0, st, b, c);
-    else if (s.R == 301 && s.Q == 3) hipLaunchKernelGGL((k_fused_pf<3, 1, false>), grid, dim3(1024), 0, st, b, c);
-    else if (s.R == 301 && a.p.m == 16384) hipLaunchKernelGGL((k_fused_pf<4, 1, true>), grid, dim3(1024), 0, st, b, c);
-    else if (s.R == 301) hipLaunchKernelGGL((k_fused_pf<4, 1, false>), grid, dim3(1024), 0, st, b, c);
-    else if (s.R == 302 && s.Q == 1 && a.p.m == 4096) hipLaunchKernelGGL((k_fused_pf<1, 2, true>), grid, dim3(1024), 0, st, b, c);
-    else if (s.R == 302 && s.Q == 1) hipLaunchKernelGGL((k_fused_pf<1, 2, false>), grid, dim3(1024), 0, st, b, c);
-    else if (s.R == 302 && a.p.m == 8192 && variant % 100 != 5) hipLaunchKernelGGL((k_fused_pf<2, 2, true>), grid, dim3(1024), 0, st, b, c);
-    else if (s.R == 302) hipLaunchKernelGGL((k_fused_pf<2, 2, false>), grid, dim3(1024), 0, st, b, c);
-    else if (s.T == 256) hipLaunchKernelGGL((k_fused<256, 1, 4>), grid, dim3(256), 0, st, b, c);
-    else if (s.T == 1024 && s.Q == 1) hipLaunchKernelGGL((k_fused<1024, 1, 4>), grid, dim3(1024), 0, st, b, c);
-    else if (s.T == 1024 && s.R == 2) hipLaunchKernelGGL((k_fused<1024, 2, 2>), grid, dim3(1024), 0, st, b, c);
-    else if (s.T == 1024) hipLaunchKernelGGL((k_fused<1024, 2, 4>), grid, dim3(1024), 0, st, b, c);
-    else if (s.R == 2) hipLaunchKernelGGL((k_fused<512, 4, 2>), grid, dim3(512), 0, st, b, c);
-    else hipLaunchKernelGGL((k_fused<512, 4, 4>), grid, dim3(512), 0, st, b, c);
+    if (s.R == 301 && s.Q == 3 && a.p.m == 12288) launch_stamped((k_fused_pf<3, 1, true>), grid, dim3(1024), st, tm, b, c);
+    else if (s.R == 301 && s.Q == 3) launch_stamped((k_fused_pf<3, 1, false>), grid, dim3(1024), st, tm, b, c);
+    else if (s.R == 301 && a.p.m == 16384) launch_stamped((k_fused_pf<4, 1, true>), grid, dim3(1024), st, tm, b, c);
+    else if (s.R == 301) launch_stamped((k_fused_pf<4, 1, false>), grid, dim3(1024), st, tm, b, c);
+    else if (s.R == 302 && s.Q == 1 && a.p.m == 4096) launch_stamped((k_fused_pf<1, 2, true>), grid, dim3(1024), st, tm, b, c);
+    else if (s.R == 302 && s.Q == 1) launch_stamped((k_fused_pf<1, 2, false>), grid, dim3(1024), st, tm, b, c);
+    else if (s.R == 302 && a.p.m == 8192 && variant % 100 != 5) launch_stamped((k_fused_pf<2, 2, true>), grid, dim3(1024), st, tm, b, c);
+    else if (s.R == 302) launch_stamped((k_fused_pf<2, 2, false>), grid, dim3(1024), st, tm, b, c);
+    else if (s.T == 256) launch_stamped((k_fused<256, 1, 4>), grid, dim3(256), st, tm, b, c);
+    else if (s.T == 1024 && s.Q == 1) launch_stamped((k_fused<1024, 1, 4>), grid, dim3(1024), st, tm, b, c);
+    else if (s.T == 1024 && s.R == 2) launch_stamped((k_fused<1024, 2, 2>), grid, dim3(1024), st, tm, b, c);
+    else if (s.T == 1024) launch_stamped((k_fused<1024, 2, 4>), grid, dim3(1024), st, tm, b, c);
+    else if (s.R == 2) launch_stamped((k_fused<512, 4, 2>), grid, dim3(512), st, tm, b, c);
+    else launch_stamped((k_fused<512, 4, 4>), grid, dim3(512), st, tm, b, c);
     return hipGetLastError();
 }
 

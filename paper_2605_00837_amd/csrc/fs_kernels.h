@@ -1,6 +1,8 @@
 // Host-visible declarations of the kernel launchers (one translation unit per
 // kernel family; the C ABI in fs_api.hip drives them).
 #pragma once
+#include <hip/hip_ext.h>
+
 #include "fs_device.h"
 
 namespace fs {
@@ -90,13 +92,24 @@ hipError_t launch_advance(hipStream_t st, const ErrSrc &es, const Ctl &c);
 
 // Dense streaming kernels (any n, m).
 void dense_stream_plan(int n, int m, int *P, int *rows_per_panel);
-hipError_t launch_dense_row(hipStream_t st, const DenseArgs &a, const Ctl &c);
+// A pair of events that the runtime stamps with the start and the stop of ONE dispatch (both null: an
+// ordinary launch).  This is how the library times its dominant kernel: begin to end on the device, as a
+// kernel trace does, without the dispatch gap that events recorded around a launch include.
+struct Stamp {
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+};
+template <class... P, class... A>
+inline void launch_stamped(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t st, const Stamp &tm, const A &...args) {
+    if (tm.t0 && tm.t1) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, tm.t0, tm.t1, 0, static_cast<P>(args)...);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, st, static_cast<P>(args)...);
+}
+hipError_t launch_dense_row(hipStream_t st, const DenseArgs &a, const Ctl &c, const Stamp &tm = Stamp());
 hipError_t launch_dense_col(hipStream_t st, const DenseArgs &a, const Ctl &c);
 
 // Dense fused row-panel kernel (m limited by what a workgroup holds in registers).
 bool dense_fused_supported(int n, int m, const void *C, int c_dtype);
 void dense_fused_plan(int n, int m, int *P);
-hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, int variant);
+hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, int variant, const Stamp &tm = Stamp());
 int dense_fused_grid(int n, int m, int variant, int c_dtype);
 bool dense_fused_predicts(int m, int variant, int c_dtype);   // this shape / variant uses predicted column references
 
@@ -118,7 +131,8 @@ struct PointsArgs {
 void points_plan(int nr, int nc, int d, int *JS, int *cols_per_split);
 void points_plan_tiles(int nr, int nc, int d, int *JS, int *cols_per_split);   // same for the after-the-loop kernels
 bool points_optimistic(int d);      // does the LSE pass for this dimension have the optimistic (FAST) variant?
-hipError_t launch_points_lse(hipStream_t st, const PointsArgs &a, const Ctl &c, int use_next_shift, int ld_shift);
+hipError_t launch_points_lse(hipStream_t st, const PointsArgs &a, const Ctl &c, int use_next_shift, int ld_shift,
+                             const Stamp &tm = Stamp());
 hipError_t launch_points_prep(hipStream_t st, const float *X, int n, int d, double s, double *plain,
                               double *scaled, double *negsq);
 

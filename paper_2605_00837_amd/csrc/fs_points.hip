@@ -337,30 +337,31 @@ void points_plan_tiles(int nr, int nc, int d, int *JS, int *cols_per_split) {
     *cols_per_split = cps;
 }
 
-hipError_t launch_points_lse(hipStream_t st, const PointsArgs &a, const Ctl &c, int use_next_shift, int ld_shift) {
+hipError_t launch_points_lse(hipStream_t st, const PointsArgs &a, const Ctl &c, int use_next_shift, int ld_shift,
+                             const Stamp &tm) {
     if (a.d <= 4 && points_ib(a.nr) == 1) {
         const dim3 grid((a.nr + kPT - 1) / kPT, a.JS);
         switch (a.d) {
-            case 1: hipLaunchKernelGGL((k_points_lse<1, 1>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
-            case 2: hipLaunchKernelGGL((k_points_lse<2, 1>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
-            case 3: hipLaunchKernelGGL((k_points_lse<3, 1>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
-            default: hipLaunchKernelGGL((k_points_lse<4, 1>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
+            case 1: launch_stamped((k_points_lse<1, 1>), grid, dim3(kPT), st, tm, a, c, use_next_shift, ld_shift); break;
+            case 2: launch_stamped((k_points_lse<2, 1>), grid, dim3(kPT), st, tm, a, c, use_next_shift, ld_shift); break;
+            case 3: launch_stamped((k_points_lse<3, 1>), grid, dim3(kPT), st, tm, a, c, use_next_shift, ld_shift); break;
+            default: launch_stamped((k_points_lse<4, 1>), grid, dim3(kPT), st, tm, a, c, use_next_shift, ld_shift); break;
         }
     } else if (a.d <= 4) {
         const dim3 grid((a.nr + kPT * kIB - 1) / (kPT * kIB), a.JS);
         switch (a.d) {
-            case 1: hipLaunchKernelGGL((k_points_lse<1, kIB>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
-            case 2: hipLaunchKernelGGL((k_points_lse<2, kIB>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
-            case 3: hipLaunchKernelGGL((k_points_lse<3, kIB>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
-            default: hipLaunchKernelGGL((k_points_lse<4, kIB>), grid, dim3(kPT), 0, st, a, c, use_next_shift, ld_shift); break;
+            case 1: launch_stamped((k_points_lse<1, kIB>), grid, dim3(kPT), st, tm, a, c, use_next_shift, ld_shift); break;
+            case 2: launch_stamped((k_points_lse<2, kIB>), grid, dim3(kPT), st, tm, a, c, use_next_shift, ld_shift); break;
+            case 3: launch_stamped((k_points_lse<3, kIB>), grid, dim3(kPT), st, tm, a, c, use_next_shift, ld_shift); break;
+            default: launch_stamped((k_points_lse<4, kIB>), grid, dim3(kPT), st, tm, a, c, use_next_shift, ld_shift); break;
         }
     } else {
         const int d4 = a.d <= 8 ? 2 : a.d <= 16 ? 4 : a.d <= 32 ? 8 : 16;
         const dim3 grid((a.nr + mfma_rows(d4) - 1) / mfma_rows(d4), a.JS);
-        if (a.d <= 8) hipLaunchKernelGGL(k_points_mfma<2>, grid, dim3(256), 0, st, a, c, use_next_shift, ld_shift);
-        else if (a.d <= 16) hipLaunchKernelGGL(k_points_mfma<4>, grid, dim3(256), 0, st, a, c, use_next_shift, ld_shift);
-        else if (a.d <= 32) hipLaunchKernelGGL(k_points_mfma<8>, grid, dim3(256), 0, st, a, c, use_next_shift, ld_shift);
-        else hipLaunchKernelGGL(k_points_mfma<16>, grid, dim3(256), 0, st, a, c, use_next_shift, ld_shift);
+        if (a.d <= 8) launch_stamped(k_points_mfma<2>, grid, dim3(256), st, tm, a, c, use_next_shift, ld_shift);
+        else if (a.d <= 16) launch_stamped(k_points_mfma<4>, grid, dim3(256), st, tm, a, c, use_next_shift, ld_shift);
+        else if (a.d <= 32) launch_stamped(k_points_mfma<8>, grid, dim3(256), st, tm, a, c, use_next_shift, ld_shift);
+        else launch_stamped(k_points_mfma<16>, grid, dim3(256), st, tm, a, c, use_next_shift, ld_shift);
     }
     return hipGetLastError();
 }
