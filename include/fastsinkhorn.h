@@ -76,7 +76,9 @@ typedef enum {
 typedef struct {
     int32_t iters;         /* iterations performed (f- and g-update pairs)               */
     int32_t converged;     /* 1 iff the tolerance test of Alg. 1 fired                   */
-    int32_t nonfinite;     /* 1 iff some returned potential is NaN or +-inf              */
+    int32_t nonfinite;     /* 1 iff some returned potential is NaN or +-inf; 2: a solver
+                              requested with kernel_mode 4 or 5 gave up waiting (see there),
+                              the potentials are not valid                                */
     float   marginal_err;  /* err after `iters` iterations; NaN if it was not evaluated  */
 } fs_result;
 
@@ -94,10 +96,16 @@ typedef struct {
                                 and a dense fp32 cost, or point clouds up to about n * m = 2^19 - exactly:
                                 roundup(n / 128, power of 2) * roundup(m / 256, power of 2) <= 16 - whose squared
                                 distances are then formed once in fp64; else FS_ERR_UNSUPPORTED; what 0 picks
-                                from there up to 2^18 entries or pairs).  Its workgroups wait for one another with a bounded number of
-                                polls: should the device keep some of them from running for seconds, the
-                                solve gives up and reports nonfinite = 1 (potentials then invalid: NaN in
-                                the parts of the workgroups that had stopped), never a silent wrong result   */
+                                from there up to 2^18 entries or pairs);
+                                5: the whole solve in one launch over up to one workgroup per compute unit,
+                                two grid-wide exchanges per iteration (dense fp32, n <= 4096, m <= 2048, at most
+                                16 entries of C per lane; else FS_ERR_UNSUPPORTED; what 0 picks beyond 2^18
+                                entries in the blocking solves).
+                                The workgroups of 4 and 5 wait for one another with a bounded number of polls:
+                                should the device keep some of them from running for seconds (other work on
+                                its compute units), the solve gives up and reports nonfinite = 2, never a
+                                silent wrong result.  When the kernel was the library's own choice (0) a
+                                blocking solve then simply runs the multi-kernel driver instead             */
     int32_t use_graph;       /* 0: automatic; 1: plain stream launches; 2: hipGraph iteration blocks  */
     int32_t skip_final_err;  /* 1: do not spend the one trailing pass that evaluates err after the
                                 last iteration when no stop fired (marginal_err is then NaN)          */

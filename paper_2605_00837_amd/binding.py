@@ -239,7 +239,7 @@ def fs_sinkhorn_solve(a, b, eps, max_iter, tol, C=None, X=None, Y=None, f=None, 
     it = _check(_lib.fs_sinkhorn_solve(Cp, _p(X), _p(Y), d, _p(a), _p(b), n, m, float(eps), int(max_iter),
                                        float(tol), _p(f), _p(g), _stream(), ctypes.byref(o), ctypes.byref(res)))
     out = dict(f=f, g=g, iters=it, converged=bool(res.converged), nonfinite=bool(res.nonfinite),
-               marginal_err=float(res.marginal_err))
+               gave_up=res.nonfinite == 2, marginal_err=float(res.marginal_err))
     if want_f64:
         out.update(f64=f64, g64=g64)
     return out

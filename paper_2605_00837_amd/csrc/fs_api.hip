@@ -55,6 +55,8 @@ struct Layout {
     size_t o_state, o_F, o_U, o_G, o_V, o_la2, o_lb2, o_part, o_part2;
     size_t o_Xp, o_Xs, o_cx, o_Yp, o_Ys, o_cy;
     size_t o_coop;         // scratch of the one-launch solver for mid-size dense problems (0: none)
+    size_t o_grid;         // scratch of the one-launch solver over the whole chip (0: none)
+    size_t o_start;        // [2][n_ld | m_ld] floats: starting potentials of an in-place warm start, kept for a second attempt
     size_t total;
 };
 
@@ -79,6 +81,7 @@ Layout make_layout(int n, int m, int d) {
         L.o_part = take(sizeof(double) * (size_t)Pmax * L.m_ld);
         L.o_part2 = L.o_part;
         if (coop_supported(n, m)) L.o_coop = take(coop_scratch_bytes());
+        if (grid_supported(n, m, kGridWMax)) L.o_grid = take(grid_scratch_bytes());
     } else {
         points_plan(n, m, d, &L.JSf, &L.cpsf);
         points_plan(m, n, d, &L.JSg, &L.cpsg);
@@ -92,6 +95,7 @@ Layout make_layout(int n, int m, int d) {
         if (coop_points_supported(n, m)) L.o_coop = take(coop_scratch_bytes());
         L.o_cy = take(sizeof(double) * L.m_ld);
     }
+    L.o_start = take(sizeof(float) * ((size_t)L.n_ld + L.m_ld));
     L.total = off;
     return L;
 }
@@ -548,7 +552,7 @@ fs_status check_options(const Problem &pr, const fs_options *opts) {
     if (!opts) return FS_OK;
     if (opts->cost_dtype < 0 || opts->cost_dtype > 2) { set_err("cost_dtype must be FS_COST_F32, FS_COST_F16 or FS_COST_BF16"); return FS_ERR_INVALID_ARG; }
     if (opts->cost_dtype != 0 && !pr.C) { set_err("cost_dtype applies to a dense cost matrix only"); return FS_ERR_INVALID_ARG; }
-    if (opts->kernel_mode < 0 || opts->kernel_mode > 4) { set_err("kernel_mode must be 0, 1, 2, 3 or 4"); return FS_ERR_INVALID_ARG; }
+    if (opts->kernel_mode < 0 || opts->kernel_mode > 5) { set_err("kernel_mode must be 0 ... 5"); return FS_ERR_INVALID_ARG; }
     return FS_OK;
 }
 
@@ -586,6 +590,38 @@ bool coop_path(const Problem &pr, const fs_options *opts, fs_status *err) {
     // the multi-kernel driver (5.6 against 11.3 us per iteration at 256 x 256, 8.4 against 12.7 at 512 x 512);
     // beyond that too few compute units are at work
     return km == 0 && (size_t)pr.n * (size_t)pr.m <= ((size_t)1 << 18);
+}
+
+// Compute units of the current device: the whole-chip one-launch solver needs one per workgroup.
+int device_cus() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return cus;
+}
+
+// Dense problems up to 4096 x 4096 can run whole inside one kernel spread over the chip (fs_grid.hip).
+bool grid_path(const Problem &pr, const fs_options *opts, bool blocking, fs_status *err, int *wmax) {
+    const int km = opts ? opts->kernel_mode : 0;
+    if (km != 5 && km != 0) return false;
+    if (!pr.C || (opts && opts->cost_dtype != 0) || pr.n > kGridMaxN || pr.m > kGridMaxM) {
+        if (km == 0) return false;
+        set_err("kernel_mode 5 needs a dense fp32 cost matrix with n <= %d, m <= %d", kGridMaxN, kGridMaxM);
+        *err = FS_ERR_UNSUPPORTED;
+        return false;
+    }
+    *wmax = device_cus();
+    if (!grid_supported(pr.n, pr.m, *wmax)) {
+        if (km == 0) return false;
+        set_err("kernel_mode 5 takes at most 16 entries per lane (n / compute units, rounded up to a power of 2, times m / 1024) and at most 16 columns per workgroup");
+        *err = FS_ERR_UNSUPPORTED;
+        return false;
+    }
+    if (opts && opts->time_kernel_every > 0) return false;
+    if (km == 5) return true;
+    // automatic: it needs every compute unit of the chip at the same moment, so the library only picks it where
+    // it can fall back (blocking solves), and only beyond the sizes of the 32-workgroup kernel
+    return blocking && (size_t)pr.n * (size_t)pr.m > ((size_t)1 << 18);
 }
 
 fs_status small_args(const Problem &pr, int batch, const fs_options *opts, float *f, float *g, SmallArgs *out) {
@@ -639,21 +675,53 @@ int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const 
     DeviceCache *dc = nullptr;
     v = get_cache(L.total, &dc);
     if (v != FS_OK) return v;
-    if (coop_path(pr, opts, &serr)) {
+    // The one-launch solvers for mid-size problems.  Their workgroups wait for one another; should the device
+    // keep part of a grid from running for seconds (other work holding its compute units) the solve gives up
+    // and says so.  When the kernel was the library's own choice the problem is then simply solved again by
+    // the multi-kernel driver; the starting potentials of an in-place warm start are kept for that.
+    int wmax = 0;
+    const bool coop = coop_path(pr, opts, &serr);
+    if (serr != FS_OK) return serr;
+    const bool grid = !coop && grid_path(pr, opts, /*blocking=*/true, &serr, &wmax);
+    if (serr != FS_OK) return serr;
+    if (coop || grid) {
+        const bool own_choice = !opts || opts->kernel_mode == 0;
+        const bool in_place = opts && opts->warm_start && !(opts->f64_in && opts->g64_in);
+        float *keep = (float *)((char *)dc->ws + L.o_start);
+        if (own_choice && in_place) {
+            FS_HIP(hipMemcpyAsync(keep, f, sizeof(float) * pr.n, hipMemcpyDeviceToDevice, st));
+            FS_HIP(hipMemcpyAsync(keep + L.n_ld, g, sizeof(float) * pr.m, hipMemcpyDeviceToDevice, st));
+        }
         HostBlock *hb = dc->host;
         memset((void *)&hb->res, 0, sizeof(hb->res));
         void *hb_dev = nullptr;
         FS_HIP(hipHostGetDevicePointer(&hb_dev, (void *)hb, 0));
-        CoopArgs A{};
-        v = small_args(pr, 1, opts, f, g, &A);
-        if (v != FS_OK) return v;
-        A.result = (ResultRecord *)((char *)hb_dev + offsetof(HostBlock, res));
-        A.spin_limit = opts ? opts->wait_limit : 0;
-        A.X = pr.X; A.Y = pr.Y; A.d = pr.C ? 0 : pr.d;
-        FS_HIP(launch_coop(st, A, (char *)dc->ws + L.o_coop, opts ? opts->fused_variant : 0));
+        ResultRecord *res_dev = (ResultRecord *)((char *)hb_dev + offsetof(HostBlock, res));
+        if (coop) {
+            CoopArgs A{};
+            v = small_args(pr, 1, opts, f, g, &A);
+            if (v != FS_OK) return v;
+            A.result = res_dev;
+            A.spin_limit = opts ? opts->wait_limit : 0;
+            A.X = pr.X; A.Y = pr.Y; A.d = pr.C ? 0 : pr.d;
+            FS_HIP(launch_coop(st, A, (char *)dc->ws + L.o_coop, opts ? opts->fused_variant : 0));
+        } else {
+            GridArgs A{};
+            v = small_args(pr, 1, opts, f, g, &A);
+            if (v != FS_OK) return v;
+            A.result = res_dev;
+            A.spin_limit = opts ? opts->wait_limit : 0;
+            FS_HIP(launch_grid(st, A, (char *)dc->ws + L.o_grid, wmax));
+        }
         FS_HIP(hipStreamSynchronize(st));
-        if (result_host) *result_host = hb->res;
-        return hb->res.iters;
+        if (!(own_choice && hb->res.nonfinite == kGaveUp)) {
+            if (result_host) *result_host = hb->res;
+            return hb->res.iters;
+        }
+        if (in_place) {
+            FS_HIP(hipMemcpyAsync(f, keep, sizeof(float) * pr.n, hipMemcpyDeviceToDevice, st));
+            FS_HIP(hipMemcpyAsync(g, keep + L.n_ld, sizeof(float) * pr.m, hipMemcpyDeviceToDevice, st));
+        }
     }
     if (serr != FS_OK) return serr;
     Solve S;
@@ -692,6 +760,20 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
         A.spin_limit = opts ? opts->wait_limit : 0;
         A.X = pr.X; A.Y = pr.Y; A.d = pr.C ? 0 : pr.d;
         FS_HIP(launch_coop(st, A, (char *)ws + L.o_coop, opts ? opts->fused_variant : 0));
+        return FS_OK;
+    }
+    if (serr != FS_OK) return serr;
+    int wmax = 0;
+    if (grid_path(pr, opts, /*blocking=*/false, &serr, &wmax)) {
+        const Layout L = make_layout(pr.n, pr.m, 0);
+        if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) { set_err("workspace must be non-null and 256-byte aligned"); return FS_ERR_WORKSPACE; }
+        if (ws_bytes < L.total) { set_err("workspace too small: %zu < %zu bytes", ws_bytes, L.total); return FS_ERR_WORKSPACE; }
+        GridArgs A{};
+        v = small_args(pr, 1, opts, f, g, &A);
+        if (v != FS_OK) return v;
+        A.result = (ResultRecord *)result_dev;
+        A.spin_limit = opts ? opts->wait_limit : 0;
+        FS_HIP(launch_grid(st, A, (char *)ws + L.o_grid, wmax));
         return FS_OK;
     }
     if (serr != FS_OK) return serr;

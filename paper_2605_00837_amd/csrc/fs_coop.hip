@@ -317,7 +317,7 @@ __global__ __launch_bounds__(kCT) void k_coop(CoopArgs A) {
         ResultRecord r;
         r.iters = alive ? iters : k;
         r.converged = alive ? converged : 0;
-        r.nonfinite = alive ? (int)__hip_atomic_load(&A.sync->bad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1;
+        r.nonfinite = alive ? (int)__hip_atomic_load(&A.sync->bad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : kGaveUp;
         r.marginal_err = alive ? (float)err_out : __builtin_nanf("");
         A.result[0] = r;
         __threadfence_system();

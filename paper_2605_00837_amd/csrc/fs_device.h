@@ -123,7 +123,7 @@ __device__ __forceinline__ float cost_entry(const float *C, int dtype, size_t id
 // use converts its 4-byte register afresh.  Without it the compiler keeps all converted values of a lane's
 // tile alive (twice the registers) across the two half-steps, or hoists them out of the iteration loop,
 // and spills.
-__device__ __forceinline__ double cost_f64(float c) {
+__device__ __forceinline__ double cost_f64(float &c) {       // by reference: the barrier acts on the register itself
 #if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("" : "+v"(c));
 #endif

@@ -168,6 +168,7 @@ hipError_t launch_bary(hipStream_t st, const PlanArgs &a, const float *Z, int dz
 // Whole solve of small dense problems in one launch (one workgroup per problem).
 constexpr int kSmallMax = 256;
 struct ResultRecord { int32_t iters, converged, nonfinite; float marginal_err; };    // = fs_result
+constexpr int32_t kGaveUp = 2;                   // ResultRecord::nonfinite of a one-launch solve that abandoned a wait
 struct SmallArgs {
     const float *C, *a, *b;          // [batch][n][m], [batch][n], [batch][m]
     int32_t n, m, batch;
@@ -207,5 +208,21 @@ bool coop_points_supported(int n, int m);
 size_t coop_scratch_bytes();                     // device scratch (256-byte aligned) one solve needs
 // variant 0: up to 32 workgroups; 1, 2, 3: at most 16, 8, 4 (more rows per lane)
 hipError_t launch_coop(hipStream_t st, const CoopArgs &a, void *scratch, int variant);
+
+// ---- dense problems up to 4096 x 2048: the whole solve in one launch over up to 256 workgroups, two
+//      grid-wide waits per iteration (fs_grid.hip)
+constexpr int kGridMaxN = 4096, kGridMaxM = 2048;
+constexpr int kGridWMax = 256;                   // most workgroups (each needs a compute unit of its own)
+struct GridLine { unsigned long long v; unsigned long long pad[31]; };      // 256 bytes
+struct GridSync { GridLine grp[8], top, release, abort_flag, bad; };
+struct GridArgs : SmallArgs {                    // batch is ignored (one problem)
+    double *xchg1;                               // [W][ldx]: column partials of every workgroup; last slot: error partial
+    double *xchg2;                               // [ldx]: the new V, written strip by strip
+    GridSync *sync;
+    int32_t ldx, spin_limit;
+};
+bool grid_supported(int n, int m, int wmax);     // wmax: workgroups that can be resident at once (compute units)
+size_t grid_scratch_bytes();
+hipError_t launch_grid(hipStream_t st, const GridArgs &a, void *scratch, int wmax);
 
 }  // namespace fs

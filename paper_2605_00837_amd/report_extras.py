@@ -61,10 +61,12 @@ def main():
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
             print(f"| {n} x {n}, {name} | 2000 | {dt * 1e3:.2f} | {dt / 2000 * 1e6:.2f} us |", flush=True)
-    for n in (256, 384, 512, 1024):
+    for n in (256, 384, 512, 1024, 2048):
         w = W.random_dense(n, n, seed=1, cmax=1.0, eps=0.05)
         C, a, b = (torch.from_numpy(t).cuda() for t in (w.C, w.a, w.b))
-        for mode, name in ((4, "one launch over several workgroups"), (2, "multi-kernel path")):
+        for mode, name in ((4, "one launch, up to 32 workgroups"), (5, "one launch, whole chip"), (2, "multi-kernel path")):
+            if mode == 4 and n > 1024:
+                continue
             fs.fs_sinkhorn_solve(a, b, w.eps, 10, 0.0, C=C, kernel_mode=mode)
             torch.cuda.synchronize()
             t0 = time.perf_counter()

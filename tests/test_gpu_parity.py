@@ -514,6 +514,101 @@ def test_coop_kernel_stop_rule_history_and_resume(fs, oracle):
                              Y=torch.zeros(1024, 3, device="cuda"), kernel_mode=4)
 
 
+# ------------------------------------------------------------------ one launch over the whole chip (n, m <= 4096)
+@pytest.mark.parametrize("n,m,iters", [(1, 1, 20), (5, 7, 20), (257, 300, 20), (1024, 1024, 12), (1000, 2048, 12),
+                                       (300, 2000, 12), (4000, 300, 12), (2048, 2048, 8), (4096, 1024, 8),
+                                       (3000, 777, 8), (1500, 1025, 8)])
+def test_grid_kernel_matches_oracle(fs, oracle, n, m, iters):
+    """kernel_mode = 5: the whole solve in one launch over up to 256 workgroups, C in registers, two grid-wide
+    waits per iteration."""
+    w = W.random_dense(n, m, seed=7900 + n + m, cmax=2.0, eps=0.02)
+    if n > 8:
+        w.a[2::9] = 0.0
+        w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, iters, kernel_mode=5)
+    assert e64 < TOL_F64 and e32 < TOL_F32, (e64, e32)
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+
+
+def test_grid_kernel_stop_rule_history_and_resume(fs, oracle):
+    import torch
+    w = W.random_dense(600, 1300, seed=7950, cmax=1.0, eps=0.05)
+    geo, a, b = to_dev(w)
+    ref = oracle.solve(w.a, w.b, w.eps, 400, tol=1e-5, check_every=7, C=w.C, err_every_iter=True)
+    hist = torch.full((400,), float("nan"), dtype=torch.float32, device="cuda")
+    r = fs.fs_sinkhorn_solve(a, b, w.eps, 400, 1e-5, C=geo["C"], want_f64=True, check_every=7, kernel_mode=5,
+                             err_history=hist)
+    assert r["converged"] and ref["converged"]
+    assert abs(r["iters"] - int(ref["iters"])) <= 7 and r["iters"] % 7 == 0
+    k = r["iters"]
+    refk = oracle.solve(w.a, w.b, w.eps, k, C=w.C)
+    assert pot_err(r["f64"].cpu().numpy(), refk["f"], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), refk["g"], w.eps) < TOL_F64
+    h = hist.cpu().numpy()
+    eh = np.asarray(ref["err_hist"], dtype=np.float64)
+    upto = min(k, int(ref["iters"]))
+    assert np.all(np.isfinite(h[:upto]))
+    assert np.allclose(h[:upto], eh[:upto], rtol=2e-3, atol=5e-7)
+    assert np.all(np.isnan(h[k:]))
+    rm = fs.fs_sinkhorn_solve(a, b, w.eps, 400, 1e-5, C=geo["C"], want_f64=True, check_every=7, kernel_mode=1)
+    assert rm["iters"] == k and float((rm["f64"] - r["f64"]).abs().max()) / w.eps < TOL_F64
+    # fixed count without the trailing error pass; resume from fp64 potentials = one longer run
+    r1 = fs.fs_sinkhorn_solve(a, b, w.eps, 11, 0.0, C=geo["C"], want_f64=True, kernel_mode=5, skip_final_err=True)
+    assert math.isnan(r1["marginal_err"]) and r1["iters"] == 11
+    r2 = fs.fs_sinkhorn_solve(a, b, w.eps, 9, 0.0, C=geo["C"], want_f64=True, kernel_mode=5, warm_start=True,
+                              f64_in=r1["f64"], g64_in=r1["g64"])
+    r3 = fs.fs_sinkhorn_solve(a, b, w.eps, 20, 0.0, C=geo["C"], want_f64=True, kernel_mode=5)
+    assert float((r2["f64"] - r3["f64"]).abs().max()) / w.eps < 1e-9
+    assert float((r2["g64"] - r3["g64"]).abs().max()) / w.eps < 1e-9
+    r4 = fs.fs_sinkhorn_solve(a, b, w.eps, 20, 0.0, C=geo["C"], want_f64=True, kernel_mode=5)
+    assert torch.equal(r3["f64"], r4["f64"]) and torch.equal(r3["g64"], r4["g64"])
+    h5 = fs.fs_sinkhorn_dense_ex(geo["C"], a, b, w.eps, 20, 0.0, kernel_mode=5)
+    res5 = h5.result()
+    assert res5["iters"] == 20 and torch.equal(h5.f, r3["f"]) and torch.equal(h5.g, r3["g"])
+    r0 = fs.fs_sinkhorn_solve(a, b, w.eps, 0, 0.0, C=geo["C"], kernel_mode=5)
+    assert r0["iters"] == 0 and float(r0["f"].abs().max()) == 0.0 and float(r0["g"].abs().max()) == 0.0
+    # a forced give-up is clean, and the next solve is unaffected
+    rg = fs.fs_sinkhorn_solve(a, b, w.eps, 30, 0.0, C=geo["C"], kernel_mode=5, wait_limit=1)
+    assert rg["nonfinite"] or rg["iters"] == 30
+    r6 = fs.fs_sinkhorn_solve(a, b, w.eps, 20, 0.0, C=geo["C"], want_f64=True, kernel_mode=5)
+    assert torch.equal(r3["f64"], r6["f64"])
+    # shapes it does not take: too few rows for that many columns, too many entries per lane
+    u16 = torch.full((16,), 1 / 16, device="cuda")
+    with pytest.raises(fs.FsError, match="kernel_mode 5"):
+        fs.fs_sinkhorn_solve(u16, torch.full((2048,), 1 / 2048, device="cuda"), w.eps, 3, 0.0,
+                             C=torch.zeros(16, 2048, device="cuda"), kernel_mode=5)
+    u4k = torch.full((4096,), 1 / 4096, device="cuda")
+    with pytest.raises(fs.FsError, match="kernel_mode 5"):
+        fs.fs_sinkhorn_solve(u4k, torch.full((2048,), 1 / 2048, device="cuda"), w.eps, 3, 0.0,
+                             C=torch.zeros(4096, 2048, device="cuda"), kernel_mode=5)
+
+
+@pytest.mark.parametrize("n,m,warm", [(300, 410, False), (1000, 1200, False), (900, 1100, True)])
+def test_one_launch_solvers_fall_back_when_they_give_up(fs, oracle, n, m, warm):
+    """Automatic mode with wait_limit = 1: the library's own choice of a one-launch kernel almost surely gives
+    up on its first wait; the blocking solve must then deliver the right answer through the multi-kernel driver,
+    also when the starting potentials were passed in place."""
+    import torch
+    w = W.random_dense(n, m, seed=8100 + n, cmax=1.0, eps=0.05)
+    geo, a, b = to_dev(w)
+    kw = {}
+    f0 = g0 = None
+    if warm:
+        rng = np.random.default_rng(5)
+        f0 = (rng.standard_normal(n) * 0.1).astype(np.float32)
+        g0 = (rng.standard_normal(m) * 0.1).astype(np.float32)
+        kw = dict(f=dev(f0), g=dev(g0), warm_start=True)
+    r = fs.fs_sinkhorn_solve(a, b, w.eps, 25, 0.0, C=geo["C"], want_f64=True, wait_limit=1, **kw)
+    ref = oracle.solve(w.a, w.b, w.eps, 25, C=w.C, f0=f0, g0=g0) if warm else oracle.solve(w.a, w.b, w.eps, 25, C=w.C)
+    assert r["iters"] == 25 and not r["nonfinite"] and not r["gave_up"]
+    assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+    # asked for by name, the same kernel reports that it gave up (or, with luck, finishes)
+    rk = fs.fs_sinkhorn_solve(a, b, w.eps, 25, 0.0, C=geo["C"], kernel_mode=4 if n * m <= 1 << 18 else 5, wait_limit=1)
+    assert rk["gave_up"] or (rk["iters"] == 25 and not rk["nonfinite"])
+
+
 def test_coop_kernel_bounded_wait_gives_up_cleanly(fs, oracle):
     """wait_limit = 1: a workgroup stops waiting for the others after a single poll.  Whether that is enough
     depends on timing, so either outcome is legal - but nothing in between: the solve is either complete and
