@@ -206,7 +206,7 @@ __global__ __launch_bounds__(kCT) void k_coop(CoopArgs A) {
                 sF[nxt][li] = fn;
                 if (need_err) {
                     const float wgt = sAw[li];
-                    if (wgt > 0.0f) e = (double)wgt * fabs(expm1((fn - sF[cur][li]) * 0.6931471805599453094));
+                    if (wgt > 0.0f) e = (double)wgt * fabs(exp2m1(fn - sF[cur][li]));
                 }
             }
             if (wr == 0) {                     // lanes 0 .. RA-1 of the first wave of the row group hold the terms

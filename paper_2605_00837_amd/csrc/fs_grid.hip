@@ -59,15 +59,6 @@ __device__ __forceinline__ float row16_add(float v) {
     return v;
 }
 
-// 2^d - 1 with a relative error below 2e-7 and few registers (the library routine would cost this kernel,
-// whose lanes hold up to 64 matrix entries, its register budget): a short series where the result is
-// small, v_exp_f32 elsewhere.
-__device__ __forceinline__ double exp2m1(double d) {
-    const double t = d * 0.6931471805599453094;
-    if (fabs(t) < 0.00390625) return t * (1.0 + t * (0.5 + t * (1.0 / 6.0 + t * (1.0 / 24.0))));
-    return (double)fast_exp2((float)d) - 1.0;
-}
-
 // Grid-wide wait number `gen` (1, 2, ...).  Every thread of the workgroup calls it after its last store
 // of the phase.  Returns false when the wait was abandoned (by this workgroup or by another).
 __device__ __forceinline__ bool grid_wait(GridSync *sy, unsigned long long gen, int W, int spin_limit, int *s_ok) {

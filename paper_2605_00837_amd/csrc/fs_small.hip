@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kST) void k_small(SmallArgs A) {
             if (tid < kSmallMax) {
                 if (tid < n) {
                     const float w = aw[tid];
-                    if (w > 0.0f) errloc = (double)w * fabs(expm1((sF[nxt][tid] - sF[cur][tid]) * 0.6931471805599453094));
+                    if (w > 0.0f) errloc = (double)w * fabs(exp2m1(sF[nxt][tid] - sF[cur][tid]));
                 }
                 errloc = wave_sum_f64(errloc);
                 if (lane == 0) sErr[wave] = errloc;
