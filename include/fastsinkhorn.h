@@ -96,11 +96,12 @@ typedef struct {
                                 and a dense fp32 cost, or point clouds up to about n * m = 2^19 - exactly:
                                 roundup(n / 128, power of 2) * roundup(m / 256, power of 2) <= 16 - whose squared
                                 distances are then formed once in fp64; else FS_ERR_UNSUPPORTED; what 0 picks
-                                from there up to 2^18 entries or pairs);
+                                from there up to 2^18 entries or pairs - in the blocking dense solves only up
+                                to 512 x 512, see 5);
                                 5: the whole solve in one launch over up to one workgroup per compute unit,
                                 two grid-wide exchanges per iteration (dense fp32, n <= 4096, m <= 2048, at most
-                                16 entries of C per lane; else FS_ERR_UNSUPPORTED; what 0 picks beyond 2^18
-                                entries in the blocking solves).
+                                16 entries of C per lane; else FS_ERR_UNSUPPORTED; what 0 picks in the blocking
+                                solves for every such problem with n or m above 512).
                                 The workgroups of 4 and 5 wait for one another with a bounded number of polls:
                                 should the device keep some of them from running for seconds (other work on
                                 its compute units), the solve gives up and reports nonfinite = 2, never a
