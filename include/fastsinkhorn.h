@@ -99,9 +99,10 @@ typedef struct {
                                 from there up to 2^18 entries or pairs - in the blocking dense solves only up
                                 to 512 x 512, see 5);
                                 5: the whole solve in one launch over up to one workgroup per compute unit,
-                                two grid-wide exchanges per iteration (dense fp32, n <= 4096, m <= 2048, at most
-                                16 entries of C per lane; else FS_ERR_UNSUPPORTED; what 0 picks in the blocking
-                                solves for every such problem with n or m above 512).
+                                two grid-wide exchanges per iteration (n <= 4096, m <= 2048; dense fp32 with at
+                                most 16 entries of C per lane, or point clouds with at most 8 pairs per lane;
+                                else FS_ERR_UNSUPPORTED; what 0 picks in the blocking solves for every such
+                                problem with n or m above 512).
                                 The workgroups of 4 and 5 wait for one another with a bounded number of polls:
                                 should the device keep some of them from running for seconds (other work on
                                 its compute units), the solve gives up and reports nonfinite = 2, never a

@@ -81,7 +81,7 @@ Layout make_layout(int n, int m, int d) {
         L.o_part = take(sizeof(double) * (size_t)Pmax * L.m_ld);
         L.o_part2 = L.o_part;
         if (coop_supported(n, m)) L.o_coop = take(coop_scratch_bytes());
-        if (grid_supported(n, m, kGridWMax)) L.o_grid = take(grid_scratch_bytes());
+        if (grid_supported(n, m, kGridWMax, false)) L.o_grid = take(grid_scratch_bytes());
     } else {
         points_plan(n, m, d, &L.JSf, &L.cpsf);
         points_plan(m, n, d, &L.JSg, &L.cpsg);
@@ -93,6 +93,7 @@ Layout make_layout(int n, int m, int d) {
         L.o_Yp = take(sizeof(double) * (size_t)m * d);
         L.o_Ys = take(sizeof(double) * (size_t)m * d);
         if (coop_points_supported(n, m)) L.o_coop = take(coop_scratch_bytes());
+        if (grid_supported(n, m, kGridWMax, true)) L.o_grid = take(grid_scratch_bytes());
         L.o_cy = take(sizeof(double) * L.m_ld);
     }
     L.o_start = take(sizeof(float) * ((size_t)L.n_ld + L.m_ld));
@@ -604,16 +605,16 @@ int device_cus() {
 bool grid_path(const Problem &pr, const fs_options *opts, bool blocking, fs_status *err, int *wmax) {
     const int km = opts ? opts->kernel_mode : 0;
     if (km != 5 && km != 0) return false;
-    if (!pr.C || (opts && opts->cost_dtype != 0) || pr.n > kGridMaxN || pr.m > kGridMaxM) {
+    if ((opts && opts->cost_dtype != 0) || pr.n > kGridMaxN || pr.m > kGridMaxM) {
         if (km == 0) return false;
-        set_err("kernel_mode 5 needs a dense fp32 cost matrix with n <= %d, m <= %d", kGridMaxN, kGridMaxM);
+        set_err("kernel_mode 5 needs n <= %d, m <= %d and a dense fp32 cost matrix or point clouds", kGridMaxN, kGridMaxM);
         *err = FS_ERR_UNSUPPORTED;
         return false;
     }
     *wmax = device_cus();
-    if (!grid_supported(pr.n, pr.m, *wmax)) {
+    if (!grid_supported(pr.n, pr.m, *wmax, pr.C == nullptr)) {
         if (km == 0) return false;
-        set_err("kernel_mode 5 takes at most 16 entries per lane (n / compute units, rounded up to a power of 2, times m / 1024) and at most 16 columns per workgroup");
+        set_err("kernel_mode 5 takes at most 16 entries per lane (8 for point clouds: n / compute units, rounded up to a power of 2, times m / 1024) and at most 16 columns per workgroup");
         *err = FS_ERR_UNSUPPORTED;
         return false;
     }
@@ -712,6 +713,7 @@ int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const 
             if (v != FS_OK) return v;
             A.result = res_dev;
             A.spin_limit = opts ? opts->wait_limit : 0;
+            A.X = pr.X; A.Y = pr.Y; A.d = pr.C ? 0 : pr.d;
             FS_HIP(launch_grid(st, A, (char *)dc->ws + L.o_grid, wmax));
         }
         FS_HIP(hipStreamSynchronize(st));
@@ -766,7 +768,7 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
     if (serr != FS_OK) return serr;
     int wmax = 0;
     if (grid_path(pr, opts, /*blocking=*/false, &serr, &wmax)) {
-        const Layout L = make_layout(pr.n, pr.m, 0);
+        const Layout L = make_layout(pr.n, pr.m, pr.C ? 0 : pr.d);
         if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) { set_err("workspace must be non-null and 256-byte aligned"); return FS_ERR_WORKSPACE; }
         if (ws_bytes < L.total) { set_err("workspace too small: %zu < %zu bytes", ws_bytes, L.total); return FS_ERR_WORKSPACE; }
         GridArgs A{};
@@ -774,6 +776,7 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
         if (v != FS_OK) return v;
         A.result = (ResultRecord *)result_dev;
         A.spin_limit = opts ? opts->wait_limit : 0;
+        A.X = pr.X; A.Y = pr.Y; A.d = pr.C ? 0 : pr.d;
         FS_HIP(launch_grid(st, A, (char *)ws + L.o_grid, wmax));
         return FS_OK;
     }

@@ -24,6 +24,8 @@
 // r + 1, which every workgroup reaches only after it has read (and used) the V of round r.  Every wait
 // is bounded: a workgroup that gives up raises a flag that makes all others give up too, and the solve
 // then reports nonfinite = 1 instead of hanging.
+#include <type_traits>
+
 #include "fs_kernels.h"
 
 namespace fs {
@@ -101,7 +103,9 @@ __global__ void k_grid_reset(GridSync *sy) {
     if (t == 11) sy->bad.v = 0ull;
 }
 
-template <int RA, int CB>
+// PTS: point clouds - the tile holds |x_i - y_j|^2 in fp64, formed once from the fp32 coordinates in the
+// difference form.
+template <int RA, int CB, bool PTS>
 __global__ __launch_bounds__(kGT) void k_grid(GridArgs A) {
     __shared__ double sF[2][kGRows];               // F = -s f of the workgroup's rows, by parity of k
     __shared__ double sLa[kGRows], sU[kGRows], sE[kGRows];
@@ -157,14 +161,24 @@ __global__ __launch_bounds__(kGT) void k_grid(GridArgs A) {
         Gc[r] = ok ? start_G(col) : 0.0;
     }
     __builtin_amdgcn_sched_barrier(0);             // the logarithms above are done before the tile takes its registers
-    float c[RA][CB];
+    typename std::conditional<PTS, double, float>::type c[RA][CB];
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
         const int j = tid + kGT * b;
 #pragma unroll
         for (int a = 0; a < RA; ++a) {
             const int i = row0 + a;
-            c[a][b] = (i < n && j < m) ? A.C[(size_t)i * m + j] : 0.0f;
+            if constexpr (PTS) {
+                double sq = 0.0;
+                if (i < n && j < m)
+                    for (int t = 0; t < A.d; ++t) {
+                        const double df = (double)A.X[(size_t)i * A.d + t] - (double)A.Y[(size_t)j * A.d + t];
+                        sq = fma(df, df, sq);
+                    }
+                c[a][b] = sq;
+            } else {
+                c[a][b] = (i < n && j < m) ? A.C[(size_t)i * m + j] : 0.0f;
+            }
         }
     }
     __syncthreads();
@@ -359,12 +373,13 @@ __global__ __launch_bounds__(kGT) void k_grid(GridArgs A) {
 #endif
 }
 
-template <int RA>
+template <int RA, bool PTS>
 hipError_t launch_cb(hipStream_t st, const GridArgs &a, int W, int cb) {
     const dim3 grid(W), block(kGT);
-    if (cb <= 1) hipLaunchKernelGGL((k_grid<RA, 1>), grid, block, 0, st, a);
-    else if constexpr (RA <= 8) hipLaunchKernelGGL((k_grid<RA, 2>), grid, block, 0, st, a);
-    else return hipErrorInvalidValue;               // more than 16 entries per lane: not built
+    constexpr int kMost = PTS ? 8 : 16;             // entries per lane that were built (fp64 entries count double)
+    if (cb <= 1) hipLaunchKernelGGL((k_grid<RA, 1, PTS>), grid, block, 0, st, a);
+    else if constexpr (RA * 2 <= kMost) hipLaunchKernelGGL((k_grid<RA, 2, PTS>), grid, block, 0, st, a);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
@@ -382,13 +397,13 @@ constexpr int kGridLdx = kGridMaxM + 32;
 // Shapes taken: at most 16 entries per lane (beyond that the multi-kernel driver is as fast or faster: the tile
 // and the working set no longer fit the 128 registers of a 1024-lane workgroup), and a strip of at most 16
 // columns per workgroup in the second level (one wave per column).
-bool grid_supported(int n, int m, int wmax) {
+bool grid_supported(int n, int m, int wmax, bool points) {
     if (n < 1 || m < 1 || n > kGridMaxN || m > kGridMaxM || wmax < 1) return false;
     if (wmax > kGridWMax) wmax = kGridWMax;
     const int ra = grid_rows(n, wmax);
     if (ra == 0) return false;
     const int cb = (m + kGT - 1) / kGT;
-    if (ra * cb > 16) return false;
+    if (ra * cb > (points ? 8 : 16)) return false;  // point clouds: the tile is fp64
     const int W = (n + ra - 1) / ra;
     return (m + W - 1) / W <= kGW * kGStripRounds;
 }
@@ -399,7 +414,8 @@ size_t grid_scratch_bytes() {
 
 hipError_t launch_grid(hipStream_t st, const GridArgs &a0, void *scratch, int wmax) {
     if (wmax > kGridWMax) wmax = kGridWMax;
-    if (!scratch || !grid_supported(a0.n, a0.m, wmax)) return hipErrorInvalidValue;
+    if (!scratch || !grid_supported(a0.n, a0.m, wmax, a0.X != nullptr)) return hipErrorInvalidValue;
+    if (a0.X && (!a0.Y || a0.d < 1)) return hipErrorInvalidValue;
     const int RA = grid_rows(a0.n, wmax);
     const int W = (a0.n + RA - 1) / RA;
     GridArgs a = a0;
@@ -412,12 +428,20 @@ hipError_t launch_grid(hipStream_t st, const GridArgs &a0, void *scratch, int wm
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int cb = (a.m + kGT - 1) / kGT;
+    if (a.X) {
+        switch (RA) {
+            case 1: return launch_cb<1, true>(st, a, W, cb);
+            case 2: return launch_cb<2, true>(st, a, W, cb);
+            case 4: return launch_cb<4, true>(st, a, W, cb);
+            default: return launch_cb<8, true>(st, a, W, cb);
+        }
+    }
     switch (RA) {
-        case 1: return launch_cb<1>(st, a, W, cb);
-        case 2: return launch_cb<2>(st, a, W, cb);
-        case 4: return launch_cb<4>(st, a, W, cb);
-        case 8: return launch_cb<8>(st, a, W, cb);
-        default: return launch_cb<16>(st, a, W, cb);
+        case 1: return launch_cb<1, false>(st, a, W, cb);
+        case 2: return launch_cb<2, false>(st, a, W, cb);
+        case 4: return launch_cb<4, false>(st, a, W, cb);
+        case 8: return launch_cb<8, false>(st, a, W, cb);
+        default: return launch_cb<16, false>(st, a, W, cb);
     }
 }
 

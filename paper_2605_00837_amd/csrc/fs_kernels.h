@@ -216,12 +216,14 @@ constexpr int kGridWMax = 256;                   // most workgroups (each needs 
 struct GridLine { unsigned long long v; unsigned long long pad[31]; };      // 256 bytes
 struct GridSync { GridLine grp[8], top, release, abort_flag, bad; };
 struct GridArgs : SmallArgs {                    // batch is ignored (one problem)
+    const float *X, *Y;                          // point clouds [n][d], [m][d] (then C is null), or null
+    int32_t d;
     double *xchg1;                               // [W][ldx]: column partials of every workgroup; last slot: error partial
     double *xchg2;                               // [ldx]: the new V, written strip by strip
     GridSync *sync;
     int32_t ldx, spin_limit;
 };
-bool grid_supported(int n, int m, int wmax);     // wmax: workgroups that can be resident at once (compute units)
+bool grid_supported(int n, int m, int wmax, bool points);   // wmax: workgroups that can be resident at once (compute units)
 size_t grid_scratch_bytes();
 hipError_t launch_grid(hipStream_t st, const GridArgs &a, void *scratch, int wmax);
 

@@ -531,6 +531,22 @@ def test_grid_kernel_matches_oracle(fs, oracle, n, m, iters):
     assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
 
 
+@pytest.mark.parametrize("n,m,d", [(5, 7, 2), (1000, 1200, 3), (2048, 1024, 2), (700, 300, 17), (300, 2000, 3),
+                                   (1500, 900, 64)])
+def test_grid_kernel_point_clouds(fs, oracle, n, m, d):
+    """kernel_mode = 5 on point clouds: squared distances formed once in fp64 and kept in registers."""
+    w = W.random_points(n, m, d, seed=7980 + n + m + d, eps=0.02)
+    if n > 8:
+        w.a[2::9] = 0.0
+        w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 15, kernel_mode=5)
+    assert e64 < TOL_F64 and e32 < TOL_F32, (e64, e32)
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], X=w.X, Y=w.Y))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+    r1, _, _, _ = _solve_and_compare(fs, oracle, w, 15, kernel_mode=1)       # the multi-kernel point-cloud path
+    assert float((r1["f64"] - r["f64"]).abs().max()) / w.eps < TOL_F64
+
+
 def test_grid_kernel_stop_rule_history_and_resume(fs, oracle):
     import torch
     w = W.random_dense(600, 1300, seed=7950, cmax=1.0, eps=0.05)
