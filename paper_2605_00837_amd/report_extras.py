@@ -74,7 +74,7 @@ def main():
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
             print(f"| {n} x {n}, {name} | 2000 | {dt * 1e3:.2f} | {dt / 2000 * 1e6:.2f} us |", flush=True)
-    for n, d in ((200, 3), (512, 3), (200, 16), (2048, 3)):
+    for n, d in ((200, 3), (512, 3), (200, 16), (1024, 3), (2048, 3)):
         w = W.random_points(n, n, d, seed=1, eps=0.05)
         X, Y, a, b = (torch.from_numpy(t).cuda() for t in (w.X, w.Y, w.a, w.b))
         for mode, name in ((0, "automatic"), (1, "multi-kernel path")):
