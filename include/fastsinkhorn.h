@@ -131,7 +131,7 @@ typedef struct {
                                 kernel_mode 3 take fp32 only; kernel_mode 2 then needs 2048 < m <= 16384 */
     int32_t wait_limit;      /* kernel_mode 4 only: polls after which a workgroup stops waiting for the others
                                 (0: default, about two million = seconds).  A tiny value makes the solve give
-                                up early and report nonfinite = 1, which is how the bounded wait is tested   */
+                                up early and report nonfinite = 2, which is how the bounded wait is tested   */
     int32_t time_kernel_every; /* blocking solves only: > 0 times the dominant kernel (row pass, fused pass
                                   or point-cloud LSE pass of the f-update) of every N-th iteration with a pair
                                   of HIP events that the runtime stamps with the start and the stop of that

@@ -22,8 +22,8 @@
 // loads; every thread waits for its own stores (vmcnt 0) before the workgroup's arrival is counted.
 // The arrival counter only grows (generation g is complete at W g arrivals), the exchange buffers
 // alternate by the parity of the generation, and every wait is bounded: a workgroup that gives up
-// raises a flag that makes all others give up too, the solve then reports NaN potentials and
-// nonfinite = 1 instead of hanging.
+// raises a flag that makes all others give up too, the solve then reports that it gave up
+// (nonfinite = 2, NaN potentials where a workgroup had stopped) instead of hanging.
 #include <type_traits>
 
 #include "fs_kernels.h"

@@ -1,4 +1,4 @@
-// Dense problems up to 4096 x 2048 whose cost matrix fits the register files of the chip: the whole of
+// Problems up to 4096 x 2048 whose cost matrix (or table of squared distances) fits the register files of the chip: the whole of
 // Alg. 1 inside ONE kernel launch over up to 256 workgroups (one per compute unit), C read from memory
 // once per SOLVE.  The multi-kernel driver pays two launches per iteration, each with a few us of
 // fixed begin-to-end cost on top of its pass over C; here an iteration is register arithmetic plus two
@@ -16,14 +16,14 @@
 // arguments in fp64 (base 2), v_exp_f32 and the sums in fp32; both LSEs are exact (maximum first).
 //
 // Grid-wide waits: arrivals are counted hierarchically (8 group counters, one top counter, one
-// release word per generation; all monotone, never reset during a solve), published values are
+// release word; all monotone, never reset during a solve), published values are
 // written and read with agent-scope relaxed atomics and every thread waits for its own stores before
 // its workgroup arrives.  Two waits per round make single exchange buffers safe: partials of round
 // r + 1 are written after the second wait of round r, which every workgroup reaches only after it has
 // read the partials of round r; the V strip of round r + 1 is written after the first wait of round
 // r + 1, which every workgroup reaches only after it has read (and used) the V of round r.  Every wait
 // is bounded: a workgroup that gives up raises a flag that makes all others give up too, and the solve
-// then reports nonfinite = 1 instead of hanging.
+// then reports that it gave up (nonfinite = 2) instead of hanging.
 #include <type_traits>
 
 #include "fs_kernels.h"
