@@ -126,9 +126,9 @@ typedef struct {
                                 n x m row-major entries of 2 bytes; the iteration then moves half the bytes.
                                 Every entry is widened exactly to fp32 and the arithmetic is unchanged, so the
                                 result is that of the solve on the rounded matrix.  Needs m % 8 == 0 and a
-                                16-byte aligned C (else FS_ERR_UNSUPPORTED); honoured by fs_sinkhorn_dense_ex,
-                                fs_sinkhorn_solve and fs_sinkhorn_annealed (dense); the batched solver and
-                                kernel_mode 3 take fp32 only; kernel_mode 2 then needs 2048 < m <= 16384 */
+                                16-byte aligned C (else FS_ERR_UNSUPPORTED); honoured by every solver that
+                                takes options (for fs_sinkhorn_dense_batched: every problem's C); kernel_mode 2
+                                then needs 2048 < m <= 16384.  The after-the-loop entry points take fp32 only */
     int32_t wait_limit;      /* kernel_mode 4 only: polls after which a workgroup stops waiting for the others
                                 (0: default, about two million = seconds).  A tiny value makes the solve give
                                 up early and report nonfinite = 2, which is how the bounded wait is tested   */

@@ -340,9 +340,10 @@ def fs_sinkhorn_dense_batched(C, a, b, eps, max_iter, tol, f=None, g=None, want_
         out["f64"] = torch.empty((B, n), dtype=torch.float64, device=dev)
         out["g64"] = torch.empty((B, m), dtype=torch.float64, device=dev)
         opt_kw.update(f64_out=out["f64"], g64_out=out["g64"])
+    Cp = _cost(C, opt_kw)
     o = make_options(**opt_kw)
     res = torch.zeros((B, 16), dtype=torch.uint8, device=dev)
-    _check(_lib.fs_sinkhorn_dense_batched(_p(C), _p(a), _p(b), B, n, m, float(eps), int(max_iter), float(tol),
+    _check(_lib.fs_sinkhorn_dense_batched(Cp, _p(a), _p(b), B, n, m, float(eps), int(max_iter), float(tol),
                                           _p(f), _p(g), _stream(), ctypes.byref(o), _p(res, torch.uint8)))
     out["result"] = res
     return out

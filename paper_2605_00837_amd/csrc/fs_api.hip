@@ -553,6 +553,10 @@ fs_status check_options(const Problem &pr, const fs_options *opts) {
     if (!opts) return FS_OK;
     if (opts->cost_dtype < 0 || opts->cost_dtype > 2) { set_err("cost_dtype must be FS_COST_F32, FS_COST_F16 or FS_COST_BF16"); return FS_ERR_INVALID_ARG; }
     if (opts->cost_dtype != 0 && !pr.C) { set_err("cost_dtype applies to a dense cost matrix only"); return FS_ERR_INVALID_ARG; }
+    if (opts->cost_dtype != 0 && (pr.m % 8 != 0 || (reinterpret_cast<uintptr_t>(pr.C) & 15u))) {
+        set_err("2-byte costs need m %% 8 == 0 (got %d) and a 16-byte aligned C", pr.m);
+        return FS_ERR_UNSUPPORTED;
+    }
     if (opts->kernel_mode < 0 || opts->kernel_mode > 5) { set_err("kernel_mode must be 0 ... 5"); return FS_ERR_INVALID_ARG; }
     return FS_OK;
 }
@@ -560,9 +564,9 @@ fs_status check_options(const Problem &pr, const fs_options *opts) {
 // Small dense problems run whole inside one single-workgroup kernel (fs_small.hip).
 bool small_path(const Problem &pr, const fs_options *opts, fs_status *err) {
     const int km = opts ? opts->kernel_mode : 0;
-    const bool fits = pr.C && pr.n <= kSmallMax && pr.m <= kSmallMax && !(opts && opts->cost_dtype != 0);
+    const bool fits = pr.C && pr.n <= kSmallMax && pr.m <= kSmallMax;
     if (km == 3 && !fits) {
-        set_err("kernel_mode 3 needs a dense fp32 cost matrix with n, m <= %d", kSmallMax);
+        set_err("kernel_mode 3 needs a dense problem with n, m <= %d", kSmallMax);
         *err = FS_ERR_UNSUPPORTED;
         return false;
     }
@@ -578,10 +582,9 @@ bool small_path(const Problem &pr, const fs_options *opts, fs_status *err) {
 // clouds (the squared distances are then formed once, in fp64, and kept in registers like a cost matrix).
 bool coop_path(const Problem &pr, const fs_options *opts, fs_status *err) {
     const int km = opts ? opts->kernel_mode : 0;
-    const bool fits = pr.C ? (coop_supported(pr.n, pr.m) && !(opts && opts->cost_dtype != 0))
-                           : coop_points_supported(pr.n, pr.m);
+    const bool fits = pr.C ? coop_supported(pr.n, pr.m) : coop_points_supported(pr.n, pr.m);
     if (km == 4 && !fits) {
-        set_err("kernel_mode 4 needs n, m <= %d and a dense fp32 cost matrix, or point clouds of at most 16 pairs per lane (n * m <= 2^19, less for ragged shapes)", kCoopMax);
+        set_err("kernel_mode 4 needs n, m <= %d and a dense cost matrix, or point clouds of at most 16 pairs per lane (n * m <= 2^19, less for ragged shapes)", kCoopMax);
         *err = FS_ERR_UNSUPPORTED;
         return false;
     }
@@ -605,9 +608,9 @@ int device_cus() {
 bool grid_path(const Problem &pr, const fs_options *opts, bool blocking, fs_status *err, int *wmax) {
     const int km = opts ? opts->kernel_mode : 0;
     if (km != 5 && km != 0) return false;
-    if ((opts && opts->cost_dtype != 0) || pr.n > kGridMaxN || pr.m > kGridMaxM) {
+    if (pr.n > kGridMaxN || pr.m > kGridMaxM) {
         if (km == 0) return false;
-        set_err("kernel_mode 5 needs n <= %d, m <= %d and a dense fp32 cost matrix or point clouds", kGridMaxN, kGridMaxM);
+        set_err("kernel_mode 5 needs n <= %d, m <= %d", kGridMaxN, kGridMaxM);
         *err = FS_ERR_UNSUPPORTED;
         return false;
     }
@@ -633,6 +636,7 @@ fs_status small_args(const Problem &pr, int batch, const fs_options *opts, float
     if (o.err_history && o.err_history_len < 0) { set_err("err_history_len < 0"); return FS_ERR_INVALID_ARG; }
     SmallArgs A{};
     A.C = pr.C; A.a = pr.a; A.b = pr.b;
+    A.c_dtype = o.cost_dtype;
     A.n = pr.n; A.m = pr.m; A.batch = batch;
     A.s = kLog2e / (double)pr.eps;
     A.max_iter = pr.max_iter; A.check_every = o.check_every;
@@ -1013,7 +1017,8 @@ fs_status fs_sinkhorn_dense_batched(const float *C, const float *a, const float 
         return FS_ERR_UNSUPPORTED;
     }
     if (opts && opts->kernel_mode != 0 && opts->kernel_mode != 3) { set_err("batched solves have one kernel (kernel_mode 0 or 3)"); return FS_ERR_INVALID_ARG; }
-    if (opts && opts->cost_dtype != 0) { set_err("batched solves take an fp32 cost matrix"); return FS_ERR_UNSUPPORTED; }
+    v = check_options(pr, opts);
+    if (v != FS_OK) return v;
     SmallArgs A;
     v = small_args(pr, batch, opts, f, g, &A);
     if (v != FS_OK) return v;

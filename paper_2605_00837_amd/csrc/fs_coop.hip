@@ -144,7 +144,7 @@ __global__ __launch_bounds__(kCT) void k_coop(CoopArgs A) {
                     }
                 c[a][b] = sq;
             } else {
-                c[a][b] = (i < n && j < m) ? A.C[(size_t)i * m + j] : 0.0f;
+                c[a][b] = (i < n && j < m) ? cost_entry(A.C, A.c_dtype, (size_t)i * m + j) : 0.0f;
             }
         }
     __syncthreads();

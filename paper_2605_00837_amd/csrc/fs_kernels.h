@@ -171,6 +171,7 @@ struct ResultRecord { int32_t iters, converged, nonfinite; float marginal_err; }
 constexpr int32_t kGaveUp = 2;                   // ResultRecord::nonfinite of a one-launch solve that abandoned a wait
 struct SmallArgs {
     const float *C, *a, *b;          // [batch][n][m], [batch][n], [batch][m]
+    int32_t c_dtype;                 // storage of C: 0 fp32, 1 fp16, 2 bfloat16 (entries of 2 bytes)
     int32_t n, m, batch;
     double s;
     int32_t max_iter, check_every;

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kST) void k_small(SmallArgs A) {
 
     const int p = blockIdx.x;
     const int n = A.n, m = A.m;
-    const float *C = A.C + (size_t)p * n * m;
+    const size_t c0 = (size_t)p * n * m;              // first entry of this problem's cost matrix
     const float *aw = A.a + (size_t)p * n;
     const float *bw = A.b + (size_t)p * m;
     const int tid = threadIdx.x, tc = tid & 31, tr = tid >> 5, lane = tid & 63, wave = tid >> 6;
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kST) void k_small(SmallArgs A) {
 #pragma unroll
         for (int b = 0; b < CB; ++b) {
             const int i = tr + 32 * a, j = tc + 32 * b;
-            c[a][b] = (i < n && j < m) ? C[(size_t)i * m + j] : 0.0f;
+            c[a][b] = (i < n && j < m) ? cost_entry(A.C, A.c_dtype, c0 + (size_t)i * m + j) : 0.0f;
         }
 
     int iters = A.max_iter, converged = 0;

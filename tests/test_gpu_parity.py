@@ -171,6 +171,37 @@ def test_dense_solve_half_precision_cost(fs, oracle, dtype_name, n, m, mode, var
     assert pot_err(r["f64"].cpu().numpy(), ref_full["f"], w.eps) > 2 * e64
 
 
+@pytest.mark.parametrize("dtype_name", ["f16", "bf16"])
+@pytest.mark.parametrize("n,m,mode", [(100, 120, 3), (64, 64, 0), (256, 256, 4), (300, 408, 0), (1000, 1024, 5),
+                                      (900, 1200, 0)])
+def test_one_launch_kernels_take_half_precision_cost(fs, oracle, dtype_name, n, m, mode):
+    """The one-launch kernels widen a 2-byte C once, when they load their register tile."""
+    w = W.random_dense(n, m, seed=3500 + n + m, cmax=2.0, eps=0.03)
+    C32, C16 = _rounded_cost(w.C, dtype_name)
+    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, 25, 0.0, C=C16, want_f64=True, kernel_mode=mode)
+    ref = oracle.solve(w.a, w.b, w.eps, 25, C=C32)
+    assert r["iters"] == 25 and not r["nonfinite"]
+    assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+
+
+def test_batched_solves_take_half_precision_cost(fs, oracle):
+    import torch
+    B, n, m = 5, 96, 104
+    rng = np.random.default_rng(3600)
+    C = rng.uniform(0.0, 2.0, size=(B, n, m)).astype(np.float32)
+    a = np.full((B, n), 1.0 / n, dtype=np.float32)
+    b = np.full((B, m), 1.0 / m, dtype=np.float32)
+    C16 = torch.from_numpy(C).to(torch.bfloat16)
+    out = fs.fs_sinkhorn_dense_batched(C16.cuda(), dev(a), dev(b), 0.05, 20, 0.0, want_f64=True)
+    res = fs.results_from_device(out["result"])
+    C32 = C16.to(torch.float32).numpy()
+    for p in range(B):
+        ref = oracle.solve(a[p], b[p], 0.05, 20, C=C32[p])
+        assert res[p]["iters"] == 20
+        assert pot_err(out["f64"][p].cpu().numpy(), ref["f"], 0.05) < TOL_F64
+
+
 def test_half_precision_cost_async_and_rejections(fs, oracle):
     import torch
     w = W.random_dense(60, 4096, seed=3401, cmax=2.0, eps=0.03)
@@ -184,17 +215,10 @@ def test_half_precision_cost_async_and_rejections(fs, oracle):
     a, b = dev(w.a), dev(np.full(4100, 1.0 / 4100, dtype=np.float32))
     with pytest.raises(fs.FsError, match="m % 8"):
         fs.fs_sinkhorn_solve(a, b, 0.1, 3, 0.0, C=torch.zeros(60, 4100, dtype=torch.float16, device="cuda"))
-    sm = torch.zeros(64, 64, dtype=torch.float16, device="cuda")
     u = torch.full((64,), 1 / 64, device="cuda")
-    with pytest.raises(fs.FsError, match="fp32"):
-        fs.fs_sinkhorn_solve(u, u, 0.1, 3, 0.0, C=sm, kernel_mode=3)
-    r = fs.fs_sinkhorn_solve(u, u, 0.1, 3, 0.0, C=sm)                 # automatic: the multi-kernel path takes it
-    assert r["iters"] == 3 and not r["nonfinite"]
     with pytest.raises(fs.FsError, match="dense cost matrix only"):
         fs.fs_sinkhorn_solve(u, u, 0.1, 3, 0.0, X=torch.zeros(64, 2, device="cuda"),
                              Y=torch.zeros(64, 2, device="cuda"), cost_dtype=1)
-    with pytest.raises(fs.FsError, match="fp32 cost"):
-        fs.fs_sinkhorn_dense_batched(sm.float()[None], u[None], u[None], 0.1, 3, 0.0, cost_dtype=1)
     with pytest.raises(fs.FsError, match="2048 < m"):
         fs.fs_sinkhorn_solve(u, torch.full((1024,), 1 / 1024, device="cuda"), 0.1, 3, 0.0,
                              C=torch.zeros(64, 1024, dtype=torch.bfloat16, device="cuda"), kernel_mode=2)
