@@ -658,6 +658,8 @@ def test_one_launch_solvers_fall_back_when_they_give_up(fs, oracle, n, m, warm):
     assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
     assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
     # asked for by name, the same kernel reports that it gave up (or, with luck, finishes)
+    if n * m > 1 << 18:
+        _needs_whole_chip()
     rk = fs.fs_sinkhorn_solve(a, b, w.eps, 25, 0.0, C=geo["C"], kernel_mode=4 if n * m <= 1 << 18 else 5, wait_limit=1)
     assert rk["gave_up"] or (rk["iters"] == 25 and not rk["nonfinite"])
 
