@@ -129,7 +129,7 @@ typedef struct {
                                 16-byte aligned C (else FS_ERR_UNSUPPORTED); honoured by every solver that
                                 takes options (for fs_sinkhorn_dense_batched: every problem's C); kernel_mode 2
                                 then needs 2048 < m <= 16384.  The after-the-loop entry points take fp32 only */
-    int32_t wait_limit;      /* kernel_mode 4 only: polls after which a workgroup stops waiting for the others
+    int32_t wait_limit;      /* kernel_mode 4 and 5: polls after which a workgroup stops waiting for the others
                                 (0: default, about two million = seconds).  A tiny value makes the solve give
                                 up early and report nonfinite = 2, which is how the bounded wait is tested   */
     int32_t time_kernel_every; /* blocking solves only: > 0 times the dominant kernel (row pass, fused pass
@@ -273,6 +273,18 @@ fs_status fs_update_g(const float *C, const float *X, const float *Y, int d, con
 const char *fs_last_error(void);     /* thread-local, static storage, never NULL        */
 void        fs_clear_cache(void);    /* frees cached workspaces and hipGraph executables */
 const char *fs_version(void);
+
+/* Which kernel a solve of this shape would run (host logic only, nothing is enqueued; d = 0: dense cost
+ * matrix, assumed suitably aligned; blocking != 0: the blocking solves, else the asynchronous ones;
+ * compute_units: of the device, 0 = ask the current device).  Returns FS_KERNEL_* or the negative fs_status
+ * the solve itself would return for this shape and these options. */
+#define FS_KERNEL_STREAM 1   /* dense, streaming row / column kernels, 2 passes over C per iteration */
+#define FS_KERNEL_FUSED  2   /* dense, fused row-panel kernel, 1 pass over C per iteration           */
+#define FS_KERNEL_SMALL  3   /* whole solve in one workgroup                                          */
+#define FS_KERNEL_COOP   4   /* whole solve in one launch, up to 32 workgroups                        */
+#define FS_KERNEL_GRID   5   /* whole solve in one launch, one workgroup per compute unit             */
+#define FS_KERNEL_POINTS 6   /* point clouds, cost recomputed per pair in every pass                  */
+int fs_kernel_choice(int n, int m, int d, const fs_options *opts, int blocking, int compute_units);
 
 /* Average duration (ms) of the dominant kernel over the launches sampled by the most recent
  * blocking solve on this thread that had time_kernel_every > 0, the number of samples, and the

@@ -59,6 +59,8 @@ def _load():
     lib.fs_last_kernel_timing.restype = ci
     lib.fs_last_kernel_timing.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32),
                                           ctypes.POINTER(ctypes.c_char_p)]
+    lib.fs_kernel_choice.restype = ci
+    lib.fs_kernel_choice.argtypes = [ci, ci, ci, vp, ci, ci]
     lib.fs_workspace_bytes.restype = ctypes.c_size_t
     lib.fs_workspace_bytes.argtypes = [ci, ci, ci]
     lib.fs_sinkhorn_dense.restype = ci
@@ -101,7 +103,7 @@ _lib = _load()
 EXPORTED = ("fs_sinkhorn_dense", "fs_sinkhorn_points", "fs_sinkhorn_solve", "fs_workspace_bytes",
             "fs_sinkhorn_dense_ex", "fs_sinkhorn_points_ex", "fs_sinkhorn_dense_batched", "fs_sinkhorn_annealed", "fs_plan", "fs_cost", "fs_plan_f64",
             "fs_cost_f64", "fs_diagnostics", "fs_barycentric", "fs_update_f", "fs_update_g", "fs_last_error", "fs_clear_cache", "fs_version",
-            "fs_last_kernel_timing")
+            "fs_last_kernel_timing", "fs_kernel_choice")
 
 
 def _check(status: int):
@@ -178,6 +180,17 @@ def make_options(check_every=0, warm_start=False, kernel_mode=0, use_graph=0, sk
 
 
 # ---------------------------------------------------------------- entry points, same names as the C ABI
+KERNEL_NAMES = {1: "stream", 2: "fused", 3: "small", 4: "coop", 5: "grid", 6: "points"}
+
+
+def fs_kernel_choice(n: int, m: int, d: int = 0, blocking: bool = True, compute_units: int = 0, **opt_kw) -> str:
+    """Name of the kernel a solve of this shape would run (host logic only; works without a GPU when
+    compute_units is given)."""
+    o = make_options(**opt_kw)
+    return KERNEL_NAMES[_check(_lib.fs_kernel_choice(int(n), int(m), int(d), ctypes.byref(o), int(blocking),
+                                                     int(compute_units)))]
+
+
 def fs_version() -> str:
     return _lib.fs_version().decode()
 

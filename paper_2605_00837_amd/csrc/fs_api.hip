@@ -597,7 +597,10 @@ bool coop_path(const Problem &pr, const fs_options *opts, fs_status *err) {
 }
 
 // Compute units of the current device: the whole-chip one-launch solver needs one per workgroup.
+thread_local int g_cus_override = 0;       // fs_kernel_choice: answer for a device with this many compute units
+
 int device_cus() {
+    if (g_cus_override > 0) return g_cus_override;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
@@ -916,6 +919,32 @@ void fs_clear_cache(void) {
         (void)hipSetDevice(cur);
     }
     g_cache.clear();
+}
+
+int fs_kernel_choice(int n, int m, int d, const fs_options *opts, int blocking, int compute_units) {
+    // the decisions of solve_blocking / solve_async in their order, on a problem that only has a shape
+    const float *dummy = reinterpret_cast<const float *>(uintptr_t(4096));
+    Problem pr{d == 0 ? dummy : nullptr, d == 0 ? nullptr : dummy, d == 0 ? nullptr : dummy, dummy, dummy, d, n, m, 1.0f, 1, 0.0f};
+    fs_status v = validate(pr, const_cast<float *>(dummy), const_cast<float *>(dummy));
+    if (v == FS_OK) v = check_options(pr, opts);
+    if (v != FS_OK) return v;
+    fs_status serr = FS_OK;
+    if (small_path(pr, opts, &serr)) return FS_KERNEL_SMALL;
+    if (serr != FS_OK) return serr;
+    g_cus_override = compute_units;
+    int wmax = 0;
+    const bool grid = grid_path(pr, opts, blocking != 0, &serr, &wmax);
+    g_cus_override = 0;
+    if (serr != FS_OK) return serr;
+    if (grid) return FS_KERNEL_GRID;
+    if (coop_path(pr, opts, &serr)) return FS_KERNEL_COOP;
+    if (serr != FS_OK) return serr;
+    if (d != 0) return FS_KERNEL_POINTS;
+    const int cd = opts ? opts->cost_dtype : 0, km = opts ? opts->kernel_mode : 0;
+    const bool fused_ok = dense_fused_supported(n, m, dummy, cd);
+    if (km == 2 && !fused_ok) { set_err("fused kernel does not support m = %d", m); return FS_ERR_UNSUPPORTED; }
+    if (km > 2) { set_err("kernel_mode %d does not take this problem", km); return FS_ERR_UNSUPPORTED; }
+    return (km == 2 || (km == 0 && fused_ok)) ? FS_KERNEL_FUSED : FS_KERNEL_STREAM;
 }
 
 fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name) {

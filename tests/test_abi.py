@@ -133,3 +133,34 @@ def test_header_is_plain_c(tmp_path):
     got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     assert got[0] == ctypes.sizeof(binding.fs_options)
     assert got[1:] == [getattr(binding.fs_options, nm).offset for nm in names]
+
+
+def test_kernel_choice_table_without_gpu():
+    """The dispatch of the solvers is host logic: which kernel takes which shape, pinned here for the five
+    benchmark configurations and for the boundaries between the kernels (256 compute units assumed)."""
+    from paper_2605_00837_amd import binding as fs
+    pick = lambda n, m, d=0, blocking=True, **kw: fs.fs_kernel_choice(n, m, d, blocking, 256, **kw)
+    assert pick(256, 256) == "coop"                          # c1
+    assert pick(8192, 8192) == "fused"                       # c2
+    assert pick(4096, 4096) == "fused"                       # c3: 64 entries per lane do not fit the one-launch kernels
+    assert pick(65536, 65536, 3) == "points"                 # c4
+    assert pick(16384, 16384, 3) == "points" and pick(16384, 12288) == "fused"      # c5
+    assert pick(64, 64) == "small" and pick(128, 128) == "small" and pick(129, 128) == "coop"
+    assert pick(512, 512) == "coop" and pick(513, 512) == "grid" and pick(1024, 1024) == "grid"
+    assert pick(2048, 2048) == "grid" and pick(4096, 1024) == "grid" and pick(4096, 2048) == "fused"
+    assert pick(100, 2048) == "fused"                        # too few rows for that many columns: strips of > 16 columns
+    assert pick(40, 20000) == "stream" and pick(30, 16384) == "fused" and pick(30, 16385) == "stream"
+    assert pick(200, 200, 3) == "coop" and pick(1024, 1024, 3) == "grid" and pick(2048, 2048, 3) == "points"
+    # asynchronous solves never pick the whole-chip kernel by themselves; a smaller device shrinks its range
+    assert pick(1024, 1024, blocking=False) == "fused" and pick(512, 512, blocking=False) == "coop"
+    assert pick(1024, 1024, blocking=False, kernel_mode=5) == "grid"
+    assert fs.fs_kernel_choice(4096, 1024, 0, True, 64) == "fused" and fs.fs_kernel_choice(1024, 1024, 0, True, 64) == "grid"
+    # 2-byte costs: fused from 2049 columns on, whole 16-byte chunks only
+    assert pick(300, 4096, cost_dtype=1) == "fused" and pick(100, 2048, cost_dtype=1) == "stream"
+    assert pick(1000, 1024, cost_dtype=2) == "grid"
+    with pytest.raises(fs.FsError, match="m % 8"):
+        pick(300, 4100, cost_dtype=1)
+    with pytest.raises(fs.FsError, match="kernel_mode 3"):
+        pick(300, 300, kernel_mode=3)
+    with pytest.raises(fs.FsError, match="kernel_mode 5"):
+        pick(4096, 4096, kernel_mode=5)
