@@ -1,5 +1,5 @@
-// Mid-size dense problems (n, m <= 1024): the whole of Alg. 1 inside ONE kernel launch spread over up
-// to 32 workgroups, the cost matrix held in registers for the entire solve, ONE grid-wide exchange per
+// Mid-size problems (n, m <= 1024; dense cost or point clouds): the whole of Alg. 1 inside ONE kernel launch spread
+// over up to 32 workgroups, the cost matrix (or the table of squared distances) held in registers for the entire solve, ONE grid-wide exchange per
 // iteration.  The multi-kernel driver spends 11 - 13 us per iteration at these sizes on its chain of
 // dependent launches; here an iteration costs the arithmetic of a few registers per lane plus one
 // round of "publish partials, wait for everyone, read everyone's partials".
