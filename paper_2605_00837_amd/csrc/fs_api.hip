@@ -464,7 +464,10 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     FS_HIP(hipHostGetDevicePointer(&hb_dev, (void *)hb, 0));
     S.host_flag = (volatile int32_t *)hb_dev;
     FS_HIP(S.enqueue_init());
-    const int block = S.opt.check_every;
+    // Iterations are enqueued in blocks; the stop rule itself runs on the device every check_every iterations,
+    // a block is only how often the host looks at the stop flag (what it enqueued beyond a stop returns at
+    // once), so small check intervals do not shrink it.
+    const int block = S.opt.check_every > 10 ? S.opt.check_every : 10;
     const int tevery = S.opt.time_kernel_every > 0 ? S.opt.time_kernel_every : 0;
     int nsamples = 0;
     g_timing = KernelTiming{};

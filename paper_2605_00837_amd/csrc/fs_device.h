@@ -119,12 +119,13 @@ __device__ __forceinline__ float cost_entry(const float *C, int dtype, size_t id
     return dtype == 1 ? cost_from_bits<1>(bits) : cost_from_bits<2>(bits);
 }
 
-// 2^d - 1 with a relative error below 2e-7 and few registers (the library's expm1 would cost the kernels whose
-// lanes hold a tile of the cost matrix much of their register budget): a short series where the result is
-// small, v_exp_f32 elsewhere.
+// 2^d - 1 with a relative error below 2e-6 and few registers (the library's expm1 costs about a hundred
+// instructions and, in the kernels whose lanes hold a tile of the cost matrix, much of their register
+// budget): a 6-term series where the result is small, v_exp_f32 elsewhere.
 __device__ __forceinline__ double exp2m1(double d) {
     const double t = d * 0.6931471805599453094;
-    if (fabs(t) < 0.00390625) return t * (1.0 + t * (0.5 + t * (1.0 / 6.0 + t * (1.0 / 24.0))));
+    if (fabs(t) < 0.0625)
+        return t * (1.0 + t * (0.5 + t * (1.0 / 6.0 + t * (1.0 / 24.0 + t * (1.0 / 120.0 + t * (1.0 / 720.0))))));
     return (double)fast_exp2((float)d) - 1.0;
 }
 

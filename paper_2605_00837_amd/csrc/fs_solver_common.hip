@@ -127,7 +127,7 @@ __device__ __forceinline__ double block_sum_1024(double v, double *lds16) {
 
 // 1 if a potential moved by more than kFastBelow (or by a non-finite amount), else 0
 __device__ __forceinline__ double big_move(double diff) { return (fabs(diff) <= kFastBelow) ? 0.0 : 1.0; }
-// Error terms a_i |2^(Fnew_i - Fold_i) - 1| of the rows first, first+stride, ... (fp64, expm1 for
+// Error terms a_i |2^(Fnew_i - Fold_i) - 1| of the rows first, first+stride, ... (fp64, a series for
 // the small differences near convergence).
 __device__ __forceinline__ double err_terms(const ErrSrc &es, int cur, int first, int stride) {
     const double *Fo = es.F + (size_t)cur * es.n_ld;
@@ -136,7 +136,7 @@ __device__ __forceinline__ double err_terms(const ErrSrc &es, int cur, int first
     for (int i = first; i < es.n; i += stride) {
         const float a = es.a[i];
         const double diff = Fn[i] - Fo[i];
-        if (a > 0.0f) acc += (double)a * fabs(expm1(diff * 0.6931471805599453094));
+        if (a > 0.0f) acc += (double)a * fabs(exp2m1(diff));
     }
     return acc;
 }
@@ -265,16 +265,16 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
             }
         }
     }
-    // error terms a_i |2^(Fnew_i - Fold_i) - 1| in fp64 (expm1 for the small differences near
+    // error terms a_i |2^(Fnew_i - Fold_i) - 1| in fp64 (a series for the small differences near
     // convergence), for either role of the two copies of F
     double term_if[2] = {0.0, 0.0};                // [0]: copy 1 is the new one, [1]: copy 0 is
     if (err_wave) {
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             if (aw[q] > 0.0f) {
-                const double x = (F1[q] - F0[q]) * kLn2;
-                term_if[0] += (double)aw[q] * fabs(expm1(x));
-                term_if[1] += (double)aw[q] * fabs(expm1(-x));
+                const double x = F1[q] - F0[q];
+                term_if[0] += (double)aw[q] * fabs(exp2m1(x));
+                term_if[1] += (double)aw[q] * fabs(exp2m1(-x));
             }
         }
     }
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
         const double *Fn = A.es.F + (size_t)nxt * A.es.n_ld;
         for (int i = ei0 + 2 * estride; i < A.es.n; i += estride) {   // only when n > 128 * (workgroups of the grid)
             const float a = A.es.a[i];
-            if (a > 0.0f) term += (double)a * fabs(expm1((Fn[i] - Fo[i]) * kLn2));
+            if (a > 0.0f) term += (double)a * fabs(exp2m1(Fn[i] - Fo[i]));
         }
         err_part = wave_sum_f64(term);
     }
