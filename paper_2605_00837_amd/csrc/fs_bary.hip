@@ -188,8 +188,9 @@ __global__ __launch_bounds__(kBP) void k_bary_points(BaryPoints A) {
             }
         }
         __syncthreads();
+        const int cnt = min(kBTile, (j1 - jt + 1) & ~1);       // staged columns (the tile is padded with -inf)
 #pragma unroll 2
-        for (int jj = 0; jj < kBTile; ++jj) {
+        for (int jj = 0; jj < cnt; ++jj) {
             double w[D + 1];
 #pragma unroll
             for (int t = 0; t <= D; ++t) w[t] = tile[jj][t];

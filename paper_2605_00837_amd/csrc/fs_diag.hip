@@ -284,8 +284,9 @@ __global__ __launch_bounds__(kPT2) void k_diag_points(PointsDiag A) {
         float rf[kIB2], cf = 0.0f, ef = 0.0f;
 #pragma unroll
         for (int b = 0; b < kIB2; ++b) rf[b] = 0.0f;
+        const int cnt = min(kTile2, (j1 - jt + 1) & ~1);       // staged columns (the tile is padded with -inf)
 #pragma unroll 2
-        for (int jj = 0; jj < kTile2; ++jj) {
+        for (int jj = 0; jj < cnt; ++jj) {
             double w[D + 2];
 #pragma unroll
             for (int t = 0; t < D + 2; ++t) w[t] = tile[jj][t];
