@@ -884,7 +884,10 @@ def test_plan_and_cost(fs, oracle, kind):
                                          ("dense", 33, 1, 0), ("dense", 90, 4101, 0), ("dense", 50, 6, 0),
                                          ("points", 700, 1300, 3), ("points", 1030, 500, 2),
                                          ("points", 90, 200, 7), ("points", 300, 1000, 16), ("points", 520, 130, 33),
-                                         ("points", 129, 257, 64)])
+                                         ("points", 129, 257, 64),
+                                         # small problems: one single-workgroup launch
+                                         ("dense", 100, 120, 0), ("dense", 1, 1, 0), ("dense", 5, 1000, 0),
+                                         ("points", 200, 210, 3), ("points", 31, 64, 1), ("points", 256, 255, 4)])
 @pytest.mark.parametrize("precision", ["f32", "f64"])
 def test_diagnostics_one_pass(fs, oracle, kind, n, m, d, precision):
     """fs_diagnostics against the oracle's direct definitions (explicit plan, own sums): cost, mass, KL,
