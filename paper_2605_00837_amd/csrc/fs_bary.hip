@@ -21,7 +21,7 @@ constexpr int kZ = kBaryMaxDim;
 
 struct BaryLayout {
     int vec, nstrips, P, rpp;       // dense
-    int JS, cps;                    // points
+    int JS, cps, ib;                // points
     int nparts;                     // partial sets per row (nstrips or JS)
     size_t o_ri, o_cj, o_part, o_xp, o_xs, o_xq, o_yp, o_ys, o_yq, total;
 };
@@ -48,7 +48,8 @@ BaryLayout bary_layout(int n, int m, int d) {
         L.P = (n + rpp - 1) / rpp;
         L.nparts = L.nstrips;
     } else {
-        points_plan_tiles(n, m, d, &L.JS, &L.cps);
+        if (d <= 4) points_plan_after(n, m, 512, 64, &L.JS, &L.cps, &L.ib);
+        else points_plan_tiles(n, m, d, &L.JS, &L.cps);
         L.nparts = L.JS;
         L.o_xp = take(sizeof(double) * (size_t)n * d);
         L.o_xs = take(sizeof(double) * (size_t)n * d);
@@ -149,17 +150,17 @@ struct BaryPoints {
     int32_t cols_per_split;
 };
 
-template <int D>
+template <int D, int IB>
 __global__ __launch_bounds__(kBP) void k_bary_points(BaryPoints A) {
     __shared__ __align__(16) double tile[kBTile][D + 1];      // [0] collog - colq, [1..D] 2 s y
     __shared__ float tileZ[kBTile][kZ];
     const int tid = threadIdx.x;
-    double x[kBIB][D], rc[kBIB];
-    int row[kBIB];
-    float acc[kBIB][kZ + 1];
+    double x[IB][D], rc[IB];
+    int row[IB];
+    float acc[IB][kZ + 1];
 #pragma unroll
-    for (int b = 0; b < kBIB; ++b) {
-        row[b] = (blockIdx.x * kBIB + b) * kBP + tid;
+    for (int b = 0; b < IB; ++b) {
+        row[b] = (blockIdx.x * IB + b) * kBP + tid;
         const bool ok = row[b] < A.nr;
 #pragma unroll
         for (int t = 0; t < D; ++t) x[b][t] = ok ? A.rows[(size_t)row[b] * D + t] : 0.0;
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(kBP) void k_bary_points(BaryPoints A) {
 #pragma unroll
             for (int t = 0; t < kZ; ++t) z[t] = tileZ[jj][t];
 #pragma unroll
-            for (int b = 0; b < kBIB; ++b) {
+            for (int b = 0; b < IB; ++b) {
                 double tq = w[0];
 #pragma unroll
                 for (int t = 0; t < D; ++t) tq = fma(x[b][t], w[1 + t], tq);
@@ -211,7 +212,7 @@ __global__ __launch_bounds__(kBP) void k_bary_points(BaryPoints A) {
         }
     }
 #pragma unroll
-    for (int b = 0; b < kBIB; ++b)
+    for (int b = 0; b < IB; ++b)
         if (row[b] < A.nr) {
 #pragma unroll
             for (int t = 0; t <= kZ; ++t) A.part[((size_t)blockIdx.y * A.nr + row[b]) * (kZ + 1) + t] = acc[b][t];
@@ -323,13 +324,20 @@ hipError_t launch_bary(hipStream_t st, const PlanArgs &a, const float *Z, int dz
         X.rows = xp; X.rowq = xq; X.rowlog = ri; X.cols2s = ys; X.colq = yq; X.collog = cj;
         X.Z = Z; X.nr = a.n; X.nc = a.m; X.dz = dz; X.part = part; X.cols_per_split = L.cps;
         if (a.d <= 4) {
-            const dim3 grid((a.n + kBP * kBIB - 1) / (kBP * kBIB), L.JS);
+            if (L.ib != 1 && L.ib != kBIB) return hipErrorInvalidValue;
+            const dim3 grid((a.n + kBP * L.ib - 1) / (kBP * L.ib), L.JS);
+#define FS_BARY_PTS(D)                                                                          \
+    do {                                                                                        \
+        if (L.ib == 1) hipLaunchKernelGGL((k_bary_points<D, 1>), grid, dim3(kBP), 0, st, X);    \
+        else hipLaunchKernelGGL((k_bary_points<D, kBIB>), grid, dim3(kBP), 0, st, X);           \
+    } while (0)
             switch (a.d) {
-                case 1: hipLaunchKernelGGL(k_bary_points<1>, grid, dim3(kBP), 0, st, X); break;
-                case 2: hipLaunchKernelGGL(k_bary_points<2>, grid, dim3(kBP), 0, st, X); break;
-                case 3: hipLaunchKernelGGL(k_bary_points<3>, grid, dim3(kBP), 0, st, X); break;
-                default: hipLaunchKernelGGL(k_bary_points<4>, grid, dim3(kBP), 0, st, X); break;
+                case 1: FS_BARY_PTS(1); break;
+                case 2: FS_BARY_PTS(2); break;
+                case 3: FS_BARY_PTS(3); break;
+                default: FS_BARY_PTS(4); break;
             }
+#undef FS_BARY_PTS
         } else {
             const dim3 grid((a.n + kTileRows - 1) / kTileRows, L.JS);
             switch (mfma_d4(a.d)) {

@@ -32,7 +32,7 @@ struct DiagLayout {
     // dense
     int vec, strip_cols, nstrips, P, rpp;
     // points
-    int JSx, cpsx, JSy, cpsy;
+    int JSx, cpsx, JSy, cpsy, ibx, iby;
     // scratch offsets (bytes)
     size_t o_ri, o_cj, o_rowpart, o_colpart, o_scal, o_red, o_out, total;
     // points extras
@@ -69,11 +69,16 @@ DiagLayout diag_layout(int n, int m, int d) {
         L.nscal = L.nstrips * L.P;
         L.o_scal = take(sizeof(double) * 2 * L.nscal);
     } else {
-        points_plan_tiles(n, m, d, &L.JSx, &L.cpsx);
-        points_plan_tiles(m, n, d, &L.JSy, &L.cpsy);
+        if (d <= 4) {
+            points_plan_after(n, m, 1024, 128, &L.JSx, &L.cpsx, &L.ibx);
+            points_plan_after(m, n, 1024, 128, &L.JSy, &L.cpsy, &L.iby);
+        } else {
+            points_plan_tiles(n, m, d, &L.JSx, &L.cpsx);
+            points_plan_tiles(m, n, d, &L.JSy, &L.cpsy);
+        }
         L.o_rowpart = take(sizeof(double) * (size_t)L.JSx * n);      // row sums per column slice
         L.o_colpart = take(sizeof(double) * (size_t)L.JSy * m);      // column sums per row slice
-        const int rows_per_wg = d <= 4 ? kPT2 * kIB2 : kTileRows;
+        const int rows_per_wg = d <= 4 ? kPT2 * L.ibx : kTileRows;
         const int gx = (n + rows_per_wg - 1) / rows_per_wg;
         L.nscal = gx * L.JSx;
         L.o_scal = take(sizeof(double) * 2 * L.nscal);
@@ -242,17 +247,17 @@ struct PointsDiag {
     int32_t cols_per_split;
 };
 
-template <int D, bool WITH_COST>
+template <int D, bool WITH_COST, int IB>
 __global__ __launch_bounds__(kPT2) void k_diag_points(PointsDiag A) {
     __shared__ __align__(16) double tile[kTile2][D + 2];     // [0] collog - colq, [1..D] 2s y, [D+1] collog
     __shared__ double lds[kPT2];
     const int tid = threadIdx.x;
-    double x[kIB2][D], rc[kIB2], rq[kIB2];
-    int row[kIB2];
-    double rs[kIB2];
+    double x[IB][D], rc[IB], rq[IB];
+    int row[IB];
+    double rs[IB];
 #pragma unroll
-    for (int b = 0; b < kIB2; ++b) {
-        row[b] = (blockIdx.x * kIB2 + b) * kPT2 + tid;
+    for (int b = 0; b < IB; ++b) {
+        row[b] = (blockIdx.x * IB + b) * kPT2 + tid;
         const bool ok = row[b] < A.nr;
 #pragma unroll
         for (int t = 0; t < D; ++t) x[b][t] = ok ? A.rows[(size_t)row[b] * D + t] : 0.0;
@@ -281,9 +286,9 @@ __global__ __launch_bounds__(kPT2) void k_diag_points(PointsDiag A) {
             }
         }
         __syncthreads();
-        float rf[kIB2], cf = 0.0f, ef = 0.0f;
+        float rf[IB], cf = 0.0f, ef = 0.0f;
 #pragma unroll
-        for (int b = 0; b < kIB2; ++b) rf[b] = 0.0f;
+        for (int b = 0; b < IB; ++b) rf[b] = 0.0f;
         const int cnt = min(kTile2, (j1 - jt + 1) & ~1);       // staged columns (the tile is padded with -inf)
 #pragma unroll 2
         for (int jj = 0; jj < cnt; ++jj) {
@@ -291,7 +296,7 @@ __global__ __launch_bounds__(kPT2) void k_diag_points(PointsDiag A) {
 #pragma unroll
             for (int t = 0; t < D + 2; ++t) w[t] = tile[jj][t];
 #pragma unroll
-            for (int b = 0; b < kIB2; ++b) {
+            for (int b = 0; b < IB; ++b) {
                 double tq = w[0];                                                  // collog - colq + 2 s x.y
 #pragma unroll
                 for (int t = 0; t < D; ++t) tq = fma(x[b][t], w[1 + t], tq);
@@ -308,12 +313,12 @@ __global__ __launch_bounds__(kPT2) void k_diag_points(PointsDiag A) {
             }
         }
 #pragma unroll
-        for (int b = 0; b < kIB2; ++b) rs[b] += (double)rf[b];
+        for (int b = 0; b < IB; ++b) rs[b] += (double)rf[b];
         cost_acc += (double)cf;
         ent_acc += (double)ef;
     }
 #pragma unroll
-    for (int b = 0; b < kIB2; ++b)
+    for (int b = 0; b < IB; ++b)
         if (row[b] < A.nr) A.part[(size_t)blockIdx.y * A.nr + row[b]] = rs[b];
     if (WITH_COST) {
         const double c_tot = block_sum<kPT2>(cost_acc, lds);
@@ -498,20 +503,34 @@ __global__ __launch_bounds__(256) void k_diag_reduce(ReduceArgs A) {
 // [6] column-marginal L1 error, [7] 0.
 __global__ __launch_bounds__(256) void k_diag_final(const double *red, int nred, const double *scal, int nscal,
                                                     double s, double *out, double *cost_out) {
-    __shared__ double lds[256];
-    double v[7];
+    __shared__ double lds[4 * 9];
+    // per-thread shares, wave sums by DPP, then the 4 waves one after the other: a fixed order
+    double w9[9];
     for (int q = 0; q < 7; ++q) {
         double acc = 0.0;
         for (int w = threadIdx.x; w < nred; w += 256) acc += red[(size_t)w * 8 + q];
-        v[q] = block_sum<256>(acc, lds);
+        w9[q] = acc;
     }
-    double sc[2];
     for (int q = 0; q < 2; ++q) {
         double acc = 0.0;
         for (int w = threadIdx.x; w < nscal; w += 256) acc += scal[(size_t)w * 2 + q];
-        sc[q] = block_sum<256>(acc, lds);
+        w9[7 + q] = acc;
     }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int q = 0; q < 9; ++q) {
+        const double t = wave_sum_f64(w9[q]);
+        if (lane == 0) lds[wave * 9 + q] = t;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
+        double v[7], sc[2];
+#pragma unroll
+        for (int q = 0; q < 9; ++q) {
+            const double t = (lds[q] + lds[9 + q]) + (lds[18 + q] + lds[27 + q]);
+            if (q < 7) v[q] = t;
+            else sc[q - 7] = t;
+        }
         const double eps = 1.4426950408889634074 / s;
         const double mass = v[0];
         const double cost = sc[0] / s;
@@ -760,21 +779,23 @@ hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *
         Y.rows = yp; Y.rowq = yq; Y.rowlog = cj; Y.cols2s = xs; Y.colq = xq; Y.collog = ri;
         Y.nr = a.m; Y.nc = a.n; Y.part = (double *)(ws + L.o_colpart); Y.scal = nullptr; Y.cols_per_split = L.cpsy;
         if (a.d <= 4) {
-            const dim3 gx((a.n + kPT2 * kIB2 - 1) / (kPT2 * kIB2), L.JSx), gy((a.m + kPT2 * kIB2 - 1) / (kPT2 * kIB2), L.JSy);
+            if ((L.ibx != 1 && L.ibx != kIB2) || (L.iby != 1 && L.iby != kIB2)) return hipErrorInvalidValue;
+            const dim3 gx((a.n + kPT2 * L.ibx - 1) / (kPT2 * L.ibx), L.JSx), gy((a.m + kPT2 * L.iby - 1) / (kPT2 * L.iby), L.JSy);
+#define FS_DIAG_PTS(D)                                                                                       \
+    do {                                                                                                     \
+        if (L.ibx == 1) hipLaunchKernelGGL((k_diag_points<D, true, 1>), gx, dim3(kPT2), 0, st, X);           \
+        else hipLaunchKernelGGL((k_diag_points<D, true, kIB2>), gx, dim3(kPT2), 0, st, X);                   \
+        if (cost_only) break;                                                                                \
+        if (L.iby == 1) hipLaunchKernelGGL((k_diag_points<D, false, 1>), gy, dim3(kPT2), 0, st, Y);          \
+        else hipLaunchKernelGGL((k_diag_points<D, false, kIB2>), gy, dim3(kPT2), 0, st, Y);                  \
+    } while (0)
             switch (a.d) {
-                case 1: hipLaunchKernelGGL((k_diag_points<1, true>), gx, dim3(kPT2), 0, st, X);
-                        if (!cost_only) hipLaunchKernelGGL((k_diag_points<1, false>), gy, dim3(kPT2), 0, st, Y);
-                        break;
-                case 2: hipLaunchKernelGGL((k_diag_points<2, true>), gx, dim3(kPT2), 0, st, X);
-                        if (!cost_only) hipLaunchKernelGGL((k_diag_points<2, false>), gy, dim3(kPT2), 0, st, Y);
-                        break;
-                case 3: hipLaunchKernelGGL((k_diag_points<3, true>), gx, dim3(kPT2), 0, st, X);
-                        if (!cost_only) hipLaunchKernelGGL((k_diag_points<3, false>), gy, dim3(kPT2), 0, st, Y);
-                        break;
-                default: hipLaunchKernelGGL((k_diag_points<4, true>), gx, dim3(kPT2), 0, st, X);
-                         if (!cost_only) hipLaunchKernelGGL((k_diag_points<4, false>), gy, dim3(kPT2), 0, st, Y);
-                        break;
+                case 1: FS_DIAG_PTS(1); break;
+                case 2: FS_DIAG_PTS(2); break;
+                case 3: FS_DIAG_PTS(3); break;
+                default: FS_DIAG_PTS(4); break;
             }
+#undef FS_DIAG_PTS
         } else {
             const dim3 gx((a.n + kTileRows - 1) / kTileRows, L.JSx), gy((a.m + kTileRows - 1) / kTileRows, L.JSy);
 #define FS_DIAG_MFMA(D4)                                                                                   \

@@ -129,7 +129,10 @@ struct PointsArgs {
     const double *rowconst;
 };
 void points_plan(int nr, int nc, int d, int *JS, int *cols_per_split);
-void points_plan_tiles(int nr, int nc, int d, int *JS, int *cols_per_split);   // same for the after-the-loop kernels
+void points_plan_tiles(int nr, int nc, int d, int *JS, int *cols_per_split);   // after-the-loop kernels, d > 4
+// After-the-loop vector kernels (d <= 4, 256 rows x ib per workgroup): rows per lane and column slices of
+// whole 64-column groups, about `wgs` workgroups and at most `max_slices` slices.
+void points_plan_after(int nr, int nc, int wgs, int max_slices, int *JS, int *cols_per_split, int *ib);
 bool points_optimistic(int d);      // does the LSE pass for this dimension have the optimistic (FAST) variant?
 hipError_t launch_points_lse(hipStream_t st, const PointsArgs &a, const Ctl &c, int use_next_shift, int ld_shift,
                              const Stamp &tm = Stamp());

@@ -321,8 +321,8 @@ void points_plan(int nr, int nc, int d, int *JS, int *cols_per_split) {
     *cols_per_split = cps;
 }
 
-// The after-the-loop kernels (diagnostics, barycentric mapping; one pass each, 4 rows per lane, tiles of
-// kTile columns walked in full): slices of whole tiles.
+// The after-the-loop matrix-core kernels (diagnostics, barycentric mapping; one pass each): slices of whole
+// tiles of kTile columns.
 void points_plan_tiles(int nr, int nc, int d, int *JS, int *cols_per_split) {
     const int rows_per_wg = (d <= 4) ? kPT * kIB : kPT;
     const int rowblocks = (nr + rows_per_wg - 1) / rows_per_wg;
@@ -333,6 +333,18 @@ void points_plan_tiles(int nr, int nc, int d, int *JS, int *cols_per_split) {
     if (js < 1) js = 1;
     int cps = (nc + js - 1) / js;
     cps = ((cps + kTile - 1) / kTile) * kTile;
+    *JS = (nc + cps - 1) / cps;
+    *cols_per_split = cps;
+}
+
+void points_plan_after(int nr, int nc, int wgs, int max_slices, int *JS, int *cols_per_split, int *ib) {
+    *ib = points_ib(nr);
+    const int rows_per_wg = kPT * *ib;
+    const int rowblocks = (nr + rows_per_wg - 1) / rows_per_wg;
+    int want = (wgs + rowblocks - 1) / rowblocks;
+    if (want > max_slices) want = max_slices;
+    int cps = (nc + want - 1) / want;
+    cps = ((cps + 63) / 64) * 64;
     *JS = (nc + cps - 1) / cps;
     *cols_per_split = cps;
 }

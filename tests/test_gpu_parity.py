@@ -887,7 +887,8 @@ def test_plan_and_cost(fs, oracle, kind):
                                          ("points", 129, 257, 64),
                                          # small problems: one single-workgroup launch
                                          ("dense", 100, 120, 0), ("dense", 1, 1, 0), ("dense", 5, 1000, 0),
-                                         ("points", 200, 210, 3), ("points", 31, 64, 1), ("points", 256, 255, 4)])
+                                         ("points", 200, 210, 3), ("points", 31, 64, 1), ("points", 256, 255, 4),
+                                         ("points", 8300, 150, 3), ("points", 150, 8300, 2), ("points", 2100, 1990, 1)])
 @pytest.mark.parametrize("precision", ["f32", "f64"])
 def test_diagnostics_one_pass(fs, oracle, kind, n, m, d, precision):
     """fs_diagnostics against the oracle's direct definitions (explicit plan, own sums): cost, mass, KL,
@@ -924,7 +925,8 @@ def test_diagnostics_one_pass(fs, oracle, kind, n, m, d, precision):
 @pytest.mark.parametrize("kind,n,m,d,dz", [("dense", 300, 257, 0, 3), ("dense", 130, 4100, 0, 1), ("dense", 700, 8192, 0, 4),
                                             ("dense", 17, 3, 0, 2), ("dense", 61, 4102, 0, 3), ("points", 700, 1300, 3, 3), ("points", 1030, 500, 2, 4),
                                             ("points", 90, 200, 7, 2), ("points", 400, 300, 12, 4), ("points", 131, 1025, 40, 1),
-                                            ("points", 260, 64, 64, 3)])
+                                            ("points", 260, 64, 64, 3), ("points", 8300, 140, 3, 2),
+                                            ("points", 2100, 1990, 4, 3)])
 def test_barycentric_mapping(fs, oracle, kind, n, m, d, dz):
     """fs_barycentric against the oracle's explicit-plan definition; a zero-weight row maps to 0."""
     import torch
