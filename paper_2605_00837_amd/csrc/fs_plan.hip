@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void k_plan_cost(PlanArgs A, const double *ri,
         lds[threadIdx.x] = acc;
         __syncthreads();
         for (int w = 128; w >= 1; w >>= 1) {
-            if (threadIdx.x < w) lds[threadIdx.x] += lds[threadIdx.x + w];
+            if ((int)threadIdx.x < w) lds[threadIdx.x] += lds[threadIdx.x + w];
             __syncthreads();
         }
         if (threadIdx.x == 0) partial[(size_t)blockIdx.y * gridDim.x + blockIdx.x] = lds[0];
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(256) void k_sum_partials(const double *partial, int
     lds[threadIdx.x] = acc;
     __syncthreads();
     for (int w = 128; w >= 1; w >>= 1) {
-        if (threadIdx.x < w) lds[threadIdx.x] += lds[threadIdx.x + w];
+        if ((int)threadIdx.x < w) lds[threadIdx.x] += lds[threadIdx.x + w];
         __syncthreads();
     }
     if (threadIdx.x == 0) out[0] = lds[0];

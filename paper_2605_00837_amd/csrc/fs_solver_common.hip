@@ -179,7 +179,6 @@ constexpr int kErrWave = 1;
 constexpr int kTicketBits = 14;                        // up to 16383 workgroups
 constexpr double kErrScale = 35184372088832.0;         // 2^45: sums below 16 fit in bits 14..62, resolution 2.8e-14
 constexpr unsigned long long kErrBad = 1ull << 63;
-constexpr double kLn2 = 0.6931471805599453094;
 
 __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
     __shared__ double sM[kCombW][64];
