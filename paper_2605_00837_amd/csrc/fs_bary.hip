@@ -48,7 +48,7 @@ BaryLayout bary_layout(int n, int m, int d) {
         L.P = (n + rpp - 1) / rpp;
         L.nparts = L.nstrips;
     } else {
-        if (d <= 4) points_plan_after(n, m, 512, 64, &L.JS, &L.cps, &L.ib);
+        if (d <= 4) points_plan_after(n, m, 2048, 64, &L.JS, &L.cps, &L.ib);
         else points_plan_tiles(n, m, d, &L.JS, &L.cps);
         L.nparts = L.JS;
         L.o_xp = take(sizeof(double) * (size_t)n * d);

@@ -70,8 +70,8 @@ DiagLayout diag_layout(int n, int m, int d) {
         L.o_scal = take(sizeof(double) * 2 * L.nscal);
     } else {
         if (d <= 4) {
-            points_plan_after(n, m, 1024, 128, &L.JSx, &L.cpsx, &L.ibx);
-            points_plan_after(m, n, 1024, 128, &L.JSy, &L.cpsy, &L.iby);
+            points_plan_after(n, m, 2048, 128, &L.JSx, &L.cpsx, &L.ibx);
+            points_plan_after(m, n, 2048, 128, &L.JSy, &L.cpsy, &L.iby);
         } else {
             points_plan_tiles(n, m, d, &L.JSx, &L.cpsx);
             points_plan_tiles(m, n, d, &L.JSy, &L.cpsy);

@@ -46,6 +46,16 @@ def main():
     print(f"| fs_cost | {tag} | {timeit(lambda: fs.fs_cost(a, b, w.eps, f, g, X=X, Y=Y), 3):.0f} |", flush=True)
     print(f"| fs_diagnostics | {tag} | {timeit(lambda: fs.fs_diagnostics(a, b, w.eps, f, g, X=X, Y=Y), 3):.0f} |", flush=True)
     print(f"| fs_barycentric (Z = Y) | {tag} | {timeit(lambda: fs.fs_barycentric(a, b, w.eps, f, g, Y, X=X, Y=Y), 3):.0f} |", flush=True)
+    del X, Y
+    for n in (512, 4096):
+        w = W.random_points(n, n, 3, seed=1, eps=0.05)
+        X, Y, a, b = (torch.from_numpy(t).cuda() for t in (w.X, w.Y, w.a, w.b))
+        r = fs.fs_sinkhorn_solve(a, b, w.eps, 30, 0.0, X=X, Y=Y, want_f64=True)
+        f, g = r["f64"], r["g64"]
+        tag = f"points {n} x {n}, d = 3"
+        print(f"| fs_cost | {tag} | {timeit(lambda: fs.fs_cost(a, b, w.eps, f, g, X=X, Y=Y), 100):.1f} |", flush=True)
+        print(f"| fs_diagnostics | {tag} | {timeit(lambda: fs.fs_diagnostics(a, b, w.eps, f, g, X=X, Y=Y), 100):.1f} |", flush=True)
+        print(f"| fs_barycentric (Z = Y) | {tag} | {timeit(lambda: fs.fs_barycentric(a, b, w.eps, f, g, Y, X=X, Y=Y), 100):.1f} |", flush=True)
 
     print()
     print("| solve | iterations | ms | per problem-iteration |")
