@@ -702,6 +702,15 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
 
 struct FusedShape { int T, Q, R; };
 
+// Workgroups the 256 compute units hold at once.
+// k_fused_pf<1, 2, true> (m = 4096, fp32: 55 registers, 67 KiB of LDS) fits twice; with at least 16 panels per
+// workgroup that is worth it (16384 x 4096: 60.7 -> 52.7 us per iteration), below and for the masked widths it is not.
+static int fused_resident(const FusedShape &s, int c_dtype, int n, int m) {
+    if (s.T == 256) return 1024;
+    if (s.R == 302 && s.Q == 1 && c_dtype == 0 && m == 4096 && n >= 8192) return 512;
+    return 256;
+}
+
 // Shapes held in registers without spilling: 4*Q*T columns, R rows per panel.
 static bool fused_shape(int m, int variant, int c_dtype, FusedShape *fsh) {
     if (variant >= 100) variant -= 100;
@@ -753,7 +762,7 @@ void dense_fused_plan(int n, int m, int *P) {
     for (int variant = 0; variant < 8; ++variant) {        // 6, 7: the shapes for 2-byte costs
         if (!fused_shape(m, variant < 6 ? variant : 0, variant < 6 ? 0 : variant - 5, &s)) continue;
         const int npanels = (n + (s.R % 100) - 1) / (s.R % 100);
-        const int resident = s.T == 256 ? 1024 : 256;      // workgroups the 256 CUs hold at once
+        const int resident = fused_resident(s, variant < 6 ? 0 : variant - 5, n, m);
         const int p = npanels < resident ? npanels : resident;
         if (p > best) best = p;
     }
@@ -764,7 +773,7 @@ hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, 
     FusedShape s;
     if (!fused_shape(a.p.m, variant, a.c_dtype, &s)) return hipErrorInvalidValue;
     const int npanels = (a.p.n + (s.R % 100) - 1) / (s.R % 100);
-    const int resident = s.T == 256 ? 1024 : 256;
+    const int resident = fused_resident(s, a.c_dtype, a.p.n, a.p.m);
     int g = npanels < resident ? npanels : resident;
     if (g > a.P) g = a.P;
     DenseArgs b = a;
@@ -812,7 +821,7 @@ int dense_fused_grid(int n, int m, int variant, int c_dtype) {
     FusedShape s;
     if (!fused_shape(m, variant, c_dtype, &s)) return 0;
     const int npanels = (n + (s.R % 100) - 1) / (s.R % 100);
-    const int resident = s.T == 256 ? 1024 : 256;
+    const int resident = fused_resident(s, c_dtype, n, m);
     return npanels < resident ? npanels : resident;
 }
 

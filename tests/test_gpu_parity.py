@@ -276,6 +276,18 @@ def test_dense_shape_sweep(fs, oracle, t, n, m, dt, mode, eps, zeros):
     assert pot_err(g64[fin_g], ref["g"][fin_g], eps) < TOL_F64
 
 
+def test_dense_tall_full_width(fs, oracle):
+    """8192 rows or more at m = 4096: the fused pass runs two workgroups per compute unit (512 sets of column
+    partials); the row count is ragged against both the panel size and the grid."""
+    n, m, eps = 8201, 4096, 0.05
+    w = W.random_dense(n, m, seed=9300, cmax=2.0, eps=eps)
+    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), eps, 6, 0.0, C=dev(w.C), want_f64=True)
+    ref = oracle.solve(w.a, w.b, eps, 6, C=w.C)
+    assert r["iters"] == 6 and not r["nonfinite"]
+    assert pot_err(r["f64"].cpu().numpy(), ref["f"], eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), ref["g"], eps) < TOL_F64
+
+
 def _points_sweep_cases():
     rng = np.random.default_rng(20240608)
     dims = [1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64]
