@@ -242,24 +242,33 @@ __global__ __launch_bounds__(T) void k_fused(DenseArgs A, Ctl c) {
     // odd iterations walk the panels from the bottom up: what the previous iteration read last is
     // still in the last-level cache and is read first
     const bool rev = (k & 1) != 0;
-    for (int pq = blockIdx.x; pq < npanels; pq += gridDim.x, par ^= 1) {
-        const int pn = rev ? npanels - 1 - pq : pq;
-        const int i0 = pn * R;
-        float cv[R][Q][4];
+    // Small panels (16 registers) are loaded one panel ahead, so that a workgroup with many panels (a tall
+    // matrix) does not wait out a full memory round trip per panel.
+    constexpr bool kAhead = T == 256 && R * Q * 4 <= 16;
+    auto load_panel = [&](int pq, float (&dst)[R][Q][4]) {
+        const int i0 = (rev ? npanels - 1 - pq : pq) * R;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const bool rok = (i0 + r) < p.n;
+            const bool rok = pq < npanels && (i0 + r) < p.n;
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
                 const int col = (q * T + tid) * 4;
                 if (rok && col < m) {
-                    VecLoad<4>::ld(A.C + (size_t)(i0 + r) * m + col, cv[r][q], 4);
+                    VecLoad<4>::ld(A.C + (size_t)(i0 + r) * m + col, dst[r][q], 4);
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) cv[r][q][e] = 0.0f;
+                    for (int e = 0; e < 4; ++e) dst[r][q][e] = 0.0f;
                 }
             }
         }
+    };
+    float cv[R][Q][4], ahead[kAhead ? R : 1][kAhead ? Q : 1][4];
+    if (kAhead) load_panel(blockIdx.x, cv);
+    for (int pq = blockIdx.x; pq < npanels; pq += gridDim.x, par ^= 1) {
+        const int pn = rev ? npanels - 1 - pq : pq;
+        const int i0 = pn * R;
+        if constexpr (kAhead) load_panel(pq + gridDim.x, ahead);
+        else load_panel(pq, cv);
         // ---- row phase: lane-local LSE over the lane's 4Q columns (one row at a time, so that
         //      only one row's fp64 arguments are live), then the wave reductions of all R rows
         Lse rs[R];
@@ -322,6 +331,14 @@ __global__ __launch_bounds__(T) void k_fused(DenseArgs A, Ctl c) {
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        if constexpr (kAhead) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) cv[r][q][e] = ahead[r][q][e];
+        }
     }
     if (col_phase) {
 #pragma unroll
@@ -332,6 +349,129 @@ __global__ __launch_bounds__(T) void k_fused(DenseArgs A, Ctl c) {
                 for (int e = 0; e < 4; ++e)
                     A.colpart[(size_t)blockIdx.x * p.m_ld + col + e] = cs[q][e].value();
             }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- fused pass, one wave per row
+// Narrow matrices (m <= 256 Q): a row fits the 64 lanes of ONE wave (Q groups of 4 adjacent columns per lane),
+// so the 4 waves of a workgroup walk different panels of R rows and never meet inside the loop: the row LSE is a
+// wave reduction, no LDS, no barrier.  Their column LSE pairs meet once, at the end, in LDS, and the workgroup
+// writes one set of column partials.  Same exact running-maximum arithmetic as k_fused; with all 256 lanes of
+// k_fused<256, 1, 4> mapped to columns, three waves in four idled at m = 256 (65536 x 256: 86 us per pass).
+template <int Q, int R>
+__global__ __launch_bounds__(256) void k_fused_rows(DenseArgs A, Ctl c) {
+    constexpr int NW = 4;
+    __shared__ double sM[NW][Q * 256];
+    __shared__ float sS[NW][Q * 256];
+    int k;
+    if (!launch_active(c, k)) return;
+    const int cur = k & 1, nxt = cur ^ 1;
+    const Pots &p = A.p;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const double ns = -p.s;
+    const bool col_phase = (c.phase == 0);        // the trailing error pass needs the row LSE only
+    const int m = p.m;                            // m % 4 == 0 on this path
+
+    double v[Q][4];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int col = (q * 64 + lane) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            v[q][e] = col < m ? p.V[(size_t)cur * p.m_ld + col + e] : -__builtin_huge_val();
+    }
+    Lse cs[Q][4];
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cs[q][e].init();
+
+    const int npanels = (p.n + R - 1) / R;
+    const int first = blockIdx.x * NW + wave, stride = gridDim.x * NW;
+    auto load_panel = [&](int pq, float (&dst)[R][Q][4]) {
+        const int i0 = pq * R;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const bool rok = pq < npanels && (i0 + r) < p.n;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int col = (q * 64 + lane) * 4;
+                if (rok && col < m) {
+                    VecLoad<4>::ld(A.C + (size_t)(i0 + r) * m + col, dst[r][q], 4);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) dst[r][q][e] = 0.0f;
+                }
+            }
+        }
+    };
+    float cv[R][Q][4], ahead[R][Q][4];
+    load_panel(first, cv);
+    for (int pq = first; pq < npanels; pq += stride) {
+        const int i0 = pq * R;
+        load_panel(pq + stride, ahead);           // one panel ahead: the round trip runs under this panel's arithmetic
+        double Fn[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            double x[Q * 4];
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[q * 4 + e] = fma(ns, (double)cv[r][q][e], v[q][e]);
+            Lse rs;
+            rs.init();
+            rs.template add<Q * 4>(x);
+            rs.wave_reduce();
+            Fn[r] = rs.value();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        double u[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const bool rok = (i0 + r) < p.n;
+            const double la = rok ? p.la2[i0 + r] : 0.0;
+            u[r] = rok ? la - Fn[r] : -__builtin_huge_val();
+            if (lane == r && rok) {               // lane r writes row r
+                p.F[(size_t)nxt * p.n_ld + i0 + r] = Fn[r];
+                p.U[(size_t)nxt * p.n_ld + i0 + r] = u[r];
+            }
+        }
+        if (col_phase) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    double y[R];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) y[r] = fma(ns, (double)cv[r][q][e], u[r]);
+                    cs[q][e].template add<R>(y);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) cv[r][q][e] = ahead[r][q][e];
+    }
+    if (col_phase) {                              // uniform over the workgroup: every wave arrives here
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                sM[wave][(q * 64 + lane) * 4 + e] = cs[q][e].M;
+                sS[wave][(q * 64 + lane) * 4 + e] = cs[q][e].s;
+            }
+        __syncthreads();
+        for (int col = tid; col < m; col += 256) {
+            Lse t;
+            t.M = sM[0][col]; t.s = sS[0][col];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) t.merge(sM[w][col], sS[w][col]);
+            A.colpart[(size_t)blockIdx.x * p.m_ld + col] = t.value();
         }
     }
 }
@@ -706,6 +846,9 @@ struct FusedShape { int T, Q, R; };
 // k_fused_pf<1, 2, true> (m = 4096, fp32: 55 registers, 67 KiB of LDS) fits twice; with at least 16 panels per
 // workgroup that is worth it (16384 x 4096: 60.7 -> 52.7 us per iteration), below and for the masked widths it is not.
 static int fused_resident(const FusedShape &s, int c_dtype, int n, int m) {
+    // one wave per row: 1024 workgroups once every wave still gets 4 panels, else 512 (half the column partials
+    // for k_combine; 8192 x 512: 16.7 against 21.1 us per iteration, 100000 x 512: 86.5 against 73.8)
+    if (s.T == 64) return (n + s.R - 1) / s.R >= 16384 ? 1024 : 512;
     if (s.T == 256) return 1024;
     if (s.R == 302 && s.Q == 1 && c_dtype == 0 && m == 4096 && n >= 8192) return 512;
     return 256;
@@ -726,6 +869,7 @@ static bool fused_shape(int m, int variant, int c_dtype, FusedShape *fsh) {
         if (m <= 1024) return false;
         if (m <= 8192) variant = 0;
     }
+    if (m <= 512 && variant != 1) { *fsh = {64, m <= 256 ? 1 : 2, m <= 256 ? 4 : 2}; return true; }    // one wave per row
     if (m <= 1024) { *fsh = {256, 1, 4}; return true; }
     if (m <= 4096) {
         if (variant == 1) *fsh = {1024, 1, 4};               // register panel, exact running-max arithmetic
@@ -761,7 +905,8 @@ void dense_fused_plan(int n, int m, int *P) {
     int best = 1;
     for (int variant = 0; variant < 8; ++variant) {        // 6, 7: the shapes for 2-byte costs
         if (!fused_shape(m, variant < 6 ? variant : 0, variant < 6 ? 0 : variant - 5, &s)) continue;
-        const int npanels = (n + (s.R % 100) - 1) / (s.R % 100);
+        int npanels = (n + (s.R % 100) - 1) / (s.R % 100);
+        if (s.T == 64) npanels = (npanels + 3) / 4;        // four waves, a panel each
         const int resident = fused_resident(s, variant < 6 ? 0 : variant - 5, n, m);
         const int p = npanels < resident ? npanels : resident;
         if (p > best) best = p;
@@ -772,7 +917,8 @@ void dense_fused_plan(int n, int m, int *P) {
 hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, int variant, const Stamp &tm) {
     FusedShape s;
     if (!fused_shape(a.p.m, variant, a.c_dtype, &s)) return hipErrorInvalidValue;
-    const int npanels = (a.p.n + (s.R % 100) - 1) / (s.R % 100);
+    int npanels = (a.p.n + (s.R % 100) - 1) / (s.R % 100);
+    if (s.T == 64) npanels = (npanels + 3) / 4;
     const int resident = fused_resident(s, a.c_dtype, a.p.n, a.p.m);
     int g = npanels < resident ? npanels : resident;
     if (g > a.P) g = a.P;
@@ -802,6 +948,8 @@ hipError_t launch_dense_fused(hipStream_t st, const DenseArgs &a, const Ctl &c, 
     else if (s.R == 302 && s.Q == 1) launch_stamped((k_fused_pf<1, 2, false>), grid, dim3(1024), st, tm, b, c);
     else if (s.R == 302 && a.p.m == 8192 && variant % 100 != 5) launch_stamped((k_fused_pf<2, 2, true>), grid, dim3(1024), st, tm, b, c);
     else if (s.R == 302) launch_stamped((k_fused_pf<2, 2, false>), grid, dim3(1024), st, tm, b, c);
+    else if (s.T == 64 && s.Q == 1) launch_stamped((k_fused_rows<1, 4>), grid, dim3(256), st, tm, b, c);
+    else if (s.T == 64) launch_stamped((k_fused_rows<2, 2>), grid, dim3(256), st, tm, b, c);
     else if (s.T == 256) launch_stamped((k_fused<256, 1, 4>), grid, dim3(256), st, tm, b, c);
     else if (s.T == 1024 && s.Q == 1) launch_stamped((k_fused<1024, 1, 4>), grid, dim3(1024), st, tm, b, c);
     else if (s.T == 1024 && s.R == 2) launch_stamped((k_fused<1024, 2, 2>), grid, dim3(1024), st, tm, b, c);
@@ -820,7 +968,8 @@ bool dense_fused_predicts(int m, int variant, int c_dtype) {
 int dense_fused_grid(int n, int m, int variant, int c_dtype) {
     FusedShape s;
     if (!fused_shape(m, variant, c_dtype, &s)) return 0;
-    const int npanels = (n + (s.R % 100) - 1) / (s.R % 100);
+    int npanels = (n + (s.R % 100) - 1) / (s.R % 100);
+    if (s.T == 64) npanels = (npanels + 3) / 4;
     const int resident = fused_resident(s, c_dtype, n, m);
     return npanels < resident ? npanels : resident;
 }

@@ -392,7 +392,15 @@ __global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
 
 hipError_t launch_combine(hipStream_t st, const CombineArgs &a, const Ctl &c) {
     if ((a.len + 63) / 64 >= (1 << kTicketBits)) return hipErrorInvalidValue;     // the ticket field would overflow
-    hipLaunchKernelGGL(k_combine, dim3((a.len + 63) / 64), dim3(kCombT), 0, st, a, c);
+    int grid = (a.len + 63) / 64;
+    if (a.do_advance) {
+        // the error sum runs over the OTHER side's es.n rows, 128 per workgroup without a loop: a tall problem
+        // (65536 x 256: 4 workgroups by len) gets workgroups that own no entry and only carry error terms
+        int want = (a.es.n + 127) / 128;
+        if (want > 2048) want = 2048;
+        if (want > grid) grid = want;
+    }
+    hipLaunchKernelGGL(k_combine, dim3(grid), dim3(kCombT), 0, st, a, c);
     return hipGetLastError();
 }
 

@@ -112,6 +112,24 @@ def test_dense_solve_modes(fs, oracle, mode, n, m):
     assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
 
 
+@pytest.mark.parametrize("variant", [0, 1])      # 0: one wave per row (k_fused_rows), 1: all lanes on columns (k_fused<256,1,4>)
+@pytest.mark.parametrize("n,m", [(5001, 256), (4099, 200), (1000, 512), (777, 260), (9, 4), (300, 508), (3, 256),
+                                 (17000, 64), (40000, 8)])
+def test_fused_narrow(fs, oracle, variant, n, m):
+    """Narrow matrices on the fused path: many panels per wave, ragged row counts, column counts on both sides of
+    the one- and two-group limits, fewer panels than waves."""
+    w = W.random_dense(n, m, seed=3500 + n + m, cmax=2.0, eps=0.04)
+    w.a[::7] = 0.0
+    w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    r, ref, e64, e32 = _solve_and_compare(fs, oracle, w, 15, kernel_mode=2, fused_variant=variant)
+    fin = np.isfinite(ref["f"])
+    assert np.array_equal(np.isfinite(r["f64"].cpu().numpy()), fin)
+    assert pot_err(r["f64"].cpu().numpy()[fin], ref["f"][fin], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+
+
 @pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
 def test_fused_variants_full_width(fs, oracle, variant):
     w = W.random_dense(70, 8192, seed=77, cmax=2.0, eps=0.03)
