@@ -333,6 +333,64 @@ def test_points_shape_sweep(fs, oracle, t, n, m, d, eps, zeros):
     assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
 
 
+def _after_loop_sweep_cases():
+    rng = np.random.default_rng(20240609)
+    cases = []
+    for t in range(40):
+        if t % 2 == 0:
+            kind, d = "dense", 0
+            n, m = int(rng.integers(1, 2500)), int(rng.integers(1, 2500))
+        else:
+            kind, d = "points", int(rng.choice([1, 2, 3, 4, 5, 16]))
+            if t % 8 == 1:                               # 8192 rows or more on one side: four rows per lane
+                n, m = int(rng.integers(8192, 9500)), int(rng.integers(1, 400))
+                if rng.integers(0, 2):
+                    n, m = m, n
+            else:
+                n, m = int(rng.integers(1, 3000)), int(rng.integers(1, 3000))
+        cases.append((t, kind, n, m, d, float(rng.choice([0.03, 0.1, 0.5])), int(rng.integers(1, 5)),
+                      "f64" if rng.integers(0, 2) else "f32", bool(rng.integers(0, 3) == 0)))
+    return cases
+
+
+@pytest.mark.parametrize("t,kind,n,m,d,eps,dz,precision,zeros", _after_loop_sweep_cases())
+def test_after_loop_shape_sweep(fs, oracle, t, kind, n, m, d, eps, dz, precision, zeros):
+    """Seeded sweep of fs_diagnostics, fs_cost, fs_barycentric and fs_plan over ragged shapes on both sides of every
+    launch-shape switch (single workgroup, one or four rows per lane, matrix-core tiles), unconverged potentials."""
+    import torch
+    w = W.random_dense(n, m, seed=9500 + t, cmax=2.0, eps=eps) if kind == "dense" else \
+        W.random_points(n, m, d, seed=9500 + t, eps=eps)
+    if zeros and n > 3 and m > 3:
+        w.a[::3] = 0.0
+        w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    ref = oracle.solve(w.a, w.b, eps, 3, C=w.C, X=w.X, Y=w.Y)
+    f_h, g_h = ref["f"], ref["g"]
+    dt = torch.float64
+    if precision == "f32":
+        f_h, g_h = f_h.astype(np.float32).astype(np.float64), g_h.astype(np.float32).astype(np.float64)
+        dt = torch.float32
+    geo, a, b = to_dev(w)
+    fd, gd = dev(f_h, dt), dev(g_h, dt)
+    r = fs.fs_diagnostics(a, b, eps, fd, gd, want_marginals=True, **geo)
+    got = dict(zip(fs.DIAG_FIELDS, r["out"].cpu().numpy()))
+    o = oracle.objectives(w.a, w.b, eps, f_h, g_h, C=w.C, X=w.X, Y=w.Y)
+    ro, co = oracle.marginals(w.a, w.b, eps, f_h, g_h, C=w.C, X=w.X, Y=w.Y)
+    for key in ("cost", "mass", "kl", "primal", "dual"):
+        assert abs(got[key] - float(o[key])) <= 2e-6 * max(1.0, abs(float(o[key]))), (key, got[key], float(o[key]))
+    assert np.abs(r["row_marginal"].cpu().numpy() - ro).sum() <= 2e-6
+    assert np.abs(r["col_marginal"].cpu().numpy() - co).sum() <= 2e-6
+    cost2 = float(fs.fs_cost(a, b, eps, fd, gd, **geo).cpu()[0])
+    assert abs(cost2 - float(o["cost"])) <= 2e-6 * max(1.0, abs(float(o["cost"])))
+    Z = np.random.default_rng(t).standard_normal((m, dz)).astype(np.float32)
+    To = oracle.barycentric(w.a, w.b, eps, f_h, g_h, Z.astype(np.float64), C=w.C, X=w.X, Y=w.Y)
+    T = fs.fs_barycentric(a, b, eps, fd, gd, dev(Z), **geo).cpu().numpy()
+    assert np.abs(T - To).max() <= 5e-6 * (1.0 + float(np.abs(Z).max()))
+    if n * m <= 2_000_000:
+        P = fs.fs_plan(a, b, eps, fd, gd, **geo).cpu().numpy()
+        Po = oracle.plan(w.a, w.b, eps, f_h, g_h, C=w.C, X=w.X, Y=w.Y)
+        assert np.abs(P - Po).sum() <= 1e-5
+
+
 @pytest.mark.parametrize("n,m,mode", [(5000, 64, 0), (3000, 12, 1), (40, 20000, 0), (9, 16388, 0), (2, 70001, 1)])
 def test_dense_extreme_aspect_ratios(fs, oracle, n, m, mode):
     """Very tall (many rows of the error sum per workgroup of the combine) and very wide (beyond the
