@@ -173,14 +173,15 @@ hipError_t launch_advance(hipStream_t st, const ErrSrc &es, const Ctl &c) {
 //
 // The kernel is a chain of memory latencies, so every load whose address does not depend on the
 // iteration counter is issued before the counter itself has arrived.
-constexpr int kCombW = 16;
-constexpr int kCombT = kCombW * 64;
 constexpr int kErrWave = 1;
 constexpr int kTicketBits = 14;                        // up to 16383 workgroups
 constexpr double kErrScale = 35184372088832.0;         // 2^45: sums below 16 fit in bits 14..62, resolution 2.8e-14
 constexpr unsigned long long kErrBad = 1ull << 63;
 
-__global__ __launch_bounds__(kCombT) void k_combine(CombineArgs A, Ctl c) {
+template <int kCombW>
+__global__ __launch_bounds__(kCombW * 64) void k_combine(CombineArgs A, Ctl c) {
+    constexpr int kCombT = kCombW * 64;
+    static_assert(kCombW > kErrWave, "the error terms have a wave of their own");
     __shared__ double sM[kCombW][64];
     __shared__ float sS[kCombW][64];
     __shared__ unsigned long long s_mask;
@@ -400,7 +401,10 @@ hipError_t launch_combine(hipStream_t st, const CombineArgs &a, const Ctl &c) {
         if (want > 2048) want = 2048;
         if (want > grid) grid = want;
     }
-    hipLaunchKernelGGL(k_combine, dim3(grid), dim3(kCombT), 0, st, a, c);
+    // 16 waves per 64 entries split up to hundreds of partial sets; with 16 sets or fewer (a tall point cloud:
+    // 65536 rows against 256 columns leave 4 column slices) 4 waves do, and four times as many workgroups fit
+    if (a.P <= 16) hipLaunchKernelGGL(k_combine<4>, dim3(grid), dim3(4 * 64), 0, st, a, c);
+    else hipLaunchKernelGGL(k_combine<16>, dim3(grid), dim3(16 * 64), 0, st, a, c);
     return hipGetLastError();
 }
 
