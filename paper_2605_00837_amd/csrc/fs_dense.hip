@@ -840,6 +840,9 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
 #endif
 }
 
+// Which fused kernel a width gets.  T = 256, 512, 1024: k_fused<T, Q, R> (T lanes on columns, Q groups of 4 columns
+// per lane, R rows per panel).  R = 301 / 302: k_fused_pf<Q, R - 300> (LDS prefetch, 1024 lanes).  T = 64:
+// k_fused_rows<Q, R> (one wave per row, 4 waves per workgroup).  R % 100 is the number of rows per panel throughout.
 struct FusedShape { int T, Q, R; };
 
 // Workgroups the 256 compute units hold at once.
