@@ -18,6 +18,7 @@
 namespace fs {
 
 constexpr int kRowsPerWG = 4;      // k_row_stream
+constexpr int kFewRows = 2048;     // below: k_row_stream_few, one row per workgroup
 constexpr int kStreamT = 256;
 
 template <int VEC>
@@ -116,6 +117,61 @@ __global__ __launch_bounds__(kStreamT) void k_row_stream(DenseArgs A, Ctl c) {
     }
 }
 
+// ---------------------------------------------------------------- row pass, few rows
+// Short and wide matrices (fewer than kFewRows rows): with 4 rows per workgroup a 512 x 100000 problem is 128
+// workgroups with one 16-byte load per row in flight per lane (1.3 TB/s).  Here a workgroup owns ONE row and every
+// lane keeps UN column chunks of it in flight.
+template <int VEC, int DT = 0>
+__global__ __launch_bounds__(kStreamT) void k_row_stream_few(DenseArgs A, Ctl c) {
+    constexpr int UN = 4;
+    __shared__ double sM[kStreamT / 64];
+    __shared__ float sS[kStreamT / 64];
+    int k;
+    if (!launch_active(c, k)) return;
+    const int cur = k & 1, nxt = cur ^ 1;
+    const Pots &p = A.p;
+    const int tid = threadIdx.x;
+    const int i = blockIdx.x;                          // the grid has exactly n workgroups
+    const double *V = p.V + (size_t)cur * p.m_ld;
+    const double ns = -p.s;
+    Lse acc;
+    acc.init();
+    for (int col0 = tid * VEC; col0 < p.m; col0 += kStreamT * VEC * UN) {
+        float cv[UN][VEC];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int col = col0 + u * kStreamT * VEC;
+            if (col < p.m) {
+                load_costs<VEC, DT>(A.C, (size_t)i * p.m + col, cv[u], p.m - col);
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) cv[u][e] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int col = col0 + u * kStreamT * VEC;
+            const int valid = p.m - col;               // <= 0 for a chunk past the end: every term is -inf
+            double x[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) x[e] = e < valid ? fma(ns, (double)cv[u][e], V[col + e]) : -__builtin_huge_val();
+            acc.template add<VEC>(x);
+        }
+    }
+    const int wave = tid >> 6, lane = tid & 63;
+    acc.wave_reduce();
+    if (lane == 0) { sM[wave] = acc.M; sS[wave] = acc.s; }
+    __syncthreads();
+    if (tid == 0) {
+        Lse t; t.init();
+#pragma unroll
+        for (int w = 0; w < kStreamT / 64; ++w) t.merge(sM[w], sS[w]);
+        const double Fn = t.value();
+        p.F[(size_t)nxt * p.n_ld + i] = Fn;
+        p.U[(size_t)nxt * p.n_ld + i] = p.la2[i] - Fn;
+    }
+}
+
 // ---------------------------------------------------------------- column pass (streaming)
 template <int VEC, int DT = 0>
 __global__ __launch_bounds__(kStreamT) void k_col_stream(DenseArgs A, Ctl c) {
@@ -181,6 +237,14 @@ void dense_stream_plan(int n, int m, int *P, int *rows_per_panel) {
 }
 
 hipError_t launch_dense_row(hipStream_t st, const DenseArgs &a, const Ctl &c, const Stamp &tm) {
+    if (a.p.n < kFewRows) {
+        const dim3 grid(a.p.n);
+        if (a.c_dtype == 1) launch_stamped((k_row_stream_few<8, 1>), grid, dim3(kStreamT), st, tm, a, c);
+        else if (a.c_dtype == 2) launch_stamped((k_row_stream_few<8, 2>), grid, dim3(kStreamT), st, tm, a, c);
+        else if (vec4_ok(a)) launch_stamped(k_row_stream_few<4>, grid, dim3(kStreamT), st, tm, a, c);
+        else launch_stamped(k_row_stream_few<1>, grid, dim3(kStreamT), st, tm, a, c);
+        return hipGetLastError();
+    }
     const dim3 grid((a.p.n + kRowsPerWG - 1) / kRowsPerWG);
     if (a.c_dtype == 1) launch_stamped((k_row_stream<8, 1>), grid, dim3(kStreamT), st, tm, a, c);
     else if (a.c_dtype == 2) launch_stamped((k_row_stream<8, 2>), grid, dim3(kStreamT), st, tm, a, c);
