@@ -50,9 +50,11 @@ struct Layout {
     int n, m, d, n_ld, m_ld;
     // dense
     int P_stream, rpp_stream, P_fused;
+    int row_splits, row_cps;     // column ranges of the streaming row pass (1: none)
     // points
     int JSf, cpsf, JSg, cpsg;
     size_t o_state, o_F, o_U, o_G, o_V, o_la2, o_lb2, o_part, o_part2;
+    size_t o_rowpart;      // [row_splits][n_ld] partial row LSE values (dense, row_splits > 1)
     size_t o_Xp, o_Xs, o_cx, o_Yp, o_Ys, o_cy;
     size_t o_coop;         // scratch of the one-launch solver for mid-size dense problems (0: none)
     size_t o_grid;         // scratch of the one-launch solver over the whole chip (0: none)
@@ -80,6 +82,8 @@ Layout make_layout(int n, int m, int d) {
         const int Pmax = L.P_stream > L.P_fused ? L.P_stream : L.P_fused;
         L.o_part = take(sizeof(double) * (size_t)Pmax * L.m_ld);
         L.o_part2 = L.o_part;
+        dense_row_split_plan(n, m, &L.row_splits, &L.row_cps);
+        if (L.row_splits > 1) L.o_rowpart = take(sizeof(double) * (size_t)L.row_splits * L.n_ld);
         if (coop_supported(n, m)) L.o_coop = take(coop_scratch_bytes());
         if (grid_supported(n, m, kGridWMax, false)) L.o_grid = take(grid_scratch_bytes());
     } else {
@@ -195,6 +199,10 @@ struct Solve {
         a.colpart = (double *)(ws + L.o_part);
         if (kind == FUSED) { a.P = dense_fused_grid(pr.n, pr.m, opt.fused_variant, opt.cost_dtype); a.rows_per_panel = 0; }
         else { a.P = L.P_stream; a.rows_per_panel = L.rpp_stream; }
+        a.rowpart = nullptr; a.row_splits = 1; a.row_cps = pr.m;
+        if (kind == STREAM && L.row_splits > 1) {
+            a.rowpart = (double *)(ws + L.o_rowpart); a.row_splits = L.row_splits; a.row_cps = L.row_cps;
+        }
         return a;
     }
     ErrSrc err_src() const {
@@ -257,7 +265,11 @@ struct Solve {
         tm.t0 = t0;
         tm.t1 = t1;
         if (mode == 3) e = launch_points_lse(st, points_f(), c, 0, L.m_ld, tm);
-        else if (kind == STREAM) e = launch_dense_row(st, dense(STREAM), c, tm);
+        else if (kind == STREAM) {
+            e = launch_dense_row(st, dense(STREAM), c, tm);
+            if (e == hipSuccess && L.row_splits > 1)       // the row pass left partial values per column range
+                e = launch_combine(st, combine_f(L.row_splits, (const double *)(ws + L.o_rowpart), nullptr), c);
+        }
         else e = launch_dense_fused(st, dense(FUSED), c, opt.fused_variant, tm);     // both half-steps
         if (mode == 3 && e == hipSuccess) {
             CombineArgs ca = combine_f(L.JSf, (const double *)(ws + L.o_part), (const double *)(ws + L.o_cx));

@@ -172,6 +172,78 @@ __global__ __launch_bounds__(kStreamT) void k_row_stream_few(DenseArgs A, Ctl c)
     }
 }
 
+// Few rows and very many columns: one row and one column range per workgroup; the partial LSE values go to the
+// combine kernel (512 x 100000: 4 ranges, 2048 workgroups instead of 512).
+template <int VEC, int DT = 0>
+__global__ __launch_bounds__(kStreamT) void k_row_split(DenseArgs A, Ctl c) {
+    constexpr int UN = 4;
+    __shared__ double sM[kStreamT / 64];
+    __shared__ float sS[kStreamT / 64];
+    int k;
+    if (!launch_active(c, k)) return;
+    const int cur = k & 1;
+    const Pots &p = A.p;
+    const int tid = threadIdx.x;
+    const int i = blockIdx.x;                          // the grid has exactly n x row_splits workgroups
+    const int j0 = blockIdx.y * A.row_cps;
+    const int j1 = min(p.m, j0 + A.row_cps);
+    const double *V = p.V + (size_t)cur * p.m_ld;
+    const double ns = -p.s;
+    Lse acc;
+    acc.init();
+    for (int col0 = j0 + tid * VEC; col0 < j1; col0 += kStreamT * VEC * UN) {
+        float cv[UN][VEC];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int col = col0 + u * kStreamT * VEC;
+            if (col < j1) {
+                load_costs<VEC, DT>(A.C, (size_t)i * p.m + col, cv[u], j1 - col);
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) cv[u][e] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int col = col0 + u * kStreamT * VEC;
+            const int valid = j1 - col;                // <= 0 for a chunk past the end: every term is -inf
+            double x[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) x[e] = e < valid ? fma(ns, (double)cv[u][e], V[col + e]) : -__builtin_huge_val();
+            acc.template add<VEC>(x);
+        }
+    }
+    const int wave = tid >> 6, lane = tid & 63;
+    acc.wave_reduce();
+    if (lane == 0) { sM[wave] = acc.M; sS[wave] = acc.s; }
+    __syncthreads();
+    if (tid == 0) {
+        Lse t; t.init();
+#pragma unroll
+        for (int w = 0; w < kStreamT / 64; ++w) t.merge(sM[w], sS[w]);
+        A.rowpart[(size_t)blockIdx.y * p.n_ld + i] = t.value();
+    }
+}
+
+void dense_row_split_plan(int n, int m, int *splits, int *cols_per_split) {
+    // about 2048 workgroups, ranges of whole 2048-column groups (every range starts 16-byte aligned for both
+    // entry sizes) and of at least 4096 columns
+    int S = 1, cps = m;
+    if (n < 1024 && m >= 8192) {                        // from 1024 rows on the extra combine launch costs more than it saves
+        S = (2048 + n - 1) / n;
+        if (S > 64) S = 64;
+        if (S > m / 4096) S = m / 4096;
+        if (S > 1) {
+            cps = (m + S - 1) / S;
+            cps = ((cps + 2047) / 2048) * 2048;
+            S = (m + cps - 1) / cps;
+        }
+        if (S <= 1) { S = 1; cps = m; }
+    }
+    *splits = S;
+    *cols_per_split = cps;
+}
+
 // ---------------------------------------------------------------- column pass (streaming)
 template <int VEC, int DT = 0>
 __global__ __launch_bounds__(kStreamT) void k_col_stream(DenseArgs A, Ctl c) {
@@ -237,6 +309,15 @@ void dense_stream_plan(int n, int m, int *P, int *rows_per_panel) {
 }
 
 hipError_t launch_dense_row(hipStream_t st, const DenseArgs &a, const Ctl &c, const Stamp &tm) {
+    if (a.row_splits > 1) {
+        if (!a.rowpart || a.row_cps % 2048 != 0) return hipErrorInvalidValue;
+        const dim3 grid(a.p.n, a.row_splits);
+        if (a.c_dtype == 1) launch_stamped((k_row_split<8, 1>), grid, dim3(kStreamT), st, tm, a, c);
+        else if (a.c_dtype == 2) launch_stamped((k_row_split<8, 2>), grid, dim3(kStreamT), st, tm, a, c);
+        else if (vec4_ok(a)) launch_stamped(k_row_split<4>, grid, dim3(kStreamT), st, tm, a, c);
+        else launch_stamped(k_row_split<1>, grid, dim3(kStreamT), st, tm, a, c);
+        return hipGetLastError();
+    }
     if (a.p.n < kFewRows) {
         const dim3 grid(a.p.n);
         if (a.c_dtype == 1) launch_stamped((k_row_stream_few<8, 1>), grid, dim3(kStreamT), st, tm, a, c);

@@ -27,6 +27,10 @@ struct DenseArgs {
     double *colpart;      // [P][m_ld] per-panel partial column LSE values
     int32_t P;            // number of row panels of the column pass
     int32_t rows_per_panel;
+    // short and wide matrices: the row pass runs over row_splits column ranges of row_cps columns and writes
+    // rowpart[split][n_ld] partial LSE values for the combine kernel (row_splits <= 1: it writes F and U itself)
+    double *rowpart;
+    int32_t row_splits, row_cps;
 };
 
 // The LDS-prefetch fused pass sums plan entries in fp32 (its column phase): a combined G_j that fell
@@ -104,6 +108,8 @@ inline void launch_stamped(void (*kernel)(P...), dim3 grid, dim3 block, hipStrea
     else hipLaunchKernelGGL(kernel, grid, block, 0, st, static_cast<P>(args)...);
 }
 hipError_t launch_dense_row(hipStream_t st, const DenseArgs &a, const Ctl &c, const Stamp &tm = Stamp());
+// column ranges of the row pass (1: none): only for few rows and very many columns
+void dense_row_split_plan(int n, int m, int *splits, int *cols_per_split);
 hipError_t launch_dense_col(hipStream_t st, const DenseArgs &a, const Ctl &c);
 
 // Dense fused row-panel kernel (m limited by what a workgroup holds in registers).
