@@ -333,6 +333,29 @@ def test_points_shape_sweep(fs, oracle, t, n, m, d, eps, zeros):
     assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
 
 
+@pytest.mark.parametrize("n,m,dt", [(300, 20000, "f32"), (17, 16391, "f32"), (100, 24576, "f16"), (64, 32768, "bf16"),
+                                    (1, 9000, "f32"), (1023, 8192, "f32"), (1024, 8192, "f32"), (700, 8190, "f32")])
+def test_dense_short_wide_row_pass(fs, oracle, n, m, dt):
+    """Few rows, many columns, streaming kernels: the row pass cut into column ranges (with a ragged last range, odd
+    widths, 2-byte costs), and its neighbours that are not cut (1024 rows; fewer than two ranges of 4096 columns)."""
+    eps = 0.05
+    w = W.random_dense(n, m, seed=9700 + n + m, cmax=2.0, eps=eps)
+    if n > 8:
+        w.a[2::9] = 0.0
+        w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    C32, Cd = (w.C, dev(w.C)) if dt == "f32" else _rounded_cost(w.C, dt)
+    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), eps, 9, 0.0, C=Cd, want_f64=True, kernel_mode=1)
+    ref = oracle.solve(w.a, w.b, eps, 9, C=C32)
+    assert r["iters"] == 9 and not r["nonfinite"]
+    fin = np.isfinite(ref["f"])
+    f64, g64 = r["f64"].cpu().numpy(), r["g64"].cpu().numpy()
+    assert np.array_equal(np.isfinite(f64), fin)
+    assert pot_err(f64[fin], ref["f"][fin], eps) < TOL_F64
+    assert pot_err(g64, ref["g"], eps) < TOL_F64
+    err_ref = float(oracle.marginal_err(w.a, w.b, eps, ref["f"], ref["g"], C=C32))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+
+
 def _after_loop_sweep_cases():
     rng = np.random.default_rng(20240609)
     cases = []
