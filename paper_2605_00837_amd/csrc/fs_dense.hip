@@ -636,17 +636,19 @@ __global__ __launch_bounds__(256) void k_fused_rows(DenseArgs A, Ctl c) {
 // Arithmetic
 //   row phase    The reference of row i is its previous LSE value rho_i = F_old_i.  Every lane forms
 //                e_ij = 2^(x_ij - rho_i) and sums it; if the workgroup-wide sum S_i lands in
-//                [2^-60, 2^60] (always, once the potentials move by less than ~40 eps per
+//                [2^-20, 2^60] (always, once the potentials move by less than ~20 base-2 units per
 //                iteration) then F_new_i = rho_i + log2 S_i with no max pass at all.  Otherwise
 //                the panel is redone with the exact running-max form of Eq. 8.
 //   column phase With the new f the plan entry is pi_ij = e_ij * a_i / S_i, all of
 //                them in [0, 1].  The column pass is therefore one fused multiply-add per entry:
 //                T_j += e_ij * alpha_i, alpha_i = a_i / S_i, and the partial column LSE is
 //                log2 T_j - V_j.  This is the classical scaling form of Sinkhorn, usable here
-//                because e_ij is already stabilised by the row reference.  It cannot overflow.  It
-//                loses a column only if that column's mass collapses by more than 2^60 in one
-//                iteration; the combine kernel detects exactly that (new G_j more than 60 below
-//                the old one, or not a number) and recomputes such columns from C.
+//                because e_ij is already stabilised by the row reference.  It cannot overflow.  What
+//                it can lose is what fp32 flushes: a factor e_ij or a product pi_ij below 2^-126.
+//                With alpha_i <= 2^20 (the lower limit on S_i) every entry of at least 2^-40 of a
+//                column total T_j >= 2^-66 survives both, so the combine kernel recomputes exactly,
+//                from C, every column whose total is below 2^-66 or not a number (a column whose
+//                weight b_j is that small, or zero, always is) and trusts the others.
 //   While the potentials still move fast (early iterations) the driver runs the exact streaming
 //   row and column kernels instead of this one; the device reports after every iteration whether
 //   at most 128 columns moved by more than 40 (base 2), and the driver follows that hint.  The hint
@@ -679,7 +681,7 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     static_assert(5 * R <= 16, "scalar staging holds 16 dwords per wave");
     constexpr int NDMA = R * Q + 5;            // loads per panel and wave (FULLW)
     constexpr float kRowHi = 1.1529215e18f;   // 2^60
-    constexpr float kRowLo = 8.6736174e-19f;  // 2^-60
+    constexpr float kRowLo = 9.5367432e-07f;  // 2^-20
     __shared__ float4 stage[2][NW][R][Q][64];
     __shared__ int scal[2][NW][16];            // [0,R) F lo  [R,2R) F hi  [2R,3R) la2 lo  [3R,4R) la2 hi  [4R,5R) a
     __shared__ float sSum[2][R][NW];

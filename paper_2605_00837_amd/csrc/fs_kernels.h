@@ -33,13 +33,14 @@ struct DenseArgs {
     int32_t row_splits, row_cps;
 };
 
-// The LDS-prefetch fused pass sums plan entries in fp32 (its column phase): a combined G_j that fell
-// by more than kColRepairBelow in one iteration (or is not a number) may have lost terms to fp32
-// underflow and is recomputed exactly by the combine kernel.  After every iteration the device
+// The LDS-prefetch fused pass sums plan entries in fp32 (its column phase): a column whose total mass
+// T_j is below kColMassFloor (or not a number) may have lost terms to fp32 underflow and is recomputed
+// exactly by the combine kernel (see the kernel's header for the bound).  After every iteration the device
 // publishes a hint (bit 1 of State::flags): FAST if at most 128 columns moved by more than kFastBelow (base-2
 // units), ROBUST otherwise; the driver runs the exact streaming kernels while the hint says ROBUST.
 constexpr double kFastBelow = 40.0;
-constexpr double kColRepairBelow = 60.0;
+constexpr double kColRepairBelow = 60.0;  // optimistic point-cloud pass: a value this far below the old one is recomputed
+constexpr double kColMassFloor = 1.3552527156068805e-20;   // 2^-66
 constexpr double kRepairAbove = 100.0;    // optimistic point-cloud pass: fp32 sums stay finite up to 2^127
 
 // Where the row-marginal error comes from.  r_i = a_i 2^(Fnew_i - Fold_i) is the row marginal of
@@ -66,8 +67,8 @@ struct CombineArgs {
                               //    the old and new F, and let the last workgroup advance the state
     ErrSrc es;
     // Repair of columns whose partials come from the LDS-prefetch fused pass: when repair_C is
-    // non-null, a combined value more than kColRepairBelow under the old G_j (or NaN) is recomputed
-    // exactly from column j of C and the new U.
+    // non-null, a column whose total is below kColMassFloor (or NaN) is recomputed exactly from
+    // column j of C and the new U.
     const float *repair_C;    // n x len row-major, or null
     const double *repair_U;   // [2][repair_ld]
     int32_t repair_n, repair_ld, repair_dtype;   // repair_dtype: storage of repair_C as in DenseArgs::c_dtype

@@ -334,9 +334,9 @@ __global__ __launch_bounds__(kCombW * 64) void k_combine(CombineArgs A, Ctl c) {
                 out = acc.value();                     // -inf when every term was -inf
             }
             out += rowconst_j;
-            // FAST column mode sums plan entries in fp32: a column whose G fell by more than 2^60
-            // in one iteration (or is not a number) may have lost terms to underflow
-            if (fast_mode) suspect = !(out >= old_j - kColRepairBelow);
+            // FAST column mode sums plan entries in fp32: a column whose total mass is below 2^-66
+            // (or not a number) may have lost terms to underflow; tiny and zero weights always land here
+            if (fast_mode) suspect = !(tsum >= kColMassFloor);
             else if (pts_check) suspect = !(out >= old_j - kColRepairBelow && out <= old_j + kRepairAbove);
             nbig = suspect ? 1.0 : big_move(out - old_j);
             A.pot[(size_t)nxt * A.ld + j] = out;
