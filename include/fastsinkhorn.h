@@ -76,9 +76,10 @@ typedef enum {
 typedef struct {
     int32_t iters;         /* iterations performed (f- and g-update pairs)               */
     int32_t converged;     /* 1 iff the tolerance test of Alg. 1 fired                   */
-    int32_t nonfinite;     /* 1 iff some returned potential is NaN or +-inf; 2: a solver
-                              requested with kernel_mode 4 or 5 gave up waiting (see there),
-                              the potentials are not valid                                */
+    int32_t nonfinite;     /* 1 iff some returned potential is NaN or +-inf; 2: a solver whose
+                              workgroups wait for one another (kernel_mode 4, 5, 6, or the
+                              asynchronous entry points' own choice of 4 for small problems)
+                              gave up waiting, see kernel_mode: the potentials are not valid */
     float   marginal_err;  /* err after `iters` iterations; NaN if it was not evaluated  */
 } fs_result;
 
@@ -102,12 +103,19 @@ typedef struct {
                                 two grid-wide exchanges per iteration (n <= 4096, m <= 2048; dense fp32 with at
                                 most 16 entries of C per lane, or point clouds with at most 8 pairs per lane;
                                 else FS_ERR_UNSUPPORTED; what 0 picks in the blocking solves for every such
-                                problem with n or m above 512).
-                                The workgroups of 4 and 5 wait for one another with a bounded number of polls:
-                                should the device keep some of them from running for seconds (other work on
-                                its compute units), the solve gives up and reports nonfinite = 2, never a
-                                silent wrong result.  When the kernel was the library's own choice (0) a
-                                blocking solve then simply runs the multi-kernel driver instead             */
+                                problem with n or m above 512);
+                                6: blocks of iterations in launches of the persistent form of the fused
+                                row-panel kernel, one resident workgroup per compute unit, two grid-wide waits
+                                per iteration (dense fp32, 1024 < m <= 16384, blocking solves only; else
+                                FS_ERR_UNSUPPORTED; what 0 picks in the blocking solves for these widths).
+                                The workgroups of 4, 5 and 6 wait for one another with a bounded number of
+                                polls: should the device keep some of them from running for seconds (other
+                                work on its compute units), the solve gives up and reports nonfinite = 2, never
+                                a silent wrong result.  When the kernel was the library's own choice (0) a
+                                blocking solve then simply runs the multi-kernel driver instead; an
+                                asynchronous solve (which picks 4 by itself up to 2^18 entries) has nobody to
+                                do that: its caller checks fs_result.nonfinite and, on 2, solves again with
+                                kernel_mode = 1                                                             */
     int32_t use_graph;       /* 0: automatic; 1: plain stream launches; 2: hipGraph iteration blocks  */
     int32_t skip_final_err;  /* 1: do not spend the one trailing pass that evaluates err after the
                                 last iteration when no stop fired (marginal_err is then NaN)          */
@@ -129,14 +137,15 @@ typedef struct {
                                 16-byte aligned C (else FS_ERR_UNSUPPORTED); honoured by every solver that
                                 takes options (for fs_sinkhorn_dense_batched: every problem's C); kernel_mode 2
                                 then needs 2048 < m <= 16384.  The after-the-loop entry points take fp32 only */
-    int32_t wait_limit;      /* kernel_mode 4 and 5: polls after which a workgroup stops waiting for the others
+    int32_t wait_limit;      /* kernel_mode 4, 5 and 6: polls after which a workgroup stops waiting for the others
                                 (0: default, about two million = seconds).  A tiny value makes the solve give
                                 up early and report nonfinite = 2, which is how the bounded wait is tested   */
     int32_t time_kernel_every; /* blocking solves only: > 0 times the dominant kernel (row pass, fused pass
                                   or point-cloud LSE pass of the f-update) of every N-th iteration with a pair
                                   of HIP events that the runtime stamps with the start and the stop of that
                                   dispatch on `stream` (hipExtLaunchKernel); read back with
-                                  fs_last_kernel_timing()                                                */
+                                  fs_last_kernel_timing().  The persistent fused pass (kernel_mode 6) is one
+                                  launch per block of iterations: every whole block is timed               */
 } fs_options;
 
 /* ---- Blocking solves (Alg. 1).  Return the number of iterations performed (>= 0) or a
@@ -159,8 +168,7 @@ int fs_sinkhorn_points(const float *X, const float *Y, int d, const float *a, co
  * stop flag is set the remaining kernels return immediately.  `workspace` is device memory of at
  * least fs_workspace_bytes(n, m, d) bytes, 256-byte aligned, exclusively this call's until its
  * stream work has finished.  `opts` may be NULL.  `result_dev` (device, may be NULL) receives
- * the fs_result.  `result_host` (pinned host memory, may be NULL) receives a copy written by
- * the device.  The blocking-with-options variants below take the same arguments. ---- */
+ * the fs_result. ---- */
 size_t fs_workspace_bytes(int n, int m, int d /* 0 = dense */);
 
 fs_status fs_sinkhorn_dense_ex(const float *C, const float *a, const float *b, int n, int m,
@@ -284,13 +292,16 @@ const char *fs_version(void);
 #define FS_KERNEL_COOP   4   /* whole solve in one launch, up to 32 workgroups                        */
 #define FS_KERNEL_GRID   5   /* whole solve in one launch, one workgroup per compute unit             */
 #define FS_KERNEL_POINTS 6   /* point clouds, cost recomputed per pair in every pass                  */
+#define FS_KERNEL_PERSIST 7  /* dense, persistent fused row-panel kernel, a block of iterations per launch */
 int fs_kernel_choice(int n, int m, int d, const fs_options *opts, int blocking, int compute_units);
 
 /* Average duration (ms) of the dominant kernel over the launches sampled by the most recent
- * blocking solve on this thread that had time_kernel_every > 0, the number of samples, and the
- * kernel's name (static storage).  Any output pointer may be NULL.  FS_ERR_INVALID_ARG when
- * there is no such solve.  For benchmarks; no effect on results. */
-fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name);
+ * blocking solve on this thread that had time_kernel_every > 0, the number of samples, the
+ * kernel's name (static storage) and the number of iterations one such launch performs (1, or the
+ * block length of the persistent fused pass).  Any output pointer may be NULL.  FS_ERR_INVALID_ARG
+ * when there is no such solve.  For benchmarks; no effect on results. */
+fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name,
+                                int32_t *iters_per_launch);
 
 #ifdef __cplusplus
 }

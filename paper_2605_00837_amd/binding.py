@@ -58,7 +58,7 @@ def _load():
     lib.fs_clear_cache.restype = None
     lib.fs_last_kernel_timing.restype = ci
     lib.fs_last_kernel_timing.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32),
-                                          ctypes.POINTER(ctypes.c_char_p)]
+                                          ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_int32)]
     lib.fs_kernel_choice.restype = ci
     lib.fs_kernel_choice.argtypes = [ci, ci, ci, vp, ci, ci]
     lib.fs_workspace_bytes.restype = ctypes.c_size_t
@@ -180,7 +180,7 @@ def make_options(check_every=0, warm_start=False, kernel_mode=0, use_graph=0, sk
 
 
 # ---------------------------------------------------------------- entry points, same names as the C ABI
-KERNEL_NAMES = {1: "stream", 2: "fused", 3: "small", 4: "coop", 5: "grid", 6: "points"}
+KERNEL_NAMES = {1: "stream", 2: "fused", 3: "small", 4: "coop", 5: "grid", 6: "points", 7: "persist"}
 
 
 def fs_kernel_choice(n: int, m: int, d: int = 0, blocking: bool = True, compute_units: int = 0, **opt_kw) -> str:
@@ -204,10 +204,11 @@ def fs_clear_cache() -> None:
 
 
 def fs_last_kernel_timing():
-    """(avg_ms, samples, kernel_name) of the dominant kernel sampled by the last timed blocking solve."""
-    ms, cnt, name = ctypes.c_float(0), ctypes.c_int32(0), ctypes.c_char_p()
-    _check(_lib.fs_last_kernel_timing(ctypes.byref(ms), ctypes.byref(cnt), ctypes.byref(name)))
-    return float(ms.value), int(cnt.value), name.value.decode()
+    """(avg_ms, samples, kernel_name, iters_per_launch) of the dominant kernel sampled by the last timed
+    blocking solve."""
+    ms, cnt, name, ipl = ctypes.c_float(0), ctypes.c_int32(0), ctypes.c_char_p(), ctypes.c_int32(0)
+    _check(_lib.fs_last_kernel_timing(ctypes.byref(ms), ctypes.byref(cnt), ctypes.byref(name), ctypes.byref(ipl)))
+    return float(ms.value), int(cnt.value), name.value.decode(), int(ipl.value)
 
 
 def fs_workspace_bytes(n: int, m: int, d: int = 0) -> int:

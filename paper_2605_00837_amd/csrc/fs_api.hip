@@ -58,6 +58,7 @@ struct Layout {
     size_t o_Xp, o_Xs, o_cx, o_Yp, o_Ys, o_cy;
     size_t o_coop;         // scratch of the one-launch solver for mid-size dense problems (0: none)
     size_t o_grid;         // scratch of the one-launch solver over the whole chip (0: none)
+    size_t o_persist;      // counters and error terms of the persistent fused pass (0: none)
     size_t o_start;        // [2][n_ld | m_ld] floats: starting potentials of an in-place warm start, kept for a second attempt
     size_t total;
 };
@@ -86,6 +87,7 @@ Layout make_layout(int n, int m, int d) {
         if (L.row_splits > 1) L.o_rowpart = take(sizeof(double) * (size_t)L.row_splits * L.n_ld);
         if (coop_supported(n, m)) L.o_coop = take(coop_scratch_bytes());
         if (grid_supported(n, m, kGridWMax, false)) L.o_grid = take(grid_scratch_bytes());
+        if (dense_persist_supported(n, m, nullptr, 0)) L.o_persist = take(persist_scratch_bytes());
     } else {
         points_plan(n, m, d, &L.JSf, &L.cpsf);
         points_plan(m, n, d, &L.JSg, &L.cpsg);
@@ -106,10 +108,15 @@ Layout make_layout(int n, int m, int d) {
 }
 
 // ---------------------------------------------------------------- per-device cache
+// The host reads the hint of a block up to 3 blocks behind what it has enqueued; with blocks of at most
+// kMaxBlock iterations the slot it reads has not been reused yet (3 * 64 < 256).
+constexpr int kMaxBlock = 64;
+static_assert(3 * kMaxBlock < kHintRing, "a hint must outlive the run-ahead of the host");
+
 struct HostBlock {            // pinned, device-visible
     volatile int32_t flag;    // done
     volatile int32_t hint;    // latest pace hint (1 = potentials move slowly)
-    volatile int32_t hints[64];   // pace hint after iteration k, at index k % 64
+    volatile int32_t hints[kHintRing];   // pace hint after iteration k, at index k % kHintRing
     int32_t pad[2];
     fs_result res;
 };
@@ -123,7 +130,7 @@ struct DeviceCache {
     hipStream_t cap_stream = nullptr;   // library-owned stream on which iteration blocks are captured
 };
 
-struct KernelTiming { float avg_ms = 0.0f; int samples = 0; const char *name = ""; };
+struct KernelTiming { float avg_ms = 0.0f; int samples = 0; const char *name = ""; int iters_per_launch = 1; };
 thread_local KernelTiming g_timing;
 
 std::mutex g_mu;
@@ -173,6 +180,8 @@ struct Solve {
     Pots pots;
     State *state;
     int mode;              // 1 streaming, 2 fused (dense); 3 points
+    bool persist = false;  // dense, mode 2: blocks of iterations run as launches of the persistent fused pass
+    int cus = 0;           // compute units of the device (persistent pass: one workgroup each)
     volatile int32_t *host_flag;   // device-visible address of the pinned flag, or null
 
     Ctl ctl(int phase) const {
@@ -254,7 +263,18 @@ struct Solve {
     }
 
     const char *dominant_kernel() const {
+        if (persist) return "k_persist";
         return mode == 1 ? "k_row_stream" : mode == 2 ? (fused_is_fp32_cols() ? "k_fused_pf" : "k_fused") : "k_points_lse";
+    }
+    // a block of up to nb iterations in one launch of the persistent fused pass
+    hipError_t enqueue_persist_block(int nb, hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr) const {
+        Stamp tm;
+        tm.t0 = t0;
+        tm.t1 = t1;
+        DenseArgs a = dense(FUSED);
+        a.P = L.P_fused;                       // sets of column sums the exchange buffer holds
+        const int cu = cus < L.P_fused ? cus : L.P_fused;
+        return launch_persist(st, a, ctl(0), ws + L.o_persist, cu, nb, opt.wait_limit, tm);
     }
     // Eq. 9.  t0/t1 (optional) are stamped by the runtime with the start and stop of the dominant kernel
     // of the iteration: the row pass, the fused pass, or the point-cloud LSE pass of the f-update.
@@ -329,6 +349,7 @@ struct Solve {
         if (opt.warm_start) warm = 3;
         hipError_t e = launch_init(st, pots, state, /*f_in*/ warm_f, warm_g, opt.f64_in && opt.g64_in ? opt.f64_in : nullptr,
                                    opt.f64_in && opt.g64_in ? opt.g64_in : nullptr, warm);
+        if (e == hipSuccess && persist) e = launch_persist_reset(st, ws + L.o_persist);
         if (e == hipSuccess && mode == 3) {
             e = launch_points_prep(st, pr.X, pr.n, pr.d, pots.s, (double *)(ws + L.o_Xp), (double *)(ws + L.o_Xs),
                                    (double *)(ws + L.o_cx));
@@ -398,8 +419,14 @@ fs_status setup(Solve &S, const Problem &pr, const fs_options *opts, float *f, f
             else set_err("fused kernel does not support m = %d (needs m <= 16384, and m %% 4 == 0 when m <= 1024)", pr.m);
             return FS_ERR_UNSUPPORTED;
         }
-        if (S.opt.kernel_mode < 0 || S.opt.kernel_mode > 2) { set_err("kernel_mode must be 0, 1, 2, 3 or 4"); return FS_ERR_INVALID_ARG; }
-        S.mode = S.opt.kernel_mode == 0 ? (fused_ok ? 2 : 1) : S.opt.kernel_mode;
+        const int km = S.opt.kernel_mode;
+        if (km == 6) {
+            if (!dense_persist_supported(pr.n, pr.m, pr.C, S.opt.cost_dtype)) {
+                set_err("kernel_mode 6 needs a dense fp32 cost matrix with 1024 < m <= 16384 (got m = %d)", pr.m);
+                return FS_ERR_UNSUPPORTED;
+            }
+        } else if (km < 0 || km > 2) { set_err("kernel_mode %d does not take this problem", km); return FS_ERR_UNSUPPORTED; }
+        S.mode = km == 0 ? (fused_ok ? 2 : 1) : km == 6 ? 2 : km;
         if (S.mode == 2 && dense_fused_grid(pr.n, pr.m, S.opt.fused_variant, S.opt.cost_dtype) == 0) S.opt.fused_variant = 0;
     } else {
         S.mode = 3;
@@ -449,6 +476,7 @@ fs_status build_block_graph(const Solve &S, hipStream_t cap, Solve::Kind kind, i
     return FS_OK;
 }
 
+constexpr int kPersistBlock = 25;       // iterations per launch of the persistent fused pass
 constexpr int kAsyncExactFirst = 4;     // asynchronous solves: exact streaming iterations before the fused kernel
 constexpr int kFirstBlock = 2;          // blocking solves: iterations before the first look at the pace hint
 
@@ -475,11 +503,23 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     void *hb_dev = nullptr;
     FS_HIP(hipHostGetDevicePointer(&hb_dev, (void *)hb, 0));
     S.host_flag = (volatile int32_t *)hb_dev;
+    // The persistent pass waits for all of its workgroups; should it give up (the device kept some of them from
+    // running) the solve is run again by the multi-kernel driver, from the same start: an in-place warm start is
+    // kept aside for that.
+    const bool own_persist = S.persist && S.opt.kernel_mode == 0;
+    const bool in_place = S.opt.warm_start && !(S.opt.f64_in && S.opt.g64_in);
+    float *keep = (float *)(S.ws + S.L.o_start);
+    if (own_persist && in_place) {
+        FS_HIP(hipMemcpyAsync(keep, f, sizeof(float) * S.pr.n, hipMemcpyDeviceToDevice, S.st));
+        FS_HIP(hipMemcpyAsync(keep + S.L.n_ld, g, sizeof(float) * S.pr.m, hipMemcpyDeviceToDevice, S.st));
+    }
     FS_HIP(S.enqueue_init());
     // Iterations are enqueued in blocks; the stop rule itself runs on the device every check_every iterations,
     // a block is only how often the host looks at the stop flag (what it enqueued beyond a stop returns at
     // once), so small check intervals do not shrink it.
-    const int block = S.opt.check_every > 10 ? S.opt.check_every : 10;
+    int block = S.opt.check_every > 10 ? S.opt.check_every : 10;
+    if (block > kMaxBlock) block = kMaxBlock;
+    if (S.persist) block = kPersistBlock;
     const int tevery = S.opt.time_kernel_every > 0 ? S.opt.time_kernel_every : 0;
     int nsamples = 0;
     g_timing = KernelTiming{};
@@ -487,16 +527,25 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     // while the device reports fast-moving potentials.  The hint used for block b is the one the
     // device published at the end of the block whose completion the host has just waited for, so the
     // sequence of kernels, and with it every bit of the result, does not depend on host timing.
-    const bool two_kinds = S.fused_is_fp32_cols();
+    // (The persistent pass takes every iteration itself: its repairs make it exact at any pace.)
+    const bool two_kinds = S.fused_is_fp32_cols() && !S.persist;
     const bool force_fused = S.opt.fused_variant >= 100;
     // Launch-bound sizes replay each block as one hipGraph (never while kernels are being timed).
     const size_t cells = (size_t)S.pr.n * (size_t)S.pr.m;
     const bool small = S.mode == 3 ? cells <= ((size_t)1 << 24) : cells <= ((size_t)1 << 22);
-    const bool use_graph = !tevery && S.pr.max_iter >= block &&
+    const bool use_graph = !tevery && !S.persist && S.pr.max_iter >= block &&
                            (S.opt.use_graph == 2 || (S.opt.use_graph == 0 && small));
     BlockGraph graphs[3];                              // indexed by kind
     int block_end[4] = {0, 0, 0, 0};
     int it = 0, blk = 0;
+    auto timing_pair = [&](int q) -> fs_status {
+        while ((int)dc->timing.size() < 2 * (q + 1)) {
+            hipEvent_t e;
+            FS_HIP(hipEventCreate(&e));
+            dc->timing.push_back(e);
+        }
+        return FS_OK;
+    };
     while (it < S.pr.max_iter) {
         if (hb->flag) break;                           // the device has stopped: enqueue nothing more
         Solve::Kind kind = S.default_kind();
@@ -507,11 +556,23 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
         if (hb->flag) break;
         if (two_kinds && !force_fused) {
             if (blk == 0) kind = Solve::STREAM;
-            else kind = hb->hints[block_end[hint_block & 3] & 63] ? Solve::FUSED : Solve::STREAM;
+            else kind = hb->hints[block_end[hint_block & 3] & (kHintRing - 1)] ? Solve::FUSED : Solve::STREAM;
         }
         int nb = (blk == 0 && two_kinds && !force_fused) ? kFirstBlock : block;
         if (nb > S.pr.max_iter - it) nb = S.pr.max_iter - it;
-        if (use_graph && nb == block) {
+        if (S.persist) {
+            // one launch per block; whole blocks are timed when asked for (begin to end of the dispatch)
+            const bool sample = tevery && nb == block && nsamples < 4096;
+            if (sample) {
+                const fs_status ts = timing_pair(nsamples);
+                if (ts != FS_OK) return ts;
+                FS_HIP(S.enqueue_persist_block(nb, dc->timing[2 * nsamples], dc->timing[2 * nsamples + 1]));
+                sample_iter.push_back(it + nb - 1);
+                ++nsamples;
+            } else {
+                FS_HIP(S.enqueue_persist_block(nb));
+            }
+        } else if (use_graph && nb == block) {
             BlockGraph &bg = graphs[(int)kind];
             if (!bg.exec) {
                 const fs_status gs = build_block_graph(S, dc->cap_stream, kind, block, &bg);
@@ -523,11 +584,8 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
             const bool sample = tevery && ((it + q) % tevery == 0) && nsamples < 4096 &&
                                 kind == S.default_kind();       // only the dominant kernel is timed
             if (sample) {
-                while ((int)dc->timing.size() < 2 * (nsamples + 1)) {
-                    hipEvent_t e;
-                    FS_HIP(hipEventCreate(&e));
-                    dc->timing.push_back(e);
-                }
+                const fs_status ts = timing_pair(nsamples);
+                if (ts != FS_OK) return ts;
                 FS_HIP(S.enqueue_iteration(kind, dc->timing[2 * nsamples], dc->timing[2 * nsamples + 1]));
                 sample_iter.push_back(it + q);
                 ++nsamples;
@@ -544,6 +602,18 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     FS_HIP(launch_finalize(S.st, S.pots, S.state, f, g, S.opt.f64_out, S.opt.g64_out, nullptr,
                            (char *)hb_dev + offsetof(HostBlock, res)));
     FS_HIP(hipStreamSynchronize(S.st));
+    if (S.persist && hb->res.nonfinite == kGaveUp) {
+        if (!own_persist) {                            // asked for by the caller: report it
+            if (result_host) *result_host = hb->res;
+            return hb->res.iters;
+        }
+        if (in_place) {
+            FS_HIP(hipMemcpyAsync(f, keep, sizeof(float) * S.pr.n, hipMemcpyDeviceToDevice, S.st));
+            FS_HIP(hipMemcpyAsync(g, keep + S.L.n_ld, sizeof(float) * S.pr.m, hipMemcpyDeviceToDevice, S.st));
+        }
+        S.persist = false;
+        return run_solve_blocking(S, dc, f, g, result_host);
+    }
     if (nsamples > 0) {
         // only launches that did work count: those of iterations the solve actually performed
         double tot = 0.0;
@@ -558,6 +628,7 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
         g_timing.avg_ms = used ? (float)(tot / used) : 0.0f;
         g_timing.samples = used;
         g_timing.name = S.dominant_kernel();
+        g_timing.iters_per_launch = S.persist ? block : 1;
     }
     if (result_host) *result_host = hb->res;
     return hb->res.iters;
@@ -572,7 +643,7 @@ fs_status check_options(const Problem &pr, const fs_options *opts) {
         set_err("2-byte costs need m %% 8 == 0 (got %d) and a 16-byte aligned C", pr.m);
         return FS_ERR_UNSUPPORTED;
     }
-    if (opts->kernel_mode < 0 || opts->kernel_mode > 5) { set_err("kernel_mode must be 0 ... 5"); return FS_ERR_INVALID_ARG; }
+    if (opts->kernel_mode < 0 || opts->kernel_mode > 6) { set_err("kernel_mode must be 0 ... 6"); return FS_ERR_INVALID_ARG; }
     return FS_OK;
 }
 
@@ -645,6 +716,27 @@ bool grid_path(const Problem &pr, const fs_options *opts, bool blocking, fs_stat
     // it can fall back (blocking solves); up to 512 x 512 the 32-workgroup kernel is as fast or faster
     // (256 x 256: 5.7 against 7.3 us per iteration), beyond that this one is (1024 x 256: 8.3 against 10.2)
     return blocking && (pr.n > 512 || pr.m > 512);
+}
+
+// Dense fp32 problems of the widths of the LDS-prefetch fused pass run their iterations in launches of the
+// persistent form of that pass (fs_persist.hip): one workgroup per compute unit stays resident for a block of
+// iterations.  Blocking solves only (a solve that gives up is run again by the multi-kernel driver).
+bool persist_path(const Problem &pr, const fs_options *opts, bool blocking, int *cus) {
+    const int km = opts ? opts->kernel_mode : 0;
+    if (!blocking || !pr.C || (km != 0 && km != 6)) return false;
+    if (!dense_persist_supported(pr.n, pr.m, pr.C, opts ? opts->cost_dtype : 0)) return false;
+    *cus = device_cus();
+    if (*cus < 1) return false;
+    if (dense_persist_grid(pr.n, pr.m, *cus) < 1) return false;      // too few workgroups for this width
+    if (km == 6) return true;
+    if (opts && opts->fused_variant != 0) return false;      // a tuning / test knob of the multi-kernel path
+    // automatic: where it is faster than the multi-kernel driver (5 - 19 % per iteration from 300 x 3000 to
+    // 16384 x 8192, 65536 x 2048).  Beyond 8192 columns the two are level (one row per panel, the pass is long
+    // against the exchange); at m = 4096 with 8192 rows or more the multi-kernel pass runs two workgroups per
+    // compute unit, which this kernel's registers do not allow, and wins by 4 - 10 %.
+    if (pr.m > 8192) return false;
+    if (pr.m == 4096 && pr.n >= 8192) return false;
+    return true;
 }
 
 fs_status small_args(const Problem &pr, int batch, const fs_options *opts, float *f, float *g, SmallArgs *out) {
@@ -752,6 +844,11 @@ int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const 
     Solve S;
     v = setup(S, pr, opts, f, g, st, dc->ws, dc->ws_bytes);
     if (v != FS_OK) return v;
+    S.persist = persist_path(pr, opts, /*blocking=*/true, &S.cus);
+    if (!S.persist && opts && opts->kernel_mode == 6) {
+        set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (n = %d, m = %d, %d compute units)", pr.n, pr.m, S.cus);
+        return FS_ERR_UNSUPPORTED;
+    }
     return run_solve_blocking(S, dc, f, g, result_host);
 }
 
@@ -803,6 +900,10 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
         return FS_OK;
     }
     if (serr != FS_OK) return serr;
+    if (opts && opts->kernel_mode == 6) {
+        set_err("kernel_mode 6 (persistent fused pass) is for the blocking solves: it needs a fallback when a wait is abandoned");
+        return FS_ERR_UNSUPPORTED;
+    }
     Solve S;
     v = setup(S, pr, opts, f, g, st, ws, ws_bytes);
     if (v != FS_OK) return v;
@@ -957,16 +1058,25 @@ int fs_kernel_choice(int n, int m, int d, const fs_options *opts, int blocking, 
     if (d != 0) return FS_KERNEL_POINTS;
     const int cd = opts ? opts->cost_dtype : 0, km = opts ? opts->kernel_mode : 0;
     const bool fused_ok = dense_fused_supported(n, m, dummy, cd);
+    if (km == 6 && !blocking) { set_err("kernel_mode 6 is for the blocking solves"); return FS_ERR_UNSUPPORTED; }
+    if (km == 6 && !dense_persist_supported(n, m, dummy, cd)) { set_err("kernel_mode 6 does not support m = %d", m); return FS_ERR_UNSUPPORTED; }
+    g_cus_override = compute_units;
+    int pcus = 0;
+    const bool persist = persist_path(pr, opts, blocking != 0, &pcus);
+    g_cus_override = 0;
+    if (persist) return FS_KERNEL_PERSIST;
+    if (km == 6) { set_err("kernel_mode 6 needs at least m / 64 row panels and compute units"); return FS_ERR_UNSUPPORTED; }
     if (km == 2 && !fused_ok) { set_err("fused kernel does not support m = %d", m); return FS_ERR_UNSUPPORTED; }
     if (km > 2) { set_err("kernel_mode %d does not take this problem", km); return FS_ERR_UNSUPPORTED; }
     return (km == 2 || (km == 0 && fused_ok)) ? FS_KERNEL_FUSED : FS_KERNEL_STREAM;
 }
 
-fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name) {
+fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name, int32_t *iters_per_launch) {
     if (g_timing.samples <= 0) { set_err("no timed solve has run on this thread"); return FS_ERR_INVALID_ARG; }
     if (avg_ms) *avg_ms = g_timing.avg_ms;
     if (samples) *samples = g_timing.samples;
     if (kernel_name) *kernel_name = g_timing.name;
+    if (iters_per_launch) *iters_per_launch = g_timing.iters_per_launch;
     return FS_OK;
 }
 

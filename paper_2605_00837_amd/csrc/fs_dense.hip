@@ -653,17 +653,6 @@ __global__ __launch_bounds__(256) void k_fused_rows(DenseArgs A, Ctl c) {
 //   row and column kernels instead of this one; the device reports after every iteration whether
 //   at most 128 columns moved by more than 40 (base 2), and the driver follows that hint.  The hint
 //   only steers performance: this kernel plus the repair is correct in either regime.
-__device__ __forceinline__ void lds_only_barrier() {
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): this wave's LDS writes are done
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-#endif
-}
-
-constexpr int waitcnt_vm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }   // s_waitcnt vmcnt(n) only
-
 // FULLW: m == 4*Q*T, every lane owns valid columns.  Then every wave issues exactly R*Q + 5
 // prefetch loads per panel, which lets the kernel keep TWO panels in flight and wait with an
 // exact vmcnt (vmcnt retires in order: "at most R*Q + 5 outstanding" means "everything but the

@@ -40,6 +40,8 @@ struct alignas(256) State {
     uint32_t big_acc[2];  // columns that moved by more than the FAST-mode threshold, by parity of the iteration
 };
 
+constexpr int kHintRing = 256;        // slots of the host-visible ring of pace hints (index: iteration mod ring)
+
 // Constant description of one solve, passed by value to the kernels.
 struct Ctl {
     State *st;
@@ -215,6 +217,20 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
     return v;
 }
 
+// ---------------------------------------------------------------- barriers and waits around LDS-DMA prefetch
+// A workgroup barrier that waits for this wave's LDS traffic only.  __syncthreads() carries a fence that also
+// waits for every vector-memory operation in flight, i.e. for an asynchronous HBM -> LDS prefetch.
+__device__ __forceinline__ void lds_only_barrier() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xc07f);            // lgkmcnt(0): this wave's LDS writes are done
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#endif
+}
+
+constexpr int waitcnt_vm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }   // s_waitcnt vmcnt(n) only
+
 // ---------------------------------------------------------------- online LSE
 // Running base-2 LogSumExp as (M, s): value = M + log2(s), s = sum 2^(x - M).
 struct Lse {
@@ -259,7 +275,7 @@ __device__ __forceinline__ void advance_state(const Ctl &c, int k, double err, d
     const int hint = (big_cols <= 128.0) ? 1 : 0;
     if (c.host_flag) {                            // made visible by the completion of this kernel
         c.host_flag[1] = hint;
-        c.host_flag[2 + ((k + 1) & 63)] = hint;
+        c.host_flag[2 + ((k + 1) & (kHintRing - 1))] = hint;
     }
     if (c.err_history && k >= 1 && k - 1 < c.err_history_len) c.err_history[k - 1] = (float)err;
     const bool checked = (c.tol > 0.0) && (k >= 1) && (k % c.check_every == 0);

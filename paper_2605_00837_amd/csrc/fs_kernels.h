@@ -234,6 +234,33 @@ struct GridArgs : SmallArgs {                    // batch is ignored (one proble
     GridSync *sync;
     int32_t ldx, spin_limit;
 };
+// ---- dense fp32 problems with 1024 < m <= 16384: a block of iterations of the fused row-panel pass in one
+//      launch, one resident workgroup per compute unit, two grid-wide waits per iteration (fs_persist.hip)
+// Counters of the persistent pass (all monotone over a solve).  A workgroup counts itself into one of 8 group
+// counters; the last of a group writes the generation into the group's word of `done`, the one line that every
+// workgroup polls (the polled line sees 8 plain stores per wait and no read-modify-write).
+struct PersistSync {
+    GridLine grp[8];
+    unsigned long long done[8];                  // generation each group has completed
+    unsigned long long abort_flag;               // same line: one poll reads the 9 words
+    unsigned long long pad[23];
+};
+struct PersistArgs {
+    PersistSync *sync;
+    double *wgpart;                              // [workgroups]: error terms of each workgroup's rows
+    int32_t nb;                                  // iterations this launch runs at most
+    int32_t spin_limit;                          // polls before a grid-wide wait is abandoned
+#ifdef FS_PERSIST_TRACE
+    long long *trace;                            // debug builds: [workgroups][8] time stamps of one iteration
+#endif
+};
+bool dense_persist_supported(int n, int m, const void *C, int c_dtype);
+int dense_persist_grid(int n, int m, int cus);   // workgroups of the launch on a device with `cus` compute units
+size_t persist_scratch_bytes();
+hipError_t launch_persist_reset(hipStream_t st, void *scratch);          // once per solve, before the first block
+hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
+                          int spin_limit, const Stamp &tm = Stamp());
+
 bool grid_supported(int n, int m, int wmax, bool points);   // wmax: workgroups that can be resident at once (compute units)
 size_t grid_scratch_bytes();
 hipError_t launch_grid(hipStream_t st, const GridArgs &a, void *scratch, int wmax);

@@ -93,7 +93,7 @@ __global__ void k_result(State *state, ResultRecord *dev, ResultRecord *host) {
     const bool done = (state->flags & kFlagDone) != 0;
     r.iters = done ? state->iters : state->k;
     r.converged = done ? state->converged : 0;
-    r.nonfinite = state->nonfinite;
+    r.nonfinite = (state->nonfinite & kGaveUp) ? kGaveUp : state->nonfinite;
     r.marginal_err = (done && state->err_valid) ? (float)state->err : __builtin_nanf("");
     if (!done) { state->iters = r.iters; state->flags |= kFlagDone; }
     if (dev) *dev = r;

@@ -141,15 +141,24 @@ def test_kernel_choice_table_without_gpu():
     from paper_2605_00837_amd import binding as fs
     pick = lambda n, m, d=0, blocking=True, **kw: fs.fs_kernel_choice(n, m, d, blocking, 256, **kw)
     assert pick(256, 256) == "coop"                          # c1
-    assert pick(8192, 8192) == "fused"                       # c2
-    assert pick(4096, 4096) == "fused"                       # c3: 64 entries per lane do not fit the one-launch kernels
+    assert pick(8192, 8192) == "persist"                     # c2
+    assert pick(4096, 4096) == "persist"                     # c3: 64 entries per lane do not fit the one-launch kernels
     assert pick(65536, 65536, 3) == "points"                 # c4
-    assert pick(16384, 16384, 3) == "points" and pick(16384, 12288) == "fused"      # c5
+    assert pick(16384, 16384, 3) == "points" and pick(16384, 12288) == "fused" and pick(16384, 16384) == "fused"   # c5
     assert pick(64, 64) == "small" and pick(128, 128) == "small" and pick(129, 128) == "coop"
     assert pick(512, 512) == "coop" and pick(513, 512) == "grid" and pick(1024, 1024) == "grid"
-    assert pick(2048, 2048) == "grid" and pick(4096, 1024) == "grid" and pick(4096, 2048) == "fused"
-    assert pick(100, 2048) == "fused"                        # too few rows for that many columns: strips of > 16 columns
+    assert pick(2048, 2048) == "grid" and pick(4096, 1024) == "grid" and pick(4096, 2048) == "persist"
+    assert pick(100, 2048) == "persist"                      # too few rows for that many columns: strips of > 16 columns
     assert pick(40, 20000) == "stream" and pick(30, 16384) == "fused" and pick(30, 16385) == "stream"
+    # the persistent fused pass: blocking solves, fp32, 1024 < m <= 8192, strips of at most 64 columns per workgroup
+    assert pick(300, 3000) == "persist" and pick(5000, 1100) == "persist" and pick(65536, 2048) == "persist"
+    assert pick(8191, 4096) == "persist" and pick(8192, 4096) == "fused"        # two workgroups per compute unit win there
+    assert pick(8192, 8193) == "fused" and pick(8192, 8192, blocking=False) == "fused"
+    assert pick(100, 8192) == "fused"                        # 50 panels of 2 rows: strips of 164 columns
+    assert pick(254, 8192) == "fused" and pick(255, 8192) == "persist"          # 127 panels: 65 columns; 128 panels: 64
+    assert pick(8192, 8192, fused_variant=1) == "fused" and pick(8192, 8192, cost_dtype=1) == "fused"
+    assert pick(8192, 8192, kernel_mode=2) == "fused" and pick(8192, 12288, kernel_mode=6) == "persist"
+    assert fs.fs_kernel_choice(8192, 8192, 0, True, 64) == "fused"              # 64 compute units: strips of 128 columns
     assert pick(200, 200, 3) == "coop" and pick(1024, 1024, 3) == "grid" and pick(2048, 2048, 3) == "points"
     # asynchronous solves never pick the whole-chip kernel by themselves; a smaller device shrinks its range
     assert pick(1024, 1024, blocking=False) == "fused" and pick(512, 512, blocking=False) == "coop"
@@ -164,3 +173,7 @@ def test_kernel_choice_table_without_gpu():
         pick(300, 300, kernel_mode=3)
     with pytest.raises(fs.FsError, match="kernel_mode 5"):
         pick(4096, 4096, kernel_mode=5)
+    with pytest.raises(fs.FsError, match="kernel_mode 6"):
+        pick(8192, 8192, blocking=False, kernel_mode=6)
+    with pytest.raises(fs.FsError, match="kernel_mode 6"):
+        pick(100, 8192, kernel_mode=6)

@@ -1,0 +1,233 @@
+"""GPU parity of the persistent fused pass (kernel_mode 6; the automatic choice of the blocking dense
+solves for 1024 < m <= 8192): one resident workgroup per compute unit, a block of iterations per launch,
+two grid-wide waits per iteration.  Everything goes through the C ABI and is compared with the CPU oracle.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2605_00837_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32, TOL_F64 = 1e-3, 2e-5
+
+
+@pytest.fixture(scope="module")
+def fs():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_00837_amd import binding
+    return binding
+
+
+def dev(x):
+    import torch
+    return None if x is None else torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def _supported(fs, n, m):
+    """The kernel needs one workgroup per strip of at most 64 columns: enough row panels and compute units."""
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    try:
+        return fs.fs_kernel_choice(n, m, 0, True, cus, kernel_mode=6) == "persist"
+    except fs.FsError:
+        return False
+
+
+def pot_err(x, ref, eps):
+    return float(np.max(np.abs(np.asarray(x, dtype=np.float64) - ref)) / eps)
+
+
+# every instantiation: one to four 16-byte groups per lane, full and masked widths; ragged last panels; many
+# panels per workgroup; grids smaller than the chip; strips that are not a power of two wide
+SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (1000, 16001), (333, 12288), (260, 16384),
+          (70, 2000), (3001, 5000), (129, 4096), (200, 1028), (1100, 6001), (600, 9000)]
+
+
+@pytest.mark.parametrize("n,m", SHAPES)
+def test_persistent_pass_matches_oracle(fs, oracle, n, m):
+    if not _supported(fs, n, m):
+        pytest.skip("needs more compute units than this device has")
+    w = W.random_dense(n, m, seed=6000 + n + m, cmax=2.0, eps=0.03)
+    iters = 27                                  # one whole block of 25 iterations and a short one
+    ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C)
+    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, iters, 0.0, C=dev(w.C), want_f64=True, kernel_mode=6)
+    assert r["iters"] == iters and not r["nonfinite"]
+    assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+    assert pot_err(r["f"].cpu().numpy(), ref["f"], w.eps) < TOL_F32
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+
+
+def test_persistent_pass_is_the_automatic_choice_and_repeats_bit_for_bit(fs, oracle):
+    import torch
+    n, m = 700, 3000
+    if not _supported(fs, n, m):
+        pytest.skip("needs more compute units than this device has")
+    w = W.random_dense(n, m, seed=6100, cmax=2.0, eps=0.04)
+    a, b, C = dev(w.a), dev(w.b), dev(w.C)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert fs.fs_kernel_choice(n, m, 0, True, cus) == "persist"
+    r0 = fs.fs_sinkhorn_solve(a, b, w.eps, 60, 0.0, C=C, want_f64=True)
+    r6 = fs.fs_sinkhorn_solve(a, b, w.eps, 60, 0.0, C=C, want_f64=True, kernel_mode=6)
+    assert torch.equal(r0["f64"], r6["f64"]) and torch.equal(r0["g64"], r6["g64"])
+    # no result depends on the order in which workgroups finish or arrive
+    for _ in range(3):
+        r = fs.fs_sinkhorn_solve(a, b, w.eps, 60, 0.0, C=C, want_f64=True)
+        assert torch.equal(r["f64"], r0["f64"]) and torch.equal(r["g"], r0["g"]) and r["marginal_err"] == r0["marginal_err"]
+    # the spec entry point takes the same path
+    f2, g2, it2 = fs.fs_sinkhorn_dense(C, a, b, w.eps, 60, 0.0)
+    assert it2 == 60 and torch.equal(f2, r0["f"]) and torch.equal(g2, r0["g"])
+    ref = oracle.solve(w.a, w.b, w.eps, 60, C=w.C)
+    assert pot_err(r0["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+
+
+def test_persistent_pass_stop_rule_history_and_resume(fs, oracle):
+    import torch
+    n, m = 320, 1500
+    if not _supported(fs, n, m):
+        pytest.skip("needs more compute units than this device has")
+    w = W.random_dense(n, m, seed=6200, eps=0.05)
+    a, b, C = dev(w.a), dev(w.b), dev(w.C)
+    tol, K = 1e-5, 400
+    full = oracle.solve(w.a, w.b, w.eps, K, C=w.C, err_every_iter=True)
+    eh = full["err_hist"]
+    for c in (1, 7, 10, 40):                     # 40: checks that fall into the second block of a launch sequence
+        hist = torch.full((K,), float("nan"), dtype=torch.float32, device="cuda")
+        r = fs.fs_sinkhorn_solve(a, b, w.eps, K, tol, C=C, want_f64=True, check_every=c, kernel_mode=6, err_history=hist)
+        ks = [k for k in range(c, K + 1, c) if eh[k - 1] < tol]
+        assert r["converged"] and r["iters"] == ks[0], (c, r["iters"], ks[0])
+        ref = oracle.solve(w.a, w.b, w.eps, r["iters"], C=w.C)
+        assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+        assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+        assert abs(r["marginal_err"] - eh[r["iters"] - 1]) <= 1e-3 * eh[r["iters"] - 1] + 5e-7
+        h = hist.cpu().numpy()[:r["iters"]]
+        assert np.all(np.isfinite(h)) and np.allclose(h, eh[:r["iters"]], rtol=1e-3, atol=5e-7)
+    # not reached: runs to max_iter, reports not converged, err of the last iterate
+    r = fs.fs_sinkhorn_solve(a, b, w.eps, 15, 1e-30, C=C, check_every=5, kernel_mode=6)
+    assert r["iters"] == 15 and not r["converged"]
+    assert abs(r["marginal_err"] - eh[14]) <= 1e-3 * eh[14] + 5e-7
+    r0 = fs.fs_sinkhorn_solve(a, b, w.eps, 0, 0.0, C=C, kernel_mode=6)
+    assert r0["iters"] == 0 and float(r0["f"].abs().max()) == 0.0
+    # resume: 13 + 9 iterations against 22 in one go (not bitwise: the hand-over rescales once)
+    r1 = fs.fs_sinkhorn_solve(a, b, w.eps, 13, 0.0, C=C, want_f64=True, kernel_mode=6)
+    r2 = fs.fs_sinkhorn_solve(a, b, w.eps, 9, 0.0, C=C, want_f64=True, kernel_mode=6, warm_start=True,
+                              f64_in=r1["f64"], g64_in=r1["g64"])
+    r3 = fs.fs_sinkhorn_solve(a, b, w.eps, 22, 0.0, C=C, want_f64=True, kernel_mode=6)
+    assert float((r2["f64"] - r3["f64"]).abs().max()) / w.eps < TOL_F64
+    assert float((r2["g64"] - r3["g64"]).abs().max()) / w.eps < TOL_F64
+    # in-place warm start through the fp32 potentials
+    f, g = r1["f"].clone(), r1["g"].clone()
+    r4 = fs.fs_sinkhorn_solve(a, b, w.eps, 9, 0.0, C=C, f=f, g=g, want_f64=True, kernel_mode=6, warm_start=True)
+    assert float((r4["f64"] - r3["f64"]).abs().max()) / w.eps < TOL_F32
+
+
+@pytest.mark.parametrize("eps", [1e-3, 1e-4])
+@pytest.mark.parametrize("n,m", [(517, 4100), (300, 4096), (600, 8190), (260, 8192), (300, 12288), (290, 16001), (1500, 3001)])
+def test_persistent_pass_small_eps(fs, oracle, n, m, eps):
+    """Costs up to 60 at eps 1e-3 and 1e-4: the exact redo of the row phase, and potentials of 10^5 .. 10^6
+    in units of eps.  Same bar as the other dense paths in this regime (the iteration does not contract there,
+    so the rounding of the 2 K half-steps adds up at worst linearly)."""
+    if not _supported(fs, n, m):
+        pytest.skip("needs more compute units than this device has")
+    iters = 300
+    w = W.random_dense(n, m, seed=7000 + n + m, cmax=60.0, eps=eps)
+    ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C, err_every_iter=True)
+    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, iters, 0.0, C=dev(w.C), want_f64=True, kernel_mode=6)
+    assert r["iters"] == iters and not r["nonfinite"]
+    df, dg = r["f64"].cpu().numpy() - ref["f"], r["g64"].cpu().numpy() - ref["g"]
+    raw = max(np.abs(df).max(), np.abs(dg).max()) / w.eps
+    assert raw < TOL_F32, raw
+    c = 0.5 * (np.median(df) - np.median(dg))
+    e64 = max(np.abs(df - c).max(), np.abs(dg + c).max()) / w.eps
+    assert e64 < max(TOL_F64, 2 * iters * 1e-7), (e64, raw)
+    assert abs(r["marginal_err"] - ref["err_hist"][-1]) <= 1e-3 * ref["err_hist"][-1] + 5e-7
+
+
+@pytest.mark.parametrize("eps", [0.05, 2e-3])
+@pytest.mark.parametrize("n,m", [(300, 4096), (600, 8192), (290, 16384), (520, 3001)])
+def test_persistent_pass_tiny_and_zero_weights(fs, oracle, n, m, eps):
+    """Weights of 1e-30, 1e-36, a denormal and an exact zero in a and b: the columns concerned total less than
+    2^-66 in fp32 and go through the exact recomputation inside the merge, every iteration."""
+    if not _supported(fs, n, m):
+        pytest.skip("needs more compute units than this device has")
+    w = W.random_dense(n, m, seed=7200 + n + m, cmax=2.0, eps=eps)
+    rng = np.random.default_rng(n + m)
+    tiny = [1e-30, 1e-36, 1e-41]
+    for vec in (w.a, w.b):
+        k = vec.shape[0]
+        idx = rng.choice(k, size=7, replace=False)
+        vec[idx[0]] = 0.0
+        for q, j in enumerate(idx[1:]):
+            vec[j] = np.float32(tiny[q % 3])
+        rest = np.ones(k, dtype=bool)
+        rest[idx] = False
+        vec[rest] = (vec[rest].astype(np.float64) / vec[rest].sum(dtype=np.float64)).astype(np.float32)
+    iters = 40
+    ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C)
+    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, iters, 0.0, C=dev(w.C), want_f64=True, kernel_mode=6)
+    assert r["iters"] == iters and not r["nonfinite"]
+    assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-3 * err_ref + 5e-7
+
+
+@pytest.mark.parametrize("warm", [False, True])
+def test_persistent_pass_gives_up_cleanly_and_the_solve_falls_back(fs, oracle, warm):
+    """wait_limit = 1: a workgroup stops waiting for the others after a single poll, which the host can force
+    without any kernel misbehaving (every workgroup still exits).  Asked for by name, the solve then says that
+    it gave up (or, with luck, completes); as the library's own choice it is followed by the multi-kernel
+    driver and delivers the right answer, also when the start was passed in place."""
+    n, m = 900, 2100
+    if not _supported(fs, n, m):
+        pytest.skip("needs more compute units than this device has")
+    w = W.random_dense(n, m, seed=6300, cmax=1.0, eps=0.05)
+    a, b, C = dev(w.a), dev(w.b), dev(w.C)
+    kw, f0, g0 = {}, None, None
+    if warm:
+        rng = np.random.default_rng(5)
+        f0 = (rng.standard_normal(n) * 0.1).astype(np.float32)
+        g0 = (rng.standard_normal(m) * 0.1).astype(np.float32)
+        kw = dict(f=dev(f0), g=dev(g0), warm_start=True)
+    ref = oracle.solve(w.a, w.b, w.eps, 30, C=w.C, f0=f0, g0=g0) if warm else oracle.solve(w.a, w.b, w.eps, 30, C=w.C)
+    r = fs.fs_sinkhorn_solve(a, b, w.eps, 30, 0.0, C=C, want_f64=True, wait_limit=1, **kw)
+    assert r["iters"] == 30 and not r["nonfinite"] and not r["gave_up"]
+    assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+    outcomes = set()
+    for _ in range(4):
+        rk = fs.fs_sinkhorn_solve(a, b, w.eps, 30, 0.0, C=C, want_f64=True, kernel_mode=6, wait_limit=1)
+        if rk["gave_up"]:
+            outcomes.add("gave up")
+            assert math.isnan(rk["marginal_err"]) and not rk["converged"]
+        else:
+            outcomes.add("completed")
+            assert rk["iters"] == 30 and not rk["nonfinite"]
+    # the next solve on the same workspace is unaffected
+    r = fs.fs_sinkhorn_solve(a, b, w.eps, 30, 0.0, C=C, want_f64=True, kernel_mode=6)
+    ref = oracle.solve(w.a, w.b, w.eps, 30, C=w.C)
+    assert r["iters"] == 30 and not r["nonfinite"]
+    assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+    print("outcomes with wait_limit = 1:", sorted(outcomes))
+
+
+def test_persistent_pass_rejections(fs):
+    import torch
+    a = torch.full((100,), 0.01, device="cuda")
+    b = torch.full((8192,), 1.0 / 8192, device="cuda")
+    C = torch.rand((100, 8192), device="cuda")
+    with pytest.raises(fs.FsError, match="kernel_mode 6"):
+        fs.fs_sinkhorn_solve(a, b, 0.05, 5, 0.0, C=C, kernel_mode=6)           # 50 panels: strips of 164 columns
+    with pytest.raises(fs.FsError, match="kernel_mode 6"):
+        fs.fs_sinkhorn_dense_ex(C, a, b, 0.05, 5, 0.0, kernel_mode=6)          # blocking solves only
+    C16 = torch.rand((300, 4096), device="cuda").to(torch.float16)
+    a3 = torch.full((300,), 1.0 / 300, device="cuda")
+    b3 = torch.full((4096,), 1.0 / 4096, device="cuda")
+    with pytest.raises(fs.FsError, match="kernel_mode 6"):
+        fs.fs_sinkhorn_solve(a3, b3, 0.05, 5, 0.0, C=C16, kernel_mode=6)       # fp32 costs only
