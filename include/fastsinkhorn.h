@@ -181,6 +181,21 @@ fs_status fs_sinkhorn_points_ex(const float *X, const float *Y, int d, const flo
                                 fs_stream stream, const fs_options *opts,
                                 void *workspace, size_t workspace_bytes, fs_result *result_dev);
 
+/* ---- For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): fs_sinkhorn_dense_ex with a scratch buffer built into the library in place
+ * of the caller's workspace.  The buffer is a static device array of FS_STATIC_SCRATCH_BYTES (each GPU the
+ * library runs on holds its own copy until the process ends); its device address is looked up on the first
+ * call on a device.  This entry point calls no hipMalloc, hipFree or other allocating routine, ever.
+ * Takes every problem with fs_workspace_bytes(n, m, 0) <= FS_STATIC_SCRATCH_BYTES (n = m = 8192 fits; so do
+ * 16384 x 4096 and 256 x 65536) and returns FS_ERR_WORKSPACE, having enqueued nothing, for a larger one.
+ * Results are those of fs_sinkhorn_dense_ex bit for bit (same kernels).  All calls on one GPU share the one
+ * buffer, which keeps the last call's contents (every solve initialises what it reads): calls that overlap on
+ * one GPU -- two streams, or two host threads -- race; order them on one stream or with events. ---- */
+#define FS_STATIC_SCRATCH_BYTES (20u << 20)
+fs_status fs_sinkhorn_dense_static(const float *C, const float *a, const float *b, int n, int m,
+                                   float eps, int max_iter, float tol, float *f, float *g,
+                                   fs_stream stream, const fs_options *opts, fs_result *result_dev);
+
 /* Blocking solve with options and a host-side result: like fs_sinkhorn_dense / _points
  * (library workspace, early stop watched from the host, one synchronisation at the end) but
  * honouring `opts` and filling *result_host (ordinary host memory, may be NULL).  Exactly one of

@@ -73,6 +73,9 @@ def _load():
     lib.fs_sinkhorn_dense_ex.restype = ci
     lib.fs_sinkhorn_dense_ex.argtypes = [vp, vp, vp, ci, ci, cf, ci, cf, vp, vp, vp,
                                          ctypes.POINTER(fs_options), vp, ctypes.c_size_t, vp]
+    lib.fs_sinkhorn_dense_static.restype = ci
+    lib.fs_sinkhorn_dense_static.argtypes = [vp, vp, vp, ci, ci, cf, ci, cf, vp, vp, vp,
+                                             ctypes.POINTER(fs_options), vp]
     lib.fs_sinkhorn_points_ex.restype = ci
     lib.fs_sinkhorn_points_ex.argtypes = [vp, vp, ci, vp, vp, ci, ci, cf, ci, cf, vp, vp, vp,
                                           ctypes.POINTER(fs_options), vp, ctypes.c_size_t, vp]
@@ -101,7 +104,7 @@ def _load():
 _lib = _load()
 
 EXPORTED = ("fs_sinkhorn_dense", "fs_sinkhorn_points", "fs_sinkhorn_solve", "fs_workspace_bytes",
-            "fs_sinkhorn_dense_ex", "fs_sinkhorn_points_ex", "fs_sinkhorn_dense_batched", "fs_sinkhorn_annealed", "fs_plan", "fs_cost", "fs_plan_f64",
+            "fs_sinkhorn_dense_ex", "fs_sinkhorn_points_ex", "fs_sinkhorn_dense_static", "fs_sinkhorn_dense_batched", "fs_sinkhorn_annealed", "fs_plan", "fs_cost", "fs_plan_f64",
             "fs_cost_f64", "fs_diagnostics", "fs_barycentric", "fs_update_f", "fs_update_g", "fs_last_error", "fs_clear_cache", "fs_version",
             "fs_last_kernel_timing", "fs_kernel_choice")
 
@@ -330,6 +333,20 @@ def _ex(fn_dense: bool, C, X, Y, a, b, eps, max_iter, tol, f, g, workspace, opt_
 def fs_sinkhorn_dense_ex(C, a, b, eps, max_iter, tol, f=None, g=None, workspace=None, **opt_kw) -> AsyncSolve:
     """Asynchronous dense solve on the current stream (no host synchronisation)."""
     return _ex(True, C, None, None, a, b, eps, max_iter, tol, f, g, workspace, opt_kw)
+
+
+FS_STATIC_SCRATCH_BYTES = 20 << 20
+
+
+def fs_sinkhorn_dense_static(C, a, b, eps, max_iter, tol, f, g, result_dev, **opt_kw) -> None:
+    """Asynchronous dense solve on the library's static scratch buffer; the C call allocates nothing.  The
+    caller supplies every output: f [n], g [m] fp32 and result_dev, a uint8 tensor of 16 bytes (decode with
+    results_from_device after synchronising)."""
+    n, m, _ = _shape(C, None, None, a, b)
+    Cp = _cost(C, opt_kw)
+    o = make_options(**opt_kw)
+    _check(_lib.fs_sinkhorn_dense_static(Cp, _p(a), _p(b), n, m, float(eps), int(max_iter), float(tol), _p(f),
+                                         _p(g), _stream(), ctypes.byref(o), _p(result_dev, torch.uint8)))
 
 
 def fs_sinkhorn_points_ex(X, Y, a, b, eps, max_iter, tol, f=None, g=None, workspace=None, **opt_kw) -> AsyncSolve:

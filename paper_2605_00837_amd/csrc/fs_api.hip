@@ -162,6 +162,29 @@ fs_status get_cache(size_t need_bytes, DeviceCache **out) {
     return FS_OK;
 }
 
+// ---------------------------------------------------------------- static scratch
+// Workspace of the entry point that allocates nothing.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: every device holds its own copy at its own address, looked up once per device (with
+// that device current) and used through the pointer from then on.
+static __device__ __align__(256) unsigned char scratch[FS_STATIC_SCRATCH_BYTES];
+
+std::map<int, void *> g_scratch_ptr;        // by device, guarded by g_mu
+
+fs_status static_scratch(void **out) {
+    int dev = 0;
+    FS_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_scratch_ptr.find(dev);
+    if (it == g_scratch_ptr.end()) {
+        void *ptr = nullptr;
+        FS_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || (reinterpret_cast<uintptr_t>(ptr) & 255u)) { set_err("static scratch has no usable device address"); return FS_ERR_HIP; }
+        it = g_scratch_ptr.emplace(dev, ptr).first;
+    }
+    *out = it->second;
+    return FS_OK;
+}
+
 // ---------------------------------------------------------------- one solve, described
 struct Problem {
     const float *C, *X, *Y, *a, *b;
@@ -1147,6 +1170,25 @@ fs_status fs_sinkhorn_dense_ex(const float *C, const float *a, const float *b, i
     if (!C) { set_err("C must be non-null"); return FS_ERR_INVALID_ARG; }
     Problem pr{C, nullptr, nullptr, a, b, 0, n, m, eps, max_iter, tol};
     return solve_async(pr, f, g, (hipStream_t)stream, opts, workspace, workspace_bytes, result_dev);
+}
+
+fs_status fs_sinkhorn_dense_static(const float *C, const float *a, const float *b, int n, int m, float eps,
+                                   int max_iter, float tol, float *f, float *g, fs_stream stream,
+                                   const fs_options *opts, fs_result *result_dev) {
+    if (!C) { set_err("C must be non-null"); return FS_ERR_INVALID_ARG; }
+    Problem pr{C, nullptr, nullptr, a, b, 0, n, m, eps, max_iter, tol};
+    fs_status v = validate(pr, f, g);
+    if (v != FS_OK) return v;
+    const size_t need = make_layout(n, m, 0).total;
+    if (need > (size_t)FS_STATIC_SCRATCH_BYTES) {
+        set_err("a %d x %d problem needs %zu bytes of scratch, the static buffer holds %zu: use fs_sinkhorn_dense_ex "
+                "with a workspace of the caller's", n, m, need, (size_t)FS_STATIC_SCRATCH_BYTES);
+        return FS_ERR_WORKSPACE;
+    }
+    void *ws = nullptr;
+    v = static_scratch(&ws);
+    if (v != FS_OK) return v;
+    return solve_async(pr, f, g, (hipStream_t)stream, opts, ws, (size_t)FS_STATIC_SCRATCH_BYTES, result_dev);
 }
 
 fs_status fs_sinkhorn_points_ex(const float *X, const float *Y, int d, const float *a, const float *b, int n,
