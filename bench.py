@@ -1,14 +1,20 @@
 #!/usr/bin/env python3
-"""Headline benchmark: log-domain Sinkhorn iterations per second on one MI355X.
+"""Benchmark of the log-domain Sinkhorn hot path on one MI355X; one JSON line per run.
 
-A "step" is one pass of the whole hot path -- f-update (row LSE), g-update (column LSE with
-the new f) and the marginal-error check -- over the dense n = m = 8192 fp32 problem at
-eps = 1e-2 (seeded synthetic inputs of `workloads.c2_dense_gauss`).  Inputs are resident in HBM
-before the timed region starts.  One JSON line is printed.
+A "step" is one pass of the whole hot path -- f-update (row LSE), g-update (column LSE with the new f) and the
+marginal-error check -- over one of the five seeded synthetic workloads (`--workload`, default c2: the dense
+n = m = 8192 fp32 problem at eps = 1e-2 that the headline metric is quoted on).  Inputs are resident in HBM
+before the timed region starts; the timed region is one blocking solve of K iterations between synchronisations.
 
-`--workload c4` times the point-cloud path instead (n = m = 65536 points on the unit sphere, d = 3,
-cost recomputed on the fly): the same JSON shape, throughput in point pairs per second, roofline
-against the vector-ALU issue rate.
+    python bench.py [--workload c1|c2|c3|c4|c5p|c5d] [--steps K] [--warmup W]
+    python bench.py --calibrate-copy      # a plain 256 MiB device copy: what the FETCH_SIZE / WRITE_SIZE counters
+                                          # read for a known size (run under rocprofv3 --pmc)
+
+Every line carries `roofline` (the dominant kernel: algorithmic bytes or operations per launch over its average
+launch duration, measured in the run with events that the runtime stamps with the start and the stop of the
+dispatch), for the dense workloads `iteration` (the whole iteration against the same HBM peak: algorithmic bytes
+of one iteration over the wall-clock time per step) and `cpu_baseline` (the CPU oracle as it stands on a bounded
+sample of the same workload).
 """
 from __future__ import annotations
 
@@ -23,45 +29,71 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+FP64_VECTOR_PEAK_TFLOPS = 78.6
+# v_exp_f32 issues at a quarter of the full vector rate: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz / 4,
+# derived from the unit counts; the measured rate on this chip is 18.2e12 per second
+EXP_PEAK_PER_S = 256 * 4 * 16 * 2.4e9 / 4
 
 
-def _traffic_from_profiles(n, m):
-    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary."""
-    path = os.path.join(ROOT, "profiles", "k_fused_pf_c2_dense8192_pmc.json")
+def _traffic_from_profiles(kernel, n, m):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary of the same
+    workload (counters are collected in runs of their own, not in this run)."""
+    path = os.path.join(ROOT, "profiles", "k_persist_c2_dense8192_pmc.json")
     try:
         with open(path) as fh:
             rec = json.load(fh)
-        if rec.get("n") == n and rec.get("m") == m:
-            return rec.get("hbm_bytes_per_launch")
+        if rec.get("n") == n and rec.get("m") == m and rec.get("kernel", "").startswith(kernel):
+            return rec.get("hbm_bytes_per_launch"), os.path.relpath(path, ROOT)
     except (OSError, ValueError):
         pass
-    return None
+    return None, None
 
 
-def cpu_baseline(w, budget_s=12.0):
-    """The CPU oracle as it stands, timed on the host cores: Alg. 1 with the paper's check
-    interval c = 10 on the same n = m = 8192 inputs, for a bounded number of iterations."""
+def _oracle_rate(solve, budget_s, unit_per_iter, max_iters=200):
+    """Times `solve(iters)` (the oracle, Alg. 1 with the paper's check interval) for about budget_s seconds."""
+    t0 = time.perf_counter()
+    solve(1)
+    one = time.perf_counter() - t0
+    iters = int(max(2, min(max_iters, budget_s / max(one, 1e-4))))
+    t0 = time.perf_counter()
+    solve(iters)
+    dt = time.perf_counter() - t0
+    return iters, dt, unit_per_iter * iters / dt
+
+
+def cpu_baseline_dense(w, eps, label, budget_s=12.0):
     import oracle
     threads = oracle.max_threads()
-    t0 = time.perf_counter()
-    oracle.solve(w.a, w.b, w.eps, 1, tol=1e-30, check_every=10, C=w.C)
-    one = time.perf_counter() - t0
-    iters = int(max(2, min(60, budget_s / max(one, 1e-3))))
-    t0 = time.perf_counter()
-    oracle.solve(w.a, w.b, w.eps, iters, tol=1e-30, check_every=10, C=w.C)
-    dt = time.perf_counter() - t0
-    # the same oracle on one thread, two iterations
+    run = lambda it: oracle.solve(w.a, w.b, eps, it, tol=1e-30, check_every=10, C=w.C)
+    iters, dt, rate = _oracle_rate(run, budget_s, 1.0)
     oracle.set_threads(1)
     try:
         t0 = time.perf_counter()
-        oracle.solve(w.a, w.b, w.eps, 2, tol=1e-30, check_every=10, C=w.C)
-        dt1 = time.perf_counter() - t0
+        run(2 if w.n * w.m > 1 << 22 else 20)
+        dt1 = (time.perf_counter() - t0) / (2 if w.n * w.m > 1 << 22 else 20)
     finally:
         oracle.set_threads(threads)
-    return {"value": iters / dt, "unit": "iter/s", "cores": threads, "kind": "oracle",
-            "sample": f"{iters} iterations of Alg. 1 (check every 10) on the same n=m={w.n} dense inputs, "
-                      f"fp64, OpenMP over rows/columns, {dt:.1f} s",
-            "one_thread_value": 2 / dt1}
+    return {"value": rate, "unit": "iter/s", "cores": threads, "kind": "oracle",
+            "sample": f"{iters} iterations of Alg. 1 (check every 10) on the same {label} inputs, fp64, "
+                      f"OpenMP over rows/columns, {dt:.1f} s",
+            "one_thread_value": 1.0 / dt1}
+
+
+def cpu_baseline_points(w, label, sub, budget_s=12.0):
+    """Point clouds: the oracle on the first `sub` points of each cloud (all of them when sub is None)."""
+    import numpy as np
+    import oracle
+    X, Y, a, b = w.X, w.Y, w.a, w.b
+    if sub is not None and sub < w.n:
+        X, Y = np.ascontiguousarray(X[:sub]), np.ascontiguousarray(Y[:sub])
+        a = np.ascontiguousarray(a[:sub] / a[:sub].sum(dtype=np.float64)).astype(np.float32)
+        b = np.ascontiguousarray(b[:sub] / b[:sub].sum(dtype=np.float64)).astype(np.float32)
+    pairs = 2.0 * X.shape[0] * Y.shape[0]
+    run = lambda it: oracle.solve(a, b, w.eps, it, tol=1e-30, check_every=10, X=X, Y=Y)
+    iters, dt, rate = _oracle_rate(run, budget_s, pairs / 1e9, max_iters=50)
+    return {"value": rate, "unit": "Gpair/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": f"{iters} iterations of Alg. 1 on {'the first %d points of each cloud of ' % sub if sub else ''}"
+                      f"the same {label} inputs, fp64, {dt:.1f} s"}
 
 
 # Point-cloud LSE pass, optimistic variant, per point pair: d fp64 FMAs, one fp64 subtraction, one
@@ -74,131 +106,187 @@ def points_alu_peak(d):
     return pairs_per_s, flop_per_pair
 
 
-def bench_points(args):
+def _solve_timed(fs, torch, a, b, eps, steps, tol, warmup, time_kernels=True, **geo_kw):
+    n, m = a.shape[0], b.shape[0]
+    f = torch.empty(n, dtype=torch.float32, device="cuda")
+    g = torch.empty(m, dtype=torch.float32, device="cuda")
+    # warm-up: W untimed iterations (also sizes the library's cached workspace)
+    fs.fs_sinkhorn_solve(a, b, eps, warmup, 0.0, f=f, g=g, **geo_kw)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    r = fs.fs_sinkhorn_solve(a, b, eps, steps, tol, f=f, g=g, time_kernel_every=1 if time_kernels else 0, **geo_kw)
+    torch.cuda.synchronize()
+    return r, time.perf_counter() - t0
+
+
+def bench_dense(args, name):
     import torch
     from paper_2605_00837_amd import binding as fs, workloads as W
 
     torch.cuda.set_device(0)
-    w = W.c4_sphere_points(args.n if args.n != 8192 else 65536)
-    n, m, d = w.n, w.m, w.X.shape[1]
-    X, Y, a, b = (torch.from_numpy(t).cuda() for t in (w.X, w.Y, w.a, w.b))
-    f = torch.empty(n, dtype=torch.float32, device="cuda")
-    g = torch.empty(m, dtype=torch.float32, device="cuda")
-    steps = args.steps if args.steps != 1000 else w.max_iter      # the configuration: 500 fixed iterations
-    fs.fs_sinkhorn_solve(a, b, w.eps, args.warmup, 0.0, X=X, Y=Y, f=f, g=g)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    r = fs.fs_sinkhorn_solve(a, b, w.eps, steps, 0.0, X=X, Y=Y, f=f, g=g, time_kernel_every=8)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if name == "c1":
+        w = W.c1_small_dense()
+        eps, steps_default, tol, label = w.eps, 200, 0.0, "c1_dense_uniform2d n=m=256"
+        desc = "uniform weights, eps=0.05, 200 fixed iterations"
+        metric = "sinkhorn_iters_per_sec_dense_n256_fp32_eps5e-2"
+    elif name == "c2":
+        w = W.c2_dense_gauss(args.n)
+        eps, steps_default, tol, label = w.eps, 1000, w.tol, f"c2_dense_gauss2d n=m={w.n}"
+        desc = "Dirichlet(1) weights, eps=1e-2, tol=1e-6, check_every=10"
+        metric = ("sinkhorn_iters_per_sec_dense_n8192_fp32_eps1e-2" if w.n == 8192
+                  else f"sinkhorn_iters_per_sec_dense_n{w.n}_fp32_eps1e-2")
+    elif name == "c3":
+        w = W.c3_small_eps()
+        eps = w.eps_list[args.eps_index]
+        steps_default, tol, label = 2000, 0.0, "c3_small_eps_sweep n=m=4096"
+        desc = f"uniform weights, cost / max cost, eps={eps:g}, 2000 fixed iterations"
+        metric = f"sinkhorn_iters_per_sec_dense_n4096_fp32_eps{eps:.0e}"
+    else:                                                     # c5d: the dense variant of the colour workload
+        w = W.c5_colour(16384, args.m5, dense=True)
+        w.X = w.Y = None
+        eps, steps_default, tol, label = w.eps, w.max_iter, w.tol, f"c5_colour_rgb dense 16384 x {args.m5}"
+        desc = "Dirichlet(2) weights, eps=5e-3, tol=1e-5, check_every=10, C built from the RGB points"
+        metric = f"sinkhorn_iters_per_sec_dense_16384x{args.m5}_fp32_eps5e-3"
+    n, m = w.n, w.m
+    steps = args.steps if args.steps > 0 else steps_default
+    C, a, b = (torch.from_numpy(t).cuda() for t in (w.C, w.a, w.b))
+    kw = dict(C=C, kernel_mode=args.kernel_mode, fused_variant=args.fused_variant)
+    if tol > 0.0:
+        kw["check_every"] = 10
+    # the kernels that run a whole solve in one launch cannot be sampled per iteration (asking for it would
+    # make the library take the multi-kernel path instead): they are timed by the wall clock alone
+    choice = fs.fs_kernel_choice(n, m, kernel_mode=args.kernel_mode, fused_variant=args.fused_variant)
+    one_launch_kernel = choice in ("small", "coop", "grid")
+    r, dt = _solve_timed(fs, torch, a, b, eps, steps, tol, args.warmup, time_kernels=not one_launch_kernel, **kw)
     iters = r["iters"]
-    kern_ms, kern_samples, kern_name = fs.fs_last_kernel_timing()
+    kern_ms, launches, kern_name, covered = (0.0, 0, "k_" + choice, 0) if one_launch_kernel else fs.fs_last_kernel_timing()
+
+    # Algorithmic bytes.  One pass over C with V in and F, U out is what one iteration of a kernel that fuses the
+    # two half-steps needs; two passes (the row pass and the column pass each read C) is the floor of any two-kernel
+    # iteration and the figure the survey of the paper's method states.  Nothing is credited above the one-pass figure.
+    bytes_one_pass = n * m * 4 + m * 8 + n * 16
+    bytes_two_pass = 2 * n * m * 4
+    per_iter_ms = kern_ms * launches / max(covered, 1)
+    alg_bytes_launch = bytes_one_pass * (covered / max(launches, 1)) if not one_launch_kernel else None
+    out = {
+        "metric": metric, "value": iters / dt, "unit": "iter/s", "n_gpus": 1, "steps": iters, "warmup": args.warmup,
+        "ms_per_step": dt * 1e3 / max(iters, 1), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{label} fp32 C ({n * m * 4 / 2 ** 20:g} MiB), {desc}, max_iter={steps}",
+                   "kernel_path": kern_name, "potentials": "fp64 internal, fp32 out"},
+        "ms_to_stop": dt * 1e3, "converged": r["converged"], "marginal_err": r["marginal_err"],
+    }
+    if alg_bytes_launch is not None and launches > 0:
+        achieved = alg_bytes_launch / (kern_ms * 1e-3) / 1e9
+        traffic, src = _traffic_from_profiles(kern_name, n, m)
+        out["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                           "traffic_source": (src + " (rocprofv3 --pmc runs of their own, not this run)") if src else None,
+                           "kernel": kern_name, "kernel_avg_us": kern_ms * 1e3, "kernel_launches_timed": launches,
+                           "iterations_per_launch": covered / max(launches, 1), "kernel_us_per_iteration": per_iter_ms * 1e3,
+                           "algorithmic_bytes_per_launch": alg_bytes_launch}
+    else:
+        # the whole solve runs inside one launch that keeps C in registers: latency-bound, no roofline fraction claimed
+        out["roofline"] = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+                           "traffic": None, "kernel": kern_name, "note": "launch- and latency-bound "
+                           "size: C is read once per solve and stays in registers; microseconds per iteration is the figure"}
+    it_gbs = bytes_one_pass * iters / dt / 1e9
+    out["iteration"] = {"bytes_one_pass": bytes_one_pass, "bytes_two_pass_survey": bytes_two_pass,
+                        "achieved_GBs": it_gbs, "frac_iteration": it_gbs / HBM_PEAK_GBS,
+                        "two_pass_equivalent_GBs": bytes_two_pass * iters / dt / 1e9,
+                        "us_per_iteration": dt * 1e6 / max(iters, 1)}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_dense(w, eps, label, budget_s=12.0 if n * m >= 1 << 20 else 3.0)
+    print(json.dumps(out))
+
+
+def bench_points(args, name):
+    import torch
+    from paper_2605_00837_amd import binding as fs, workloads as W
+
+    torch.cuda.set_device(0)
+    if name == "c4":
+        w = W.c4_sphere_points(args.n if args.n != 8192 else 65536)
+        steps_default, tol = w.max_iter, 0.0
+        label = f"c4_sphere_points n=m={w.n} d=3"
+        desc = f"eps={w.eps:g}, uniform weights, fixed iterations"
+        sub = 16384
+    else:
+        w = W.c5_colour(16384, args.m5)
+        steps_default, tol = w.max_iter, w.tol
+        label = f"c5_colour_rgb points 16384 x {args.m5} d=3"
+        desc = f"eps={w.eps:g}, Dirichlet(2) weights, tol=1e-5, check_every=10"
+        sub = None
+    n, m, d = w.n, w.m, w.X.shape[1]
+    steps = args.steps if args.steps > 0 else steps_default
+    X, Y, a, b = (torch.from_numpy(t).cuda() for t in (w.X, w.Y, w.a, w.b))
+    kw = dict(X=X, Y=Y)
+    if tol > 0.0:
+        kw["check_every"] = 10
+    r, dt = _solve_timed(fs, torch, a, b, w.eps, steps, tol, args.warmup, **kw)
+    iters = r["iters"]
+    kern_ms, launches, kern_name, covered = fs.fs_last_kernel_timing()
     peak_pairs, flop_per_pair = points_alu_peak(d)
-    achieved = n * m * flop_per_pair / (kern_ms * 1e-3) / 1e12
+    pairs_per_s = n * m / (kern_ms * 1e-3)
+    achieved = pairs_per_s * flop_per_pair / 1e12
     peak = peak_pairs * flop_per_pair / 1e12
     out = {
-        "metric": f"sinkhorn_point_pairs_per_sec_n{n}_d{d}", "value": 2.0 * n * m * iters / dt / 1e9, "unit": "Gpair/s",
-        "n_gpus": 1, "steps": iters, "warmup": args.warmup, "ms_per_step": dt * 1e3 / iters,
+        "metric": f"sinkhorn_point_pairs_per_sec_{n}x{m}_d{d}", "value": 2.0 * n * m * iters / dt / 1e9, "unit": "Gpair/s",
+        "n_gpus": 1, "steps": iters, "warmup": args.warmup, "ms_per_step": dt * 1e3 / max(iters, 1),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-        "config": {"workload": f"c4_sphere_points n=m={n} d={d} eps={w.eps:g}, uniform weights, fixed {iters} "
-                               f"iterations, cost recomputed per pair (never stored)",
+        "config": {"workload": f"{label}, {desc}, max_iter={steps}, cost recomputed per pair (never stored)",
                    "kernel_path": kern_name},
-        "iters_per_sec": iters / dt, "marginal_err": r["marginal_err"],
+        "iters_per_sec": iters / dt, "ms_to_stop": dt * 1e3, "converged": r["converged"], "marginal_err": r["marginal_err"],
         "roofline": {"bound": "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": None, "kernel": kern_name, "kernel_avg_us": kern_ms * 1e3,
-                     "kernel_samples": kern_samples, "flop_per_pair": flop_per_pair,
-                     "pairs_per_launch": n * m},
+                     "traffic": None, "kernel": kern_name, "kernel_avg_us": kern_ms * 1e3, "kernel_launches_timed": launches,
+                     "flop_per_pair": flop_per_pair, "pairs_per_launch": n * m,
+                     "peak_note": "issue rate of this kernel's own instruction mix (d + 3 full-rate vector "
+                                  "instructions and one v_exp_f32 per pair); the two fractions below are against the "
+                                  "chip's plain fp64 vector peak and against its v_exp_f32 rate",
+                     "fp64_vector": {"achieved_TFLOPs": pairs_per_s * (2 * d + 1) / 1e12, "peak_TFLOPs": FP64_VECTOR_PEAK_TFLOPS,
+                                     "frac": pairs_per_s * (2 * d + 1) / 1e12 / FP64_VECTOR_PEAK_TFLOPS},
+                     "v_exp_f32": {"achieved_per_s": pairs_per_s, "peak_per_s": EXP_PEAK_PER_S,
+                                   "frac": pairs_per_s / EXP_PEAK_PER_S}},
     }
     if not args.no_cpu_baseline:
-        import oracle
-        t0 = time.perf_counter()
-        oracle.solve(w.a, w.b, w.eps, 2, X=w.X, Y=w.Y)
-        dtc = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": 2.0 * n * m * 2 / dtc / 1e9, "unit": "Gpair/s", "cores": oracle.max_threads(),
-                               "kind": "oracle", "sample": f"2 iterations on the same point clouds, fp64, {dtc:.1f} s"}
+        out["cpu_baseline"] = cpu_baseline_points(w, label, sub)
     print(json.dumps(out))
+
+
+def calibrate_copy(mib=256, reps=5):
+    import torch
+    src = torch.empty(mib << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibrate_copy_mib": mib, "copies": reps}))
 
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", choices=["c2", "c4"], default="c2")
+    ap.add_argument("--workload", choices=["c1", "c2", "c3", "c4", "c5p", "c5d"], default="c2")
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--steps", type=int, default=0, help="iterations of the timed solve (0: the workload's own count)")
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--n", type=int, default=8192, help="problem size (default: the headline n = m = 8192)")
+    ap.add_argument("--n", type=int, default=8192, help="c2 / c4: problem size (default: the workload's own)")
+    ap.add_argument("--m5", type=int, default=16384, choices=[16384, 12288], help="c5: number of target points")
+    ap.add_argument("--eps-index", type=int, default=1, help="c3: which of eps = 1e-1, 1e-2, 1e-3, 1e-4")
     ap.add_argument("--kernel-mode", type=int, default=0)
     ap.add_argument("--fused-variant", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
-
-    if args.workload == "c4":
-        bench_points(args)
-        return
-
-    import numpy as np
-    import torch
-    from paper_2605_00837_amd import binding as fs, workloads as W
-
-    torch.cuda.set_device(0)
-    w = W.c2_dense_gauss(args.n)
-    n, m = w.n, w.m
-    C = torch.from_numpy(w.C).cuda()
-    a = torch.from_numpy(w.a).cuda()
-    b = torch.from_numpy(w.b).cuda()
-    f = torch.empty(n, dtype=torch.float32, device="cuda")
-    g = torch.empty(m, dtype=torch.float32, device="cuda")
-    kw = dict(kernel_mode=args.kernel_mode, fused_variant=args.fused_variant)
-
-    # warmup: W untimed iterations (also sizes the library's cached workspace)
-    fs.fs_sinkhorn_solve(a, b, w.eps, args.warmup, 0.0, C=C, f=f, g=g, **kw)
-    torch.cuda.synchronize()
-
-    # timed: exactly K iterations of the configuration itself (tol = 1e-6 is not reached within
-    # 1000 iterations on this problem, so every enqueued iteration runs), bracketed by synchronize
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    r = fs.fs_sinkhorn_solve(a, b, w.eps, args.steps, w.tol, C=C, f=f, g=g, check_every=10,
-                             time_kernel_every=8, **kw)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    iters = r["iters"]
-    kern_ms, kern_samples, kern_name = fs.fs_last_kernel_timing()
-
-    # algorithmic bytes of one launch of the dominant kernel: C once, V in, F and U out
-    alg_bytes = n * m * 4 + m * 8 + n * 16
-    achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
-    out = {
-        "metric": "sinkhorn_iters_per_sec_dense_n8192_fp32_eps1e-2" if args.n == 8192
-                  else f"sinkhorn_iters_per_sec_dense_n{n}_fp32_eps1e-2",
-        "value": iters / dt,
-        "unit": "iter/s",
-        "n_gpus": 1,
-        "steps": iters,
-        "warmup": args.warmup,
-        "ms_per_step": dt * 1e3 / iters,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32",
-        "data": "synthetic",
-        "config": {"workload": f"c2_dense_gauss2d n=m={n} fp32 C ({n * m * 4 >> 20} MiB), Dirichlet(1) weights, "
-                               f"eps=1e-2, tol=1e-6, max_iter={args.steps}, check_every=10",
-                   "kernel_path": kern_name, "potentials": "fp64 internal, fp32 out"},
-        "ms_to_stop": dt * 1e3,
-        "converged": r["converged"],
-        "marginal_err": r["marginal_err"],
-        "two_pass_equivalent_GBs": 2 * n * m * 4 * iters / dt / 1e9,
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": _traffic_from_profiles(n, m),
-                     "kernel": kern_name, "kernel_avg_us": kern_ms * 1e3, "kernel_samples": kern_samples,
-                     "algorithmic_bytes_per_launch": alg_bytes},
-    }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w)
-    print(json.dumps(out))
+    if args.calibrate_copy:
+        calibrate_copy()
+    elif args.workload in ("c4", "c5p"):
+        bench_points(args, args.workload)
+    else:
+        bench_dense(args, args.workload)
 
 
 if __name__ == "__main__":

@@ -145,7 +145,7 @@ typedef struct {
                                   of HIP events that the runtime stamps with the start and the stop of that
                                   dispatch on `stream` (hipExtLaunchKernel); read back with
                                   fs_last_kernel_timing().  The persistent fused pass (kernel_mode 6) is one
-                                  launch per block of iterations: every whole block is timed               */
+                                  launch per block of iterations: every launch is timed                    */
 } fs_options;
 
 /* ---- Blocking solves (Alg. 1).  Return the number of iterations performed (>= 0) or a
@@ -311,12 +311,13 @@ const char *fs_version(void);
 int fs_kernel_choice(int n, int m, int d, const fs_options *opts, int blocking, int compute_units);
 
 /* Average duration (ms) of the dominant kernel over the launches sampled by the most recent
- * blocking solve on this thread that had time_kernel_every > 0, the number of samples, the
- * kernel's name (static storage) and the number of iterations one such launch performs (1, or the
- * block length of the persistent fused pass).  Any output pointer may be NULL.  FS_ERR_INVALID_ARG
- * when there is no such solve.  For benchmarks; no effect on results. */
+ * blocking solve on this thread that had time_kernel_every > 0, the number of sampled launches, the
+ * kernel's name (static storage) and the number of iterations the sampled launches performed in all
+ * (= samples, except for the persistent fused pass, whose launches run a block of iterations each).
+ * Any output pointer may be NULL.  FS_ERR_INVALID_ARG when there is no such solve.  For benchmarks;
+ * no effect on results. */
 fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name,
-                                int32_t *iters_per_launch);
+                                int32_t *iters_sampled);
 
 #ifdef __cplusplus
 }

@@ -207,8 +207,8 @@ def fs_clear_cache() -> None:
 
 
 def fs_last_kernel_timing():
-    """(avg_ms, samples, kernel_name, iters_per_launch) of the dominant kernel sampled by the last timed
-    blocking solve."""
+    """(avg_ms per launch, sampled launches, kernel_name, iterations the sampled launches performed) of the
+    dominant kernel of the last timed blocking solve."""
     ms, cnt, name, ipl = ctypes.c_float(0), ctypes.c_int32(0), ctypes.c_char_p(), ctypes.c_int32(0)
     _check(_lib.fs_last_kernel_timing(ctypes.byref(ms), ctypes.byref(cnt), ctypes.byref(name), ctypes.byref(ipl)))
     return float(ms.value), int(cnt.value), name.value.decode(), int(ipl.value)

@@ -130,7 +130,7 @@ struct DeviceCache {
     hipStream_t cap_stream = nullptr;   // library-owned stream on which iteration blocks are captured
 };
 
-struct KernelTiming { float avg_ms = 0.0f; int samples = 0; const char *name = ""; int iters_per_launch = 1; };
+struct KernelTiming { float avg_ms = 0.0f; int samples = 0; const char *name = ""; int iters_sampled = 0; };
 thread_local KernelTiming g_timing;
 
 std::mutex g_mu;
@@ -297,7 +297,7 @@ struct Solve {
         DenseArgs a = dense(FUSED);
         a.P = L.P_fused;                       // sets of column sums the exchange buffer holds
         const int cu = cus < L.P_fused ? cus : L.P_fused;
-        return launch_persist(st, a, ctl(0), ws + L.o_persist, cu, nb, opt.wait_limit, tm);
+        return launch_persist(st, a, ctl(0), ws + L.o_persist, cu, nb, opt.wait_limit, opt.skip_final_err ? 0 : 1, tm);
     }
     // Eq. 9.  t0/t1 (optional) are stamped by the runtime with the start and stop of the dominant kernel
     // of the iteration: the row pass, the fused pass, or the point-cloud LSE pass of the f-update.
@@ -522,7 +522,7 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     hb->hint = 0;
     for (auto &h : hb->hints) h = 0;
     memset((void *)&hb->res, 0, sizeof(hb->res));
-    std::vector<int> sample_iter;
+    std::vector<int> sample_iter, sample_len;      // last iteration and number of iterations of a timed launch
     void *hb_dev = nullptr;
     FS_HIP(hipHostGetDevicePointer(&hb_dev, (void *)hb, 0));
     S.host_flag = (volatile int32_t *)hb_dev;
@@ -584,13 +584,14 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
         int nb = (blk == 0 && two_kinds && !force_fused) ? kFirstBlock : block;
         if (nb > S.pr.max_iter - it) nb = S.pr.max_iter - it;
         if (S.persist) {
-            // one launch per block; whole blocks are timed when asked for (begin to end of the dispatch)
-            const bool sample = tevery && nb == block && nsamples < 4096;
+            // one launch per block, timed when asked for (begin to end of the dispatch)
+            const bool sample = tevery && nsamples < 4096;
             if (sample) {
                 const fs_status ts = timing_pair(nsamples);
                 if (ts != FS_OK) return ts;
                 FS_HIP(S.enqueue_persist_block(nb, dc->timing[2 * nsamples], dc->timing[2 * nsamples + 1]));
                 sample_iter.push_back(it + nb - 1);
+                sample_len.push_back(nb);
                 ++nsamples;
             } else {
                 FS_HIP(S.enqueue_persist_block(nb));
@@ -621,7 +622,8 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
         block_end[blk & 3] = it;
         ++blk;
     }
-    if (!S.opt.skip_final_err && !hb->flag) FS_HIP(S.enqueue_trailing());
+    // (the persistent pass evaluates err of the last iterate itself, in the launch that reaches max_iter)
+    if (!S.opt.skip_final_err && !hb->flag && !(S.persist && S.pr.max_iter > 0)) FS_HIP(S.enqueue_trailing());
     FS_HIP(launch_finalize(S.st, S.pots, S.state, f, g, S.opt.f64_out, S.opt.g64_out, nullptr,
                            (char *)hb_dev + offsetof(HostBlock, res)));
     FS_HIP(hipStreamSynchronize(S.st));
@@ -640,18 +642,19 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     if (nsamples > 0) {
         // only launches that did work count: those of iterations the solve actually performed
         double tot = 0.0;
-        int used = 0;
+        int used = 0, covered = 0;
         for (int q = 0; q < nsamples; ++q) {
             if (sample_iter[q] >= hb->res.iters) break;
             float ms = 0.0f;
             FS_HIP(hipEventElapsedTime(&ms, dc->timing[2 * q], dc->timing[2 * q + 1]));
             tot += ms;
             ++used;
+            covered += S.persist ? sample_len[q] : 1;
         }
         g_timing.avg_ms = used ? (float)(tot / used) : 0.0f;
         g_timing.samples = used;
         g_timing.name = S.dominant_kernel();
-        g_timing.iters_per_launch = S.persist ? block : 1;
+        g_timing.iters_sampled = covered;
     }
     if (result_host) *result_host = hb->res;
     return hb->res.iters;
@@ -1094,12 +1097,12 @@ int fs_kernel_choice(int n, int m, int d, const fs_options *opts, int blocking, 
     return (km == 2 || (km == 0 && fused_ok)) ? FS_KERNEL_FUSED : FS_KERNEL_STREAM;
 }
 
-fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name, int32_t *iters_per_launch) {
+fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name, int32_t *iters_sampled) {
     if (g_timing.samples <= 0) { set_err("no timed solve has run on this thread"); return FS_ERR_INVALID_ARG; }
     if (avg_ms) *avg_ms = g_timing.avg_ms;
     if (samples) *samples = g_timing.samples;
     if (kernel_name) *kernel_name = g_timing.name;
-    if (iters_per_launch) *iters_per_launch = g_timing.iters_per_launch;
+    if (iters_sampled) *iters_sampled = g_timing.iters_sampled;
     return FS_OK;
 }
 

@@ -250,6 +250,8 @@ struct PersistArgs {
     double *wgpart;                              // [workgroups]: error terms of each workgroup's rows
     int32_t nb;                                  // iterations this launch runs at most
     int32_t spin_limit;                          // polls before a grid-wide wait is abandoned
+    int32_t final_err;                           // 1: a launch that reaches max_iter without a stop goes on to evaluate
+                                                 //    err of the last iterate (one more row phase over C) and closes the solve
 #ifdef FS_PERSIST_TRACE
     long long *trace;                            // debug builds: [workgroups][8] time stamps of one iteration
 #endif
@@ -259,7 +261,7 @@ int dense_persist_grid(int n, int m, int cus);   // workgroups of the launch on 
 size_t persist_scratch_bytes();
 hipError_t launch_persist_reset(hipStream_t st, void *scratch);          // once per solve, before the first block
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
-                          int spin_limit, const Stamp &tm = Stamp());
+                          int spin_limit, int final_err, const Stamp &tm = Stamp());
 
 bool grid_supported(int n, int m, int wmax, bool points);   // wmax: workgroups that can be resident at once (compute units)
 size_t grid_scratch_bytes();

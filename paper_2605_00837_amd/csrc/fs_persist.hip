@@ -150,6 +150,8 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
     int k;
     if (!launch_active(c, k)) return;          // nothing is in flight yet
     const int k_end = min(k + X.nb, c.max_iter);
+    // the launch that reaches max_iter goes on with one more row phase: it yields err of the last iterate
+    const bool with_trailing = X.final_err != 0 && k_end == c.max_iter;
 
     if (!FULLW) {
 #pragma unroll
@@ -244,17 +246,6 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
     while ((1 << lgSwp) < Sw) ++lgSwp;
     const int Swp = 1 << lgSwp, lgQN = lgSwp - 2, QN = 1 << lgQN;    // QN 16-byte chunks per source set
     float *xchg = reinterpret_cast<float *>(A.colpart);
-    // where this lane's groups of 4 column sums go: strip col / Sw, this workgroup's set, col mod Sw
-    int pub_off[Q];
-#pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        const int col = (q * T + tid) * 4;
-        const int dest = col / Sw;
-        pub_off[q] = ((((dest * W + w) << lgSwp) + (col - dest * Sw))) * 4;       // bytes
-    }
-    const __amdgpu_buffer_rsrc_t rsX = __builtin_amdgcn_make_buffer_rsrc((void *)xchg, 0, ((W * W) << lgSwp) * 4, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsMine = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(xchg + ((size_t)(w * W) << lgSwp)), 0, (W << lgSwp) * 4, 0x00020000);
     // the column whose total this thread finishes in the merge
     const int own_col = strip0 + tid;
     const bool own_ok = tid < Sw && own_col < strip1;
@@ -269,6 +260,7 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
     for (;;) {
         const int cur = k & 1, nxt = cur ^ 1;
         const bool rev = cur != 0;
+        const bool trailing = k == c.max_iter;       // row phase only: the error of the last iterate
         float cS[Q][4];                              // column sums of the plan entries of this workgroup's rows
 #pragma unroll
         for (int q = 0; q < Q; ++q)
@@ -389,7 +381,7 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
                 issue(panel_row(t + 2, rev), buf, cur, wave);
                 asm volatile("" ::: "memory");
             }
-            // ---- column phase with the new f
+            // ---- column phase with the new f (the trailing round does it too: its sums are simply not published)
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 float alpha = bcast_f32(alpha_lane, r * NW);
@@ -404,12 +396,19 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
         FS_TRACE(1);
         // ---- publish: column sums of this workgroup's rows (16-byte stores), and the error terms of its rows
         {
+            // where a group of 4 column sums goes: strip col / Sw, this workgroup's set, column col mod Sw
+            const __amdgpu_buffer_rsrc_t rsX =
+                __builtin_amdgcn_make_buffer_rsrc((void *)xchg, 0, ((W * W) << lgSwp) * 4, 0x00020000);
+            if (!trailing)
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
                 if (colok(q)) {
+                    const int col = (q * T + tid) * 4;
+                    const int dest = col / Sw;
                     const v4u pk = {__float_as_uint(cS[q][0]), __float_as_uint(cS[q][1]), __float_as_uint(cS[q][2]),
                                     __float_as_uint(cS[q][3])};
-                    __builtin_amdgcn_raw_buffer_store_b128(pk, rsX, pub_off[q], 0, kAgent);
+                    __builtin_amdgcn_raw_buffer_store_b128(pk, rsX, ((((dest * W + w) << lgSwp) + (col - dest * Sw))) * 4, 0,
+                                                           kAgent);
                 }
             }
             if (wave == 0) {
@@ -426,7 +425,7 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));     // this wave's stores have been acknowledged
         lds_only_barrier();                            // ... and so have every wave's (the new F of this workgroup's rows too)
         FS_TRACE(2);
-        const bool more = k + 1 < k_end;
+        const bool more = k + 1 < k_end || (k + 1 == k_end && with_trailing);
         ++gen;
         if (wave == 0) {
             const unsigned long long old = grid_arrive(X.sync);
@@ -454,7 +453,9 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
             // column group c % QN; thread t takes the chunks t, t + 1024, ..., i.e. always the same column group.
             // Four loads are in flight at a time; chunks past the end of the block read as zero.
             double acc[4] = {0.0, 0.0, 0.0, 0.0};
-            const int nchunks = W << lgQN;
+            const int nchunks = trailing ? 0 : W << lgQN;
+            const __amdgpu_buffer_rsrc_t rsMine = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(xchg + ((size_t)(w * W) << lgSwp)), 0, (W << lgSwp) * 4, 0x00020000);
             for (int ch = tid; ch < nchunks; ch += 4 * T) {
                 v4u x[4];
 #pragma unroll
@@ -493,7 +494,7 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
             }
             lds_only_barrier();
             FS_TRACE(5);
-            if (own_ok) {
+            if (own_ok && !trailing) {
                 double tot = 0.0;
 #pragma unroll
                 for (int w2 = 0; w2 < NW; ++w2) tot += sPart[(w2 << lgSwp) + tid];
@@ -532,6 +533,15 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
             if (tid == 0) sNsus = 0;                   // everyone has read it (a barrier lies behind every read)
         }
         const double err = sErrTot;
+        if (trailing) {
+            // nothing left to run: err of the last iterate closes the solve (potentials: F[cur], G[cur])
+            if (w == 0 && tid == 0) {
+                Ctl ct = c;
+                ct.phase = 1;
+                advance_state(ct, k, err, 0.0);
+            }
+            break;
+        }
         if (c.tol > 0.0 && k >= 1 && (k % c.check_every == 0) && err < c.tol) {
             // stop at k (Alg. 1): F[cur], G[cur] still hold iterate k; what the merge wrote is the other buffer
             if (w == 0 && tid == 0) advance_state(c, k, err, 0.0);
@@ -589,7 +599,7 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
         }
         FS_TRACE(7);
         ++k;
-        if (k >= k_end) break;
+        if (k >= k_end && !(k == k_end && with_trailing)) break;
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));         // no prefetch may land after the workgroup has given up its LDS
     if (!alive && tid == 0) {
@@ -647,7 +657,7 @@ hipError_t launch_persist_reset(hipStream_t st, void *scratch) {
 }
 
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
-                          int spin_limit, const Stamp &tm) {
+                          int spin_limit, int final_err, const Stamp &tm) {
     PShape s;
     if (!scratch || a.c_dtype != 0 || !persist_shape(a.p.m, &s) || nb < 1) return hipErrorInvalidValue;
     const int g = dense_persist_grid(a.p.n, a.p.m, cus);
@@ -664,6 +674,7 @@ hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void
     x.wgpart = reinterpret_cast<double *>(x.sync + 1);
     x.nb = nb;
     x.spin_limit = spin_limit > 0 ? spin_limit : (1 << 21);
+    x.final_err = final_err;
 #ifdef FS_PERSIST_TRACE
     x.trace = nullptr;
     if (const char *tp = getenv("FS_TRACE_PTR")) x.trace = reinterpret_cast<long long *>(strtoull(tp, nullptr, 0));
