@@ -23,7 +23,9 @@ def _lib(long_double: bool = False):
     key = bool(long_double)
     if key not in _libs:
         _build.build()
-        lib = ctypes.CDLL(_build.LIB_LD if key else _build.LIB)
+        # FS_ORACLE_LIB: another build of the same source in place of the ordinary one (the sanitizer leg)
+        override = os.environ.get("FS_ORACLE_LIB") if not key else None
+        lib = ctypes.CDLL(override or (_build.LIB_LD if key else _build.LIB))
         real = ctypes.c_longdouble if key else ctypes.c_double
         lib.fso_marginal_err.restype = real
         lib.fso_solve.restype = ctypes.c_int

@@ -62,5 +62,38 @@ def build(force: bool = True, verbose: bool = False, extra=()):
     return LIB
 
 
+SAN_DIR = os.path.join(OBJDIR, "host_san")
+SAN_DRIVER = os.path.join(os.path.dirname(HERE), "tests", "host", "host_sanitize_check.cpp")
+SAN_EXE = os.path.join(SAN_DIR, "host_sanitize_check")
+# sanitizers on the HOST pass only (each -fsanitize= directly behind -Xarch_host); device code is built as always
+_HOST_SAN = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer"]
+
+
+def build_host_sanitized(force: bool = False) -> str:
+    """The library's sources with their host code under AddressSanitizer + UBSan, linked with the driver
+    tests/host/host_sanitize_check.cpp into one executable (CPU only: it never touches a device)."""
+    newest = max(_deps_mtime(), os.path.getmtime(SAN_DRIVER))
+    if not force and os.path.exists(SAN_EXE) and os.path.getmtime(SAN_EXE) >= newest:
+        return SAN_EXE
+    os.makedirs(SAN_DIR, exist_ok=True)
+    flags = ["-O1", "-g"] + [f for f in FLAGS if f != "-O3"] + _HOST_SAN
+    procs, objs = [], []
+    for src in sources() + [SAN_DRIVER]:
+        obj = os.path.join(SAN_DIR, os.path.basename(src) + ".o")
+        objs.append(obj)
+        procs.append((src, subprocess.Popen([HIPCC, *flags, "-x", "hip", "-c", src, "-o", obj],
+                                            stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for src, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            print(f"--- {src} FAILED\n{out}", file=sys.stderr)
+            raise RuntimeError("hipcc failed (host sanitizer build)")
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", *_HOST_SAN, *objs, "-o", SAN_EXE])
+    return SAN_EXE
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose="-v" in sys.argv))
+    if "--host-sanitize" in sys.argv:
+        print(build_host_sanitized(force=True))
