@@ -30,9 +30,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 FP64_VECTOR_PEAK_TFLOPS = 78.6
-# v_exp_f32 issues at a quarter of the full vector rate: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz / 4,
-# derived from the unit counts; the measured rate on this chip is 18.2e12 per second
-EXP_PEAK_PER_S = 256 * 4 * 16 * 2.4e9 / 4
+# v_exp_f32 takes 8 issue cycles per wave64 instruction (half the rate of a plain fp32 or fp64 instruction):
+# 256 compute units x 4 SIMDs x 64 lanes x 2.4 GHz / 8.  The point-cloud kernel's measured time fits this
+# figure together with 4 cycles for each of its other instructions to within 1 %.
+EXP_PEAK_PER_S = 256 * 4 * 64 * 2.4e9 / 8
 
 
 def _traffic_from_profiles(kernel, n, m):
@@ -106,10 +107,35 @@ def points_alu_peak(d):
     return pairs_per_s, flop_per_pair
 
 
-def _solve_timed(fs, torch, a, b, eps, steps, tol, warmup, time_kernels=True, **geo_kw):
+def _spin_up(torch, kind, ms, solve):
+    """Brings the device from idle to its sustained clocks before anything is timed.  An idle MI355X runs the
+    first milliseconds of a compute-heavy kernel slower: the same 100-iteration c2 solve takes 51.3 us per
+    iteration after 0.5 s of idle, 49.5 after 100 - 400 ms of plain copies (memory traffic alone does not raise
+    the shader clock), 47.6 right after 25 ms or more of the solver's own work, and 50.6 again after 20 ms of
+    idle.  kind = "solver": untimed solves of the same problem for `ms` milliseconds; "copies": device-to-device
+    copies; "none".  Not part of any timed region, and separate from the W warm-up steps, which still run."""
+    if ms <= 0 or kind == "none":
+        return
+    t0 = time.perf_counter()
+    if kind == "copies":
+        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        while (time.perf_counter() - t0) * 1e3 < ms:
+            for _ in range(8):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+        return
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        solve()
+        torch.cuda.synchronize()
+
+
+def _solve_timed(fs, torch, a, b, eps, steps, tol, warmup, time_kernels=True, spinup=("none", 0.0), **geo_kw):
     n, m = a.shape[0], b.shape[0]
     f = torch.empty(n, dtype=torch.float32, device="cuda")
     g = torch.empty(m, dtype=torch.float32, device="cuda")
+    _spin_up(torch, spinup[0], spinup[1],
+             lambda: fs.fs_sinkhorn_solve(a, b, eps, max(1, min(200, steps)), 0.0, f=f, g=g, **geo_kw))
     # warm-up: W untimed iterations (also sizes the library's cached workspace)
     fs.fs_sinkhorn_solve(a, b, eps, warmup, 0.0, f=f, g=g, **geo_kw)
     torch.cuda.synchronize()
@@ -157,7 +183,8 @@ def bench_dense(args, name):
     # make the library take the multi-kernel path instead): they are timed by the wall clock alone
     choice = fs.fs_kernel_choice(n, m, kernel_mode=args.kernel_mode, fused_variant=args.fused_variant)
     one_launch_kernel = choice in ("small", "coop", "grid")
-    r, dt = _solve_timed(fs, torch, a, b, eps, steps, tol, args.warmup, time_kernels=not one_launch_kernel, **kw)
+    r, dt = _solve_timed(fs, torch, a, b, eps, steps, tol, args.warmup, time_kernels=not one_launch_kernel,
+                         spinup=(args.spinup, args.spinup_ms), **kw)
     iters = r["iters"]
     kern_ms, launches, kern_name, covered = (0.0, 0, "k_" + choice, 0) if one_launch_kernel else fs.fs_last_kernel_timing()
 
@@ -173,7 +200,8 @@ def bench_dense(args, name):
         "ms_per_step": dt * 1e3 / max(iters, 1), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{label} fp32 C ({n * m * 4 / 2 ** 20:g} MiB), {desc}, max_iter={steps}",
-                   "kernel_path": kern_name, "potentials": "fp64 internal, fp32 out"},
+                   "kernel_path": kern_name, "potentials": "fp64 internal, fp32 out",
+                   "spinup": f"{args.spinup} {args.spinup_ms:g} ms"},
         "ms_to_stop": dt * 1e3, "converged": r["converged"], "marginal_err": r["marginal_err"],
     }
     if alg_bytes_launch is not None and launches > 0:
@@ -223,7 +251,7 @@ def bench_points(args, name):
     kw = dict(X=X, Y=Y)
     if tol > 0.0:
         kw["check_every"] = 10
-    r, dt = _solve_timed(fs, torch, a, b, w.eps, steps, tol, args.warmup, **kw)
+    r, dt = _solve_timed(fs, torch, a, b, w.eps, steps, tol, args.warmup, spinup=(args.spinup, args.spinup_ms), **kw)
     iters = r["iters"]
     kern_ms, launches, kern_name, covered = fs.fs_last_kernel_timing()
     peak_pairs, flop_per_pair = points_alu_peak(d)
@@ -235,7 +263,7 @@ def bench_points(args, name):
         "n_gpus": 1, "steps": iters, "warmup": args.warmup, "ms_per_step": dt * 1e3 / max(iters, 1),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{label}, {desc}, max_iter={steps}, cost recomputed per pair (never stored)",
-                   "kernel_path": kern_name},
+                   "kernel_path": kern_name, "spinup": f"{args.spinup} {args.spinup_ms:g} ms"},
         "iters_per_sec": iters / dt, "ms_to_stop": dt * 1e3, "converged": r["converged"], "marginal_err": r["marginal_err"],
         "roofline": {"bound": "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": None, "kernel": kern_name, "kernel_avg_us": kern_ms * 1e3, "kernel_launches_timed": launches,
@@ -264,12 +292,67 @@ def calibrate_copy(mib=256, reps=5):
     print(json.dumps({"calibrate_copy_mib": mib, "copies": reps}))
 
 
+def bench_after_loop(args):
+    """The entry points that follow a solve (Eq. 5 plan, cost of Alg. 1's last step, one-pass diagnostics,
+    barycentric mapping of Sec. 5.6), timed end to end on the workload's inputs after a short solve:
+    `reps` back-to-back calls between two synchronisations, all launches of a call included.  Prints one JSON
+    object (not the headline line)."""
+    import torch
+    from paper_2605_00837_amd import binding as fs, workloads as W
+
+    torch.cuda.set_device(0)
+    name = args.workload
+    if name in ("c4", "c5p"):
+        w = W.c4_sphere_points(args.n if args.n != 8192 else 65536) if name == "c4" else W.c5_colour(16384, args.m5)
+        geo = dict(X=torch.from_numpy(w.X).cuda(), Y=torch.from_numpy(w.Y).cuda())
+        unit_bytes = None
+    else:
+        w = {"c1": W.c1_small_dense, "c2": lambda: W.c2_dense_gauss(args.n), "c3": W.c3_small_eps}.get(
+            name, lambda: W.c5_colour(16384, args.m5, dense=True))()
+        geo = dict(C=torch.from_numpy(w.C).cuda())
+        unit_bytes = w.n * w.m * 4
+    eps = w.eps_list[args.eps_index] if name == "c3" else w.eps
+    a, b = torch.from_numpy(w.a).cuda(), torch.from_numpy(w.b).cuda()
+    _spin_up(torch, "copies", args.spinup_ms, None)
+    r = fs.fs_sinkhorn_solve(a, b, eps, 50, 0.0, **geo)
+    f, g = r["f"], r["g"]
+    Z = torch.rand(w.m, 3, device="cuda")
+    calls = {"fs_cost": lambda: fs.fs_cost(a, b, eps, f, g, **geo),
+             "fs_diagnostics": lambda: fs.fs_diagnostics(a, b, eps, f, g, **geo),
+             "fs_barycentric_dz3": lambda: fs.fs_barycentric(a, b, eps, f, g, Z, **geo)}
+    if unit_bytes is not None and w.m % 4 == 0:
+        P = torch.empty(w.n, w.m, device="cuda")
+        calls["fs_plan"] = lambda: fs.fs_plan(a, b, eps, f, g, P=P, **geo)
+    reps = 20 if unit_bytes is not None else 5
+    out = {"after_loop": name, "n": w.n, "m": w.m, "reps": reps, "us_per_call": {}}
+    for key, fn in calls.items():
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) / reps * 1e6
+        out["us_per_call"][key] = us
+        if unit_bytes is not None:
+            nbytes = unit_bytes * (2 if key == "fs_plan" else 1)
+            out.setdefault("frac_of_hbm_peak", {})[key] = nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS
+        else:
+            # in units of one LSE pass over all point pairs at that kernel's issue bound
+            pairs_per_s, _ = points_alu_peak(w.X.shape[1])
+            out.setdefault("lse_passes_equivalent", {})[key] = us * 1e-6 * pairs_per_s / (w.n * w.m)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", choices=["c1", "c2", "c3", "c4", "c5p", "c5d"], default="c2")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="iterations of the timed solve (0: the workload's own count)")
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--spinup", choices=["solver", "copies", "none"], default="solver",
+                    help="what keeps the device busy before the warm-up solve (clock ramp from idle; untimed)")
+    ap.add_argument("--spinup-ms", type=float, default=100.0, help="for how long, in milliseconds")
     ap.add_argument("--n", type=int, default=8192, help="c2 / c4: problem size (default: the workload's own)")
     ap.add_argument("--m5", type=int, default=16384, choices=[16384, 12288], help="c5: number of target points")
     ap.add_argument("--eps-index", type=int, default=1, help="c3: which of eps = 1e-1, 1e-2, 1e-3, 1e-4")
@@ -277,12 +360,16 @@ def main():
     ap.add_argument("--fused-variant", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true")
+    ap.add_argument("--after-loop", action="store_true",
+                    help="time fs_cost / fs_diagnostics / fs_plan / fs_barycentric on the workload instead of the solve")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
     if args.calibrate_copy:
         calibrate_copy()
+    elif args.after_loop:
+        bench_after_loop(args)
     elif args.workload in ("c4", "c5p"):
         bench_points(args, args.workload)
     else:

@@ -128,6 +128,7 @@ struct DeviceCache {
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
     std::vector<hipEvent_t> timing;     // start/stop pairs for sampled kernel timing
     hipStream_t cap_stream = nullptr;   // library-owned stream on which iteration blocks are captured
+    unsigned int *tickets = nullptr;    // 64 arrival counters of the after-the-loop kernels; each returns to 0 after use
 };
 
 struct KernelTiming { float avg_ms = 0.0f; int samples = 0; const char *name = ""; int iters_sampled = 0; };
@@ -146,6 +147,8 @@ fs_status get_cache(size_t need_bytes, DeviceCache **out) {
         memset((void *)c.host, 0, sizeof(HostBlock));
         for (auto &e : c.ev) FS_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
         FS_HIP(hipStreamCreateWithFlags(&c.cap_stream, hipStreamNonBlocking));
+        FS_HIP(hipMalloc((void **)&c.tickets, 64 * sizeof(unsigned int)));
+        FS_HIP(hipMemset(c.tickets, 0, 64 * sizeof(unsigned int)));
     }
     if (c.ws_bytes < need_bytes) {
         if (c.ws) {
@@ -371,8 +374,8 @@ struct Solve {
         int warm = 0;
         if (opt.warm_start) warm = 3;
         hipError_t e = launch_init(st, pots, state, /*f_in*/ warm_f, warm_g, opt.f64_in && opt.g64_in ? opt.f64_in : nullptr,
-                                   opt.f64_in && opt.g64_in ? opt.g64_in : nullptr, warm);
-        if (e == hipSuccess && persist) e = launch_persist_reset(st, ws + L.o_persist);
+                                   opt.f64_in && opt.g64_in ? opt.g64_in : nullptr, warm,
+                                   persist ? ws + L.o_persist : nullptr);     // the pass's arrival counters start at 0
         if (e == hipSuccess && mode == 3) {
             e = launch_points_prep(st, pr.X, pr.n, pr.d, pots.s, (double *)(ws + L.o_Xp), (double *)(ws + L.o_Xs),
                                    (double *)(ws + L.o_cx));
@@ -584,8 +587,11 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
         int nb = (blk == 0 && two_kinds && !force_fused) ? kFirstBlock : block;
         if (nb > S.pr.max_iter - it) nb = S.pr.max_iter - it;
         if (S.persist) {
-            // one launch per block, timed when asked for (begin to end of the dispatch)
-            const bool sample = tevery && nsamples < 4096;
+            // one launch per block; when timing is asked for, about a dozen launches spread over the solve are
+            // stamped with their begin and end (a stamped dispatch costs about 10 us of queue time)
+            const int nblocks = (S.pr.max_iter + block - 1) / block;
+            const int stride = nblocks > 12 ? nblocks / 12 : 1;
+            const bool sample = tevery && (blk % stride) == 0 && nsamples < 4096;
             if (sample) {
                 const fs_status ts = timing_pair(nsamples);
                 if (ts != FS_OK) return ts;
@@ -955,7 +961,7 @@ fs_status plan_or_cost(const float *C, const float *X, const float *Y, int d, co
     A.n = n; A.m = m; A.d = dd;
     A.s = kLog2e / (double)eps;
     if (P) FS_HIP(launch_plan(st, A, P, (double *)dc->ws, need));
-    else FS_HIP(launch_diag(st, A, nullptr, nullptr, nullptr, dc->ws, dc->ws_bytes, cost_dev));   // one pass
+    else FS_HIP(launch_diag(st, A, nullptr, nullptr, nullptr, dc->ws, dc->ws_bytes, dc->tickets, cost_dev));   // one pass
     return FS_OK;
 }
 
@@ -978,7 +984,7 @@ fs_status diagnostics(const float *C, const float *X, const float *Y, int d, con
     A.C = C; A.X = X; A.Y = Y; A.a = a; A.b = b; A.f = f64 ? nullptr : f; A.g = g64 ? nullptr : g; A.f64 = f64; A.g64 = g64;
     A.n = n; A.m = m; A.d = dd;
     A.s = kLog2e / (double)eps;
-    FS_HIP(launch_diag(st, A, out8, row_marg, col_marg, dc->ws, dc->ws_bytes));
+    FS_HIP(launch_diag(st, A, out8, row_marg, col_marg, dc->ws, dc->ws_bytes, dc->tickets));
     return FS_OK;
 }
 
@@ -1058,6 +1064,7 @@ void fs_clear_cache(void) {
         for (auto &e : c.ev) if (e) (void)hipEventDestroy(e);
         for (auto &e : c.timing) (void)hipEventDestroy(e);
         if (c.cap_stream) (void)hipStreamDestroy(c.cap_stream);
+        if (c.tickets) (void)hipFree(c.tickets);
         (void)hipSetDevice(cur);
     }
     g_cache.clear();

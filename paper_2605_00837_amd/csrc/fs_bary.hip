@@ -47,6 +47,10 @@ BaryLayout bary_layout(int n, int m, int d) {
         L.rpp = rpp;
         L.P = (n + rpp - 1) / rpp;
         L.nparts = L.nstrips;
+        if (m % 4 == 0) {                    // the matrix-core kernel (it also needs C 16-byte aligned): slices of 1024 columns
+            const int slices = (m + 1023) / 1024;
+            if (slices > L.nparts) L.nparts = slices;
+        }
     } else {
         if (d <= 4) points_plan_after(n, m, 2048, 64, &L.JS, &L.cps, &L.ib);
         else points_plan_tiles(n, m, d, &L.JS, &L.cps);
@@ -138,6 +142,100 @@ __global__ __launch_bounds__(kBT) void k_bary_dense(BaryDense A) {
             }
         }
         __syncthreads();
+    }
+}
+
+// Dense, m a multiple of 4 and C 16-byte aligned: the sums over j run on the matrix cores.  The five sums of a row
+// (four numerators and the denominator) are the row of the product P Z' with Z' = [Z, 1]: a wave forms a 16 x 16
+// patch of plan entries at a time, lane l holding row l mod 16 and the 4 columns of group l / 16 (one 16-byte load),
+// and four v_mfma_f32_16x16x4_f32 add the patch's contribution to a 16 x 16 accumulator whose columns 0..4 are used:
+// for element e of the load, operand A is P[row l mod 16][column 4 (l / 16) + e] and operand B is
+// Z'[column 4 (l / 16) + e][l mod 16].  There is no cross-lane reduction and no barrier in the loop (the per-row
+// wave reductions of the kernel above cost more than its arithmetic).  A workgroup of 8 waves owns a slice of
+// 1024 columns, whose c_j and Z' it stages in LDS once, and 128 rows (16 per wave); partial sums per
+// (slice, row) go to the finishing kernel as before.
+constexpr int kMMSlice = 1024;          // columns per workgroup
+constexpr int kMMWaves = 8;             // waves per workgroup, 16 rows each per round
+constexpr int kMMRounds = 1;            // rounds per workgroup
+
+typedef float float4_v __attribute__((ext_vector_type(4)));
+typedef double double2_a __attribute__((ext_vector_type(2)));
+
+__global__ __launch_bounds__(kMMWaves * 64) void k_bary_dense_mm(BaryDense A) {
+    __shared__ __align__(16) double sCj[kMMSlice];
+    __shared__ __align__(16) float sZ[kZ + 2][kMMSlice];      // rows 0..3: Z (0 beyond dz), 4: ones, 5: zeros
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int li = lane & 15, lk = lane >> 4;
+    const int col0 = blockIdx.x * kMMSlice;
+    for (int c = tid; c < kMMSlice; c += kMMWaves * 64) {
+        const int j = col0 + c;
+        const bool ok = j < A.m;
+        sCj[c] = ok ? A.cj[j] : -__builtin_huge_val();
+#pragma unroll
+        for (int t = 0; t < kZ; ++t) sZ[t][c] = (ok && t < A.dz) ? A.Z[(size_t)j * A.dz + t] : 0.0f;
+        sZ[kZ][c] = ok ? 1.0f : 0.0f;
+        sZ[kZ + 1][c] = 0.0f;
+    }
+    __syncthreads();
+    const float *zrow = sZ[li < kZ + 1 ? li : kZ + 1];
+    const int nstep = (min(kMMSlice, A.m - col0) + 63) / 64;      // steps of 64 columns
+    for (int rd = 0; rd < kMMRounds; ++rd) {
+        const int r0 = ((blockIdx.y * kMMRounds + rd) * kMMWaves + wave) * 16;
+        if (r0 >= A.n) break;                                  // uniform over the wave
+        const int my_row = r0 + li;
+        const bool rok = my_row < A.n;
+        const double rv = rok ? A.ri[my_row] : -__builtin_huge_val();
+        const float *crow = A.C + (size_t)(rok ? my_row : A.n - 1) * A.m;
+        float4_v acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        // Four column groups (64 columns) per step; the loads of the next step are in flight while this one is
+        // worked on.  Groups past the slice's last column read column 0 instead: their c_j is -inf in LDS.
+        auto load4 = [&](float4_v (&c4)[4], int st) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int col = col0 + (st * 4 + u) * 16 + 4 * lk;
+                if (col >= A.m) col = 0;
+                c4[u] = *reinterpret_cast<const float4_v *>(crow + col);
+            }
+        };
+        auto work4 = [&](const float4_v (&c4)[4], int st, double rv) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = (st * 4 + u) * 16 + 4 * lk;
+                const double2_a cja = *reinterpret_cast<const double2_a *>(&sCj[c]);
+                const double2_a cjb = *reinterpret_cast<const double2_a *>(&sCj[c + 2]);
+                const float4_v zb = *reinterpret_cast<const float4_v *>(&zrow[c]);
+                const double cj[4] = {cja.x, cja.y, cjb.x, cjb.y};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // an exponent of -inf or NaN (zero weights, potentials that are not finite) gives a plan entry of 0
+                    const float arg = fmaxf((float)fma(-A.s, (double)c4[u][e], rv + cj[e]), -200.0f);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(fast_exp2(arg), zb[e], acc, 0, 0, 0);
+                }
+            }
+        };
+        // (Straight-line code: a step past the end loads the last step again and works on it with a row term of
+        // -inf, which adds nothing; so the number of loads in flight at every wait is known at compile time.)
+        // Every wave starts its sweep at a different step (and wraps round): waves that run side by side then read
+        // different 256-byte blocks of their rows, which all lie a multiple of the row pitch apart.
+        const int rot = (wave * 2 + blockIdx.y * 5 + blockIdx.x * 3) % nstep;
+        auto at = [&](int st) { const int q = st + rot; return q >= nstep ? q - nstep : q; };
+        float4_v ca[4], cb[4];
+        load4(ca, at(0));
+        for (int st = 0; st < nstep; st += 2) {
+            const bool second = st + 1 < nstep;
+            load4(cb, at(second ? st + 1 : st));
+            work4(ca, at(st), rv);
+            load4(ca, at(min(st + 2, nstep - 1)));
+            work4(cb, at(second ? st + 1 : st), second ? rv : -__builtin_huge_val());
+        }
+        // accumulator register q of lane l: row 4 (l / 16) + q, column l mod 16
+        if (li <= kZ) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int row = r0 + 4 * lk + q;
+                if (row < A.n) A.part[((size_t)blockIdx.x * A.n + row) * (kZ + 1) + li] = acc[q];
+            }
+        }
     }
 }
 
@@ -312,12 +410,20 @@ hipError_t launch_bary(hipStream_t st, const PlanArgs &a, const float *Z, int dz
     hipError_t e = launch_plan_prep_all(st, a, ri, cj, xp, xs, xq, yp, ys, yq);
     if (e != hipSuccess) return e;
     float *part = (float *)(ws + L.o_part);
+    int nparts = L.nparts;
+    if (a.d == 0) nparts = L.nstrips;
     if (a.d == 0) {
         BaryDense D{};
         D.C = a.C; D.ri = ri; D.cj = cj; D.Z = Z; D.n = a.n; D.m = a.m; D.dz = dz; D.s = a.s;
         D.part = part; D.rpp = L.rpp;
         const dim3 grid(L.nstrips, L.P);
-        if (L.vec == 4) hipLaunchKernelGGL(k_bary_dense<4>, grid, dim3(kBT), 0, st, D);
+        if (a.m % 4 == 0 && (reinterpret_cast<uintptr_t>(a.C) & 15) == 0) {
+            nparts = (a.m + kMMSlice - 1) / kMMSlice;
+            const int rows_per_wg = kMMRounds * kMMWaves * 16;
+            const dim3 gmm(nparts, (a.n + rows_per_wg - 1) / rows_per_wg);
+            hipLaunchKernelGGL(k_bary_dense_mm, gmm, dim3(kMMWaves * 64), 0, st, D);
+        }
+        else if (L.vec == 4) hipLaunchKernelGGL(k_bary_dense<4>, grid, dim3(kBT), 0, st, D);
         else hipLaunchKernelGGL(k_bary_dense<1>, grid, dim3(kBT), 0, st, D);
     } else {
         BaryPoints X{};
@@ -348,7 +454,7 @@ hipError_t launch_bary(hipStream_t st, const PlanArgs &a, const float *Z, int dz
             }
         }
     }
-    hipLaunchKernelGGL(k_bary_finish, dim3((a.n + 255) / 256), dim3(256), 0, st, part, L.nparts, a.n, dz, T);
+    hipLaunchKernelGGL(k_bary_finish, dim3((a.n + 255) / 256), dim3(256), 0, st, part, nparts, a.n, dz, T);
     return hipGetLastError();
 }
 

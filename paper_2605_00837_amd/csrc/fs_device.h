@@ -38,6 +38,7 @@ struct alignas(256) State {
     // Returns to 0 after every use.
     unsigned long long err_acc;
     uint32_t big_acc[2];  // columns that moved by more than the FAST-mode threshold, by parity of the iteration
+    uint32_t fin_ticket;  // workgroups of the finalize kernel that are through (the last one writes the result record)
 };
 
 constexpr int kHintRing = 256;        // slots of the host-visible ring of pace hints (index: iteration mod ring)

@@ -5,9 +5,9 @@
 //   P_ij = 2^(e_ij),  e_ij = ri_i + cj_j - s C_ij,  ri_i = s f_i + log2 a_i,  cj_j = s g_j + log2 b_j.
 //
 // The exponent is formed in fp64 and rounded to fp32 for v_exp_f32; sums over at most a few dozen
-// entries are kept in fp32, everything longer in fp64.  log(P_ij/(a_i b_j)) = (e_ij - log2 a_i -
-// log2 b_j) ln 2, so  sum P log(P/(a b)) = ln 2 (sum P e - sum_i r_i log2 a_i - sum_j c_j log2 b_j)
-// and only sum P e has to be collected per entry.
+// entries are kept in fp32, everything longer in fp64.  The entropy term needs no sum over the entries:
+// log(P_ij/(a_i b_j)) = (f_i + g_j - C_ij)/eps by Eq. 5, so  sum P log(P/(a b)) = (<r, f> + <c, g> - <C, P>)/eps
+// with the marginals r, c of P, whatever f and g are.
 //
 // Dense: a workgroup of 1024 lanes owns a strip of 1024*VEC columns and a panel of rows; lanes keep
 // their column sums, row sums go wave -> LDS -> one value per (strip, row).  Points: the layout of
@@ -77,9 +77,10 @@ DiagLayout diag_layout(int n, int m, int d) {
             points_plan_tiles(m, n, d, &L.JSy, &L.cpsy);
         }
         L.o_rowpart = take(sizeof(double) * (size_t)L.JSx * n);      // row sums per column slice
-        L.o_colpart = take(sizeof(double) * (size_t)L.JSy * m);      // column sums per row slice
         const int rows_per_wg = d <= 4 ? kPT2 * L.ibx : kTileRows;
         const int gx = (n + rows_per_wg - 1) / rows_per_wg;
+        // column sums: per block of rows (fp32, d <= 4: one pass does both sides) or per row slice of the second pass
+        L.o_colpart = take(d <= 4 ? sizeof(float) * (size_t)gx * m : sizeof(double) * (size_t)L.JSy * m);
         L.nscal = gx * L.JSx;
         L.o_scal = take(sizeof(double) * 2 * L.nscal);
         L.o_xp = take(sizeof(double) * (size_t)n * d);
@@ -142,6 +143,28 @@ __device__ __forceinline__ double block_sum(double v, double *lds) {
     return lds[0];
 }
 
+// What one workgroup hands to the workgroup that finishes the call (whichever arrives last): stores and loads at
+// agent scope, which pass the per-die caches, and an arrival counter that returns to 0 after use.
+__device__ __forceinline__ void pub_f64(double *p, double v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double get_f64(const double *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Called by every thread of a workgroup after thread 0 has published the workgroup's record: true (for all
+// threads) in the workgroup that arrives last of `total`.
+__device__ __forceinline__ bool last_to_arrive(unsigned int *ticket, unsigned int total, int *lds_flag) {
+    if (threadIdx.x == 0) {
+        __builtin_amdgcn_s_waitcnt(0);                 // this workgroup's record has been acknowledged
+        const unsigned int t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = t == total - 1u;
+        if (last) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *lds_flag = last;
+    }
+    __syncthreads();
+    return *lds_flag != 0;
+}
+
 // ---------------------------------------------------------------- dense
 struct DenseDiag {
     const float *C;
@@ -152,12 +175,18 @@ struct DenseDiag {
     float *colpart;      // [P][m]
     double *scal;        // [nstrips * P][2]: sum P (s C), sum P e
     int32_t rpp;
+    unsigned int *ticket;   // cost only: arrival counter (0 before and after the launch)
+    double *cost_out;       // cost only: <C, P>, written by the workgroup that arrives last
 };
 
-template <int VEC>
+// COST_ONLY: only sum P C is wanted (fs_cost): no marginals, so no row reductions and no exchange in the loop,
+// and the workgroup that arrives last adds the per-workgroup sums in index order and writes the cost: the whole
+// call is this one launch after the preparation.
+template <int VEC, bool COST_ONLY>
 __global__ __launch_bounds__(kDT) void k_diag_dense(DenseDiag A) {
-    __shared__ float sRow[kDRows][kDT / 64];
+    __shared__ float sRow[COST_ONLY ? 1 : kDRows][kDT / 64];
     __shared__ double lds[kDT];
+    __shared__ int sLast;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int strip = blockIdx.x, panel = blockIdx.y;
     const int j0 = (strip * kDT + tid) * VEC;
@@ -171,11 +200,11 @@ __global__ __launch_bounds__(kDT) void k_diag_dense(DenseDiag A) {
     float cs[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) cs[e] = 0.0f;
-    double cost_acc = 0.0, ent_acc = 0.0;
+    double cost_acc = 0.0;
     const int i0 = panel * A.rpp;
     const int i1 = min(A.n, i0 + A.rpp);
     for (int ib = i0; ib < i1; ib += kDRows) {
-        float cf = 0.0f, ef = 0.0f;            // this chunk's share of sum P (s C) and sum P e
+        float cf = 0.0f;                       // this chunk's share of sum P C
 #pragma unroll 4
         for (int r = 0; r < kDRows; ++r) {
             const int i = ib + r;
@@ -196,40 +225,52 @@ __global__ __launch_bounds__(kDT) void k_diag_dense(DenseDiag A) {
                 const double rv = A.ri[i];
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
-                    const double sc = A.s * (double)cv[e];
-                    const double arg = (rv + cjv[e]) - sc;
-                    const float p = fast_exp2((float)arg);
-                    if (p > 0.0f) {                                  // also skips NaN
+                    // log2 of the plan entry; -inf (a zero weight) or NaN becomes -200, whose power of two is 0 in
+                    // fp32, so such an entry adds nothing anywhere
+                    const float argf = fmaxf((float)fma(-A.s, (double)cv[e], rv + cjv[e]), -200.0f);
+                    const float p = fast_exp2(argf);
+                    cf = fmaf(p, cv[e], cf);
+                    if constexpr (!COST_ONLY) {
                         rs += p;
                         cs[e] += p;
-                        cf = fmaf(p, (float)sc, cf);
-                        ef = fmaf(p, (float)arg, ef);
                     }
                 }
             }
-            rs = wave_sum_f32(rs);
-            if (lane == 0) sRow[r][wave] = rs;
+            if constexpr (!COST_ONLY) {
+                rs = wave_sum_f32(rs);
+                if (lane == 0) sRow[r][wave] = rs;
+            }
         }
         cost_acc += (double)cf;
-        ent_acc += (double)ef;
-        __syncthreads();
-        if (tid < kDRows && ib + tid < i1) {
-            double tot = 0.0;
+        if constexpr (!COST_ONLY) {
+            __syncthreads();
+            if (tid < kDRows && ib + tid < i1) {
+                double tot = 0.0;
 #pragma unroll
-            for (int w = 0; w < kDT / 64; ++w) tot += (double)sRow[tid][w];
-            A.rowpart[(size_t)strip * A.n + ib + tid] = tot;
+                for (int w = 0; w < kDT / 64; ++w) tot += (double)sRow[tid][w];
+                A.rowpart[(size_t)strip * A.n + ib + tid] = tot;
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
+    const size_t w = (size_t)panel * gridDim.x + strip;
+    const double c_tot = A.s * block_sum<kDT>(cost_acc, lds);        // sum P (s C), the unit the tail works in
+    if constexpr (COST_ONLY) {
+        const unsigned int total = gridDim.x * gridDim.y;
+        if (tid == 0) pub_f64(&A.scal[2 * w], c_tot);
+        if (!last_to_arrive(A.ticket, total, &sLast)) return;
+        double acc = 0.0;
+        for (unsigned int q = tid; q < total; q += kDT) acc += get_f64(&A.scal[2 * (size_t)q]);
+        const double tot = block_sum<kDT>(acc, lds);
+        if (tid == 0) A.cost_out[0] = tot / A.s;
+    } else {
 #pragma unroll
-    for (int e = 0; e < VEC; ++e)
-        if (jok[e]) A.colpart[(size_t)panel * A.m + j0 + e] = cs[e];
-    const double c_tot = block_sum<kDT>(cost_acc, lds);
-    const double e_tot = block_sum<kDT>(ent_acc, lds);
-    if (tid == 0) {
-        const size_t w = (size_t)panel * gridDim.x + strip;
-        A.scal[2 * w] = c_tot;
-        A.scal[2 * w + 1] = e_tot;
+        for (int e = 0; e < VEC; ++e)
+            if (jok[e]) A.colpart[(size_t)panel * A.m + j0 + e] = cs[e];
+        if (tid == 0) {
+            A.scal[2 * w] = c_tot;
+            A.scal[2 * w + 1] = 0.0;
+        }
     }
 }
 
@@ -243,14 +284,27 @@ struct PointsDiag {
     const double *collog;    // [nc]
     int32_t nr, nc;
     double *part;            // [JS][nr] row sums of this column slice
-    double *scal;            // [gridDim.x * JS][2] or null: sum P (s C), sum P e
+    double *scal;            // [gridDim.x * JS][2] or null: sum P (s C), (unused)
     int32_t cols_per_split;
+    float *colpart;          // d <= 4, everything in one pass: [gridDim.x][nc] column sums of each block of rows
+    unsigned int *ticket;    // d <= 4, cost only: arrival counter, and where the last workgroup writes <C, P>
+    double *cost_out;
+    double s;
 };
 
-template <int D, bool WITH_COST, int IB>
+// d <= 4, on the vector ALUs.  MODE 0: the cost alone (fs_cost).  MODE 1: everything in ONE pass over the
+// pairs: row sums are lane-local; the sum of a column over the rows of the workgroup takes 4 DPP additions
+// inside each 16-lane row per column and one LDS word per row of lanes, and the 16 words of a column are added
+// in a fixed order when the tile is done.  The entropy term needs no sum of its own (see the reduction below).
+// A zero weight enters the tile as -1e300 instead of -inf: the exponent still rounds to -inf in fp32 (the plan
+// entry is 0) while s C_ij = (s|x|^2 + cl_j) - (cl_j - s|y|^2 + 2 s x.y) stays finite, so no product 0 * inf can
+// arise and the loop needs no guards.
+template <int D, int MODE, int IB>
 __global__ __launch_bounds__(kPT2) void k_diag_points(PointsDiag A) {
     __shared__ __align__(16) double tile[kTile2][D + 2];     // [0] collog - colq, [1..D] 2s y, [D+1] collog
     __shared__ double lds[kPT2];
+    __shared__ float sCol[MODE == 1 ? 16 : 1][kTile2];
+    __shared__ int sLast;
     const int tid = threadIdx.x;
     double x[IB][D], rc[IB], rq[IB];
     int row[IB];
@@ -265,7 +319,7 @@ __global__ __launch_bounds__(kPT2) void k_diag_points(PointsDiag A) {
         rc[b] = ok ? A.rowlog[row[b]] - rq[b] : -__builtin_huge_val();
         rs[b] = 0.0;
     }
-    double cost_acc = 0.0, ent_acc = 0.0;
+    double cost_acc = 0.0;
     const int j0 = blockIdx.y * A.cols_per_split;
     const int j1 = min(A.nc, j0 + A.cols_per_split);
     for (int jt = j0; jt < j1; jt += kTile2) {
@@ -273,61 +327,84 @@ __global__ __launch_bounds__(kPT2) void k_diag_points(PointsDiag A) {
         {
             const int j = jt + tid;
             if (j < j1) {
-                const double lg = A.collog[j];
+                const double lg = fmax(A.collog[j], -1.0e300);
                 tile[tid][0] = lg - A.colq[j];
 #pragma unroll
                 for (int t = 0; t < D; ++t) tile[tid][1 + t] = A.cols2s[(size_t)j * D + t];
                 tile[tid][D + 1] = lg;
             } else {
-                tile[tid][0] = -__builtin_huge_val();
+                tile[tid][0] = -1.0e300;
 #pragma unroll
                 for (int t = 0; t < D; ++t) tile[tid][1 + t] = 0.0;
-                tile[tid][D + 1] = 0.0;
+                tile[tid][D + 1] = -1.0e300;
             }
         }
         __syncthreads();
-        float rf[IB], cf = 0.0f, ef = 0.0f;
+        float rf[IB], cf = 0.0f;
 #pragma unroll
         for (int b = 0; b < IB; ++b) rf[b] = 0.0f;
-        const int cnt = min(kTile2, (j1 - jt + 1) & ~1);       // staged columns (the tile is padded with -inf)
+        const int cnt = min(kTile2, (j1 - jt + 1) & ~1);       // staged columns (the tile is padded)
 #pragma unroll 2
         for (int jj = 0; jj < cnt; ++jj) {
             double w[D + 2];
 #pragma unroll
             for (int t = 0; t < D + 2; ++t) w[t] = tile[jj][t];
+            float colsum = 0.0f;
 #pragma unroll
             for (int b = 0; b < IB; ++b) {
                 double tq = w[0];                                                  // collog - colq + 2 s x.y
 #pragma unroll
                 for (int t = 0; t < D; ++t) tq = fma(x[b][t], w[1 + t], tq);
-                const double arg = tq + rc[b];
-                const float argf = (float)arg;
-                float p = fast_exp2(argf);
-                p = p > 0.0f ? p : 0.0f;                                           // drops NaN
-                rf[b] += p;
-                if (WITH_COST) {
-                    const double sc = (rq[b] + w[D + 1]) - tq;                     // s |x - y|^2, w[D+1] = collog
-                    cf = fmaf(p, fminf((float)sc, 1.0e30f), cf);                   // 0 * inf (or NaN) must stay 0:
-                    ef = fmaf(p, fmaxf(argf, -1.0e30f), ef);                       // zero-weight entries
+                const float argf = fmaxf((float)(tq + rc[b]), -200.0f);            // -inf, NaN: the entry is 0
+                const float p = fast_exp2(argf);
+                const double sc = (rq[b] + w[D + 1]) - tq;                         // s |x - y|^2, w[D+1] = collog
+                cf = fmaf(p, (float)sc, cf);
+                if (MODE == 1) {
+                    rf[b] += p;
+                    colsum += p;
                 }
+            }
+            if (MODE == 1) {
+                colsum += dpp_f32<0x128>(colsum);
+                colsum += dpp_f32<0x124>(colsum);
+                colsum += dpp_f32<0x122>(colsum);
+                colsum += dpp_f32<0x121>(colsum);
+                if ((tid & 15) == 0) sCol[tid >> 4][jj] = colsum;
             }
         }
 #pragma unroll
         for (int b = 0; b < IB; ++b) rs[b] += (double)rf[b];
         cost_acc += (double)cf;
-        ent_acc += (double)ef;
-    }
+        if (MODE == 1) {
+            __syncthreads();
+            if (tid < cnt && jt + tid < j1) {
+                double tot = 0.0;
 #pragma unroll
-    for (int b = 0; b < IB; ++b)
-        if (row[b] < A.nr) A.part[(size_t)blockIdx.y * A.nr + row[b]] = rs[b];
-    if (WITH_COST) {
-        const double c_tot = block_sum<kPT2>(cost_acc, lds);
-        const double e_tot = block_sum<kPT2>(ent_acc, lds);
-        if (tid == 0) {
-            const size_t w = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
-            A.scal[2 * w] = c_tot;
-            A.scal[2 * w + 1] = e_tot;
+                for (int q = 0; q < 16; ++q) tot += (double)sCol[q][tid];
+                A.colpart[(size_t)blockIdx.x * A.nc + jt + tid] = (float)tot;
+            }
         }
+    }
+    if (MODE == 1) {
+#pragma unroll
+        for (int b = 0; b < IB; ++b)
+            if (row[b] < A.nr) A.part[(size_t)blockIdx.y * A.nr + row[b]] = rs[b];
+    }
+    const double c_tot = block_sum<kPT2>(cost_acc, lds);
+    const size_t w = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+    if (MODE == 1) {
+        if (tid == 0) {
+            A.scal[2 * w] = c_tot;
+            A.scal[2 * w + 1] = 0.0;
+        }
+    } else {                                   // the workgroup that arrives last finishes the call
+        const unsigned int total = gridDim.x * gridDim.y;
+        if (tid == 0) pub_f64(&A.scal[2 * w], c_tot);
+        if (!last_to_arrive(A.ticket, total, &sLast)) return;
+        double acc = 0.0;
+        for (unsigned int q = tid; q < total; q += kPT2) acc += get_f64(&A.scal[2 * (size_t)q]);
+        const double tot = block_sum<kPT2>(acc, lds);
+        if (tid == 0) A.cost_out[0] = tot / A.s;
     }
 }
 
@@ -409,6 +486,57 @@ __global__ __launch_bounds__(256) void k_diag_points_mfma(PointsDiag A, int d) {
     }
 }
 
+// out[0] cost, [1] mass, [2] KL(P | a x b), [3] primal, [4] dual, [5] row-marginal L1 error,
+// [6] column-marginal L1 error, [7] 0.  Called by all 256 threads of one workgroup: per-thread shares in index
+// order, wave sums by DPP, then the 4 waves one after the other, so the order of the additions is fixed.
+__device__ __forceinline__ void diag_totals(const double *red, int nred, const double *scal, int nscal, double s,
+                                            double *out, double *cost_out, double *lds, bool agent_loads) {
+    double w9[9];
+    for (int q = 0; q < 7; ++q) {
+        double acc = 0.0;
+        for (int w = threadIdx.x; w < nred; w += 256)
+            acc += agent_loads ? get_f64(&red[(size_t)w * 8 + q]) : red[(size_t)w * 8 + q];
+        w9[q] = acc;
+    }
+    for (int q = 0; q < 2; ++q) {
+        double acc = 0.0;
+        for (int w = threadIdx.x; w < nscal; w += 256) acc += scal[(size_t)w * 2 + q];   // written by an earlier launch
+        w9[7 + q] = acc;
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int q = 0; q < 9; ++q) {
+        const double t = wave_sum_f64(w9[q]);
+        if (lane == 0) lds[wave * 9 + q] = t;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double v[7], sc[2];
+#pragma unroll
+        for (int q = 0; q < 9; ++q) {
+            const double t = (lds[q] + lds[9 + q]) + (lds[18 + q] + lds[27 + q]);
+            if (q < 7) v[q] = t;
+            else sc[q - 7] = t;
+        }
+        const double eps = 1.4426950408889634074 / s;
+        const double mass = v[0];
+        const double cost = sc[0] / s;
+        const double plogp = (v[5] + v[6] - cost) / eps;         // sum P log(P/(a b)) = (<r,f> + <c,g> - <C,P>)/eps
+        const double kl = plogp - mass + 1.0;
+        if (out) {
+            out[0] = cost;
+            out[1] = mass;
+            out[2] = kl;
+            out[3] = cost + eps * kl;
+            out[4] = v[3] + v[4] - eps * mass + eps;
+            out[5] = v[1];
+            out[6] = v[2];
+            out[7] = 0.0;
+        }
+        if (cost_out) cost_out[0] = cost;
+    }
+}
+
 // ---------------------------------------------------------------- reduction of the partials
 // Entry t = row t and column t: marginals, their L1 errors, <a,f>, <b,g>, and the sums
 // r_i log2 a_i, c_j log2 b_j.  One record of 8 doubles per workgroup.
@@ -419,12 +547,19 @@ struct ReduceArgs {
     int32_t colpart_is_float;
     double *row_marg, *col_marg;                  // optional outputs
     double *red;                                  // [gridDim.x][8]
+    // the tail: the workgroup that arrives last adds the records of all workgroups and the per-workgroup sums of
+    // the pass (scal) in index order and writes the results
+    const double *scal; int32_t nscal;
+    unsigned int *ticket;
+    double *out8, *cost_out;
 };
 
 // A workgroup of 256 threads finishes 64 rows and 64 columns: lane = entry, the 4 waves split the
 // partial sets (8 loads in flight each) and meet in LDS.
 __global__ __launch_bounds__(256) void k_diag_reduce(ReduceArgs A) {
     __shared__ double sR[4][64], sC[4][64];
+    __shared__ double lds9[4 * 9];
+    __shared__ int sLast;
     const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
     const int t = blockIdx.x * 64 + lane;
     double r = 0.0, c = 0.0;
@@ -466,7 +601,7 @@ __global__ __launch_bounds__(256) void k_diag_reduce(ReduceArgs A) {
     sR[grp][lane] = r;
     sC[grp][lane] = c;
     __syncthreads();
-    double v[7] = {0, 0, 0, 0, 0, 0, 0};          // mass, row err, col err, <a,f>, <b,g>, r.log2 a, c.log2 b
+    double v[7] = {0, 0, 0, 0, 0, 0, 0};          // mass, row err, col err, <a,f>, <b,g>, <r,f>, <c,g>
     if (grp == 0) {
         r = (sR[0][lane] + sR[1][lane]) + (sR[2][lane] + sR[3][lane]);
         c = (sC[0][lane] + sC[1][lane]) + (sC[2][lane] + sC[3][lane]);
@@ -475,77 +610,27 @@ __global__ __launch_bounds__(256) void k_diag_reduce(ReduceArgs A) {
             if (A.row_marg) A.row_marg[t] = r;
             v[0] = r;
             v[1] = fabs(r - (double)a);
-            if (a > 0.0f) {
-                const double f = A.P.f64 ? A.P.f64[t] : (double)A.P.f[t];
-                v[3] = (double)a * f;
-                v[5] = r * log2((double)a);
-            }
+            const double f = A.P.f64 ? A.P.f64[t] : (double)A.P.f[t];
+            if (a > 0.0f) v[3] = (double)a * f;
+            if (r > 0.0) v[5] = r * f;
         }
         if (t < A.P.m) {
             const float b = A.P.b[t];
             if (A.col_marg) A.col_marg[t] = c;
             v[2] = fabs(c - (double)b);
-            if (b > 0.0f) {
-                const double g = A.P.g64 ? A.P.g64[t] : (double)A.P.g[t];
-                v[4] = (double)b * g;
-                v[6] = c * log2((double)b);
-            }
+            const double g = A.P.g64 ? A.P.g64[t] : (double)A.P.g[t];
+            if (b > 0.0f) v[4] = (double)b * g;
+            if (c > 0.0) v[6] = c * g;
         }
 #pragma unroll
         for (int q = 0; q < 7; ++q) {
             const double tot = wave_sum_f64(v[q]);
-            if (lane == 0) A.red[(size_t)blockIdx.x * 8 + q] = tot;
+            if (lane == 0) pub_f64(&A.red[(size_t)blockIdx.x * 8 + q], tot);
         }
     }
-}
-
-// out[0] cost, [1] mass, [2] KL(P | a x b), [3] primal, [4] dual, [5] row-marginal L1 error,
-// [6] column-marginal L1 error, [7] 0.
-__global__ __launch_bounds__(256) void k_diag_final(const double *red, int nred, const double *scal, int nscal,
-                                                    double s, double *out, double *cost_out) {
-    __shared__ double lds[4 * 9];
-    // per-thread shares, wave sums by DPP, then the 4 waves one after the other: a fixed order
-    double w9[9];
-    for (int q = 0; q < 7; ++q) {
-        double acc = 0.0;
-        for (int w = threadIdx.x; w < nred; w += 256) acc += red[(size_t)w * 8 + q];
-        w9[q] = acc;
-    }
-    for (int q = 0; q < 2; ++q) {
-        double acc = 0.0;
-        for (int w = threadIdx.x; w < nscal; w += 256) acc += scal[(size_t)w * 2 + q];
-        w9[7 + q] = acc;
-    }
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int q = 0; q < 9; ++q) {
-        const double t = wave_sum_f64(w9[q]);
-        if (lane == 0) lds[wave * 9 + q] = t;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double v[7], sc[2];
-#pragma unroll
-        for (int q = 0; q < 9; ++q) {
-            const double t = (lds[q] + lds[9 + q]) + (lds[18 + q] + lds[27 + q]);
-            if (q < 7) v[q] = t;
-            else sc[q - 7] = t;
-        }
-        const double eps = 1.4426950408889634074 / s;
-        const double mass = v[0];
-        const double cost = sc[0] / s;
-        const double plogp = kLn2d * (sc[1] - v[5] - v[6]);      // sum P log(P/(a b))
-        const double kl = plogp - mass + 1.0;
-        out[0] = cost;
-        out[1] = mass;
-        out[2] = kl;
-        out[3] = cost + eps * kl;
-        out[4] = v[3] + v[4] - eps * mass + eps;
-        out[5] = v[1];
-        out[6] = v[2];
-        out[7] = 0.0;
-        if (cost_out) cost_out[0] = cost;
-    }
+    __syncthreads();                                  // (thread 0 is lane 0 of the wave that stored the record)
+    if (!last_to_arrive(A.ticket, gridDim.x, &sLast)) return;
+    diag_totals(A.red, (int)gridDim.x, A.scal, A.nscal, A.P.s, A.out8, A.cost_out, lds9, /*agent_loads=*/true);
 }
 
 // ---------------------------------------------------------------- small problems: everything in one workgroup
@@ -733,7 +818,8 @@ hipError_t launch_plan_prep_all(hipStream_t st, const PlanArgs &a, double *ri, d
 }
 
 hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *row_marg, double *col_marg,
-                       void *scratch, size_t scratch_bytes, double *cost_only_out) {
+                       void *scratch, size_t scratch_bytes, unsigned int *tickets, double *cost_only_out) {
+    if (!tickets) return hipErrorInvalidValue;
     if (a.n <= kOneMax && a.m <= kOneMax && a.d <= 4 &&
         (size_t)a.n * (size_t)a.m <= (size_t)(a.d > 0 ? kOnePairs : kOneEntries)) {
         OneArgs O{};
@@ -745,7 +831,6 @@ hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *
     const DiagLayout L = diag_layout(a.n, a.m, a.d);
     if (scratch_bytes < L.total) return hipErrorInvalidValue;
     unsigned char *ws = (unsigned char *)scratch;
-    if (!out8) out8 = (double *)(ws + L.o_out);
     const bool cost_only = cost_only_out != nullptr;
     double *ri = (double *)(ws + L.o_ri), *cj = (double *)(ws + L.o_cj);
     const int len = a.n > a.m ? a.n : a.m;
@@ -766,9 +851,15 @@ hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *
         D.rowpart = (double *)(ws + L.o_rowpart);
         D.colpart = (float *)(ws + L.o_colpart);
         D.scal = scal; D.rpp = L.rpp;
+        D.ticket = tickets; D.cost_out = cost_only_out;
         const dim3 grid(L.nstrips, L.P);
-        if (L.vec == 4) hipLaunchKernelGGL(k_diag_dense<4>, grid, dim3(kDT), 0, st, D);
-        else hipLaunchKernelGGL(k_diag_dense<1>, grid, dim3(kDT), 0, st, D);
+        if (cost_only) {                        // the pass finishes the call itself
+            if (L.vec == 4) hipLaunchKernelGGL((k_diag_dense<4, true>), grid, dim3(kDT), 0, st, D);
+            else hipLaunchKernelGGL((k_diag_dense<1, true>), grid, dim3(kDT), 0, st, D);
+            return hipGetLastError();
+        }
+        if (L.vec == 4) hipLaunchKernelGGL((k_diag_dense<4, false>), grid, dim3(kDT), 0, st, D);
+        else hipLaunchKernelGGL((k_diag_dense<1, false>), grid, dim3(kDT), 0, st, D);
         R.rowpart = D.rowpart; R.nrowpart = L.nstrips;
         R.colpart = D.colpart; R.ncolpart = L.P; R.colpart_is_float = 1;
     } else {
@@ -779,15 +870,19 @@ hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *
         Y.rows = yp; Y.rowq = yq; Y.rowlog = cj; Y.cols2s = xs; Y.colq = xq; Y.collog = ri;
         Y.nr = a.m; Y.nc = a.n; Y.part = (double *)(ws + L.o_colpart); Y.scal = nullptr; Y.cols_per_split = L.cpsy;
         if (a.d <= 4) {
-            if ((L.ibx != 1 && L.ibx != kIB2) || (L.iby != 1 && L.iby != kIB2)) return hipErrorInvalidValue;
-            const dim3 gx((a.n + kPT2 * L.ibx - 1) / (kPT2 * L.ibx), L.JSx), gy((a.m + kPT2 * L.iby - 1) / (kPT2 * L.iby), L.JSy);
+            if (L.ibx != 1 && L.ibx != kIB2) return hipErrorInvalidValue;
+            const dim3 gx((a.n + kPT2 * L.ibx - 1) / (kPT2 * L.ibx), L.JSx);
+            X.colpart = (float *)(ws + L.o_colpart);
+            X.ticket = tickets; X.cost_out = cost_only_out; X.s = a.s;
 #define FS_DIAG_PTS(D)                                                                                       \
     do {                                                                                                     \
-        if (L.ibx == 1) hipLaunchKernelGGL((k_diag_points<D, true, 1>), gx, dim3(kPT2), 0, st, X);           \
-        else hipLaunchKernelGGL((k_diag_points<D, true, kIB2>), gx, dim3(kPT2), 0, st, X);                   \
-        if (cost_only) break;                                                                                \
-        if (L.iby == 1) hipLaunchKernelGGL((k_diag_points<D, false, 1>), gy, dim3(kPT2), 0, st, Y);          \
-        else hipLaunchKernelGGL((k_diag_points<D, false, kIB2>), gy, dim3(kPT2), 0, st, Y);                  \
+        if (cost_only) {                                                                                     \
+            if (L.ibx == 1) hipLaunchKernelGGL((k_diag_points<D, 0, 1>), gx, dim3(kPT2), 0, st, X);          \
+            else hipLaunchKernelGGL((k_diag_points<D, 0, kIB2>), gx, dim3(kPT2), 0, st, X);                  \
+        } else {                                                                                             \
+            if (L.ibx == 1) hipLaunchKernelGGL((k_diag_points<D, 1, 1>), gx, dim3(kPT2), 0, st, X);          \
+            else hipLaunchKernelGGL((k_diag_points<D, 1, kIB2>), gx, dim3(kPT2), 0, st, X);                  \
+        }                                                                                                    \
     } while (0)
             switch (a.d) {
                 case 1: FS_DIAG_PTS(1); break;
@@ -796,6 +891,9 @@ hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *
                 default: FS_DIAG_PTS(4); break;
             }
 #undef FS_DIAG_PTS
+            if (cost_only) return hipGetLastError();      // the pass has written the cost itself
+            R.rowpart = X.part; R.nrowpart = L.JSx;
+            R.colpart = X.colpart; R.ncolpart = (int)gx.x; R.colpart_is_float = 1;
         } else {
             const dim3 gx((a.n + kTileRows - 1) / kTileRows, L.JSx), gy((a.m + kTileRows - 1) / kTileRows, L.JSy);
 #define FS_DIAG_MFMA(D4)                                                                                   \
@@ -810,12 +908,14 @@ hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *
                 default: FS_DIAG_MFMA(16); break;
             }
 #undef FS_DIAG_MFMA
+            R.rowpart = X.part; R.nrowpart = L.JSx;
+            R.colpart = Y.part; R.ncolpart = cost_only ? 0 : L.JSy; R.colpart_is_float = 0;
         }
-        R.rowpart = X.part; R.nrowpart = L.JSx;
-        R.colpart = Y.part; R.ncolpart = cost_only ? 0 : L.JSy; R.colpart_is_float = 0;
     }
+    R.scal = scal; R.nscal = L.nscal;
+    R.ticket = tickets + 1;
+    R.out8 = out8; R.cost_out = cost_only_out;
     hipLaunchKernelGGL(k_diag_reduce, dim3(L.nred), dim3(256), 0, st, R);
-    hipLaunchKernelGGL(k_diag_final, dim3(1), dim3(256), 0, st, R.red, L.nred, scal, L.nscal, a.s, out8, cost_only_out);
     return hipGetLastError();
 }
 

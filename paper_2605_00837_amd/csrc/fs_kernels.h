@@ -87,7 +87,7 @@ struct CombineArgs {
 
 // warm: bit 0 = start f from f_in / f64_in, bit 1 = start g from g_in / g64_in (else zero)
 hipError_t launch_init(hipStream_t st, const Pots &p, State *state, const float *f_in, const float *g_in,
-                       const double *f64_in, const double *g64_in, int warm);
+                       const double *f64_in, const double *g64_in, int warm, void *persist_sync = nullptr);
 // out[t] = -pot[t] / s (potential in natural units, double precision)
 hipError_t launch_export(hipStream_t st, const double *pot, int len, double s, double *out);
 hipError_t launch_finalize(hipStream_t st, const Pots &p, State *state, float *f, float *g,
@@ -163,7 +163,7 @@ int plan_scratch_len(int n, int m, int d);
 // Diagnostics in one pass (cost, mass, KL, primal, dual, marginal errors; optional marginals).
 size_t diag_scratch_bytes(int n, int m, int d);
 hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *row_marg, double *col_marg,
-                       void *scratch, size_t scratch_bytes, double *cost_only_out = nullptr);
+                       void *scratch, size_t scratch_bytes, unsigned int *tickets, double *cost_only_out = nullptr);
 
 // ri = s f + log2 a, cj = s g + log2 b; for point clouds also the repacked clouds (plain, times 2s, s|.|^2).
 hipError_t launch_plan_prep_all(hipStream_t st, const PlanArgs &a, double *ri, double *cj, double *xp, double *xs,
@@ -259,7 +259,6 @@ struct PersistArgs {
 bool dense_persist_supported(int n, int m, const void *C, int c_dtype);
 int dense_persist_grid(int n, int m, int cus);   // workgroups of the launch on a device with `cus` compute units
 size_t persist_scratch_bytes();
-hipError_t launch_persist_reset(hipStream_t st, void *scratch);          // once per solve, before the first block
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
                           int spin_limit, int final_err, const Stamp &tm = Stamp());
 

@@ -89,12 +89,6 @@ __device__ __forceinline__ int grid_wait(PersistSync *sy, unsigned long long old
     return good;
 }
 
-__global__ void k_persist_reset(PersistSync *sy) {
-    const int t = threadIdx.x;
-    if (t < 8) { sy->grp[t].v = 0ull; sy->done[t] = 0ull; }
-    if (t == 8) sy->abort_flag = 0ull;
-}
-
 constexpr int kWgPartLd = 512;          // slots of the per-workgroup exchange array
 constexpr int kAgent = 16;              // cache policy of a buffer load / store that other workgroups must see: sc1
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
@@ -649,12 +643,6 @@ int dense_persist_grid(int n, int m, int cus) {
 }
 
 size_t persist_scratch_bytes() { return sizeof(PersistSync) + sizeof(double) * kWgPartLd; }
-
-hipError_t launch_persist_reset(hipStream_t st, void *scratch) {
-    if (!scratch) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k_persist_reset, dim3(1), dim3(64), 0, st, reinterpret_cast<PersistSync *>(scratch));
-    return hipGetLastError();
-}
 
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
                           int spin_limit, int final_err, const Stamp &tm) {

@@ -9,17 +9,23 @@ namespace fs {
 
 // ---------------------------------------------------------------- init
 // la2 = log2 a, lb2 = log2 b (Alg. 1 "precompute"); F = G = 0 (Eqs. 6-7) or the
-// caller's warm start; U = la2 - F, V = lb2 - G; state cleared.
+// caller's warm start; U = la2 - F, V = lb2 - G; state cleared, and with it the arrival counters of the
+// persistent pass when the solve uses it (psync, else null).
 __global__ __launch_bounds__(256) void k_init(Pots p, State *state, const float *f_in,
                                               const float *g_in, const double *f64_in, const double *g64_in,
-                                              int warm) {
+                                              int warm, PersistSync *psync) {
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t == 0) {
         state->k = 0; state->flags = 0; state->iters = 0; state->converged = 0; state->nonfinite = 0;
         state->err_valid = 0;
         state->err_acc = 0;
         state->big_acc[0] = 0; state->big_acc[1] = 0x7fffffffu;   // no count yet: the first hint says ROBUST
+        state->fin_ticket = 0;
         state->err = __builtin_nan("");
+    }
+    if (psync && t >= 64 && t < 73) {
+        if (t < 72) { psync->grp[t - 64].v = 0ull; psync->done[t - 64] = 0ull; }
+        else psync->abort_flag = 0ull;
     }
     double *la2 = const_cast<double *>(p.la2);
     double *lb2 = const_cast<double *>(p.lb2);
@@ -46,10 +52,10 @@ __global__ __launch_bounds__(256) void k_init(Pots p, State *state, const float 
 }
 
 hipError_t launch_init(hipStream_t st, const Pots &p, State *state, const float *f_in, const float *g_in,
-                       const double *f64_in, const double *g64_in, int warm) {
+                       const double *f64_in, const double *g64_in, int warm, void *persist_sync) {
     const int len = p.n > p.m ? p.n : p.m;
     hipLaunchKernelGGL(k_init, dim3((len + 255) / 256), dim3(256), 0, st, p, state, f_in, g_in, f64_in,
-                       g64_in, warm);
+                       g64_in, warm, reinterpret_cast<PersistSync *>(persist_sync));
     return hipGetLastError();
 }
 
@@ -64,9 +70,11 @@ hipError_t launch_export(hipStream_t st, const double *pot, int len, double s, d
 }
 
 // ---------------------------------------------------------------- finalize
-// f = -F/s, g = -G/s from the buffer of the returned iterate; flags non-finite values.
+// f = -F/s, g = -G/s from the buffer of the returned iterate; flags non-finite values.  The workgroup that
+// finishes last writes the result record (to device memory, or to pinned host memory for the blocking solves)
+// and closes the state, so a solve ends with this one launch.
 __global__ __launch_bounds__(256) void k_finalize(Pots p, State *state, float *f, float *g, double *f64_out,
-                                                  double *g64_out) {
+                                                  double *g64_out, ResultRecord *dev, ResultRecord *host) {
     const int t = blockIdx.x * 256 + threadIdx.x;
     const int it = (state->flags & kFlagDone) ? state->iters : state->k;
     const int buf = it & 1;
@@ -84,18 +92,23 @@ __global__ __launch_bounds__(256) void k_finalize(Pots p, State *state, float *f
         if (g64_out) g64_out[t] = v;
         bad |= !(fabs(v) <= 1.7e308);
     }
-    if (bad) atomicOr(&state->nonfinite, 1);
-}
-
-__global__ void k_result(State *state, ResultRecord *dev, ResultRecord *host) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    if (bad) __hip_atomic_fetch_or(&state->nonfinite, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // every thread's flag is out before its workgroup takes a ticket (the barrier orders the workgroup's atomics
+    // before thread 0's, all on the same agent-scope path)
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    const unsigned ticket = __hip_atomic_fetch_add(&state->fin_ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (ticket != gridDim.x - 1) return;
+    const int nonfinite = __hip_atomic_load(&state->nonfinite, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     ResultRecord r;
     const bool done = (state->flags & kFlagDone) != 0;
     r.iters = done ? state->iters : state->k;
     r.converged = done ? state->converged : 0;
-    r.nonfinite = (state->nonfinite & kGaveUp) ? kGaveUp : state->nonfinite;
+    r.nonfinite = (nonfinite & kGaveUp) ? kGaveUp : nonfinite;
     r.marginal_err = (done && state->err_valid) ? (float)state->err : __builtin_nanf("");
     if (!done) { state->iters = r.iters; state->flags |= kFlagDone; }
+    state->fin_ticket = 0;
     if (dev) *dev = r;
     if (host) {
         *host = r;
@@ -106,9 +119,8 @@ __global__ void k_result(State *state, ResultRecord *dev, ResultRecord *host) {
 hipError_t launch_finalize(hipStream_t st, const Pots &p, State *state, float *f, float *g, double *f64_out,
                            double *g64_out, void *result_dev, void *result_host) {
     const int len = p.n > p.m ? p.n : p.m;
-    hipLaunchKernelGGL(k_finalize, dim3((len + 255) / 256), dim3(256), 0, st, p, state, f, g, f64_out, g64_out);
-    hipLaunchKernelGGL(k_result, dim3(1), dim3(64), 0, st, state, (ResultRecord *)result_dev,
-                       (ResultRecord *)result_host);
+    hipLaunchKernelGGL(k_finalize, dim3((len + 255) / 256), dim3(256), 0, st, p, state, f, g, f64_out, g64_out,
+                       (ResultRecord *)result_dev, (ResultRecord *)result_host);
     return hipGetLastError();
 }
 
