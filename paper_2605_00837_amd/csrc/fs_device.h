@@ -266,6 +266,36 @@ struct Lse {
     __device__ __forceinline__ double value() const { return M + log2_sum(s); }
 };
 
+// ---------------------------------------------------------------- last workgroup finishes
+// What one workgroup hands to the workgroup that finishes the call (whichever arrives last): stores and loads at
+// agent scope, which pass the per-die caches, and an arrival counter that returns to 0 after use.
+__device__ __forceinline__ void agent_store_f64(double *p, double v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double agent_load_f64(const double *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void agent_store_f32(float *p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float agent_load_f32(const float *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Called by every thread of a workgroup after thread 0 has published the workgroup's record: true (for all
+// threads) in the workgroup that arrives last of `total`.
+__device__ __forceinline__ bool last_to_arrive(unsigned int *ticket, unsigned int total, int *lds_flag) {
+    if (threadIdx.x == 0) {
+        __builtin_amdgcn_s_waitcnt(0);                 // this workgroup's record has been acknowledged
+        const unsigned int t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = t == total - 1u;
+        if (last) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *lds_flag = last;
+    }
+    __syncthreads();
+    return *lds_flag != 0;
+}
+
+
 // ---------------------------------------------------------------- advance
 // Runs in ONE thread after the g-update of an iteration (or after the trailing
 // error pass).  `err` is the row-marginal error of the iterate the launch

@@ -143,28 +143,6 @@ __device__ __forceinline__ double block_sum(double v, double *lds) {
     return lds[0];
 }
 
-// What one workgroup hands to the workgroup that finishes the call (whichever arrives last): stores and loads at
-// agent scope, which pass the per-die caches, and an arrival counter that returns to 0 after use.
-__device__ __forceinline__ void pub_f64(double *p, double v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ double get_f64(const double *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// Called by every thread of a workgroup after thread 0 has published the workgroup's record: true (for all
-// threads) in the workgroup that arrives last of `total`.
-__device__ __forceinline__ bool last_to_arrive(unsigned int *ticket, unsigned int total, int *lds_flag) {
-    if (threadIdx.x == 0) {
-        __builtin_amdgcn_s_waitcnt(0);                 // this workgroup's record has been acknowledged
-        const unsigned int t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int last = t == total - 1u;
-        if (last) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *lds_flag = last;
-    }
-    __syncthreads();
-    return *lds_flag != 0;
-}
-
 // ---------------------------------------------------------------- dense
 struct DenseDiag {
     const float *C;
@@ -257,10 +235,10 @@ __global__ __launch_bounds__(kDT) void k_diag_dense(DenseDiag A) {
     const double c_tot = A.s * block_sum<kDT>(cost_acc, lds);        // sum P (s C), the unit the tail works in
     if constexpr (COST_ONLY) {
         const unsigned int total = gridDim.x * gridDim.y;
-        if (tid == 0) pub_f64(&A.scal[2 * w], c_tot);
+        if (tid == 0) agent_store_f64(&A.scal[2 * w], c_tot);
         if (!last_to_arrive(A.ticket, total, &sLast)) return;
         double acc = 0.0;
-        for (unsigned int q = tid; q < total; q += kDT) acc += get_f64(&A.scal[2 * (size_t)q]);
+        for (unsigned int q = tid; q < total; q += kDT) acc += agent_load_f64(&A.scal[2 * (size_t)q]);
         const double tot = block_sum<kDT>(acc, lds);
         if (tid == 0) A.cost_out[0] = tot / A.s;
     } else {
@@ -399,10 +377,10 @@ __global__ __launch_bounds__(kPT2) void k_diag_points(PointsDiag A) {
         }
     } else {                                   // the workgroup that arrives last finishes the call
         const unsigned int total = gridDim.x * gridDim.y;
-        if (tid == 0) pub_f64(&A.scal[2 * w], c_tot);
+        if (tid == 0) agent_store_f64(&A.scal[2 * w], c_tot);
         if (!last_to_arrive(A.ticket, total, &sLast)) return;
         double acc = 0.0;
-        for (unsigned int q = tid; q < total; q += kPT2) acc += get_f64(&A.scal[2 * (size_t)q]);
+        for (unsigned int q = tid; q < total; q += kPT2) acc += agent_load_f64(&A.scal[2 * (size_t)q]);
         const double tot = block_sum<kPT2>(acc, lds);
         if (tid == 0) A.cost_out[0] = tot / A.s;
     }
@@ -487,20 +465,21 @@ __global__ __launch_bounds__(256) void k_diag_points_mfma(PointsDiag A, int d) {
 }
 
 // out[0] cost, [1] mass, [2] KL(P | a x b), [3] primal, [4] dual, [5] row-marginal L1 error,
-// [6] column-marginal L1 error, [7] 0.  Called by all 256 threads of one workgroup: per-thread shares in index
-// order, wave sums by DPP, then the 4 waves one after the other, so the order of the additions is fixed.
+// [6] column-marginal L1 error, [7] 0.  Called by all T threads of one workgroup: per-thread shares in index
+// order, wave sums by DPP, then the waves one after the other, so the order of the additions is fixed.
+template <int T>
 __device__ __forceinline__ void diag_totals(const double *red, int nred, const double *scal, int nscal, double s,
                                             double *out, double *cost_out, double *lds, bool agent_loads) {
     double w9[9];
     for (int q = 0; q < 7; ++q) {
         double acc = 0.0;
-        for (int w = threadIdx.x; w < nred; w += 256)
-            acc += agent_loads ? get_f64(&red[(size_t)w * 8 + q]) : red[(size_t)w * 8 + q];
+        for (int w = threadIdx.x; w < nred; w += T)
+            acc += agent_loads ? agent_load_f64(&red[(size_t)w * 8 + q]) : red[(size_t)w * 8 + q];
         w9[q] = acc;
     }
     for (int q = 0; q < 2; ++q) {
         double acc = 0.0;
-        for (int w = threadIdx.x; w < nscal; w += 256) acc += scal[(size_t)w * 2 + q];   // written by an earlier launch
+        for (int w = threadIdx.x; w < nscal; w += T) acc += scal[(size_t)w * 2 + q];   // written by an earlier launch
         w9[7 + q] = acc;
     }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -514,7 +493,9 @@ __device__ __forceinline__ void diag_totals(const double *red, int nred, const d
         double v[7], sc[2];
 #pragma unroll
         for (int q = 0; q < 9; ++q) {
-            const double t = (lds[q] + lds[9 + q]) + (lds[18 + q] + lds[27 + q]);
+            double t = 0.0;
+#pragma unroll
+            for (int w = 0; w < T / 64; ++w) t += lds[w * 9 + q];
             if (q < 7) v[q] = t;
             else sc[q - 7] = t;
         }
@@ -554,57 +535,44 @@ struct ReduceArgs {
     double *out8, *cost_out;
 };
 
-// A workgroup of 256 threads finishes 64 rows and 64 columns: lane = entry, the 4 waves split the
+// A workgroup of 1024 threads finishes 64 rows and 64 columns: lane = entry, the 16 waves split the
 // partial sets (8 loads in flight each) and meet in LDS.
-__global__ __launch_bounds__(256) void k_diag_reduce(ReduceArgs A) {
-    __shared__ double sR[4][64], sC[4][64];
-    __shared__ double lds9[4 * 9];
+constexpr int kRW = 16;             // waves of the reduction kernel
+__global__ __launch_bounds__(kRW * 64) void k_diag_reduce(ReduceArgs A) {
+    __shared__ double sR[kRW][64], sC[kRW][64];
+    __shared__ double lds9[kRW * 9];
     __shared__ int sLast;
     const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
     const int t = blockIdx.x * 64 + lane;
     double r = 0.0, c = 0.0;
-    if (t < A.P.n) {
+    // partial sets grp, grp + 16, ...: eight loads in flight, added in index order
+    auto gather = [&](auto ptr, int nsets, int ld) -> double {
+        double acc = 0.0;
         int q = grp;
-        for (; q + 28 < A.nrowpart; q += 32) {
+        for (; q + 7 * kRW < nsets; q += 8 * kRW) {
             double x[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) x[u] = A.rowpart[(size_t)(q + 4 * u) * A.P.n + t];
+            for (int u = 0; u < 8; ++u) x[u] = (double)ptr[(size_t)(q + kRW * u) * ld + t];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) r += x[u];
+            for (int u = 0; u < 8; ++u) acc += x[u];
         }
-        for (; q < A.nrowpart; q += 4) r += A.rowpart[(size_t)q * A.P.n + t];
-    }
+        for (; q < nsets; q += kRW) acc += (double)ptr[(size_t)q * ld + t];
+        return acc;
+    };
+    if (t < A.P.n) r = gather(A.rowpart, A.nrowpart, A.P.n);
     if (t < A.P.m) {
-        int q = grp;
-        if (A.colpart_is_float) {
-            const float *cp = (const float *)A.colpart;
-            for (; q + 28 < A.ncolpart; q += 32) {
-                float x[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = cp[(size_t)(q + 4 * u) * A.P.m + t];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) c += (double)x[u];
-            }
-            for (; q < A.ncolpart; q += 4) c += (double)cp[(size_t)q * A.P.m + t];
-        } else {
-            const double *cp = (const double *)A.colpart;
-            for (; q + 28 < A.ncolpart; q += 32) {
-                double x[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = cp[(size_t)(q + 4 * u) * A.P.m + t];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) c += x[u];
-            }
-            for (; q < A.ncolpart; q += 4) c += cp[(size_t)q * A.P.m + t];
-        }
+        if (A.colpart_is_float) c = gather((const float *)A.colpart, A.ncolpart, A.P.m);
+        else c = gather((const double *)A.colpart, A.ncolpart, A.P.m);
     }
     sR[grp][lane] = r;
     sC[grp][lane] = c;
     __syncthreads();
     double v[7] = {0, 0, 0, 0, 0, 0, 0};          // mass, row err, col err, <a,f>, <b,g>, <r,f>, <c,g>
     if (grp == 0) {
-        r = (sR[0][lane] + sR[1][lane]) + (sR[2][lane] + sR[3][lane]);
-        c = (sC[0][lane] + sC[1][lane]) + (sC[2][lane] + sC[3][lane]);
+        r = 0.0;
+        c = 0.0;
+#pragma unroll
+        for (int w = 0; w < kRW; ++w) { r += sR[w][lane]; c += sC[w][lane]; }
         if (t < A.P.n) {
             const float a = A.P.a[t];
             if (A.row_marg) A.row_marg[t] = r;
@@ -625,12 +593,12 @@ __global__ __launch_bounds__(256) void k_diag_reduce(ReduceArgs A) {
 #pragma unroll
         for (int q = 0; q < 7; ++q) {
             const double tot = wave_sum_f64(v[q]);
-            if (lane == 0) pub_f64(&A.red[(size_t)blockIdx.x * 8 + q], tot);
+            if (lane == 0) agent_store_f64(&A.red[(size_t)blockIdx.x * 8 + q], tot);
         }
     }
     __syncthreads();                                  // (thread 0 is lane 0 of the wave that stored the record)
     if (!last_to_arrive(A.ticket, gridDim.x, &sLast)) return;
-    diag_totals(A.red, (int)gridDim.x, A.scal, A.nscal, A.P.s, A.out8, A.cost_out, lds9, /*agent_loads=*/true);
+    diag_totals<kRW * 64>(A.red, (int)gridDim.x, A.scal, A.nscal, A.P.s, A.out8, A.cost_out, lds9, /*agent_loads=*/true);
 }
 
 // ---------------------------------------------------------------- small problems: everything in one workgroup
@@ -915,7 +883,7 @@ hipError_t launch_diag(hipStream_t st, const PlanArgs &a, double *out8, double *
     R.scal = scal; R.nscal = L.nscal;
     R.ticket = tickets + 1;
     R.out8 = out8; R.cost_out = cost_only_out;
-    hipLaunchKernelGGL(k_diag_reduce, dim3(L.nred), dim3(256), 0, st, R);
+    hipLaunchKernelGGL(k_diag_reduce, dim3(L.nred), dim3(kRW * 64), 0, st, R);
     return hipGetLastError();
 }
 
