@@ -160,3 +160,24 @@ def test_tiny_weights_point_clouds(fs, oracle, n, m, d, mode, variant, eps):
                              kernel_mode=mode, fused_variant=variant)
     assert r["iters"] == iters
     _compare(r, ref, w.eps, (n, m, d, mode, variant, eps))
+
+
+# ------------------------------------------------------------------ pace hints with long check intervals
+@pytest.mark.parametrize("check_every", [50, 64, 200])
+def test_pace_hints_with_long_check_intervals(fs, oracle, check_every):
+    """The multi-kernel driver chooses between the exact streaming kernels and the optimistic fused kernel block by
+    block, from the pace hint the device left in a ring of 256 slots for the last block the host has waited for.
+    With blocks of 50 and 64 iterations (and 200, which is cut to 64) and three blocks in flight, a slot must not be
+    overwritten before it is read: the kernel sequence, and with it every bit of the result, is the same in every
+    run, and the result matches the oracle."""
+    import torch
+    w = W.random_dense(600, 4096, seed=7400 + check_every, cmax=40.0, eps=0.02)
+    iters = 400
+    ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C)
+    C, a, b = dev(w.C), dev(w.a), dev(w.b)
+    runs = [fs.fs_sinkhorn_solve(a, b, w.eps, iters, 0.0, C=C, want_f64=True, kernel_mode=2, check_every=check_every)
+            for _ in range(4)]
+    for r in runs:
+        assert r["iters"] == iters
+        assert torch.equal(r["f64"], runs[0]["f64"]) and torch.equal(r["g64"], runs[0]["g64"])
+    _compare(runs[0], ref, w.eps, ("check_every", check_every))
