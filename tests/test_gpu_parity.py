@@ -1010,6 +1010,9 @@ def test_diagnostics_one_pass(fs, oracle, kind, n, m, d, precision):
     if n > 40:
         w.a[5::11] = 0.0
         w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    if m > 40:                                  # zero column weights too: plan columns of exact zeros
+        w.b[3::13] = 0.0
+        w.b[:] = w.b / w.b.sum(dtype=np.float64)
     ref = oracle.solve(w.a, w.b, w.eps, 3, C=w.C, X=w.X, Y=w.Y)
     f_h, g_h = ref["f"], ref["g"]
     if precision == "f32":
@@ -1034,7 +1037,8 @@ def test_diagnostics_one_pass(fs, oracle, kind, n, m, d, precision):
 
 
 @pytest.mark.parametrize("kind,n,m,d,dz", [("dense", 300, 257, 0, 3), ("dense", 130, 4100, 0, 1), ("dense", 700, 8192, 0, 4),
-                                            ("dense", 17, 3, 0, 2), ("dense", 61, 4102, 0, 3), ("points", 700, 1300, 3, 3), ("points", 1030, 500, 2, 4),
+                                            ("dense", 17, 3, 0, 2), ("dense", 61, 4102, 0, 3), ("dense", 1000, 1024, 0, 2), ("dense", 129, 2052, 0, 4),
+                                            ("dense", 5000, 1028, 0, 3), ("points", 700, 1300, 3, 3), ("points", 1030, 500, 2, 4),
                                             ("points", 90, 200, 7, 2), ("points", 400, 300, 12, 4), ("points", 131, 1025, 40, 1),
                                             ("points", 260, 64, 64, 3), ("points", 8300, 140, 3, 2),
                                             ("points", 2100, 1990, 4, 3)])
@@ -1045,6 +1049,9 @@ def test_barycentric_mapping(fs, oracle, kind, n, m, d, dz):
         W.random_points(n, m, d, seed=6500 + n + m + d, eps=0.05)
     w.a[1] = 0.0
     w.a[:] = w.a / w.a.sum(dtype=np.float64)
+    if m > 8:
+        w.b[2::7] = 0.0                         # targets without mass take no part in the mapping
+        w.b[:] = w.b / w.b.sum(dtype=np.float64)
     ref = oracle.solve(w.a, w.b, w.eps, 4, C=w.C, X=w.X, Y=w.Y)
     rng = np.random.default_rng(n + m)
     Z = rng.standard_normal((m, dz)).astype(np.float32) if kind == "dense" or dz != d else w.Y.copy()
