@@ -176,6 +176,10 @@ def bench_dense(args, name):
     n, m = w.n, w.m
     steps = args.steps if args.steps > 0 else steps_default
     C, a, b = (torch.from_numpy(t).cuda() for t in (w.C, w.a, w.b))
+    esize = 4
+    if args.cost_dtype != "f32":      # C stored in 2 bytes per entry (the arithmetic stays what it is): not the headline
+        C = C.to(torch.float16 if args.cost_dtype == "f16" else torch.bfloat16)
+        esize = 2
     kw = dict(C=C, kernel_mode=args.kernel_mode, fused_variant=args.fused_variant)
     if tol > 0.0:
         kw["check_every"] = 10
@@ -191,15 +195,16 @@ def bench_dense(args, name):
     # Algorithmic bytes.  One pass over C with V in and F, U out is what one iteration of a kernel that fuses the
     # two half-steps needs; two passes (the row pass and the column pass each read C) is the floor of any two-kernel
     # iteration and the figure the survey of the paper's method states.  Nothing is credited above the one-pass figure.
-    bytes_one_pass = n * m * 4 + m * 8 + n * 16
-    bytes_two_pass = 2 * n * m * 4
+    bytes_one_pass = n * m * esize + m * 8 + n * 16
+    bytes_two_pass = 2 * n * m * esize
     per_iter_ms = kern_ms * launches / max(covered, 1)
     alg_bytes_launch = bytes_one_pass * (covered / max(launches, 1)) if not one_launch_kernel else None
     out = {
-        "metric": metric, "value": iters / dt, "unit": "iter/s", "n_gpus": 1, "steps": iters, "warmup": args.warmup,
+        "metric": metric if esize == 4 else metric.replace("_fp32_", f"_{args.cost_dtype}cost_"),
+        "value": iters / dt, "unit": "iter/s", "n_gpus": 1, "steps": iters, "warmup": args.warmup,
         "ms_per_step": dt * 1e3 / max(iters, 1), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{label} fp32 C ({n * m * 4 / 2 ** 20:g} MiB), {desc}, max_iter={steps}",
+        "config": {"workload": f"{label} {args.cost_dtype} C ({n * m * esize / 2 ** 20:g} MiB), {desc}, max_iter={steps}",
                    "kernel_path": kern_name, "potentials": "fp64 internal, fp32 out",
                    "spinup": f"{args.spinup} {args.spinup_ms:g} ms"},
         "ms_to_stop": dt * 1e3, "converged": r["converged"], "marginal_err": r["marginal_err"],
@@ -223,7 +228,7 @@ def bench_dense(args, name):
                         "achieved_GBs": it_gbs, "frac_iteration": it_gbs / HBM_PEAK_GBS,
                         "two_pass_equivalent_GBs": bytes_two_pass * iters / dt / 1e9,
                         "us_per_iteration": dt * 1e6 / max(iters, 1)}
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and esize == 4:
         out["cpu_baseline"] = cpu_baseline_dense(w, eps, label, budget_s=12.0 if n * m >= 1 << 20 else 3.0)
     print(json.dumps(out))
 
@@ -358,6 +363,8 @@ def main():
     ap.add_argument("--eps-index", type=int, default=1, help="c3: which of eps = 1e-1, 1e-2, 1e-3, 1e-4")
     ap.add_argument("--kernel-mode", type=int, default=0)
     ap.add_argument("--fused-variant", type=int, default=0)
+    ap.add_argument("--cost-dtype", choices=["f32", "f16", "bf16"], default="f32",
+                    help="dense workloads: storage type of C (2-byte types are widened exactly; not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true")
     ap.add_argument("--after-loop", action="store_true",

@@ -145,7 +145,8 @@ typedef struct {
                                   of HIP events that the runtime stamps with the start and the stop of that
                                   dispatch on `stream` (hipExtLaunchKernel); read back with
                                   fs_last_kernel_timing().  The persistent fused pass (kernel_mode 6) is one
-                                  launch per block of iterations: every launch is timed                    */
+                                  launch per block of iterations: every launch of a solve of up to 12
+                                  blocks is timed, else about a dozen spread evenly over the solve         */
 } fs_options;
 
 /* ---- Blocking solves (Alg. 1).  Return the number of iterations performed (>= 0) or a
