@@ -95,7 +95,10 @@ typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 // Debug builds (-DFS_PERSIST_TRACE) stamp the phases of one iteration per workgroup with the 100 MHz clock.
 #ifdef FS_PERSIST_TRACE
-#define FS_TRACE(slot) do { if (lane == 0 && X.trace && k == k_end - 2) X.trace[(w * 16 + wave) * 8 + (slot)] = (long long)__builtin_amdgcn_s_memrealtime(); } while (0)
+#define FS_TRACE(slot) do { if (lane == 0 && X.trace) { \
+        const long long now_ = (long long)__builtin_amdgcn_s_memrealtime(); \
+        if (X.trace[65536 + 8191] < 0 ? k == 0 : k == k_end - 2) X.trace[(w * 16 + wave) * 8 + (slot)] = now_; \
+        if ((slot) <= 1 && wave == 0 && (w == 0 || w == 100) && k < 2000) X.trace[65536 + (w ? 4096 : 0) + 2 * k + (slot)] = now_; } } while (0)
 #else
 #define FS_TRACE(slot) do { } while (0)
 #endif
@@ -314,51 +317,54 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
             double Fn_lane = rho_lane + log2_sum(S);
             float alpha_lane = a_lane / S;                        // pi_ij = e_ij * a_i / S_i
             if (__builtin_expect(!__all(fine || !rowok), 0)) {
-                // ---- exact redo of the row phase of this panel (uniform over the workgroup)
+                // ---- exact redo of the row phase of this panel (uniform over the workgroup): Eq. 8 as written,
+                //      the maximum of the row first (no exponentials), then the sum relative to it
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    Lse rs; rs.init();
+                    double mx = kNegHuge;
 #pragma unroll
                     for (int q = 0; q < Q; ++q) {
                         const float4 c4 = stage[buf][wave][r][q][lane];
                         float cvv[4];
                         unpack(c4, q, cvv);
-                        double x[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) x[e] = fma(ns, (double)cvv[e], v[q][e]);
-                        rs.template add<4>(x);
+                        for (int e = 0; e < 4; ++e) mx = dmax(mx, fma(ns, (double)cvv[e], v[q][e]));
                     }
-                    rs.wave_reduce();
-                    if (lane == 0) { sM[buf][r][wave] = rs.M; sS[buf][r][wave] = rs.s; }
+                    mx = wave_max_f64(mx);
+                    if (lane == 0) sM[buf][r][wave] = mx;
                 }
-                lds_only_barrier();
-                Lse tl; tl.init();
-                if (rr < R) { tl.M = sM[buf][rc][lane % NW]; tl.s = sS[buf][rc][lane % NW]; }
-                double Mg = tl.M;
+                lds_only_barrier();                              // (every wave has read sSum by now)
+                double Mg = rr < R ? sM[buf][rc][lane % NW] : kNegHuge;
                 Mg = dmax(Mg, dpp_f64<0x128>(Mg));
                 Mg = dmax(Mg, dpp_f64<0x124>(Mg));
                 Mg = dmax(Mg, dpp_f64<0x122>(Mg));
                 Mg = dmax(Mg, dpp_f64<0x121>(Mg));
-                float sg = tl.s * fast_exp2((float)(tl.M - Mg));
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const double Mr = bcast_f64(Mg, r * NW);
+                    float acc = 0.0f;
+#pragma unroll
+                    for (int q = 0; q < Q; ++q) {
+                        const float4 c4 = stage[buf][wave][r][q][lane];
+                        float cvv[4];
+                        unpack(c4, q, cvv);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            ev[r][q][e] = fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - Mr));
+                            acc += ev[r][q][e];
+                        }
+                    }
+                    acc = wave_sum_f32(acc);
+                    if (lane == 0) sSum[buf][r][wave] = acc;
+                }
+                lds_only_barrier();
+                float sg = rr < R ? sSum[buf][rc][lane % NW] : 1.0f;
                 sg += dpp_f32<0x128>(sg);
                 sg += dpp_f32<0x124>(sg);
                 sg += dpp_f32<0x122>(sg);
                 sg += dpp_f32<0x121>(sg);
                 Fn_lane = Mg + log2_sum(sg);
-                alpha_lane = a_lane;                               // e is re-based on the new F below
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const double Fn = bcast_f64(Fn_lane, r * NW);
-#pragma unroll
-                    for (int q = 0; q < Q; ++q) {
-                        const float4 c4 = stage[buf][wave][r][q][lane];
-                        float cvv[4];
-                        unpack(c4, q, cvv);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            ev[r][q][e] = fast_exp2((float)(fma(ns, (double)cvv[e], v[q][e]) - Fn));
-                    }
-                }
+                alpha_lane = a_lane / sg;                          // e is relative to the row maximum: pi = e a / sum
             }
             if (wave == 0 && (lane % NW) == 0 && rowok) {
                 // F stays with this workgroup (it is the old F of the same rows in the next iteration); U is
