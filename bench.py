@@ -140,9 +140,18 @@ def _solve_timed(fs, torch, a, b, eps, steps, tol, warmup, time_kernels=True, sp
     fs.fs_sinkhorn_solve(a, b, eps, warmup, 0.0, f=f, g=g, **geo_kw)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    r = fs.fs_sinkhorn_solve(a, b, eps, steps, tol, f=f, g=g, time_kernel_every=1 if time_kernels else 0, **geo_kw)
+    r = fs.fs_sinkhorn_solve(a, b, eps, steps, tol, f=f, g=g, **geo_kw)
     torch.cuda.synchronize()
-    return r, time.perf_counter() - t0
+    dt = time.perf_counter() - t0
+    if time_kernels:
+        # The dominant kernel's own duration comes from the SAME solve run once more, right away, with its launches
+        # stamped by HIP events: a stamped dispatch costs 10 - 50 us of queue and host time, which at 20 iterations
+        # (one launch) would be 2 - 5 % of the very time being reported.  Same inputs, same iteration count, same
+        # kernels (the results are bit-identical); fs_last_kernel_timing() reads the events afterwards.
+        r2 = fs.fs_sinkhorn_solve(a, b, eps, steps, tol, f=f, g=g, time_kernel_every=1, **geo_kw)
+        torch.cuda.synchronize()
+        assert r2["iters"] == r["iters"]
+    return r, dt
 
 
 def bench_dense(args, name):
@@ -216,6 +225,8 @@ def bench_dense(args, name):
                            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                            "traffic_source": (src + " (rocprofv3 --pmc runs of their own, not this run)") if src else None,
                            "kernel": kern_name, "kernel_avg_us": kern_ms * 1e3, "kernel_launches_timed": launches,
+                           "kernel_timing": "HIP events stamped with the start and stop of the dispatch, in a repeat of "
+                                            "the timed solve run right after it (stamping costs queue time)",
                            "iterations_per_launch": covered / max(launches, 1), "kernel_us_per_iteration": per_iter_ms * 1e3,
                            "algorithmic_bytes_per_launch": alg_bytes_launch}
     else:

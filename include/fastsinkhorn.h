@@ -315,8 +315,9 @@ int fs_kernel_choice(int n, int m, int d, const fs_options *opts, int blocking, 
  * blocking solve on this thread that had time_kernel_every > 0, the number of sampled launches, the
  * kernel's name (static storage) and the number of iterations the sampled launches performed in all
  * (= samples, except for the persistent fused pass, whose launches run a block of iterations each).
- * Any output pointer may be NULL.  FS_ERR_INVALID_ARG when there is no such solve.  For benchmarks;
- * no effect on results. */
+ * Any output pointer may be NULL.  FS_ERR_INVALID_ARG when there is no such solve.  The durations are read
+ * from the events by this call, not by the solve: call it before the next timed solve on the device and before
+ * fs_clear_cache().  For benchmarks; no effect on results. */
 fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name,
                                 int32_t *iters_sampled);
 

@@ -12,6 +12,7 @@
 #include <map>
 #include <mutex>
 #include <tuple>
+#include <utility>
 #include <vector>
 
 #include "../../include/fastsinkhorn.h"
@@ -131,7 +132,16 @@ struct DeviceCache {
     unsigned int *tickets = nullptr;    // 64 arrival counters of the after-the-loop kernels; each returns to 0 after use
 };
 
-struct KernelTiming { float avg_ms = 0.0f; int samples = 0; const char *name = ""; int iters_sampled = 0; };
+// Result of the sampled kernel timing of the last timed solve on this thread.  The solve only notes which event
+// pairs count; the durations are read from the events when fs_last_kernel_timing() asks for them, so that this
+// bookkeeping is not part of the solve's own run time.
+struct KernelTiming {
+    float avg_ms = 0.0f;
+    int samples = 0;
+    const char *name = "";
+    int iters_sampled = 0;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pending;   // not yet read; the events live in the device cache
+};
 thread_local KernelTiming g_timing;
 
 std::mutex g_mu;
@@ -647,17 +657,13 @@ int run_solve_blocking(Solve &S, DeviceCache *dc, float *f, float *g, fs_result 
     }
     if (nsamples > 0) {
         // only launches that did work count: those of iterations the solve actually performed
-        double tot = 0.0;
         int used = 0, covered = 0;
         for (int q = 0; q < nsamples; ++q) {
             if (sample_iter[q] >= hb->res.iters) break;
-            float ms = 0.0f;
-            FS_HIP(hipEventElapsedTime(&ms, dc->timing[2 * q], dc->timing[2 * q + 1]));
-            tot += ms;
+            g_timing.pending.emplace_back(dc->timing[2 * q], dc->timing[2 * q + 1]);
             ++used;
             covered += S.persist ? sample_len[q] : 1;
         }
-        g_timing.avg_ms = used ? (float)(tot / used) : 0.0f;
         g_timing.samples = used;
         g_timing.name = S.dominant_kernel();
         g_timing.iters_sampled = covered;
@@ -1052,6 +1058,7 @@ const char *fs_last_error(void) { return g_err; }
 const char *fs_version(void) { return "fastsinkhorn-gfx950 0.1"; }
 
 void fs_clear_cache(void) {
+    g_timing = KernelTiming{};              // its events are about to go
     std::lock_guard<std::mutex> lk(g_mu);
     for (auto &kv : g_cache) {
         DeviceCache &c = kv.second;
@@ -1106,6 +1113,16 @@ int fs_kernel_choice(int n, int m, int d, const fs_options *opts, int blocking, 
 
 fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name, int32_t *iters_sampled) {
     if (g_timing.samples <= 0) { set_err("no timed solve has run on this thread"); return FS_ERR_INVALID_ARG; }
+    if (!g_timing.pending.empty()) {
+        double tot = 0.0;
+        for (const auto &ev : g_timing.pending) {
+            float ms = 0.0f;
+            FS_HIP(hipEventElapsedTime(&ms, ev.first, ev.second));
+            tot += ms;
+        }
+        g_timing.avg_ms = (float)(tot / (double)g_timing.pending.size());
+        g_timing.pending.clear();
+    }
     if (avg_ms) *avg_ms = g_timing.avg_ms;
     if (samples) *samples = g_timing.samples;
     if (kernel_name) *kernel_name = g_timing.name;
