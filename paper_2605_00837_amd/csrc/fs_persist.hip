@@ -314,8 +314,16 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
             S += dpp_f32<0x122>(S);
             S += dpp_f32<0x121>(S);
             const bool fine = (S >= kRowLo) && (S <= kRowHi);    // false for NaN / inf / 0
-            double Fn_lane = rho_lane + log2_sum(S);
-            float alpha_lane = a_lane / S;                        // pi_ij = e_ij * a_i / S_i
+            // pi_ij = e_ij * a_i / S_i.  Every wave needs a_i / S_i (reciprocal, one Newton step, product: within 1.5
+            // ulp); the new F = reference + log2 S is formed by the one wave that stores it, further down.
+            double Fbase = rho_lane;
+            float Ssum = S;
+            float alpha_lane;
+            {
+                float rcp = __builtin_amdgcn_rcpf(S);
+                rcp = fmaf(fmaf(-S, rcp, 1.0f), rcp, rcp);
+                alpha_lane = a_lane * rcp;
+            }
             if (__builtin_expect(!__all(fine || !rowok), 0)) {
                 // ---- exact redo of the row phase of this panel (uniform over the workgroup): Eq. 8 as written,
                 //      the maximum of the row first (no exponentials), then the sum relative to it
@@ -363,12 +371,14 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
                 sg += dpp_f32<0x124>(sg);
                 sg += dpp_f32<0x122>(sg);
                 sg += dpp_f32<0x121>(sg);
-                Fn_lane = Mg + log2_sum(sg);
+                Fbase = Mg;
+                Ssum = sg;
                 alpha_lane = a_lane / sg;                          // e is relative to the row maximum: pi = e a / sum
             }
             if (wave == 0 && (lane % NW) == 0 && rowok) {
                 // F stays with this workgroup (it is the old F of the same rows in the next iteration); U is
                 // what a repair in another workgroup reads
+                const double Fn_lane = Fbase + log2_sum(Ssum);
                 p.F[(size_t)nxt * p.n_ld + i0 + rr] = Fn_lane;
                 pub_f64(p.U + (size_t)nxt * p.n_ld + i0 + rr, la2_lane - Fn_lane);
                 // error term of Sec. 4.5 for the iterate this iteration started from: a_i |2^(Fnew - Fold) - 1|
