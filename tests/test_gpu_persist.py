@@ -231,3 +231,40 @@ def test_persistent_pass_rejections(fs):
     b3 = torch.full((4096,), 1.0 / 4096, device="cuda")
     with pytest.raises(fs.FsError, match="kernel_mode 6"):
         fs.fs_sinkhorn_solve(a3, b3, 0.05, 5, 0.0, C=C16, kernel_mode=6)       # fp32 costs only
+
+
+def _sweep_cases():
+    rng = np.random.default_rng(20260511)
+    cases = []
+    for t in range(24):
+        m = int(rng.integers(1025, 16385))
+        n = int(rng.integers(40, 2600))
+        cases.append((t, n, m, float(rng.choice([0.01, 0.03, 0.1])), float(rng.choice([2.0, 20.0])),
+                      int(rng.integers(3, 70)), bool(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("t,n,m,eps,cmax,iters,warm", _sweep_cases())
+def test_persistent_pass_seeded_shape_sweep(fs, oracle, t, n, m, eps, cmax, iters, warm):
+    """Random shapes over the whole range of widths, two cost scales, iteration counts on both sides of a block of
+    25, cold and warm starts (the warm start: the oracle's potentials after 5 iterations, given in fp64)."""
+    if not _supported(fs, n, m):
+        pytest.skip("needs more compute units than this device has")
+    import torch
+    w = W.random_dense(n, m, seed=8100 + t, cmax=cmax, eps=eps)
+    kw = {}
+    if warm:
+        start = oracle.solve(w.a, w.b, w.eps, 5, C=w.C)
+        ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C, f0=start["f"], g0=start["g"])
+        kw = dict(f=dev(start["f"].astype(np.float32)), g=dev(start["g"].astype(np.float32)), warm_start=True,
+                  f64_in=dev(start["f"]), g64_in=dev(start["g"]))
+    else:
+        ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C)
+    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, iters, 0.0, C=dev(w.C), want_f64=True, kernel_mode=6, **kw)
+    assert r["iters"] == iters and not r["nonfinite"]
+    tol64 = max(TOL_F64, 2 * iters * 1e-7) if eps * 1e3 < cmax else TOL_F64
+    df = r["f64"].cpu().numpy() - ref["f"]
+    dg = r["g64"].cpu().numpy() - ref["g"]
+    c = 0.5 * (np.median(df) - np.median(dg))
+    assert max(np.abs(df).max(), np.abs(dg).max()) / eps < TOL_F32
+    assert max(np.abs(df - c).max(), np.abs(dg + c).max()) / eps < tol64, (n, m, eps, cmax, iters, warm)
