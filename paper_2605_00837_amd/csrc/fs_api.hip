@@ -769,11 +769,9 @@ bool persist_path(const Problem &pr, const fs_options *opts, bool blocking, int 
     if (km == 6) return true;
     if (opts && opts->fused_variant != 0) return false;      // a tuning / test knob of the multi-kernel path
     // automatic: where it is faster than the multi-kernel driver (5 - 19 % per iteration from 300 x 3000 to
-    // 16384 x 8192, 65536 x 2048).  Beyond 8192 columns the two are level (one row per panel, the pass is long
-    // against the exchange); at m = 4096 with 8192 rows or more the multi-kernel pass runs two workgroups per
-    // compute unit, which this kernel's registers do not allow, and wins by 4 - 10 %.
+    // 16384 x 8192, 65536 x 2048; 7 - 12 % at 4096 columns from 2048 to 16384 rows, with panels of 4 rows).
+    // Beyond 8192 columns the two are level (one row per panel, the pass is long against the exchange).
     if (pr.m > 8192) return false;
-    if (pr.m == 4096 && pr.n >= 8192) return false;
     return true;
 }
 

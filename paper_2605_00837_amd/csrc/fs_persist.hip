@@ -110,12 +110,12 @@ template <int Q, int R, bool FULLW>
 __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ctl c) {
     constexpr int T = 1024, NW = 16;
     static_assert(R * NW <= 64, "one wave merges all (row, wave) partials in one shot");
-    static_assert(5 * R <= 16, "scalar staging holds 16 dwords per wave");
+    static_assert(5 * R <= 32, "scalar staging holds 16 or 32 dwords per wave");
     constexpr int NDMA = R * Q + 5;            // prefetch loads per panel and wave (FULLW)
     constexpr float kRowHi = 1.1529215e18f;    // 2^60
     constexpr float kRowLo = 9.5367432e-07f;   // 2^-20
     __shared__ float4 stage[2][NW][R][Q][64];
-    __shared__ int scal[2][NW][16];            // [0,R) F lo  [R,2R) F hi  [2R,3R) la2 lo  [3R,4R) la2 hi  [4R,5R) a
+    __shared__ int scal[2][NW][5 * R > 16 ? 32 : 16];            // [0,R) F lo  [R,2R) F hi  [2R,3R) la2 lo  [3R,4R) la2 hi  [4R,5R) a
     __shared__ float sSum[2][R][NW];
     __shared__ double sM[2][R][NW];
     __shared__ float sS[2][R][NW];
@@ -627,9 +627,12 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
 struct PShape { int Q, R; };
 
 // the widths of the LDS-prefetch fused pass, fp32 costs: R = 2 rows per panel up to 8192 columns, else 1
-bool persist_shape(int m, PShape *s) {
+bool persist_shape(int n, int m, PShape *s) {
     if (m <= 1024 || m > 16384) return false;
-    if (m <= 4096) *s = {1, 2};
+    // 4096 columns exactly (every lane owns valid columns) and enough rows: panels of 4 rows, 64 KiB like those of
+    // 8192 columns (c3: 21.1 -> 20.3 us per iteration against panels of 2 rows, side by side)
+    if (m == 4096 && n >= 2048) *s = {1, 4};
+    else if (m <= 4096) *s = {1, 2};
     else if (m <= 8192) *s = {2, 2};
     else if (m <= 12288) *s = {3, 1};
     else *s = {4, 1};
@@ -640,8 +643,7 @@ bool persist_shape(int m, PShape *s) {
 
 bool dense_persist_supported(int n, int m, const void *C, int c_dtype) {
     PShape s;
-    (void)n;
-    return c_dtype == 0 && persist_shape(m, &s) && ((reinterpret_cast<uintptr_t>(C) & 3u) == 0);
+    return c_dtype == 0 && persist_shape(n, m, &s) && ((reinterpret_cast<uintptr_t>(C) & 3u) == 0);
 }
 
 // Workgroups of the persistent launch: one per compute unit, never more than there are panels.  0 when the
@@ -649,7 +651,7 @@ bool dense_persist_supported(int n, int m, const void *C, int c_dtype) {
 // them, so a short matrix (few panels) or a small device leaves too few workgroups for a wide one.
 int dense_persist_grid(int n, int m, int cus) {
     PShape s;
-    if (!persist_shape(m, &s) || cus < 1) return 0;
+    if (!persist_shape(n, m, &s) || cus < 1) return 0;
     const int npanels = (n + s.R - 1) / s.R;
     int g = npanels < cus ? npanels : cus;
     if (g > kWgPartLd) g = kWgPartLd;
@@ -663,7 +665,7 @@ size_t persist_scratch_bytes() { return sizeof(PersistSync) + sizeof(double) * k
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
                           int spin_limit, int final_err, const Stamp &tm) {
     PShape s;
-    if (!scratch || a.c_dtype != 0 || !persist_shape(a.p.m, &s) || nb < 1) return hipErrorInvalidValue;
+    if (!scratch || a.c_dtype != 0 || !persist_shape(a.p.n, a.p.m, &s) || nb < 1) return hipErrorInvalidValue;
     const int g = dense_persist_grid(a.p.n, a.p.m, cus);
     if (g < 1 || g > a.P) return hipErrorInvalidValue;     // the exchange buffer holds a.P sets of column sums
     {
@@ -685,7 +687,8 @@ hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void
 #endif
     const dim3 grid(g), block(1024);
     const int m = a.p.m;
-    if (s.Q == 1 && m == 4096) launch_stamped((k_persist<1, 2, true>), grid, block, st, tm, a, x, c);
+    if (s.Q == 1 && s.R == 4) launch_stamped((k_persist<1, 4, true>), grid, block, st, tm, a, x, c);
+    else if (s.Q == 1 && m == 4096) launch_stamped((k_persist<1, 2, true>), grid, block, st, tm, a, x, c);
     else if (s.Q == 1) launch_stamped((k_persist<1, 2, false>), grid, block, st, tm, a, x, c);
     else if (s.Q == 2 && m == 8192) launch_stamped((k_persist<2, 2, true>), grid, block, st, tm, a, x, c);
     else if (s.Q == 2) launch_stamped((k_persist<2, 2, false>), grid, block, st, tm, a, x, c);

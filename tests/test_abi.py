@@ -152,7 +152,7 @@ def test_kernel_choice_table_without_gpu():
     assert pick(40, 20000) == "stream" and pick(30, 16384) == "fused" and pick(30, 16385) == "stream"
     # the persistent fused pass: blocking solves, fp32, 1024 < m <= 8192, strips of at most 64 columns per workgroup
     assert pick(300, 3000) == "persist" and pick(5000, 1100) == "persist" and pick(65536, 2048) == "persist"
-    assert pick(8191, 4096) == "persist" and pick(8192, 4096) == "fused"        # two workgroups per compute unit win there
+    assert pick(8191, 4096) == "persist" and pick(16384, 4096) == "persist"     # panels of 4 rows from 2048 rows up
     assert pick(8192, 8193) == "fused" and pick(8192, 8192, blocking=False) == "fused"
     assert pick(100, 8192) == "fused"                        # 50 panels of 2 rows: strips of 164 columns
     assert pick(254, 8192) == "fused" and pick(255, 8192) == "persist"          # 127 panels: 65 columns; 128 panels: 64

@@ -45,7 +45,8 @@ def pot_err(x, ref, eps):
 # every instantiation: one to four 16-byte groups per lane, full and masked widths; ragged last panels; many
 # panels per workgroup; grids smaller than the chip; strips that are not a power of two wide
 SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (1000, 16001), (333, 12288), (260, 16384),
-          (70, 2000), (3001, 5000), (129, 4096), (200, 1028), (1100, 6001), (600, 9000)]
+          (70, 2000), (3001, 5000), (129, 4096), (200, 1028), (1100, 6001), (600, 9000),
+          (4099, 4096), (2047, 4096), (9001, 4096)]      # 4096 columns: panels of 4 rows from 2048 rows up, of 2 below
 
 
 @pytest.mark.parametrize("n,m", SHAPES)
