@@ -223,7 +223,9 @@ def bench_dense(args, name):
         traffic, src = _traffic_from_profiles(kern_name, n, m)
         out["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                           "traffic_source": (src + " (rocprofv3 --pmc runs of their own, not this run)") if src else None,
+                           "traffic_source": (src + " (rocprofv3 --pmc runs of their own, not this run; FETCH_SIZE + "
+                                                    "WRITE_SIZE count L2 <-> fabric bytes, served by the memory-side "
+                                                    "cache or by HBM alike)") if src else None,
                            "kernel": kern_name, "kernel_avg_us": kern_ms * 1e3, "kernel_launches_timed": launches,
                            "kernel_timing": "HIP events stamped with the start and stop of the dispatch, in a repeat of "
                                             "the timed solve run right after it (stamping costs queue time)",
