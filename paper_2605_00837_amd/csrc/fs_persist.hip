@@ -10,18 +10,20 @@
 //
 //   pass      every workgroup: its panels; new F, U of its rows; fp32 column sums T_j of its rows
 //   publish   the m column sums and the error terms of its rows (Sec. 4.5)
-//   wait 1    --- the first panels of the NEXT iteration are already on their way into LDS (C never changes)
+//   wait 1
 //   merge     workgroup w adds the W partial sums of ITS strip of columns in a fixed order,
 //             G_j = log2 T_j - V_j, recomputes exactly (from C and the new U) every column whose total is
 //             below 2^-66, and publishes the strip of the new G and V; every workgroup adds the same W
 //             error terms in the same order and so takes the same stop decision (Alg. 1)
-//   wait 2
+//   wait 2    --- the first panel of the NEXT iteration goes on its way into LDS as soon as the workgroup has
+//             arrived, the second right after the read (C never changes)
 //   read      every lane takes the new V of its own columns; workgroup 0 advances the solver state
 //
 // Everything exchanged is written with agent-scope stores and read with agent-scope loads (relaxed atomics,
 // or 16-byte buffer accesses with the same cache policy; no cache maintenance); every wave waits for its own
 // stores before the workgroup arrives.  Arrivals are counted in 8 group counters (monotone over a solve,
-// reset by the init kernel) that one wave per workgroup watches with one load per poll.  Every wait is bounded: a workgroup that gives up raises a flag that
+// reset by the init kernel); the workgroup that completes a group says so in one line that one wave per
+// workgroup watches with one load per poll.  Every wait is bounded: a workgroup that gives up raises a flag that
 // makes all others give up, the solve is marked as abandoned (nonfinite = 2) and the host runs the
 // multi-kernel driver instead.  The results do not depend on timing: panel ownership is static and every
 // sum has a fixed order.
