@@ -269,3 +269,20 @@ def test_persistent_pass_seeded_shape_sweep(fs, oracle, t, n, m, eps, cmax, iter
     c = 0.5 * (np.median(df) - np.median(dg))
     assert max(np.abs(df).max(), np.abs(dg).max()) / eps < TOL_F32
     assert max(np.abs(df - c).max(), np.abs(dg + c).max()) / eps < tol64, (n, m, eps, cmax, iters, warm)
+
+
+@pytest.mark.parametrize("n,m,iters", [(65536, 2048, 4), (16384, 8192, 3), (40000, 4096, 3)])
+def test_persistent_pass_many_rows(fs, oracle, n, m, iters):
+    """Hundreds of panels per workgroup (the shapes the automatic choice takes up to 16384 x 8192 and 65536 x 2048):
+    512 MiB of C, every workgroup walks its panels up on even and down on odd iterations."""
+    if not _supported(fs, n, m):
+        pytest.skip("needs more compute units than this device has")
+    w = W.random_dense(n, m, seed=8300 + m, cmax=2.0, eps=0.05)
+    ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C)
+    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, iters, 0.0, C=dev(w.C), want_f64=True)
+    assert fs.fs_kernel_choice(n, m) == "persist"
+    assert r["iters"] == iters and not r["nonfinite"]
+    assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+    assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+    err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
