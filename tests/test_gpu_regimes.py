@@ -181,3 +181,42 @@ def test_pace_hints_with_long_check_intervals(fs, oracle, check_every):
         assert r["iters"] == iters
         assert torch.equal(r["f64"], runs[0]["f64"]) and torch.equal(r["g64"], runs[0]["g64"])
     _compare(runs[0], ref, w.eps, ("check_every", check_every))
+
+
+# ------------------------------------------------------------------ degenerate inputs, automatic kernel choice
+def _degenerate(kind, n, m, rng):
+    u = lambda k: np.full(k, 1.0 / k, dtype=np.float32)
+    C = rng.random((n, m)).astype(np.float32)
+    a, b, eps = u(n), u(m), 0.05
+    if kind == "zero cost":
+        C = np.zeros((n, m), np.float32)
+    elif kind == "constant cost":
+        C, eps = np.full((n, m), 3.5, np.float32), 0.01
+    elif kind == "one-hot a":
+        a = np.zeros(n, np.float32); a[7] = 1.0
+    elif kind == "two-point b":
+        b = np.zeros(m, np.float32); b[11] = 0.25; b[m - 1] = 0.75
+    elif kind == "row and column of cost 1e6":
+        C[:, 5] = 1e6; C[3, :] = 1e6
+    elif kind == "costs up to 1e4 at eps 1":
+        C, eps = (C * 1e4).astype(np.float32), 1.0
+    elif kind == "huge eps":
+        eps = 1e3
+    return C, a, b, eps
+
+
+@pytest.mark.parametrize("kind", ["zero cost", "constant cost", "one-hot a", "two-point b", "row and column of cost 1e6",
+                                  "costs up to 1e4 at eps 1", "huge eps"])
+@pytest.mark.parametrize("n,m", [(700, 4096), (300, 8192), (2100, 2000), (150, 300)])
+def test_degenerate_inputs(fs, oracle, kind, n, m):
+    """Inputs at the edges of the method: no cost at all, all mass in one or two points (every other potential of that
+    side is then defined by Eqs. 9-10 alone), prohibitive rows and columns, huge costs and huge eps.  Whatever kernel the
+    automatic choice takes, the potentials, their finiteness pattern and the marginal error are the oracle's."""
+    C, a, b, eps = _degenerate(kind, n, m, np.random.default_rng(n + m))
+    iters = 30
+    ref = oracle.solve(a, b, eps, iters, C=C)
+    r = fs.fs_sinkhorn_solve(dev(a), dev(b), eps, iters, 0.0, C=dev(C), want_f64=True)
+    assert r["iters"] == iters
+    _compare(r, ref, eps, (kind, n, m))
+    err_ref = float(oracle.marginal_err(a, b, eps, ref["f"], ref["g"], C=C))
+    assert abs(r["marginal_err"] - err_ref) <= 1e-3 * err_ref + 5e-7
