@@ -220,3 +220,36 @@ def test_degenerate_inputs(fs, oracle, kind, n, m):
     _compare(r, ref, eps, (kind, n, m))
     err_ref = float(oracle.marginal_err(a, b, eps, ref["f"], ref["g"], C=C))
     assert abs(r["marginal_err"] - err_ref) <= 1e-3 * err_ref + 5e-7
+
+
+@pytest.mark.parametrize("kind", ["identical clouds", "all points the same", "clouds near 1000", "spread 100 at eps 1",
+                                  "duplicated source points", "eps 1e-3"])
+@pytest.mark.parametrize("n,m,d", [(3000, 2500, 3), (9000, 8200, 2), (700, 900, 8), (300, 280, 3)])
+def test_degenerate_point_clouds(fs, oracle, kind, n, m, d):
+    """Point clouds at the edges: coincident points (zero costs), clouds far from the origin (the expanded squared
+    distance |x|^2 + |y|^2 - 2 x.y cancels eight digits there: it is formed in fp64 from exact products), large spreads,
+    small eps; potentials and the cost of the resulting plan against the oracle, whatever kernel the shape gets."""
+    rng = np.random.default_rng(n + m + d)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    Y = rng.standard_normal((m, d)).astype(np.float32)
+    a, b, eps = np.full(n, 1.0 / n, np.float32), np.full(m, 1.0 / m, np.float32), 0.05
+    if kind == "identical clouds":
+        Y = np.vstack([X, X])[:m].copy()
+    elif kind == "all points the same":
+        X, Y = np.ones((n, d), np.float32), np.ones((m, d), np.float32)
+    elif kind == "clouds near 1000":
+        X, Y = X + np.float32(1000.0), Y + np.float32(1000.0)
+    elif kind == "spread 100 at eps 1":
+        X, Y, eps = X * np.float32(100.0), Y * np.float32(100.0), 1.0
+    elif kind == "duplicated source points":
+        X[1::2] = X[0::2][: len(X[1::2])]
+    else:
+        eps = 1e-3
+    iters = 25
+    ref = oracle.solve(a, b, eps, iters, X=X, Y=Y)
+    r = fs.fs_sinkhorn_solve(dev(a), dev(b), eps, iters, 0.0, X=dev(X), Y=dev(Y), want_f64=True)
+    assert r["iters"] == iters
+    _compare(r, ref, eps, (kind, n, m, d))
+    cost = float(fs.fs_cost(dev(a), dev(b), eps, r["f64"], r["g64"], X=dev(X), Y=dev(Y)).cpu()[0])
+    cost_ref = float(oracle.objectives(a, b, eps, ref["f"], ref["g"], X=X, Y=Y)["cost"])
+    assert abs(cost - cost_ref) <= 1e-4 * abs(cost_ref) + 1e-12, (cost, cost_ref)
