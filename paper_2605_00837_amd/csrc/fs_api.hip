@@ -518,6 +518,16 @@ constexpr int kFirstBlock = 2;          // blocking solves: iterations before th
 
 fs_status run_solve_async(Solve &S, float *f, float *g, fs_result *result_dev) {
     FS_HIP(S.enqueue_init());
+    if (S.persist) {
+        // the persistent pass, a block of iterations per launch; the launch that reaches max_iter evaluates the
+        // error of the last iterate itself.  A launch whose wait is abandoned marks the solve (nonfinite = 2) and
+        // everything enqueued behind it returns at once.
+        for (int it = 0; it < S.pr.max_iter; it += kPersistBlock)
+            FS_HIP(S.enqueue_persist_block(S.pr.max_iter - it < kPersistBlock ? S.pr.max_iter - it : kPersistBlock));
+        if (S.pr.max_iter == 0 && !S.opt.skip_final_err) FS_HIP(S.enqueue_trailing());
+        FS_HIP(launch_finalize(S.st, S.pots, S.state, f, g, S.opt.f64_out, S.opt.g64_out, result_dev, nullptr));
+        return FS_OK;
+    }
     // Without a host in the loop the pace hint cannot be followed: the fp32-column fused kernel takes
     // over after a fixed number of exact streaming iterations (its repair keeps it correct anyway).
     const bool two_kinds = S.fused_is_fp32_cols();
@@ -758,10 +768,12 @@ bool grid_path(const Problem &pr, const fs_options *opts, bool blocking, fs_stat
 
 // Dense fp32 problems of the widths of the LDS-prefetch fused pass run their iterations in launches of the
 // persistent form of that pass (fs_persist.hip): one workgroup per compute unit stays resident for a block of
-// iterations.  Blocking solves only (a solve that gives up is run again by the multi-kernel driver).
+// iterations.  The library's own choice in the blocking solves only (a solve that gives up is run again by the
+// multi-kernel driver); the asynchronous entry points take it on request (kernel_mode 6) and report a wait that
+// was abandoned as nonfinite = 2.
 bool persist_path(const Problem &pr, const fs_options *opts, bool blocking, int *cus) {
     const int km = opts ? opts->kernel_mode : 0;
-    if (!blocking || !pr.C || (km != 0 && km != 6)) return false;
+    if (!pr.C || (km != 0 && km != 6) || (!blocking && km != 6)) return false;
     if (!dense_persist_supported(pr.n, pr.m, pr.C, opts ? opts->cost_dtype : 0)) return false;
     *cus = device_cus();
     if (*cus < 1) return false;
@@ -936,13 +948,14 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
         return FS_OK;
     }
     if (serr != FS_OK) return serr;
-    if (opts && opts->kernel_mode == 6) {
-        set_err("kernel_mode 6 (persistent fused pass) is for the blocking solves: it needs a fallback when a wait is abandoned");
-        return FS_ERR_UNSUPPORTED;
-    }
     Solve S;
     v = setup(S, pr, opts, f, g, st, ws, ws_bytes);
     if (v != FS_OK) return v;
+    S.persist = persist_path(pr, opts, /*blocking=*/false, &S.cus);      // on request only
+    if (!S.persist && opts && opts->kernel_mode == 6) {
+        set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (n = %d, m = %d, %d compute units)", pr.n, pr.m, S.cus);
+        return FS_ERR_UNSUPPORTED;
+    }
     return run_solve_async(S, f, g, result_dev);
 }
 

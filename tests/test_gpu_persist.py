@@ -226,7 +226,7 @@ def test_persistent_pass_rejections(fs):
     with pytest.raises(fs.FsError, match="kernel_mode 6"):
         fs.fs_sinkhorn_solve(a, b, 0.05, 5, 0.0, C=C, kernel_mode=6)           # 50 panels: strips of 164 columns
     with pytest.raises(fs.FsError, match="kernel_mode 6"):
-        fs.fs_sinkhorn_dense_ex(C, a, b, 0.05, 5, 0.0, kernel_mode=6)          # blocking solves only
+        fs.fs_sinkhorn_dense_ex(C, a, b, 0.05, 5, 0.0, kernel_mode=6)          # the same through the asynchronous entry
     C16 = torch.rand((300, 4096), device="cuda").to(torch.float16)
     a3 = torch.full((300,), 1.0 / 300, device="cuda")
     b3 = torch.full((4096,), 1.0 / 4096, device="cuda")
@@ -286,3 +286,30 @@ def test_persistent_pass_many_rows(fs, oracle, n, m, iters):
     assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
     err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
     assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
+
+
+@pytest.mark.parametrize("n,m,iters", [(600, 8192, 60), (2100, 4096, 27), (300, 3000, 25), (517, 12288, 10)])
+def test_persistent_pass_on_request_in_the_asynchronous_solve(fs, oracle, n, m, iters):
+    """kernel_mode 6 through fs_sinkhorn_dense_ex (caller workspace, device-side result, no host in the loop): the same
+    launches as the blocking solve, so the same bits, and the oracle's potentials; a stop by tolerance ends it too."""
+    if not _supported(fs, n, m):
+        pytest.skip("needs more compute units than this device has")
+    import torch
+    w = W.random_dense(n, m, seed=8500 + n + m, cmax=2.0, eps=0.04)
+    C, a, b = dev(w.C), dev(w.a), dev(w.b)
+    ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C)
+    r = fs.fs_sinkhorn_solve(a, b, w.eps, iters, 0.0, C=C, kernel_mode=6)
+    h = fs.fs_sinkhorn_dense_ex(C, a, b, w.eps, iters, 0.0, kernel_mode=6)
+    res = h.result()
+    assert res["iters"] == iters and not res["nonfinite"]
+    assert torch.equal(h.f, r["f"]) and torch.equal(h.g, r["g"])
+    assert pot_err(h.f.cpu().numpy(), ref["f"], w.eps) < TOL_F32
+    assert abs(res["marginal_err"] - r["marginal_err"]) == 0.0
+    # stop rule on the device: tolerance reached at a check iteration
+    tol = float(oracle.solve(w.a, w.b, w.eps, 20, C=w.C, want_err=True, err_every_iter=True)["err_hist"][9]) * 1.5
+    tol = max(tol, 2e-6)                        # (the device's error has an fp32 floor of about 1e-7)
+    rb = fs.fs_sinkhorn_solve(a, b, w.eps, 200, tol, C=C, kernel_mode=6, check_every=10)
+    hb = fs.fs_sinkhorn_dense_ex(C, a, b, w.eps, 200, tol, kernel_mode=6, check_every=10)
+    resb = hb.result()
+    assert resb["iters"] == rb["iters"] and resb["converged"] and rb["iters"] <= 40
+    assert torch.equal(hb.f, rb["f"]) and torch.equal(hb.g, rb["g"])

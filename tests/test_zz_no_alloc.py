@@ -65,6 +65,13 @@ def test_static_scratch_entry_point_matches_the_workspace_one(fs, oracle):
     _both(fs, w3, 30, 0.0)
     w4 = W.random_dense(64, 8192, seed=9004, cmax=2.0, eps=0.05)
     _both(fs, w4, 12, 0.0)
+    # 4: the persistent fused pass on request (its counters and error terms live in the buffer too)
+    import torch
+    if torch.cuda.get_device_properties(0).multi_processor_count >= 128:
+        w5 = W.random_dense(700, 8192, seed=9005, cmax=2.0, eps=0.05)
+        f5, g5, r5 = _both(fs, w5, 30, 0.0, kernel_mode=6)
+        ref = oracle.solve(w5.a, w5.b, w5.eps, 30, C=w5.C)
+        assert max(np.abs(f5 - ref["f"]).max(), np.abs(g5 - ref["g"]).max()) / w5.eps < 1e-3
 
 
 def test_static_scratch_entry_point_rejects_what_does_not_fit(fs):
