@@ -293,7 +293,7 @@ def _result_from_device(t: torch.Tensor):
     raw = t.cpu().numpy().tobytes()
     r = fs_result.from_buffer_copy(raw)
     return dict(iters=int(r.iters), converged=bool(r.converged), nonfinite=bool(r.nonfinite),
-                marginal_err=float(r.marginal_err))
+                gave_up=r.nonfinite == 2, marginal_err=float(r.marginal_err))
 
 
 class AsyncSolve:

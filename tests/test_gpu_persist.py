@@ -313,3 +313,24 @@ def test_persistent_pass_on_request_in_the_asynchronous_solve(fs, oracle, n, m, 
     resb = hb.result()
     assert resb["iters"] == rb["iters"] and resb["converged"] and rb["iters"] <= 40
     assert torch.equal(hb.f, rb["f"]) and torch.equal(hb.g, rb["g"])
+
+
+def test_asynchronous_persistent_solve_reports_an_abandoned_wait(fs, oracle):
+    """wait_limit = 1 makes every workgroup stop waiting at once (forced from the host; every workgroup still exits):
+    the asynchronous solve has nobody to fall back for it, so it says nonfinite = 2, the launches enqueued behind the
+    abandoned one return at once, and the next solve on the same workspace is unaffected."""
+    n, m = 600, 8192
+    if not _supported(fs, n, m):
+        pytest.skip("needs more compute units than this device has")
+    import torch
+    w = W.random_dense(n, m, seed=8600, cmax=2.0, eps=0.05)
+    C, a, b = dev(w.C), dev(w.a), dev(w.b)
+    ws = torch.empty(fs.fs_workspace_bytes(n, m, 0), dtype=torch.uint8, device="cuda")
+    h = fs.fs_sinkhorn_dense_ex(C, a, b, w.eps, 80, 0.0, workspace=ws, kernel_mode=6, wait_limit=1)
+    res = h.result()
+    assert res["gave_up"] and res["nonfinite"]
+    h2 = fs.fs_sinkhorn_dense_ex(C, a, b, w.eps, 30, 0.0, workspace=ws, kernel_mode=6)
+    res2 = h2.result()
+    ref = oracle.solve(w.a, w.b, w.eps, 30, C=w.C)
+    assert res2["iters"] == 30 and not res2["nonfinite"]
+    assert pot_err(h2.f.cpu().numpy(), ref["f"], w.eps) < TOL_F32
