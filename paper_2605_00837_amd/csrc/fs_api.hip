@@ -512,7 +512,7 @@ fs_status build_block_graph(const Solve &S, hipStream_t cap, Solve::Kind kind, i
     return FS_OK;
 }
 
-constexpr int kPersistBlock = 25;       // iterations per launch of the persistent fused pass
+constexpr int kPersistBlock = 50;       // iterations per launch of the persistent fused pass
 constexpr int kAsyncExactFirst = 4;     // asynchronous solves: exact streaming iterations before the fused kernel
 constexpr int kFirstBlock = 2;          // blocking solves: iterations before the first look at the pace hint
 
