@@ -730,13 +730,14 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
     const int npanels = (n + R - 1) / R;
     const int G = gridDim.x;
     const int mine = ((int)blockIdx.x < npanels) ? (npanels - 1 - (int)blockIdx.x) / G + 1 : 0;
-    const __amdgpu_buffer_rsrc_t rsF0 = __builtin_amdgcn_make_buffer_rsrc((void *)p.F, 0, n * 8, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsF0 = __builtin_amdgcn_make_buffer_rsrc((void *)p.F, 0, p.n_ld * 8, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsF1 =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(p.F + p.n_ld), 0, n * 8, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void *)(p.F + p.n_ld), 0, p.n_ld * 8, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsL = __builtin_amdgcn_make_buffer_rsrc((void *)p.la2, 0, n * 8, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void *)p.a, 0, n * 4, 0x00020000);
     // HBM -> LDS prefetch of one panel (rows i0, i0 + 1, ...) and of its weights into staging buffer
-    // `buf`.  The buffer descriptors cover exactly the valid rows, so rows past n read as zero.
+    // `buf`.  The descriptors of C and of the weights cover exactly the valid rows, so rows past n read as zero;
+    // their old F comes from the padding of F, which holds kPadF: every term of such a row is exactly 0.
     // Per-lane offsets stay loop-invariant (lane * 8, tid * 16); everything that changes from load to
     // load goes through the scalar offset operand.  (The instruction's immediate offset is not used:
     // it would shift the LDS destination as well as the memory address.)

@@ -41,6 +41,7 @@ struct DenseArgs {
 constexpr double kFastBelow = 40.0;
 constexpr double kColRepairBelow = 60.0;  // optimistic point-cloud pass: a value this far below the old one is recomputed
 constexpr double kColMassFloor = 1.3552527156068805e-20;   // 2^-66
+constexpr double kPadF = 1e300;           // F of the rows in the padding behind the n rows (see k_init)
 constexpr double kRepairAbove = 100.0;    // optimistic point-cloud pass: fp32 sums stay finite up to 2^127
 
 // Where the row-marginal error comes from.  r_i = a_i 2^(Fnew_i - Fold_i) is the row marginal of

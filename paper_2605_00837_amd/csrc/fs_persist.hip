@@ -174,9 +174,9 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
     // still holds from the previous pass is read first).
     const int npanels = (n + R - 1) / R;
     const int mine = (npanels - 1 - w) / W + 1;        // >= 1: the grid never has more workgroups than panels
-    const __amdgpu_buffer_rsrc_t rsF0 = __builtin_amdgcn_make_buffer_rsrc((void *)p.F, 0, n * 8, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsF0 = __builtin_amdgcn_make_buffer_rsrc((void *)p.F, 0, p.n_ld * 8, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsF1 =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(p.F + p.n_ld), 0, n * 8, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void *)(p.F + p.n_ld), 0, p.n_ld * 8, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsL = __builtin_amdgcn_make_buffer_rsrc((void *)p.la2, 0, n * 8, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void *)p.a, 0, n * 4, 0x00020000);
     auto panel_row = [&](int t, bool rev) { return (w + (t == 0 ? 0 : (rev ? mine - t : t)) * W) * R; };

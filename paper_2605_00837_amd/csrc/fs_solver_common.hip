@@ -39,6 +39,14 @@ __global__ __launch_bounds__(256) void k_init(Pots p, State *state, const float 
         p.F[p.n_ld + t] = F;
         p.U[p.n_ld + t] = la - F;
     }
+    // The padding behind the n rows of F holds a reference no exponent reaches: a fused pass whose last panel
+    // is ragged reads it as the old F of the rows past n, and every term of such a row becomes exactly 0
+    // (with F = 0 there, 2^V_j overflows for large V_j and the column sums turn NaN: correct after the exact
+    // repair of every column, but many times slower).
+    if (t >= p.n && t < p.n_ld) {
+        p.F[t] = kPadF;
+        p.F[p.n_ld + t] = kPadF;
+    }
     if (t < p.m) {
         const double lb = log2_weight(p.b[t]);
         double G = 0.0;

@@ -334,3 +334,39 @@ def test_asynchronous_persistent_solve_reports_an_abandoned_wait(fs, oracle):
     ref = oracle.solve(w.a, w.b, w.eps, 30, C=w.C)
     assert res2["iters"] == 30 and not res2["nonfinite"]
     assert pot_err(h2.f.cpu().numpy(), ref["f"], w.eps) < TOL_F32
+
+
+@pytest.mark.parametrize("kernel_mode", [6, 2])
+def test_ragged_last_panel_with_large_potentials(fs, oracle, kernel_mode):
+    """A number of rows that is not a multiple of the panel height, with potentials that are large in units of eps
+    (a warm start shifted along the gauge: f - 15, g + 15 at eps = 0.05, so that every V_j exceeds 128 in base-2 units):
+    the rows past n of the last panel must contribute exactly nothing.  (They once contributed 2^V_j * 0 = NaN: right
+    after the exact repair of every column, but many times slower; hence the comparison of the two solve times beside
+    the comparison with the oracle.)"""
+    import time
+    import torch
+    iters = 12
+    times = {}
+    for n in (1200, 1201):
+        if not _supported(fs, n, 4096):
+            pytest.skip("needs more compute units than this device has")
+        w = W.random_dense(n, 4096, seed=8700, cmax=2.0, eps=0.05)
+        C, a, b = dev(w.C), dev(w.a), dev(w.b)
+        start = oracle.solve(w.a, w.b, w.eps, 3, C=w.C)
+        f0, g0 = start["f"] - 15.0, start["g"] + 15.0
+        ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C, f0=f0, g0=g0)
+        kw = dict(warm_start=True, f64_in=dev(f0), g64_in=dev(g0))
+        best = 1e9
+        for rep in range(4):
+            f32, g32 = dev(f0.astype(np.float32)), dev(g0.astype(np.float32))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            r = fs.fs_sinkhorn_solve(a, b, w.eps, iters, 0.0, C=C, f=f32, g=g32, want_f64=True,
+                                     kernel_mode=kernel_mode, **kw)
+            torch.cuda.synchronize()
+            best = min(best, time.perf_counter() - t0)
+        times[n] = best
+        assert r["iters"] == iters and not r["nonfinite"]
+        assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+        assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+    assert times[1201] < 2.0 * times[1200] + 2e-4, times
