@@ -299,7 +299,7 @@ struct Solve {
     }
 
     const char *dominant_kernel() const {
-        if (persist) return "k_persist";
+        if (persist) return dense_persist_resident(pr.n, pr.m, cus < L.P_fused ? cus : L.P_fused, opt.fused_variant % 100) ? "k_resident" : "k_persist";
         return mode == 1 ? "k_row_stream" : mode == 2 ? (fused_is_fp32_cols() ? "k_fused_pf" : "k_fused") : "k_points_lse";
     }
     // a block of up to nb iterations in one launch of the persistent fused pass
@@ -310,7 +310,8 @@ struct Solve {
         DenseArgs a = dense(FUSED);
         a.P = L.P_fused;                       // sets of column sums the exchange buffer holds
         const int cu = cus < L.P_fused ? cus : L.P_fused;
-        return launch_persist(st, a, ctl(0), ws + L.o_persist, cu, nb, opt.wait_limit, opt.skip_final_err ? 0 : 1, tm);
+        return launch_persist(st, a, ctl(0), ws + L.o_persist, cu, nb, opt.wait_limit, opt.skip_final_err ? 0 : 1,
+                              opt.fused_variant % 100, tm);
     }
     // Eq. 9.  t0/t1 (optional) are stamped by the runtime with the start and stop of the dominant kernel
     // of the iteration: the row pass, the fused pass, or the point-cloud LSE pass of the f-update.

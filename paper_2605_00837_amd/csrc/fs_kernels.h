@@ -260,8 +260,15 @@ struct PersistArgs {
 bool dense_persist_supported(int n, int m, const void *C, int c_dtype);
 int dense_persist_grid(int n, int m, int cus);   // workgroups of the launch on a device with `cus` compute units
 size_t persist_scratch_bytes();
+// variant 0: the resident form (fs_resident.hip) where the workgroups can hold their share of C, else the
+// streaming form; 1: always the streaming form
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
-                          int spin_limit, int final_err, const Stamp &tm = Stamp());
+                          int spin_limit, int final_err, int variant, const Stamp &tm = Stamp());
+bool dense_persist_resident(int n, int m, int cus, int variant);   // which of the two forms launch_persist takes
+// fs_resident.hip: the same iteration with the workgroup's share of C held in LDS and registers for the whole launch
+bool dense_resident_fits(int n, int m, int grid);
+hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs &x, const Ctl &c, int grid,
+                           const Stamp &tm);
 
 bool grid_supported(int n, int m, int wmax, bool points);   // wmax: workgroups that can be resident at once (compute units)
 size_t grid_scratch_bytes();

@@ -30,70 +30,11 @@
 #include <cstdlib>
 
 #include "fs_kernels.h"
+#include "fs_persist_sync.h"
 
 namespace fs {
 
 namespace {
-
-__device__ __forceinline__ void pub_f64(double *p, double v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ double get_f64(const double *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float get_f32(const float *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// two adjacent floats at an 8-byte boundary as one store
-__device__ __forceinline__ void pub_f32x2(float *p, float x, float y) {
-    const unsigned long long v = (unsigned long long)__float_as_uint(x) | ((unsigned long long)__float_as_uint(y) << 32);
-    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Grid-wide wait number `gen`, in two halves called by all 64 lanes of ONE wave while the others are parked at
-// barriers, after every wave's published stores have been acknowledged.
-//   grid_arrive  lane 0 counts the workgroup into its group's counter (the value comes back later);
-//   grid_wait    the workgroup that completed its group writes `gen` into the group's word of the `done`
-//                line; lanes 0..7 watch one word of that line each and lane 8 the abort flag next to them, with
-//                ONE load instruction (one memory request) per poll.  Everything only grows.
-// grid_wait returns 0 when the wait was abandoned (by this workgroup or by another).
-__device__ __forceinline__ unsigned long long grid_arrive(PersistSync *sy) {
-    unsigned long long old = 0ull;
-    if ((threadIdx.x & 63) == 0)
-        old = __hip_atomic_fetch_add(&sy->grp[blockIdx.x & 7].v, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return old;
-}
-__device__ __forceinline__ int grid_wait(PersistSync *sy, unsigned long long old, unsigned long long gen, int W,
-                                         int spin_limit) {
-    const int lane = threadIdx.x & 63;
-    if (lane == 0) {
-        const int grp = blockIdx.x & 7;
-        const unsigned long long members = (unsigned long long)((W - grp + 7) / 8);
-        if (old + 1ull == gen * members)
-            __hip_atomic_store(&sy->done[grp], gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    const int groups = W < 8 ? W : 8;
-    const unsigned long long *watch = lane < 8 ? &sy->done[lane] : &sy->abort_flag;
-    int good = 1, spins = 0;
-    for (;;) {
-        unsigned long long v = 0ull;
-        if (lane <= 8) v = __hip_atomic_load(watch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const bool reached = lane < groups ? v >= gen : true;
-        const bool aborted = lane == 8 && v != 0ull;
-        if (__any(aborted) || ++spins > spin_limit) {
-            good = 0;
-            if (lane == 0) __hip_atomic_store(&sy->abort_flag, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            break;
-        }
-        if (__all(reached)) break;
-        __builtin_amdgcn_s_sleep(1);
-    }
-    return good;
-}
-
-constexpr int kWgPartLd = 512;          // slots of the per-workgroup exchange array
-constexpr int kAgent = 16;              // cache policy of a buffer load / store that other workgroups must see: sc1
-typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 // Debug builds (-DFS_PERSIST_TRACE) stamp the phases of one iteration per workgroup with the 100 MHz clock.
 #ifdef FS_PERSIST_TRACE
@@ -664,8 +605,12 @@ int dense_persist_grid(int n, int m, int cus) {
 
 size_t persist_scratch_bytes() { return sizeof(PersistSync) + sizeof(double) * kWgPartLd; }
 
+bool dense_persist_resident(int n, int m, int cus, int variant) {
+    return variant != 1 && dense_resident_fits(n, m, dense_persist_grid(n, m, cus));
+}
+
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
-                          int spin_limit, int final_err, const Stamp &tm) {
+                          int spin_limit, int final_err, int variant, const Stamp &tm) {
     PShape s;
     if (!scratch || a.c_dtype != 0 || !persist_shape(a.p.n, a.p.m, &s) || nb < 1) return hipErrorInvalidValue;
     const int g = dense_persist_grid(a.p.n, a.p.m, cus);
@@ -687,6 +632,7 @@ hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void
     x.trace = nullptr;
     if (const char *tp = getenv("FS_TRACE_PTR")) x.trace = reinterpret_cast<long long *>(strtoull(tp, nullptr, 0));
 #endif
+    if (variant != 1 && dense_resident_fits(a.p.n, a.p.m, g)) return launch_resident(st, a, x, c, g, tm);
     const dim3 grid(g), block(1024);
     const int m = a.p.m;
     if (s.Q == 1 && s.R == 4) launch_stamped((k_persist<1, 4, true>), grid, block, st, tm, a, x, c);

@@ -1,0 +1,485 @@
+// Resident form of the persistent fused pass (Alg. 1, Eqs. 9-10): a block of Sinkhorn iterations in ONE launch
+// during which the cost matrix never leaves the chip.
+//
+// A compute unit of this device has 160 KiB of LDS and 512 KiB of vector registers.  With one workgroup of 512
+// lanes per compute unit (two waves per SIMD, 256 registers per lane), a share of up to 4 panels of 64 KiB
+// (256 KiB: a 64 MiB matrix on 256 compute units, 4096 x 4096 or 2048 x 8192) is read from memory ONCE per
+// launch -- panels 0 and 1 into LDS, panels 2 and 3 into 64 registers per lane -- and every iteration of the
+// block runs its row and column phase from there.  The iteration is then bound by the vector ALUs (about 12
+// instructions per entry) and by the exchange, not by the memory system; the persistent pass that streams C
+// (fs_persist.hip) reads it from the last-level cache every iteration.  (1024 lanes with 128 registers each
+// hold the same bytes, but 32 of 128 registers for the panels leave the hot loop short: the compiler then keeps
+// V in scratch memory and the pass is slower than the streaming one.)
+//
+// Everything else is the persistent pass: the same optimistic row phase with its exact redo, the same fp32
+// column sums, the same exchange between two bounded grid-wide waits (publish, merge of the own strip with the
+// exact repair of columns below 2^-66, new G and V, read), the same stop rule (Alg. 1), the same trailing row
+// phase for the error of the last iterate (Sec. 4.5), the same fixed orders of every sum.  The old F of the
+// workgroup's rows stays in LDS as well (two parities); F and U still go to memory every iteration, for the
+// repairs in other workgroups and for whatever runs after this launch.
+#include "fs_kernels.h"
+#include "fs_persist_sync.h"
+
+namespace fs {
+
+namespace {
+
+constexpr int kResPanels = 4;           // panels a workgroup holds: kResLds in LDS, the others in registers
+constexpr int kResLds = 2;
+
+// Q groups of 4 adjacent columns per lane (column(q, e) = (q 512 + tid) 4 + e), R rows per panel, m = 2048 Q
+// (every lane owns valid columns), R Q = 8 (a panel is 64 KiB: 32 entries per lane).
+template <int Q, int R>
+__global__ __launch_bounds__(512) void k_resident(DenseArgs A, PersistArgs X, Ctl c) {
+    constexpr int NW = 8, T = 64 * NW, NP = kResPanels, NL = kResLds;
+    constexpr int LW = 16;                     // lanes per row in the merge of the wave sums: NW partials, then zeros
+    static_assert(R * Q == 8, "a panel is 32 entries per lane");
+    static_assert(R * LW <= 64, "one wave merges all (row, wave) partials in one shot");
+    static_assert(NP * R <= 64, "one wave loads the row scalars");
+    constexpr float kRowHi = 1.1529215e18f;    // 2^60
+    constexpr float kRowLo = 9.5367432e-07f;   // 2^-20
+    __shared__ float4 stage[NL][NW][R][Q][64]; // panels 0 .. NL-1, every wave its own slice
+    __shared__ double sF[2][NP][R];            // F of this workgroup's rows by parity of the iteration; kPadF past n
+    __shared__ double sLa2[NP][R];
+    __shared__ float sA[NP][R];
+    __shared__ float sSum[NP][R][NW];
+    __shared__ double sM[R][NW];               // exact redo: row maxima by wave
+    __shared__ double sMr[NW];                 // exact repair of a column: running pairs by wave
+    __shared__ float sSr[NW];
+    __shared__ double sPart[T];                // merge: partial totals by (set group, column)
+    __shared__ int sSus[T];                    // merge: columns of this round to recompute exactly
+    __shared__ int sNsus, sOk;
+    __shared__ unsigned long long sGen;
+    __shared__ double sErrTot;
+#if defined(__HIP_DEVICE_COMPILE__)
+    const Pots &p = A.p;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const double ns = -p.s;
+    const int m = p.m, n = p.n;
+    const int W = gridDim.x, w = blockIdx.x;
+    const int rr = lane / LW, ww = lane % LW;  // the panel row and the wave whose partial this lane takes in the merge
+    const int rc = rr < R ? rr : R - 1;
+    const int wc = ww < NW ? ww : NW - 1;
+
+    int k;
+    if (!launch_active(c, k)) return;
+    const int k_end = min(k + X.nb, c.max_iter);
+    // the launch that reaches max_iter goes on with one more row phase: it yields err of the last iterate
+    const bool with_trailing = X.final_err != 0 && k_end == c.max_iter;
+
+    // This workgroup owns the panels w, w + W, ... (at most NP: the launcher sees to it), in every iteration.
+    const int npanels = (n + R - 1) / R;
+    const int mine = (npanels - 1 - w) / W + 1;
+    if (tid == 0) {
+        // waits completed so far in this solve: the generation numbers of this launch go on from there
+        sGen = __hip_atomic_load(&X.sync->done[w & 7], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sNsus = 0;
+    }
+    if (tid < NP * R) {
+        const int t = tid / R, r = tid % R;
+        const int row = (w + t * W) * R + r;
+        const bool ok = t < mine && row < n;
+        sF[k & 1][t][r] = ok ? p.F[(size_t)(k & 1) * p.n_ld + row] : kPadF;
+        sF[(k & 1) ^ 1][t][r] = kPadF;         // (rows of this workgroup: written before it is read)
+        sLa2[t][r] = ok ? p.la2[row] : -__builtin_huge_val();
+        sA[t][r] = ok ? p.a[row] : 0.0f;
+    }
+    // ---- the workgroup's share of C, once: memory -> LDS without passing through registers (panels 0 .. NL-1),
+    //      memory -> registers (the others).  The descriptors cover exactly the valid rows: rows past n read as 0.
+    float creg[NP - NL][R][Q][4];
+#pragma unroll
+    for (int t = 0; t < NP; ++t) {
+        const int i0 = (w + t * W) * R;
+        const int rows = t < mine ? ((n - i0) < R ? (n - i0) : R) : 0;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)((const char *)A.C + (size_t)(t < mine ? i0 : 0) * m * 4), 0, rows * m * 4, 0x00020000);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                if (t < NL) {
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, &stage[t][wave][r][q][0], 16, tid * 16,
+                                                             (r * m + q * T * 4) * 4, 0, 0);
+                } else {
+                    const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, tid * 16, (r * m + q * T * 4) * 4, 0);
+                    float (&cr)[4] = creg[t < NL ? 0 : t - NL][r][q];
+                    cr[0] = __uint_as_float(x.x); cr[1] = __uint_as_float(x.y);
+                    cr[2] = __uint_as_float(x.z); cr[3] = __uint_as_float(x.w);
+                }
+            }
+    }
+    // V of this lane's columns (written before this launch)
+    double v[Q][4];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int col = (q * T + tid) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[q][e] = p.V[(size_t)(k & 1) * p.m_ld + col + e];
+    }
+    // The strip of columns this workgroup merges: Sw columns (a multiple of 4, at most 64: the launcher sees to
+    // it).  The exchange buffer is laid out by destination: [strip][source workgroup][Swp floats], Swp = Sw
+    // rounded up to a power of two, so that a workgroup reads all it has to merge as ONE contiguous block.
+    const int Sw = (((m + W - 1) / W) + 3) & ~3;
+    const int strip0 = min(m, w * Sw), strip1 = min(m, strip0 + Sw);
+    int lgSwp = 2;
+    while ((1 << lgSwp) < Sw) ++lgSwp;
+    const int lgQN = lgSwp - 2, QN = 1 << lgQN;        // QN 16-byte chunks per source set
+    float *xchg = reinterpret_cast<float *>(A.colpart);
+    // the column whose total this thread finishes in the merge
+    const int own_col = strip0 + tid;
+    const bool own_ok = tid < Sw && own_col < strip1;
+
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));         // the LDS panels have landed
+    __syncthreads();
+    unsigned long long gen = sGen;
+
+    bool alive = true;
+    for (;;) {
+        const int cur = k & 1, nxt = cur ^ 1;
+        const bool trailing = k == c.max_iter;       // row phase only: the error of the last iterate
+        float cS[Q][4];                              // column sums of the plan entries of this workgroup's rows
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) cS[q][e] = 0.0f;
+        double err_acc = 0.0;                        // error terms of this workgroup's rows (lanes that own a row)
+
+#pragma unroll
+        for (int t = 0; t < NP; ++t) {
+            if (t < mine) {
+                const int i0 = (w + t * W) * R;
+                const bool rowok = rr < R && (i0 + rr) < n;
+                const double rho_lane = sF[cur][t][rc];
+                const double la2_lane = rowok ? sLa2[t][rc] : -__builtin_huge_val();
+                const float a_lane = rowok ? sA[t][rc] : 0.0f;
+                double rho[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) rho[r] = sF[cur][t][r];
+                // the 4 entries (r, q, .) of this panel as fp64 values: from LDS, or from the lane's registers (through a
+                // compiler barrier: every use converts the 4-byte register afresh; without it the converted values of
+                // all register panels are kept over the iteration loop, in twice the registers)
+                auto cost4 = [&](int r, int q, double (&o)[4]) {
+                    if (t < NL) {
+                        const float4 c4 = stage[t < NL ? t : 0][wave][r][q][lane];
+                        o[0] = (double)c4.x; o[1] = (double)c4.y; o[2] = (double)c4.z; o[3] = (double)c4.w;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = cost_f64(creg[t < NL ? 0 : t - NL][r][q][e]);
+                    }
+                };
+                // ---- row phase, optimistic: e = 2^(x - rho_r), summed
+                float ev[R][Q][4];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float acc = 0.0f;
+#pragma unroll
+                    for (int q = 0; q < Q; ++q) {
+                        double cvv[4];
+                        cost4(r, q, cvv);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            ev[r][q][e] = fast_exp2((float)(fma(ns, cvv[e], v[q][e]) - rho[r]));
+                            acc += ev[r][q][e];
+                        }
+                    }
+                    acc = wave_sum_f32(acc);
+                    if (lane == 0) sSum[t][r][wave] = acc;
+                }
+                lds_only_barrier();
+                float S = rr < R ? (ww < NW ? sSum[t][rc][wc] : 0.0f) : 1.0f;
+                S += dpp_f32<0x128>(S);
+                S += dpp_f32<0x124>(S);
+                S += dpp_f32<0x122>(S);
+                S += dpp_f32<0x121>(S);
+                const bool fine = (S >= kRowLo) && (S <= kRowHi);    // false for NaN / inf / 0
+                // pi_ij = e_ij * a_i / S_i.  Every wave needs a_i / S_i (reciprocal, one Newton step, product: within
+                // 1.5 ulp); the new F = reference + log2 S is formed by the one wave that stores it, further down.
+                double Fbase = rho_lane;
+                float Ssum = S;
+                float alpha_lane;
+                {
+                    float rcp = __builtin_amdgcn_rcpf(S);
+                    rcp = fmaf(fmaf(-S, rcp, 1.0f), rcp, rcp);
+                    alpha_lane = a_lane * rcp;
+                }
+                if (__builtin_expect(!__all(fine || !rowok), 0)) {
+                    // ---- exact redo of the row phase of this panel (uniform over the workgroup): Eq. 8 as written,
+                    //      the maximum of the row first (no exponentials), then the sum relative to it
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        double mx = kNegHuge;
+#pragma unroll
+                        for (int q = 0; q < Q; ++q) {
+                            double cvv[4];
+                            cost4(r, q, cvv);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) mx = dmax(mx, fma(ns, cvv[e], v[q][e]));
+                        }
+                        mx = wave_max_f64(mx);
+                        if (lane == 0) sM[r][wave] = mx;
+                    }
+                    lds_only_barrier();                              // (every wave has read sSum by now)
+                    double Mg = rr < R && ww < NW ? sM[rc][wc] : kNegHuge;
+                    Mg = dmax(Mg, dpp_f64<0x128>(Mg));
+                    Mg = dmax(Mg, dpp_f64<0x124>(Mg));
+                    Mg = dmax(Mg, dpp_f64<0x122>(Mg));
+                    Mg = dmax(Mg, dpp_f64<0x121>(Mg));
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const double Mr = bcast_f64(Mg, r * LW);
+                        float acc = 0.0f;
+#pragma unroll
+                        for (int q = 0; q < Q; ++q) {
+                            double cvv[4];
+                            cost4(r, q, cvv);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                ev[r][q][e] = fast_exp2((float)(fma(ns, cvv[e], v[q][e]) - Mr));
+                                acc += ev[r][q][e];
+                            }
+                        }
+                        acc = wave_sum_f32(acc);
+                        if (lane == 0) sSum[t][r][wave] = acc;
+                    }
+                    lds_only_barrier();                              // (and every wave has read sM)
+                    float sg = rr < R ? (ww < NW ? sSum[t][rc][wc] : 0.0f) : 1.0f;
+                    sg += dpp_f32<0x128>(sg);
+                    sg += dpp_f32<0x124>(sg);
+                    sg += dpp_f32<0x122>(sg);
+                    sg += dpp_f32<0x121>(sg);
+                    Fbase = Mg;
+                    Ssum = sg;
+                    alpha_lane = a_lane / sg;                          // e is relative to the row maximum: pi = e a / sum
+                }
+                if (wave == 0 && ww == 0 && rowok) {
+                    // the new F stays in LDS (the old F of the same rows in the next iteration) and goes to memory for
+                    // whatever runs after this launch; U is what a repair in another workgroup reads
+                    const double Fn_lane = Fbase + log2_sum(Ssum);
+                    int row = i0 + rr;
+                    asm volatile("" : "+v"(row));          // (addresses formed here, not kept in registers over the loop)
+                    sF[nxt][t][rr] = Fn_lane;
+                    p.F[(size_t)nxt * p.n_ld + row] = Fn_lane;
+                    pub_f64(p.U + (size_t)nxt * p.n_ld + row, la2_lane - Fn_lane);
+                    // error term of Sec. 4.5 for the iterate this iteration started from: a_i |2^(Fnew - Fold) - 1|
+                    if (a_lane > 0.0f) err_acc += (double)a_lane * fabs(exp2m1(Fn_lane - rho_lane));
+                }
+                // ---- column phase with the new f (the trailing round does it too: its sums are simply not published)
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float alpha = bcast_f32(alpha_lane, r * LW);
+                    if (!(alpha == alpha) || (i0 + r) >= n) alpha = 0.0f;   // rows past n, or a row whose F is not finite
+#pragma unroll
+                    for (int q = 0; q < Q; ++q)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) cS[q][e] = fmaf(ev[r][q][e], alpha, cS[q][e]);
+                }
+            }
+        }
+
+        // ---- publish: column sums of this workgroup's rows (16-byte stores), and the error terms of its rows
+        {
+            // where a group of 4 column sums goes: strip col / Sw, this workgroup's set, column col mod Sw
+            const __amdgpu_buffer_rsrc_t rsX =
+                __builtin_amdgcn_make_buffer_rsrc((void *)xchg, 0, ((W * W) << lgSwp) * 4, 0x00020000);
+            if (!trailing)
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int col = (q * T + tid) * 4;
+                const int dest = col / Sw;
+                const v4u pk = {__float_as_uint(cS[q][0]), __float_as_uint(cS[q][1]), __float_as_uint(cS[q][2]),
+                                __float_as_uint(cS[q][3])};
+                __builtin_amdgcn_raw_buffer_store_b128(pk, rsX, ((((dest * W + w) << lgSwp) + (col - dest * Sw))) * 4, 0,
+                                                       kAgent);
+            }
+            if (wave == 0) {
+                const double e = wave_sum_f64(err_acc);
+                if (lane == 0) pub_f64(X.wgpart + w, e);
+            }
+        }
+        // the old V of the column this thread will finish in the merge
+        double myV = 0.0, myLb = 0.0;
+        if (own_ok) {
+            myV = get_f64(p.V + (size_t)cur * p.m_ld + own_col);
+            myLb = p.lb2[own_col];
+        }
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));     // this wave's stores have been acknowledged
+        lds_only_barrier();                            // ... and so have every wave's
+        ++gen;
+        if (wave == 0) {
+            const unsigned long long old = grid_arrive(X.sync);
+            const int ok = grid_wait(X.sync, old, gen, W, X.spin_limit);
+            if (lane == 0) sOk = ok;
+        }
+        lds_only_barrier();
+        if (!sOk) { alive = false; break; }
+
+        // ---- merge of this workgroup's strip; beside it, the error of the iterate this iteration started from
+        //      (the same W terms in the same order in every workgroup, so that all take the same decision)
+        {
+            double *Vn = p.V + (size_t)nxt * p.m_ld, *Gn = p.G + (size_t)nxt * p.m_ld;
+            const double *Un = p.U + (size_t)nxt * p.n_ld;
+            // error terms of all workgroups: lane l of the last wave takes the terms 4 l .. 4 l + 3 (two 16-byte loads;
+            // slots past the grid read as zero)
+            v4u ep0 = {0u, 0u, 0u, 0u}, ep1 = {0u, 0u, 0u, 0u};
+            if (wave == NW - 1) {
+                const __amdgpu_buffer_rsrc_t rsE = __builtin_amdgcn_make_buffer_rsrc((void *)X.wgpart, 0, W * 8, 0x00020000);
+                ep0 = __builtin_amdgcn_raw_buffer_load_b128(rsE, lane * 32, 0, kAgent);
+                ep1 = __builtin_amdgcn_raw_buffer_load_b128(rsE, lane * 32 + 16, 0, kAgent);
+            }
+            // Chunk c of the block (16 bytes: 4 adjacent columns of one source set) belongs to set c / QN and
+            // column group c % QN; thread t takes the chunks t, t + T, ..., i.e. always the same column group.
+            // Four loads are in flight at a time; chunks past the end of the block read as zero.
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            const int nchunks = trailing ? 0 : W << lgQN;
+            const __amdgpu_buffer_rsrc_t rsMine = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(xchg + ((size_t)(w * W) << lgSwp)), 0, (W << lgSwp) * 4, 0x00020000);
+            for (int ch = tid; ch < nchunks; ch += 4 * T) {
+                v4u x[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) x[u] = __builtin_amdgcn_raw_buffer_load_b128(rsMine, (ch + u * T) * 16, 0, kAgent);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    acc[0] += (double)__uint_as_float(x[u].x); acc[1] += (double)__uint_as_float(x[u].y);
+                    acc[2] += (double)__uint_as_float(x[u].z); acc[3] += (double)__uint_as_float(x[u].w);
+                }
+            }
+            double epart = (__hiloint2double((int)ep0.y, (int)ep0.x) + __hiloint2double((int)ep0.w, (int)ep0.z)) +
+                           (__hiloint2double((int)ep1.y, (int)ep1.x) + __hiloint2double((int)ep1.w, (int)ep1.z));
+            // lanes with the same column group (lane mod QN) meet inside the wave, in a fixed order
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                double t4 = acc[e];
+                if (lgQN <= 0) t4 += dpp_f64<0x121>(t4);
+                if (lgQN <= 1) t4 += dpp_f64<0x122>(t4);
+                if (lgQN <= 2) t4 += dpp_f64<0x124>(t4);
+                if (lgQN <= 3) t4 += dpp_f64<0x128>(t4);
+                if (lgQN <= 4) t4 += swz16_f64(t4);
+                t4 += xor32_f64(t4);
+                acc[e] = t4;
+            }
+            if (lane < QN) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sPart[(wave << lgSwp) + lane * 4 + e] = acc[e];
+            }
+            if (wave == NW - 1) {
+                epart = wave_sum_f64(epart);
+                if (lane == 0) sErrTot = epart;
+            }
+            lds_only_barrier();
+            if (own_ok && !trailing) {
+                double tot = 0.0;
+#pragma unroll
+                for (int w2 = 0; w2 < NW; ++w2) tot += sPart[(w2 << lgSwp) + tid];
+                // a column whose total mass is below 2^-66 (or not a number) may have lost terms to fp32
+                // underflow: it is recomputed exactly below
+                if (!(tot >= kColMassFloor)) {
+                    sSus[atomicAdd(&sNsus, 1)] = own_col;
+                } else {
+                    const double out = log2_sum(tot) - myV;
+                    pub_f64(Gn + own_col, out);
+                    pub_f64(Vn + own_col, myLb - out);
+                }
+            }
+            lds_only_barrier();
+            const int nsus = sNsus;
+            for (int q = 0; q < nsus; ++q) {
+                const int jj = sSus[q];
+                Lse ex; ex.init();
+                for (int i = tid; i < n; i += T) {
+                    double y[1] = {fma(ns, (double)A.C[(size_t)i * m + jj], get_f64(Un + i))};
+                    ex.add<1>(y);
+                }
+                ex.wave_reduce();
+                if (lane == 0) { sMr[wave] = ex.M; sSr[wave] = ex.s; }
+                lds_only_barrier();
+                if (tid == 0) {
+                    Lse tl; tl.init();
+#pragma unroll
+                    for (int w2 = 0; w2 < NW; ++w2) tl.merge(sMr[w2], sSr[w2]);
+                    const double out = tl.value();
+                    pub_f64(Gn + jj, out);
+                    pub_f64(Vn + jj, p.lb2[jj] - out);
+                }
+                lds_only_barrier();                    // sMr is free again
+            }
+            if (tid == 0) sNsus = 0;                   // everyone has read it (a barrier lies behind every read)
+        }
+        const double err = sErrTot;
+        if (trailing) {
+            // nothing left to run: err of the last iterate closes the solve (potentials: F[cur], G[cur])
+            if (w == 0 && tid == 0) {
+                Ctl ct = c;
+                ct.phase = 1;
+                advance_state(ct, k, err, 0.0);
+            }
+            break;
+        }
+        if (c.tol > 0.0 && k >= 1 && (k % c.check_every == 0) && err < c.tol) {
+            // stop at k (Alg. 1): F[cur], G[cur] still hold iterate k; what the merge wrote is the other buffer
+            if (w == 0 && tid == 0) advance_state(c, k, err, 0.0);
+            break;
+        }
+        ++gen;
+        if (wave == 0) {
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0)); // the strip's new G and V (all published by this wave) are acknowledged
+            const unsigned long long old2 = grid_arrive(X.sync);
+            const int ok = grid_wait(X.sync, old2, gen, W, X.spin_limit);
+            if (lane == 0) {
+                sOk = ok;
+                if (ok && w == 0) advance_state(c, k, err, 0.0);      // k + 1 iterations are complete
+            }
+        }
+        lds_only_barrier();
+        if (!sOk) { alive = false; break; }
+        // ---- the new V of this lane's columns (16-byte loads, two values each)
+        {
+            const __amdgpu_buffer_rsrc_t rsV = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(p.V + (size_t)nxt * p.m_ld), 0, p.m_ld * 8, 0x00020000);
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int col = (q * T + tid) * 4;
+                const v4u lo = __builtin_amdgcn_raw_buffer_load_b128(rsV, col * 8, 0, kAgent);
+                const v4u hi = __builtin_amdgcn_raw_buffer_load_b128(rsV, col * 8 + 16, 0, kAgent);
+                v[q][0] = __hiloint2double((int)lo.y, (int)lo.x);
+                v[q][1] = __hiloint2double((int)lo.w, (int)lo.z);
+                v[q][2] = __hiloint2double((int)hi.y, (int)hi.x);
+                v[q][3] = __hiloint2double((int)hi.w, (int)hi.z);
+            }
+        }
+        ++k;
+        if (k >= k_end && !(k == k_end && with_trailing)) break;
+    }
+    if (!alive && tid == 0) {
+        // abandoned: mark the solve as such and stop everything that was enqueued behind this launch
+        atomicOr(&c.st->nonfinite, kGaveUp);
+        atomicOr(&c.st->flags, kFlagDone);
+        if (c.host_flag) {
+            *c.host_flag = 1;
+            __threadfence_system();
+        }
+    }
+#endif
+}
+
+}  // namespace
+
+// The shapes the resident pass takes: fp32 costs, every lane with valid columns (4096 or 8192 columns) and at
+// most kResPanels panels of 64 KiB per workgroup of a grid of `grid` workgroups.
+bool dense_resident_fits(int n, int m, int grid) {
+    if (grid < 1 || (m != 4096 && m != 8192)) return false;
+    const int R = m == 4096 ? 4 : 2;
+    const long long npanels = ((long long)n + R - 1) / R;
+    return npanels >= grid && npanels <= (long long)kResPanels * grid;    // every workgroup owns 1 .. kResPanels panels
+}
+
+hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs &x, const Ctl &c, int grid,
+                           const Stamp &tm) {
+    if (a.c_dtype != 0 || !dense_resident_fits(a.p.n, a.p.m, grid)) return hipErrorInvalidValue;
+    const dim3 g(grid), block(512);
+    if (a.p.m == 4096) launch_stamped((k_resident<2, 4>), g, block, st, tm, a, x, c);
+    else launch_stamped((k_resident<4, 2>), g, block, st, tm, a, x, c);
+    return hipGetLastError();
+}
+
+}  // namespace fs
