@@ -231,6 +231,19 @@ def bench_dense(args, name):
                                             "the timed solve run right after it (stamping costs queue time)",
                            "iterations_per_launch": covered / max(launches, 1), "kernel_us_per_iteration": per_iter_ms * 1e3,
                            "algorithmic_bytes_per_launch": alg_bytes_launch}
+        if kern_name == "k_resident":
+            # C stays in LDS and registers for a whole launch: the algorithmic bytes above are NOT read from memory
+            # (achieved / frac say how this compares with a pass that would stream them).  What bounds the pass is
+            # vector-ALU issue: 8 issue slots per entry (cvt, fma64, add64, cvt, v_exp_f32 = 2, add, fma) of 4 cycles
+            # per wave instruction on 1024 SIMDs at 2.4 GHz.
+            peak_entries = 1024 * 2.4e9 * 64 / (8 * 4)
+            ach_entries = n * m / (per_iter_ms * 1e-3)
+            out["roofline"]["resident"] = {
+                "note": "the workgroups hold C in LDS and registers for a whole launch: nothing of size n x m is read "
+                        "from memory inside an iteration; the pass is bound by vector-ALU issue, the iteration by the "
+                        "pass plus the grid-wide exchange",
+                "bound": "alu", "achieved": ach_entries, "peak": peak_entries, "unit": "entries/s",
+                "frac": ach_entries / peak_entries}
     else:
         # the whole solve runs inside one launch that keeps C in registers: latency-bound, no roofline fraction claimed
         out["roofline"] = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,

@@ -36,16 +36,6 @@ namespace fs {
 
 namespace {
 
-// Debug builds (-DFS_PERSIST_TRACE) stamp the phases of one iteration per workgroup with the 100 MHz clock.
-#ifdef FS_PERSIST_TRACE
-#define FS_TRACE(slot) do { if (lane == 0 && X.trace) { \
-        const long long now_ = (long long)__builtin_amdgcn_s_memrealtime(); \
-        if (X.trace[65536 + 8191] < 0 ? k == 0 : k == k_end - 2) X.trace[(w * 16 + wave) * 8 + (slot)] = now_; \
-        if ((slot) <= 1 && wave == 0 && (w == 0 || w == 100) && k < 2000) X.trace[65536 + (w ? 4096 : 0) + 2 * k + (slot)] = now_; } } while (0)
-#else
-#define FS_TRACE(slot) do { } while (0)
-#endif
-
 // Q groups of 4 adjacent columns per lane (column(q, e) = (q 1024 + tid) 4 + e), R rows per panel.
 // FULLW: m == 4096 Q, every lane owns valid columns; then two panels are in flight and the waits on the
 // prefetch are exact (see k_fused_pf, whose pass this is).

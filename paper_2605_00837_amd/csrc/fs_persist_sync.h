@@ -69,3 +69,13 @@ typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 }  // namespace
 }  // namespace fs
+
+// Debug builds (-DFS_PERSIST_TRACE) stamp the phases of one iteration per workgroup with the 100 MHz clock.
+#ifdef FS_PERSIST_TRACE
+#define FS_TRACE(slot) do { if (lane == 0 && X.trace) { \
+        const long long now_ = (long long)__builtin_amdgcn_s_memrealtime(); \
+        if (X.trace[65536 + 8191] < 0 ? k == 0 : k == k_end - 2) X.trace[(w * 16 + wave) * 8 + (slot)] = now_; \
+        if ((slot) <= 1 && wave == 0 && (w == 0 || w == 100) && k < 2000) X.trace[65536 + (w ? 4096 : 0) + 2 * k + (slot)] = now_; } } while (0)
+#else
+#define FS_TRACE(slot) do { } while (0)
+#endif

@@ -29,11 +29,11 @@ constexpr int kResLds = 2;
 
 // Q groups of 4 adjacent columns per lane (column(q, e) = (q 512 + tid) 4 + e), R rows per panel, m = 2048 Q
 // (every lane owns valid columns), R Q = 8 (a panel is 64 KiB: 32 entries per lane).
-template <int Q, int R>
-__global__ __launch_bounds__(512) void k_resident(DenseArgs A, PersistArgs X, Ctl c) {
-    constexpr int NW = 8, T = 64 * NW, NP = kResPanels, NL = kResLds;
+template <int Q, int R, int NW>
+__global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X, Ctl c) {
+    constexpr int T = 64 * NW, NP = kResPanels, NL = kResLds;
     constexpr int LW = 16;                     // lanes per row in the merge of the wave sums: NW partials, then zeros
-    static_assert(R * Q == 8, "a panel is 32 entries per lane");
+    static_assert(R * Q * NW == 64, "a panel is 64 KiB");
     static_assert(R * LW <= 64, "one wave merges all (row, wave) partials in one shot");
     static_assert(NP * R <= 64, "one wave loads the row scalars");
     constexpr float kRowHi = 1.1529215e18f;    // 2^60
@@ -145,6 +145,7 @@ __global__ __launch_bounds__(512) void k_resident(DenseArgs A, PersistArgs X, Ct
             for (int e = 0; e < 4; ++e) cS[q][e] = 0.0f;
         double err_acc = 0.0;                        // error terms of this workgroup's rows (lanes that own a row)
 
+        FS_TRACE(0);
 #pragma unroll
         for (int t = 0; t < NP; ++t) {
             if (t < mine) {
@@ -277,6 +278,7 @@ __global__ __launch_bounds__(512) void k_resident(DenseArgs A, PersistArgs X, Ct
             }
         }
 
+        FS_TRACE(1);
         // ---- publish: column sums of this workgroup's rows (16-byte stores), and the error terms of its rows
         {
             // where a group of 4 column sums goes: strip col / Sw, this workgroup's set, column col mod Sw
@@ -305,6 +307,7 @@ __global__ __launch_bounds__(512) void k_resident(DenseArgs A, PersistArgs X, Ct
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));     // this wave's stores have been acknowledged
         lds_only_barrier();                            // ... and so have every wave's
+        FS_TRACE(2);
         ++gen;
         if (wave == 0) {
             const unsigned long long old = grid_arrive(X.sync);
@@ -313,6 +316,7 @@ __global__ __launch_bounds__(512) void k_resident(DenseArgs A, PersistArgs X, Ct
         }
         lds_only_barrier();
         if (!sOk) { alive = false; break; }
+        FS_TRACE(3);
 
         // ---- merge of this workgroup's strip; beside it, the error of the iterate this iteration started from
         //      (the same W terms in the same order in every workgroup, so that all take the same decision)
@@ -346,6 +350,10 @@ __global__ __launch_bounds__(512) void k_resident(DenseArgs A, PersistArgs X, Ct
             }
             double epart = (__hiloint2double((int)ep0.y, (int)ep0.x) + __hiloint2double((int)ep0.w, (int)ep0.z)) +
                            (__hiloint2double((int)ep1.y, (int)ep1.x) + __hiloint2double((int)ep1.w, (int)ep1.z));
+#ifdef FS_PERSIST_TRACE
+            asm volatile("" :: "v"(acc[0]), "v"(acc[1]), "v"(acc[2]), "v"(acc[3]));
+            FS_TRACE(4);
+#endif
             // lanes with the same column group (lane mod QN) meet inside the wave, in a fixed order
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -367,6 +375,7 @@ __global__ __launch_bounds__(512) void k_resident(DenseArgs A, PersistArgs X, Ct
                 if (lane == 0) sErrTot = epart;
             }
             lds_only_barrier();
+            FS_TRACE(5);
             if (own_ok && !trailing) {
                 double tot = 0.0;
 #pragma unroll
@@ -432,6 +441,7 @@ __global__ __launch_bounds__(512) void k_resident(DenseArgs A, PersistArgs X, Ct
         }
         lds_only_barrier();
         if (!sOk) { alive = false; break; }
+        FS_TRACE(6);
         // ---- the new V of this lane's columns (16-byte loads, two values each)
         {
             const __amdgpu_buffer_rsrc_t rsV = __builtin_amdgcn_make_buffer_rsrc(
@@ -447,6 +457,10 @@ __global__ __launch_bounds__(512) void k_resident(DenseArgs A, PersistArgs X, Ct
                 v[q][3] = __hiloint2double((int)hi.w, (int)hi.z);
             }
         }
+#ifdef FS_PERSIST_TRACE
+        asm volatile("" :: "v"(v[0][0]), "v"(v[Q - 1][3]));
+#endif
+        FS_TRACE(7);
         ++k;
         if (k >= k_end && !(k == k_end && with_trailing)) break;
     }
@@ -477,8 +491,8 @@ hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs
                            const Stamp &tm) {
     if (a.c_dtype != 0 || !dense_resident_fits(a.p.n, a.p.m, grid)) return hipErrorInvalidValue;
     const dim3 g(grid), block(512);
-    if (a.p.m == 4096) launch_stamped((k_resident<2, 4>), g, block, st, tm, a, x, c);
-    else launch_stamped((k_resident<4, 2>), g, block, st, tm, a, x, c);
+    if (a.p.m == 4096) launch_stamped((k_resident<2, 4, 8>), g, block, st, tm, a, x, c);
+    else launch_stamped((k_resident<4, 2, 8>), g, block, st, tm, a, x, c);
     return hipGetLastError();
 }
 

@@ -46,20 +46,41 @@ def pot_err(x, ref, eps):
 # panels per workgroup; grids smaller than the chip; strips that are not a power of two wide
 SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (1000, 16001), (333, 12288), (260, 16384),
           (70, 2000), (3001, 5000), (129, 4096), (200, 1028), (1100, 6001), (600, 9000),
-          (4099, 4096), (2047, 4096), (9001, 4096)]      # 4096 columns: panels of 4 rows from 2048 rows up, of 2 below
+          (4099, 4096), (2047, 4096), (9001, 4096),      # 4096 columns: panels of 4 rows from 2048 rows up, of 2 below
+          (4096, 4096), (1024, 4096), (3070, 4096), (2048, 8192), (1500, 8192)]   # shares of C that stay on the chip
+
+
+def _resident(n, m, cus=256):
+    """Whether a grid of min(cus, panels) workgroups can hold the matrix on the chip (4096 or 8192 columns, one to four
+    panels of 64 KiB per workgroup): the persistent pass then takes its resident form unless fused_variant = 1."""
+    if m not in (4096, 8192):
+        return False
+    rows = 4 if m == 4096 else 2
+    stream_rows = 4 if (m == 4096 and n >= 2048) else 2      # the grid is that of the streaming form
+    grid = min(cus, -(-n // stream_rows))
+    panels = -(-n // rows)
+    return grid <= panels <= 4 * grid
 
 
 @pytest.mark.parametrize("n,m", SHAPES)
 def test_persistent_pass_matches_oracle(fs, oracle, n, m):
+    """Both forms of the persistent pass where both apply: the one that streams C every iteration (fused_variant = 1)
+    and the one that keeps the workgroup's share of C in LDS and registers (the default where it fits)."""
     if not _supported(fs, n, m):
         pytest.skip("needs more compute units than this device has")
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
     w = W.random_dense(n, m, seed=6000 + n + m, cmax=2.0, eps=0.03)
     iters = 52                                  # one whole block of 50 iterations and a short one
     ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C)
-    r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, iters, 0.0, C=dev(w.C), want_f64=True, kernel_mode=6)
-    assert r["iters"] == iters and not r["nonfinite"]
-    assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
-    assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+    for variant in ((0, 1) if _resident(n, m, cus) else (0,)):
+        r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, iters, 0.0, C=dev(w.C), want_f64=True, kernel_mode=6,
+                                 fused_variant=variant, time_kernel_every=1)
+        assert r["iters"] == iters and not r["nonfinite"]
+        assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
+        assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
+        name = fs.fs_last_kernel_timing()[2]
+        assert name == ("k_resident" if _resident(n, m, cus) and variant == 0 else "k_persist"), (n, m, variant, name)
     assert pot_err(r["f"].cpu().numpy(), ref["f"], w.eps) < TOL_F32
     err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
     assert abs(r["marginal_err"] - err_ref) <= 1e-4 * err_ref + 5e-7
@@ -88,9 +109,9 @@ def test_persistent_pass_is_the_automatic_choice_and_repeats_bit_for_bit(fs, ora
     assert pot_err(r0["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
 
 
-def test_persistent_pass_stop_rule_history_and_resume(fs, oracle):
+@pytest.mark.parametrize("n,m", [(320, 1500), (1030, 4096)])      # the streaming form; the resident form (ragged last panel)
+def test_persistent_pass_stop_rule_history_and_resume(fs, oracle, n, m):
     import torch
-    n, m = 320, 1500
     if not _supported(fs, n, m):
         pytest.skip("needs more compute units than this device has")
     w = W.random_dense(n, m, seed=6200, eps=0.05)
@@ -179,13 +200,13 @@ def test_persistent_pass_tiny_and_zero_weights(fs, oracle, n, m, eps):
     assert abs(r["marginal_err"] - err_ref) <= 1e-3 * err_ref + 5e-7
 
 
+@pytest.mark.parametrize("n,m", [(900, 2100), (1030, 4096)])       # the streaming form; the resident form
 @pytest.mark.parametrize("warm", [False, True])
-def test_persistent_pass_gives_up_cleanly_and_the_solve_falls_back(fs, oracle, warm):
+def test_persistent_pass_gives_up_cleanly_and_the_solve_falls_back(fs, oracle, warm, n, m):
     """wait_limit = 1: a workgroup stops waiting for the others after a single poll, which the host can force
     without any kernel misbehaving (every workgroup still exits).  Asked for by name, the solve then says that
     it gave up (or, with luck, completes); as the library's own choice it is followed by the multi-kernel
     driver and delivers the right answer, also when the start was passed in place."""
-    n, m = 900, 2100
     if not _supported(fs, n, m):
         pytest.skip("needs more compute units than this device has")
     w = W.random_dense(n, m, seed=6300, cmax=1.0, eps=0.05)
