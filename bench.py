@@ -7,6 +7,7 @@ n = m = 8192 fp32 problem at eps = 1e-2 that the headline metric is quoted on). 
 before the timed region starts; the timed region is one blocking solve of K iterations between synchronisations.
 
     python bench.py [--workload c1|c2|c3|c4|c5p|c5d] [--steps K] [--warmup W]
+    python bench.py --calibrate-read      # the read rate a plain streaming kernel reaches (practical ceiling beside the peak)
     python bench.py --calibrate-copy      # a plain 256 MiB device copy: what the FETCH_SIZE / WRITE_SIZE counters
                                           # read for a known size (run under rocprofv3 --pmc)
 
@@ -323,6 +324,24 @@ def calibrate_copy(mib=256, reps=5):
     print(json.dumps({"calibrate_copy_mib": mib, "copies": reps}))
 
 
+def calibrate_read(sizes_mib=(64, 128, 256, 512, 1024), reps=20):
+    """The practical read ceiling of the device: a plain streaming read kernel (fs_read_rate: one workgroup of 1024
+    lanes per compute unit, 16-byte loads) over buffers of the sizes of the dense workloads, beside the published
+    HBM peak.  One JSON line."""
+    import torch
+    from paper_2605_00837_amd import binding as fs
+    torch.cuda.set_device(0)
+    buf = torch.zeros(max(sizes_mib) << 20, dtype=torch.uint8, device="cuda")
+    _spin_up(torch, "copies", 100.0, None)
+    out = {"calibrate_read": "plain streaming read kernel, average of %d passes after 2 untimed ones" % reps,
+           "hbm_peak_GBs": HBM_PEAK_GBS, "sizes": []}
+    for mib in sizes_mib:
+        us = min(fs.fs_read_rate(buf[: mib << 20], reps) for _ in range(3))
+        out["sizes"].append({"MiB": mib, "us_per_pass": us, "GBs": (mib << 20) / (us * 1e-6) / 1e9,
+                             "frac_of_peak": (mib << 20) / (us * 1e-6) / 1e9 / HBM_PEAK_GBS})
+    print(json.dumps(out))
+
+
 def bench_after_loop(args):
     """The entry points that follow a solve (Eq. 5 plan, cost of Alg. 1's last step, one-pass diagnostics,
     barycentric mapping of Sec. 5.6), timed end to end on the workload's inputs after a short solve:
@@ -393,6 +412,8 @@ def main():
                     help="dense workloads: storage type of C (2-byte types are widened exactly; not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true")
+    ap.add_argument("--calibrate-read", action="store_true",
+                    help="print the read rate a plain streaming kernel reaches on buffers of 64 MiB .. 1 GiB")
     ap.add_argument("--after-loop", action="store_true",
                     help="time fs_cost / fs_diagnostics / fs_plan / fs_barycentric on the workload instead of the solve")
     args = ap.parse_args()
@@ -401,6 +422,8 @@ def main():
         sys.exit(2)
     if args.calibrate_copy:
         calibrate_copy()
+    elif args.calibrate_read:
+        calibrate_read()
     elif args.after_loop:
         bench_after_loop(args)
     elif args.workload in ("c4", "c5p"):

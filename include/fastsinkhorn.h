@@ -323,6 +323,14 @@ int fs_kernel_choice(int n, int m, int d, const fs_options *opts, int blocking, 
 fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **kernel_name,
                                 int32_t *iters_sampled);
 
+/* Measurement aid, not part of the method: reads the `bytes` bytes of the device buffer `buf` (16-byte aligned)
+ * `reps` times (after two untimed passes) with a plain streaming kernel -- one workgroup of 1024 lanes per
+ * compute unit, 16-byte loads -- on `stream`, waits for it, and returns the average duration of a pass in
+ * microseconds (HIP events around the `reps` launches) in *us_per_pass (host).  bytes / us_per_pass is the
+ * practical read ceiling of the device for a buffer of that size, to be put beside the published HBM peak.
+ * FS_ERR_INVALID_ARG for a null or misaligned buffer, bytes < 16 or reps < 1.  For benchmarks. */
+fs_status fs_read_rate(const void *buf, size_t bytes, int reps, float *us_per_pass, fs_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

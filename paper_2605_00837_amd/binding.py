@@ -59,6 +59,8 @@ def _load():
     lib.fs_last_kernel_timing.restype = ci
     lib.fs_last_kernel_timing.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32),
                                           ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_int32)]
+    lib.fs_read_rate.restype = ci
+    lib.fs_read_rate.argtypes = [vp, ctypes.c_size_t, ci, ctypes.POINTER(ctypes.c_float), vp]
     lib.fs_kernel_choice.restype = ci
     lib.fs_kernel_choice.argtypes = [ci, ci, ci, vp, ci, ci]
     lib.fs_workspace_bytes.restype = ctypes.c_size_t
@@ -106,7 +108,7 @@ _lib = _load()
 EXPORTED = ("fs_sinkhorn_dense", "fs_sinkhorn_points", "fs_sinkhorn_solve", "fs_workspace_bytes",
             "fs_sinkhorn_dense_ex", "fs_sinkhorn_points_ex", "fs_sinkhorn_dense_static", "fs_sinkhorn_dense_batched", "fs_sinkhorn_annealed", "fs_plan", "fs_cost", "fs_plan_f64",
             "fs_cost_f64", "fs_diagnostics", "fs_barycentric", "fs_update_f", "fs_update_g", "fs_last_error", "fs_clear_cache", "fs_version",
-            "fs_last_kernel_timing", "fs_kernel_choice")
+            "fs_last_kernel_timing", "fs_kernel_choice", "fs_read_rate")
 
 
 def _check(status: int):
@@ -212,6 +214,14 @@ def fs_last_kernel_timing():
     ms, cnt, name, ipl = ctypes.c_float(0), ctypes.c_int32(0), ctypes.c_char_p(), ctypes.c_int32(0)
     _check(_lib.fs_last_kernel_timing(ctypes.byref(ms), ctypes.byref(cnt), ctypes.byref(name), ctypes.byref(ipl)))
     return float(ms.value), int(cnt.value), name.value.decode(), int(ipl.value)
+
+
+def fs_read_rate(buf, reps: int = 20) -> float:
+    """Average microseconds a plain streaming read kernel takes for one pass over the device tensor `buf` (the
+    practical read ceiling of the device for a buffer of that size; a measurement aid for benchmarks)."""
+    us = ctypes.c_float(0)
+    _check(_lib.fs_read_rate(_p(buf, buf.dtype), int(buf.numel() * buf.element_size()), int(reps), ctypes.byref(us), _stream()))
+    return float(us.value)
 
 
 def fs_workspace_bytes(n: int, m: int, d: int = 0) -> int:

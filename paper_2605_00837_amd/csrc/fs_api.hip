@@ -1142,6 +1142,34 @@ fs_status fs_last_kernel_timing(float *avg_ms, int32_t *samples, const char **ke
     return FS_OK;
 }
 
+fs_status fs_read_rate(const void *buf, size_t bytes, int reps, float *us_per_pass, fs_stream stream) {
+    if (!buf || !us_per_pass || bytes < 16 || reps < 1 || (reinterpret_cast<uintptr_t>(buf) & 15u) != 0) {
+        set_err("fs_read_rate: buf (16-byte aligned) and us_per_pass must be non-null, bytes >= 16, reps >= 1");
+        return FS_ERR_INVALID_ARG;
+    }
+    DeviceCache *dc = nullptr;
+    const fs_status v = get_cache(256, &dc);
+    if (v != FS_OK) return v;
+    const int cus = device_cus();
+    if (cus < 1) { set_err("fs_read_rate: no compute units reported"); return FS_ERR_HIP; }
+    hipStream_t st = (hipStream_t)stream;
+    float *sink = reinterpret_cast<float *>(dc->tickets) + 63;      // never written (see the kernel)
+    hipEvent_t e0, e1;
+    FS_HIP(hipEventCreate(&e0));
+    FS_HIP(hipEventCreate(&e1));
+    for (int r = 0; r < 2; ++r) FS_HIP(launch_read_stream(st, buf, bytes, cus, sink));
+    FS_HIP(hipEventRecord(e0, st));
+    for (int r = 0; r < reps; ++r) FS_HIP(launch_read_stream(st, buf, bytes, cus, sink));
+    FS_HIP(hipEventRecord(e1, st));
+    FS_HIP(hipEventSynchronize(e1));
+    float ms = 0.0f;
+    FS_HIP(hipEventElapsedTime(&ms, e0, e1));
+    FS_HIP(hipEventDestroy(e0));
+    FS_HIP(hipEventDestroy(e1));
+    *us_per_pass = ms * 1e3f / (float)reps;
+    return FS_OK;
+}
+
 size_t fs_workspace_bytes(int n, int m, int d) {
     if (n < 1 || m < 1 || d < 0 || d > FS_MAX_DIM) return 0;
     return make_layout(n, m, d).total;

@@ -257,16 +257,19 @@ struct PersistArgs {
     long long *trace;                            // debug builds: [workgroups][8] time stamps of one iteration
 #endif
 };
+// fs_calib.hip: a plain streaming read of `bytes` bytes (measurement aid; `sink` is never written)
+hipError_t launch_read_stream(hipStream_t st, const void *buf, size_t bytes, int cus, float *sink);
 bool dense_persist_supported(int n, int m, const void *C, int c_dtype);
 int dense_persist_grid(int n, int m, int cus);   // workgroups of the launch on a device with `cus` compute units
 size_t persist_scratch_bytes();
-// variant 0: the resident form (fs_resident.hip) where the workgroups can hold their share of C, else the
-// streaming form; 1: always the streaming form
+// variant 0: the 512-lane kernel of fs_resident.hip where the workgroups can hold their share of C, or most of the
+// panels they stream are few (up to 12 panels per workgroup), else the 1024-lane streaming kernel; 1: always the
+// 1024-lane streaming kernel; 2: the 512-lane kernel up to 32 panels per workgroup
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
                           int spin_limit, int final_err, int variant, const Stamp &tm = Stamp());
 bool dense_persist_resident(int n, int m, int cus, int variant);   // which of the two forms launch_persist takes
 // fs_resident.hip: the same iteration with the workgroup's share of C held in LDS and registers for the whole launch
-bool dense_resident_fits(int n, int m, int grid);
+bool dense_resident_fits(int n, int m, int grid, bool all);
 hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs &x, const Ctl &c, int grid,
                            const Stamp &tm);
 

@@ -596,7 +596,7 @@ int dense_persist_grid(int n, int m, int cus) {
 size_t persist_scratch_bytes() { return sizeof(PersistSync) + sizeof(double) * kWgPartLd; }
 
 bool dense_persist_resident(int n, int m, int cus, int variant) {
-    return variant != 1 && dense_resident_fits(n, m, dense_persist_grid(n, m, cus));
+    return variant != 1 && dense_resident_fits(n, m, dense_persist_grid(n, m, cus), variant == 2);
 }
 
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
@@ -622,7 +622,7 @@ hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void
     x.trace = nullptr;
     if (const char *tp = getenv("FS_TRACE_PTR")) x.trace = reinterpret_cast<long long *>(strtoull(tp, nullptr, 0));
 #endif
-    if (variant != 1 && dense_resident_fits(a.p.n, a.p.m, g)) return launch_resident(st, a, x, c, g, tm);
+    if (variant != 1 && dense_resident_fits(a.p.n, a.p.m, g, variant == 2)) return launch_resident(st, a, x, c, g, tm);
     const dim3 grid(g), block(1024);
     const int m = a.p.m;
     if (s.Q == 1 && s.R == 4) launch_stamped((k_persist<1, 4, true>), grid, block, st, tm, a, x, c);

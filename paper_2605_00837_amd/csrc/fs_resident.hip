@@ -17,6 +17,8 @@
 // phase for the error of the last iterate (Sec. 4.5), the same fixed orders of every sum.  The old F of the
 // workgroup's rows stays in LDS as well (two parities); F and U still go to memory every iteration, for the
 // repairs in other workgroups and for whatever runs after this launch.
+#include <type_traits>
+
 #include "fs_kernels.h"
 #include "fs_persist_sync.h"
 
@@ -24,25 +26,30 @@ namespace fs {
 
 namespace {
 
-constexpr int kResPanels = 4;           // panels a workgroup holds: kResLds in LDS, the others in registers
-constexpr int kResLds = 2;
+constexpr int kResRegs = 2;             // panels a workgroup keeps in registers (64 registers per lane)
+constexpr int kResLds = 2;              // panels the LDS holds: the other resident ones, or the two staging buffers
+constexpr int kResPanels = kResRegs + kResLds;   // up to here the whole share stays on the chip
+constexpr int kResMaxPanels = 32;       // panels per workgroup at most (row scalars in LDS)
+constexpr int kResAutoPanels = 12;      // up to here this kernel is the faster one (measured: 27.1 against 28.6 us per
+                                        // iteration at 4096 x 8192, 36.5 against 37.3 at 6144 x 8192, a tie at 8192 x
+                                        // 8192, 73.7 against 69.0 at 12288 x 8192)
 
 // Q groups of 4 adjacent columns per lane (column(q, e) = (q 512 + tid) 4 + e), R rows per panel, m = 2048 Q
 // (every lane owns valid columns), R Q = 8 (a panel is 64 KiB: 32 entries per lane).
-template <int Q, int R, int NW>
+template <int Q, int R, int NW, bool STREAM>
 __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X, Ctl c) {
-    constexpr int T = 64 * NW, NP = kResPanels, NL = kResLds;
+    constexpr int T = 64 * NW, NP = kResMaxPanels, NR = kResRegs, NL = kResLds;
+    constexpr int NDMA = R * Q;                // prefetch loads per panel and wave
     constexpr int LW = 16;                     // lanes per row in the merge of the wave sums: NW partials, then zeros
     static_assert(R * Q * NW == 64, "a panel is 64 KiB");
     static_assert(R * LW <= 64, "one wave merges all (row, wave) partials in one shot");
-    static_assert(NP * R <= 64, "one wave loads the row scalars");
     constexpr float kRowHi = 1.1529215e18f;    // 2^60
     constexpr float kRowLo = 9.5367432e-07f;   // 2^-20
-    __shared__ float4 stage[NL][NW][R][Q][64]; // panels 0 .. NL-1, every wave its own slice
+    __shared__ float4 stage[NL][NW][R][Q][64]; // the panels behind the register panels (two: resident; more: staged), every wave its own slice
     __shared__ double sF[2][NP][R];            // F of this workgroup's rows by parity of the iteration; kPadF past n
     __shared__ double sLa2[NP][R];
     __shared__ float sA[NP][R];
-    __shared__ float sSum[NP][R][NW];
+    __shared__ float sSum[NR + NL][R][NW];     // by register panel, then by staging buffer
     __shared__ double sM[R][NW];               // exact redo: row maxima by wave
     __shared__ double sMr[NW];                 // exact repair of a column: running pairs by wave
     __shared__ float sSr[NW];
@@ -68,16 +75,22 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     // the launch that reaches max_iter goes on with one more row phase: it yields err of the last iterate
     const bool with_trailing = X.final_err != 0 && k_end == c.max_iter;
 
-    // This workgroup owns the panels w, w + W, ... (at most NP: the launcher sees to it), in every iteration.
+    // This workgroup owns the panels w, w + W, ... (3 .. NP of them, or at most NR + NL: the launcher sees to it), in
+    // every iteration.  Panels 0 .. NR-1 live in registers.  The others live in LDS when there are at most NL of
+    // them (loaded once); else they are streamed through the NL staging buffers every iteration, two panels
+    // ahead, as in the streaming form of the pass: the first of them always first, the others upwards on even
+    // and downwards on odd iterations (what the last-level cache still holds from the pass before is read first).
     const int npanels = (n + R - 1) / R;
     const int mine = (npanels - 1 - w) / W + 1;
+    const int ms = mine > NR ? mine - NR : 0;          // panels behind the register panels
+    const bool streaming = STREAM && ms > NL;      // (STREAM = false: the launcher has seen that no workgroup has more)
     if (tid == 0) {
         // waits completed so far in this solve: the generation numbers of this launch go on from there
         sGen = __hip_atomic_load(&X.sync->done[w & 7], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sNsus = 0;
     }
-    if (tid < NP * R) {
-        const int t = tid / R, r = tid % R;
+    for (int x = tid; x < NP * R; x += T) {
+        const int t = x / R, r = x % R;
         const int row = (w + t * W) * R + r;
         const bool ok = t < mine && row < n;
         sF[k & 1][t][r] = ok ? p.F[(size_t)(k & 1) * p.n_ld + row] : kPadF;
@@ -85,30 +98,47 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
         sLa2[t][r] = ok ? p.la2[row] : -__builtin_huge_val();
         sA[t][r] = ok ? p.a[row] : 0.0f;
     }
-    // ---- the workgroup's share of C, once: memory -> LDS without passing through registers (panels 0 .. NL-1),
-    //      memory -> registers (the others).  The descriptors cover exactly the valid rows: rows past n read as 0.
-    float creg[NP - NL][R][Q][4];
+    // panel j of this workgroup: rows (w + j W) R ...; its descriptor covers exactly the valid rows (rows past n read as 0)
+    auto panel_rsrc = [&](int j) {
+        const int i0 = (w + j * W) * R;
+        const int rows = j < mine ? ((n - i0) < R ? (n - i0) : R) : 0;
+        return __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)A.C + (size_t)(j < mine ? i0 : 0) * m * 4), 0,
+                                                 rows * m * 4, 0x00020000);
+    };
+    // memory -> LDS without passing through registers: panel j into staging buffer buf, every wave its own slice
+    // (slice tw: the wave's own, except between iterations, see below)
+    auto issue = [&](int j, int buf, int tw) {
+        const __amdgpu_buffer_rsrc_t rsrc = panel_rsrc(j);
 #pragma unroll
-    for (int t = 0; t < NP; ++t) {
-        const int i0 = (w + t * W) * R;
-        const int rows = t < mine ? ((n - i0) < R ? (n - i0) : R) : 0;
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)((const char *)A.C + (size_t)(t < mine ? i0 : 0) * m * 4), 0, rows * m * 4, 0x00020000);
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, &stage[buf][tw][r][q][0], 16, (tw * 64 + lane) * 16,
+                                                         (r * m + q * T * 4) * 4, 0, 0);
+    };
+    // the panel behind the register panels that a pass visits in position t
+    auto lds_panel = [&](int t, bool rev) { return NR + (t == 0 ? 0 : (rev ? ms - t : t)); };
+    // ---- the register panels, once per launch
+    float creg[NR][R][Q][4];
+#pragma unroll
+    for (int t = 0; t < NR; ++t) {
+        const __amdgpu_buffer_rsrc_t rsrc = panel_rsrc(t);
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
-                if (t < NL) {
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, &stage[t][wave][r][q][0], 16, tid * 16,
-                                                             (r * m + q * T * 4) * 4, 0, 0);
-                } else {
-                    const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, tid * 16, (r * m + q * T * 4) * 4, 0);
-                    float (&cr)[4] = creg[t < NL ? 0 : t - NL][r][q];
-                    cr[0] = __uint_as_float(x.x); cr[1] = __uint_as_float(x.y);
-                    cr[2] = __uint_as_float(x.z); cr[3] = __uint_as_float(x.w);
-                }
+                const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, tid * 16, (r * m + q * T * 4) * 4, 0);
+                float (&cr)[4] = creg[t][r][q];
+                cr[0] = __uint_as_float(x.x); cr[1] = __uint_as_float(x.y);
+                cr[2] = __uint_as_float(x.z); cr[3] = __uint_as_float(x.w);
             }
     }
+    // ---- the LDS panels: the resident ones once per launch; a streaming workgroup the first two of this pass (those
+    //      of the passes after it go on their way during the exchange of the iteration before, C never changes:
+    //      the first -- always the same panel -- as soon as the workgroup has arrived at the second wait, by the
+    //      waves that do not do the waiting, the second right after the read of V)
+    if (ms > 0) issue(lds_panel(0, (k & 1) != 0), 0, wave);
+    if (ms > 1) issue(lds_panel(1, (k & 1) != 0), 1, wave);
     // V of this lane's columns (written before this launch)
     double v[Q][4];
 #pragma unroll
@@ -137,6 +167,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     bool alive = true;
     for (;;) {
         const int cur = k & 1, nxt = cur ^ 1;
+        const bool rev = cur != 0;
         const bool trailing = k == c.max_iter;       // row phase only: the error of the last iterate
         float cS[Q][4];                              // column sums of the plan entries of this workgroup's rows
 #pragma unroll
@@ -146,33 +177,90 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
         double err_acc = 0.0;                        // error terms of this workgroup's rows (lanes that own a row)
 
         FS_TRACE(0);
+        // One panel: REG >= 0: register panel REG (= panel REG of this workgroup); REG < 0: the panel j in staging
+        // buffer slot - NR.  `slot` also names the row-sum staging this panel uses.
+        auto do_panel = [&](auto reg_tag, int slot, int j) {
+            constexpr int REG = decltype(reg_tag)::value;
+            const int i0 = (w + j * W) * R;
+            const bool rowok = rr < R && (i0 + rr) < n;
+            const double rho_lane = sF[cur][j][rc];
+            const double la2_lane = rowok ? sLa2[j][rc] : -__builtin_huge_val();
+            const float a_lane = rowok ? sA[j][rc] : 0.0f;
+            double rho[R];
 #pragma unroll
-        for (int t = 0; t < NP; ++t) {
-            if (t < mine) {
-                const int i0 = (w + t * W) * R;
-                const bool rowok = rr < R && (i0 + rr) < n;
-                const double rho_lane = sF[cur][t][rc];
-                const double la2_lane = rowok ? sLa2[t][rc] : -__builtin_huge_val();
-                const float a_lane = rowok ? sA[t][rc] : 0.0f;
-                double rho[R];
+            for (int r = 0; r < R; ++r) rho[r] = sF[cur][j][r];
+            // the 4 entries (r, q, .) of this panel as fp64 values: from the lane's registers (through a compiler
+            // barrier: every use converts the 4-byte register afresh; without it the converted values of all
+            // register panels are kept over the iteration loop, in twice the registers), or from LDS
+            auto cost4 = [&](int r, int q, double (&o)[4]) {
+                if constexpr (REG >= 0) {
 #pragma unroll
-                for (int r = 0; r < R; ++r) rho[r] = sF[cur][t][r];
-                // the 4 entries (r, q, .) of this panel as fp64 values: from LDS, or from the lane's registers (through a
-                // compiler barrier: every use converts the 4-byte register afresh; without it the converted values of
-                // all register panels are kept over the iteration loop, in twice the registers)
-                auto cost4 = [&](int r, int q, double (&o)[4]) {
-                    if (t < NL) {
-                        const float4 c4 = stage[t < NL ? t : 0][wave][r][q][lane];
-                        o[0] = (double)c4.x; o[1] = (double)c4.y; o[2] = (double)c4.z; o[3] = (double)c4.w;
-                    } else {
+                    for (int e = 0; e < 4; ++e) o[e] = cost_f64(creg[REG][r][q][e]);
+                } else {
+                    const float4 c4 = stage[slot - NR][wave][r][q][lane];
+                    o[0] = (double)c4.x; o[1] = (double)c4.y; o[2] = (double)c4.z; o[3] = (double)c4.w;
+                }
+            };
+            // ---- row phase, optimistic: e = 2^(x - rho_r), summed
+            float ev[R][Q][4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = cost_f64(creg[t < NL ? 0 : t - NL][r][q][e]);
+            for (int r = 0; r < R; ++r) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    double cvv[4];
+                    cost4(r, q, cvv);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        ev[r][q][e] = fast_exp2((float)(fma(ns, cvv[e], v[q][e]) - rho[r]));
+                        acc += ev[r][q][e];
                     }
-                };
-                // ---- row phase, optimistic: e = 2^(x - rho_r), summed
-                float ev[R][Q][4];
+                }
+                acc = wave_sum_f32(acc);
+                if (lane == 0) sSum[slot][r][wave] = acc;
+            }
+            lds_only_barrier();
+            float S = rr < R ? (ww < NW ? sSum[slot][rc][wc] : 0.0f) : 1.0f;
+            S += dpp_f32<0x128>(S);
+            S += dpp_f32<0x124>(S);
+            S += dpp_f32<0x122>(S);
+            S += dpp_f32<0x121>(S);
+            const bool fine = (S >= kRowLo) && (S <= kRowHi);    // false for NaN / inf / 0
+            // pi_ij = e_ij * a_i / S_i.  Every wave needs a_i / S_i (reciprocal, one Newton step, product: within
+            // 1.5 ulp); the new F = reference + log2 S is formed by the one wave that stores it, further down.
+            double Fbase = rho_lane;
+            float Ssum = S;
+            float alpha_lane;
+            {
+                float rcp = __builtin_amdgcn_rcpf(S);
+                rcp = fmaf(fmaf(-S, rcp, 1.0f), rcp, rcp);
+                alpha_lane = a_lane * rcp;
+            }
+            if (__builtin_expect(!__all(fine || !rowok), 0)) {
+                // ---- exact redo of the row phase of this panel (uniform over the workgroup): Eq. 8 as written,
+                //      the maximum of the row first (no exponentials), then the sum relative to it
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
+                    double mx = kNegHuge;
+#pragma unroll
+                    for (int q = 0; q < Q; ++q) {
+                        double cvv[4];
+                        cost4(r, q, cvv);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) mx = dmax(mx, fma(ns, cvv[e], v[q][e]));
+                    }
+                    mx = wave_max_f64(mx);
+                    if (lane == 0) sM[r][wave] = mx;
+                }
+                lds_only_barrier();                              // (every wave has read sSum by now)
+                double Mg = rr < R && ww < NW ? sM[rc][wc] : kNegHuge;
+                Mg = dmax(Mg, dpp_f64<0x128>(Mg));
+                Mg = dmax(Mg, dpp_f64<0x124>(Mg));
+                Mg = dmax(Mg, dpp_f64<0x122>(Mg));
+                Mg = dmax(Mg, dpp_f64<0x121>(Mg));
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const double Mr = bcast_f64(Mg, r * LW);
                     float acc = 0.0f;
 #pragma unroll
                     for (int q = 0; q < Q; ++q) {
@@ -180,102 +268,83 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                         cost4(r, q, cvv);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            ev[r][q][e] = fast_exp2((float)(fma(ns, cvv[e], v[q][e]) - rho[r]));
+                            ev[r][q][e] = fast_exp2((float)(fma(ns, cvv[e], v[q][e]) - Mr));
                             acc += ev[r][q][e];
                         }
                     }
                     acc = wave_sum_f32(acc);
-                    if (lane == 0) sSum[t][r][wave] = acc;
+                    if (lane == 0) sSum[slot][r][wave] = acc;
                 }
-                lds_only_barrier();
-                float S = rr < R ? (ww < NW ? sSum[t][rc][wc] : 0.0f) : 1.0f;
-                S += dpp_f32<0x128>(S);
-                S += dpp_f32<0x124>(S);
-                S += dpp_f32<0x122>(S);
-                S += dpp_f32<0x121>(S);
-                const bool fine = (S >= kRowLo) && (S <= kRowHi);    // false for NaN / inf / 0
-                // pi_ij = e_ij * a_i / S_i.  Every wave needs a_i / S_i (reciprocal, one Newton step, product: within
-                // 1.5 ulp); the new F = reference + log2 S is formed by the one wave that stores it, further down.
-                double Fbase = rho_lane;
-                float Ssum = S;
-                float alpha_lane;
-                {
-                    float rcp = __builtin_amdgcn_rcpf(S);
-                    rcp = fmaf(fmaf(-S, rcp, 1.0f), rcp, rcp);
-                    alpha_lane = a_lane * rcp;
-                }
-                if (__builtin_expect(!__all(fine || !rowok), 0)) {
-                    // ---- exact redo of the row phase of this panel (uniform over the workgroup): Eq. 8 as written,
-                    //      the maximum of the row first (no exponentials), then the sum relative to it
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        double mx = kNegHuge;
-#pragma unroll
-                        for (int q = 0; q < Q; ++q) {
-                            double cvv[4];
-                            cost4(r, q, cvv);
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) mx = dmax(mx, fma(ns, cvv[e], v[q][e]));
-                        }
-                        mx = wave_max_f64(mx);
-                        if (lane == 0) sM[r][wave] = mx;
-                    }
-                    lds_only_barrier();                              // (every wave has read sSum by now)
-                    double Mg = rr < R && ww < NW ? sM[rc][wc] : kNegHuge;
-                    Mg = dmax(Mg, dpp_f64<0x128>(Mg));
-                    Mg = dmax(Mg, dpp_f64<0x124>(Mg));
-                    Mg = dmax(Mg, dpp_f64<0x122>(Mg));
-                    Mg = dmax(Mg, dpp_f64<0x121>(Mg));
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        const double Mr = bcast_f64(Mg, r * LW);
-                        float acc = 0.0f;
-#pragma unroll
-                        for (int q = 0; q < Q; ++q) {
-                            double cvv[4];
-                            cost4(r, q, cvv);
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                ev[r][q][e] = fast_exp2((float)(fma(ns, cvv[e], v[q][e]) - Mr));
-                                acc += ev[r][q][e];
-                            }
-                        }
-                        acc = wave_sum_f32(acc);
-                        if (lane == 0) sSum[t][r][wave] = acc;
-                    }
-                    lds_only_barrier();                              // (and every wave has read sM)
-                    float sg = rr < R ? (ww < NW ? sSum[t][rc][wc] : 0.0f) : 1.0f;
-                    sg += dpp_f32<0x128>(sg);
-                    sg += dpp_f32<0x124>(sg);
-                    sg += dpp_f32<0x122>(sg);
-                    sg += dpp_f32<0x121>(sg);
-                    Fbase = Mg;
-                    Ssum = sg;
-                    alpha_lane = a_lane / sg;                          // e is relative to the row maximum: pi = e a / sum
-                }
-                if (wave == 0 && ww == 0 && rowok) {
-                    // the new F stays in LDS (the old F of the same rows in the next iteration) and goes to memory for
-                    // whatever runs after this launch; U is what a repair in another workgroup reads
-                    const double Fn_lane = Fbase + log2_sum(Ssum);
-                    int row = i0 + rr;
-                    asm volatile("" : "+v"(row));          // (addresses formed here, not kept in registers over the loop)
-                    sF[nxt][t][rr] = Fn_lane;
-                    p.F[(size_t)nxt * p.n_ld + row] = Fn_lane;
-                    pub_f64(p.U + (size_t)nxt * p.n_ld + row, la2_lane - Fn_lane);
-                    // error term of Sec. 4.5 for the iterate this iteration started from: a_i |2^(Fnew - Fold) - 1|
-                    if (a_lane > 0.0f) err_acc += (double)a_lane * fabs(exp2m1(Fn_lane - rho_lane));
-                }
-                // ---- column phase with the new f (the trailing round does it too: its sums are simply not published)
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    float alpha = bcast_f32(alpha_lane, r * LW);
-                    if (!(alpha == alpha) || (i0 + r) >= n) alpha = 0.0f;   // rows past n, or a row whose F is not finite
-#pragma unroll
-                    for (int q = 0; q < Q; ++q)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) cS[q][e] = fmaf(ev[r][q][e], alpha, cS[q][e]);
-                }
+                lds_only_barrier();                              // (and every wave has read sM)
+                float sg = rr < R ? (ww < NW ? sSum[slot][rc][wc] : 0.0f) : 1.0f;
+                sg += dpp_f32<0x128>(sg);
+                sg += dpp_f32<0x124>(sg);
+                sg += dpp_f32<0x122>(sg);
+                sg += dpp_f32<0x121>(sg);
+                Fbase = Mg;
+                Ssum = sg;
+                alpha_lane = a_lane / sg;                          // e is relative to the row maximum: pi = e a / sum
             }
+            if (wave == 0 && ww == 0 && rowok) {
+                // the new F stays in LDS (the old F of the same rows in the next iteration) and goes to memory for
+                // whatever runs after this launch; U is what a repair in another workgroup reads
+                const double Fn_lane = Fbase + log2_sum(Ssum);
+                int row = i0 + rr;
+                asm volatile("" : "+v"(row));          // (addresses formed here, not kept in registers over the loop)
+                sF[nxt][j][rr] = Fn_lane;
+                p.F[(size_t)nxt * p.n_ld + row] = Fn_lane;
+                pub_f64(p.U + (size_t)nxt * p.n_ld + row, la2_lane - Fn_lane);
+                // error term of Sec. 4.5 for the iterate this iteration started from: a_i |2^(Fnew - Fold) - 1|
+                if (a_lane > 0.0f) err_acc += (double)a_lane * fabs(exp2m1(Fn_lane - rho_lane));
+            }
+            // ---- column phase with the new f (the trailing round does it too: its sums are simply not published)
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                float alpha = bcast_f32(alpha_lane, r * LW);
+                if (!(alpha == alpha) || (i0 + r) >= n) alpha = 0.0f;   // rows past n, or a row whose F is not finite
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) cS[q][e] = fmaf(ev[r][q][e], alpha, cS[q][e]);
+            }
+        };
+        // A streaming workgroup is bound by the memory system (a panel arrives in 2.4 us and takes 1.6 us of
+        // arithmetic): its register panels go where it would otherwise wait, behind the two staged panels that
+        // are already here.
+        if constexpr (!STREAM) {
+            // everything is on the chip: the panels in program order, every index a constant
+            if (ms > 0) do_panel(std::integral_constant<int, -1>(), NR, NR);
+            if (ms > 1) do_panel(std::integral_constant<int, -1>(), NR + 1, NR + 1);
+            if (mine > 0) do_panel(std::integral_constant<int, 0>(), 0, 0);
+            if (mine > 1) do_panel(std::integral_constant<int, 1>(), 1, 1);
+        } else {
+        int regs_done = 0;
+        auto reg_panel = [&]() {
+            if (regs_done == 0 && mine > 0) do_panel(std::integral_constant<int, 0>(), 0, 0);
+            if (regs_done == 1 && mine > 1) do_panel(std::integral_constant<int, 1>(), 1, 1);
+            ++regs_done;
+        };
+        for (int t = 0; t < ms; ++t) {
+            const int buf = t & 1;
+            if (streaming && t >= 2 && regs_done < NR) reg_panel();
+            if (streaming) {
+                // Panel t must have landed: the only younger vector-memory operations are the NDMA loads of panel
+                // t + 1 (if there is one), which may stay in flight (loads return in order; what wave 0 stored
+                // after them only makes its wait stricter).
+                if (t + 1 < ms) __builtin_amdgcn_s_waitcnt(waitcnt_vm(NDMA));
+                else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+                asm volatile("" ::: "memory");
+            }
+            do_panel(std::integral_constant<int, -1>(), NR + buf, lds_panel(t, rev));
+            if (streaming && t + 2 < ms) {
+                // the panel after next into the buffer this panel occupied (this wave's own slice, its reads are done)
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0xc07f);
+                issue(lds_panel(t + 2, rev), buf, wave);
+                asm volatile("" ::: "memory");
+            }
+        }
+        while (regs_done < NR) reg_panel();
         }
 
         FS_TRACE(1);
@@ -430,9 +499,25 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
             break;
         }
         ++gen;
+        const bool more = k + 1 < k_end || (k + 1 == k_end && with_trailing);
+        unsigned long long old2 = 0ull;
         if (wave == 0) {
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(0)); // the strip's new G and V (all published by this wave) are acknowledged
-            const unsigned long long old2 = grid_arrive(X.sync);
+            old2 = grid_arrive(X.sync);
+        }
+        if (streaming && more) {
+            // The first staged panel of the next pass goes on its way now: the arrival is out, and by the time a poll can
+            // see the last workgroup arrive, the memory pipeline of this compute unit has drained these requests.  Wave 0
+            // does the waiting, with polls that would queue behind a prefetch of its own: wave 1 fetches its slice too.
+            lds_only_barrier();
+            if (wave != 0) {
+                asm volatile("" ::: "memory");
+                issue(lds_panel(0, false), 0, wave);
+                if (wave == 1) issue(lds_panel(0, false), 0, 0);
+                asm volatile("" ::: "memory");
+            }
+        }
+        if (wave == 0) {
             const int ok = grid_wait(X.sync, old2, gen, W, X.spin_limit);
             if (lane == 0) {
                 sOk = ok;
@@ -457,6 +542,14 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                 v[q][3] = __hiloint2double((int)hi.w, (int)hi.z);
             }
         }
+        if (streaming && more) {
+            // the second staged panel behind the loads of V: "all but the youngest NDMA loads have landed" then means
+            // that V and the first panel are here (wave 0's slice of it came through wave 1, hence the barrier)
+            asm volatile("" ::: "memory");
+            issue(lds_panel(1, nxt != 0), 1, wave);
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(NDMA));
+            lds_only_barrier();
+        }
 #ifdef FS_PERSIST_TRACE
         asm volatile("" :: "v"(v[0][0]), "v"(v[Q - 1][3]));
 #endif
@@ -464,6 +557,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
         ++k;
         if (k >= k_end && !(k == k_end && with_trailing)) break;
     }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));         // no prefetch may land after the workgroup has given up its LDS
     if (!alive && tid == 0) {
         // abandoned: mark the solve as such and stop everything that was enqueued behind this launch
         atomicOr(&c.st->nonfinite, kGaveUp);
@@ -478,21 +572,31 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 
 }  // namespace
 
-// The shapes the resident pass takes: fp32 costs, every lane with valid columns (4096 or 8192 columns) and at
-// most kResPanels panels of 64 KiB per workgroup of a grid of `grid` workgroups.
-bool dense_resident_fits(int n, int m, int grid) {
+// The shapes this kernel takes: fp32 costs, every lane with valid columns (4096 or 8192 columns), between 1 and
+// `most` panels of 64 KiB per workgroup of a grid of `grid` workgroups.  Up to kResPanels the whole share stays on
+// the chip; beyond, the panels behind the register panels are streamed: up to kResAutoPanels as the library's own
+// choice, up to kResMaxPanels on request (`all`).
+bool dense_resident_fits(int n, int m, int grid, bool all) {
     if (grid < 1 || (m != 4096 && m != 8192)) return false;
     const int R = m == 4096 ? 4 : 2;
     const long long npanels = ((long long)n + R - 1) / R;
-    return npanels >= grid && npanels <= (long long)kResPanels * grid;    // every workgroup owns 1 .. kResPanels panels
+    const long long most = all ? kResMaxPanels : kResAutoPanels;
+    return npanels >= grid && npanels <= most * grid;
 }
 
 hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs &x, const Ctl &c, int grid,
                            const Stamp &tm) {
-    if (a.c_dtype != 0 || !dense_resident_fits(a.p.n, a.p.m, grid)) return hipErrorInvalidValue;
+    if (a.c_dtype != 0 || !dense_resident_fits(a.p.n, a.p.m, grid, true)) return hipErrorInvalidValue;
     const dim3 g(grid), block(512);
-    if (a.p.m == 4096) launch_stamped((k_resident<2, 4, 8>), g, block, st, tm, a, x, c);
-    else launch_stamped((k_resident<4, 2, 8>), g, block, st, tm, a, x, c);
+    const int R = a.p.m == 4096 ? 4 : 2;
+    const bool stream = ((long long)a.p.n + R - 1) / R > (long long)kResPanels * grid;
+    if (a.p.m == 4096) {
+        if (stream) launch_stamped((k_resident<2, 4, 8, true>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<2, 4, 8, false>), g, block, st, tm, a, x, c);
+    } else {
+        if (stream) launch_stamped((k_resident<4, 2, 8, true>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<4, 2, 8, false>), g, block, st, tm, a, x, c);
+    }
     return hipGetLastError();
 }
 

@@ -89,6 +89,13 @@ int main() {
     CHECK(fs_update_f(p, nullptr, nullptr, 0, p, p, 8, 8, 0.1f, nullptr, &y, nullptr) == FS_ERR_INVALID_ARG);
     CHECK(fs_update_g(p, nullptr, nullptr, 0, p, p, 8, 8, 0.1f, &y, nullptr, nullptr) == FS_ERR_INVALID_ARG);
     CHECK(fs_last_kernel_timing(nullptr, nullptr, nullptr, nullptr) == FS_ERR_INVALID_ARG);
+    {
+        float us = 0.0f;
+        CHECK(fs_read_rate(nullptr, 1 << 20, 3, &us, nullptr) == FS_ERR_INVALID_ARG);
+        CHECK(fs_read_rate(p, 1 << 20, 0, &us, nullptr) == FS_ERR_INVALID_ARG);
+        CHECK(fs_read_rate(p, 8, 3, &us, nullptr) == FS_ERR_INVALID_ARG);
+        CHECK(fs_read_rate(p, 1 << 20, 3, nullptr, nullptr) == FS_ERR_INVALID_ARG);
+    }
     fs_clear_cache();
     if (fails) { std::fprintf(stderr, "host_sanitize_check: %d check(s) failed\n", fails); return 1; }
     std::printf("host_sanitize_check: ok\n");

@@ -53,3 +53,20 @@ def test_bench_prints_one_json_line_with_the_contract_keys(workload, extra):
         assert 0.3 < d["iteration"]["frac_iteration"] <= r["frac"] + 0.05
     b = d["cpu_baseline"]
     assert b["kind"] == "oracle" and b["cores"] >= 1 and b["value"] > 0 and "sample" in b
+
+
+@pytest.mark.gpu
+def test_read_rate_calibration():
+    """The measurement aid behind `bench.py --calibrate-read`: a plain streaming read of a device buffer reaches a
+    plausible fraction of the published peak (a few TB/s on an MI355X; anything above 0.2 TB/s and below the peak passes,
+    so that the test holds on smaller devices), and invalid arguments are refused."""
+    import torch
+    from paper_2605_00837_amd import binding as fs
+    buf = torch.zeros(128 << 20, dtype=torch.uint8, device="cuda")
+    us = min(fs.fs_read_rate(buf, 10) for _ in range(3))
+    rate = buf.numel() / (us * 1e-6) / 1e12
+    assert 0.2 < rate < 8.0, rate
+    with pytest.raises(fs.FsError):
+        fs.fs_read_rate(buf[:8], 10)
+    with pytest.raises(fs.FsError):
+        fs.fs_read_rate(buf, 0)
