@@ -34,14 +34,16 @@ constexpr int kResAutoPanels = 12;      // up to here this kernel is the faster 
                                         // iteration at 4096 x 8192, 36.5 against 37.3 at 6144 x 8192, a tie at 8192 x
                                         // 8192, 73.7 against 69.0 at 12288 x 8192)
 
-// Q groups of 4 adjacent columns per lane (column(q, e) = (q 512 + tid) 4 + e), R rows per panel, m = 2048 Q
-// (every lane owns valid columns), R Q = 8 (a panel is 64 KiB: 32 entries per lane).
-template <int Q, int R, int NW, bool STREAM>
+// Q groups of 4 adjacent columns per lane (column(q, e) = (q 512 + tid) 4 + e), R rows per panel, R Q = 8 (a panel
+// is 64 KiB: 32 entries per lane).  FULLW: m = 2048 Q, every lane owns valid columns; else 2048 (Q - 2) < m <
+// 2048 Q and the columns past m are masked (V = -inf, C = 0, nothing published).
+template <int Q, int R, int NW, bool STREAM, bool FULLW>
 __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X, Ctl c) {
     constexpr int T = 64 * NW, NP = kResMaxPanels, NR = kResRegs, NL = kResLds;
     constexpr int NDMA = R * Q;                // prefetch loads per panel and wave
     constexpr int LW = 16;                     // lanes per row in the merge of the wave sums: NW partials, then zeros
     static_assert(R * Q * NW == 64, "a panel is 64 KiB");
+    static_assert(FULLW || !STREAM, "a width with idle lanes is taken only where C is read once per launch");
     static_assert(R * LW <= 64, "one wave merges all (row, wave) partials in one shot");
     constexpr float kRowHi = 1.1529215e18f;    // 2^60
     constexpr float kRowLo = 9.5367432e-07f;   // 2^-20
@@ -131,6 +133,14 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                 float (&cr)[4] = creg[t][r][q];
                 cr[0] = __uint_as_float(x.x); cr[1] = __uint_as_float(x.y);
                 cr[2] = __uint_as_float(x.z); cr[3] = __uint_as_float(x.w);
+                if (!FULLW) {
+                    // columns past m: what was read there belongs to the next row (or to nobody); the entry counts
+                    // for nothing (V = -inf there) and is set to 0 so that it cannot turn -inf into NaN either
+                    const int col = (q * T + tid) * 4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col + e >= m) cr[e] = 0.0f;
+                }
             }
     }
     // ---- the LDS panels: the resident ones once per launch; a streaming workgroup the first two of this pass (those
@@ -145,7 +155,8 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     for (int q = 0; q < Q; ++q) {
         const int col = (q * T + tid) * 4;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[q][e] = p.V[(size_t)(k & 1) * p.m_ld + col + e];
+        for (int e = 0; e < 4; ++e)
+            v[q][e] = (FULLW || col + e < m) ? p.V[(size_t)(k & 1) * p.m_ld + col + e] : -__builtin_huge_val();
     }
     // The strip of columns this workgroup merges: Sw columns (a multiple of 4, at most 64: the launcher sees to
     // it).  The exchange buffer is laid out by destination: [strip][source workgroup][Swp floats], Swp = Sw
@@ -161,6 +172,25 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     const bool own_ok = tid < Sw && own_col < strip1;
 
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));         // the LDS panels have landed
+    if (!FULLW) {
+        // the same for the LDS panels (every lane its own entries; once per launch: they are resident)
+#pragma unroll
+        for (int b = 0; b < NL; ++b)
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    const int col = (q * T + tid) * 4;
+                    if (col + 4 > m) {
+                        float4 c4 = stage[b][wave][r][q][lane];
+                        if (col >= m) c4.x = 0.0f;
+                        if (col + 1 >= m) c4.y = 0.0f;
+                        if (col + 2 >= m) c4.z = 0.0f;
+                        if (col + 3 >= m) c4.w = 0.0f;
+                        stage[b][wave][r][q][lane] = c4;
+                    }
+                }
+    }
     __syncthreads();
     unsigned long long gen = sGen;
 
@@ -357,11 +387,13 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
                 const int col = (q * T + tid) * 4;
-                const int dest = col / Sw;
-                const v4u pk = {__float_as_uint(cS[q][0]), __float_as_uint(cS[q][1]), __float_as_uint(cS[q][2]),
-                                __float_as_uint(cS[q][3])};
-                __builtin_amdgcn_raw_buffer_store_b128(pk, rsX, ((((dest * W + w) << lgSwp) + (col - dest * Sw))) * 4, 0,
-                                                       kAgent);
+                if (FULLW || col < m) {
+                    const int dest = col / Sw;
+                    const v4u pk = {__float_as_uint(cS[q][0]), __float_as_uint(cS[q][1]), __float_as_uint(cS[q][2]),
+                                    __float_as_uint(cS[q][3])};
+                    __builtin_amdgcn_raw_buffer_store_b128(pk, rsX, ((((dest * W + w) << lgSwp) + (col - dest * Sw))) * 4, 0,
+                                                           kAgent);
+                }
             }
             if (wave == 0) {
                 const double e = wave_sum_f64(err_acc);
@@ -534,12 +566,19 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
                 const int col = (q * T + tid) * 4;
-                const v4u lo = __builtin_amdgcn_raw_buffer_load_b128(rsV, col * 8, 0, kAgent);
-                const v4u hi = __builtin_amdgcn_raw_buffer_load_b128(rsV, col * 8 + 16, 0, kAgent);
-                v[q][0] = __hiloint2double((int)lo.y, (int)lo.x);
-                v[q][1] = __hiloint2double((int)lo.w, (int)lo.z);
-                v[q][2] = __hiloint2double((int)hi.y, (int)hi.x);
-                v[q][3] = __hiloint2double((int)hi.w, (int)hi.z);
+                if (FULLW || col < m) {
+                    const v4u lo = __builtin_amdgcn_raw_buffer_load_b128(rsV, col * 8, 0, kAgent);
+                    const v4u hi = __builtin_amdgcn_raw_buffer_load_b128(rsV, col * 8 + 16, 0, kAgent);
+                    v[q][0] = __hiloint2double((int)lo.y, (int)lo.x);
+                    v[q][1] = __hiloint2double((int)lo.w, (int)lo.z);
+                    v[q][2] = __hiloint2double((int)hi.y, (int)hi.x);
+                    v[q][3] = __hiloint2double((int)hi.w, (int)hi.z);
+                    if (!FULLW) {
+#pragma unroll
+                        for (int e = 1; e < 4; ++e)
+                            if (col + e >= m) v[q][e] = -__builtin_huge_val();
+                    }
+                }
             }
         }
         if (streaming && more) {
@@ -572,15 +611,17 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 
 }  // namespace
 
-// The shapes this kernel takes: fp32 costs, every lane with valid columns (4096 or 8192 columns), between 1 and
-// `most` panels of 64 KiB per workgroup of a grid of `grid` workgroups.  Up to kResPanels the whole share stays on
-// the chip; beyond, the panels behind the register panels are streamed: up to kResAutoPanels as the library's own
+// The shapes this kernel takes: fp32 costs, 2048 < m <= 8192 (panels of 4 rows up to 4096 columns, of 2 rows
+// beyond), between 1 and `most` panels per workgroup of a grid of `grid` workgroups.  Up to kResPanels the whole
+// share stays on the chip, for any width.  Beyond, the panels behind the register panels are streamed, which is
+// done only for the widths without idle lanes (4096 and 8192 columns): up to kResAutoPanels as the library's own
 // choice, up to kResMaxPanels on request (`all`).
 bool dense_resident_fits(int n, int m, int grid, bool all) {
-    if (grid < 1 || (m != 4096 && m != 8192)) return false;
-    const int R = m == 4096 ? 4 : 2;
+    if (grid < 1 || m <= 2048 || m > 8192) return false;
+    const int R = m <= 4096 ? 4 : 2;
+    const bool fullw = m == 4096 || m == 8192;
     const long long npanels = ((long long)n + R - 1) / R;
-    const long long most = all ? kResMaxPanels : kResAutoPanels;
+    const long long most = !fullw ? kResPanels : all ? kResMaxPanels : kResAutoPanels;
     return npanels >= grid && npanels <= most * grid;
 }
 
@@ -588,14 +629,19 @@ hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs
                            const Stamp &tm) {
     if (a.c_dtype != 0 || !dense_resident_fits(a.p.n, a.p.m, grid, true)) return hipErrorInvalidValue;
     const dim3 g(grid), block(512);
-    const int R = a.p.m == 4096 ? 4 : 2;
+    const int m = a.p.m;
+    const int R = m <= 4096 ? 4 : 2;
     const bool stream = ((long long)a.p.n + R - 1) / R > (long long)kResPanels * grid;
-    if (a.p.m == 4096) {
-        if (stream) launch_stamped((k_resident<2, 4, 8, true>), g, block, st, tm, a, x, c);
-        else launch_stamped((k_resident<2, 4, 8, false>), g, block, st, tm, a, x, c);
+    if (m == 4096) {
+        if (stream) launch_stamped((k_resident<2, 4, 8, true, true>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<2, 4, 8, false, true>), g, block, st, tm, a, x, c);
+    } else if (m == 8192) {
+        if (stream) launch_stamped((k_resident<4, 2, 8, true, true>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<4, 2, 8, false, true>), g, block, st, tm, a, x, c);
+    } else if (m < 4096) {
+        launch_stamped((k_resident<2, 4, 8, false, false>), g, block, st, tm, a, x, c);
     } else {
-        if (stream) launch_stamped((k_resident<4, 2, 8, true>), g, block, st, tm, a, x, c);
-        else launch_stamped((k_resident<4, 2, 8, false>), g, block, st, tm, a, x, c);
+        launch_stamped((k_resident<4, 2, 8, false, false>), g, block, st, tm, a, x, c);
     }
     return hipGetLastError();
 }
