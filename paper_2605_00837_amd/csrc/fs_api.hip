@@ -763,7 +763,12 @@ bool grid_path(const Problem &pr, const fs_options *opts, bool blocking, fs_stat
     if (km == 5) return true;
     // automatic: it needs every compute unit of the chip at the same moment, so the library only picks it where
     // it can fall back (blocking solves); up to 512 x 512 the 32-workgroup kernel is as fast or faster
-    // (256 x 256: 5.7 against 7.3 us per iteration), beyond that this one is (1024 x 256: 8.3 against 10.2)
+    // (256 x 256: 5.7 against 7.3 us per iteration), beyond that this one is (1024 x 256: 8.3 against 10.2) --
+    // except where the persistent pass can keep its share of C on the chip: from 2048 rows up at more than 1024
+    // columns that one is faster (2048 x 2048: 10.5 against 14.0 us per iteration, 2048 x 1025: 10.0 against 12.2)
+    if (blocking && pr.C && (!opts || (opts->fused_variant == 0 && opts->cost_dtype == 0)) &&
+        dense_persist_supported(pr.n, pr.m, pr.C, 0) && dense_persist_resident(pr.n, pr.m, *wmax, 0))
+        return false;
     return blocking && (pr.n > 512 || pr.m > 512);
 }
 

@@ -34,14 +34,44 @@ constexpr int kResAutoPanels = 12;      // up to here this kernel is the faster 
                                         // iteration at 4096 x 8192, 36.5 against 37.3 at 6144 x 8192, a tie at 8192 x
                                         // 8192, 73.7 against 69.0 at 12288 x 8192)
 
+// All-reduce over aligned groups of LW lanes (16: a DPP row, rotated; 8: lane ^ 1, lane ^ 2, then the half row mirrored).
+template <int LW>
+__device__ __forceinline__ float group_sum_f32(float x) {
+    if (LW == 16) {
+        x += dpp_f32<0x128>(x);
+        x += dpp_f32<0x124>(x);
+        x += dpp_f32<0x122>(x);
+        x += dpp_f32<0x121>(x);
+    } else {
+        x += dpp_f32<0xB1>(x);     // quad_perm [1, 0, 3, 2]
+        x += dpp_f32<0x4E>(x);     // quad_perm [2, 3, 0, 1]
+        x += dpp_f32<0x141>(x);    // row_half_mirror
+    }
+    return x;
+}
+template <int LW>
+__device__ __forceinline__ double group_max_f64(double x) {
+    if (LW == 16) {
+        x = dmax(x, dpp_f64<0x128>(x));
+        x = dmax(x, dpp_f64<0x124>(x));
+        x = dmax(x, dpp_f64<0x122>(x));
+        x = dmax(x, dpp_f64<0x121>(x));
+    } else {
+        x = dmax(x, dpp_f64<0xB1>(x));
+        x = dmax(x, dpp_f64<0x4E>(x));
+        x = dmax(x, dpp_f64<0x141>(x));
+    }
+    return x;
+}
+
 // Q groups of 4 adjacent columns per lane (column(q, e) = (q 512 + tid) 4 + e), R rows per panel, R Q = 8 (a panel
-// is 64 KiB: 32 entries per lane).  FULLW: m = 2048 Q, every lane owns valid columns; else 2048 (Q - 2) < m <
-// 2048 Q and the columns past m are masked (V = -inf, C = 0, nothing published).
+// is 64 KiB: 32 entries per lane).  FULLW: m = 2048 Q, every lane owns valid columns; else m < 2048 Q and the
+// columns past m are masked (V = -inf, C = 0, nothing published).
 template <int Q, int R, int NW, bool STREAM, bool FULLW>
 __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X, Ctl c) {
     constexpr int T = 64 * NW, NP = kResMaxPanels, NR = kResRegs, NL = kResLds;
     constexpr int NDMA = R * Q;                // prefetch loads per panel and wave
-    constexpr int LW = 16;                     // lanes per row in the merge of the wave sums: NW partials, then zeros
+    constexpr int LW = R > 4 ? 8 : 16;         // lanes per row in the merge of the wave sums: NW partials (then zeros)
     static_assert(R * Q * NW == 64, "a panel is 64 KiB");
     static_assert(FULLW || !STREAM, "a width with idle lanes is taken only where C is read once per launch");
     static_assert(R * LW <= 64, "one wave merges all (row, wave) partials in one shot");
@@ -251,10 +281,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
             }
             lds_only_barrier();
             float S = rr < R ? (ww < NW ? sSum[slot][rc][wc] : 0.0f) : 1.0f;
-            S += dpp_f32<0x128>(S);
-            S += dpp_f32<0x124>(S);
-            S += dpp_f32<0x122>(S);
-            S += dpp_f32<0x121>(S);
+            S = group_sum_f32<LW>(S);
             const bool fine = (S >= kRowLo) && (S <= kRowHi);    // false for NaN / inf / 0
             // pi_ij = e_ij * a_i / S_i.  Every wave needs a_i / S_i (reciprocal, one Newton step, product: within
             // 1.5 ulp); the new F = reference + log2 S is formed by the one wave that stores it, further down.
@@ -284,10 +311,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                 }
                 lds_only_barrier();                              // (every wave has read sSum by now)
                 double Mg = rr < R && ww < NW ? sM[rc][wc] : kNegHuge;
-                Mg = dmax(Mg, dpp_f64<0x128>(Mg));
-                Mg = dmax(Mg, dpp_f64<0x124>(Mg));
-                Mg = dmax(Mg, dpp_f64<0x122>(Mg));
-                Mg = dmax(Mg, dpp_f64<0x121>(Mg));
+                Mg = group_max_f64<LW>(Mg);
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
                     const double Mr = bcast_f64(Mg, r * LW);
@@ -307,10 +331,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                 }
                 lds_only_barrier();                              // (and every wave has read sM)
                 float sg = rr < R ? (ww < NW ? sSum[slot][rc][wc] : 0.0f) : 1.0f;
-                sg += dpp_f32<0x128>(sg);
-                sg += dpp_f32<0x124>(sg);
-                sg += dpp_f32<0x122>(sg);
-                sg += dpp_f32<0x121>(sg);
+                sg = group_sum_f32<LW>(sg);
                 Fbase = Mg;
                 Ssum = sg;
                 alpha_lane = a_lane / sg;                          // e is relative to the row maximum: pi = e a / sum
@@ -611,15 +632,15 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 
 }  // namespace
 
-// The shapes this kernel takes: fp32 costs, 2048 < m <= 8192 (panels of 4 rows up to 4096 columns, of 2 rows
-// beyond), between 1 and `most` panels per workgroup of a grid of `grid` workgroups.  Up to kResPanels the whole
-// share stays on the chip, for any width.  Beyond, the panels behind the register panels are streamed, which is
-// done only for the widths without idle lanes (4096 and 8192 columns): up to kResAutoPanels as the library's own
-// choice, up to kResMaxPanels on request (`all`).
+// The shapes this kernel takes: fp32 costs, 1024 < m <= 8192 (panels of 8 rows up to 2048 columns, of 4 up to 4096,
+// of 2 beyond), between 1 and `most` panels per workgroup of a grid of `grid` workgroups.  Up to kResPanels the
+// whole share stays on the chip, for any width.  Beyond, the panels behind the register panels are streamed,
+// which is done only for the widths without idle lanes (2048, 4096 and 8192 columns): up to kResAutoPanels as the
+// library's own choice, up to kResMaxPanels on request (`all`).
 bool dense_resident_fits(int n, int m, int grid, bool all) {
-    if (grid < 1 || m <= 2048 || m > 8192) return false;
-    const int R = m <= 4096 ? 4 : 2;
-    const bool fullw = m == 4096 || m == 8192;
+    if (grid < 1 || m <= 1024 || m > 8192) return false;
+    const int R = m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
+    const bool fullw = m == 2048 || m == 4096 || m == 8192;
     const long long npanels = ((long long)n + R - 1) / R;
     const long long most = !fullw ? kResPanels : all ? kResMaxPanels : kResAutoPanels;
     return npanels >= grid && npanels <= most * grid;
@@ -630,14 +651,19 @@ hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs
     if (a.c_dtype != 0 || !dense_resident_fits(a.p.n, a.p.m, grid, true)) return hipErrorInvalidValue;
     const dim3 g(grid), block(512);
     const int m = a.p.m;
-    const int R = m <= 4096 ? 4 : 2;
+    const int R = m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
     const bool stream = ((long long)a.p.n + R - 1) / R > (long long)kResPanels * grid;
-    if (m == 4096) {
+    if (m == 2048) {
+        if (stream) launch_stamped((k_resident<1, 8, 8, true, true>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<1, 8, 8, false, true>), g, block, st, tm, a, x, c);
+    } else if (m == 4096) {
         if (stream) launch_stamped((k_resident<2, 4, 8, true, true>), g, block, st, tm, a, x, c);
         else launch_stamped((k_resident<2, 4, 8, false, true>), g, block, st, tm, a, x, c);
     } else if (m == 8192) {
         if (stream) launch_stamped((k_resident<4, 2, 8, true, true>), g, block, st, tm, a, x, c);
         else launch_stamped((k_resident<4, 2, 8, false, true>), g, block, st, tm, a, x, c);
+    } else if (m < 2048) {
+        launch_stamped((k_resident<1, 8, 8, false, false>), g, block, st, tm, a, x, c);
     } else if (m < 4096) {
         launch_stamped((k_resident<2, 4, 8, false, false>), g, block, st, tm, a, x, c);
     } else {

@@ -49,22 +49,23 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
           (4099, 4096), (2047, 4096), (9001, 4096),      # 4096 columns: panels of 4 rows from 2048 rows up, of 2 below
           (4096, 4096), (1024, 4096), (3070, 4096), (2048, 8192), (1500, 8192),   # shares of C that stay on the chip
           (2100, 8192), (6001, 4096), (12000, 4096), (13000, 4096), (6200, 8192),
-          (3000, 3000), (1500, 2049), (4000, 4095), (2000, 6145), (1025, 8191), (1200, 5000), (1023, 4097)]   # ... idle lanes      # ... and shares of which the 512-lane kernel streams a part
+          (3000, 3000), (1500, 2049), (4000, 4095), (2000, 6145), (1025, 8191), (1200, 5000), (1023, 4097),   # ... idle lanes
+          (2048, 2048), (8190, 2048), (3000, 1500), (5000, 1025), (2051, 2047), (20000, 2048), (70000, 2048)]   # panels of 8 rows      # ... and shares of which the 512-lane kernel streams a part
 
 
 def _resident(n, m, cus=256, most=4):
-    """Whether the 512-lane kernel of the persistent pass takes the shape (2048 < m <= 8192, 1 .. most panels of 64 KiB
+    """Whether the 512-lane kernel of the persistent pass takes the shape (1024 < m <= 8192, 1 .. most panels of 64 KiB
     per workgroup of a grid of min(cus, panels)): up to 4 panels the matrix stays on the chip for a whole launch; beyond
-    that, and only at 4096 and 8192 columns, the panels behind the two in registers are streamed: up to 12 panels it is
+    that, and only at 2048, 4096 and 8192 columns, the panels behind the two in registers are streamed: up to 12 panels it is
     the library's own choice (fused_variant = 1 asks for the 1024-lane streaming kernel instead), up to 32 it can be
     asked for (fused_variant = 2)."""
-    if not 2048 < m <= 8192:
+    if not 1024 < m <= 8192:
         return False
-    rows = 4 if m <= 4096 else 2
+    rows = 8 if m <= 2048 else 4 if m <= 4096 else 2
     stream_rows = 4 if (m == 4096 and n >= 2048) else 2      # the grid is that of the streaming form
     grid = min(cus, -(-n // stream_rows))
     panels = -(-n // rows)
-    if m not in (4096, 8192):
+    if m not in (2048, 4096, 8192):
         most = min(most, 4)
     return grid <= panels <= most * grid
 
