@@ -269,7 +269,7 @@ hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void
                           int spin_limit, int final_err, int variant, const Stamp &tm = Stamp());
 bool dense_persist_resident(int n, int m, int cus, int variant);   // which of the two forms launch_persist takes
 // fs_resident.hip: the same iteration with the workgroup's share of C held in LDS and registers for the whole launch
-bool dense_resident_fits(int n, int m, int grid, bool all);
+int dense_resident_grid(int n, int m, int cus, bool all);   // workgroups of its launch; 0: shape not taken
 hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs &x, const Ctl &c, int grid,
                            const Stamp &tm);
 

@@ -596,22 +596,25 @@ int dense_persist_grid(int n, int m, int cus) {
 size_t persist_scratch_bytes() { return sizeof(PersistSync) + sizeof(double) * kWgPartLd; }
 
 bool dense_persist_resident(int n, int m, int cus, int variant) {
-    return variant != 1 && dense_resident_fits(n, m, dense_persist_grid(n, m, cus), variant == 2);
+    return variant != 1 && dense_resident_grid(n, m, cus > 256 ? 256 : cus, variant == 2) > 0;
 }
+
 
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
                           int spin_limit, int final_err, int variant, const Stamp &tm) {
     PShape s;
     if (!scratch || a.c_dtype != 0 || !persist_shape(a.p.n, a.p.m, &s) || nb < 1) return hipErrorInvalidValue;
     const int g = dense_persist_grid(a.p.n, a.p.m, cus);
-    if (g < 1 || g > a.P) return hipErrorInvalidValue;     // the exchange buffer holds a.P sets of column sums
-    {
-        // [strip][source][strip width rounded up to a power of two] floats must fit what a.P sets of doubles take
-        const int strip = (((a.p.m + g - 1) / g) + 3) & ~3;
+    // the exchange buffer holds a.P sets of column sums, and [strip][source][strip width rounded up to a power of
+    // two] floats must fit what a.P sets of doubles take
+    auto exchange_fits = [&](int grid) {
+        if (grid < 1 || grid > a.P) return false;
+        const int strip = (((a.p.m + grid - 1) / grid) + 3) & ~3;
         int swp = 4;
         while (swp < strip) swp <<= 1;
-        if ((size_t)g * g * swp * sizeof(float) > (size_t)a.P * a.p.m_ld * sizeof(double)) return hipErrorInvalidValue;
-    }
+        return (size_t)grid * grid * swp * sizeof(float) <= (size_t)a.P * a.p.m_ld * sizeof(double);
+    };
+    if (!exchange_fits(g)) return hipErrorInvalidValue;
     PersistArgs x;
     x.sync = reinterpret_cast<PersistSync *>(scratch);
     x.wgpart = reinterpret_cast<double *>(x.sync + 1);
@@ -622,7 +625,11 @@ hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void
     x.trace = nullptr;
     if (const char *tp = getenv("FS_TRACE_PTR")) x.trace = reinterpret_cast<long long *>(strtoull(tp, nullptr, 0));
 #endif
-    if (variant != 1 && dense_resident_fits(a.p.n, a.p.m, g, variant == 2)) return launch_resident(st, a, x, c, g, tm);
+    if (variant != 1) {
+        // (cus is at most a.P here: the exchange buffer holds a set of column sums per workgroup of either form)
+        const int gr = dense_resident_grid(a.p.n, a.p.m, cus > 256 ? 256 : cus, variant == 2);
+        if (gr > 0 && exchange_fits(gr)) return launch_resident(st, a, x, c, gr, tm);
+    }
     const dim3 grid(g), block(1024);
     const int m = a.p.m;
     if (s.Q == 1 && s.R == 4) launch_stamped((k_persist<1, 4, true>), grid, block, st, tm, a, x, c);

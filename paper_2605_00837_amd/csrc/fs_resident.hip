@@ -633,22 +633,28 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 }  // namespace
 
 // The shapes this kernel takes: fp32 costs, 1024 < m <= 8192 (panels of 8 rows up to 2048 columns, of 4 up to 4096,
-// of 2 beyond), between 1 and `most` panels per workgroup of a grid of `grid` workgroups.  Up to kResPanels the
-// whole share stays on the chip, for any width.  Beyond, the panels behind the register panels are streamed,
-// which is done only for the widths without idle lanes (2048, 4096 and 8192 columns): up to kResAutoPanels as the
-// library's own choice, up to kResMaxPanels on request (`all`).
-bool dense_resident_fits(int n, int m, int grid, bool all) {
-    if (grid < 1 || m <= 1024 || m > 8192) return false;
+// of 2 beyond), on a grid of one workgroup per compute unit, never more than there are panels and never so few
+// that a workgroup would merge a strip of more than 64 columns.  Up to kResPanels panels per workgroup the whole
+// share stays on the chip, for any width.  Beyond, the panels behind the register panels are streamed, which is
+// done only for the widths without idle lanes (2048, 4096 and 8192 columns): up to kResAutoPanels as the library's
+// own choice, up to kResMaxPanels on request (`all`).  Returns the workgroups of the launch, 0 when the shape is
+// not taken.
+int dense_resident_grid(int n, int m, int cus, bool all) {
+    if (cus < 1 || n < 1 || m <= 1024 || m > 8192) return 0;
     const int R = m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
     const bool fullw = m == 2048 || m == 4096 || m == 8192;
     const long long npanels = ((long long)n + R - 1) / R;
+    long long g = npanels < cus ? npanels : cus;
+    if (g > 256) g = 256;                                  // the exchange buffer holds 256 sets of column sums
+    const int strip = (int)(((m + g - 1) / g + 3) & ~3ll);
+    if (strip > 64) return 0;
     const long long most = !fullw ? kResPanels : all ? kResMaxPanels : kResAutoPanels;
-    return npanels >= grid && npanels <= most * grid;
+    return npanels <= most * g ? (int)g : 0;
 }
 
 hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs &x, const Ctl &c, int grid,
                            const Stamp &tm) {
-    if (a.c_dtype != 0 || !dense_resident_fits(a.p.n, a.p.m, grid, true)) return hipErrorInvalidValue;
+    if (a.c_dtype != 0 || grid < 1 || dense_resident_grid(a.p.n, a.p.m, grid, true) != grid) return hipErrorInvalidValue;
     const dim3 g(grid), block(512);
     const int m = a.p.m;
     const int R = m <= 2048 ? 8 : m <= 4096 ? 4 : 2;

@@ -147,9 +147,11 @@ def test_kernel_choice_table_without_gpu():
     assert pick(16384, 16384, 3) == "points" and pick(16384, 12288) == "fused" and pick(16384, 16384) == "fused"   # c5
     assert pick(64, 64) == "small" and pick(128, 128) == "small" and pick(129, 128) == "coop"
     assert pick(512, 512) == "coop" and pick(513, 512) == "grid" and pick(1024, 1024) == "grid"
-    assert pick(2040, 2048) == "grid" and pick(4096, 1024) == "grid" and pick(4096, 2048) == "persist"
-    # from 256 panels of 8 rows up, at more than 1024 columns, the persistent pass keeps C on the chip and is preferred
-    assert pick(2041, 2048) == "persist" and pick(2048, 1025) == "persist" and pick(2048, 1024) == "grid"
+    assert pick(4096, 1024) == "grid" and pick(4096, 2048) == "persist"
+    # at more than 1024 columns the persistent pass keeps C on the chip and is preferred, unless the problem is small
+    assert pick(2048, 2048) == "persist" and pick(2048, 1025) == "persist" and pick(2048, 1024) == "grid"
+    assert pick(256, 2048) == "persist" and pick(800, 1200) == "persist" and pick(640, 1280) == "grid"
+    assert pick(300, 1100) == "grid" and pick(200, 2048) == "grid"       # 25 panels: strips of more than 64 columns
     assert pick(2048, 2048, cost_dtype=1) == "grid" and pick(2048, 2048, blocking=False) != "persist"
     assert pick(100, 2048) == "persist"                      # too few rows for that many columns: strips of > 16 columns
     assert pick(40, 20000) == "stream" and pick(30, 16384) == "fused" and pick(30, 16385) == "stream"

@@ -55,19 +55,20 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
 
 def _resident(n, m, cus=256, most=4):
     """Whether the 512-lane kernel of the persistent pass takes the shape (1024 < m <= 8192, 1 .. most panels of 64 KiB
-    per workgroup of a grid of min(cus, panels)): up to 4 panels the matrix stays on the chip for a whole launch; beyond
+    per workgroup of a grid of min(cus, panels) workgroups that merge at most 64 columns each): up to 4 panels the matrix stays on the chip for a whole launch; beyond
     that, and only at 2048, 4096 and 8192 columns, the panels behind the two in registers are streamed: up to 12 panels it is
     the library's own choice (fused_variant = 1 asks for the 1024-lane streaming kernel instead), up to 32 it can be
     asked for (fused_variant = 2)."""
     if not 1024 < m <= 8192:
         return False
     rows = 8 if m <= 2048 else 4 if m <= 4096 else 2
-    stream_rows = 4 if (m == 4096 and n >= 2048) else 2      # the grid is that of the streaming form
-    grid = min(cus, -(-n // stream_rows))
     panels = -(-n // rows)
+    grid = min(cus, panels, 256)
+    if (-(-m // grid) + 3) // 4 * 4 > 64:                    # a workgroup merges a strip of at most 64 columns
+        return False
     if m not in (2048, 4096, 8192):
         most = min(most, 4)
-    return grid <= panels <= most * grid
+    return panels <= most * grid
 
 
 @pytest.mark.parametrize("n,m", SHAPES)
