@@ -238,14 +238,21 @@ struct GridArgs : SmallArgs {                    // batch is ignored (one proble
 // ---- dense fp32 problems with 1024 < m <= 16384: a block of iterations of the fused row-panel pass in one
 //      launch, one resident workgroup per compute unit, two grid-wide waits per iteration (fs_persist.hip)
 // Counters of the persistent pass (all monotone over a solve).  A workgroup counts itself into one of 8 group
-// counters; the last of a group writes the generation into the group's word of `done`, the one line that every
-// workgroup polls (the polled line sees 8 plain stores per wait and no read-modify-write).
+// counters; the last of a group writes the generation into the group's word of the `done` line -- of every copy of
+// it: a polled line sees 8 plain stores per wait, no read-modify-write, and the polls of only a few workgroups
+// (polled by all 256, a line takes hundreds of requests per microsecond and the store everybody waits for queues
+// behind them).
+constexpr int kSyncGroups = 8;                   // arrival counters (a workgroup counts itself into number workgroup mod kSyncGroups)
 struct PersistSync {
-    GridLine grp[8];
-    unsigned long long done[8];                  // generation each group has completed
-    unsigned long long abort_flag;               // same line: one poll reads the 9 words
-    unsigned long long pad[23];
+    GridLine grp[kSyncGroups];
+    unsigned long long done[kSyncGroups];        // generation each group has completed
+    unsigned long long abort_flag;
+    unsigned long long pad[31 - kSyncGroups];
+    // kSyncCopies copies of that line (words 0 .. kSyncGroups-1: done, then the abort flag), 256 bytes apart: a workgroup polls
+    // copy workgroup mod kSyncCopies, so that a line is watched by a few workgroups, not by all of them
+    unsigned long long copy[64][32];
 };
+constexpr int kSyncCopies = 64;
 struct PersistArgs {
     PersistSync *sync;
     double *wgpart;                              // [workgroups]: error terms of each workgroup's rows

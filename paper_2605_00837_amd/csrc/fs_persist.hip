@@ -22,8 +22,8 @@
 // Everything exchanged is written with agent-scope stores and read with agent-scope loads (relaxed atomics,
 // or 16-byte buffer accesses with the same cache policy; no cache maintenance); every wave waits for its own
 // stores before the workgroup arrives.  Arrivals are counted in 8 group counters (monotone over a solve,
-// reset by the init kernel); the workgroup that completes a group says so in one line that one wave per
-// workgroup watches with one load per poll.  Every wait is bounded: a workgroup that gives up raises a flag that
+// reset by the init kernel); the workgroup that completes a group says so in a line (kept in 64 copies, each
+// watched by 4 workgroups) that one wave per workgroup watches with one load per poll.  Every wait is bounded: a workgroup that gives up raises a flag that
 // makes all others give up, the solve is marked as abandoned (nonfinite = 2) and the host runs the
 // multi-kernel driver instead.  The results do not depend on timing: panel ownership is static and every
 // sum has a fixed order.
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
     if (tid == 0) {
         // waits completed so far in this solve (every workgroup of the launches before this one has counted
         // itself in for each of them): the generation numbers of this launch go on from there
-        sGen = __hip_atomic_load(&X.sync->done[w & 7], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sGen = __hip_atomic_load(&X.sync->done[w % kSyncGroups], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sNsus = 0;
     }
     __syncthreads();

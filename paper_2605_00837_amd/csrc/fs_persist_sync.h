@@ -25,35 +25,46 @@ __device__ __forceinline__ void pub_f32x2(float *p, float x, float y) {
 // Grid-wide wait number `gen`, in two halves called by all 64 lanes of ONE wave while the others are parked at
 // barriers, after every wave's published stores have been acknowledged.
 //   grid_arrive  lane 0 counts the workgroup into its group's counter (the value comes back later);
-//   grid_wait    the workgroup that completed its group writes `gen` into the group's word of the `done`
-//                line; lanes 0..7 watch one word of that line each and lane 8 the abort flag next to them, with
-//                ONE load instruction (one memory request) per poll.  Everything only grows.
+//   grid_wait    the workgroup that completed its group writes `gen` into the group's word of every copy of the
+//                `done` line (one store instruction); lanes 0..7 watch one word each of the copy this workgroup is
+//                assigned and lane 8 the abort flag next to them, with ONE load instruction per poll, one poll at
+//                a time (more polls in flight, or more pollers per line, delay the store they wait for).
+//                Everything only grows.
 // grid_wait returns 0 when the wait was abandoned (by this workgroup or by another).
 __device__ __forceinline__ unsigned long long grid_arrive(PersistSync *sy) {
     unsigned long long old = 0ull;
     if ((threadIdx.x & 63) == 0)
-        old = __hip_atomic_fetch_add(&sy->grp[blockIdx.x & 7].v, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        old = __hip_atomic_fetch_add(&sy->grp[blockIdx.x % kSyncGroups].v, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return old;
 }
 __device__ __forceinline__ int grid_wait(PersistSync *sy, unsigned long long old, unsigned long long gen, int W,
                                          int spin_limit) {
     const int lane = threadIdx.x & 63;
+    const int grp = blockIdx.x % kSyncGroups;
+    int last = 0;
     if (lane == 0) {
-        const int grp = blockIdx.x & 7;
-        const unsigned long long members = (unsigned long long)((W - grp + 7) / 8);
-        if (old + 1ull == gen * members)
-            __hip_atomic_store(&sy->done[grp], gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long members = (unsigned long long)((W - grp + kSyncGroups - 1) / kSyncGroups);
+        last = old + 1ull == gen * members;
     }
-    const int groups = W < 8 ? W : 8;
-    const unsigned long long *watch = lane < 8 ? &sy->done[lane] : &sy->abort_flag;
+    if (__builtin_amdgcn_readfirstlane(last)) {
+        // the workgroup that completed its group says so in every copy of the line: one store instruction
+        if (lane == 0) __hip_atomic_store(&sy->done[grp], gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int q = lane; q < kSyncCopies; q += 64)
+            __hip_atomic_store(&sy->copy[q][grp], gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const int groups = W < kSyncGroups ? W : kSyncGroups;
+    const unsigned long long *watch = &sy->copy[blockIdx.x & (kSyncCopies - 1)][lane < kSyncGroups ? lane : kSyncGroups];
     int good = 1, spins = 0;
     for (;;) {
         unsigned long long v = 0ull;
-        if (lane <= 8) v = __hip_atomic_load(watch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (lane <= kSyncGroups) v = __hip_atomic_load(watch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const bool reached = lane < groups ? v >= gen : true;
-        const bool aborted = lane == 8 && v != 0ull;
+        const bool aborted = lane == kSyncGroups && v != 0ull;
         if (__any(aborted) || ++spins > spin_limit) {
             good = 0;
+            for (int q = lane; q < kSyncCopies; q += 64)
+                __hip_atomic_store(&sy->copy[q][kSyncGroups], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (lane == 0) __hip_atomic_store(&sy->abort_flag, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             break;
         }

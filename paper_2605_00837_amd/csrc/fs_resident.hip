@@ -118,7 +118,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     const bool streaming = STREAM && ms > NL;      // (STREAM = false: the launcher has seen that no workgroup has more)
     if (tid == 0) {
         // waits completed so far in this solve: the generation numbers of this launch go on from there
-        sGen = __hip_atomic_load(&X.sync->done[w & 7], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sGen = __hip_atomic_load(&X.sync->done[w % kSyncGroups], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sNsus = 0;
     }
     for (int x = tid; x < NP * R; x += T) {

@@ -23,10 +23,13 @@ __global__ __launch_bounds__(256) void k_init(Pots p, State *state, const float 
         state->fin_ticket = 0;
         state->err = __builtin_nan("");
     }
-    if (psync && t >= 64 && t < 73) {
-        if (t < 72) { psync->grp[t - 64].v = 0ull; psync->done[t - 64] = 0ull; }
+    if (psync && t >= 64 && t <= 64 + kSyncGroups) {
+        if (t < 64 + kSyncGroups) { psync->grp[t - 64].v = 0ull; psync->done[t - 64] = 0ull; }
         else psync->abort_flag = 0ull;
     }
+    if (psync)
+        for (int q = t; q < kSyncCopies * (kSyncGroups + 1); q += gridDim.x * 256)
+            psync->copy[q / (kSyncGroups + 1)][q % (kSyncGroups + 1)] = 0ull;
     double *la2 = const_cast<double *>(p.la2);
     double *lb2 = const_cast<double *>(p.lb2);
     if (t < p.n) {
