@@ -15,8 +15,9 @@
 // the stop decision is taken identically everywhere.  Arithmetic as everywhere else: exponent
 // arguments in fp64 (base 2), v_exp_f32 and the sums in fp32; both LSEs are exact (maximum first).
 //
-// Grid-wide waits: arrivals are counted hierarchically (8 group counters, one top counter, one
-// release word; all monotone, never reset during a solve), published values are
+// Grid-wide waits: arrivals are counted in 8 group counters; the workgroup that completes a group says so in
+// the `done` line, kept in 64 copies of which every workgroup polls one (as in the persistent pass,
+// fs_persist_sync.h; all monotone, never reset during a solve), published values are
 // written and read with agent-scope relaxed atomics and every thread waits for its own stores before
 // its workgroup arrives.  Two waits per round make single exchange buffers safe: partials of round
 // r + 1 are written after the second wait of round r, which every workgroup reaches only after it has
@@ -27,6 +28,7 @@
 #include <type_traits>
 
 #include "fs_kernels.h"
+#include "fs_persist_sync.h"
 
 namespace fs {
 
@@ -62,30 +64,16 @@ __device__ __forceinline__ float row16_add(float v) {
 }
 
 // Grid-wide wait number `gen` (1, 2, ...).  Every thread of the workgroup calls it after its last store
-// of the phase.  Returns false when the wait was abandoned (by this workgroup or by another).
+// of the phase; wave 0 counts the workgroup in and watches its copy of the `done` line (fs_persist_sync.h).
+// Returns false when the wait was abandoned (by this workgroup or by another).
 __device__ __forceinline__ bool grid_wait(GridSync *sy, unsigned long long gen, int W, int spin_limit, int *s_ok) {
 #if defined(__HIP_DEVICE_COMPILE__)
     __builtin_amdgcn_s_waitcnt(0);                       // this thread's published values have been acknowledged
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int good = 1;
-        const int grp = blockIdx.x & 7;
-        const unsigned long long members = (unsigned long long)((W - grp + 7) / 8);
-        if (bump(&sy->grp[grp].v) + 1ull == gen * members) {
-            const unsigned long long groups = (unsigned long long)(W < 8 ? W : 8);
-            if (bump(&sy->top.v) + 1ull == gen * groups)
-                __hip_atomic_store(&sy->release.v, gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        int spins = 0;
-        while (__hip_atomic_load(&sy->release.v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < gen) {
-            if (++spins > spin_limit || __hip_atomic_load(&sy->abort_flag.v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
-                good = 0;
-                __hip_atomic_store(&sy->abort_flag.v, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
-            }
-            __builtin_amdgcn_s_sleep(1);
-        }
-        *s_ok = good;
+    if (threadIdx.x < 64) {
+        const unsigned long long old = grid_arrive(&sy->ps);
+        const int good = fs::grid_wait(&sy->ps, old, gen, W, spin_limit);
+        if (threadIdx.x == 0) *s_ok = good;
     }
     __syncthreads();
     return *s_ok != 0;
@@ -96,11 +84,11 @@ __device__ __forceinline__ bool grid_wait(GridSync *sy, unsigned long long gen, 
 
 __global__ void k_grid_reset(GridSync *sy) {
     const int t = threadIdx.x;
-    if (t < 8) sy->grp[t].v = 0ull;
-    if (t == 8) sy->top.v = 0ull;
-    if (t == 9) sy->release.v = 0ull;
-    if (t == 10) sy->abort_flag.v = 0ull;
-    if (t == 11) sy->bad.v = 0ull;
+    if (t < kSyncGroups) { sy->ps.grp[t].v = 0ull; sy->ps.done[t] = 0ull; }
+    if (t == kSyncGroups) sy->ps.abort_flag = 0ull;
+    if (t == kSyncGroups + 1) sy->bad.v = 0ull;
+    for (int q = t; q < kSyncCopies * (kSyncGroups + 1); q += blockDim.x)
+        sy->ps.copy[q / (kSyncGroups + 1)][q % (kSyncGroups + 1)] = 0ull;
 }
 
 // PTS: point clouds - the tile holds |x_i - y_j|^2 in fp64, formed once from the fp32 coordinates in the
@@ -424,7 +412,7 @@ hipError_t launch_grid(hipStream_t st, const GridArgs &a0, void *scratch, int wm
     a.xchg2 = a.xchg1 + (size_t)kGridWMax * kGridLdx;
     a.sync = reinterpret_cast<GridSync *>(a.xchg2 + kGridLdx);
     if (a.spin_limit <= 0) a.spin_limit = 1 << 21;
-    hipLaunchKernelGGL(k_grid_reset, dim3(1), dim3(64), 0, st, a.sync);
+    hipLaunchKernelGGL(k_grid_reset, dim3(1), dim3(256), 0, st, a.sync);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int cb = (a.m + kGT - 1) / kGT;

@@ -199,8 +199,30 @@ struct SmallArgs {
 };
 hipError_t launch_small(hipStream_t st, const SmallArgs &a);
 
+// ---- the grid-wide wait of the kernels whose workgroups stay resident on every compute unit (fs_persist.hip,
+//      fs_resident.hip, fs_grid.hip; the code is in fs_persist_sync.h)
+struct GridLine { unsigned long long v; unsigned long long pad[31]; };      // 256 bytes
+// Counters of the persistent pass (all monotone over a solve).  A workgroup counts itself into one of 8 group
+// counters; the last of a group writes the generation into the group's word of the `done` line -- of every copy of
+// it: a polled line sees 8 plain stores per wait, no read-modify-write, and the polls of only a few workgroups
+// (polled by all 256, a line takes hundreds of requests per microsecond and the store everybody waits for queues
+// behind them).
+constexpr int kSyncGroups = 8;                   // arrival counters (a workgroup counts itself into number workgroup mod kSyncGroups)
+struct PersistSync {
+    GridLine grp[kSyncGroups];
+    unsigned long long done[kSyncGroups];        // generation each group has completed
+    unsigned long long abort_flag;
+    unsigned long long pad[31 - kSyncGroups];
+    // kSyncCopies copies of that line (words 0 .. kSyncGroups-1: done, then the abort flag), 256 bytes apart: a workgroup polls
+    // copy workgroup mod kSyncCopies, so that a line is watched by a few workgroups, not by all of them
+    unsigned long long copy[64][32];
+};
+constexpr int kSyncCopies = 64;
+
 // ---- mid-size dense problems: the whole solve in one launch over up to 32 workgroups (fs_coop.hip)
 constexpr int kCoopMax = 1024;                   // largest n, m
+// (up to 32 workgroups: one counter that everybody adds to and polls is the faster wait there, 5.66 against 5.81 us
+// per iteration at 256 x 256)
 struct CoopSync {                                // two 256-byte lines
     unsigned long long arrivals;                 // workgroups that have reached a grid-wide wait, ever
     unsigned long long pad0[31];
@@ -225,8 +247,8 @@ hipError_t launch_coop(hipStream_t st, const CoopArgs &a, void *scratch, int var
 //      grid-wide waits per iteration (fs_grid.hip)
 constexpr int kGridMaxN = 4096, kGridMaxM = 2048;
 constexpr int kGridWMax = 256;                   // most workgroups (each needs a compute unit of its own)
-struct GridLine { unsigned long long v; unsigned long long pad[31]; };      // 256 bytes
-struct GridSync { GridLine grp[8], top, release, abort_flag, bad; };
+// the one-launch kernel of fs_grid.hip waits the same way; `bad`: some workgroup met a non-finite value
+struct GridSync { PersistSync ps; GridLine bad; };
 struct GridArgs : SmallArgs {                    // batch is ignored (one problem)
     const float *X, *Y;                          // point clouds [n][d], [m][d] (then C is null), or null
     int32_t d;
@@ -237,22 +259,6 @@ struct GridArgs : SmallArgs {                    // batch is ignored (one proble
 };
 // ---- dense fp32 problems with 1024 < m <= 16384: a block of iterations of the fused row-panel pass in one
 //      launch, one resident workgroup per compute unit, two grid-wide waits per iteration (fs_persist.hip)
-// Counters of the persistent pass (all monotone over a solve).  A workgroup counts itself into one of 8 group
-// counters; the last of a group writes the generation into the group's word of the `done` line -- of every copy of
-// it: a polled line sees 8 plain stores per wait, no read-modify-write, and the polls of only a few workgroups
-// (polled by all 256, a line takes hundreds of requests per microsecond and the store everybody waits for queues
-// behind them).
-constexpr int kSyncGroups = 8;                   // arrival counters (a workgroup counts itself into number workgroup mod kSyncGroups)
-struct PersistSync {
-    GridLine grp[kSyncGroups];
-    unsigned long long done[kSyncGroups];        // generation each group has completed
-    unsigned long long abort_flag;
-    unsigned long long pad[31 - kSyncGroups];
-    // kSyncCopies copies of that line (words 0 .. kSyncGroups-1: done, then the abort flag), 256 bytes apart: a workgroup polls
-    // copy workgroup mod kSyncCopies, so that a line is watched by a few workgroups, not by all of them
-    unsigned long long copy[64][32];
-};
-constexpr int kSyncCopies = 64;
 struct PersistArgs {
     PersistSync *sync;
     double *wgpart;                              // [workgroups]: error terms of each workgroup's rows
