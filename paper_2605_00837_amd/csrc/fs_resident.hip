@@ -3,13 +3,18 @@
 //
 // A compute unit of this device has 160 KiB of LDS and 512 KiB of vector registers.  With one workgroup of 512
 // lanes per compute unit (two waves per SIMD, 256 registers per lane), a share of up to 4 panels of 64 KiB
-// (256 KiB: a 64 MiB matrix on 256 compute units, 4096 x 4096 or 2048 x 8192) is read from memory ONCE per
-// launch -- panels 0 and 1 into LDS, panels 2 and 3 into 64 registers per lane -- and every iteration of the
-// block runs its row and column phase from there.  The iteration is then bound by the vector ALUs (about 12
-// instructions per entry) and by the exchange, not by the memory system; the persistent pass that streams C
-// (fs_persist.hip) reads it from the last-level cache every iteration.  (1024 lanes with 128 registers each
-// hold the same bytes, but 32 of 128 registers for the panels leave the hot loop short: the compiler then keeps
-// V in scratch memory and the pass is slower than the streaming one.)
+// (256 KiB: a 64 MiB matrix on 256 compute units, e.g. 8192 x 2048, 4096 x 4096 or 2048 x 8192) is read from
+// memory ONCE per launch -- panels 0 and 1 into 64 registers per lane, panels 2 and 3 into LDS -- and every
+// iteration of the block runs its row and column phase from there.  The iteration is then bound by the vector
+// ALUs (about 11 instructions per entry) and by the exchange, not by the memory system; the persistent pass
+// that streams C (fs_persist.hip) reads it from the last-level cache every iteration.  (1024 lanes with 128
+// registers each hold the same bytes, but 32 of 128 registers for the panels leave the hot loop short of
+// registers and it runs 8 % slower.)
+//
+// Widths from 1025 to 8192 columns are taken: a panel is 8 rows up to 2048 columns, 4 up to 4096, 2 beyond, and
+// the lanes whose columns lie past m are masked.  The grid is one workgroup per compute unit, fewer for a short
+// matrix.  A share of more than 4 panels (widths without idle lanes only) is streamed: the two register panels
+// stay, the others go through the two LDS buffers two panels ahead, as in fs_persist.hip.
 //
 // Everything else is the persistent pass: the same optimistic row phase with its exact redo, the same fp32
 // column sums, the same exchange between two bounded grid-wide waits (publish, merge of the own strip with the
