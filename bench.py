@@ -40,14 +40,15 @@ EXP_PEAK_PER_S = 256 * 4 * 64 * 2.4e9 / 8
 def _traffic_from_profiles(kernel, n, m):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary of the same
     workload (counters are collected in runs of their own, not in this run)."""
-    path = os.path.join(ROOT, "profiles", "k_persist_c2_dense8192_pmc.json")
-    try:
-        with open(path) as fh:
-            rec = json.load(fh)
-        if rec.get("n") == n and rec.get("m") == m and rec.get("kernel", "").startswith(kernel):
-            return rec.get("hbm_bytes_per_launch"), os.path.relpath(path, ROOT)
-    except (OSError, ValueError):
-        pass
+    for name in ("k_resident_c2_dense8192_pmc.json", "k_persist_c2_dense8192_pmc.json"):
+        path = os.path.join(ROOT, "profiles", name)
+        try:
+            with open(path) as fh:
+                rec = json.load(fh)
+            if rec.get("n") == n and rec.get("m") == m and rec.get("kernel", "").startswith(kernel):
+                return rec.get("hbm_bytes_per_launch"), os.path.relpath(path, ROOT)
+        except (OSError, ValueError):
+            pass
     return None, None
 
 
@@ -232,7 +233,16 @@ def bench_dense(args, name):
                                             "the timed solve run right after it (stamping costs queue time)",
                            "iterations_per_launch": covered / max(launches, 1), "kernel_us_per_iteration": per_iter_ms * 1e3,
                            "algorithmic_bytes_per_launch": alg_bytes_launch}
-        if kern_name == "k_resident":
+        rows_pp = 8 if m <= 2048 else 4 if m <= 4096 else 2           # rows per panel of k_resident
+        panels = -(-n // rows_pp)
+        wgs = min(torch.cuda.get_device_properties(0).multi_processor_count, panels, 256)
+        if kern_name == "k_resident" and panels > 4 * wgs:
+            per_wg = -(-panels // wgs)
+            out["roofline"]["resident"] = {
+                "note": "two of the %d panels of every workgroup stay in registers for a whole launch: %.3f of C is "
+                        "read from memory per iteration; achieved / frac are the algorithmic bytes (all of C) over "
+                        "time, as for any other kernel" % (per_wg, 1.0 - 2.0 / per_wg)}
+        elif kern_name == "k_resident":
             # C stays in LDS and registers for a whole launch: the algorithmic bytes above are NOT read from memory
             # (achieved / frac say how this compares with a pass that would stream them).  What bounds the pass is
             # vector-ALU issue: 8 issue slots per entry (cvt, fma64, add64, cvt, v_exp_f32 = 2, add, fma) of 4 cycles

@@ -35,9 +35,12 @@ constexpr int kResRegs = 2;             // panels a workgroup keeps in registers
 constexpr int kResLds = 2;              // panels the LDS holds: the other resident ones, or the two staging buffers
 constexpr int kResPanels = kResRegs + kResLds;   // up to here the whole share stays on the chip
 constexpr int kResMaxPanels = 32;       // panels per workgroup at most (row scalars in LDS)
-constexpr int kResAutoPanels = 12;      // up to here this kernel is the faster one (measured: 27.1 against 28.6 us per
-                                        // iteration at 4096 x 8192, 36.5 against 37.3 at 6144 x 8192, a tie at 8192 x
-                                        // 8192, 73.7 against 69.0 at 12288 x 8192)
+constexpr int kResAutoPanels = 16;      // up to here this kernel is the faster one at 4096 and 8192 columns (measured,
+                                        // 8192 columns: 27.1 against 28.6 us per iteration at 4096 rows, 35.7 / 36.1 at
+                                        // 6144, 44.9 / 45.8 at 8192, 59.1 / 56.5 at 10240, 73.6 / 68.6 at 12288; 4096
+                                        // columns: 46.5 / 47.7 at 16384 rows, 76.9 / 73.8 at 24576); at 2048 columns,
+                                        // where the 1024-lane kernel has idle lanes, as far as it goes (32768 rows:
+                                        // 53.8 against 96.7)
 
 // All-reduce over aligned groups of LW lanes (16: a DPP row, rotated; 8: lane ^ 1, lane ^ 2, then the half row mirrored).
 template <int LW>
@@ -642,7 +645,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 // that a workgroup would merge a strip of more than 64 columns.  Up to kResPanels panels per workgroup the whole
 // share stays on the chip, for any width.  Beyond, the panels behind the register panels are streamed, which is
 // done only for the widths without idle lanes (2048, 4096 and 8192 columns): up to kResAutoPanels as the library's
-// own choice, up to kResMaxPanels on request (`all`).  Returns the workgroups of the launch, 0 when the shape is
+// own choice (at 2048 columns: up to kResMaxPanels), up to kResMaxPanels on request (`all`).  Returns the workgroups of the launch, 0 when the shape is
 // not taken.
 int dense_resident_grid(int n, int m, int cus, bool all) {
     if (cus < 1 || n < 1 || m <= 1024 || m > 8192) return 0;
@@ -653,7 +656,7 @@ int dense_resident_grid(int n, int m, int cus, bool all) {
     if (g > 256) g = 256;                                  // the exchange buffer holds 256 sets of column sums
     const int strip = (int)(((m + g - 1) / g + 3) & ~3ll);
     if (strip > 64) return 0;
-    const long long most = !fullw ? kResPanels : all ? kResMaxPanels : kResAutoPanels;
+    const long long most = !fullw ? kResPanels : (all || m == 2048) ? kResMaxPanels : kResAutoPanels;
     return npanels <= most * g ? (int)g : 0;
 }
 

@@ -48,7 +48,7 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
           (70, 2000), (3001, 5000), (129, 4096), (200, 1028), (1100, 6001), (600, 9000),
           (4099, 4096), (2047, 4096), (9001, 4096),      # 4096 columns: panels of 4 rows from 2048 rows up, of 2 below
           (4096, 4096), (1024, 4096), (3070, 4096), (2048, 8192), (1500, 8192),   # shares of C that stay on the chip
-          (2100, 8192), (6001, 4096), (12000, 4096), (13000, 4096), (6200, 8192),
+          (2100, 8192), (6001, 4096), (12000, 4096), (13000, 4096), (6200, 8192), (17000, 4096), (8300, 8192),
           (3000, 3000), (1500, 2049), (4000, 4095), (2000, 6145), (1025, 8191), (1200, 5000), (1023, 4097),   # ... idle lanes
           (2048, 2048), (8190, 2048), (3000, 1500), (5000, 1025), (2051, 2047), (20000, 2048), (70000, 2048)]   # panels of 8 rows      # ... and shares of which the 512-lane kernel streams a part
 
@@ -56,7 +56,7 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
 def _resident(n, m, cus=256, most=4):
     """Whether the 512-lane kernel of the persistent pass takes the shape (1024 < m <= 8192, 1 .. most panels of 64 KiB
     per workgroup of a grid of min(cus, panels) workgroups that merge at most 64 columns each): up to 4 panels the matrix stays on the chip for a whole launch; beyond
-    that, and only at 2048, 4096 and 8192 columns, the panels behind the two in registers are streamed: up to 12 panels it is
+    that, and only at 2048, 4096 and 8192 columns, the panels behind the two in registers are streamed: up to 16 panels (32 at 2048 columns) it is
     the library's own choice (fused_variant = 1 asks for the 1024-lane streaming kernel instead), up to 32 it can be
     asked for (fused_variant = 2)."""
     if not 1024 < m <= 8192:
@@ -68,6 +68,8 @@ def _resident(n, m, cus=256, most=4):
         return False
     if m not in (2048, 4096, 8192):
         most = min(most, 4)
+    elif m == 2048 and most == 16:
+        most = 32
     return panels <= most * grid
 
 
@@ -82,7 +84,7 @@ def test_persistent_pass_matches_oracle(fs, oracle, n, m):
     w = W.random_dense(n, m, seed=6000 + n + m, cmax=2.0, eps=0.03)
     iters = 52                                  # one whole block of 50 iterations and a short one
     ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C)
-    variants = (0, 1) if _resident(n, m, cus, most=12) else (0, 2) if _resident(n, m, cus, most=32) else (0,)
+    variants = (0, 1) if _resident(n, m, cus, most=16) else (0, 2) if _resident(n, m, cus, most=32) else (0,)
     for variant in variants:
         r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, iters, 0.0, C=dev(w.C), want_f64=True, kernel_mode=6,
                                  fused_variant=variant, time_kernel_every=1)
@@ -90,7 +92,7 @@ def test_persistent_pass_matches_oracle(fs, oracle, n, m):
         assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
         assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
         name = fs.fs_last_kernel_timing()[2]
-        assert name == ("k_resident" if (_resident(n, m, cus, most=12) and variant == 0) or variant == 2 else "k_persist"), \
+        assert name == ("k_resident" if (_resident(n, m, cus, most=16) and variant == 0) or variant == 2 else "k_persist"), \
             (n, m, variant, name)
     assert pot_err(r["f"].cpu().numpy(), ref["f"], w.eps) < TOL_F32
     err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
