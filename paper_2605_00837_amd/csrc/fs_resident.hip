@@ -13,7 +13,7 @@
 //
 // Widths from 1025 to 8192 columns are taken: a panel is 8 rows up to 2048 columns, 4 up to 4096, 2 beyond, and
 // the lanes whose columns lie past m are masked.  The grid is one workgroup per compute unit, fewer for a short
-// matrix.  A share of more than 4 panels (widths without idle lanes only) is streamed: the two register panels
+// matrix.  A share of more than 4 panels is streamed: the two register panels
 // stay, the others go through the two LDS buffers two panels ahead, as in fs_persist.hip.
 //
 // Everything else is the persistent pass: the same optimistic row phase with its exact redo, the same fp32
@@ -81,7 +81,6 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     constexpr int NDMA = R * Q;                // prefetch loads per panel and wave
     constexpr int LW = R > 4 ? 8 : 16;         // lanes per row in the merge of the wave sums: NW partials (then zeros)
     static_assert(R * Q * NW == 64, "a panel is 64 KiB");
-    static_assert(FULLW || !STREAM, "a width with idle lanes is taken only where C is read once per launch");
     static_assert(R * LW <= 64, "one wave merges all (row, wave) partials in one shot");
     constexpr float kRowHi = 1.1529215e18f;    // 2^60
     constexpr float kRowLo = 9.5367432e-07f;   // 2^-20
@@ -152,9 +151,14 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int q = 0; q < Q; ++q)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, &stage[buf][tw][r][q][0], 16, (tw * 64 + lane) * 16,
+            for (int q = 0; q < Q; ++q) {
+                // a lane whose columns lie past m asks for an address outside the descriptor: nothing is read from
+                // memory for it, zeros land in LDS, and every wave still issues the same number of loads
+                const int slot = tw * 64 + lane;
+                const int voff = (FULLW || (q * T + slot) * 4 < m) ? slot * 16 : 0x40000000;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, &stage[buf][tw][r][q][0], 16, voff,
                                                          (r * m + q * T * 4) * 4, 0, 0);
+            }
     };
     // the panel behind the register panels that a pass visits in position t
     auto lds_panel = [&](int t, bool rev) { return NR + (t == 0 ? 0 : (rev ? ms - t : t)); };
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     const bool own_ok = tid < Sw && own_col < strip1;
 
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));         // the LDS panels have landed
-    if (!FULLW) {
+    if (!FULLW && !STREAM) {
         // the same for the LDS panels (every lane its own entries; once per launch: they are resident)
 #pragma unroll
         for (int b = 0; b < NL; ++b)
@@ -269,6 +273,24 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                     o[0] = (double)c4.x; o[1] = (double)c4.y; o[2] = (double)c4.z; o[3] = (double)c4.w;
                 }
             };
+            if constexpr (REG < 0 && !FULLW && STREAM) {
+                // a staged panel has just landed: the one lane per row that owns the last valid column clears what it
+                // read past it (entries of the next row: they count for nothing, V = -inf there, and must not be NaN)
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    const int col = (q * T + tid) * 4;
+                    if (col < m && col + 4 > m) {
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+                            float4 c4 = stage[slot - NR][wave][r][q][lane];
+                            if (col + 1 >= m) c4.y = 0.0f;
+                            if (col + 2 >= m) c4.z = 0.0f;
+                            if (col + 3 >= m) c4.w = 0.0f;
+                            stage[slot - NR][wave][r][q][lane] = c4;
+                        }
+                    }
+                }
+            }
             // ---- row phase, optimistic: e = 2^(x - rho_r), summed
             float ev[R][Q][4];
 #pragma unroll
@@ -643,20 +665,22 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 // The shapes this kernel takes: fp32 costs, 1024 < m <= 8192 (panels of 8 rows up to 2048 columns, of 4 up to 4096,
 // of 2 beyond), on a grid of one workgroup per compute unit, never more than there are panels and never so few
 // that a workgroup would merge a strip of more than 64 columns.  Up to kResPanels panels per workgroup the whole
-// share stays on the chip, for any width.  Beyond, the panels behind the register panels are streamed, which is
-// done only for the widths without idle lanes (2048, 4096 and 8192 columns): up to kResAutoPanels as the library's
-// own choice (at 2048 columns: up to kResMaxPanels), up to kResMaxPanels on request (`all`).  Returns the workgroups of the launch, 0 when the shape is
-// not taken.
+// share stays on the chip; beyond, the panels behind the register panels are streamed: up to kResAutoPanels as the
+// library's own choice (at exactly 2048 columns: up to kResMaxPanels; between 4097 and 8191 columns: not at all),
+// up to kResMaxPanels on request (`all`).
+// Returns the workgroups of the launch, 0 when the shape is not taken.
 int dense_resident_grid(int n, int m, int cus, bool all) {
     if (cus < 1 || n < 1 || m <= 1024 || m > 8192) return 0;
     const int R = m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
-    const bool fullw = m == 2048 || m == 4096 || m == 8192;
     const long long npanels = ((long long)n + R - 1) / R;
     long long g = npanels < cus ? npanels : cus;
     if (g > 256) g = 256;                                  // the exchange buffer holds 256 sets of column sums
     const int strip = (int)(((m + g - 1) / g + 3) & ~3ll);
     if (strip > 64) return 0;
-    const long long most = !fullw ? kResPanels : (all || m == 2048) ? kResMaxPanels : kResAutoPanels;
+    // (a width between 4097 and 8191 columns is streamed by the 1024-lane kernel as fast or faster: 8000 x 8000 46.6
+    // against 47.3 us per iteration, 6000 x 6000 34.1 / 34.9; below, this one wins: 16384 x 3000 47.6 against 53.5,
+    // 8000 x 2500 25.6 / 30.4, 12000 x 1500 23.5 / 40.1)
+    const long long most = all || m == 2048 ? kResMaxPanels : (m > 4096 && m < 8192) ? kResPanels : kResAutoPanels;
     return npanels <= most * g ? (int)g : 0;
 }
 
@@ -677,11 +701,14 @@ hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs
         if (stream) launch_stamped((k_resident<4, 2, 8, true, true>), g, block, st, tm, a, x, c);
         else launch_stamped((k_resident<4, 2, 8, false, true>), g, block, st, tm, a, x, c);
     } else if (m < 2048) {
-        launch_stamped((k_resident<1, 8, 8, false, false>), g, block, st, tm, a, x, c);
+        if (stream) launch_stamped((k_resident<1, 8, 8, true, false>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<1, 8, 8, false, false>), g, block, st, tm, a, x, c);
     } else if (m < 4096) {
-        launch_stamped((k_resident<2, 4, 8, false, false>), g, block, st, tm, a, x, c);
+        if (stream) launch_stamped((k_resident<2, 4, 8, true, false>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<2, 4, 8, false, false>), g, block, st, tm, a, x, c);
     } else {
-        launch_stamped((k_resident<4, 2, 8, false, false>), g, block, st, tm, a, x, c);
+        if (stream) launch_stamped((k_resident<4, 2, 8, true, false>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<4, 2, 8, false, false>), g, block, st, tm, a, x, c);
     }
     return hipGetLastError();
 }

@@ -50,13 +50,14 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
           (4096, 4096), (1024, 4096), (3070, 4096), (2048, 8192), (1500, 8192),   # shares of C that stay on the chip
           (2100, 8192), (6001, 4096), (12000, 4096), (13000, 4096), (6200, 8192), (17000, 4096), (8300, 8192),
           (3000, 3000), (1500, 2049), (4000, 4095), (2000, 6145), (1025, 8191), (1200, 5000), (1023, 4097),   # ... idle lanes
-          (2048, 2048), (8190, 2048), (3000, 1500), (5000, 1025), (2051, 2047), (20000, 2048), (70000, 2048)]   # panels of 8 rows      # ... and shares of which the 512-lane kernel streams a part
+          (2048, 2048), (8190, 2048), (3000, 1500), (5000, 1025), (2051, 2047), (20000, 2048), (70000, 2048),   # panels of 8 rows
+          (4200, 2500), (8300, 1500), (2200, 5000), (2300, 8000), (6000, 6000), (9000, 3000), (5000, 6145)]   # ... idle lanes, streamed      # ... and shares of which the 512-lane kernel streams a part
 
 
 def _resident(n, m, cus=256, most=4):
     """Whether the 512-lane kernel of the persistent pass takes the shape (1024 < m <= 8192, 1 .. most panels of 64 KiB
     per workgroup of a grid of min(cus, panels) workgroups that merge at most 64 columns each): up to 4 panels the matrix stays on the chip for a whole launch; beyond
-    that, and only at 2048, 4096 and 8192 columns, the panels behind the two in registers are streamed: up to 16 panels (32 at 2048 columns) it is
+    that the panels behind the two in registers are streamed: up to 16 panels (32 at 2048 columns) it is
     the library's own choice (fused_variant = 1 asks for the 1024-lane streaming kernel instead), up to 32 it can be
     asked for (fused_variant = 2)."""
     if not 1024 < m <= 8192:
@@ -66,10 +67,10 @@ def _resident(n, m, cus=256, most=4):
     grid = min(cus, panels, 256)
     if (-(-m // grid) + 3) // 4 * 4 > 64:                    # a workgroup merges a strip of at most 64 columns
         return False
-    if m not in (2048, 4096, 8192):
-        most = min(most, 4)
-    elif m == 2048 and most == 16:
+    if m == 2048 and most == 16:
         most = 32
+    if 4096 < m < 8192 and most == 16:
+        most = 4                                             # streamed by the 1024-lane kernel unless asked otherwise
     return panels <= most * grid
 
 
