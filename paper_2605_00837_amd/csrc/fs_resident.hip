@@ -72,15 +72,15 @@ __device__ __forceinline__ double group_max_f64(double x) {
     return x;
 }
 
-// Q groups of 4 adjacent columns per lane (column(q, e) = (q 512 + tid) 4 + e), R rows per panel, R Q = 8 (a panel
-// is 64 KiB: 32 entries per lane).  FULLW: m = 2048 Q, every lane owns valid columns; else m < 2048 Q and the
+// Q groups of 4 adjacent columns per lane (column(q, e) = (q 512 + tid) 4 + e), R rows per panel, R Q <= 8 (a panel
+// is at most 64 KiB: 32 entries per lane; 48 KiB for the widths up to 6144 columns).  FULLW: m = 2048 Q, every lane owns valid columns; else m < 2048 Q and the
 // columns past m are masked (V = -inf, C = 0, nothing published).
 template <int Q, int R, int NW, bool STREAM, bool FULLW>
 __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X, Ctl c) {
     constexpr int T = 64 * NW, NP = kResMaxPanels, NR = kResRegs, NL = kResLds;
     constexpr int NDMA = R * Q;                // prefetch loads per panel and wave
     constexpr int LW = R > 4 ? 8 : 16;         // lanes per row in the merge of the wave sums: NW partials (then zeros)
-    static_assert(R * Q * NW == 64, "a panel is 64 KiB");
+    static_assert(R * Q * NW <= 64, "a panel is at most 64 KiB");
     static_assert(R * LW <= 64, "one wave merges all (row, wave) partials in one shot");
     constexpr float kRowHi = 1.1529215e18f;    // 2^60
     constexpr float kRowLo = 9.5367432e-07f;   // 2^-20
@@ -663,10 +663,10 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 }  // namespace
 
 // The shapes this kernel takes: fp32 costs, 1024 < m <= 8192 (panels of 8 rows up to 2048 columns, of 4 up to 4096,
-// of 2 beyond), on a grid of one workgroup per compute unit, never more than there are panels and never so few
+// of 2 beyond; 2048, 4096, 6144 or 8192 column slots), on a grid of one workgroup per compute unit, never more than there are panels and never so few
 // that a workgroup would merge a strip of more than 64 columns.  Up to kResPanels panels per workgroup the whole
 // share stays on the chip; beyond, the panels behind the register panels are streamed: up to kResAutoPanels as the
-// library's own choice (at exactly 2048 columns: up to kResMaxPanels; between 4097 and 8191 columns: not at all),
+// library's own choice (at exactly 2048 columns: up to kResMaxPanels; between 6145 and 8191 columns: not at all),
 // up to kResMaxPanels on request (`all`).
 // Returns the workgroups of the launch, 0 when the shape is not taken.
 int dense_resident_grid(int n, int m, int cus, bool all) {
@@ -677,10 +677,10 @@ int dense_resident_grid(int n, int m, int cus, bool all) {
     if (g > 256) g = 256;                                  // the exchange buffer holds 256 sets of column sums
     const int strip = (int)(((m + g - 1) / g + 3) & ~3ll);
     if (strip > 64) return 0;
-    // (a width between 4097 and 8191 columns is streamed by the 1024-lane kernel as fast or faster: 8000 x 8000 46.6
-    // against 47.3 us per iteration, 6000 x 6000 34.1 / 34.9; below, this one wins: 16384 x 3000 47.6 against 53.5,
-    // 8000 x 2500 25.6 / 30.4, 12000 x 1500 23.5 / 40.1)
-    const long long most = all || m == 2048 ? kResMaxPanels : (m > 4096 && m < 8192) ? kResPanels : kResAutoPanels;
+    // (a width between 6145 and 8191 columns is streamed by the 1024-lane kernel as fast or faster: 8000 x 8000 46.4
+    // against 47.3 us per iteration; below, this one wins: 6000 x 6000 31.8 against 34.0, 8000 x 5000 38.7 / 40.8,
+    // 16384 x 3000 47.6 / 53.5, 8000 x 2500 25.6 / 30.4, 12000 x 1500 23.5 / 40.1)
+    const long long most = all || m == 2048 ? kResMaxPanels : (m > 6144 && m < 8192) ? kResPanels : kResAutoPanels;
     return npanels <= most * g ? (int)g : 0;
 }
 
@@ -697,6 +697,9 @@ hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs
     } else if (m == 4096) {
         if (stream) launch_stamped((k_resident<2, 4, 8, true, true>), g, block, st, tm, a, x, c);
         else launch_stamped((k_resident<2, 4, 8, false, true>), g, block, st, tm, a, x, c);
+    } else if (m == 6144) {
+        if (stream) launch_stamped((k_resident<3, 2, 8, true, true>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<3, 2, 8, false, true>), g, block, st, tm, a, x, c);
     } else if (m == 8192) {
         if (stream) launch_stamped((k_resident<4, 2, 8, true, true>), g, block, st, tm, a, x, c);
         else launch_stamped((k_resident<4, 2, 8, false, true>), g, block, st, tm, a, x, c);
@@ -706,6 +709,9 @@ hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs
     } else if (m < 4096) {
         if (stream) launch_stamped((k_resident<2, 4, 8, true, false>), g, block, st, tm, a, x, c);
         else launch_stamped((k_resident<2, 4, 8, false, false>), g, block, st, tm, a, x, c);
+    } else if (m < 6144) {
+        if (stream) launch_stamped((k_resident<3, 2, 8, true, false>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<3, 2, 8, false, false>), g, block, st, tm, a, x, c);
     } else {
         if (stream) launch_stamped((k_resident<4, 2, 8, true, false>), g, block, st, tm, a, x, c);
         else launch_stamped((k_resident<4, 2, 8, false, false>), g, block, st, tm, a, x, c);

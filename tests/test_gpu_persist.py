@@ -51,7 +51,8 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
           (2100, 8192), (6001, 4096), (12000, 4096), (13000, 4096), (6200, 8192), (17000, 4096), (8300, 8192),
           (3000, 3000), (1500, 2049), (4000, 4095), (2000, 6145), (1025, 8191), (1200, 5000), (1023, 4097),   # ... idle lanes
           (2048, 2048), (8190, 2048), (3000, 1500), (5000, 1025), (2051, 2047), (20000, 2048), (70000, 2048),   # panels of 8 rows
-          (4200, 2500), (8300, 1500), (2200, 5000), (2300, 8000), (6000, 6000), (9000, 3000), (5000, 6145)]   # ... idle lanes, streamed      # ... and shares of which the 512-lane kernel streams a part
+          (4200, 2500), (8300, 1500), (2200, 5000), (2300, 8000), (6000, 6000), (9000, 3000), (5000, 6145),
+          (2048, 6144), (5000, 6144), (1000, 6000), (2301, 4097)]   # ... idle lanes, streamed      # ... and shares of which the 512-lane kernel streams a part
 
 
 def _resident(n, m, cus=256, most=4):
@@ -69,7 +70,7 @@ def _resident(n, m, cus=256, most=4):
         return False
     if m == 2048 and most == 16:
         most = 32
-    if 4096 < m < 8192 and most == 16:
+    if 6144 < m < 8192 and most == 16:
         most = 4                                             # streamed by the 1024-lane kernel unless asked otherwise
     return panels <= most * grid
 
