@@ -51,6 +51,7 @@ struct Layout {
     int n, m, d, n_ld, m_ld;
     // dense
     int P_stream, rpp_stream, P_fused;
+    int P_part;            // sets of m_ld doubles that o_part holds
     int row_splits, row_cps;     // column ranges of the streaming row pass (1: none)
     // points
     int JSf, cpsf, JSg, cpsg;
@@ -81,7 +82,10 @@ Layout make_layout(int n, int m, int d) {
     if (d == 0) {
         dense_stream_plan(n, m, &L.P_stream, &L.rpp_stream);
         dense_fused_plan(n, m, &L.P_fused);
-        const int Pmax = L.P_stream > L.P_fused ? L.P_stream : L.P_fused;
+        int Pmax = L.P_stream > L.P_fused ? L.P_stream : L.P_fused;
+        // (a width that only the resident form of the persistent pass takes: its exchange buffer holds 256 sets)
+        if (dense_persist_supported(n, m, nullptr, 0) && Pmax < 256) Pmax = 256;
+        L.P_part = Pmax;
         L.o_part = take(sizeof(double) * (size_t)Pmax * L.m_ld);
         L.o_part2 = L.o_part;
         dense_row_split_plan(n, m, &L.row_splits, &L.row_cps);
@@ -298,8 +302,10 @@ struct Solve {
         return a;
     }
 
+    // sets of column sums the exchange buffer of the persistent pass holds (up to 1024 columns the pass has its own count)
+    int persist_sets() const { return pr.m <= 1024 ? L.P_part : L.P_fused; }
     const char *dominant_kernel() const {
-        if (persist) return dense_persist_resident(pr.n, pr.m, cus < L.P_fused ? cus : L.P_fused, opt.fused_variant % 100) ? "k_resident" : "k_persist";
+        if (persist) return dense_persist_resident(pr.n, pr.m, cus < persist_sets() ? cus : persist_sets(), opt.fused_variant % 100) ? "k_resident" : "k_persist";
         return mode == 1 ? "k_row_stream" : mode == 2 ? (fused_is_fp32_cols() ? "k_fused_pf" : "k_fused") : "k_points_lse";
     }
     // a block of up to nb iterations in one launch of the persistent fused pass
@@ -308,8 +314,8 @@ struct Solve {
         tm.t0 = t0;
         tm.t1 = t1;
         DenseArgs a = dense(FUSED);
-        a.P = L.P_fused;                       // sets of column sums the exchange buffer holds
-        const int cu = cus < L.P_fused ? cus : L.P_fused;
+        a.P = persist_sets();
+        const int cu = cus < a.P ? cus : a.P;
         return launch_persist(st, a, ctl(0), ws + L.o_persist, cu, nb, opt.wait_limit, opt.skip_final_err ? 0 : 1,
                               opt.fused_variant % 100, tm);
     }
@@ -904,7 +910,7 @@ int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const 
     if (v != FS_OK) return v;
     S.persist = persist_path(pr, opts, /*blocking=*/true, &S.cus);
     if (!S.persist && opts && opts->kernel_mode == 6) {
-        set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (n = %d, m = %d, %d compute units)", pr.n, pr.m, S.cus);
+        set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (and up to 1024 columns at most 8192 rows per compute unit) (n = %d, m = %d, %d compute units)", pr.n, pr.m, S.cus);
         return FS_ERR_UNSUPPORTED;
     }
     return run_solve_blocking(S, dc, f, g, result_host);
@@ -963,7 +969,7 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
     if (v != FS_OK) return v;
     S.persist = persist_path(pr, opts, /*blocking=*/false, &S.cus);      // on request only
     if (!S.persist && opts && opts->kernel_mode == 6) {
-        set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (n = %d, m = %d, %d compute units)", pr.n, pr.m, S.cus);
+        set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (and up to 1024 columns at most 8192 rows per compute unit) (n = %d, m = %d, %d compute units)", pr.n, pr.m, S.cus);
         return FS_ERR_UNSUPPORTED;
     }
     return run_solve_async(S, f, g, result_dev);
@@ -1126,7 +1132,7 @@ int fs_kernel_choice(int n, int m, int d, const fs_options *opts, int blocking, 
     const bool persist = persist_path(pr, opts, blocking != 0, &pcus);
     g_cus_override = 0;
     if (persist) return FS_KERNEL_PERSIST;
-    if (km == 6) { set_err("kernel_mode 6 needs at least m / 64 row panels and compute units"); return FS_ERR_UNSUPPORTED; }
+    if (km == 6) { set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (and up to 1024 columns at most 8192 rows per compute unit)"); return FS_ERR_UNSUPPORTED; }
     if (km == 2 && !fused_ok) { set_err("fused kernel does not support m = %d", m); return FS_ERR_UNSUPPORTED; }
     if (km > 2) { set_err("kernel_mode %d does not take this problem", km); return FS_ERR_UNSUPPORTED; }
     return (km == 2 || (km == 0 && fused_ok)) ? FS_KERNEL_FUSED : FS_KERNEL_STREAM;

@@ -572,11 +572,14 @@ bool persist_shape(int n, int m, PShape *s) {
     return true;
 }
 
+// widths that only the resident form takes (two row groups per workgroup): the streaming form has no shape for them
+bool narrow_shape(int m) { return m > 512 && m <= 1024; }
+
 }  // namespace
 
 bool dense_persist_supported(int n, int m, const void *C, int c_dtype) {
     PShape s;
-    return c_dtype == 0 && persist_shape(n, m, &s) && ((reinterpret_cast<uintptr_t>(C) & 3u) == 0);
+    return c_dtype == 0 && (persist_shape(n, m, &s) || narrow_shape(m)) && ((reinterpret_cast<uintptr_t>(C) & 3u) == 0);
 }
 
 // Workgroups of the persistent launch: one per compute unit, never more than there are panels.  0 when the
@@ -584,6 +587,7 @@ bool dense_persist_supported(int n, int m, const void *C, int c_dtype) {
 // them, so a short matrix (few panels) or a small device leaves too few workgroups for a wide one.
 int dense_persist_grid(int n, int m, int cus) {
     PShape s;
+    if (narrow_shape(m)) return dense_resident_grid(n, m, cus > 256 ? 256 : cus, true);
     if (!persist_shape(n, m, &s) || cus < 1) return 0;
     const int npanels = (n + s.R - 1) / s.R;
     int g = npanels < cus ? npanels : cus;
@@ -596,14 +600,16 @@ int dense_persist_grid(int n, int m, int cus) {
 size_t persist_scratch_bytes() { return sizeof(PersistSync) + sizeof(double) * kWgPartLd; }
 
 bool dense_persist_resident(int n, int m, int cus, int variant) {
+    if (narrow_shape(m)) return dense_resident_grid(n, m, cus > 256 ? 256 : cus, true) > 0;
     return variant != 1 && dense_resident_grid(n, m, cus > 256 ? 256 : cus, variant == 2) > 0;
 }
 
 
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
                           int spin_limit, int final_err, int variant, const Stamp &tm) {
-    PShape s;
-    if (!scratch || a.c_dtype != 0 || !persist_shape(a.p.n, a.p.m, &s) || nb < 1) return hipErrorInvalidValue;
+    PShape s{0, 0};
+    const bool narrow = narrow_shape(a.p.m);
+    if (!scratch || a.c_dtype != 0 || !(narrow || persist_shape(a.p.n, a.p.m, &s)) || nb < 1) return hipErrorInvalidValue;
     const int g = dense_persist_grid(a.p.n, a.p.m, cus);
     // the exchange buffer holds a.P sets of column sums, and [strip][source][strip width rounded up to a power of
     // two] floats must fit what a.P sets of doubles take
@@ -625,6 +631,7 @@ hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void
     x.trace = nullptr;
     if (const char *tp = getenv("FS_TRACE_PTR")) x.trace = reinterpret_cast<long long *>(strtoull(tp, nullptr, 0));
 #endif
+    if (narrow) return launch_resident(st, a, x, c, g, tm);      // (g is the resident grid, and it fits)
     if (variant != 1) {
         // (cus is at most a.P here: the exchange buffer holds a set of column sums per workgroup of either form)
         const int gr = dense_resident_grid(a.p.n, a.p.m, cus > 256 ? 256 : cus, variant == 2);

@@ -42,7 +42,7 @@ constexpr int kResAutoPanels = 16;      // up to here this kernel is the faster 
                                         // where the 1024-lane kernel has idle lanes, as far as it goes (32768 rows:
                                         // 53.8 against 96.7)
 
-// All-reduce over aligned groups of LW lanes (16: a DPP row, rotated; 8: lane ^ 1, lane ^ 2, then the half row mirrored).
+// All-reduce over aligned groups of LW lanes (16: a DPP row, rotated; 4: lane ^ 1, lane ^ 2; 8: then the half row mirrored).
 template <int LW>
 __device__ __forceinline__ float group_sum_f32(float x) {
     if (LW == 16) {
@@ -53,7 +53,7 @@ __device__ __forceinline__ float group_sum_f32(float x) {
     } else {
         x += dpp_f32<0xB1>(x);     // quad_perm [1, 0, 3, 2]
         x += dpp_f32<0x4E>(x);     // quad_perm [2, 3, 0, 1]
-        x += dpp_f32<0x141>(x);    // row_half_mirror
+        if (LW == 8) x += dpp_f32<0x141>(x);    // row_half_mirror
     }
     return x;
 }
@@ -67,7 +67,7 @@ __device__ __forceinline__ double group_max_f64(double x) {
     } else {
         x = dmax(x, dpp_f64<0xB1>(x));
         x = dmax(x, dpp_f64<0x4E>(x));
-        x = dmax(x, dpp_f64<0x141>(x));
+        if (LW == 8) x = dmax(x, dpp_f64<0x141>(x));
     }
     return x;
 }
@@ -75,21 +75,26 @@ __device__ __forceinline__ double group_max_f64(double x) {
 // Q groups of 4 adjacent columns per lane (column(q, e) = (q 512 + tid) 4 + e), R rows per panel, R Q <= 8 (a panel
 // is at most 64 KiB: 32 entries per lane; 48 KiB for the widths up to 6144 columns).  FULLW: m = 2048 Q, every lane owns valid columns; else m < 2048 Q and the
 // columns past m are masked (V = -inf, C = 0, nothing published).
-template <int Q, int R, int NW, bool STREAM, bool FULLW>
+// H > 1 (narrow matrices): the workgroup is H row groups of T / H lanes; a row is spread over the NW / H waves of
+// its group only (column(q, e) = (q T / H + tid mod (T / H)) 4 + e) and group h works on the rows h R / H ...
+// of every panel; the groups add their column sums in LDS before the workgroup publishes them.
+template <int Q, int R, int NW, bool STREAM, bool FULLW, int H = 1>
 __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X, Ctl c) {
     constexpr int T = 64 * NW, NP = kResMaxPanels, NR = kResRegs, NL = kResLds;
-    constexpr int NDMA = R * Q;                // prefetch loads per panel and wave
-    constexpr int LW = R > 4 ? 8 : 16;         // lanes per row in the merge of the wave sums: NW partials (then zeros)
-    static_assert(R * Q * NW <= 64, "a panel is at most 64 KiB");
-    static_assert(R * LW <= 64, "one wave merges all (row, wave) partials in one shot");
+    constexpr int TC = T / H, RH = R / H, NWH = NW / H;      // lanes per row, rows per group and panel, waves per row
+    constexpr int NDMA = RH * Q;               // prefetch loads per panel and wave
+    constexpr int LW = R <= 4 ? 16 : 64 / R;   // lanes per row in the merge of the wave sums: NWH partials (then zeros)
+    static_assert(T % H == 0 && R % H == 0 && NW % H == 0 && TC % 64 == 0, "whole waves per row group");
+    static_assert(RH * Q * NW <= 64, "a panel is at most 64 KiB");
+    static_assert(R * LW <= 64 && NWH <= LW, "one wave merges all (row, wave) partials in one shot");
     constexpr float kRowHi = 1.1529215e18f;    // 2^60
     constexpr float kRowLo = 9.5367432e-07f;   // 2^-20
-    __shared__ float4 stage[NL][NW][R][Q][64]; // the panels behind the register panels (two: resident; more: staged), every wave its own slice
+    __shared__ float4 stage[NL][NW][RH][Q][64]; // the panels behind the register panels (two: resident; more: staged), every wave its own slice
     __shared__ double sF[2][NP][R];            // F of this workgroup's rows by parity of the iteration; kPadF past n
     __shared__ double sLa2[NP][R];
     __shared__ float sA[NP][R];
-    __shared__ float sSum[NR + NL][R][NW];     // by register panel, then by staging buffer
-    __shared__ double sM[R][NW];               // exact redo: row maxima by wave
+    __shared__ float sSum[NR + NL][R][NWH];    // by register panel, then by staging buffer
+    __shared__ double sM[R][NWH];              // exact redo: row maxima by wave
     __shared__ double sMr[NW];                 // exact repair of a column: running pairs by wave
     __shared__ float sSr[NW];
     __shared__ double sPart[T];                // merge: partial totals by (set group, column)
@@ -106,7 +111,10 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     const int W = gridDim.x, w = blockIdx.x;
     const int rr = lane / LW, ww = lane % LW;  // the panel row and the wave whose partial this lane takes in the merge
     const int rc = rr < R ? rr : R - 1;
-    const int wc = ww < NW ? ww : NW - 1;
+    const int wc = ww < NWH ? ww : NWH - 1;
+    const int tc = tid % TC;                   // the lane's place in its row group: it owns the columns (q TC + tc) 4 ...
+    const int hh = __builtin_amdgcn_readfirstlane(tid / TC), wq = wave % NWH;   // row group; the wave's place in it
+    static_assert(sizeof(sPart) >= (size_t)(H - 1) * TC * Q * 16, "the row groups meet in sPart");
 
     int k;
     if (!launch_active(c, k)) return;
@@ -148,37 +156,37 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     // (slice tw: the wave's own, except between iterations, see below)
     auto issue = [&](int j, int buf, int tw) {
         const __amdgpu_buffer_rsrc_t rsrc = panel_rsrc(j);
+        const int tslot = (tw * 64 + lane) % TC, tg = (tw * 64) / TC;    // place in the row group, row group of slice tw
 #pragma unroll
-        for (int r = 0; r < R; ++r)
+        for (int r = 0; r < RH; ++r)
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
                 // a lane whose columns lie past m asks for an address outside the descriptor: nothing is read from
                 // memory for it, zeros land in LDS, and every wave still issues the same number of loads
-                const int slot = tw * 64 + lane;
-                const int voff = (FULLW || (q * T + slot) * 4 < m) ? slot * 16 : 0x40000000;
+                const int voff = (FULLW || (q * TC + tslot) * 4 < m) ? tslot * 16 : 0x40000000;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, &stage[buf][tw][r][q][0], 16, voff,
-                                                         (r * m + q * T * 4) * 4, 0, 0);
+                                                         ((tg * RH + r) * m + q * TC * 4) * 4, 0, 0);
             }
     };
     // the panel behind the register panels that a pass visits in position t
     auto lds_panel = [&](int t, bool rev) { return NR + (t == 0 ? 0 : (rev ? ms - t : t)); };
     // ---- the register panels, once per launch
-    float creg[NR][R][Q][4];
+    float creg[NR][RH][Q][4];
 #pragma unroll
     for (int t = 0; t < NR; ++t) {
         const __amdgpu_buffer_rsrc_t rsrc = panel_rsrc(t);
 #pragma unroll
-        for (int r = 0; r < R; ++r)
+        for (int r = 0; r < RH; ++r)
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
-                const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, tid * 16, (r * m + q * T * 4) * 4, 0);
+                const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, tc * 16, ((hh * RH + r) * m + q * TC * 4) * 4, 0);
                 float (&cr)[4] = creg[t][r][q];
                 cr[0] = __uint_as_float(x.x); cr[1] = __uint_as_float(x.y);
                 cr[2] = __uint_as_float(x.z); cr[3] = __uint_as_float(x.w);
                 if (!FULLW) {
                     // columns past m: what was read there belongs to the next row (or to nobody); the entry counts
                     // for nothing (V = -inf there) and is set to 0 so that it cannot turn -inf into NaN either
-                    const int col = (q * T + tid) * 4;
+                    const int col = (q * TC + tc) * 4;
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         if (col + e >= m) cr[e] = 0.0f;
@@ -195,7 +203,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     double v[Q][4];
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
-        const int col = (q * T + tid) * 4;
+        const int col = (q * TC + tc) * 4;
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             v[q][e] = (FULLW || col + e < m) ? p.V[(size_t)(k & 1) * p.m_ld + col + e] : -__builtin_huge_val();
@@ -219,10 +227,10 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 #pragma unroll
         for (int b = 0; b < NL; ++b)
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+            for (int r = 0; r < RH; ++r)
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
-                    const int col = (q * T + tid) * 4;
+                    const int col = (q * TC + tc) * 4;
                     if (col + 4 > m) {
                         float4 c4 = stage[b][wave][r][q][lane];
                         if (col >= m) c4.x = 0.0f;
@@ -258,9 +266,9 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
             const double rho_lane = sF[cur][j][rc];
             const double la2_lane = rowok ? sLa2[j][rc] : -__builtin_huge_val();
             const float a_lane = rowok ? sA[j][rc] : 0.0f;
-            double rho[R];
+            double rho[RH];                    // (r below: a row of this lane's group, row hh RH + r of the panel)
 #pragma unroll
-            for (int r = 0; r < R; ++r) rho[r] = sF[cur][j][r];
+            for (int r = 0; r < RH; ++r) rho[r] = sF[cur][j][hh * RH + r];
             // the 4 entries (r, q, .) of this panel as fp64 values: from the lane's registers (through a compiler
             // barrier: every use converts the 4-byte register afresh; without it the converted values of all
             // register panels are kept over the iteration loop, in twice the registers), or from LDS
@@ -278,10 +286,10 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                 // read past it (entries of the next row: they count for nothing, V = -inf there, and must not be NaN)
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
-                    const int col = (q * T + tid) * 4;
+                    const int col = (q * TC + tc) * 4;
                     if (col < m && col + 4 > m) {
 #pragma unroll
-                        for (int r = 0; r < R; ++r) {
+                        for (int r = 0; r < RH; ++r) {
                             float4 c4 = stage[slot - NR][wave][r][q][lane];
                             if (col + 1 >= m) c4.y = 0.0f;
                             if (col + 2 >= m) c4.z = 0.0f;
@@ -292,9 +300,9 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                 }
             }
             // ---- row phase, optimistic: e = 2^(x - rho_r), summed
-            float ev[R][Q][4];
+            float ev[RH][Q][4];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
+            for (int r = 0; r < RH; ++r) {
                 float acc = 0.0f;
 #pragma unroll
                 for (int q = 0; q < Q; ++q) {
@@ -307,10 +315,10 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                     }
                 }
                 acc = wave_sum_f32(acc);
-                if (lane == 0) sSum[slot][r][wave] = acc;
+                if (lane == 0) sSum[slot][hh * RH + r][wq] = acc;
             }
             lds_only_barrier();
-            float S = rr < R ? (ww < NW ? sSum[slot][rc][wc] : 0.0f) : 1.0f;
+            float S = rr < R ? (ww < NWH ? sSum[slot][rc][wc] : 0.0f) : 1.0f;
             S = group_sum_f32<LW>(S);
             const bool fine = (S >= kRowLo) && (S <= kRowHi);    // false for NaN / inf / 0
             // pi_ij = e_ij * a_i / S_i.  Every wave needs a_i / S_i (reciprocal, one Newton step, product: within
@@ -327,7 +335,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                 // ---- exact redo of the row phase of this panel (uniform over the workgroup): Eq. 8 as written,
                 //      the maximum of the row first (no exponentials), then the sum relative to it
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
+                for (int r = 0; r < RH; ++r) {
                     double mx = kNegHuge;
 #pragma unroll
                     for (int q = 0; q < Q; ++q) {
@@ -337,14 +345,14 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                         for (int e = 0; e < 4; ++e) mx = dmax(mx, fma(ns, cvv[e], v[q][e]));
                     }
                     mx = wave_max_f64(mx);
-                    if (lane == 0) sM[r][wave] = mx;
+                    if (lane == 0) sM[hh * RH + r][wq] = mx;
                 }
                 lds_only_barrier();                              // (every wave has read sSum by now)
-                double Mg = rr < R && ww < NW ? sM[rc][wc] : kNegHuge;
+                double Mg = rr < R && ww < NWH ? sM[rc][wc] : kNegHuge;
                 Mg = group_max_f64<LW>(Mg);
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const double Mr = bcast_f64(Mg, r * LW);
+                for (int r = 0; r < RH; ++r) {
+                    const double Mr = bcast_f64(Mg, (hh * RH + r) * LW);
                     float acc = 0.0f;
 #pragma unroll
                     for (int q = 0; q < Q; ++q) {
@@ -357,10 +365,10 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                         }
                     }
                     acc = wave_sum_f32(acc);
-                    if (lane == 0) sSum[slot][r][wave] = acc;
+                    if (lane == 0) sSum[slot][hh * RH + r][wq] = acc;
                 }
                 lds_only_barrier();                              // (and every wave has read sM)
-                float sg = rr < R ? (ww < NW ? sSum[slot][rc][wc] : 0.0f) : 1.0f;
+                float sg = rr < R ? (ww < NWH ? sSum[slot][rc][wc] : 0.0f) : 1.0f;
                 sg = group_sum_f32<LW>(sg);
                 Fbase = Mg;
                 Ssum = sg;
@@ -380,9 +388,9 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
             }
             // ---- column phase with the new f (the trailing round does it too: its sums are simply not published)
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                float alpha = bcast_f32(alpha_lane, r * LW);
-                if (!(alpha == alpha) || (i0 + r) >= n) alpha = 0.0f;   // rows past n, or a row whose F is not finite
+            for (int r = 0; r < RH; ++r) {
+                float alpha = bcast_f32(alpha_lane, (hh * RH + r) * LW);
+                if (!(alpha == alpha) || (i0 + hh * RH + r) >= n) alpha = 0.0f;   // rows past n, or a row whose F is not finite
 #pragma unroll
                 for (int q = 0; q < Q; ++q)
 #pragma unroll
@@ -429,6 +437,25 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
         }
 
         FS_TRACE(1);
+        if constexpr (H > 1) {
+            // the row groups add their column sums: groups 1 .. H-1 hand theirs over in LDS (sPart is free until the merge)
+            float *sCS = reinterpret_cast<float *>(sPart);
+            if (hh > 0) {
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sCS[(((hh - 1) * Q + q) * 4 + e) * TC + tc] = cS[q][e];
+            }
+            lds_only_barrier();
+            if (hh == 0) {
+#pragma unroll
+                for (int g2 = 1; g2 < H; ++g2)
+#pragma unroll
+                    for (int q = 0; q < Q; ++q)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) cS[q][e] += sCS[(((g2 - 1) * Q + q) * 4 + e) * TC + tc];
+            }
+        }                                              // (barriers lie between these reads and the merge's use of sPart)
         // ---- publish: column sums of this workgroup's rows (16-byte stores), and the error terms of its rows
         {
             // where a group of 4 column sums goes: strip col / Sw, this workgroup's set, column col mod Sw
@@ -437,8 +464,8 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
             if (!trailing)
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
-                const int col = (q * T + tid) * 4;
-                if (FULLW || col < m) {
+                const int col = (q * TC + tc) * 4;
+                if (hh == 0 && (FULLW || col < m)) {
                     const int dest = col / Sw;
                     const v4u pk = {__float_as_uint(cS[q][0]), __float_as_uint(cS[q][1]), __float_as_uint(cS[q][2]),
                                     __float_as_uint(cS[q][3])};
@@ -616,7 +643,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                 (void *)(p.V + (size_t)nxt * p.m_ld), 0, p.m_ld * 8, 0x00020000);
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
-                const int col = (q * T + tid) * 4;
+                const int col = (q * TC + tc) * 4;
                 if (FULLW || col < m) {
                     const v4u lo = __builtin_amdgcn_raw_buffer_load_b128(rsV, col * 8, 0, kAgent);
                     const v4u hi = __builtin_amdgcn_raw_buffer_load_b128(rsV, col * 8 + 16, 0, kAgent);
@@ -670,8 +697,8 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 // up to kResMaxPanels on request (`all`).
 // Returns the workgroups of the launch, 0 when the shape is not taken.
 int dense_resident_grid(int n, int m, int cus, bool all) {
-    if (cus < 1 || n < 1 || m <= 1024 || m > 8192) return 0;
-    const int R = m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
+    if (cus < 1 || n < 1 || m <= 512 || m > 8192) return 0;
+    const int R = m <= 1024 ? 16 : m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
     const long long npanels = ((long long)n + R - 1) / R;
     long long g = npanels < cus ? npanels : cus;
     if (g > 256) g = 256;                                  // the exchange buffer holds 256 sets of column sums
@@ -680,7 +707,7 @@ int dense_resident_grid(int n, int m, int cus, bool all) {
     // (a width between 6145 and 8191 columns is streamed by the 1024-lane kernel as fast or faster: 8000 x 8000 46.4
     // against 47.3 us per iteration; below, this one wins: 6000 x 6000 31.8 against 34.0, 8000 x 5000 38.7 / 40.8,
     // 16384 x 3000 47.6 / 53.5, 8000 x 2500 25.6 / 30.4, 12000 x 1500 23.5 / 40.1)
-    const long long most = all || m == 2048 ? kResMaxPanels : (m > 6144 && m < 8192) ? kResPanels : kResAutoPanels;
+    const long long most = all || m <= 1024 || m == 2048 ? kResMaxPanels : (m > 6144 && m < 8192) ? kResPanels : kResAutoPanels;
     return npanels <= most * g ? (int)g : 0;
 }
 
@@ -689,9 +716,15 @@ hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs
     if (a.c_dtype != 0 || grid < 1 || dense_resident_grid(a.p.n, a.p.m, grid, true) != grid) return hipErrorInvalidValue;
     const dim3 g(grid), block(512);
     const int m = a.p.m;
-    const int R = m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
+    const int R = m <= 1024 ? 16 : m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
     const bool stream = ((long long)a.p.n + R - 1) / R > (long long)kResPanels * grid;
-    if (m == 2048) {
+    if (m == 1024) {
+        if (stream) launch_stamped((k_resident<1, 16, 8, true, true, 2>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<1, 16, 8, false, true, 2>), g, block, st, tm, a, x, c);
+    } else if (m < 1024) {
+        if (stream) launch_stamped((k_resident<1, 16, 8, true, false, 2>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<1, 16, 8, false, false, 2>), g, block, st, tm, a, x, c);
+    } else if (m == 2048) {
         if (stream) launch_stamped((k_resident<1, 8, 8, true, true>), g, block, st, tm, a, x, c);
         else launch_stamped((k_resident<1, 8, 8, false, true>), g, block, st, tm, a, x, c);
     } else if (m == 4096) {

@@ -52,24 +52,26 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
           (3000, 3000), (1500, 2049), (4000, 4095), (2000, 6145), (1025, 8191), (1200, 5000), (1023, 4097),   # ... idle lanes
           (2048, 2048), (8190, 2048), (3000, 1500), (5000, 1025), (2051, 2047), (20000, 2048), (70000, 2048),   # panels of 8 rows
           (4200, 2500), (8300, 1500), (2200, 5000), (2300, 8000), (6000, 6000), (9000, 3000), (5000, 6145),
-          (2048, 6144), (5000, 6144), (1000, 6000), (2301, 4097)]   # ... idle lanes, streamed      # ... and shares of which the 512-lane kernel streams a part
+          (2048, 6144), (5000, 6144), (1000, 6000), (2301, 4097),   # ... and shares of which the 512-lane kernel streams a part
+          (1000, 1000), (4096, 1024), (8191, 1024), (333, 700), (5000, 513), (9000, 1024),   # two row groups per workgroup
+          (17000, 1024), (20000, 1000)]                            # ... streamed
 
 
 def _resident(n, m, cus=256, most=4):
-    """Whether the 512-lane kernel of the persistent pass takes the shape (1024 < m <= 8192, 1 .. most panels of 64 KiB
+    """Whether the 512-lane kernel of the persistent pass takes the shape (512 < m <= 8192, 1 .. most panels of 64 KiB
     per workgroup of a grid of min(cus, panels) workgroups that merge at most 64 columns each): up to 4 panels the matrix stays on the chip for a whole launch; beyond
     that the panels behind the two in registers are streamed: up to 16 panels (32 at 2048 columns) it is
     the library's own choice (fused_variant = 1 asks for the 1024-lane streaming kernel instead), up to 32 it can be
     asked for (fused_variant = 2)."""
-    if not 1024 < m <= 8192:
+    if not 512 < m <= 8192:
         return False
-    rows = 8 if m <= 2048 else 4 if m <= 4096 else 2
+    rows = 16 if m <= 1024 else 8 if m <= 2048 else 4 if m <= 4096 else 2
     panels = -(-n // rows)
     grid = min(cus, panels, 256)
     if (-(-m // grid) + 3) // 4 * 4 > 64:                    # a workgroup merges a strip of at most 64 columns
         return False
-    if m == 2048 and most == 16:
-        most = 32
+    if m == 2048 or m <= 1024:
+        most = 32                                            # (up to 1024 columns there is no 1024-lane form)
     if 6144 < m < 8192 and most == 16:
         most = 4                                             # streamed by the 1024-lane kernel unless asked otherwise
     return panels <= most * grid
@@ -86,7 +88,7 @@ def test_persistent_pass_matches_oracle(fs, oracle, n, m):
     w = W.random_dense(n, m, seed=6000 + n + m, cmax=2.0, eps=0.03)
     iters = 52                                  # one whole block of 50 iterations and a short one
     ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C)
-    variants = (0, 1) if _resident(n, m, cus, most=16) else (0, 2) if _resident(n, m, cus, most=32) else (0,)
+    variants = (0,) if m <= 1024 else (0, 1) if _resident(n, m, cus, most=16) else (0, 2) if _resident(n, m, cus, most=32) else (0,)
     for variant in variants:
         r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, iters, 0.0, C=dev(w.C), want_f64=True, kernel_mode=6,
                                  fused_variant=variant, time_kernel_every=1)
@@ -124,7 +126,8 @@ def test_persistent_pass_is_the_automatic_choice_and_repeats_bit_for_bit(fs, ora
     assert pot_err(r0["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
 
 
-@pytest.mark.parametrize("n,m", [(320, 1500), (1030, 4096)])      # the streaming form; the resident form (ragged last panel)
+# the streaming form; the resident form (ragged last panel); the resident form with two row groups per workgroup
+@pytest.mark.parametrize("n,m", [(320, 1500), (1030, 4096), (1210, 1000)])
 def test_persistent_pass_stop_rule_history_and_resume(fs, oracle, n, m):
     import torch
     if not _supported(fs, n, m):
@@ -165,7 +168,8 @@ def test_persistent_pass_stop_rule_history_and_resume(fs, oracle, n, m):
 
 
 @pytest.mark.parametrize("eps", [1e-3, 1e-4])
-@pytest.mark.parametrize("n,m", [(517, 4100), (300, 4096), (600, 8190), (260, 8192), (300, 12288), (290, 16001), (1500, 3001)])
+@pytest.mark.parametrize("n,m", [(517, 4100), (300, 4096), (600, 8190), (260, 8192), (300, 12288), (290, 16001), (1500, 3001),
+                                 (1100, 1024), (5000, 900)])
 def test_persistent_pass_small_eps(fs, oracle, n, m, eps):
     """Costs up to 60 at eps 1e-3 and 1e-4: the exact redo of the row phase, and potentials of 10^5 .. 10^6
     in units of eps.  Same bar as the other dense paths in this regime (the iteration does not contract there,
@@ -187,7 +191,7 @@ def test_persistent_pass_small_eps(fs, oracle, n, m, eps):
 
 
 @pytest.mark.parametrize("eps", [0.05, 2e-3])
-@pytest.mark.parametrize("n,m", [(300, 4096), (600, 8192), (290, 16384), (520, 3001)])
+@pytest.mark.parametrize("n,m", [(300, 4096), (600, 8192), (290, 16384), (520, 3001), (1300, 1024), (700, 600)])
 def test_persistent_pass_tiny_and_zero_weights(fs, oracle, n, m, eps):
     """Weights of 1e-30, 1e-36, a denormal and an exact zero in a and b: the columns concerned total less than
     2^-66 in fp32 and go through the exact recomputation inside the merge, every iteration."""
@@ -215,7 +219,7 @@ def test_persistent_pass_tiny_and_zero_weights(fs, oracle, n, m, eps):
     assert abs(r["marginal_err"] - err_ref) <= 1e-3 * err_ref + 5e-7
 
 
-@pytest.mark.parametrize("n,m", [(900, 2100), (1030, 4096)])       # the streaming form; the resident form
+@pytest.mark.parametrize("n,m", [(900, 2100), (1030, 4096), (1500, 1024)])   # the streaming form; the resident forms
 @pytest.mark.parametrize("warm", [False, True])
 def test_persistent_pass_gives_up_cleanly_and_the_solve_falls_back(fs, oracle, warm, n, m):
     """wait_limit = 1: a workgroup stops waiting for the others after a single poll, which the host can force
