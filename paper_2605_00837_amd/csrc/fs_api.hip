@@ -83,8 +83,12 @@ Layout make_layout(int n, int m, int d) {
         dense_stream_plan(n, m, &L.P_stream, &L.rpp_stream);
         dense_fused_plan(n, m, &L.P_fused);
         int Pmax = L.P_stream > L.P_fused ? L.P_stream : L.P_fused;
-        // (a width that only the resident form of the persistent pass takes: its exchange buffer holds 256 sets)
-        if (dense_persist_supported(n, m, nullptr, 0) && Pmax < 256) Pmax = 256;
+        // a width that only the resident form of the persistent pass takes: its exchange buffer holds 256 sets, and
+        // 256 x 256 strips of 4 floats (it is laid out by strip, not by column: below 512 columns that is the larger)
+        if (m <= 1024 && dense_persist_supported(n, m, nullptr, 0)) {
+            const int sets = (int)std::max<size_t>(256, (size_t(256) * 256 * 16 + size_t(L.m_ld) * 8 - 1) / (size_t(L.m_ld) * 8));
+            if (Pmax < sets) Pmax = sets;
+        }
         L.P_part = Pmax;
         L.o_part = take(sizeof(double) * (size_t)Pmax * L.m_ld);
         L.o_part2 = L.o_part;
@@ -465,7 +469,7 @@ fs_status setup(Solve &S, const Problem &pr, const fs_options *opts, float *f, f
         const int km = S.opt.kernel_mode;
         if (km == 6) {
             if (!dense_persist_supported(pr.n, pr.m, pr.C, S.opt.cost_dtype)) {
-                set_err("kernel_mode 6 needs a dense fp32 cost matrix with 1024 < m <= 16384 (got m = %d)", pr.m);
+                set_err("kernel_mode 6 needs a dense fp32 cost matrix with 256 < m <= 16384 (got m = %d)", pr.m);
                 return FS_ERR_UNSUPPORTED;
             }
         } else if (km < 0 || km > 2) { set_err("kernel_mode %d does not take this problem", km); return FS_ERR_UNSUPPORTED; }
@@ -910,7 +914,7 @@ int solve_blocking(const Problem &pr, float *f, float *g, hipStream_t st, const 
     if (v != FS_OK) return v;
     S.persist = persist_path(pr, opts, /*blocking=*/true, &S.cus);
     if (!S.persist && opts && opts->kernel_mode == 6) {
-        set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (and up to 1024 columns at most 8192 rows per compute unit) (n = %d, m = %d, %d compute units)", pr.n, pr.m, S.cus);
+        set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (and up to 1024 columns at most 512 rows per compute unit) (n = %d, m = %d, %d compute units)", pr.n, pr.m, S.cus);
         return FS_ERR_UNSUPPORTED;
     }
     return run_solve_blocking(S, dc, f, g, result_host);
@@ -969,7 +973,7 @@ fs_status solve_async(const Problem &pr, float *f, float *g, hipStream_t st, con
     if (v != FS_OK) return v;
     S.persist = persist_path(pr, opts, /*blocking=*/false, &S.cus);      // on request only
     if (!S.persist && opts && opts->kernel_mode == 6) {
-        set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (and up to 1024 columns at most 8192 rows per compute unit) (n = %d, m = %d, %d compute units)", pr.n, pr.m, S.cus);
+        set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (and up to 1024 columns at most 512 rows per compute unit) (n = %d, m = %d, %d compute units)", pr.n, pr.m, S.cus);
         return FS_ERR_UNSUPPORTED;
     }
     return run_solve_async(S, f, g, result_dev);
@@ -1132,7 +1136,7 @@ int fs_kernel_choice(int n, int m, int d, const fs_options *opts, int blocking, 
     const bool persist = persist_path(pr, opts, blocking != 0, &pcus);
     g_cus_override = 0;
     if (persist) return FS_KERNEL_PERSIST;
-    if (km == 6) { set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (and up to 1024 columns at most 8192 rows per compute unit)"); return FS_ERR_UNSUPPORTED; }
+    if (km == 6) { set_err("kernel_mode 6 needs at least m / 64 row panels and compute units (and up to 1024 columns at most 512 rows per compute unit)"); return FS_ERR_UNSUPPORTED; }
     if (km == 2 && !fused_ok) { set_err("fused kernel does not support m = %d", m); return FS_ERR_UNSUPPORTED; }
     if (km > 2) { set_err("kernel_mode %d does not take this problem", km); return FS_ERR_UNSUPPORTED; }
     return (km == 2 || (km == 0 && fused_ok)) ? FS_KERNEL_FUSED : FS_KERNEL_STREAM;

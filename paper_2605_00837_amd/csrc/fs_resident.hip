@@ -42,7 +42,7 @@ constexpr int kResAutoPanels = 16;      // up to here this kernel is the faster 
                                         // where the 1024-lane kernel has idle lanes, as far as it goes (32768 rows:
                                         // 53.8 against 96.7)
 
-// All-reduce over aligned groups of LW lanes (16: a DPP row, rotated; 4: lane ^ 1, lane ^ 2; 8: then the half row mirrored).
+// All-reduce over aligned groups of LW lanes (16: a DPP row, rotated; 2: lane ^ 1; 4: then lane ^ 2; 8: then the half row mirrored).
 template <int LW>
 __device__ __forceinline__ float group_sum_f32(float x) {
     if (LW == 16) {
@@ -52,7 +52,7 @@ __device__ __forceinline__ float group_sum_f32(float x) {
         x += dpp_f32<0x121>(x);
     } else {
         x += dpp_f32<0xB1>(x);     // quad_perm [1, 0, 3, 2]
-        x += dpp_f32<0x4E>(x);     // quad_perm [2, 3, 0, 1]
+        if (LW >= 4) x += dpp_f32<0x4E>(x);     // quad_perm [2, 3, 0, 1]
         if (LW == 8) x += dpp_f32<0x141>(x);    // row_half_mirror
     }
     return x;
@@ -66,7 +66,7 @@ __device__ __forceinline__ double group_max_f64(double x) {
         x = dmax(x, dpp_f64<0x121>(x));
     } else {
         x = dmax(x, dpp_f64<0xB1>(x));
-        x = dmax(x, dpp_f64<0x4E>(x));
+        if (LW >= 4) x = dmax(x, dpp_f64<0x4E>(x));
         if (LW == 8) x = dmax(x, dpp_f64<0x141>(x));
     }
     return x;
@@ -80,7 +80,7 @@ __device__ __forceinline__ double group_max_f64(double x) {
 // of every panel; the groups add their column sums in LDS before the workgroup publishes them.
 template <int Q, int R, int NW, bool STREAM, bool FULLW, int H = 1>
 __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X, Ctl c) {
-    constexpr int T = 64 * NW, NP = kResMaxPanels, NR = kResRegs, NL = kResLds;
+    constexpr int T = 64 * NW, NP = H > 2 ? kResMaxPanels / 2 : kResMaxPanels, NR = kResRegs, NL = kResLds;
     constexpr int TC = T / H, RH = R / H, NWH = NW / H;      // lanes per row, rows per group and panel, waves per row
     constexpr int NDMA = RH * Q;               // prefetch loads per panel and wave
     constexpr int LW = R <= 4 ? 16 : 64 / R;   // lanes per row in the merge of the wave sums: NWH partials (then zeros)
@@ -97,7 +97,8 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     __shared__ double sM[R][NWH];              // exact redo: row maxima by wave
     __shared__ double sMr[NW];                 // exact repair of a column: running pairs by wave
     __shared__ float sSr[NW];
-    __shared__ double sPart[T];                // merge: partial totals by (set group, column)
+    constexpr int NPART = (H - 1) * TC * Q * 2 > T ? (H - 1) * TC * Q * 2 : T;
+    __shared__ double sPart[NPART];            // merge: partial totals by (set group, column); the row groups' column sums
     __shared__ int sSus[T];                    // merge: columns of this round to recompute exactly
     __shared__ int sNsus, sOk;
     __shared__ unsigned long long sGen;
@@ -697,8 +698,8 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 // up to kResMaxPanels on request (`all`).
 // Returns the workgroups of the launch, 0 when the shape is not taken.
 int dense_resident_grid(int n, int m, int cus, bool all) {
-    if (cus < 1 || n < 1 || m <= 512 || m > 8192) return 0;
-    const int R = m <= 1024 ? 16 : m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
+    if (cus < 1 || n < 1 || m <= 256 || m > 8192) return 0;
+    const int R = m <= 512 ? 32 : m <= 1024 ? 16 : m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
     const long long npanels = ((long long)n + R - 1) / R;
     long long g = npanels < cus ? npanels : cus;
     if (g > 256) g = 256;                                  // the exchange buffer holds 256 sets of column sums
@@ -707,7 +708,7 @@ int dense_resident_grid(int n, int m, int cus, bool all) {
     // (a width between 6145 and 8191 columns is streamed by the 1024-lane kernel as fast or faster: 8000 x 8000 46.4
     // against 47.3 us per iteration; below, this one wins: 6000 x 6000 31.8 against 34.0, 8000 x 5000 38.7 / 40.8,
     // 16384 x 3000 47.6 / 53.5, 8000 x 2500 25.6 / 30.4, 12000 x 1500 23.5 / 40.1)
-    const long long most = all || m <= 1024 || m == 2048 ? kResMaxPanels : (m > 6144 && m < 8192) ? kResPanels : kResAutoPanels;
+    const long long most = m <= 512 ? kResMaxPanels / 2 : all || m <= 1024 || m == 2048 ? kResMaxPanels : (m > 6144 && m < 8192) ? kResPanels : kResAutoPanels;
     return npanels <= most * g ? (int)g : 0;
 }
 
@@ -716,9 +717,15 @@ hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs
     if (a.c_dtype != 0 || grid < 1 || dense_resident_grid(a.p.n, a.p.m, grid, true) != grid) return hipErrorInvalidValue;
     const dim3 g(grid), block(512);
     const int m = a.p.m;
-    const int R = m <= 1024 ? 16 : m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
+    const int R = m <= 512 ? 32 : m <= 1024 ? 16 : m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
     const bool stream = ((long long)a.p.n + R - 1) / R > (long long)kResPanels * grid;
-    if (m == 1024) {
+    if (m == 512) {
+        if (stream) launch_stamped((k_resident<1, 32, 8, true, true, 4>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<1, 32, 8, false, true, 4>), g, block, st, tm, a, x, c);
+    } else if (m < 512) {
+        if (stream) launch_stamped((k_resident<1, 32, 8, true, false, 4>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<1, 32, 8, false, false, 4>), g, block, st, tm, a, x, c);
+    } else if (m == 1024) {
         if (stream) launch_stamped((k_resident<1, 16, 8, true, true, 2>), g, block, st, tm, a, x, c);
         else launch_stamped((k_resident<1, 16, 8, false, true, 2>), g, block, st, tm, a, x, c);
     } else if (m < 1024) {
