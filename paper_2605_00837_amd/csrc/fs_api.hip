@@ -774,10 +774,11 @@ bool grid_path(const Problem &pr, const fs_options *opts, bool blocking, fs_stat
     // automatic: it needs every compute unit of the chip at the same moment, so the library only picks it where
     // it can fall back (blocking solves); up to 512 x 512 the 32-workgroup kernel is as fast or faster
     // (256 x 256: 5.7 against 7.3 us per iteration), beyond that this one is (1024 x 256: 8.3 against 10.2) --
-    // except where the persistent pass can keep its share of C on the chip (more than 1024 columns) and the problem
+    // except where the persistent pass can keep its share of C on the chip (more than 256 columns) and the problem
     // is not small: that one runs an iteration in 9.4 us plus 1.5 us per 16 MiB of C (2048 x 2048: 10.5 against
     // 14.0 us per iteration, 1024 x 2048: 9.6 / 12.0, 256 x 2048: 9.4 / 10.9, 800 x 1200: 9.6 / 10.4; but 640 x 1280:
-    // 9.7 / 9.3, 300 x 1100: 9.6 / 8.1)
+    // 9.7 / 9.3, 300 x 1100: 9.6 / 8.1; with the wait as it is now 1024 x 1024: 8.9 / 9.4, 2048 x 512: 8.7 / 9.9, but
+    // 320 x 1024: 8.7 / 7.6, 700 x 520: 8.9 / 7.7)
     if (blocking && pr.C && (!opts || (opts->fused_variant == 0 && opts->cost_dtype == 0)) &&
         (pr.m >= 2048 || (size_t)pr.n * (size_t)pr.m >= 900000) &&
         dense_persist_supported(pr.n, pr.m, pr.C, 0) && dense_persist_grid(pr.n, pr.m, *wmax) >= 1 &&

@@ -257,8 +257,9 @@ struct GridArgs : SmallArgs {                    // batch is ignored (one proble
     GridSync *sync;
     int32_t ldx, spin_limit;
 };
-// ---- dense fp32 problems with 1024 < m <= 16384: a block of iterations of the fused row-panel pass in one
-//      launch, one resident workgroup per compute unit, two grid-wide waits per iteration (fs_persist.hip)
+// ---- dense fp32 problems with 256 < m <= 16384: a block of iterations of the fused row-panel pass in one
+//      launch, one resident workgroup per compute unit, two grid-wide waits per iteration (fs_persist.hip; up to
+//      1024 columns only its resident form, fs_resident.hip)
 struct PersistArgs {
     PersistSync *sync;
     double *wgpart;                              // [workgroups]: error terms of each workgroup's rows
@@ -277,7 +278,8 @@ int dense_persist_grid(int n, int m, int cus);   // workgroups of the launch on 
 size_t persist_scratch_bytes();
 // variant 0: the 512-lane kernel of fs_resident.hip where the workgroups can hold their share of C, or most of the
 // panels they stream are few (up to 16 panels per workgroup; 32 at 2048 columns), else the 1024-lane streaming kernel; 1: always the
-// 1024-lane streaming kernel; 2: the 512-lane kernel up to 32 panels per workgroup
+// 1024-lane streaming kernel; 2: the 512-lane kernel up to 32 panels per workgroup.  Up to 1024 columns there is only
+// the 512-lane kernel, whatever the variant.
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,
                           int spin_limit, int final_err, int variant, const Stamp &tm = Stamp());
 bool dense_persist_resident(int n, int m, int cus, int variant);   // which of the two forms launch_persist takes

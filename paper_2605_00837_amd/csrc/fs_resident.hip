@@ -11,8 +11,9 @@
 // registers each hold the same bytes, but 32 of 128 registers for the panels leave the hot loop short of
 // registers and it runs 8 % slower.)
 //
-// Widths from 1025 to 8192 columns are taken: a panel is 8 rows up to 2048 columns, 4 up to 4096, 2 beyond, and
-// the lanes whose columns lie past m are masked.  The grid is one workgroup per compute unit, fewer for a short
+// Widths from 257 to 8192 columns are taken: a panel is 8 rows up to 2048 columns, 4 up to 4096, 2 beyond, and
+// the lanes whose columns lie past m are masked.  Up to 1024 columns a row does not need 512 lanes: the workgroup
+// splits into 2 (513 .. 1024 columns, panels of 16 rows) or 4 (257 .. 512, panels of 32 rows) row groups.  The grid is one workgroup per compute unit, fewer for a short
 // matrix.  A share of more than 4 panels is streamed: the two register panels
 // stay, the others go through the two LDS buffers two panels ahead, as in fs_persist.hip.
 //
@@ -690,12 +691,13 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 
 }  // namespace
 
-// The shapes this kernel takes: fp32 costs, 1024 < m <= 8192 (panels of 8 rows up to 2048 columns, of 4 up to 4096,
+// The shapes this kernel takes: fp32 costs, 256 < m <= 8192 (panels of 32 rows up to 512 columns, of 16 up to 1024, of 8 up to 2048, of 4 up to 4096,
 // of 2 beyond; 2048, 4096, 6144 or 8192 column slots), on a grid of one workgroup per compute unit, never more than there are panels and never so few
 // that a workgroup would merge a strip of more than 64 columns.  Up to kResPanels panels per workgroup the whole
 // share stays on the chip; beyond, the panels behind the register panels are streamed: up to kResAutoPanels as the
 // library's own choice (at exactly 2048 columns: up to kResMaxPanels; between 6145 and 8191 columns: not at all),
-// up to kResMaxPanels on request (`all`).
+// up to kResMaxPanels on request (`all`).  Up to 1024 columns: always up to kResMaxPanels (half of that up to 512
+// columns, where the row scalars of a panel of 32 rows take twice the LDS).
 // Returns the workgroups of the launch, 0 when the shape is not taken.
 int dense_resident_grid(int n, int m, int cus, bool all) {
     if (cus < 1 || n < 1 || m <= 256 || m > 8192) return 0;

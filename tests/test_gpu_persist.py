@@ -1,5 +1,5 @@
 """GPU parity of the persistent fused pass (kernel_mode 6; the automatic choice of the blocking dense
-solves for 1024 < m <= 8192): one resident workgroup per compute unit, a block of iterations per launch,
+solves for 256 < m <= 8192): one resident workgroup per compute unit, a block of iterations per launch,
 two grid-wide waits per iteration.  Everything goes through the C ABI and is compared with the CPU oracle.
 """
 import math
@@ -278,9 +278,9 @@ def test_persistent_pass_rejections(fs):
 def _sweep_cases():
     rng = np.random.default_rng(20260511)
     cases = []
-    for t in range(24):
-        m = int(rng.integers(1025, 16385))
-        n = int(rng.integers(40, 2600))
+    for t in range(34):                          # (from 24 on: the widths with several row groups per workgroup)
+        m = int(rng.integers(1025, 16385)) if t < 24 else int(rng.integers(257, 1025))
+        n = int(rng.integers(40, 2600)) if t < 24 else int(rng.integers(300, 9000))
         cases.append((t, n, m, float(rng.choice([0.01, 0.03, 0.1])), float(rng.choice([2.0, 20.0])),
                       int(rng.integers(3, 70)), bool(rng.integers(0, 2))))
     return cases
