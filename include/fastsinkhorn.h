@@ -106,7 +106,7 @@ typedef struct {
                                 problem with n or m above 512);
                                 6: blocks of iterations in launches of the persistent form of the fused
                                 row-panel kernel, one resident workgroup per compute unit, two grid-wide waits
-                                per iteration (dense fp32, 256 < m <= 16384 and at least m / 64 row panels and
+                                per iteration (dense fp32, 128 < m <= 16384 and at least m / 64 row panels and
                                 compute units, up to 1024 columns also at most 512 rows per compute unit; else
                                 FS_ERR_UNSUPPORTED; what 0 picks in the blocking solves up to
                                 8192 columns; the asynchronous solves take it on request only, because it

@@ -469,11 +469,13 @@ fs_status setup(Solve &S, const Problem &pr, const fs_options *opts, float *f, f
         const int km = S.opt.kernel_mode;
         if (km == 6) {
             if (!dense_persist_supported(pr.n, pr.m, pr.C, S.opt.cost_dtype)) {
-                set_err("kernel_mode 6 needs a dense fp32 cost matrix with 256 < m <= 16384 (got m = %d)", pr.m);
+                set_err("kernel_mode 6 needs a dense fp32 cost matrix with 128 < m <= 16384 (got m = %d)", pr.m);
                 return FS_ERR_UNSUPPORTED;
             }
         } else if (km < 0 || km > 2) { set_err("kernel_mode %d does not take this problem", km); return FS_ERR_UNSUPPORTED; }
-        S.mode = km == 0 ? (fused_ok ? 2 : 1) : km == 6 ? 2 : km;
+        // (6: the kernels around the persistent pass -- err of a solve of 0 iterations, the second attempt after a wait
+        // that was abandoned -- are those of the automatic choice)
+        S.mode = km == 0 || km == 6 ? (fused_ok ? 2 : 1) : km;
         if (S.mode == 2 && dense_fused_grid(pr.n, pr.m, S.opt.fused_variant, S.opt.cost_dtype) == 0) S.opt.fused_variant = 0;
     } else {
         S.mode = 3;
@@ -774,7 +776,7 @@ bool grid_path(const Problem &pr, const fs_options *opts, bool blocking, fs_stat
     // automatic: it needs every compute unit of the chip at the same moment, so the library only picks it where
     // it can fall back (blocking solves); up to 512 x 512 the 32-workgroup kernel is as fast or faster
     // (256 x 256: 5.7 against 7.3 us per iteration), beyond that this one is (1024 x 256: 8.3 against 10.2) --
-    // except where the persistent pass can keep its share of C on the chip (more than 256 columns) and the problem
+    // except where the persistent pass can keep its share of C on the chip (more than 128 columns) and the problem
     // is not small: that one runs an iteration in 9.4 us plus 1.5 us per 16 MiB of C (2048 x 2048: 10.5 against
     // 14.0 us per iteration, 1024 x 2048: 9.6 / 12.0, 256 x 2048: 9.4 / 10.9, 800 x 1200: 9.6 / 10.4; but 640 x 1280:
     // 9.7 / 9.3, 300 x 1100: 9.6 / 8.1; with the wait as it is now 1024 x 1024: 8.9 / 9.4, 2048 x 512: 8.7 / 9.9, but

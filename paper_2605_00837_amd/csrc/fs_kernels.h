@@ -257,7 +257,7 @@ struct GridArgs : SmallArgs {                    // batch is ignored (one proble
     GridSync *sync;
     int32_t ldx, spin_limit;
 };
-// ---- dense fp32 problems with 256 < m <= 16384: a block of iterations of the fused row-panel pass in one
+// ---- dense fp32 problems with 128 < m <= 16384: a block of iterations of the fused row-panel pass in one
 //      launch, one resident workgroup per compute unit, two grid-wide waits per iteration (fs_persist.hip; up to
 //      1024 columns only its resident form, fs_resident.hip)
 struct PersistArgs {

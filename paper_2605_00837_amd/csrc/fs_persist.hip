@@ -572,8 +572,8 @@ bool persist_shape(int n, int m, PShape *s) {
     return true;
 }
 
-// widths that only the resident form takes (two or four row groups per workgroup): the streaming form has no shape for them
-bool narrow_shape(int m) { return m > 256 && m <= 1024; }
+// widths that only the resident form takes (two, four or eight row groups per workgroup): the streaming form has no shape for them
+bool narrow_shape(int m) { return m > 128 && m <= 1024; }
 
 }  // namespace
 

@@ -11,9 +11,10 @@
 // registers each hold the same bytes, but 32 of 128 registers for the panels leave the hot loop short of
 // registers and it runs 8 % slower.)
 //
-// Widths from 257 to 8192 columns are taken: a panel is 8 rows up to 2048 columns, 4 up to 4096, 2 beyond, and
+// Widths from 129 to 8192 columns are taken: a panel is 8 rows up to 2048 columns, 4 up to 4096, 2 beyond, and
 // the lanes whose columns lie past m are masked.  Up to 1024 columns a row does not need 512 lanes: the workgroup
-// splits into 2 (513 .. 1024 columns, panels of 16 rows) or 4 (257 .. 512, panels of 32 rows) row groups.  The grid is one workgroup per compute unit, fewer for a short
+// splits into 2 (513 .. 1024 columns, panels of 16 rows), 4 (257 .. 512, 32 rows) or 8 (129 .. 256, 64 rows: a wave per
+// row) row groups.  The grid is one workgroup per compute unit, fewer for a short
 // matrix.  A share of more than 4 panels is streamed: the two register panels
 // stay, the others go through the two LDS buffers two panels ahead, as in fs_persist.hip.
 //
@@ -43,7 +44,7 @@ constexpr int kResAutoPanels = 16;      // up to here this kernel is the faster 
                                         // where the 1024-lane kernel has idle lanes, as far as it goes (32768 rows:
                                         // 53.8 against 96.7)
 
-// All-reduce over aligned groups of LW lanes (16: a DPP row, rotated; 2: lane ^ 1; 4: then lane ^ 2; 8: then the half row mirrored).
+// All-reduce over aligned groups of LW lanes (16: a DPP row, rotated; 1: nothing to do; 2: lane ^ 1; 4: then lane ^ 2; 8: then the half row mirrored).
 template <int LW>
 __device__ __forceinline__ float group_sum_f32(float x) {
     if (LW == 16) {
@@ -52,7 +53,7 @@ __device__ __forceinline__ float group_sum_f32(float x) {
         x += dpp_f32<0x122>(x);
         x += dpp_f32<0x121>(x);
     } else {
-        x += dpp_f32<0xB1>(x);     // quad_perm [1, 0, 3, 2]
+        if (LW >= 2) x += dpp_f32<0xB1>(x);     // quad_perm [1, 0, 3, 2]
         if (LW >= 4) x += dpp_f32<0x4E>(x);     // quad_perm [2, 3, 0, 1]
         if (LW == 8) x += dpp_f32<0x141>(x);    // row_half_mirror
     }
@@ -66,7 +67,7 @@ __device__ __forceinline__ double group_max_f64(double x) {
         x = dmax(x, dpp_f64<0x122>(x));
         x = dmax(x, dpp_f64<0x121>(x));
     } else {
-        x = dmax(x, dpp_f64<0xB1>(x));
+        if (LW >= 2) x = dmax(x, dpp_f64<0xB1>(x));
         if (LW >= 4) x = dmax(x, dpp_f64<0x4E>(x));
         if (LW == 8) x = dmax(x, dpp_f64<0x141>(x));
     }
@@ -81,7 +82,7 @@ __device__ __forceinline__ double group_max_f64(double x) {
 // of every panel; the groups add their column sums in LDS before the workgroup publishes them.
 template <int Q, int R, int NW, bool STREAM, bool FULLW, int H = 1>
 __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X, Ctl c) {
-    constexpr int T = 64 * NW, NP = H > 2 ? kResMaxPanels / 2 : kResMaxPanels, NR = kResRegs, NL = kResLds;
+    constexpr int T = 64 * NW, NP = H > 2 ? 2 * kResMaxPanels / H : kResMaxPanels, NR = kResRegs, NL = kResLds;
     constexpr int TC = T / H, RH = R / H, NWH = NW / H;      // lanes per row, rows per group and panel, waves per row
     constexpr int NDMA = RH * Q;               // prefetch loads per panel and wave
     constexpr int LW = R <= 4 ? 16 : 64 / R;   // lanes per row in the merge of the wave sums: NWH partials (then zeros)
@@ -691,17 +692,17 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 
 }  // namespace
 
-// The shapes this kernel takes: fp32 costs, 256 < m <= 8192 (panels of 32 rows up to 512 columns, of 16 up to 1024, of 8 up to 2048, of 4 up to 4096,
+// The shapes this kernel takes: fp32 costs, 128 < m <= 8192 (panels of 64 rows up to 256 columns, of 32 up to 512, of 16 up to 1024, of 8 up to 2048, of 4 up to 4096,
 // of 2 beyond; 2048, 4096, 6144 or 8192 column slots), on a grid of one workgroup per compute unit, never more than there are panels and never so few
 // that a workgroup would merge a strip of more than 64 columns.  Up to kResPanels panels per workgroup the whole
 // share stays on the chip; beyond, the panels behind the register panels are streamed: up to kResAutoPanels as the
 // library's own choice (at exactly 2048 columns: up to kResMaxPanels; between 6145 and 8191 columns: not at all),
 // up to kResMaxPanels on request (`all`).  Up to 1024 columns: always up to kResMaxPanels (half of that up to 512
-// columns, where the row scalars of a panel of 32 rows take twice the LDS).
+// columns, a quarter up to 256: the row scalars of a taller panel take more LDS), i.e. 512 rows per workgroup.
 // Returns the workgroups of the launch, 0 when the shape is not taken.
 int dense_resident_grid(int n, int m, int cus, bool all) {
-    if (cus < 1 || n < 1 || m <= 256 || m > 8192) return 0;
-    const int R = m <= 512 ? 32 : m <= 1024 ? 16 : m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
+    if (cus < 1 || n < 1 || m <= 128 || m > 8192) return 0;
+    const int R = m <= 256 ? 64 : m <= 512 ? 32 : m <= 1024 ? 16 : m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
     const long long npanels = ((long long)n + R - 1) / R;
     long long g = npanels < cus ? npanels : cus;
     if (g > 256) g = 256;                                  // the exchange buffer holds 256 sets of column sums
@@ -710,7 +711,7 @@ int dense_resident_grid(int n, int m, int cus, bool all) {
     // (a width between 6145 and 8191 columns is streamed by the 1024-lane kernel as fast or faster: 8000 x 8000 46.4
     // against 47.3 us per iteration; below, this one wins: 6000 x 6000 31.8 against 34.0, 8000 x 5000 38.7 / 40.8,
     // 16384 x 3000 47.6 / 53.5, 8000 x 2500 25.6 / 30.4, 12000 x 1500 23.5 / 40.1)
-    const long long most = m <= 512 ? kResMaxPanels / 2 : all || m <= 1024 || m == 2048 ? kResMaxPanels : (m > 6144 && m < 8192) ? kResPanels : kResAutoPanels;
+    const long long most = m <= 256 ? kResMaxPanels / 4 : m <= 512 ? kResMaxPanels / 2 : all || m <= 1024 || m == 2048 ? kResMaxPanels : (m > 6144 && m < 8192) ? kResPanels : kResAutoPanels;
     return npanels <= most * g ? (int)g : 0;
 }
 
@@ -719,9 +720,15 @@ hipError_t launch_resident(hipStream_t st, const DenseArgs &a, const PersistArgs
     if (a.c_dtype != 0 || grid < 1 || dense_resident_grid(a.p.n, a.p.m, grid, true) != grid) return hipErrorInvalidValue;
     const dim3 g(grid), block(512);
     const int m = a.p.m;
-    const int R = m <= 512 ? 32 : m <= 1024 ? 16 : m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
+    const int R = m <= 256 ? 64 : m <= 512 ? 32 : m <= 1024 ? 16 : m <= 2048 ? 8 : m <= 4096 ? 4 : 2;
     const bool stream = ((long long)a.p.n + R - 1) / R > (long long)kResPanels * grid;
-    if (m == 512) {
+    if (m == 256) {
+        if (stream) launch_stamped((k_resident<1, 64, 8, true, true, 8>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<1, 64, 8, false, true, 8>), g, block, st, tm, a, x, c);
+    } else if (m < 256) {
+        if (stream) launch_stamped((k_resident<1, 64, 8, true, false, 8>), g, block, st, tm, a, x, c);
+        else launch_stamped((k_resident<1, 64, 8, false, false, 8>), g, block, st, tm, a, x, c);
+    } else if (m == 512) {
         if (stream) launch_stamped((k_resident<1, 32, 8, true, true, 4>), g, block, st, tm, a, x, c);
         else launch_stamped((k_resident<1, 32, 8, false, true, 4>), g, block, st, tm, a, x, c);
     } else if (m < 512) {

@@ -147,12 +147,13 @@ def test_kernel_choice_table_without_gpu():
     assert pick(16384, 16384, 3) == "points" and pick(16384, 12288) == "fused" and pick(16384, 16384) == "fused"   # c5
     assert pick(64, 64) == "small" and pick(128, 128) == "small" and pick(129, 128) == "coop"
     assert pick(512, 512) == "coop" and pick(513, 512) == "grid" and pick(800, 1024) == "grid"
-    assert pick(4096, 256) == "grid" and pick(4096, 2048) == "persist"
-    # at more than 256 columns the persistent pass keeps C on the chip and is preferred, unless the problem is small
+    assert pick(4096, 128) == "grid" and pick(3000, 256) == "grid" and pick(4096, 2048) == "persist"
+    # at more than 128 columns the persistent pass keeps C on the chip and is preferred, unless the problem is small
     assert pick(2048, 2048) == "persist" and pick(2048, 1025) == "persist" and pick(2048, 1024) == "persist"
     assert pick(1024, 1024) == "persist" and pick(4096, 1024) == "persist" and pick(2048, 513) == "persist"
     assert pick(65536, 1024) == "persist" and pick(131072, 600) == "persist" and pick(131073, 600) == "fused"   # 32 panels of 16 rows
     assert pick(4096, 512) == "persist" and pick(4096, 257) == "persist" and pick(131072, 400) == "persist" and pick(131073, 400) == "fused"
+    assert pick(4096, 256) == "persist" and pick(131072, 129) == "persist" and pick(131073, 129) != "persist" and pick(65536, 128) != "persist"
     assert pick(256, 2048) == "persist" and pick(800, 1200) == "persist" and pick(640, 1280) == "grid"
     assert pick(300, 1100) == "grid" and pick(200, 2048) == "grid"       # 25 panels: strips of more than 64 columns
     assert pick(2048, 2048, cost_dtype=1) == "grid" and pick(2048, 2048, blocking=False) != "persist"
@@ -171,7 +172,7 @@ def test_kernel_choice_table_without_gpu():
     # asynchronous solves never pick the whole-chip kernel by themselves; a smaller device shrinks its range
     assert pick(1024, 1024, blocking=False) == "fused" and pick(512, 512, blocking=False) == "coop"
     assert pick(1024, 1024, blocking=False, kernel_mode=5) == "grid"
-    assert fs.fs_kernel_choice(4096, 256, 0, True, 64) == "fused" and fs.fs_kernel_choice(1024, 256, 0, True, 64) == "grid"
+    assert fs.fs_kernel_choice(4096, 128, 0, True, 64) in ("fused", "stream") and fs.fs_kernel_choice(1024, 128, 0, True, 64) == "grid"
     assert fs.fs_kernel_choice(4096, 1024, 0, True, 64) == "persist" and fs.fs_kernel_choice(4096, 1024, 0, True, 8) == "fused"
     # 2-byte costs: fused from 2049 columns on, whole 16-byte chunks only
     assert pick(300, 4096, cost_dtype=1) == "fused" and pick(100, 2048, cost_dtype=1) == "stream"

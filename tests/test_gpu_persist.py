@@ -1,5 +1,5 @@
 """GPU parity of the persistent fused pass (kernel_mode 6; the automatic choice of the blocking dense
-solves for 256 < m <= 8192): one resident workgroup per compute unit, a block of iterations per launch,
+solves for 128 < m <= 8192): one resident workgroup per compute unit, a block of iterations per launch,
 two grid-wide waits per iteration.  Everything goes through the C ABI and is compared with the CPU oracle.
 """
 import math
@@ -55,24 +55,25 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
           (2048, 6144), (5000, 6144), (1000, 6000), (2301, 4097),   # ... and shares of which the 512-lane kernel streams a part
           (1000, 1000), (4096, 1024), (8191, 1024), (333, 700), (5000, 513), (9000, 1024),   # two row groups per workgroup
           (17000, 1024), (20000, 1000),                            # ... streamed
-          (2100, 512), (8190, 512), (1000, 300), (4097, 257), (33000, 512), (40000, 400)]   # four row groups; streamed
+          (2100, 512), (8190, 512), (1000, 300), (4097, 257), (33000, 512), (40000, 400),   # four row groups; streamed
+          (5000, 256), (4500, 129), (16383, 256), (70000, 256), (66000, 200)]                 # eight row groups; streamed
 
 
 def _resident(n, m, cus=256, most=4):
-    """Whether the 512-lane kernel of the persistent pass takes the shape (256 < m <= 8192, 1 .. most panels of 64 KiB
+    """Whether the 512-lane kernel of the persistent pass takes the shape (128 < m <= 8192, 1 .. most panels of 64 KiB
     per workgroup of a grid of min(cus, panels) workgroups that merge at most 64 columns each): up to 4 panels the matrix stays on the chip for a whole launch; beyond
     that the panels behind the two in registers are streamed: up to 16 panels (32 at 2048 columns) it is
     the library's own choice (fused_variant = 1 asks for the 1024-lane streaming kernel instead), up to 32 it can be
     asked for (fused_variant = 2)."""
-    if not 256 < m <= 8192:
+    if not 128 < m <= 8192:
         return False
-    rows = 32 if m <= 512 else 16 if m <= 1024 else 8 if m <= 2048 else 4 if m <= 4096 else 2
+    rows = 64 if m <= 256 else 32 if m <= 512 else 16 if m <= 1024 else 8 if m <= 2048 else 4 if m <= 4096 else 2
     panels = -(-n // rows)
     grid = min(cus, panels, 256)
     if (-(-m // grid) + 3) // 4 * 4 > 64:                    # a workgroup merges a strip of at most 64 columns
         return False
     if m == 2048 or m <= 1024:
-        most = 32 if m > 512 else 16                         # (up to 1024 columns there is no 1024-lane form)
+        most = 32 if m > 512 else 16 if m > 256 else 8                         # (up to 1024 columns there is no 1024-lane form)
     if 6144 < m < 8192 and most == 16:
         most = 4                                             # streamed by the 1024-lane kernel unless asked otherwise
     return panels <= most * grid
@@ -128,7 +129,7 @@ def test_persistent_pass_is_the_automatic_choice_and_repeats_bit_for_bit(fs, ora
 
 
 # the streaming form; the resident form (ragged last panel); the resident form with two row groups per workgroup
-@pytest.mark.parametrize("n,m", [(320, 1500), (1030, 4096), (1210, 1000), (2500, 500)])
+@pytest.mark.parametrize("n,m", [(320, 1500), (1030, 4096), (1210, 1000), (2500, 500), (5000, 250)])
 def test_persistent_pass_stop_rule_history_and_resume(fs, oracle, n, m):
     import torch
     if not _supported(fs, n, m):
@@ -170,7 +171,7 @@ def test_persistent_pass_stop_rule_history_and_resume(fs, oracle, n, m):
 
 @pytest.mark.parametrize("eps", [1e-3, 1e-4])
 @pytest.mark.parametrize("n,m", [(517, 4100), (300, 4096), (600, 8190), (260, 8192), (300, 12288), (290, 16001), (1500, 3001),
-                                 (1100, 1024), (5000, 900), (3000, 512)])
+                                 (1100, 1024), (5000, 900), (3000, 512), (6000, 256)])
 def test_persistent_pass_small_eps(fs, oracle, n, m, eps):
     """Costs up to 60 at eps 1e-3 and 1e-4: the exact redo of the row phase, and potentials of 10^5 .. 10^6
     in units of eps.  Same bar as the other dense paths in this regime (the iteration does not contract there,
@@ -192,7 +193,7 @@ def test_persistent_pass_small_eps(fs, oracle, n, m, eps):
 
 
 @pytest.mark.parametrize("eps", [0.05, 2e-3])
-@pytest.mark.parametrize("n,m", [(300, 4096), (600, 8192), (290, 16384), (520, 3001), (1300, 1024), (700, 600), (2200, 300)])
+@pytest.mark.parametrize("n,m", [(300, 4096), (600, 8192), (290, 16384), (520, 3001), (1300, 1024), (700, 600), (2200, 300), (4400, 200)])
 def test_persistent_pass_tiny_and_zero_weights(fs, oracle, n, m, eps):
     """Weights of 1e-30, 1e-36, a denormal and an exact zero in a and b: the columns concerned total less than
     2^-66 in fp32 and go through the exact recomputation inside the merge, every iteration."""
@@ -220,7 +221,7 @@ def test_persistent_pass_tiny_and_zero_weights(fs, oracle, n, m, eps):
     assert abs(r["marginal_err"] - err_ref) <= 1e-3 * err_ref + 5e-7
 
 
-@pytest.mark.parametrize("n,m", [(900, 2100), (1030, 4096), (1500, 1024), (3000, 400)])   # the streaming form; the resident forms
+@pytest.mark.parametrize("n,m", [(900, 2100), (1030, 4096), (1500, 1024), (3000, 400), (5000, 256)])   # the streaming form; the resident forms
 @pytest.mark.parametrize("warm", [False, True])
 def test_persistent_pass_gives_up_cleanly_and_the_solve_falls_back(fs, oracle, warm, n, m):
     """wait_limit = 1: a workgroup stops waiting for the others after a single poll, which the host can force
@@ -279,7 +280,7 @@ def _sweep_cases():
     rng = np.random.default_rng(20260511)
     cases = []
     for t in range(34):                          # (from 24 on: the widths with several row groups per workgroup)
-        m = int(rng.integers(1025, 16385)) if t < 24 else int(rng.integers(257, 1025))
+        m = int(rng.integers(1025, 16385)) if t < 24 else int(rng.integers(129, 1025))
         n = int(rng.integers(40, 2600)) if t < 24 else int(rng.integers(300, 9000))
         cases.append((t, n, m, float(rng.choice([0.01, 0.03, 0.1])), float(rng.choice([2.0, 20.0])),
                       int(rng.integers(3, 70)), bool(rng.integers(0, 2))))
