@@ -74,12 +74,14 @@ __device__ __forceinline__ double group_max_f64(double x) {
     return x;
 }
 
-// Q groups of 4 adjacent columns per lane (column(q, e) = (q 512 + tid) 4 + e), R rows per panel, R Q <= 8 (a panel
-// is at most 64 KiB: 32 entries per lane; 48 KiB for the widths up to 6144 columns).  FULLW: m = 2048 Q, every lane owns valid columns; else m < 2048 Q and the
-// columns past m are masked (V = -inf, C = 0, nothing published).
+// Q groups of 4 adjacent columns per lane (column(q, e) = (q 512 + tid) 4 + e), R rows per panel, R Q <= 8 H (a panel
+// is at most 64 KiB: 32 entries per lane; 48 KiB for the widths up to 6144 columns).  FULLW: m = 2048 Q / H, every
+// lane owns valid columns; else m is less than that and the columns past m are masked (V = -inf, C = 0, nothing
+// published).
 // H > 1 (narrow matrices): the workgroup is H row groups of T / H lanes; a row is spread over the NW / H waves of
 // its group only (column(q, e) = (q T / H + tid mod (T / H)) 4 + e) and group h works on the rows h R / H ...
-// of every panel; the groups add their column sums in LDS before the workgroup publishes them.
+// of every panel; the groups add their column sums in LDS before the workgroup publishes them.  The row scalars
+// of kResMaxPanels panels of 16 rows fit the LDS; taller panels (H > 2) come with proportionally fewer of them.
 template <int Q, int R, int NW, bool STREAM, bool FULLW, int H = 1>
 __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X, Ctl c) {
     constexpr int T = 64 * NW, NP = H > 2 ? 2 * kResMaxPanels / H : kResMaxPanels, NR = kResRegs, NL = kResLds;
