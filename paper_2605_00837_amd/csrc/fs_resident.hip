@@ -117,8 +117,10 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     const int rr = lane / LW, ww = lane % LW;  // the panel row and the wave whose partial this lane takes in the merge
     const int rc = rr < R ? rr : R - 1;
     const int wc = ww < NWH ? ww : NWH - 1;
-    const int tc = tid % TC;                   // the lane's place in its row group: it owns the columns (q TC + tc) 4 ...
-    const int hh = __builtin_amdgcn_readfirstlane(tid / TC), wq = wave % NWH;   // row group; the wave's place in it
+    // (one row group: plain constants, so that nothing of this is left in the code)
+    const int tc = H == 1 ? tid : tid % TC;    // the lane's place in its row group: it owns the columns (q TC + tc) 4 ...
+    const int hh = H == 1 ? 0 : __builtin_amdgcn_readfirstlane(tid / TC);       // row group
+    const int wq = H == 1 ? wave : wave % NWH;                                 // the wave's place in it
     static_assert(sizeof(sPart) >= (size_t)(H - 1) * TC * Q * 16, "the row groups meet in sPart");
 
     int k;
@@ -161,7 +163,8 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     // (slice tw: the wave's own, except between iterations, see below)
     auto issue = [&](int j, int buf, int tw) {
         const __amdgpu_buffer_rsrc_t rsrc = panel_rsrc(j);
-        const int tslot = (tw * 64 + lane) % TC, tg = (tw * 64) / TC;    // place in the row group, row group of slice tw
+        const int tslot = H == 1 ? tw * 64 + lane : (tw * 64 + lane) % TC;     // place in the row group
+        const int tg = H == 1 ? 0 : (tw * 64) / TC;                             // row group of slice tw
 #pragma unroll
         for (int r = 0; r < RH; ++r)
 #pragma unroll
@@ -250,6 +253,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     unsigned long long gen = sGen;
 
     bool alive = true;
+    int flip = 0;                                // a streaming workgroup: the buffer of the pass's first staged panel
     for (;;) {
         const int cur = k & 1, nxt = cur ^ 1;
         const bool rev = cur != 0;
@@ -419,25 +423,29 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
             ++regs_done;
         };
         for (int t = 0; t < ms; ++t) {
-            const int buf = t & 1;
+            const int buf = (t + flip) & 1;
             if (streaming && t >= 2 && regs_done < NR) reg_panel();
             if (streaming) {
-                // Panel t must have landed: the only younger vector-memory operations are the NDMA loads of panel
-                // t + 1 (if there is one), which may stay in flight (loads return in order; what wave 0 stored
-                // after them only makes its wait stricter).
-                if (t + 1 < ms) __builtin_amdgcn_s_waitcnt(waitcnt_vm(NDMA));
-                else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+                // Panel t must have landed: the only younger vector-memory operations are the NDMA loads issued after
+                // the panel before it (panel t + 1 of this pass, or the first panel of the next one), which may stay
+                // in flight (loads return in order; what wave 0 stored after them only makes its wait stricter).
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(NDMA));
                 asm volatile("" ::: "memory");
             }
             do_panel(std::integral_constant<int, -1>(), NR + buf, lds_panel(t, rev));
-            if (streaming && t + 2 < ms) {
-                // the panel after next into the buffer this panel occupied (this wave's own slice, its reads are done)
+            if (streaming && t + 1 < ms) {
+                // into the buffer this panel occupied (this wave's own slice, its reads are done): the panel after
+                // next or, behind the last but one, the first panel of the NEXT pass (C never changes; it lands while
+                // the register panels are worked on, and no load of the exchange has to queue behind it)
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_s_waitcnt(0xc07f);
-                issue(lds_panel(t + 2, rev), buf, wave);
+                issue(t + 2 < ms ? lds_panel(t + 2, rev) : lds_panel(0, false), buf, wave);
                 asm volatile("" ::: "memory");
             }
         }
+        // the last staged panel of this pass is the second of the next one (the sweep turns round): it stays where it
+        // is, and the buffers swap roles when their number of turns is odd
+        if (streaming) flip ^= ms & 1;
         while (regs_done < NR) reg_panel();
         }
 
@@ -614,23 +622,10 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
             break;
         }
         ++gen;
-        const bool more = k + 1 < k_end || (k + 1 == k_end && with_trailing);
         unsigned long long old2 = 0ull;
         if (wave == 0) {
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(0)); // the strip's new G and V (all published by this wave) are acknowledged
             old2 = grid_arrive(X.sync);
-        }
-        if (streaming && more) {
-            // The first staged panel of the next pass goes on its way now: the arrival is out, and by the time a poll can
-            // see the last workgroup arrive, the memory pipeline of this compute unit has drained these requests.  Wave 0
-            // does the waiting, with polls that would queue behind a prefetch of its own: wave 1 fetches its slice too.
-            lds_only_barrier();
-            if (wave != 0) {
-                asm volatile("" ::: "memory");
-                issue(lds_panel(0, false), 0, wave);
-                if (wave == 1) issue(lds_panel(0, false), 0, 0);
-                asm volatile("" ::: "memory");
-            }
         }
         if (wave == 0) {
             const int ok = grid_wait(X.sync, old2, gen, W, X.spin_limit);
@@ -663,14 +658,6 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                     }
                 }
             }
-        }
-        if (streaming && more) {
-            // the second staged panel behind the loads of V: "all but the youngest NDMA loads have landed" then means
-            // that V and the first panel are here (wave 0's slice of it came through wave 1, hence the barrier)
-            asm volatile("" ::: "memory");
-            issue(lds_panel(1, nxt != 0), 1, wave);
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(NDMA));
-            lds_only_barrier();
         }
 #ifdef FS_PERSIST_TRACE
         asm volatile("" :: "v"(v[0][0]), "v"(v[Q - 1][3]));
