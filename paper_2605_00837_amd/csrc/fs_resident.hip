@@ -132,8 +132,9 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     // This workgroup owns the panels w, w + W, ... (3 .. NP of them, or at most NR + NL: the launcher sees to it), in
     // every iteration.  Panels 0 .. NR-1 live in registers.  The others live in LDS when there are at most NL of
     // them (loaded once); else they are streamed through the NL staging buffers every iteration, two panels
-    // ahead, as in the streaming form of the pass: the first of them always first, the others upwards on even
-    // and downwards on odd iterations (what the last-level cache still holds from the pass before is read first).
+    // ahead, upwards on even and downwards on odd iterations: the two panels a pass ends with are the two the next
+    // pass begins with, they stay in the staging buffers and are not fetched again (and what the last-level cache
+    // still holds from the pass before is read first).
     const int npanels = (n + R - 1) / R;
     const int mine = (npanels - 1 - w) / W + 1;
     const int ms = mine > NR ? mine - NR : 0;          // panels behind the register panels
@@ -177,7 +178,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
             }
     };
     // the panel behind the register panels that a pass visits in position t
-    auto lds_panel = [&](int t, bool rev) { return NR + (t == 0 ? 0 : (rev ? ms - t : t)); };
+    auto lds_panel = [&](int t, bool rev) { return NR + (rev ? ms - 1 - t : t); };
     // ---- the register panels, once per launch
     float creg[NR][RH][Q][4];
 #pragma unroll
@@ -201,12 +202,11 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                 }
             }
     }
-    // ---- the LDS panels: the resident ones once per launch; a streaming workgroup the first two of this pass (those
-    //      of the passes after it go on their way during the exchange of the iteration before, C never changes:
-    //      the first -- always the same panel -- as soon as the workgroup has arrived at the second wait, by the
-    //      waves that do not do the waiting, the second right after the read of V)
-    if (ms > 0) issue(lds_panel(0, (k & 1) != 0), 0, wave);
-    if (ms > 1) issue(lds_panel(1, (k & 1) != 0), 1, wave);
+    // ---- the LDS panels: the resident ones once per launch; a streaming workgroup the first two of its first pass
+    //      (every later pass finds its first two where the pass before it left them)
+    const bool rev0 = STREAM && (k & 1) != 0;
+    if (ms > 0) issue(lds_panel(0, rev0), 0, wave);
+    if (ms > 1) issue(lds_panel(1, rev0), 1, wave);
     // V of this lane's columns (written before this launch)
     double v[Q][4];
 #pragma unroll
@@ -253,7 +253,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
     unsigned long long gen = sGen;
 
     bool alive = true;
-    int flip = 0;                                // a streaming workgroup: the buffer of the pass's first staged panel
+    int flip = 0;                                // the staging buffer of the pass's first staged panel
     for (;;) {
         const int cur = k & 1, nxt = cur ^ 1;
         const bool rev = cur != 0;
@@ -426,26 +426,26 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
             const int buf = (t + flip) & 1;
             if (streaming && t >= 2 && regs_done < NR) reg_panel();
             if (streaming) {
-                // Panel t must have landed: the only younger vector-memory operations are the NDMA loads issued after
-                // the panel before it (panel t + 1 of this pass, or the first panel of the next one), which may stay
-                // in flight (loads return in order; what wave 0 stored after them only makes its wait stricter).
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm(NDMA));
+                // Panel t must have landed: the only younger vector-memory operations are the NDMA loads of panel
+                // t + 1 (if there is one), which may stay in flight (loads return in order; what wave 0 stored
+                // after them only makes its wait stricter).
+                if (t + 1 < ms) __builtin_amdgcn_s_waitcnt(waitcnt_vm(NDMA));
+                else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
                 asm volatile("" ::: "memory");
             }
             do_panel(std::integral_constant<int, -1>(), NR + buf, lds_panel(t, rev));
-            if (streaming && t + 1 < ms) {
-                // into the buffer this panel occupied (this wave's own slice, its reads are done): the panel after
-                // next or, behind the last but one, the first panel of the NEXT pass (C never changes; it lands while
-                // the register panels are worked on, and no load of the exchange has to queue behind it)
+            if (streaming && t + 2 < ms) {
+                // the panel after next into the buffer this panel occupied (this wave's own slice, its reads are done)
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_s_waitcnt(0xc07f);
-                issue(t + 2 < ms ? lds_panel(t + 2, rev) : lds_panel(0, false), buf, wave);
+                issue(lds_panel(t + 2, rev), buf, wave);
                 asm volatile("" ::: "memory");
             }
         }
-        // the last staged panel of this pass is the second of the next one (the sweep turns round): it stays where it
-        // is, and the buffers swap roles when their number of turns is odd
-        if (streaming) flip ^= ms & 1;
+        // The sweep turns round: the last two staged panels of this pass are the first two of the next one, they stay
+        // where they are (no load of the exchange ever queues behind a prefetch), and the buffers swap roles when
+        // the last panel sits in the buffer that the first one started in.
+        if (ms > 0) flip ^= (ms - 1) & 1;
         while (regs_done < NR) reg_panel();
         }
 
