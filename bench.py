@@ -233,15 +233,16 @@ def bench_dense(args, name):
                                             "the timed solve run right after it (stamping costs queue time)",
                            "iterations_per_launch": covered / max(launches, 1), "kernel_us_per_iteration": per_iter_ms * 1e3,
                            "algorithmic_bytes_per_launch": alg_bytes_launch}
-        rows_pp = 8 if m <= 2048 else 4 if m <= 4096 else 2           # rows per panel of k_resident
+        rows_pp = 64 if m <= 256 else 32 if m <= 512 else 16 if m <= 1024 else 8 if m <= 2048 else 4 if m <= 4096 else 2   # rows per panel of k_resident
         panels = -(-n // rows_pp)
         wgs = min(torch.cuda.get_device_properties(0).multi_processor_count, panels, 256)
         if kern_name == "k_resident" and panels > 4 * wgs:
             per_wg = -(-panels // wgs)
             out["roofline"]["resident"] = {
-                "note": "two of the %d panels of every workgroup stay in registers for a whole launch: %.3f of C is "
-                        "read from memory per iteration; achieved / frac are the algorithmic bytes (all of C) over "
-                        "time, as for any other kernel" % (per_wg, 1.0 - 2.0 / per_wg)}
+                "note": "four of the %d panels of every workgroup are not fetched in an iteration: two stay in registers "
+                        "for a whole launch, and the two a pass ends with stay in LDS as the first two of the next pass "
+                        "(the sweep turns round): %.3f of C is read from memory per iteration; achieved / frac are the "
+                        "algorithmic bytes (all of C) over time, as for any other kernel" % (per_wg, 1.0 - 4.0 / per_wg)}
         elif kern_name == "k_resident":
             # C stays in LDS and registers for a whole launch: the algorithmic bytes above are NOT read from memory
             # (achieved / frac say how this compares with a pass that would stream them).  What bounds the pass is

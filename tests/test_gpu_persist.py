@@ -54,7 +54,7 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
           (4200, 2500), (8300, 1500), (2200, 5000), (2300, 8000), (6000, 6000), (9000, 3000), (5000, 6145),
           (2048, 6144), (5000, 6144), (1000, 6000), (2301, 4097),   # ... and shares of which the 512-lane kernel streams a part
           (1000, 1000), (4096, 1024), (8191, 1024), (333, 700), (5000, 513), (9000, 1024),   # two row groups per workgroup
-          (17000, 1024), (20000, 1000),                            # ... streamed
+          (17000, 1024), (20000, 1000), (4700, 8100), (9300, 8192),    # ... streamed
           (2100, 512), (8190, 512), (1000, 300), (4097, 257), (33000, 512), (40000, 400),   # four row groups; streamed
           (5000, 256), (4500, 129), (16383, 256), (70000, 256), (66000, 200)]                 # eight row groups; streamed
 
@@ -62,8 +62,8 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
 def _resident(n, m, cus=256, most=4):
     """Whether the 512-lane kernel of the persistent pass takes the shape (128 < m <= 8192, 1 .. most panels of 64 KiB
     per workgroup of a grid of min(cus, panels) workgroups that merge at most 64 columns each): up to 4 panels the matrix stays on the chip for a whole launch; beyond
-    that the panels behind the two in registers are streamed: up to 16 panels (32 at 2048 columns) it is
-    the library's own choice (fused_variant = 1 asks for the 1024-lane streaming kernel instead), up to 32 it can be
+    that the panels behind the two in registers are streamed: up to 20 panels (most = "auto"; 18 between 6145 and 8191
+    columns, 32 at 2048 columns) it is the library's own choice (fused_variant = 1 asks for the 1024-lane streaming kernel instead), up to 32 it can be
     asked for (fused_variant = 2)."""
     if not 128 < m <= 8192:
         return False
@@ -74,8 +74,8 @@ def _resident(n, m, cus=256, most=4):
         return False
     if m == 2048 or m <= 1024:
         most = 32 if m > 512 else 16 if m > 256 else 8                         # (up to 1024 columns there is no 1024-lane form)
-    if 6144 < m < 8192 and most == 16:
-        most = 4                                             # streamed by the 1024-lane kernel unless asked otherwise
+    if most == "auto":
+        most = 18 if 6144 < m < 8192 else 20
     return panels <= most * grid
 
 
@@ -90,7 +90,7 @@ def test_persistent_pass_matches_oracle(fs, oracle, n, m):
     w = W.random_dense(n, m, seed=6000 + n + m, cmax=2.0, eps=0.03)
     iters = 52                                  # one whole block of 50 iterations and a short one
     ref = oracle.solve(w.a, w.b, w.eps, iters, C=w.C)
-    variants = (0,) if m <= 1024 else (0, 1) if _resident(n, m, cus, most=16) else (0, 2) if _resident(n, m, cus, most=32) else (0,)
+    variants = (0,) if m <= 1024 else (0, 1) if _resident(n, m, cus, most="auto") else (0, 2) if _resident(n, m, cus, most=32) else (0,)
     for variant in variants:
         r = fs.fs_sinkhorn_solve(dev(w.a), dev(w.b), w.eps, iters, 0.0, C=dev(w.C), want_f64=True, kernel_mode=6,
                                  fused_variant=variant, time_kernel_every=1)
@@ -98,7 +98,7 @@ def test_persistent_pass_matches_oracle(fs, oracle, n, m):
         assert pot_err(r["f64"].cpu().numpy(), ref["f"], w.eps) < TOL_F64
         assert pot_err(r["g64"].cpu().numpy(), ref["g"], w.eps) < TOL_F64
         name = fs.fs_last_kernel_timing()[2]
-        assert name == ("k_resident" if (_resident(n, m, cus, most=16) and variant == 0) or variant == 2 else "k_persist"), \
+        assert name == ("k_resident" if (_resident(n, m, cus, most="auto") and variant == 0) or variant == 2 else "k_persist"), \
             (n, m, variant, name)
     assert pot_err(r["f"].cpu().numpy(), ref["f"], w.eps) < TOL_F32
     err_ref = float(oracle.marginal_err(w.a, w.b, w.eps, ref["f"], ref["g"], C=w.C))
