@@ -55,6 +55,7 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
           (2048, 6144), (5000, 6144), (1000, 6000), (2301, 4097),   # ... and shares of which the 512-lane kernel streams a part
           (1000, 1000), (4096, 1024), (8191, 1024), (333, 700), (5000, 513), (9000, 1024),   # two row groups per workgroup
           (17000, 1024), (20000, 1000), (4700, 8100), (9300, 8192),    # ... streamed
+          (22000, 4096),                                           # ... 22 panels per workgroup: the 512-lane kernel on request only
           (2100, 512), (8190, 512), (1000, 300), (4097, 257), (33000, 512), (40000, 400),   # four row groups; streamed
           (5000, 256), (4500, 129), (16383, 256), (70000, 256), (66000, 200)]                 # eight row groups; streamed
 
