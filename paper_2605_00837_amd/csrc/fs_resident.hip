@@ -409,9 +409,11 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                     for (int e = 0; e < 4; ++e) cS[q][e] = fmaf(ev[r][q][e], alpha, cS[q][e]);
             }
         };
-        // A streaming workgroup is bound by the memory system (a panel arrives in 2.4 us and takes 1.6 us of
-        // arithmetic): its register panels go where it would otherwise wait, behind the two staged panels that
-        // are already here.
+        // A streaming workgroup is bound by the memory system (a panel arrives in 2.3 us and takes 1.7 us of
+        // arithmetic): its register panels go early in the pass, one behind each of the first two staged panels (which
+        // are already here when the pass begins), so that the first requests of the pass have a lead over the
+        // arithmetic that absorbs the spread of the fetch times.  (With masked lanes: behind the second and the
+        // third.  Measured; later in the pass, or both in one place, is 1 - 3 us per iteration slower at 8192 x 8192.)
         if constexpr (!STREAM) {
             // everything is on the chip: the panels in program order, every index a constant
             if (ms > 0) do_panel(std::integral_constant<int, -1>(), NR, NR);
@@ -427,7 +429,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
         };
         for (int t = 0; t < ms; ++t) {
             const int buf = (t + flip) & 1;
-            if (streaming && t >= 2 && regs_done < NR) reg_panel();
+            if (streaming && t >= (FULLW ? 1 : 2) && regs_done < NR) reg_panel();
             if (streaming) {
                 // Panel t must have landed: the only younger vector-memory operations are the NDMA loads of panel
                 // t + 1 (if there is one), which may stay in flight (loads return in order; what wave 0 stored
