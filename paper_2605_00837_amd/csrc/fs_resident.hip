@@ -271,7 +271,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
         FS_TRACE(0);
         // One panel: REG >= 0: register panel REG (= panel REG of this workgroup); REG < 0: the panel j in staging
         // buffer slot - NR.  `slot` also names the row-sum staging this panel uses.
-        auto do_panel = [&](auto reg_tag, int slot, int j) {
+        auto do_panel = [&](auto reg_tag, int slot, int j, int jnext = -1) {
             constexpr int REG = decltype(reg_tag)::value;
             const int i0 = (w + j * W) * R;
             const bool rowok = rr < R && (i0 + rr) < n;
@@ -398,6 +398,16 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                 // error term of Sec. 4.5 for the iterate this iteration started from: a_i |2^(Fnew - Fold) - 1|
                 if (a_lane > 0.0f) err_acc += (double)a_lane * fabs(exp2m1(Fn_lane - rho_lane));
             }
+            if constexpr (REG < 0 && STREAM) {
+                // nothing below reads the staging buffer: the panel after next goes into it now (this wave's own
+                // slice, its reads are done)
+                if (jnext >= 0) {
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_s_waitcnt(0xc07f);
+                    issue(jnext, slot - NR, wave);
+                    asm volatile("" ::: "memory");
+                }
+            }
             // ---- column phase with the new f (the trailing round does it too: its sums are simply not published)
 #pragma unroll
             for (int r = 0; r < RH; ++r) {
@@ -438,14 +448,8 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                 else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
                 asm volatile("" ::: "memory");
             }
-            do_panel(std::integral_constant<int, -1>(), NR + buf, lds_panel(t, rev));
-            if (streaming && t + 2 < ms) {
-                // the panel after next into the buffer this panel occupied (this wave's own slice, its reads are done)
-                asm volatile("" ::: "memory");
-                __builtin_amdgcn_s_waitcnt(0xc07f);
-                issue(lds_panel(t + 2, rev), buf, wave);
-                asm volatile("" ::: "memory");
-            }
+            do_panel(std::integral_constant<int, -1>(), NR + buf, lds_panel(t, rev),
+                     streaming && t + 2 < ms ? lds_panel(t + 2, rev) : -1);
         }
         // The sweep turns round: the last two staged panels of this pass are the first two of the next one, they stay
         // where they are (no load of the exchange ever queues behind a prefetch), and the buffers swap roles when
