@@ -5,8 +5,8 @@
 //
 // Layout: 1024 lanes = 32 x 32; lane (tr, tc) = (tid / 32, tid % 32) owns the entries
 // (tr + 32 a, tc + 32 b), a < RA, b < CB.  Row LSE (Eq. 9): the 32 lanes of a row group sit in one
-// half-wave, so the maximum and the sum are all-reduced with DPP and one swizzle, no LDS.  Column
-// LSE (Eq. 10): the two half-waves of a wave meet through ds_bpermute, the 16 waves through LDS.
+// half-wave, so the maximum and the sum are all-reduced with DPP and one lane swap, no LDS.  Column
+// LSE (Eq. 10): the two half-waves of a wave meet through a lane swap, the 16 waves through LDS.
 // Both are the two-pass LogSumExp of Eq. 8 over registers: exact maximum first, then the sum.
 // Arithmetic as everywhere else: potentials and exponent arguments in fp64 (scaled to base 2),
 // v_exp_f32 and the sums in fp32.
