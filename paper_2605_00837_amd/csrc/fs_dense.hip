@@ -864,6 +864,7 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
         };
         // ---- row phase, optimistic: e = 2^(x - rho_r), summed
         float ev[R][Q][EPL];
+        float racc[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             float acc = 0.0f;
@@ -878,9 +879,9 @@ __global__ __launch_bounds__(1024) void k_fused_pf(DenseArgs A, Ctl c) {
                     acc += ev[r][q][e];
                 }
             }
-            acc = wave_sum_f32(acc);
-            if (lane == 0) sSum[buf][r][wave] = acc;
+            racc[r] = acc;
         }
+        rows_sum_store<R>(racc, &sSum[buf][0][wave], NW, lane);
         lds_only_barrier();
         float S = rr < R ? sSum[buf][rc][lane % NW] : 1.0f;
         S += dpp_f32<0x128>(S);

@@ -313,6 +313,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
             }
             // ---- row phase, optimistic: e = 2^(x - rho_r), summed
             float ev[RH][Q][4];
+            float racc[RH];
 #pragma unroll
             for (int r = 0; r < RH; ++r) {
                 float acc = 0.0f;
@@ -326,9 +327,9 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
                         acc += ev[r][q][e];
                     }
                 }
-                acc = wave_sum_f32(acc);
-                if (lane == 0) sSum[slot][hh * RH + r][wq] = acc;
+                racc[r] = acc;
             }
+            rows_sum_store<RH>(racc, &sSum[slot][hh * RH][wq], NWH, lane);
             lds_only_barrier();
             float S = rr < R ? (ww < NWH ? sSum[slot][rc][wc] : 0.0f) : 1.0f;
             S = group_sum_f32<LW>(S);
