@@ -223,7 +223,7 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
             }
             // ---- row phase, optimistic: e = 2^(x - rho_r), summed
             float ev[R][Q][4];
-            float racc[R];
+            float racc[R];                     // (Q == 1 only)
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 float acc = 0.0f;
@@ -238,9 +238,15 @@ __global__ __launch_bounds__(1024) void k_persist(DenseArgs A, PersistArgs X, Ct
                         acc += ev[r][q][e];
                     }
                 }
-                racc[r] = acc;
+                if constexpr (Q == 1) {
+                    racc[r] = acc;       // two rows per lane exchange, below
+                } else {
+                    // (with more columns per lane the kernel is at its register limit and the two-row form spills)
+                    acc = wave_sum_f32(acc);
+                    if (lane == 0) sSum[buf][r][wave] = acc;
+                }
             }
-            rows_sum_store<R>(racc, &sSum[buf][0][wave], NW, lane);
+            if constexpr (Q == 1) rows_sum_store<R>(racc, &sSum[buf][0][wave], NW, lane);
             lds_only_barrier();
             float S = rr < R ? sSum[buf][rc][lane % NW] : 1.0f;
             S += dpp_f32<0x128>(S);
