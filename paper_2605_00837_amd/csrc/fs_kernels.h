@@ -277,7 +277,7 @@ bool dense_persist_supported(int n, int m, const void *C, int c_dtype);
 int dense_persist_grid(int n, int m, int cus);   // workgroups of the launch on a device with `cus` compute units
 size_t persist_scratch_bytes();
 // variant 0: the 512-lane kernel of fs_resident.hip where the workgroups can hold their share of C, or most of the
-// panels they stream are few (up to 20 panels per workgroup; 18 between 6145 and 8191 columns, 32 at 2048 columns), else the 1024-lane streaming kernel; 1: always the
+// panels they stream are few (up to 32 panels per workgroup; 20 between 6145 and 8191 columns), else the 1024-lane streaming kernel; 1: always the
 // 1024-lane streaming kernel; 2: the 512-lane kernel up to 32 panels per workgroup.  Up to 1024 columns there is only
 // the 512-lane kernel, whatever the variant.
 hipError_t launch_persist(hipStream_t st, const DenseArgs &a, const Ctl &c, void *scratch, int cus, int nb,

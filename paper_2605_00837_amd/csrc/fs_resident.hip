@@ -38,14 +38,15 @@ constexpr int kResRegs = 2;             // panels a workgroup keeps in registers
 constexpr int kResLds = 2;              // panels the LDS holds: the other resident ones, or the two staging buffers
 constexpr int kResPanels = kResRegs + kResLds;   // up to here the whole share stays on the chip
 constexpr int kResMaxPanels = 32;       // panels per workgroup at most (row scalars in LDS)
-constexpr int kResAutoPanels = 20;      // up to here this kernel is the faster one at 4096 and 8192 columns (measured,
-                                        // 8192 columns: 33.4 against 36.4 us per iteration at 6144 rows, 42.2 / 45.9 at
-                                        // 8192, 55.1 / 56.3 at 10240, 62.5 / 61.7 at 11264, 70.3 / 67.7 at 12288; 4096
-                                        // columns: 44.2 / 47.7 at 16384 rows, 57.2 / 61.3 at 20480, 73.8 / 73.2 at
-                                        // 24576); at 2048 columns, where the 1024-lane kernel has idle lanes, as far
-                                        // as it goes (32768 rows: 51.8 against 96.1)
-constexpr int kResAutoPanelsWide = 18;  // the same between 6145 and 8191 columns (8000 x 8000: 44.8 against 46.3,
-                                        // 9000 x 8100: 50.9 / 52.9, 10000 x 8000: 57.5 / 57.2, 10000 x 7000: 55.2 / 52.5)
+constexpr int kResAutoPanels = kResMaxPanels;   // this kernel is the faster one as far as it goes (measured, 8192 columns:
+                                        // 31.7 against 36.3 us per iteration at 6144 rows, 40.5 / 46.0 at 8192, 53.0 / 57.6
+                                        // at 10240, 66.7 / 69.6 at 12288, 78.1 / 80.2 at 14336, 87.0 / 90.8 at 16384; 4096
+                                        // columns: 39.7 / 45.4 at 16384 rows, 51.9 / 56.7 at 20480, 66.3 / 68.6 at 24576,
+                                        // 79.1 / 80.6 at 28672; 2048 columns, where the 1024-lane kernel has idle lanes:
+                                        // 40.4 / 86.3 at 32768 rows) ...
+constexpr int kResAutoPanelsWide = 20;  // ... except between 6145 and 8191 columns (8000 x 8000: 42.8 against 46.2,
+                                        // 9000 x 8100: 49.6 / 52.9, 10000 x 7000: 50.0 / 51.9, 10000 x 8000: 55.4 / 57.4, but
+                                        // 12000 x 8000: 69.5 / 68.1, 14000 x 7000: 78.0 / 71.1)
 
 // All-reduce over aligned groups of LW lanes (16: a DPP row, rotated; 1: nothing to do; 2: lane ^ 1; 4: then lane ^ 2; 8: then the half row mirrored).
 template <int LW>
@@ -695,8 +696,7 @@ __global__ __launch_bounds__(64 * NW) void k_resident(DenseArgs A, PersistArgs X
 // of 2 beyond; 2048, 4096, 6144 or 8192 column slots), on a grid of one workgroup per compute unit, never more than there are panels and never so few
 // that a workgroup would merge a strip of more than 64 columns.  Up to kResPanels panels per workgroup the whole
 // share stays on the chip; beyond, the panels behind the register panels are streamed: up to kResAutoPanels as the
-// library's own choice (at exactly 2048 columns: up to kResMaxPanels; between 6145 and 8191 columns: kResAutoPanelsWide),
-// up to kResMaxPanels on request (`all`).  Up to 1024 columns: always up to kResMaxPanels (half of that up to 512
+// library's own choice (between 6145 and 8191 columns: kResAutoPanelsWide), up to kResMaxPanels on request (`all`).  Up to 1024 columns: always up to kResMaxPanels (half of that up to 512
 // columns, a quarter up to 256: the row scalars of a taller panel take more LDS), i.e. 512 rows per workgroup.
 // Returns the workgroups of the launch, 0 when the shape is not taken.
 int dense_resident_grid(int n, int m, int cus, bool all) {
@@ -709,7 +709,7 @@ int dense_resident_grid(int n, int m, int cus, bool all) {
     if (strip > 64) return 0;
     // (widths with idle lanes: 6000 x 6000 30.7 against 34.0 us per iteration, 8000 x 5000 38.0 / 40.6,
     // 16384 x 3000 43.1 / 53.2, 12000 x 1500 22.5 / 40.5)
-    const long long most = m <= 256 ? kResMaxPanels / 4 : m <= 512 ? kResMaxPanels / 2 : all || m <= 1024 || m == 2048 ? kResMaxPanels : (m > 6144 && m < 8192) ? kResAutoPanelsWide : kResAutoPanels;
+    const long long most = m <= 256 ? kResMaxPanels / 4 : m <= 512 ? kResMaxPanels / 2 : all ? kResMaxPanels : (m > 6144 && m < 8192) ? kResAutoPanelsWide : kResAutoPanels;
     return npanels <= most * g ? (int)g : 0;
 }
 

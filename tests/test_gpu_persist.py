@@ -55,7 +55,7 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
           (2048, 6144), (5000, 6144), (1000, 6000), (2301, 4097),   # ... and shares of which the 512-lane kernel streams a part
           (1000, 1000), (4096, 1024), (8191, 1024), (333, 700), (5000, 513), (9000, 1024),   # two row groups per workgroup
           (17000, 1024), (20000, 1000), (4700, 8100), (9300, 8192),    # ... streamed
-          (22000, 4096),                                           # ... 22 panels per workgroup: the 512-lane kernel on request only
+          (22000, 4096), (11500, 7000),                            # ... 22 / 23 panels per workgroup (masked: the 512-lane kernel on request only)
           (2100, 512), (8190, 512), (1000, 300), (4097, 257), (33000, 512), (40000, 400),   # four row groups; streamed
           (5000, 256), (4500, 129), (16383, 256), (70000, 256), (66000, 200)]                 # eight row groups; streamed
 
@@ -63,8 +63,8 @@ SHAPES = [(255, 8192), (300, 8190), (517, 4100), (2049, 4096), (300, 1100), (100
 def _resident(n, m, cus=256, most=4):
     """Whether the 512-lane kernel of the persistent pass takes the shape (128 < m <= 8192, 1 .. most panels of 64 KiB
     per workgroup of a grid of min(cus, panels) workgroups that merge at most 64 columns each): up to 4 panels the matrix stays on the chip for a whole launch; beyond
-    that the panels behind the two in registers are streamed: up to 20 panels (most = "auto"; 18 between 6145 and 8191
-    columns, 32 at 2048 columns) it is the library's own choice (fused_variant = 1 asks for the 1024-lane streaming kernel instead), up to 32 it can be
+    that the panels behind the two in registers are streamed: up to 32 panels (most = "auto"; 20 between 6145 and 8191
+    columns) it is the library's own choice (fused_variant = 1 asks for the 1024-lane streaming kernel instead), up to 32 it can be
     asked for (fused_variant = 2)."""
     if not 128 < m <= 8192:
         return False
@@ -76,7 +76,7 @@ def _resident(n, m, cus=256, most=4):
     if m == 2048 or m <= 1024:
         most = 32 if m > 512 else 16 if m > 256 else 8                         # (up to 1024 columns there is no 1024-lane form)
     if most == "auto":
-        most = 18 if 6144 < m < 8192 else 20
+        most = 20 if 6144 < m < 8192 else 32
     return panels <= most * grid
 
 
