@@ -22,7 +22,7 @@
 // Everything else is the persistent pass: the same optimistic row phase with its exact redo, the same fp32
 // column sums, the same exchange between two bounded grid-wide waits (publish, merge of the own strip with the
 // exact repair of columns below 2^-66, new G and V, read), the same stop rule (Alg. 1), the same trailing row
-// phase for the error of the last iterate (Sec. 4.5), the same fixed orders of every sum.  The old F of the
+// phase for the error of the last iterate (Sec. 4.5), a fixed order of every sum (results do not depend on timing).  The old F of the
 // workgroup's rows stays in LDS as well (two parities); F and U still go to memory every iteration, for the
 // repairs in other workgroups and for whatever runs after this launch.
 #include <type_traits>
